@@ -1,0 +1,147 @@
+"""Pins for oracle/scheduler.py and oracle/bubbles.py: hand-computed example, exhaustive invariants, closed
+forms, and a discrete-event simulation of the 1F1B pipeline written independently of the closed form."""
+import itertools
+import os
+
+import pytest
+
+import synth_inputs as S
+from oracle import bubbles as B
+from oracle import scheduler as K
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_zero_count_and_window():
+    assert K.zero_count([]) == 0
+    assert K.zero_count([3, 0, 0]) == 2 and K.zero_count([0, 0, 1]) == 0 and K.zero_count([0, 0, 0]) == 3
+    bm = K.BubbleMonitor(4)
+    assert [bm.push(c) for c in (5, 0, 0, 0, 0, 0, 2, 0)] == [0, 1, 2, 3, 4, 4, 0, 1]   # saturates at the window
+
+
+def test_alg1_hand_example():
+    rows = [tuple(map(int, l.split())) for l in open(os.path.join(GOLD, "alg1_worked_example.txt")) if l[0] != "#"]
+    pool = 0
+    for zc, want_pool, want_grant, want_status in rows:
+        pool, grant, status = K.alg1_step(zc, pool, 2, 5, 2, 1, 2, 8, 64, 1)
+        assert (pool, grant, status) == (want_pool, want_grant, want_status)
+
+
+def test_alg1_phase_invariants_exhaustive():
+    # every Z_c trace of length <= 6 over {0..5}, a small parameter grid
+    for alpha, beta, m, ll, ul, t0, gn, gd in ((0, 2, 1, 4, 16, 1, 2, 1), (1, 3, 2, 6, 40, 2, 3, 2), (2, 2, 3, 9, 9, 3, 2, 1)):
+        for n in range(1, 7):
+            for trace in itertools.product(range(6), repeat=n):
+                pool = 0
+                for zc in trace:
+                    prev = pool
+                    pool, grant, status = K.alg1_step(zc, pool, alpha, beta, gn, gd, m, ll, ul, t0)
+                    assert (grant == 0 and pool == 0) == (zc <= alpha) or (zc > alpha and pool // m == 0)
+                    assert (status == K.IDLE) == (zc > beta)
+                    if zc <= alpha:
+                        assert pool == 0 and grant == 0 and status == K.BUSY
+                    elif zc <= beta:
+                        assert pool == min(ll, max(prev, t0) * gn // gd) and grant == pool // m <= ll // m
+                    else:
+                        assert pool == min(ul, max(prev, t0) * gn // gd) and grant == pool // m <= ul // m
+
+
+def test_alg1_constant_phase_closed_form():
+    # k periods in the stable phase from an empty pool: pool = min(UL, T0 * gamma^k)
+    pool = 0
+    for k in range(1, 12):
+        pool, grant, _ = K.alg1_step(99, pool, 1, 4, 2, 1, 1, 50, 1000, 3)
+        assert pool == min(1000, 3 * 2 ** k) and grant == pool
+
+
+def test_kb_release_rules():
+    assert K.kb_release([3, 3, 3], 7) == (2, 1)
+    assert K.kb_release([5, 1, 1], 4) == (0, 4)          # head of line blocks
+    assert K.kb_release([], 10) == (0, 10)
+    assert K.kb_release([2, 2], 0) == (0, 0)
+    assert K.kb_release([0, 0], 0) == (2, 0)
+    # brute force: released prefix is the longest whose running sum fits
+    for costs in itertools.product(range(4), repeat=4):
+        for bal in range(8):
+            n, left = K.kb_release(list(costs), bal)
+            assert sum(costs[:n]) + left == bal and (n == 4 or costs[n] > left)
+
+
+def test_online_pull_and_principles():
+    assert K.online_pull_ok(K.IDLE, 1, 10, 10)
+    assert not K.online_pull_ok(K.BUSY, 1, 10, 1)
+    assert not K.online_pull_ok(K.IDLE, 0, 10, 1)
+    assert not K.online_pull_ok(K.IDLE, 1, 9, 10)
+    assert K.principle_1([30, 9], 40) and not K.principle_1([30, 10], 40)
+    assert K.principle_2(5, 6) and not K.principle_2(6, 6)
+
+
+def test_run_trace_releases_only_with_tokens():
+    counts = [4, 0, 0, 0, 0, 0, 0, 3, 0, 0, 0]
+    costs = [2] * 30
+    rows = K.run_trace(counts, costs, 8, 1, 3, 2, 1, 1, 4, 16, 1)
+    assert [r[0] for r in rows] == [0, 1, 2, 3, 4, 5, 6, 0, 1, 2, 3]
+    assert [r[1] for r in rows] == [0, 0, 2, 4, 8, 16, 16, 0, 0, 2, 4]
+    assert [r[4] for r in rows] == [0, 0, 1, 2, 4, 8, 8, 0, 0, 1, 2]
+    for zc, pool, grant, status, n in rows:
+        assert 2 * n <= grant
+
+
+# ---------------------------------------------------------------- bubble model
+def test_dp_and_tp_closed_values():
+    from oracle.decoder import n_params
+    n = n_params(S.DP_DECODER)
+    (site, ns), = B.dp_bubbles(n, 2, 50_000_000_000)
+    assert n * 2 == 248_879_616 and ns == 4_977_592          # 248.9 MB at 50 GB/s = 4.98 ms
+    (_, ns_ring), = B.dp_bubbles(n, 2, 50_000_000_000, ring_factor_num=6, ring_factor_den=4)   # 2(N-1)/N, N=4
+    assert ns_ring == 7_466_388
+    c = S.TP_DECODER
+    tp = B.tp_bubbles(c["n_layers"], c["batch"] * c["seq"], c["d_model"], 2, c["bw_bytes_per_s"])
+    assert len(tp) == 96 and all(ns == 1_342_177 for _, ns in tp)   # 67,108,864 B at 50 GB/s
+    assert tp[0][0] == "fwd0.attn_out" and tp[48][0] == "bwd23.mlp_up_dgrad" and tp[-1][0] == "bwd0.qkv_dgrad"
+
+
+def simulate_1f1b(p, m, tf, tb):
+    """Event simulation of all stages: F(s,k) needs F(s-1,k); B(s,k) needs B(s+1,k) (and F(s,k) on the last
+    stage); each stage runs its ops in 1F1B order.  Returns per stage the list of (op, start, end)."""
+    order = [B.pp_1f1b_ops(s, p, m) for s in range(p)]
+    done, pos, free, log = {}, [0] * p, [0] * p, [[] for _ in range(p)]
+    progressed = True
+    while progressed:
+        progressed = False
+        for s in range(p):
+            if pos[s] == len(order[s]):
+                continue
+            kind, k = order[s][pos[s]]
+            if kind == "F":
+                dep = done.get(("F", s - 1, k)) if s > 0 else 0
+            else:
+                dep = done.get(("B", s + 1, k)) if s < p - 1 else done.get(("F", s, k))
+            if dep is None:
+                continue
+            start = max(dep, free[s])
+            end = start + (tf if kind == "F" else tb)
+            done[(kind, s, k)] = end
+            free[s] = end
+            log[s].append(((kind, k), start, end))
+            pos[s] += 1
+            progressed = True
+    assert all(pos[s] == len(order[s]) for s in range(p))
+    return log
+
+
+@pytest.mark.parametrize("p,m,tf,tb", [(4, 8, 100, 200), (4, 8, 7, 19), (3, 3, 5, 5), (2, 6, 11, 30), (5, 9, 3, 8)])
+def test_pp_closed_form_against_event_simulation(p, m, tf, tb):
+    log = simulate_1f1b(p, m, tf, tb)
+    t_end = max(l[-1][2] for l in log)
+    assert t_end == (m + p - 1) * (tf + tb)
+    for s in range(p):
+        gaps, t = [], 0
+        for op, start, end in log[s]:
+            if start > t:
+                gaps.append((("before", op), start - t))
+            t = end
+        if t_end > t:
+            gaps.append((("end", None), t_end - t))
+        assert gaps == B.pp_1f1b_bubbles(s, p, m, tf, tb), s
+        assert sum(g for _, g in gaps) == (p - 1) * (tf + tb)
