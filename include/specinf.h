@@ -1,0 +1,375 @@
+/*
+ * specinf.h -- C ABI of libspecinf.so: the per-GPU hot path of SpecInF (speculative inference filling,
+ * arxiv 2503.02550) on one MI355X (gfx950).
+ *
+ * One training instance runs its compute on a caller-supplied HIP stream; a Bubble Monitor counts its kernels
+ * per period and reports the zero-count Z_c (Sec. 3.3 "Bubble Monitor"); Algorithm 1 turns Z_c into tokens
+ * and a busy/idle status (Sec. 3.3 "CUDA Kernel Scheduler"); a Kernel Barrier forwards queued inference
+ * kernels to a second stream while tokens last, or pulls online requests one by one while idle (Sec. 3.3
+ * "Kernel Barrier").  Every kernel carries a prologue/epilogue that keeps a per-stream activity record in
+ * HBM; inference kernels are launched speculatively and re-check that record on the device before they run.
+ * Collective waits of the distributed training job are modelled as timed waits of the training stream.
+ *
+ * Conventions
+ *   - All pointers named *_dev are device (HBM) addresses, all others are host addresses.
+ *   - The caller owns every device buffer and both streams; the library borrows them from register/submit
+ *     until the ticket completes or sif_destroy returns.  The library allocates only host control state and
+ *     one small pinned host mailbox per context; nothing is allocated on the hot path.
+ *   - Matrices are row-major.  Weights are stored [out_features, in_features].  bf16 = upper 16 bits of an
+ *     IEEE binary32, rounded to nearest even; accumulation is fp32.
+ *   - Every function returns a sif_status: 0 = SIF_OK, > 0 = warning (work was done), < 0 = error (nothing
+ *     was done).  No function throws or aborts.  sif_last_error() gives the text of the last error of the
+ *     calling thread.
+ *   - Structs start with `struct_size` = sizeof(the struct) as the caller compiled it.
+ */
+#ifndef SPECINF_H
+#define SPECINF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sif_ctx sif_ctx;
+typedef int32_t sif_status;
+typedef uint64_t sif_ticket;
+typedef int32_t sif_handle;
+
+enum {
+  SIF_OK = 0,
+  SIF_W_SLO_RISK = 1,   /* Principle-II violated: batch-1 request longer than the longest bubble */
+  SIF_E_INVAL = -1,
+  SIF_E_NOMEM = -2,     /* workspace too small, or Principle-I violated */
+  SIF_E_AGAIN = -3,     /* queue full */
+  SIF_E_CANCELLED = -4,
+  SIF_E_TIMEOUT = -5,
+  SIF_E_DEVICE = -6     /* a HIP call failed; text in sif_last_error() */
+};
+
+enum { SIF_F32 = 0, SIF_BF16 = 1 };
+enum { SIF_STATUS_BUSY = 0, SIF_STATUS_IDLE = 1 };
+
+const char* sif_last_error(void);
+int32_t sif_abi_version(void);
+
+/* ====================================================================================================
+ * 1. Scheduler rules as pure host functions (no GPU needed).  The runtime threads call exactly these.
+ * ==================================================================================================== */
+
+/* Constants of Algorithm 1 (inputs alpha, beta, gamma, m, UL, LL of the listing) plus the seed t0 that the
+ * multiplicative update restarts from after the conservative phase.  Tokens are integers; one token is one
+ * microsecond of predicted inference-kernel time.  gamma = gamma_num / gamma_den. */
+typedef struct sif_alg1_params {
+  uint32_t alpha, beta;
+  uint32_t gamma_num, gamma_den;
+  uint32_t m;
+  uint32_t reserved;
+  uint64_t ll, ul, t0;
+} sif_alg1_params;
+
+/* Bubble Monitor: number of consecutive zero counts ending at counts[n-1] (the newest sample). */
+uint32_t sif_zero_count(const uint32_t* counts, uint32_t n);
+
+/* Algorithm 1, one evaluation.  *pool is the per-GPU token state carried between periods (starts at 0);
+ * *grant receives the tokens handed to each of the m instances, *status SIF_STATUS_BUSY / _IDLE.
+ *   Z_c <= alpha         : pool = 0,                                       busy   (conservative)
+ *   alpha < Z_c <= beta  : pool = min(LL, floor(max(pool,t0)*gamma)),      busy   (incremental)
+ *   Z_c > beta           : pool = min(UL, floor(max(pool,t0)*gamma)),      idle   (stable)
+ *   grant = floor(pool / m)
+ * Returns SIF_E_INVAL for null pointers, m = 0 or gamma_den = 0. */
+sif_status sif_alg1_step(const sif_alg1_params* p, uint32_t zc, uint64_t* pool, uint64_t* grant, int32_t* status);
+
+/* Kernel Barrier, offline rule: with `balance` tokens, how many kernels from the head of the FIFO of costs
+ * are forwarded (a kernel is forwarded iff balance >= cost, then balance -= cost; the head blocks the rest).
+ * *balance_left may be null. */
+uint32_t sif_kb_release(const uint32_t* costs, uint32_t n, uint64_t balance, uint64_t* balance_left);
+
+/* Kernel Barrier, online rule: 1 iff status is idle, a request waits and the predicted rest of the bubble
+ * holds the predicted request time. */
+int32_t sif_online_pull_ok(int32_t status, uint32_t queue_len, uint64_t predicted_remaining_ns,
+                           uint64_t predicted_request_ns);
+
+/* Collocation principles (Sec. 3.2).  1 = satisfied. */
+int32_t sif_principle_1(const uint64_t* peak_bytes, uint32_t n, uint64_t capacity_bytes);
+int32_t sif_principle_2(uint64_t min_exec_ns, uint64_t max_bubble_ns);
+
+/* Bubble model: duration of a modelled collective, floor(bytes * 1e9 / bw). */
+uint64_t sif_collective_ns(uint64_t n_bytes, uint64_t bw_bytes_per_s);
+
+/* Idle intervals of one 1F1B pipeline stage (uniform per-micro-batch forward time tf and backward time tb,
+ * n_micro >= n_stages).  Writes up to `max` entries: kind[i] 0 = gap before forward pass index[i],
+ * 1 = gap before backward pass index[i], 2 = wait at the end of the step; ns[i] its length.
+ * Returns the number of gaps (may exceed max; then only max were written), or a negative sif_status. */
+int32_t sif_pp_1f1b_bubbles(uint32_t stage, uint32_t n_stages, uint32_t n_micro, uint64_t tf_ns, uint64_t tb_ns,
+                            int32_t* kind, int32_t* index, uint64_t* ns, uint32_t max);
+
+/* ====================================================================================================
+ * 2. Single kernels (raw launchers).  Each enqueues one kernel on `stream` (a hipStream_t, may be null =
+ *    default stream) and returns without synchronising.  Used by the model code below and by the parity
+ *    tests.  All operand pointers are device addresses, 16-byte aligned; see each function for shapes.
+ * ==================================================================================================== */
+
+/* Operand layouts of the general matrix product  C[M,N] = alpha * sum_k A(m,k) B(k,n)  (+ epilogue). */
+enum {
+  SIF_A_ROW_K = 0,  /* A stored [M][K], lda = row stride      (activations in a forward product)        */
+  SIF_A_ROW_M = 1   /* A stored [K][M], lda = row stride      (left operand of a weight gradient)       */
+};
+enum {
+  SIF_B_ROW_K = 0,  /* B stored [N][K], ldb = row stride      (weights [out,in] in a forward product)   */
+  SIF_B_ROW_N = 1   /* B stored [K][N], ldb = row stride      (weights in a data gradient, V in P*V)    */
+};
+enum {
+  SIF_EPI_NONE = 0,
+  SIF_EPI_BIAS = 1,        /* + bias[n]                                                        */
+  SIF_EPI_GELU = 2,        /* C = GELU(acc + bias); if aux_dev != null also aux[m,n] = acc + bias (pre-activation) */
+  SIF_EPI_RESIDUAL = 4,    /* + res[m,n] (same layout and dtype as C, ld = ldc)                        */
+  SIF_EPI_GELU_GRAD = 8,   /* C = acc * GELU'(aux[m,n])  (aux bf16, ld = ldc)                          */
+  SIF_EPI_OUT_F32 = 16,    /* C is fp32 instead of bf16                                                */
+  SIF_EPI_CAUSAL_SKIP = 32 /* square per-batch problem: tiles strictly above the diagonal are not computed
+                              nor written                                                             */
+};
+
+typedef struct sif_gemm_args {
+  uint32_t struct_size;
+  uint32_t a_layout, b_layout, epilogue;
+  uint32_t m, n, k;            /* logical extents.  The extent along an operand's contiguous dimension may
+                                  be ragged only if the row is padded (ld >= extent rounded up to 8) with
+                                  zeros; ld must be a multiple of 8 elements.                          */
+  uint32_t lda, ldb, ldc;
+  uint32_t batch_outer, batch_inner;             /* grid z = batch_outer * batch_inner (>= 1 each)     */
+  int64_t a_stride_outer, a_stride_inner;        /* element offsets per batch index                    */
+  int64_t b_stride_outer, b_stride_inner;
+  int64_t c_stride_outer, c_stride_inner;
+  float alpha;
+  uint32_t k_causal;           /* 0 = full K.  1: contract only k <  row-tile end (lower-triangular A)
+                                  2: contract only k >= column-tile start (A stored [K][M], upper part zero) */
+  const void* a_dev;           /* bf16 */
+  const void* b_dev;           /* bf16 */
+  void* c_dev;                 /* bf16 or fp32 (SIF_EPI_OUT_F32)                                        */
+  const void* bias_dev;        /* bf16 [N] or null                                                      */
+  const void* res_dev;         /* residual, or null                                                     */
+  void* aux_dev;               /* see SIF_EPI_GELU / SIF_EPI_GELU_GRAD                                  */
+} sif_gemm_args;
+
+/* bf16 matrix product on the MFMA units, fp32 accumulation. */
+sif_status sif_k_gemm_bf16(const sif_gemm_args* a, void* stream);
+
+/* fp32 matrix product C[M,N] = sum_k A(m,k) B(k,n) with arbitrary element strides (Tiny configuration):
+ * A(m,k) = a[m*a_sm + k*a_sk], B(k,n) = b[k*b_sk + n*b_sn], C row-major ldc.  epilogue: SIF_EPI_BIAS,
+ * SIF_EPI_GELU (aux = pre-activation, fp32), SIF_EPI_GELU_GRAD (aux fp32) as above, all fp32. */
+sif_status sif_k_gemm_f32(const float* a_dev, int64_t a_sm, int64_t a_sk, const float* b_dev, int64_t b_sk,
+                          int64_t b_sn, float* c_dev, int64_t ldc, uint32_t m, uint32_t n, uint32_t k,
+                          uint32_t epilogue, const float* bias_dev, float* aux_dev, void* stream);
+
+/* LayerNorm over the last dimension (biased variance, eps 1e-5), bf16 in/out, fp32 statistics.
+ * mean_dev / rstd_dev: fp32 [rows] or null (not saved). */
+sif_status sif_k_layernorm_fwd(const void* x_dev, const void* g_dev, const void* b_dev, void* y_dev,
+                               float* mean_dev, float* rstd_dev, uint32_t rows, uint32_t d, void* stream);
+/* dx = res + LNbwd(dy) (res_dev may be null), dg/db = column sums; part_dev is fp32 scratch of
+ * 2 * sif_colsum_parts(rows) * d floats.  Fixed summation order (no atomics). */
+sif_status sif_k_layernorm_bwd(const void* dy_dev, const void* x_dev, const void* g_dev, const float* mean_dev,
+                               const float* rstd_dev, const void* res_dev, void* dx_dev, void* dg_dev,
+                               void* db_dev, float* part_dev, uint32_t rows, uint32_t d, void* stream);
+uint32_t sif_colsum_parts(uint32_t rows);
+/* out[n] = sum_m x[m,n]  (bf16 in/out, fp32 fixed-order accumulation); part_dev: sif_colsum_parts(rows)*n floats */
+sif_status sif_k_colsum(const void* x_dev, uint32_t ld, void* out_dev, float* part_dev, uint32_t rows, uint32_t n,
+                        void* stream);
+
+/* Row softmax of fp32 scores [batch][rows][ld_s] into bf16 probabilities [batch][rows][ld_p]; causal != 0
+ * keeps columns j <= i only; columns >= cols (up to ld_p) are written as zeros. */
+sif_status sif_k_softmax_fwd(const float* s_dev, void* p_dev, uint32_t batch, uint32_t rows, uint32_t cols,
+                             uint32_t ld_s, uint32_t ld_p, uint32_t causal, void* stream);
+/* dS = scale * P .* (dP - rowsum(dP .* P)), dP fp32, P and dS bf16 (causal: columns j > i written as 0) */
+sif_status sif_k_softmax_bwd(const float* dp_dev, const void* p_dev, void* ds_dev, uint32_t batch, uint32_t rows,
+                             uint32_t cols, uint32_t ld, float scale, uint32_t causal, void* stream);
+
+/* x[t,:] = wte[ids[t],:] + wpe[t % seq,:]   (bf16) */
+sif_status sif_k_embed_fwd(const int32_t* ids_dev, const void* wte_dev, const void* wpe_dev, void* x_dev,
+                           uint32_t tokens, uint32_t seq, uint32_t d, void* stream);
+/* dwte[v,:] += sum over tokens t with ids[t] = v of dx[t,:] in ascending t (bf16, fp32 sum, no atomics);
+ * dwpe[s,:] = sum over the batch of dx[b*seq+s,:]. */
+sif_status sif_k_embed_bwd(const int32_t* ids_dev, const void* dx_dev, void* dwte_dev, void* dwpe_dev,
+                           uint32_t tokens, uint32_t seq, uint32_t d, void* stream);
+
+/* Mean token cross entropy over bf16 logits [tokens][ld] (first `vocab` columns valid): per-token loss into
+ * loss_dev[t] (fp32) and, in place, logits <- (softmax - onehot(target)) / tokens with the padding columns
+ * vocab..ld-1 set to zero. */
+sif_status sif_k_xent_fwd_bwd(void* logits_dev, const int32_t* targets_dev, float* loss_dev, uint32_t tokens,
+                              uint32_t vocab, uint32_t ld, void* stream);
+/* out[0] = scale * sum x[0..n)  fixed order, one block (fp32) */
+sif_status sif_k_reduce_sum(const float* x_dev, float* out_dev, uint32_t n, float scale, void* stream);
+
+/* master <- master - lr * grad (fp32 master, bf16 grad), work <- bf16(master).  lr = 0 makes the working copy. */
+sif_status sif_k_sgd_bf16(float* master_dev, const void* grad_dev, void* work_dev, uint64_t n, float lr, void* stream);
+/* fp32 everything: p <- p - lr * g */
+sif_status sif_k_sgd_f32(float* p_dev, const float* g_dev, uint64_t n, float lr, void* stream);
+/* MLP loss: d[i] = (y[i]-t[i])/n, loss_dev[0] = sum (y-t)^2 / (2n)   (fp32, one pass, fixed order) */
+sif_status sif_k_mse_fwd_bwd(const float* y_dev, const float* t_dev, float* d_dev, float* loss_dev, uint32_t n,
+                             void* stream);
+/* fp32 column sum: out[n] = sum_m x[m*ld + n] */
+sif_status sif_k_colsum_f32(const float* x_dev, uint32_t ld, float* out_dev, uint32_t rows, uint32_t n, void* stream);
+
+/* ====================================================================================================
+ * 3. The collocation runtime.
+ * ==================================================================================================== */
+
+typedef struct sif_config {
+  uint32_t struct_size;
+  uint32_t period_us;        /* Bubble Monitor sampling period P                                       */
+  uint32_t window;           /* sliding-window length W (<= 1024)                                      */
+  uint32_t count_running;    /* 1: a period in which a training kernel is still running counts >= 1
+                                (a launch counter alone reads 0 under one long kernel)                 */
+  sif_alg1_params alg1;
+  uint32_t kernel_us_max;    /* inference kernels predicted longer than this are split along rows      */
+  uint32_t collocate;        /* 0: the barrier never releases anything (solo training / overhead run)  */
+  uint32_t device_timed_bubbles; /* 0: bubbles are released by the host clock; 1: timed on the device  */
+  uint32_t reserved;
+  uint64_t device_capacity_bytes; /* Principle-I capacity; 0 = total memory of the current device      */
+} sif_config;
+
+/* Fills *cfg with the defaults (P = 100 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = P/4, LL = P,
+ * UL = 4P tokens, kernel_us_max 200, collocate 1). */
+sif_status sif_default_config(sif_config* cfg);
+
+/* Bytes of device workspace sif_create needs (activity records, trace rings). */
+uint64_t sif_ctx_workspace_bytes(void);
+
+/* Creates a context on the current device.  train_stream / infer_stream: two distinct hipStream_t of default
+ * priority.  workspace_dev: caller-owned HBM, >= sif_ctx_workspace_bytes(), 256-byte aligned, zero-filled
+ * by this call.  Starts the monitor and barrier threads. */
+sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_stream, void* workspace_dev,
+                      uint64_t workspace_bytes, sif_ctx** out);
+/* Stops the threads, cancels pending tickets (SIF_E_CANCELLED), synchronises both streams. */
+sif_status sif_destroy(sif_ctx* ctx);
+
+enum { SIF_MODEL_MLP = 0, SIF_MODEL_DECODER = 1, SIF_MODEL_ENCODER = 2 };
+enum { SIF_PAR_NONE = 0, SIF_PAR_FIXED = 1, SIF_PAR_DP = 2, SIF_PAR_PP = 3, SIF_PAR_TP = 4 };
+
+/* Shape of a model.  MLP: d_in, d_hidden, d_out, batch.  DECODER / ENCODER: n_layers, d_model, n_heads,
+ * d_head, d_ffn, vocab, max_pos, batch, seq (vocab = 0: layer stack only, activations in / gradient in).
+ * d_model, d_head, d_ffn multiples of 8; batch*seq a multiple of 8 for training. */
+typedef struct sif_model_shape {
+  uint32_t kind, dtype;
+  uint32_t n_layers, d_model, n_heads, d_head, d_ffn, vocab, max_pos;
+  uint32_t d_in, d_hidden, d_out;
+  uint32_t batch, seq;
+} sif_model_shape;
+
+/* Flat parameter layout (element offsets into one array of sif_model_n_params elements), in this order:
+ *   MLP     : w1[d_hidden,d_in] b1 w2[d_out,d_hidden] b2
+ *   DECODER : (vocab > 0: wte[vocab,d] wpe[max_pos,d]) then per layer ln1_g ln1_b w_qkv[3da,d] b_qkv w_o[d,da]
+ *             b_o ln2_g ln2_b w_fc[f,d] b_fc w_proj[d,f] b_proj, then (vocab > 0: lnf_g lnf_b); da = n_heads*d_head
+ *   ENCODER : wte wpe emb_ln_g emb_ln_b then per layer w_qkv b_qkv w_o b_o ln1_g ln1_b w_fc b_fc w_proj b_proj
+ *             ln2_g ln2_b */
+uint64_t sif_model_n_params(const sif_model_shape* s);
+
+typedef struct sif_train_desc {
+  uint32_t struct_size;
+  uint32_t par_mode;             /* SIF_PAR_*: which bubbles the step contains                          */
+  sif_model_shape shape;
+  float lr;
+  uint32_t pp_stages, pp_micro, pp_stage;
+  uint64_t bw_bytes_per_s;       /* DP, TP: modelled collective bandwidth                               */
+  uint64_t fixed_bubble_ns;      /* FIXED: one bubble of this length after backward                     */
+  uint64_t pp_tf_ns, pp_tb_ns;   /* PP: per-micro-batch forward/backward time (0 = measured by calibration) */
+  float* master_dev;             /* fp32 [n_params], caller-initialised, updated in place by each step  */
+  void* workspace_dev;           /* >= sif_train_workspace_bytes(), 256-byte aligned                    */
+  uint64_t workspace_bytes;
+} sif_train_desc;
+
+uint64_t sif_train_workspace_bytes(const sif_train_desc* d);
+
+/* Registers the training instance (one per context).  Builds the kernel sequence and the bubble sites, makes
+ * the working copy of the parameters (one cast kernel per tensor group on the training stream) and returns. */
+sif_status sif_register_training_step(sif_ctx* ctx, const sif_train_desc* d, sif_handle* out);
+
+/* Enqueues one training step on the training stream and returns without waiting.
+ *   MLP: inputs_dev fp32 [batch,d_in], targets_dev fp32 [batch,d_out].
+ *   DECODER with vocab: inputs_dev / targets_dev int32 token ids [batch,seq].
+ *   DECODER stack: inputs_dev fp32->(stored bf16) activations are taken as bf16 [batch,seq,d]; targets_dev is
+ *   the upstream gradient, bf16 [batch,seq,d].
+ * loss_dev: fp32 device scalar written by the step (may be null).  Buffers must stay valid until the step
+ * has run (sif_sync_training). */
+sif_status sif_run_training_step(sif_ctx* ctx, sif_handle h, const void* inputs_dev, const void* targets_dev,
+                                 float* loss_dev);
+sif_status sif_sync_training(sif_ctx* ctx);
+
+/* Device address of a named tensor inside the training workspace, for inspection after sif_sync_training:
+ * "work" (working copy of all parameters), "grads" (all gradients, parameter layout; bf16 or fp32 as the
+ * model), per layer: "ln1" "qkv" "prob" "o" "x_mid" "ln2" "z" "a" "x_out", and "logits", "x0".
+ * *elems = number of elements. */
+sif_status sif_train_tensor(sif_ctx* ctx, sif_handle h, const char* name, int32_t layer, void** ptr_dev,
+                            uint64_t* elems);
+
+typedef struct sif_infer_desc {
+  uint32_t struct_size;
+  uint32_t online;               /* 0 = offline (token mechanism), 1 = online (pull-and-execute)        */
+  sif_model_shape shape;         /* batch, seq = the largest batch / sequence a submit may carry        */
+  const float* master_dev;       /* fp32 [n_params] weights, caller-owned                               */
+  void* workspace_dev;           /* >= sif_infer_workspace_bytes(): working copy + activations          */
+  uint64_t workspace_bytes;
+  uint64_t peak_bytes;           /* declared peak memory of this instance (Principle-I)                 */
+} sif_infer_desc;
+
+uint64_t sif_infer_workspace_bytes(const sif_infer_desc* d);
+
+/* Registers an inference instance.  SIF_E_NOMEM if the declared peaks of all instances plus the training
+ * workspace exceed the device capacity (Principle-I). */
+sif_status sif_register_inference_model(sif_ctx* ctx, const sif_infer_desc* d, sif_handle* out);
+
+/* Runs the registered models alone (no collocation, gates open) `iters` times to measure per-kernel costs,
+ * the solo step time and the bubble lengths; blocks until done.  Returns SIF_W_SLO_RISK if an online model's
+ * batch-1 time exceeds the longest bubble (Principle-II). */
+sif_status sif_calibrate(sif_ctx* ctx, uint32_t iters, const void* train_inputs_dev, const void* train_targets_dev);
+
+/* Queues one offline batch / one online request (non-blocking, any thread).  in_dev: int32 ids [batch,seq]
+ * (ENCODER) or fp32 [batch,d_in] (MLP); out_dev: bf16 [batch,seq,d] or fp32 [batch,d_out]. */
+sif_status sif_submit_offline_batch(sif_ctx* ctx, sif_handle model, const void* in_dev, void* out_dev,
+                                    uint32_t batch, uint32_t seq, sif_ticket* out);
+sif_status sif_submit_online_request(sif_ctx* ctx, sif_handle model, const void* in_dev, void* out_dev,
+                                     uint32_t seq, uint64_t t_arrival_ns, sif_ticket* out);
+/* Blocks until the ticket completes or timeout_ns passes (SIF_E_TIMEOUT). */
+sif_status sif_wait(sif_ctx* ctx, sif_ticket t, uint64_t timeout_ns);
+/* Host monotonic clock used for t_arrival_ns and the latency statistics. */
+uint64_t sif_now_ns(void);
+
+typedef struct sif_stats {
+  uint32_t struct_size;
+  uint32_t status_now, zc_now, reserved;
+  uint64_t tokens_now;
+  uint64_t steps;                 /* training steps completed                                           */
+  uint64_t step_ns_sum, step_ns_last, step_solo_ns;
+  uint64_t bubble_ns;             /* total modelled idle time of completed bubbles                      */
+  uint64_t filled_ns;             /* inference kernel time that fell inside bubbles                     */
+  uint64_t infer_busy_ns;         /* all inference kernel time                                          */
+  uint64_t offline_samples, offline_batches;
+  uint64_t online_done, online_p50_ns, online_p95_ns;
+  uint64_t kernels_launched, kernels_skipped, kernels_run;
+  uint64_t gate_violations;       /* inference kernels that ran although the gate was closed (must be 0) */
+  uint64_t train_kernels;
+  uint64_t periods;               /* monitor periods evaluated                                           */
+} sif_stats;
+
+/* Snapshot of the counters; never blocks, never touches a stream. */
+sif_status sif_poll_stats(sif_ctx* ctx, sif_stats* out);
+/* Zeroes the accumulating counters (between measurement phases); requires both streams idle. */
+sif_status sif_reset_stats(sif_ctx* ctx);
+
+/* One record of the device trace ring. */
+typedef struct sif_trace_rec {
+  uint32_t kind;        /* 1 training kernel, 2 inference kernel, 3 bubble, 4 step                      */
+  uint32_t id;          /* kernel sequence number / bubble site / step index                            */
+  uint32_t decision;    /* inference kernels: 1 ran, 2 skipped                                          */
+  uint32_t reserved;
+  uint64_t t0_ns, t1_ns;/* device wall clock                                                            */
+} sif_trace_rec;
+/* Copies the newest records of a stream's ring (0 = training, 1 = inference) to out[0..max), oldest first;
+ * synchronises both streams first.  Returns the count in *n. */
+sif_status sif_read_trace(sif_ctx* ctx, uint32_t which, sif_trace_rec* out, uint32_t max, uint32_t* n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,267 @@
+"""ctypes binding of libspecinf.so.  Argument marshalling only: every function forwards to the C entry point of
+the same name (include/specinf.h); torch tensors are passed as their device addresses.  There is no fallback:
+if the library is missing, importing this module raises."""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspecinf.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} not built; run `python -m paper_2503_02550_amd.build`")
+lib = C.CDLL(LIB_PATH)
+
+u32, u64, i32, i64, f32, vp = C.c_uint32, C.c_uint64, C.c_int32, C.c_int64, C.c_float, C.c_void_p
+
+# status codes / enums (mirrors of the header)
+SIF_OK, SIF_W_SLO_RISK = 0, 1
+SIF_E_INVAL, SIF_E_NOMEM, SIF_E_AGAIN, SIF_E_CANCELLED, SIF_E_TIMEOUT, SIF_E_DEVICE = -1, -2, -3, -4, -5, -6
+SIF_F32, SIF_BF16 = 0, 1
+SIF_STATUS_BUSY, SIF_STATUS_IDLE = 0, 1
+SIF_A_ROW_K, SIF_A_ROW_M = 0, 1
+SIF_B_ROW_K, SIF_B_ROW_N = 0, 1
+SIF_EPI_NONE, SIF_EPI_BIAS, SIF_EPI_GELU, SIF_EPI_RESIDUAL, SIF_EPI_GELU_GRAD, SIF_EPI_OUT_F32, SIF_EPI_CAUSAL_SKIP = 0, 1, 2, 4, 8, 16, 32
+SIF_MODEL_MLP, SIF_MODEL_DECODER, SIF_MODEL_ENCODER = 0, 1, 2
+SIF_PAR_NONE, SIF_PAR_FIXED, SIF_PAR_DP, SIF_PAR_PP, SIF_PAR_TP = 0, 1, 2, 3, 4
+
+
+class SifError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"sif status {status}: {text}")
+        self.status = status
+
+
+def last_error():
+    return lib.sif_last_error().decode()
+
+
+def check(status):
+    if status < 0:
+        raise SifError(status, last_error())
+    return status
+
+
+def ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def stream_ptr(s):
+    if s is None:
+        return None
+    return s.cuda_stream if hasattr(s, "cuda_stream") else int(s)
+
+
+class sif_alg1_params(C.Structure):
+    _fields_ = [("alpha", u32), ("beta", u32), ("gamma_num", u32), ("gamma_den", u32), ("m", u32), ("reserved", u32),
+                ("ll", u64), ("ul", u64), ("t0", u64)]
+
+
+class sif_gemm_args(C.Structure):
+    _fields_ = [("struct_size", u32), ("a_layout", u32), ("b_layout", u32), ("epilogue", u32),
+                ("m", u32), ("n", u32), ("k", u32), ("lda", u32), ("ldb", u32), ("ldc", u32),
+                ("batch_outer", u32), ("batch_inner", u32),
+                ("a_stride_outer", i64), ("a_stride_inner", i64), ("b_stride_outer", i64), ("b_stride_inner", i64),
+                ("c_stride_outer", i64), ("c_stride_inner", i64),
+                ("alpha", f32), ("k_causal", u32),
+                ("a_dev", vp), ("b_dev", vp), ("c_dev", vp), ("bias_dev", vp), ("res_dev", vp), ("aux_dev", vp)]
+
+
+class sif_config(C.Structure):
+    _fields_ = [("struct_size", u32), ("period_us", u32), ("window", u32), ("count_running", u32),
+                ("alg1", sif_alg1_params), ("kernel_us_max", u32), ("collocate", u32), ("device_timed_bubbles", u32),
+                ("reserved", u32), ("device_capacity_bytes", u64)]
+
+
+class sif_model_shape(C.Structure):
+    _fields_ = [("kind", u32), ("dtype", u32), ("n_layers", u32), ("d_model", u32), ("n_heads", u32), ("d_head", u32),
+                ("d_ffn", u32), ("vocab", u32), ("max_pos", u32), ("d_in", u32), ("d_hidden", u32), ("d_out", u32),
+                ("batch", u32), ("seq", u32)]
+
+
+class sif_train_desc(C.Structure):
+    _fields_ = [("struct_size", u32), ("par_mode", u32), ("shape", sif_model_shape), ("lr", f32),
+                ("pp_stages", u32), ("pp_micro", u32), ("pp_stage", u32),
+                ("bw_bytes_per_s", u64), ("fixed_bubble_ns", u64), ("pp_tf_ns", u64), ("pp_tb_ns", u64),
+                ("master_dev", vp), ("workspace_dev", vp), ("workspace_bytes", u64)]
+
+
+class sif_infer_desc(C.Structure):
+    _fields_ = [("struct_size", u32), ("online", u32), ("shape", sif_model_shape), ("master_dev", vp),
+                ("workspace_dev", vp), ("workspace_bytes", u64), ("peak_bytes", u64)]
+
+
+class sif_stats(C.Structure):
+    _fields_ = [("struct_size", u32), ("status_now", u32), ("zc_now", u32), ("reserved", u32), ("tokens_now", u64),
+                ("steps", u64), ("step_ns_sum", u64), ("step_ns_last", u64), ("step_solo_ns", u64),
+                ("bubble_ns", u64), ("filled_ns", u64), ("infer_busy_ns", u64),
+                ("offline_samples", u64), ("offline_batches", u64),
+                ("online_done", u64), ("online_p50_ns", u64), ("online_p95_ns", u64),
+                ("kernels_launched", u64), ("kernels_skipped", u64), ("kernels_run", u64),
+                ("gate_violations", u64), ("train_kernels", u64), ("periods", u64)]
+
+
+class sif_trace_rec(C.Structure):
+    _fields_ = [("kind", u32), ("id", u32), ("decision", u32), ("reserved", u32), ("t0_ns", u64), ("t1_ns", u64)]
+
+
+def _sig(name, restype, *argtypes):
+    f = getattr(lib, name)
+    f.restype, f.argtypes = restype, list(argtypes)
+    return f
+
+
+P = C.POINTER
+_sig("sif_last_error", C.c_char_p)
+_sig("sif_abi_version", i32)
+_sig("sif_zero_count", u32, P(u32), u32)
+_sig("sif_alg1_step", i32, P(sif_alg1_params), u32, P(u64), P(u64), P(i32))
+_sig("sif_kb_release", u32, P(u32), u32, u64, P(u64))
+_sig("sif_online_pull_ok", i32, i32, u32, u64, u64)
+_sig("sif_principle_1", i32, P(u64), u32, u64)
+_sig("sif_principle_2", i32, u64, u64)
+_sig("sif_collective_ns", u64, u64, u64)
+_sig("sif_pp_1f1b_bubbles", i32, u32, u32, u32, u64, u64, P(i32), P(i32), P(u64), u32)
+_sig("sif_k_gemm_bf16", i32, P(sif_gemm_args), vp)
+_sig("sif_k_gemm_f32", i32, vp, i64, i64, vp, i64, i64, vp, i64, u32, u32, u32, u32, vp, vp, vp)
+_sig("sif_k_layernorm_fwd", i32, vp, vp, vp, vp, vp, vp, u32, u32, vp)
+_sig("sif_k_layernorm_bwd", i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, vp)
+_sig("sif_colsum_parts", u32, u32)
+_sig("sif_k_colsum", i32, vp, u32, vp, vp, u32, u32, vp)
+_sig("sif_k_softmax_fwd", i32, vp, vp, u32, u32, u32, u32, u32, u32, vp)
+_sig("sif_k_softmax_bwd", i32, vp, vp, vp, u32, u32, u32, u32, f32, u32, vp)
+_sig("sif_k_embed_fwd", i32, vp, vp, vp, vp, u32, u32, u32, vp)
+_sig("sif_k_embed_bwd", i32, vp, vp, vp, vp, u32, u32, u32, vp)
+_sig("sif_k_xent_fwd_bwd", i32, vp, vp, vp, u32, u32, u32, vp)
+_sig("sif_k_reduce_sum", i32, vp, vp, u32, f32, vp)
+_sig("sif_k_sgd_bf16", i32, vp, vp, vp, u64, f32, vp)
+_sig("sif_k_sgd_f32", i32, vp, vp, u64, f32, vp)
+_sig("sif_k_mse_fwd_bwd", i32, vp, vp, vp, vp, u32, vp)
+_sig("sif_k_colsum_f32", i32, vp, u32, vp, u32, u32, vp)
+
+
+# ---- pure host rules ------------------------------------------------------------------------------------
+def sif_zero_count(counts):
+    arr = (u32 * len(counts))(*counts)
+    return lib.sif_zero_count(arr, len(counts))
+
+
+def sif_alg1_step(params, zc, pool):
+    """Returns (pool', grant, status)."""
+    p, g, s = u64(pool), u64(0), i32(0)
+    check(lib.sif_alg1_step(C.byref(params), zc, C.byref(p), C.byref(g), C.byref(s)))
+    return p.value, g.value, s.value
+
+
+def sif_kb_release(costs, balance):
+    arr = (u32 * max(1, len(costs)))(*costs)
+    left = u64(0)
+    n = lib.sif_kb_release(arr, len(costs), balance, C.byref(left))
+    return n, left.value
+
+
+def sif_online_pull_ok(status, queue_len, remaining_ns, request_ns):
+    return bool(lib.sif_online_pull_ok(status, queue_len, remaining_ns, request_ns))
+
+
+def sif_principle_1(peaks, capacity):
+    arr = (u64 * max(1, len(peaks)))(*peaks)
+    return bool(lib.sif_principle_1(arr, len(peaks), capacity))
+
+
+def sif_principle_2(min_exec_ns, max_bubble_ns):
+    return bool(lib.sif_principle_2(min_exec_ns, max_bubble_ns))
+
+
+def sif_collective_ns(n_bytes, bw):
+    return lib.sif_collective_ns(n_bytes, bw)
+
+
+def sif_pp_1f1b_bubbles(stage, n_stages, n_micro, tf_ns, tb_ns, cap=64):
+    kind, idx, ns = (i32 * cap)(), (i32 * cap)(), (u64 * cap)()
+    n = check(lib.sif_pp_1f1b_bubbles(stage, n_stages, n_micro, tf_ns, tb_ns, kind, idx, ns, cap))
+    return [(kind[i], idx[i], ns[i]) for i in range(min(n, cap))]
+
+
+# ---- single kernels -------------------------------------------------------------------------------------
+def sif_k_gemm_bf16(a, b, c, m, n, k, lda, ldb, ldc, a_layout=SIF_A_ROW_K, b_layout=SIF_B_ROW_K, epilogue=0,
+                    bias=None, res=None, aux=None, alpha=1.0, batch_outer=1, batch_inner=1,
+                    a_strides=(0, 0), b_strides=(0, 0), c_strides=(0, 0), k_causal=0, stream=None):
+    g = sif_gemm_args()
+    g.struct_size = C.sizeof(sif_gemm_args)
+    g.a_layout, g.b_layout, g.epilogue = a_layout, b_layout, epilogue
+    g.m, g.n, g.k, g.lda, g.ldb, g.ldc = m, n, k, lda, ldb, ldc
+    g.batch_outer, g.batch_inner = batch_outer, batch_inner
+    g.a_stride_outer, g.a_stride_inner = a_strides
+    g.b_stride_outer, g.b_stride_inner = b_strides
+    g.c_stride_outer, g.c_stride_inner = c_strides
+    g.alpha, g.k_causal = alpha, k_causal
+    g.a_dev, g.b_dev, g.c_dev, g.bias_dev, g.res_dev, g.aux_dev = ptr(a), ptr(b), ptr(c), ptr(bias), ptr(res), ptr(aux)
+    return check(lib.sif_k_gemm_bf16(C.byref(g), stream_ptr(stream)))
+
+
+def sif_k_gemm_f32(a, a_sm, a_sk, b, b_sk, b_sn, c, ldc, m, n, k, epilogue=0, bias=None, aux=None, stream=None):
+    return check(lib.sif_k_gemm_f32(ptr(a), a_sm, a_sk, ptr(b), b_sk, b_sn, ptr(c), ldc, m, n, k, epilogue, ptr(bias),
+                                    ptr(aux), stream_ptr(stream)))
+
+
+def sif_k_layernorm_fwd(x, g, b, y, mean, rstd, rows, d, stream=None):
+    return check(lib.sif_k_layernorm_fwd(ptr(x), ptr(g), ptr(b), ptr(y), ptr(mean), ptr(rstd), rows, d, stream_ptr(stream)))
+
+
+def sif_k_layernorm_bwd(dy, x, g, mean, rstd, res, dx, dg, db, part, rows, d, stream=None):
+    return check(lib.sif_k_layernorm_bwd(ptr(dy), ptr(x), ptr(g), ptr(mean), ptr(rstd), ptr(res), ptr(dx), ptr(dg),
+                                         ptr(db), ptr(part), rows, d, stream_ptr(stream)))
+
+
+def sif_colsum_parts(rows):
+    return lib.sif_colsum_parts(rows)
+
+
+def sif_k_colsum(x, ld, out, part, rows, n, stream=None):
+    return check(lib.sif_k_colsum(ptr(x), ld, ptr(out), ptr(part), rows, n, stream_ptr(stream)))
+
+
+def sif_k_softmax_fwd(s, p, batch, rows, cols, ld_s, ld_p, causal, stream=None):
+    return check(lib.sif_k_softmax_fwd(ptr(s), ptr(p), batch, rows, cols, ld_s, ld_p, causal, stream_ptr(stream)))
+
+
+def sif_k_softmax_bwd(dp, p, ds, batch, rows, cols, ld, scale, causal, stream=None):
+    return check(lib.sif_k_softmax_bwd(ptr(dp), ptr(p), ptr(ds), batch, rows, cols, ld, scale, causal, stream_ptr(stream)))
+
+
+def sif_k_embed_fwd(ids, wte, wpe, x, tokens, seq, d, stream=None):
+    return check(lib.sif_k_embed_fwd(ptr(ids), ptr(wte), ptr(wpe), ptr(x), tokens, seq, d, stream_ptr(stream)))
+
+
+def sif_k_embed_bwd(ids, dx, dwte, dwpe, tokens, seq, d, stream=None):
+    return check(lib.sif_k_embed_bwd(ptr(ids), ptr(dx), ptr(dwte), ptr(dwpe), tokens, seq, d, stream_ptr(stream)))
+
+
+def sif_k_xent_fwd_bwd(logits, targets, loss, tokens, vocab, ld, stream=None):
+    return check(lib.sif_k_xent_fwd_bwd(ptr(logits), ptr(targets), ptr(loss), tokens, vocab, ld, stream_ptr(stream)))
+
+
+def sif_k_reduce_sum(x, out, n, scale, stream=None):
+    return check(lib.sif_k_reduce_sum(ptr(x), ptr(out), n, scale, stream_ptr(stream)))
+
+
+def sif_k_sgd_bf16(master, grad, work, n, lr, stream=None):
+    return check(lib.sif_k_sgd_bf16(ptr(master), ptr(grad), ptr(work), n, lr, stream_ptr(stream)))
+
+
+def sif_k_sgd_f32(p, g, n, lr, stream=None):
+    return check(lib.sif_k_sgd_f32(ptr(p), ptr(g), n, lr, stream_ptr(stream)))
+
+
+def sif_k_mse_fwd_bwd(y, t, d, loss, n, stream=None):
+    return check(lib.sif_k_mse_fwd_bwd(ptr(y), ptr(t), ptr(d), ptr(loss), n, stream_ptr(stream)))
+
+
+def sif_k_colsum_f32(x, ld, out, rows, n, stream=None):
+    return check(lib.sif_k_colsum_f32(ptr(x), ld, ptr(out), rows, n, stream_ptr(stream)))

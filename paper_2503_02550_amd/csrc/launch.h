@@ -1,0 +1,55 @@
+// Host-side helpers shared by the launchers: error reporting and the internal launcher prototypes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "monitor.h"
+#include "specinf.h"
+
+namespace sif {
+
+sif_status fail(sif_status code, const char* fmt, ...);
+sif_status fail_hip(hipError_t e, const char* what);
+// Checks hipGetLastError() after a launch.
+sif_status check_launch(const char* what);
+
+inline KCtl no_ctl() { KCtl c{}; return c; }
+
+// Internal launchers: same argument checks as the public sif_k_* entry points, plus the monitor control block.
+sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t s, const KCtl& c);
+sif_status launch_gemm_f32(const float* a, int64_t a_sm, int64_t a_sk, const float* b, int64_t b_sk, int64_t b_sn,
+                           float* c, int64_t ldc, uint32_t m, uint32_t n, uint32_t k, uint32_t epi, const float* bias,
+                           float* aux, hipStream_t s, const KCtl& ctl);
+sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
+                                uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c);
+sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                                   const void* res, void* dx, float* part, uint32_t rows, uint32_t d, hipStream_t s,
+                                   const KCtl& c);
+sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, hipStream_t s,
+                                    const KCtl& c);
+sif_status launch_colsum_part(const void* x, uint32_t ld, float* part, uint32_t rows, uint32_t n, hipStream_t s,
+                              const KCtl& c);
+sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c);
+sif_status launch_softmax_fwd(const float* sc, void* p, uint32_t batch, uint32_t rows, uint32_t cols, uint32_t ld_s,
+                              uint32_t ld_p, uint32_t causal, hipStream_t s, const KCtl& c);
+sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t batch, uint32_t rows, uint32_t cols,
+                              uint32_t ld, float scale, uint32_t causal, hipStream_t s, const KCtl& c);
+sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens,
+                            uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c);
+sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t tokens, uint32_t d,
+                                hipStream_t s, const KCtl& c);
+sif_status launch_embed_bwd_wpe(const void* dx, void* dwpe, uint32_t tokens, uint32_t seq, uint32_t d, hipStream_t s,
+                                const KCtl& c);
+sif_status launch_xent(void* logits, const int32_t* targets, float* loss, uint32_t tokens, uint32_t vocab, uint32_t ld,
+                       hipStream_t s, const KCtl& c);
+sif_status launch_reduce_sum(const float* x, float* out, uint32_t n, float scale, hipStream_t s, const KCtl& c);
+sif_status launch_sgd_bf16(float* master, const void* grad, void* work, uint64_t n, float lr, hipStream_t s,
+                           const KCtl& c);
+sif_status launch_sgd_f32(float* p, const float* g, uint64_t n, float lr, hipStream_t s, const KCtl& c);
+sif_status launch_mse(const float* y, const float* t, float* d, float* loss, uint32_t n, hipStream_t s, const KCtl& c);
+sif_status launch_colsum_f32(const float* x, uint32_t ld, float* out, uint32_t rows, uint32_t n, hipStream_t s,
+                             const KCtl& c);
+sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c);
+
+uint32_t colsum_parts(uint32_t rows);
+
+}  // namespace sif

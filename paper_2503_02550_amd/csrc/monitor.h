@@ -1,0 +1,188 @@
+// Device-side activity monitor: the record every hot-path kernel keeps up to date in HBM, the per-launch trace
+// slot, and the pinned host mailbox the monitor and barrier threads read.
+//
+// Role in the method (Sec. 3.3): the paper's monitoring library counts the kernels a training instance issues
+// and its Kernel Barrier blocks or forwards each inference kernel at the CPU launch site.  Here the count is
+// kept by a prologue/epilogue inside each kernel, and an inference kernel that was launched speculatively
+// re-checks the training stream's state on the device before it does any work: the first block of the launch
+// decides (run or skip), publishes the decision, and every other block follows it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sif {
+
+constexpr uint32_t kNone = 0xFFFFFFFFu;
+constexpr uint32_t kRingSlots = 1u << 16;   // trace slots per stream
+constexpr uint32_t kStateIdle = 0, kStateBusy = 1;
+enum : uint32_t { kKindTrain = 1, kKindInfer = 2, kKindBubble = 3, kKindStep = 4 };
+
+struct alignas(128) StreamRec {     // one per stream, in HBM
+  uint32_t state;                   // training stream: kStateBusy / kStateIdle (inside a bubble)
+  uint32_t seq;                     // number of the current / last bubble
+  uint32_t site;                    // its site in the step
+  uint32_t launched;                // kernels started on this stream
+  uint32_t completed;               // kernels finished
+  uint32_t skip_from;               // inference stream: first skipped launch (poison), kNone if clear
+  uint32_t pad0, pad1;
+  uint64_t t_start, t_end;          // last kernel start / end (device wall clock ticks)
+  uint64_t t_idle_begin;            // start of the current / last bubble
+  uint64_t t_busy_begin;            // end of the last finished bubble
+  uint64_t t_expected_end;          // predicted end of the current bubble
+  uint64_t step_t0;
+  // accumulators (ticks / counts), mirrored to the host mailbox by whoever updates them
+  uint64_t steps, step_ticks_sum, step_ticks_last;
+  uint64_t bubble_ticks, filled_ticks, infer_ticks;
+  uint64_t kernels_run, kernels_skipped, train_kernels;
+};
+
+struct alignas(32) Slot {           // one per launch, ring indexed by launch number
+  uint32_t arrive;                  // blocks that entered the prologue
+  uint32_t done;                    // blocks that left the epilogue
+  uint32_t decision;                // (launch number << 2) | 1 run | 2 skip
+  uint32_t kind_id;                 // (kind << 28) | id
+  uint64_t t0, t1;
+};
+
+struct Mirror {                     // pinned, coherent host memory
+  // device -> host
+  uint32_t t_launched, t_completed;
+  uint32_t idle_seq, busy_seq, idle_site, pad0;
+  uint32_t i_done, i_skip_from, i_reset_ack, pad1;
+  uint64_t steps, step_ticks_sum, step_ticks_last;
+  uint64_t bubble_ticks, filled_ticks, infer_ticks;
+  uint64_t kernels_run, kernels_skipped, train_kernels;
+  // host -> device
+  uint32_t release_seq, pad2;
+};
+
+struct KCtl {                       // by-value kernel argument
+  StreamRec* rec;                   // this stream's record; nullptr = unmonitored launch
+  Mirror* mir;
+  Slot* slot;
+  const StreamRec* gate;            // training record an inference kernel is gated on, or nullptr
+  uint32_t kseq;                    // launch number on this stream (>= 1)
+  uint32_t cost_ticks;              // predicted duration
+  uint32_t kind_id;
+  uint32_t pad;
+};
+
+__device__ __forceinline__ uint64_t now_ticks() { return wall_clock64(); }
+
+template <typename T>
+__device__ __forceinline__ T ld_agent(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void st_agent(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void st_sys(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+template <typename T>
+__device__ __forceinline__ T ld_sys(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__device__ __forceinline__ uint32_t grid_blocks() { return gridDim.x * gridDim.y * gridDim.z; }
+__device__ __forceinline__ bool first_thread() { return threadIdx.x == 0 && threadIdx.y == 0 && threadIdx.z == 0; }
+
+// Decision of the first block of a gated launch: run only if no earlier launch of this speculation window was
+// skipped, the training stream is inside a bubble, the predicted rest of the bubble holds this kernel, and
+// the bubble is still the same one after the start time was stamped.
+__device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
+  if (ld_agent(&c.rec->skip_from) != kNone) return false;
+  uint32_t st = ld_agent(&c.gate->state);
+  uint32_t sq = ld_agent(&c.gate->seq);
+  if (st != kStateIdle) return false;
+  uint64_t t = now_ticks();
+  if (t + c.cost_ticks > ld_agent(&c.gate->t_expected_end)) return false;
+  if (ld_agent(&c.gate->state) != kStateIdle || ld_agent(&c.gate->seq) != sq) return false;
+  *t0 = t;
+  return true;
+}
+
+// Kernel prologue.  Every thread calls it; returns false when the launch is skipped (the kernel must then do
+// nothing but call kernel_end(c, false)).  Deadlock-free: only blocks that arrived after the deciding block
+// wait, and the deciding block is running and waits for nothing.
+__device__ __forceinline__ bool kernel_begin(const KCtl& c) {
+  if (c.rec == nullptr) return true;
+  __shared__ int s_run;
+  if (first_thread()) {
+    int run = 1;
+    uint32_t old = atomicAdd(&c.slot->arrive, 1u);
+    if (old == 0) {
+      uint64_t t0 = now_ticks();
+      if (c.gate != nullptr) run = gate_decide(c, &t0) ? 1 : 0;
+      if (run) {
+        st_agent(&c.slot->t0, t0);
+        c.slot->kind_id = c.kind_id;
+        st_agent(&c.rec->t_start, t0);
+        uint32_t l = ld_agent(&c.rec->launched) + 1;
+        st_agent(&c.rec->launched, l);
+        if ((c.kind_id >> 28) == kKindTrain) st_sys(&c.mir->t_launched, l);
+      } else {
+        c.slot->t0 = t0;
+        c.slot->t1 = t0;
+        c.slot->kind_id = c.kind_id;
+        if (ld_agent(&c.rec->skip_from) == kNone) {
+          st_agent(&c.rec->skip_from, c.kseq);
+          st_sys(&c.mir->i_skip_from, c.kseq);
+        }
+      }
+      st_agent(&c.slot->decision, (c.kseq << 2) | (run ? 1u : 2u));
+    } else {
+      uint32_t d;
+      while (((d = ld_agent(&c.slot->decision)) >> 2) != c.kseq) __builtin_amdgcn_s_sleep(2);
+      run = (d & 3u) == 1u;
+    }
+    s_run = run;
+  }
+  __syncthreads();
+  return s_run != 0;
+}
+
+// Kernel epilogue.  Every thread calls it after its last global store.  The last block to leave stamps the
+// end time, bumps the counters and re-arms the slot.
+__device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
+  if (c.rec == nullptr) return;
+  __syncthreads();
+  if (!first_thread()) return;
+  __threadfence();
+  uint32_t old = atomicAdd(&c.slot->done, 1u);
+  if (old + 1 != grid_blocks()) return;
+  c.slot->done = 0;
+  st_agent(&c.slot->arrive, 0u);
+  Mirror* m = c.mir;
+  StreamRec* r = c.rec;
+  if (!ran) {
+    st_sys(&m->kernels_skipped, ++r->kernels_skipped);
+    return;
+  }
+  uint64_t t1 = now_ticks();
+  uint64_t t0 = ld_agent(&c.slot->t0);
+  c.slot->t1 = t1;
+  st_agent(&c.rec->t_end, t1);
+  uint32_t done = ld_agent(&c.rec->completed) + 1;
+  st_agent(&c.rec->completed, done);
+  if ((c.kind_id >> 28) == kKindTrain) {
+    st_sys(&m->t_completed, done);
+    st_sys(&m->train_kernels, ++r->train_kernels);
+  } else {
+    uint64_t dur = t1 - t0, fill = dur;
+    if (c.gate != nullptr) {
+      uint64_t ib = ld_agent(&c.gate->t_idle_begin);
+      uint64_t end = (ld_agent(&c.gate->state) == kStateIdle) ? t1 : ld_agent(&c.gate->t_busy_begin);
+      uint64_t lo = t0 > ib ? t0 : ib, hi = t1 < end ? t1 : end;
+      fill = hi > lo ? hi - lo : 0;
+    }
+    st_sys(&m->infer_ticks, r->infer_ticks += dur);
+    st_sys(&m->filled_ticks, r->filled_ticks += fill);
+    st_sys(&m->kernels_run, ++r->kernels_run);
+    st_sys(&m->i_done, c.kseq);
+  }
+}
+
+}  // namespace sif

@@ -1,0 +1,593 @@
+// Memory-bound kernels of the training step and the inference forward pass: LayerNorm, softmax, embedding,
+// cross entropy, column sums, SGD.  They are bound by HBM traffic, so each reads its operands once with 16-byte
+// accesses, keeps fp32 statistics in registers / LDS, and uses fixed-order reductions (no float atomics) so
+// that results are bit-identical from run to run and independent of what else shares the GPU.
+#include "common.h"
+#include "launch.h"
+
+namespace sif {
+
+constexpr float kLnEps = 1e-5f;
+
+__device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
+  f[0] = bflo(v.x); f[1] = bfhi(v.x); f[2] = bflo(v.y); f[3] = bfhi(v.y);
+  f[4] = bflo(v.z); f[5] = bfhi(v.z); f[6] = bflo(v.w); f[7] = bfhi(v.w);
+}
+__device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
+  return make_uint4(pack_bf2(f[0], f[1]), pack_bf2(f[2], f[3]), pack_bf2(f[4], f[5]), pack_bf2(f[6], f[7]));
+}
+
+// ---------------------------------------------------------------------------------------------- LayerNorm
+// One wavefront per row, 4 rows per block.
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
+                                                            const bf16_t* __restrict__ b, bf16_t* __restrict__ y,
+                                                            float* __restrict__ mean_out, float* __restrict__ rstd_out,
+                                                            uint32_t rows, uint32_t d, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, nv = d >> 3;
+  if (row < rows) {
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
+    float s = 0.f, f[8];
+    for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) s += f[i]; }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+    for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) { float t = f[i] - mean; q += t * t; } }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + kLnEps);
+    uint4* yr = reinterpret_cast<uint4*>(y + (size_t)row * d);
+    for (uint32_t v = lane; v < nv; v += 64) {
+      float fg[8], fb[8], o[8];
+      unpack8(xr[v], f); unpack8(reinterpret_cast<const uint4*>(g)[v], fg); unpack8(reinterpret_cast<const uint4*>(b)[v], fb);
+      for (int i = 0; i < 8; ++i) o[i] = (f[i] - mean) * rstd * fg[i] + fb[i];
+      yr[v] = pack8(o);
+    }
+    if (lane == 0 && mean_out != nullptr) { mean_out[row] = mean; rstd_out[row] = rstd; }
+  }
+  kernel_end(ctl, true);
+}
+
+constexpr int LN_MAXV = 8;   // vectors of 8 columns per lane: d <= 4096
+uint32_t colsum_parts(uint32_t rows) { uint32_t p = (rows + 31) / 32; return p < 1 ? 1 : (p > 512 ? 512 : p); }
+
+// dx = res + rstd * (dy*g - mean(dy*g) - xhat * mean(dy*g*xhat)); per-block partial column sums of dy*xhat and
+// dy are written to part[blk][d] and part[parts+blk][d].  Block b handles rows b, b+parts, ... in wave order.
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
+                                                            const bf16_t* __restrict__ g, const float* __restrict__ mean,
+                                                            const float* __restrict__ rstd, const bf16_t* __restrict__ res,
+                                                            bf16_t* __restrict__ dx, float* __restrict__ part,
+                                                            uint32_t rows, uint32_t d, uint32_t parts, KCtl ctl) {
+  __shared__ float sred[4 * 512];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nv = d >> 3;
+  const uint32_t rows_per = (rows + parts - 1) / parts;
+  const uint32_t r_begin = blockIdx.x * rows_per, r_end = min(rows, r_begin + rows_per);
+  float ag[LN_MAXV][8], ab[LN_MAXV][8];
+#pragma unroll
+  for (int t = 0; t < LN_MAXV; ++t)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { ag[t][i] = 0.f; ab[t][i] = 0.f; }
+  for (uint32_t row = r_begin + wave; row < r_end; row += 4) {
+    const uint4* dyr = reinterpret_cast<const uint4*>(dy + (size_t)row * d);
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
+    const float mu = mean[row], rs = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int t = 0; t < LN_MAXV; ++t) {
+      const uint32_t v = lane + 64 * t;
+      if (v < nv) {
+        float fdy[8], fx[8], fg[8];
+        unpack8(dyr[v], fdy); unpack8(xr[v], fx); unpack8(reinterpret_cast<const uint4*>(g)[v], fg);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float xh = (fx[i] - mu) * rs, dxh = fdy[i] * fg[i];
+          s1 += dxh; s2 += dxh * xh;
+          ag[t][i] += fdy[i] * xh; ab[t][i] += fdy[i];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int t = 0; t < LN_MAXV; ++t) {
+      const uint32_t v = lane + 64 * t;
+      if (v < nv) {
+        float fdy[8], fx[8], fg[8], fr[8], o[8];
+        unpack8(dyr[v], fdy); unpack8(xr[v], fx); unpack8(reinterpret_cast<const uint4*>(g)[v], fg);
+        if (res != nullptr) unpack8(reinterpret_cast<const uint4*>(res + (size_t)row * d)[v], fr);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float xh = (fx[i] - mu) * rs;
+          o[i] = rs * (fdy[i] * fg[i] - m1 - xh * m2);
+          if (res != nullptr) o[i] += fr[i];
+        }
+        reinterpret_cast<uint4*>(dx + (size_t)row * d)[v] = pack8(o);
+      }
+    }
+  }
+  // combine the four wavefronts in order 0,1,2,3, 512 columns at a time
+  for (int t = 0; t < LN_MAXV; ++t) {
+    if ((uint32_t)(64 * t) >= nv) break;
+    for (int which = 0; which < 2; ++which) {
+      __syncthreads();
+      for (int i = 0; i < 8; ++i) sred[wave * 512 + lane * 8 + i] = which ? ab[t][i] : ag[t][i];
+      __syncthreads();
+      for (uint32_t cidx = threadIdx.x; cidx < 512; cidx += 256) {
+        const uint32_t col = 512 * t + cidx;
+        if (col < d) {
+          const float s = ((sred[cidx] + sred[512 + cidx]) + sred[1024 + cidx]) + sred[1536 + cidx];
+          part[(size_t)(which * parts + blockIdx.x) * d + col] = s;
+        }
+      }
+    }
+  }
+  kernel_end(ctl, true);
+}
+
+// out[c] = bf16(sum_p part[p][c]) for dg (first `parts` rows) and db (next `parts` rows).
+__global__ __launch_bounds__(256) void layernorm_bwd_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ dg,
+                                                                bf16_t* __restrict__ db, uint32_t parts, uint32_t d, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+  if (c < d) {
+    float sg = 0.f, sb = 0.f;
+    for (uint32_t p = 0; p < parts; ++p) { sg += part[(size_t)p * d + c]; sb += part[(size_t)(parts + p) * d + c]; }
+    dg[c] = f2bf(sg); db[c] = f2bf(sb);
+  }
+  kernel_end(ctl, true);
+}
+
+// ---------------------------------------------------------------------------------------------- column sums
+// grid (ceil(n/512), parts): lane owns 8 columns, wave w takes rows r_begin+w, +4, ...
+__global__ __launch_bounds__(256) void colsum_part_kernel(const bf16_t* __restrict__ x, uint32_t ld, float* __restrict__ part,
+                                                          uint32_t rows, uint32_t n, uint32_t parts, KCtl ctl) {
+  __shared__ float sred[4 * 512];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t c0 = blockIdx.x * 512 + lane * 8;
+  const uint32_t rows_per = (rows + parts - 1) / parts;
+  const uint32_t r_begin = blockIdx.y * rows_per, r_end = min(rows, r_begin + rows_per);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c0 < n) {
+    for (uint32_t row = r_begin + wave; row < r_end; row += 4) {
+      float f[8];
+      unpack8(*reinterpret_cast<const uint4*>(x + (size_t)row * ld + c0), f);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += f[i];
+    }
+  }
+  for (int i = 0; i < 8; ++i) sred[wave * 512 + lane * 8 + i] = acc[i];
+  __syncthreads();
+  for (uint32_t cidx = threadIdx.x; cidx < 512; cidx += 256) {
+    const uint32_t col = blockIdx.x * 512 + cidx;
+    if (col < n) part[(size_t)blockIdx.y * n + col] = ((sred[cidx] + sred[512 + cidx]) + sred[1024 + cidx]) + sred[1536 + cidx];
+  }
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(256) void colsum_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
+                                                         uint32_t parts, uint32_t n, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+  if (c < n) {
+    float s = 0.f;
+    for (uint32_t p = 0; p < parts; ++p) s += part[(size_t)p * n + c];
+    out[c] = f2bf(s);
+  }
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(256) void colsum_f32_kernel(const float* __restrict__ x, uint32_t ld, float* __restrict__ out,
+                                                         uint32_t rows, uint32_t n, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+  if (c < n) {
+    float s = 0.f;
+    for (uint32_t r = 0; r < rows; ++r) s += x[(size_t)r * ld + c];
+    out[c] = s;
+  }
+  kernel_end(ctl, true);
+}
+
+// ---------------------------------------------------------------------------------------------- softmax
+constexpr int SM_MAXT = 8;   // 4 columns per lane per step: cols <= 2048
+
+// One wavefront per row; the row lives in registers.
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restrict__ s, bf16_t* __restrict__ p, uint32_t rows,
+                                                          uint32_t cols, uint32_t ld_s, uint32_t ld_p, uint32_t causal, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row < rows) {
+    const size_t r = (size_t)blockIdx.y * rows + row;
+    const uint32_t valid = causal ? min(cols, row + 1) : cols;
+    const float* sr = s + r * ld_s;
+    float v[SM_MAXT][4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < SM_MAXT; ++t) {
+      const uint32_t c = (t * 64 + lane) * 4;
+      if (c < valid) {
+        const float4 q = *reinterpret_cast<const float4*>(sr + c);
+        v[t][0] = q.x; v[t][1] = (c + 1 < valid) ? q.y : -INFINITY; v[t][2] = (c + 2 < valid) ? q.z : -INFINITY;
+        v[t][3] = (c + 3 < valid) ? q.w : -INFINITY;
+      } else { v[t][0] = v[t][1] = v[t][2] = v[t][3] = -INFINITY; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mx = fmaxf(mx, v[t][i]);
+    }
+    mx = wave_max(mx);
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < SM_MAXT; ++t)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { v[t][i] = __expf(v[t][i] - mx); sum += v[t][i]; }
+    const float inv = 1.0f / wave_sum(sum);
+    bf16_t* pr = p + r * ld_p;
+#pragma unroll
+    for (int t = 0; t < SM_MAXT; ++t) {
+      const uint32_t c = (t * 64 + lane) * 4;
+      if (c < ld_p) *reinterpret_cast<uint2*>(pr + c) = make_uint2(pack_bf2(v[t][0] * inv, v[t][1] * inv), pack_bf2(v[t][2] * inv, v[t][3] * inv));
+    }
+  }
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* __restrict__ dp, const bf16_t* __restrict__ p,
+                                                          bf16_t* __restrict__ ds, uint32_t rows, uint32_t cols, uint32_t ld,
+                                                          float scale, uint32_t causal, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row < rows) {
+    const size_t r = (size_t)blockIdx.y * rows + row;
+    const uint32_t valid = causal ? min(cols, row + 1) : cols;
+    float a[SM_MAXT][4], q[SM_MAXT][4];
+    float dot = 0.f;
+#pragma unroll
+    for (int t = 0; t < SM_MAXT; ++t) {
+      const uint32_t c = (t * 64 + lane) * 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[t][i] = 0.f; q[t][i] = 0.f; }
+      if (c < valid) {
+        const float4 g = *reinterpret_cast<const float4*>(dp + r * ld + c);
+        const uint2 w = *reinterpret_cast<const uint2*>(p + r * ld + c);
+        a[t][0] = g.x; a[t][1] = g.y; a[t][2] = g.z; a[t][3] = g.w;
+        q[t][0] = bflo(w.x); q[t][1] = bfhi(w.x); q[t][2] = bflo(w.y); q[t][3] = bfhi(w.y);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (c + i >= valid) { a[t][i] = 0.f; q[t][i] = 0.f; }
+          dot += a[t][i] * q[t][i];
+        }
+      }
+    }
+    dot = wave_sum(dot);
+#pragma unroll
+    for (int t = 0; t < SM_MAXT; ++t) {
+      const uint32_t c = (t * 64 + lane) * 4;
+      if (c < ld) {
+        float o[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = scale * q[t][i] * (a[t][i] - dot);
+        *reinterpret_cast<uint2*>(ds + r * ld + c) = make_uint2(pack_bf2(o[0], o[1]), pack_bf2(o[2], o[3]));
+      }
+    }
+  }
+  kernel_end(ctl, true);
+}
+
+// ---------------------------------------------------------------------------------------------- embedding
+__global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restrict__ ids, const bf16_t* __restrict__ wte,
+                                                        const bf16_t* __restrict__ wpe, bf16_t* __restrict__ x,
+                                                        uint32_t tokens, uint32_t seq, uint32_t d, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, nv = d >> 3;
+  if (t < tokens) {
+    const uint4* a = reinterpret_cast<const uint4*>(wte + (size_t)ids[t] * d);
+    const uint4* b = reinterpret_cast<const uint4*>(wpe + (size_t)(t % seq) * d);
+    uint4* o = reinterpret_cast<uint4*>(x + (size_t)t * d);
+    for (uint32_t v = lane; v < nv; v += 64) {
+      float fa[8], fb[8], r[8];
+      unpack8(a[v], fa); unpack8(b[v], fb);
+      for (int i = 0; i < 8; ++i) r[i] = fa[i] + fb[i];
+      o[v] = pack8(r);
+    }
+  }
+  kernel_end(ctl, true);
+}
+
+constexpr int EB_MAXC = 16;   // columns per thread: d <= 4096
+
+// Block t owns token t.  If an earlier token has the same id the block has nothing to do; otherwise it adds the
+// rows dx[j] of every token j >= t with that id, in ascending j, to dwte[id].
+__global__ __launch_bounds__(256) void embed_bwd_wte_kernel(const int32_t* __restrict__ ids, const bf16_t* __restrict__ dx,
+                                                            bf16_t* __restrict__ dwte, uint32_t tokens, uint32_t d, KCtl ctl) {
+  __shared__ int sflag[256];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t t = blockIdx.x;
+  const int32_t id = ids[t];
+  int seen = 0;
+  for (uint32_t j = threadIdx.x; j < t; j += 256) seen |= (ids[j] == id);
+  if (!__syncthreads_or(seen)) {
+    float acc[EB_MAXC];
+#pragma unroll
+    for (int i = 0; i < EB_MAXC; ++i) acc[i] = 0.f;
+    for (uint32_t base = t; base < tokens; base += 256) {
+      const uint32_t j = base + threadIdx.x;
+      const int hit = (j < tokens) && (ids[j] == id);
+      __syncthreads();
+      sflag[threadIdx.x] = hit;
+      if (__syncthreads_or(hit)) {
+        for (uint32_t w = 0; w < 256; ++w) {
+          if (sflag[w]) {
+            const bf16_t* row = dx + (size_t)(base + w) * d;
+#pragma unroll
+            for (int i = 0; i < EB_MAXC; ++i) { const uint32_t c = threadIdx.x + 256 * i; if (c < d) acc[i] += bf2f(row[c]); }
+          }
+        }
+      }
+    }
+    bf16_t* out = dwte + (size_t)id * d;
+#pragma unroll
+    for (int i = 0; i < EB_MAXC; ++i) { const uint32_t c = threadIdx.x + 256 * i; if (c < d) out[c] = f2bf(bf2f(out[c]) + acc[i]); }
+  }
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(256) void embed_bwd_wpe_kernel(const bf16_t* __restrict__ dx, bf16_t* __restrict__ dwpe,
+                                                            uint32_t tokens, uint32_t seq, uint32_t d, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t s = blockIdx.x;
+  for (uint32_t c = threadIdx.x; c < d; c += 256) {
+    float a = 0.f;
+    for (uint32_t t = s; t < tokens; t += seq) a += bf2f(dx[(size_t)t * d + c]);
+    dwpe[(size_t)s * d + c] = f2bf(a);
+  }
+  kernel_end(ctl, true);
+}
+
+// ---------------------------------------------------------------------------------------------- cross entropy
+// One block per token; the row of logits is staged in LDS (up to 144 KB of the CU's 160 KB), reduced, and
+// written back as the gradient.
+__global__ __launch_bounds__(1024) void xent_kernel(bf16_t* __restrict__ logits, const int32_t* __restrict__ targets,
+                                                    float* __restrict__ loss, uint32_t tokens, uint32_t vocab, uint32_t ld, KCtl ctl) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  __shared__ float sred[16];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  uint4* row_s = reinterpret_cast<uint4*>(smem_raw);
+  bf16_t* row_e = reinterpret_cast<bf16_t*>(smem_raw);
+  const uint32_t t = blockIdx.x, nv = ld >> 3;
+  uint4* gr = reinterpret_cast<uint4*>(logits + (size_t)t * ld);
+  float mx = -INFINITY;
+  for (uint32_t v = threadIdx.x; v < nv; v += blockDim.x) {
+    const uint4 q = gr[v];
+    row_s[v] = q;
+    float f[8];
+    unpack8(q, f);
+    for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) mx = fmaxf(mx, f[i]);
+  }
+  mx = block_max(mx, sred);
+  float sum = 0.f;
+  for (uint32_t v = threadIdx.x; v < nv; v += blockDim.x) {
+    float f[8];
+    unpack8(row_s[v], f);
+    for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) sum += __expf(f[i] - mx);
+  }
+  sum = block_sum(sum, sred);
+  const int32_t tg = targets[t];
+  const float inv = 1.0f / sum, invn = 1.0f / (float)tokens;
+  if (threadIdx.x == 0) loss[t] = (mx + __logf(sum)) - bf2f(row_e[tg]);
+  __syncthreads();
+  for (uint32_t v = threadIdx.x; v < nv; v += blockDim.x) {
+    float f[8], o[8];
+    unpack8(row_s[v], f);
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t c = v * 8 + i;
+      o[i] = c < vocab ? (__expf(f[i] - mx) * inv - (c == (uint32_t)tg ? 1.f : 0.f)) * invn : 0.f;
+    }
+    gr[v] = pack8(o);
+  }
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(1024) void reduce_sum_kernel(const float* __restrict__ x, float* __restrict__ out, uint32_t n, float scale, KCtl ctl) {
+  __shared__ float sred[16];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  float s = 0.f;
+  for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) s += x[i];
+  s = block_sum(s, sred);
+  if (threadIdx.x == 0) out[0] = s * scale;
+  kernel_end(ctl, true);
+}
+
+// ---------------------------------------------------------------------------------------------- optimizer
+__global__ __launch_bounds__(256) void sgd_bf16_kernel(float* __restrict__ master, const bf16_t* __restrict__ grad,
+                                                       bf16_t* __restrict__ work, uint64_t n, float lr, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint64_t nv = n >> 3;
+  for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < nv; v += (uint64_t)gridDim.x * 256) {
+    float4 m0 = reinterpret_cast<float4*>(master)[2 * v], m1 = reinterpret_cast<float4*>(master)[2 * v + 1];
+    float w[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+    if (lr != 0.f) {
+      float g[8];
+      unpack8(reinterpret_cast<const uint4*>(grad)[v], g);
+      for (int i = 0; i < 8; ++i) w[i] = w[i] - lr * g[i];
+      reinterpret_cast<float4*>(master)[2 * v] = make_float4(w[0], w[1], w[2], w[3]);
+      reinterpret_cast<float4*>(master)[2 * v + 1] = make_float4(w[4], w[5], w[6], w[7]);
+    }
+    reinterpret_cast<uint4*>(work)[v] = pack8(w);
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (n & 7)) {        // ragged tail
+    const uint64_t i = (nv << 3) + threadIdx.x;
+    float w = master[i];
+    if (lr != 0.f) { w = w - lr * bf2f(grad[i]); master[i] = w; }
+    work[i] = f2bf(w);
+  }
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(256) void sgd_f32_kernel(float* __restrict__ p, const float* __restrict__ g, uint64_t n, float lr, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) p[i] = p[i] - lr * g[i];
+  kernel_end(ctl, true);
+}
+
+// d = (y - t)/n, loss = sum (y-t)^2 / (2n); one block, fixed order.
+__global__ __launch_bounds__(1024) void mse_kernel(const float* __restrict__ y, const float* __restrict__ t, float* __restrict__ d,
+                                                   float* __restrict__ loss, uint32_t n, KCtl ctl) {
+  __shared__ float sred[16];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  float s = 0.f;
+  const float invn = 1.0f / (float)n;
+  for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) { const float e = y[i] - t[i]; d[i] = e * invn; s += e * e; }
+  s = block_sum(s, sred);
+  if (threadIdx.x == 0 && loss != nullptr) loss[0] = 0.5f * s * invn;
+  kernel_end(ctl, true);
+}
+
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p, uint32_t v, uint64_t n, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)gridDim.x * 256) p[i] = v;
+  kernel_end(ctl, true);
+}
+
+// ---------------------------------------------------------------------------------------------- launchers
+static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+#define REQ(cond, msg) do { if (!(cond)) return fail(SIF_E_INVAL, msg); } while (0)
+
+sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
+                                uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(x && g && b && y && rows > 0 && d > 0, "layernorm_fwd: null or empty");
+  REQ((d & 7) == 0 && al16(x) && al16(g) && al16(b) && al16(y), "layernorm_fwd: d must be a multiple of 8, pointers 16-byte aligned");
+  REQ((mean == nullptr) == (rstd == nullptr), "layernorm_fwd: mean and rstd go together");
+  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g,
+                     (const bf16_t*)b, (bf16_t*)y, mean, rstd, rows, d, c);
+  return check_launch("layernorm_fwd");
+}
+
+sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
+                                   const void* res, void* dx, float* part, uint32_t rows, uint32_t d, hipStream_t s,
+                                   const KCtl& c) {
+  REQ(dy && x && g && mean && rstd && dx && part && rows > 0, "layernorm_bwd: null or empty");
+  REQ((d & 7) == 0 && d <= 8 * 64 * LN_MAXV, "layernorm_bwd: d must be a multiple of 8 and <= 4096");
+  REQ(al16(dy) && al16(x) && al16(g) && al16(dx) && (res == nullptr || al16(res)), "layernorm_bwd: pointers must be 16-byte aligned");
+  const uint32_t parts = colsum_parts(rows);
+  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(parts), dim3(256), 0, s, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g,
+                     mean, rstd, (const bf16_t*)res, (bf16_t*)dx, part, rows, d, parts, c);
+  return check_launch("layernorm_bwd");
+}
+
+sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(part && dg && db, "layernorm_bwd_fin: null");
+  hipLaunchKernelGGL(layernorm_bwd_fin_kernel, dim3((d + 255) / 256), dim3(256), 0, s, part, (bf16_t*)dg, (bf16_t*)db,
+                     colsum_parts(rows), d, c);
+  return check_launch("layernorm_bwd_fin");
+}
+
+sif_status launch_colsum_part(const void* x, uint32_t ld, float* part, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c) {
+  REQ(x && part && rows > 0 && n > 0, "colsum: null or empty");
+  REQ((n & 7) == 0 && (ld & 7) == 0 && ld >= n && al16(x), "colsum: n and ld must be multiples of 8, x 16-byte aligned");
+  const uint32_t parts = colsum_parts(rows);
+  hipLaunchKernelGGL(colsum_part_kernel, dim3((n + 511) / 512, parts), dim3(256), 0, s, (const bf16_t*)x, ld, part, rows, n, parts, c);
+  return check_launch("colsum_part");
+}
+
+sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c) {
+  REQ(part && out, "colsum_fin: null");
+  hipLaunchKernelGGL(colsum_fin_kernel, dim3((n + 255) / 256), dim3(256), 0, s, part, (bf16_t*)out, colsum_parts(rows), n, c);
+  return check_launch("colsum_fin");
+}
+
+sif_status launch_colsum_f32(const float* x, uint32_t ld, float* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c) {
+  REQ(x && out && rows > 0 && n > 0 && ld >= n, "colsum_f32: bad arguments");
+  hipLaunchKernelGGL(colsum_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, x, ld, out, rows, n, c);
+  return check_launch("colsum_f32");
+}
+
+sif_status launch_softmax_fwd(const float* sc, void* p, uint32_t batch, uint32_t rows, uint32_t cols, uint32_t ld_s,
+                              uint32_t ld_p, uint32_t causal, hipStream_t s, const KCtl& c) {
+  REQ(sc && p && batch > 0 && rows > 0 && cols > 0, "softmax_fwd: null or empty");
+  REQ(cols <= 256 * SM_MAXT && ld_p <= 256 * SM_MAXT, "softmax_fwd: at most 2048 columns");
+  REQ((ld_s & 3) == 0 && (ld_p & 3) == 0 && ld_s >= ((cols + 3) & ~3u) && ld_p >= cols && al16(sc) && al16(p), "softmax_fwd: ld must be multiples of 4 and cover cols");
+  REQ(batch <= 65535, "softmax_fwd: batch too large");
+  hipLaunchKernelGGL(softmax_fwd_kernel, dim3((rows + 3) / 4, batch), dim3(256), 0, s, sc, (bf16_t*)p, rows, cols, ld_s, ld_p, causal, c);
+  return check_launch("softmax_fwd");
+}
+
+sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t batch, uint32_t rows, uint32_t cols,
+                              uint32_t ld, float scale, uint32_t causal, hipStream_t s, const KCtl& c) {
+  REQ(dp && p && ds && batch > 0 && rows > 0 && cols > 0, "softmax_bwd: null or empty");
+  REQ(ld <= 256 * SM_MAXT && (ld & 3) == 0 && ld >= cols && al16(dp) && al16(p) && al16(ds), "softmax_bwd: ld must be a multiple of 4, cover cols, at most 2048");
+  REQ(batch <= 65535, "softmax_bwd: batch too large");
+  hipLaunchKernelGGL(softmax_bwd_kernel, dim3((rows + 3) / 4, batch), dim3(256), 0, s, dp, (const bf16_t*)p, (bf16_t*)ds, rows, cols, ld, scale, causal, c);
+  return check_launch("softmax_bwd");
+}
+
+sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens,
+                            uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(ids && wte && wpe && x && tokens > 0 && seq > 0, "embed_fwd: null or empty");
+  REQ((d & 7) == 0 && al16(wte) && al16(wpe) && al16(x), "embed_fwd: d must be a multiple of 8, pointers 16-byte aligned");
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, ids, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, seq, d, c);
+  return check_launch("embed_fwd");
+}
+
+sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t tokens, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(ids && dx && dwte && tokens > 0, "embed_bwd: null or empty");
+  REQ(d <= 256 * EB_MAXC, "embed_bwd: d must be <= 4096");
+  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(tokens), dim3(256), 0, s, ids, (const bf16_t*)dx, (bf16_t*)dwte, tokens, d, c);
+  return check_launch("embed_bwd_wte");
+}
+
+sif_status launch_embed_bwd_wpe(const void* dx, void* dwpe, uint32_t tokens, uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(dx && dwpe && tokens > 0 && seq > 0 && seq <= tokens, "embed_bwd_wpe: bad arguments");
+  hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3(seq), dim3(256), 0, s, (const bf16_t*)dx, (bf16_t*)dwpe, tokens, seq, d, c);
+  return check_launch("embed_bwd_wpe");
+}
+
+sif_status launch_xent(void* logits, const int32_t* targets, float* loss, uint32_t tokens, uint32_t vocab, uint32_t ld,
+                       hipStream_t s, const KCtl& c) {
+  REQ(logits && targets && loss && tokens > 0 && vocab > 0, "xent: null or empty");
+  REQ((ld & 7) == 0 && ld >= vocab && al16(logits), "xent: ld must be a multiple of 8 and >= vocab");
+  const size_t lds = (size_t)ld * sizeof(bf16_t);
+  REQ(lds <= 144 * 1024, "xent: row does not fit in LDS (vocab <= 73728)");
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(xent_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024);
+    if (e != hipSuccess) return fail_hip(e, "xent: hipFuncSetAttribute");
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(xent_kernel, dim3(tokens), dim3(1024), lds, s, (bf16_t*)logits, targets, loss, tokens, vocab, ld, c);
+  return check_launch("xent");
+}
+
+sif_status launch_reduce_sum(const float* x, float* out, uint32_t n, float scale, hipStream_t s, const KCtl& c) {
+  REQ(x && out && n > 0, "reduce_sum: null or empty");
+  hipLaunchKernelGGL(reduce_sum_kernel, dim3(1), dim3(1024), 0, s, x, out, n, scale, c);
+  return check_launch("reduce_sum");
+}
+
+static uint32_t grid_for(uint64_t work_items) {
+  uint64_t b = (work_items + 255) / 256;
+  return (uint32_t)(b < 1 ? 1 : (b > 4096 ? 4096 : b));
+}
+
+sif_status launch_sgd_bf16(float* master, const void* grad, void* work, uint64_t n, float lr, hipStream_t s, const KCtl& c) {
+  REQ(master && work && n > 0 && (grad || lr == 0.f), "sgd_bf16: null or empty");
+  REQ(al16(master) && al16(work) && (grad == nullptr || al16(grad)), "sgd_bf16: pointers must be 16-byte aligned");
+  hipLaunchKernelGGL(sgd_bf16_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, master, (const bf16_t*)grad, (bf16_t*)work, n, lr, c);
+  return check_launch("sgd_bf16");
+}
+
+sif_status launch_sgd_f32(float* p, const float* g, uint64_t n, float lr, hipStream_t s, const KCtl& c) {
+  REQ(p && g && n > 0, "sgd_f32: null or empty");
+  hipLaunchKernelGGL(sgd_f32_kernel, dim3(grid_for(n)), dim3(256), 0, s, p, g, n, lr, c);
+  return check_launch("sgd_f32");
+}
+
+sif_status launch_mse(const float* y, const float* t, float* d, float* loss, uint32_t n, hipStream_t s, const KCtl& c) {
+  REQ(y && t && d && n > 0, "mse: null or empty");
+  hipLaunchKernelGGL(mse_kernel, dim3(1), dim3(1024), 0, s, y, t, d, loss, n, c);
+  return check_launch("mse");
+}
+
+sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c) {
+  REQ(p && n > 0, "fill: null or empty");
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(n)), dim3(256), 0, s, p, v, n, c);
+  return check_launch("fill");
+}
+
+}  // namespace sif

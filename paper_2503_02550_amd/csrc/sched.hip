@@ -1,0 +1,81 @@
+// Scheduler rules as pure host functions: Bubble Monitor zero-count, Algorithm 1 (Adaptive Kernel Scheduling),
+// the Kernel Barrier's offline token rule and online pull rule (Sec. 3.3), the collocation principles
+// (Sec. 3.2) and the bubble model.  The runtime threads call these; they touch no GPU state.
+#include "launch.h"
+
+extern "C" {
+
+uint32_t sif_zero_count(const uint32_t* counts, uint32_t n) {
+  uint32_t z = 0;
+  if (counts == nullptr) return 0;
+  while (z < n && counts[n - 1 - z] == 0) ++z;
+  return z;
+}
+
+sif_status sif_alg1_step(const sif_alg1_params* p, uint32_t zc, uint64_t* pool, uint64_t* grant, int32_t* status) {
+  if (!p || !pool || !grant || !status) return sif::fail(SIF_E_INVAL, "alg1: null pointer");
+  if (p->m == 0 || p->gamma_den == 0) return sif::fail(SIF_E_INVAL, "alg1: m and gamma_den must be positive");
+  if (zc <= p->alpha) {                     // conservative phase: keep the GPU logically busy
+    *pool = 0; *grant = 0; *status = SIF_STATUS_BUSY;
+    return SIF_OK;
+  }
+  const uint64_t base = *pool > p->t0 ? *pool : p->t0;
+  const uint64_t grown = base * p->gamma_num / p->gamma_den;
+  if (zc <= p->beta) {                      // incremental phase: grow towards LL, still busy for online
+    *pool = grown < p->ll ? grown : p->ll;
+    *status = SIF_STATUS_BUSY;
+  } else {                                  // stable phase: grow towards UL, idle
+    *pool = grown < p->ul ? grown : p->ul;
+    *status = SIF_STATUS_IDLE;
+  }
+  *grant = *pool / p->m;
+  return SIF_OK;
+}
+
+uint32_t sif_kb_release(const uint32_t* costs, uint32_t n, uint64_t balance, uint64_t* balance_left) {
+  uint32_t i = 0;
+  while (costs != nullptr && i < n && balance >= costs[i]) balance -= costs[i++];
+  if (balance_left) *balance_left = balance;
+  return i;
+}
+
+int32_t sif_online_pull_ok(int32_t status, uint32_t queue_len, uint64_t predicted_remaining_ns, uint64_t predicted_request_ns) {
+  return status == SIF_STATUS_IDLE && queue_len > 0 && predicted_remaining_ns >= predicted_request_ns;
+}
+
+int32_t sif_principle_1(const uint64_t* peak_bytes, uint32_t n, uint64_t capacity_bytes) {
+  uint64_t s = 0;
+  for (uint32_t i = 0; peak_bytes != nullptr && i < n; ++i) {
+    if (s + peak_bytes[i] < s) return 0;    // overflow
+    s += peak_bytes[i];
+  }
+  return s < capacity_bytes;
+}
+
+int32_t sif_principle_2(uint64_t min_exec_ns, uint64_t max_bubble_ns) { return min_exec_ns < max_bubble_ns; }
+
+uint64_t sif_collective_ns(uint64_t n_bytes, uint64_t bw_bytes_per_s) {
+  if (bw_bytes_per_s == 0) return 0;
+  return (uint64_t)(((unsigned __int128)n_bytes * 1000000000ull) / bw_bytes_per_s);
+}
+
+int32_t sif_pp_1f1b_bubbles(uint32_t stage, uint32_t n_stages, uint32_t n_micro, uint64_t tf_ns, uint64_t tb_ns,
+                            int32_t* kind, int32_t* index, uint64_t* ns, uint32_t max) {
+  if (n_stages == 0 || stage >= n_stages || n_micro < n_stages) return sif::fail(SIF_E_INVAL, "pp: need stage < n_stages <= n_micro");
+  if (max > 0 && (!kind || !index || !ns)) return sif::fail(SIF_E_INVAL, "pp: null output");
+  const uint32_t w = n_stages - 1 - stage;   // warm-up forwards = cool-down backwards
+  uint32_t cnt = 0;
+  auto put = [&](int32_t k, int32_t i, uint64_t t) {
+    if (cnt < max) { kind[cnt] = k; index[cnt] = i; ns[cnt] = t; }
+    ++cnt;
+  };
+  if (stage > 0) put(0, 0, (uint64_t)stage * tf_ns);            // wait for the first activation
+  if (w > 0) {
+    put(1, 0, (uint64_t)w * tb_ns);                             // first gradient travels back through w stages
+    for (uint32_t k = n_micro - w; k < n_micro; ++k) put(1, (int32_t)k, tf_ns);   // cool-down: one forward slot empty
+  }
+  if (stage > 0) put(2, -1, (uint64_t)stage * tb_ns);           // earlier stages still draining
+  return (int32_t)cnt;
+}
+
+}  // extern "C"

@@ -1,0 +1,260 @@
+"""GPU parity of the single kernels against the oracle's definitions (fp64 numpy), through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import numerics as N
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2503_02550_amd as S
+    from gpu_util import DEV, bf, f32, i32, up, q, assert_bf16_close, assert_f32_close
+
+
+def rnd(seed, *shape, scale=1.0):
+    return (np.random.default_rng(seed).standard_normal(shape) * scale).astype(np.float32)
+
+
+# ------------------------------------------------------------------------------------------------ bf16 GEMM
+@pytest.mark.parametrize("al,bl", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("m,n,k", [(200, 264, 136), (128, 128, 64), (1, 8, 8), (300, 72, 520)])
+def test_gemm_bf16_layouts(al, bl, m, n, k):
+    if al == 1 and m % 8:
+        m = (m + 7) // 8 * 8
+    a, b = rnd(1, m, k), rnd(2, k, n)
+    ref = q(a) @ q(b)
+    A = bf(a if al == 0 else a.T)
+    B = bf(b.T if bl == 0 else b)
+    c = torch.full((m, n), 7.0, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_gemm_bf16(A, B, c, m, n, k, A.shape[1], B.shape[1], n, a_layout=al, b_layout=bl)
+    torch.cuda.synchronize()
+    assert_bf16_close(up(c), ref, f"gemm {al}{bl} {m}x{n}x{k}")
+
+
+def test_gemm_bf16_epilogues_and_f32_out():
+    m, n, k = 136, 200, 72
+    a, b, bias, res = rnd(3, m, k), rnd(4, n, k), rnd(5, n), rnd(6, m, n)
+    acc = q(a) @ q(b).T
+    A, B, BI, R = bf(a), bf(b), bf(bias), bf(res)
+    c = torch.zeros((m, n), device=DEV, dtype=torch.bfloat16)
+    S.sif_k_gemm_bf16(A, B, c, m, n, k, k, k, n, epilogue=S.SIF_EPI_BIAS | S.SIF_EPI_RESIDUAL, bias=BI, res=R, alpha=0.5)
+    assert_bf16_close(up(c), 0.5 * acc + q(bias) + q(res), "bias+res")
+    z = torch.zeros_like(c)
+    S.sif_k_gemm_bf16(A, B, c, m, n, k, k, k, n, epilogue=S.SIF_EPI_GELU, bias=BI, aux=z)
+    assert_bf16_close(up(z), acc + q(bias), "gelu pre-activation")
+    assert_bf16_close(up(c), N.gelu(acc + q(bias)), "gelu")
+    S.sif_k_gemm_bf16(A, B, c, m, n, k, k, k, n, epilogue=S.SIF_EPI_GELU_GRAD, aux=z)
+    assert_bf16_close(up(c), acc * N.gelu_grad(up(z)), "gelu grad")
+    cf = torch.zeros((m, n), device=DEV, dtype=torch.float32)
+    S.sif_k_gemm_bf16(A, B, cf, m, n, k, k, k, n, epilogue=S.SIF_EPI_OUT_F32, alpha=0.125)
+    assert_f32_close(up(cf), 0.125 * acc, "f32 out", tol=1e-5)
+
+
+def test_gemm_bf16_batched_heads_and_causal():
+    # attention-shaped: qkv [B,S,3*H*dh]; scores = q k^T per (b,h); P V with a lower-triangular P
+    bsz, s, h, dh = 2, 200, 3, 64
+    da = h * dh
+    qkv = rnd(7, bsz, s, 3 * da)
+    Q = bf(qkv)
+    sc = torch.zeros((bsz * h, s, s), device=DEV, dtype=torch.float32)
+    S.sif_k_gemm_bf16(Q, Q[:, :, da:], sc, s, s, dh, 3 * da, 3 * da, s, epilogue=S.SIF_EPI_OUT_F32 | S.SIF_EPI_CAUSAL_SKIP,
+                      alpha=0.125, batch_outer=bsz, batch_inner=h, a_strides=(s * 3 * da, dh), b_strides=(s * 3 * da, dh),
+                      c_strides=(h * s * s, s * s))
+    x = q(qkv).reshape(bsz, s, 3, h, dh)
+    ref = 0.125 * np.einsum("bihd,bjhd->bhij", x[:, :, 0], x[:, :, 1]).reshape(bsz * h, s, s)
+    got = up(sc)
+    tile_lower = (np.arange(s)[None, :] // 128) <= (np.arange(s)[:, None] // 128)
+    assert_f32_close(got[:, tile_lower], ref[:, tile_lower], "scores", tol=1e-5)
+    assert np.all(got[:, ~tile_lower] == 0)                      # skipped tiles untouched
+    p = np.tril(np.abs(rnd(8, bsz * h, s, s)))
+    P = bf(p)
+    o = torch.zeros((bsz, s, da), device=DEV, dtype=torch.bfloat16)
+    S.sif_k_gemm_bf16(P, Q[:, :, 2 * da:], o, s, dh, s, s, 3 * da, da, b_layout=S.SIF_B_ROW_N, batch_outer=bsz, batch_inner=h,
+                      a_strides=(h * s * s, s * s), b_strides=(s * 3 * da, dh), c_strides=(s * da, dh), k_causal=1)
+    ref = np.einsum("bhij,bjhd->bihd", q(p).reshape(bsz, h, s, s), x[:, :, 2]).reshape(bsz, s, da)
+    assert_bf16_close(up(o), ref, "P V causal")
+    # dV = P^T dO: A stored [K=i][M=j], contraction only over i >= j
+    do = rnd(9, bsz, s, da)
+    DO = bf(do)
+    dv = torch.zeros((bsz, s, da), device=DEV, dtype=torch.bfloat16)
+    S.sif_k_gemm_bf16(P, DO, dv, s, dh, s, s, da, da, a_layout=S.SIF_A_ROW_M, b_layout=S.SIF_B_ROW_N, batch_outer=bsz,
+                      batch_inner=h, a_strides=(h * s * s, s * s), b_strides=(s * da, dh), c_strides=(s * da, dh), k_causal=2)
+    ref = np.einsum("bhij,bihd->bjhd", q(p).reshape(bsz, h, s, s), q(do).reshape(bsz, s, h, dh)).reshape(bsz, s, da)
+    assert_bf16_close(up(dv), ref, "P^T dO causal")
+
+
+def test_gemm_bf16_row_range_is_bit_identical():
+    m, n, k = 512, 256, 192
+    A, B = bf(rnd(10, m, k)), bf(rnd(11, n, k))
+    full = torch.zeros((m, n), device=DEV, dtype=torch.bfloat16)
+    part = torch.zeros_like(full)
+    S.sif_k_gemm_bf16(A, B, full, m, n, k, k, k, n)
+    for r0, r1 in ((0, 128), (128, 384), (384, 512)):
+        S.sif_k_gemm_bf16(A[r0:], B, part[r0:], r1 - r0, n, k, k, k, n)
+    torch.cuda.synchronize()
+    assert torch.equal(full, part)
+
+
+def test_gemm_bf16_rejects_bad_arguments():
+    A = bf(rnd(12, 16, 16))
+    c = torch.zeros((16, 16), device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16(A, A, c, 16, 16, 16, 12, 16, 16)          # lda not a multiple of 8
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16(A, A, c, 0, 16, 16, 16, 16, 16)           # empty
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16(A, A, None, 16, 16, 16, 16, 16, 16)       # null output
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16(A, A, c, 16, 16, 16, 16, 16, 16, epilogue=S.SIF_EPI_RESIDUAL)
+
+
+# ------------------------------------------------------------------------------------------------ fp32 GEMM
+def test_gemm_f32_strided_and_epilogues():
+    m, n, k = 37, 70, 45
+    a, b, bias = rnd(13, m, k), rnd(14, n, k), rnd(15, n)
+    A, B, BI = f32(a), f32(b), f32(bias)
+    c, z = torch.zeros((m, n), device=DEV), torch.zeros((m, n), device=DEV)
+    S.sif_k_gemm_f32(A, k, 1, B, 1, k, c, n, m, n, k, epilogue=S.SIF_EPI_GELU, bias=BI, aux=z)       # x W^T + b
+    pre = a.astype(np.float64) @ b.astype(np.float64).T + bias
+    assert_f32_close(up(z), pre, "pre", 1e-5)
+    assert_f32_close(up(c), N.gelu(pre), "gelu", 1e-5)
+    dy = rnd(16, m, n)
+    DY, dx = f32(dy), torch.zeros((m, k), device=DEV)
+    S.sif_k_gemm_f32(DY, n, 1, B, k, 1, dx, k, m, k, n)                                             # dy W
+    assert_f32_close(up(dx), dy.astype(np.float64) @ b.astype(np.float64), "dgrad", 1e-5)
+    dw = torch.zeros((n, k), device=DEV)
+    S.sif_k_gemm_f32(DY, 1, n, A, k, 1, dw, k, n, k, m)                                             # dy^T x
+    assert_f32_close(up(dw), dy.astype(np.float64).T @ a.astype(np.float64), "wgrad", 1e-5)
+    S.sif_k_gemm_f32(DY, n, 1, B, k, 1, dx, k, m, k, n, epilogue=S.SIF_EPI_GELU_GRAD, aux=f32(a))
+    assert_f32_close(up(dx), (dy.astype(np.float64) @ b.astype(np.float64)) * N.gelu_grad(a), "gelu grad", 1e-5)
+
+
+# ------------------------------------------------------------------------------------------------ row kernels
+@pytest.mark.parametrize("rows,d", [(1, 8), (37, 768), (130, 2048), (5, 4096)])
+def test_layernorm_fwd_bwd(rows, d):
+    x, g, b, dy, res = rnd(20, rows, d, scale=2.0) + 0.5, rnd(21, d) + 1, rnd(22, d), rnd(23, rows, d), rnd(24, rows, d)
+    X, G, B_, DY, R = bf(x), bf(g), bf(b), bf(dy), bf(res)
+    y = torch.zeros_like(X)
+    mean, rstd = torch.zeros(rows, device=DEV), torch.zeros(rows, device=DEV)
+    S.sif_k_layernorm_fwd(X, G, B_, y, mean, rstd, rows, d)
+    ry, rm, rr = N.layernorm_fwd(q(x), q(g), q(b))
+    assert_bf16_close(up(y), ry, "ln y")
+    assert_f32_close(up(mean), rm[:, 0], "mean", 1e-5)
+    assert_f32_close(up(rstd), rr[:, 0], "rstd", 1e-5)
+    dx, dg, db = torch.zeros_like(X), torch.zeros(d, device=DEV, dtype=torch.bfloat16), torch.zeros(d, device=DEV, dtype=torch.bfloat16)
+    part = torch.zeros(2 * S.sif_colsum_parts(rows) * d, device=DEV)
+    S.sif_k_layernorm_bwd(DY, X, G, mean, rstd, R, dx, dg, db, part, rows, d)
+    rdx, rdg, rdb = N.layernorm_bwd(q(dy), q(x), q(g), rm, rr)
+    assert_bf16_close(up(dx), q(res) + rdx, "ln dx")
+    assert_bf16_close(up(dg), rdg, "ln dg")
+    assert_bf16_close(up(db), rdb, "ln db")
+    S.sif_k_layernorm_bwd(DY, X, G, mean, rstd, None, dx, dg, db, part, rows, d)
+    assert_bf16_close(up(dx), rdx, "ln dx no residual")
+
+
+@pytest.mark.parametrize("rows,n,ld", [(1, 8, 8), (333, 776, 784), (4100, 2304, 2304)])
+def test_colsum(rows, n, ld):
+    x = rnd(25, rows, ld)
+    X = bf(x)
+    out = torch.zeros(n, device=DEV, dtype=torch.bfloat16)
+    part = torch.zeros(S.sif_colsum_parts(rows) * n, device=DEV)
+    S.sif_k_colsum(X, ld, out, part, rows, n)
+    assert_bf16_close(up(out), q(x)[:, :n].sum(axis=0), "colsum")
+
+
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("batch,rows,cols", [(3, 37, 37), (2, 200, 200), (1, 5, 2048), (2, 128, 128)])
+def test_softmax_fwd_bwd(batch, rows, cols, causal):
+    if causal and rows != cols:
+        pytest.skip("causal needs a square problem")
+    ld = (cols + 7) // 8 * 8
+    s = np.zeros((batch, rows, ld), np.float32)
+    s[:, :, :cols] = rnd(26, batch, rows, cols, scale=3.0)
+    Sd = f32(s)
+    p = torch.full((batch, rows, ld), 9.0, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_softmax_fwd(Sd, p, batch, rows, cols, ld, ld, causal)
+    sm = s[:, :, :cols].astype(np.float64)
+    if causal:
+        sm = np.where(np.tril(np.ones((rows, cols), bool)), sm, -np.inf)
+    ref = N.softmax_rows(sm)
+    got = up(p)
+    assert_bf16_close(got[:, :, :cols], ref, "softmax")
+    assert np.all(got[:, :, cols:] == 0)
+    if causal:
+        assert np.all(got[:, :, :cols][:, ~np.tril(np.ones((rows, cols), bool))] == 0)
+    dp = np.zeros((batch, rows, ld), np.float32)
+    dp[:, :, :cols] = rnd(27, batch, rows, cols)
+    ds = torch.full((batch, rows, ld), 9.0, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_softmax_bwd(f32(dp), p, ds, batch, rows, cols, ld, 0.125, causal)
+    pq = got[:, :, :cols]
+    d = dp[:, :, :cols].astype(np.float64)
+    if causal:
+        d = np.where(np.tril(np.ones((rows, cols), bool)), d, 0.0)
+    ref = 0.125 * pq * (d - (d * pq).sum(-1, keepdims=True))
+    assert_bf16_close(up(ds)[:, :, :cols], ref, "softmax bwd")
+    assert np.all(up(ds)[:, :, cols:] == 0)
+
+
+def test_embedding_fwd_bwd():
+    tokens, seq, d, vocab = 96, 24, 64, 17          # small vocabulary: many repeated ids
+    ids = np.random.default_rng(28).integers(0, vocab, tokens).astype(np.int32)
+    wte, wpe, dx = rnd(29, vocab, d), rnd(30, seq, d), rnd(31, tokens, d)
+    I, WTE, WPE, DX = i32(ids), bf(wte), bf(wpe), bf(dx)
+    x = torch.zeros((tokens, d), device=DEV, dtype=torch.bfloat16)
+    S.sif_k_embed_fwd(I, WTE, WPE, x, tokens, seq, d)
+    assert_bf16_close(up(x), q(wte)[ids] + q(wpe)[np.arange(tokens) % seq], "embed")
+    head = rnd(32, vocab, d)
+    dwte, dwpe = bf(head), torch.zeros((seq, d), device=DEV, dtype=torch.bfloat16)
+    S.sif_k_embed_bwd(I, DX, dwte, dwpe, tokens, seq, d)
+    scat = np.zeros((vocab, d))
+    np.add.at(scat, ids, q(dx))
+    assert_bf16_close(up(dwte), q(head) + scat, "dwte")
+    assert_bf16_close(up(dwpe), q(dx).reshape(-1, seq, d).sum(0), "dwpe")
+    again = bf(head)
+    S.sif_k_embed_bwd(I, DX, again, dwpe, tokens, seq, d)
+    assert torch.equal(again, dwte)                 # fixed summation order
+
+
+@pytest.mark.parametrize("tokens,vocab", [(5, 37), (64, 50257), (3, 8)])
+def test_cross_entropy(tokens, vocab):
+    ld = (vocab + 7) // 8 * 8
+    lg = np.zeros((tokens, ld), np.float32)
+    lg[:, :vocab] = rnd(33, tokens, vocab, scale=2.0)
+    lg[:, vocab:] = 50.0                            # padding must be ignored
+    tg = np.random.default_rng(34).integers(0, vocab, tokens).astype(np.int32)
+    L = bf(lg)
+    loss = torch.zeros(tokens, device=DEV)
+    S.sif_k_xent_fwd_bwd(L, i32(tg), loss, tokens, vocab, ld)
+    rl, rd = N.cross_entropy_mean(q(lg)[:, :vocab], tg)
+    out = torch.zeros(1, device=DEV)
+    S.sif_k_reduce_sum(loss, out, tokens, 1.0 / tokens)
+    assert abs(out.item() - rl) <= 1e-4 * abs(rl)
+    got = up(L)
+    assert_bf16_close(got[:, :vocab], rd, "dlogits", elem_slack=1e-3)
+    assert np.all(got[:, vocab:] == 0)
+
+
+def test_sgd_and_mse_and_colsum_f32():
+    n = 8 * 1000 + 5
+    m, g = rnd(35, n), rnd(36, n)
+    M, G = f32(m), bf(g)
+    W = torch.zeros(n, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_sgd_bf16(M, None, W, n, 0.0)
+    assert np.array_equal(up(W), q(m)) and np.array_equal(up(M), m.astype(np.float64))
+    S.sif_k_sgd_bf16(M, G, W, n, 0.01)
+    ref = m.astype(np.float64) - 0.01 * q(g)
+    assert_f32_close(up(M), ref, "sgd master", 1e-6)
+    assert np.array_equal(up(W), q(up(M)))
+    P_, G2 = f32(m), f32(g)
+    S.sif_k_sgd_f32(P_, G2, n, 0.01)
+    assert_f32_close(up(P_), m.astype(np.float64) - 0.01 * g.astype(np.float64), "sgd f32", 1e-6)
+    y, t = rnd(37, 32, 256), rnd(38, 32, 256)
+    d, loss = torch.zeros(32 * 256, device=DEV), torch.zeros(1, device=DEV)
+    S.sif_k_mse_fwd_bwd(f32(y), f32(t), d, loss, 32 * 256)
+    e = y.astype(np.float64) - t
+    assert abs(loss.item() - 0.5 * (e ** 2).mean()) < 1e-5
+    assert_f32_close(up(d).reshape(32, 256), e / e.size, "mse grad", 1e-6)
+    cs = torch.zeros(256, device=DEV)
+    S.sif_k_colsum_f32(f32(y), 256, cs, 32, 256)
+    assert_f32_close(up(cs), y.astype(np.float64).sum(0), "colsum f32", 1e-5)
