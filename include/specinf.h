@@ -243,6 +243,9 @@ sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_str
                       uint64_t workspace_bytes, sif_ctx** out);
 /* Stops the threads, cancels pending tickets (SIF_E_CANCELLED), synchronises both streams. */
 sif_status sif_destroy(sif_ctx* ctx);
+/* on = 0: the barrier releases nothing while a training instance is registered (solo training, or the
+ * "collocated but no requests served" overhead run of Sec. 5.4); on = 1: normal operation. */
+sif_status sif_set_collocate(sif_ctx* ctx, uint32_t on);
 
 enum { SIF_MODEL_MLP = 0, SIF_MODEL_DECODER = 1, SIF_MODEL_ENCODER = 2 };
 enum { SIF_PAR_NONE = 0, SIF_PAR_FIXED = 1, SIF_PAR_DP = 2, SIF_PAR_PP = 3, SIF_PAR_TP = 4 };

@@ -265,3 +265,137 @@ def sif_k_mse_fwd_bwd(y, t, d, loss, n, stream=None):
 
 def sif_k_colsum_f32(x, ld, out, rows, n, stream=None):
     return check(lib.sif_k_colsum_f32(ptr(x), ld, ptr(out), rows, n, stream_ptr(stream)))
+
+
+# ---- runtime ----------------------------------------------------------------------------------------------
+_sig("sif_now_ns", u64)
+_sig("sif_default_config", i32, P(sif_config))
+_sig("sif_ctx_workspace_bytes", u64)
+_sig("sif_create", i32, P(sif_config), vp, vp, vp, u64, P(vp))
+_sig("sif_destroy", i32, vp)
+_sig("sif_set_collocate", i32, vp, u32)
+_sig("sif_model_n_params", u64, P(sif_model_shape))
+_sig("sif_train_workspace_bytes", u64, P(sif_train_desc))
+_sig("sif_register_training_step", i32, vp, P(sif_train_desc), P(i32))
+_sig("sif_run_training_step", i32, vp, i32, vp, vp, vp)
+_sig("sif_sync_training", i32, vp)
+_sig("sif_train_tensor", i32, vp, i32, C.c_char_p, i32, P(vp), P(u64))
+_sig("sif_infer_workspace_bytes", u64, P(sif_infer_desc))
+_sig("sif_register_inference_model", i32, vp, P(sif_infer_desc), P(i32))
+_sig("sif_calibrate", i32, vp, u32, vp, vp)
+_sig("sif_submit_offline_batch", i32, vp, i32, vp, vp, u32, u32, P(u64))
+_sig("sif_submit_online_request", i32, vp, i32, vp, vp, u32, u64, P(u64))
+_sig("sif_wait", i32, vp, u64, u64)
+_sig("sif_poll_stats", i32, vp, P(sif_stats))
+_sig("sif_reset_stats", i32, vp)
+_sig("sif_read_trace", i32, vp, u32, P(sif_trace_rec), u32, P(u32))
+
+
+def sif_now_ns():
+    return lib.sif_now_ns()
+
+
+def sif_default_config():
+    cfg = sif_config()
+    check(lib.sif_default_config(C.byref(cfg)))
+    return cfg
+
+
+def sif_ctx_workspace_bytes():
+    return lib.sif_ctx_workspace_bytes()
+
+
+def sif_create(cfg, train_stream, infer_stream, workspace, workspace_bytes):
+    out = vp()
+    check(lib.sif_create(C.byref(cfg), stream_ptr(train_stream), stream_ptr(infer_stream), ptr(workspace), workspace_bytes,
+                         C.byref(out)))
+    return out
+
+
+def sif_destroy(ctx):
+    return check(lib.sif_destroy(ctx))
+
+
+def sif_set_collocate(ctx, on):
+    return check(lib.sif_set_collocate(ctx, 1 if on else 0))
+
+
+def sif_model_n_params(shape):
+    return lib.sif_model_n_params(C.byref(shape))
+
+
+def sif_train_workspace_bytes(desc):
+    n = lib.sif_train_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise SifError(SIF_E_INVAL, last_error())
+    return n
+
+
+def sif_register_training_step(ctx, desc):
+    h = i32(-1)
+    check(lib.sif_register_training_step(ctx, C.byref(desc), C.byref(h)))
+    return h.value
+
+
+def sif_run_training_step(ctx, h, inputs, targets, loss=None):
+    return check(lib.sif_run_training_step(ctx, h, ptr(inputs), ptr(targets), ptr(loss)))
+
+
+def sif_sync_training(ctx):
+    return check(lib.sif_sync_training(ctx))
+
+
+def sif_train_tensor(ctx, h, name, layer=0):
+    """Returns (device address, element count)."""
+    p, n = vp(), u64(0)
+    check(lib.sif_train_tensor(ctx, h, name.encode(), layer, C.byref(p), C.byref(n)))
+    return p.value, n.value
+
+
+def sif_infer_workspace_bytes(desc):
+    return lib.sif_infer_workspace_bytes(C.byref(desc))
+
+
+def sif_register_inference_model(ctx, desc):
+    h = i32(-1)
+    check(lib.sif_register_inference_model(ctx, C.byref(desc), C.byref(h)))
+    return h.value
+
+
+def sif_calibrate(ctx, iters, train_inputs=None, train_targets=None):
+    return check(lib.sif_calibrate(ctx, iters, ptr(train_inputs), ptr(train_targets)))
+
+
+def sif_submit_offline_batch(ctx, model, inp, out, batch, seq):
+    t = u64(0)
+    check(lib.sif_submit_offline_batch(ctx, model, ptr(inp), ptr(out), batch, seq, C.byref(t)))
+    return t.value
+
+
+def sif_submit_online_request(ctx, model, inp, out, seq, t_arrival_ns=0):
+    t = u64(0)
+    check(lib.sif_submit_online_request(ctx, model, ptr(inp), ptr(out), seq, t_arrival_ns, C.byref(t)))
+    return t.value
+
+
+def sif_wait(ctx, ticket, timeout_ns=10_000_000_000):
+    return check(lib.sif_wait(ctx, ticket, timeout_ns))
+
+
+def sif_poll_stats(ctx):
+    s = sif_stats()
+    s.struct_size = C.sizeof(sif_stats)
+    check(lib.sif_poll_stats(ctx, C.byref(s)))
+    return s
+
+
+def sif_reset_stats(ctx):
+    return check(lib.sif_reset_stats(ctx))
+
+
+def sif_read_trace(ctx, which, cap=65535):
+    """Returns a list of (kind, id, decision, launch number, t0_ns, t1_ns), oldest first."""
+    arr = (sif_trace_rec * cap)()
+    n = u32(0)
+    check(lib.sif_read_trace(ctx, which, arr, cap, C.byref(n)))
+    return [(arr[i].kind, arr[i].id, arr[i].decision, arr[i].reserved, arr[i].t0_ns, arr[i].t1_ns) for i in range(n.value)]

@@ -1,0 +1,92 @@
+// Marker kernels of the training stream: the modelled bubble (a timed wait that occupies one wavefront and no
+// other compute resource), step begin/end stamps, and the poison reset of the inference stream.
+//
+// A bubble stands for the wait on a collective of the distributed training job (Sec. 2.1: communication leaves
+// the GPU idle).  On entry the kernel stamps the time and then declares the stream idle; on exit it declares the
+// stream busy and then stamps the time, so an inference kernel that saw "idle" before and after stamping its own
+// start time started strictly inside the stamped interval.  The wait always ends: either the host releases it,
+// or the device deadline passes.
+#include "common.h"
+#include "launch.h"
+#include "runtime.h"
+
+namespace sif {
+
+__global__ __launch_bounds__(64) void bubble_kernel(StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site,
+                                                    uint64_t ticks, uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
+  if (threadIdx.x != 0) return;
+  const uint64_t t0 = now_ticks();
+  st_agent(&rec->seq, seq);
+  st_agent(&rec->site, site);
+  st_agent(&rec->t_idle_begin, t0);
+  st_agent(&rec->t_expected_end, t0 + ticks);
+  st_agent(&rec->state, kStateIdle);
+  st_sys(&mir->idle_site, site);
+  st_sys(&mir->idle_seq, seq);
+  const uint64_t deadline = t0 + (device_timed ? ticks : max_ticks);
+  while (now_ticks() < deadline) {
+    if (!device_timed && ld_sys(&mir->release_seq) >= seq) break;
+    __builtin_amdgcn_s_sleep(64);
+  }
+  st_agent(&rec->state, kStateBusy);
+  const uint64_t t1 = now_ticks();
+  st_agent(&rec->t_busy_begin, t1);
+  rec->bubble_ticks += t1 - t0;
+  st_sys(&mir->bubble_ticks, rec->bubble_ticks);
+  st_sys(&mir->busy_seq, seq);
+  slot->kind_id = kind_id;
+  slot->decision = 1;
+  slot->t0 = t0;
+  slot->t1 = t1;
+}
+
+__global__ __launch_bounds__(64) void step_marker_kernel(StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id) {
+  if (threadIdx.x != 0) return;
+  const uint64_t t = now_ticks();
+  if (!end) {
+    rec->step_t0 = t;
+    st_agent(&rec->state, kStateBusy);
+    slot->kind_id = 0;      // the begin marker leaves no trace record of its own
+    slot->decision = 0;
+    slot->t0 = t;
+    slot->t1 = t;
+    return;
+  }
+  const uint64_t dt = t - rec->step_t0;
+  rec->steps += 1;
+  rec->step_ticks_sum += dt;
+  rec->step_ticks_last = dt;
+  st_sys(&mir->step_ticks_last, dt);
+  st_sys(&mir->step_ticks_sum, rec->step_ticks_sum);
+  st_sys(&mir->steps, rec->steps);
+  slot->kind_id = kind_id;
+  slot->decision = 1;
+  slot->t0 = rec->step_t0;
+  slot->t1 = t;
+}
+
+// Clears the poison of the inference stream after the host has taken note of the first skipped launch.
+__global__ __launch_bounds__(64) void reset_skip_kernel(StreamRec* rec, Mirror* mir, uint32_t epoch) {
+  if (threadIdx.x != 0) return;
+  st_agent(&rec->skip_from, kNone);
+  st_sys(&mir->i_skip_from, kNone);
+  st_sys(&mir->i_reset_ack, epoch);
+}
+
+sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,
+                         uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
+  hipLaunchKernelGGL(bubble_kernel, dim3(1), dim3(64), 0, s, rec, mir, slot, seq, site, ticks, max_ticks, device_timed, kind_id);
+  return check_launch("bubble");
+}
+
+sif_status launch_step_marker(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id) {
+  hipLaunchKernelGGL(step_marker_kernel, dim3(1), dim3(64), 0, s, rec, mir, slot, end, kind_id);
+  return check_launch("step_marker");
+}
+
+sif_status launch_reset_skip(hipStream_t s, StreamRec* rec, Mirror* mir, uint32_t epoch) {
+  hipLaunchKernelGGL(reset_skip_kernel, dim3(1), dim3(64), 0, s, rec, mir, epoch);
+  return check_launch("reset_skip");
+}
+
+}  // namespace sif

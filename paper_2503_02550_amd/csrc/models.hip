@@ -1,0 +1,531 @@
+// Kernel plans of the registered models: which kernels one training step (forward, loss, backward, optimizer,
+// with the modelled bubbles at their sites) and one inference forward pass consist of, and where their tensors
+// live inside the caller's workspace.  The paper schedules the kernels of named transformer models (Sec. 5.1
+// "Workloads"); these are the textbook blocks of those models at the benchmark shapes:
+//   training  : two-Linear fp32 MLP, or a pre-LN GPT-style decoder (optionally with embedding + tied LM head)
+//   inference : the same MLP forward, or a post-LN BERT-shaped encoder forward
+// Attention materialises the score matrix per (batch, head) with the batched GEMM; every reduction has a fixed
+// order, so a plan gives bit-identical results whenever and next to whatever it runs.
+#include <math.h>
+#include <string.h>
+
+#include "common.h"
+#include "runtime.h"
+
+namespace sif {
+
+// ------------------------------------------------------------------------------------------ parameter layout
+struct ParamMap {
+  std::unordered_map<std::string, uint64_t> off;
+  uint64_t n = 0;
+  void add(const std::string& k, uint64_t elems) { off[k] = n; n += elems; }
+  uint64_t at(const std::string& k) const { return off.at(k); }
+};
+
+static std::string L(uint32_t l, const char* k) { return "L" + std::to_string(l) + "." + k; }
+
+static ParamMap param_map(const sif_model_shape& s) {
+  ParamMap m;
+  const uint64_t d = s.d_model, da = (uint64_t)s.n_heads * s.d_head, f = s.d_ffn;
+  if (s.kind == SIF_MODEL_MLP) {
+    m.add("w1", (uint64_t)s.d_hidden * s.d_in); m.add("b1", s.d_hidden);
+    m.add("w2", (uint64_t)s.d_out * s.d_hidden); m.add("b2", s.d_out);
+  } else if (s.kind == SIF_MODEL_DECODER) {
+    if (s.vocab) { m.add("wte", (uint64_t)s.vocab * d); m.add("wpe", (uint64_t)s.max_pos * d); }
+    for (uint32_t l = 0; l < s.n_layers; ++l) {
+      m.add(L(l, "ln1_g"), d); m.add(L(l, "ln1_b"), d); m.add(L(l, "w_qkv"), 3 * da * d); m.add(L(l, "b_qkv"), 3 * da);
+      m.add(L(l, "w_o"), d * da); m.add(L(l, "b_o"), d); m.add(L(l, "ln2_g"), d); m.add(L(l, "ln2_b"), d);
+      m.add(L(l, "w_fc"), f * d); m.add(L(l, "b_fc"), f); m.add(L(l, "w_proj"), d * f); m.add(L(l, "b_proj"), d);
+    }
+    if (s.vocab) { m.add("lnf_g", d); m.add("lnf_b", d); }
+  } else if (s.kind == SIF_MODEL_ENCODER) {
+    m.add("wte", (uint64_t)s.vocab * d); m.add("wpe", (uint64_t)s.max_pos * d); m.add("emb_ln_g", d); m.add("emb_ln_b", d);
+    for (uint32_t l = 0; l < s.n_layers; ++l) {
+      m.add(L(l, "w_qkv"), 3 * da * d); m.add(L(l, "b_qkv"), 3 * da); m.add(L(l, "w_o"), d * da); m.add(L(l, "b_o"), d);
+      m.add(L(l, "ln1_g"), d); m.add(L(l, "ln1_b"), d); m.add(L(l, "w_fc"), f * d); m.add(L(l, "b_fc"), f);
+      m.add(L(l, "w_proj"), d * f); m.add(L(l, "b_proj"), d); m.add(L(l, "ln2_g"), d); m.add(L(l, "ln2_b"), d);
+    }
+  }
+  return m;
+}
+
+uint64_t model_n_params(const sif_model_shape& s) { return param_map(s).n; }
+
+static sif_status check_shape(const sif_model_shape& s, bool training) {
+  if (s.kind == SIF_MODEL_MLP) {
+    if (s.dtype != SIF_F32) return fail(SIF_E_INVAL, "MLP models are fp32");
+    if (!s.d_in || !s.d_hidden || !s.d_out || !s.batch) return fail(SIF_E_INVAL, "MLP: empty dimension");
+    return SIF_OK;
+  }
+  if (s.kind != SIF_MODEL_DECODER && s.kind != SIF_MODEL_ENCODER) return fail(SIF_E_INVAL, "unknown model kind");
+  if (s.dtype != SIF_BF16) return fail(SIF_E_INVAL, "transformer models are bf16");
+  if (!s.n_layers || !s.d_model || !s.n_heads || !s.d_head || !s.d_ffn || !s.batch || !s.seq) return fail(SIF_E_INVAL, "transformer: empty dimension");
+  if ((s.d_model | s.d_head | s.d_ffn) & 7) return fail(SIF_E_INVAL, "d_model, d_head and d_ffn must be multiples of 8");
+  if (s.d_model > 4096) return fail(SIF_E_INVAL, "d_model must be <= 4096");
+  if (s.seq > 2048) return fail(SIF_E_INVAL, "seq must be <= 2048");
+  if (s.kind == SIF_MODEL_ENCODER && (!s.vocab || !s.max_pos)) return fail(SIF_E_INVAL, "encoder needs vocab and max_pos");
+  if (s.vocab && s.max_pos < s.seq) return fail(SIF_E_INVAL, "max_pos must be >= seq");
+  if (training && ((s.batch * s.seq) & 7)) return fail(SIF_E_INVAL, "training needs batch*seq to be a multiple of 8");
+  return SIF_OK;
+}
+
+// ------------------------------------------------------------------------------------------ op builders
+struct G {
+  sif_gemm_args a;
+  G(const void* A, const void* B, void* C, uint32_t m, uint32_t n, uint32_t k, uint32_t lda, uint32_t ldb, uint32_t ldc) {
+    memset(&a, 0, sizeof(a));
+    a.struct_size = sizeof(a);
+    a.a_dev = A; a.b_dev = B; a.c_dev = C; a.m = m; a.n = n; a.k = k; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.batch_outer = a.batch_inner = 1; a.alpha = 1.0f;
+  }
+  G& lay(uint32_t al, uint32_t bl) { a.a_layout = al; a.b_layout = bl; return *this; }
+  G& epi(uint32_t e, const void* bias = nullptr, const void* res = nullptr, void* aux = nullptr) {
+    a.epilogue = e; a.bias_dev = bias; a.res_dev = res; a.aux_dev = aux; return *this;
+  }
+  G& batch(uint32_t bo, uint32_t bi, int64_t aso, int64_t asi, int64_t bso, int64_t bsi, int64_t cso, int64_t csi) {
+    a.batch_outer = bo; a.batch_inner = bi; a.a_stride_outer = aso; a.a_stride_inner = asi; a.b_stride_outer = bso;
+    a.b_stride_inner = bsi; a.c_stride_outer = cso; a.c_stride_inner = csi; return *this;
+  }
+  G& alpha(float v) { a.alpha = v; return *this; }
+  G& causal(uint32_t kc) { a.k_causal = kc; return *this; }
+};
+
+static double gemm_cost_us(const sif_gemm_args& g) {
+  double flops = 2.0 * g.m * g.n * g.k * g.batch_outer * g.batch_inner;
+  if (g.k_causal || (g.epilogue & SIF_EPI_CAUSAL_SKIP)) flops *= 0.55;
+  return 4.0 + flops / 3.0e8;          // 300 TFLOP/s plus launch latency
+}
+static double bytes_cost_us(double bytes) { return 3.0 + bytes / 2.0e6; }   // 2 TB/s plus launch latency
+
+static void emit_gemm(Plan& p, const char* name, const G& g) {
+  Op op;
+  op.name = name;
+  const sif_gemm_args a = g.a;
+  op.fn = [a](hipStream_t s, const KCtl& c) { return launch_gemm_bf16(&a, s, c); };
+  op.cost_us = gemm_cost_us(a);
+  p.push_back(std::move(op));
+}
+
+// A GEMM whose rows are independent (A [M][K] row-major, C [M][N]) split into row ranges of at most
+// `rows_per` rows (a multiple of the 128-row tile), so that no single launch exceeds the kernel time limit.
+static void emit_gemm_rows(Plan& p, const char* name, const G& g, uint32_t kernel_us_max) {
+  const double cost = gemm_cost_us(g.a);
+  if (kernel_us_max == 0 || cost <= kernel_us_max || g.a.a_layout != SIF_A_ROW_K || g.a.batch_outer * g.a.batch_inner != 1 || g.a.m <= 128) {
+    emit_gemm(p, name, g);
+    return;
+  }
+  uint32_t pieces = (uint32_t)ceil(cost / kernel_us_max);
+  uint32_t rows_per = ((g.a.m + pieces - 1) / pieces + 127) / 128 * 128;
+  for (uint32_t r0 = 0; r0 < g.a.m; r0 += rows_per) {
+    G part = g;
+    const uint32_t rows = (g.a.m - r0 < rows_per) ? g.a.m - r0 : rows_per;
+    const size_t csz = (g.a.epilogue & SIF_EPI_OUT_F32) ? 4 : 2;
+    part.a.m = rows;
+    part.a.a_dev = (const bf16_t*)g.a.a_dev + (size_t)r0 * g.a.lda;
+    part.a.c_dev = (unsigned char*)g.a.c_dev + (size_t)r0 * g.a.ldc * csz;
+    if (g.a.res_dev) part.a.res_dev = (const unsigned char*)g.a.res_dev + (size_t)r0 * g.a.ldc * csz;
+    if (g.a.aux_dev) part.a.aux_dev = (bf16_t*)g.a.aux_dev + (size_t)r0 * g.a.ldc;
+    emit_gemm(p, name, part);
+  }
+}
+
+static void emit(Plan& p, const char* name, double cost_us, std::function<sif_status(hipStream_t, const KCtl&)> fn) {
+  Op op;
+  op.name = name; op.cost_us = cost_us; op.fn = std::move(fn);
+  p.push_back(std::move(op));
+}
+
+static void emit_bubble(Plan& p, int32_t site, uint64_t ns) {
+  Op op;
+  op.name = "bubble"; op.bubble_site = site; op.bubble_ns = ns; op.cost_us = ns / 1000.0;
+  p.push_back(std::move(op));
+}
+
+static void emit_colsum(Plan& p, const char* name, const void* x, uint32_t ld, void* out, float* part, uint32_t rows, uint32_t n) {
+  emit(p, name, bytes_cost_us(2.0 * rows * n), [=](hipStream_t s, const KCtl& c) { return launch_colsum_part(x, ld, part, rows, n, s, c); });
+  emit(p, name, 3.0, [=](hipStream_t s, const KCtl& c) { return launch_colsum_fin(part, out, rows, n, s, c); });
+}
+
+static void emit_ln_bwd(Plan& p, const void* dy, const void* x, const void* g, const float* mean, const float* rstd, const void* res,
+                        void* dx, void* dg, void* db, float* part, uint32_t rows, uint32_t d) {
+  emit(p, "ln_bwd", bytes_cost_us(8.0 * rows * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, s, c); });
+  emit(p, "ln_bwd_fin", 3.0, [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_fin(part, dg, db, rows, d, s, c); });
+}
+
+// ------------------------------------------------------------------------------------------ transformer block
+struct Dims { uint32_t B, S, M, d, H, dh, da, f, Sp; };
+
+static Dims dims_of(const sif_model_shape& s, uint32_t batch, uint32_t seq) {
+  Dims q;
+  q.B = batch; q.S = seq; q.M = batch * seq; q.d = s.d_model; q.H = s.n_heads; q.dh = s.d_head; q.da = s.n_heads * s.d_head;
+  q.f = s.d_ffn; q.Sp = (seq + 7) & ~7u;
+  return q;
+}
+
+// Attention for all (batch, head) pairs: scores (fp32) = scale q k^T, prob = softmax, o = prob v.
+static void emit_attention_fwd(Plan& p, const Dims& q, const bf16_t* qkv, float* scores, bf16_t* prob, bf16_t* o, bool causal) {
+  const int64_t ss = (int64_t)q.S * q.Sp;
+  const float scale = 1.0f / sqrtf((float)q.dh);
+  emit_gemm(p, "attn_scores", G(qkv, qkv + q.da, scores, q.S, q.S, q.dh, 3 * q.da, 3 * q.da, q.Sp)
+                                  .epi(SIF_EPI_OUT_F32 | (causal ? SIF_EPI_CAUSAL_SKIP : 0)).alpha(scale)
+                                  .batch(q.B, q.H, (int64_t)q.S * 3 * q.da, q.dh, (int64_t)q.S * 3 * q.da, q.dh, q.H * ss, ss));
+  const uint32_t bh = q.B * q.H, S = q.S, Sp = q.Sp, c = causal ? 1 : 0;
+  emit(p, "attn_softmax", bytes_cost_us(6.0 * bh * S * Sp * (causal ? 0.5 : 1.0)),
+       [=](hipStream_t s, const KCtl& k) { return launch_softmax_fwd(scores, prob, bh, S, S, Sp, Sp, c, s, k); });
+  emit_gemm(p, "attn_pv", G(prob, qkv + 2 * q.da, o, q.S, q.dh, q.S, q.Sp, 3 * q.da, q.da).lay(SIF_A_ROW_K, SIF_B_ROW_N)
+                              .causal(causal ? 1 : 0)
+                              .batch(q.B, q.H, q.H * ss, ss, (int64_t)q.S * 3 * q.da, q.dh, (int64_t)q.S * q.da, q.dh));
+}
+
+// dqkv from do, the saved probabilities and qkv.  dp (fp32) and ds (bf16) are scratch [B*H][S][Sp].
+static void emit_attention_bwd(Plan& p, const Dims& q, const bf16_t* qkv, const bf16_t* prob, const bf16_t* d_o, float* dp, bf16_t* ds,
+                               bf16_t* dqkv) {
+  const int64_t ss = (int64_t)q.S * q.Sp, row3 = (int64_t)q.S * 3 * q.da, row1 = (int64_t)q.S * q.da;
+  const float scale = 1.0f / sqrtf((float)q.dh);
+  emit_gemm(p, "attn_dv", G(prob, d_o, dqkv + 2 * q.da, q.S, q.dh, q.S, q.Sp, q.da, 3 * q.da).lay(SIF_A_ROW_M, SIF_B_ROW_N).causal(2)
+                              .batch(q.B, q.H, q.H * ss, ss, row1, q.dh, row3, q.dh));
+  emit_gemm(p, "attn_dp", G(d_o, qkv + 2 * q.da, dp, q.S, q.S, q.dh, q.da, 3 * q.da, q.Sp).epi(SIF_EPI_OUT_F32 | SIF_EPI_CAUSAL_SKIP)
+                              .batch(q.B, q.H, row1, q.dh, row3, q.dh, q.H * ss, ss));
+  const uint32_t bh = q.B * q.H, S = q.S, Sp = q.Sp;
+  emit(p, "attn_softmax_bwd", bytes_cost_us(4.0 * bh * S * Sp),
+       [=](hipStream_t s, const KCtl& k) { return launch_softmax_bwd(dp, prob, ds, bh, S, S, Sp, scale, 1, s, k); });
+  emit_gemm(p, "attn_dq", G(ds, qkv + q.da, dqkv, q.S, q.dh, q.S, q.Sp, 3 * q.da, 3 * q.da).lay(SIF_A_ROW_K, SIF_B_ROW_N).causal(1)
+                              .batch(q.B, q.H, q.H * ss, ss, row3, q.dh, row3, q.dh));
+  emit_gemm(p, "attn_dk", G(ds, qkv, dqkv + q.da, q.S, q.dh, q.S, q.Sp, 3 * q.da, 3 * q.da).lay(SIF_A_ROW_M, SIF_B_ROW_N).causal(2)
+                              .batch(q.B, q.H, q.H * ss, ss, row3, q.dh, row3, q.dh));
+}
+
+struct LayerActs {       // saved by the forward pass of one decoder layer
+  bf16_t *ln1, *qkv, *prob, *o, *x_mid, *ln2, *z, *a, *x_out;
+  float *m1, *r1, *m2, *r2;
+};
+struct LayerW { const bf16_t *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_fc, *b_fc, *w_proj, *b_proj; };
+struct LayerG { bf16_t *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_fc, *b_fc, *w_proj, *b_proj; };
+struct Scratch { float* scores; bf16_t* ds; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; float* part; };
+
+template <typename T, typename P>
+static T layer_ptrs(P* base, const ParamMap& pm, uint32_t l) {
+  T w;
+  w.ln1_g = base + pm.at(L(l, "ln1_g")); w.ln1_b = base + pm.at(L(l, "ln1_b")); w.w_qkv = base + pm.at(L(l, "w_qkv"));
+  w.b_qkv = base + pm.at(L(l, "b_qkv")); w.w_o = base + pm.at(L(l, "w_o")); w.b_o = base + pm.at(L(l, "b_o"));
+  w.ln2_g = base + pm.at(L(l, "ln2_g")); w.ln2_b = base + pm.at(L(l, "ln2_b")); w.w_fc = base + pm.at(L(l, "w_fc"));
+  w.b_fc = base + pm.at(L(l, "b_fc")); w.w_proj = base + pm.at(L(l, "w_proj")); w.b_proj = base + pm.at(L(l, "b_proj"));
+  return w;
+}
+
+struct TpSites { bool on; uint64_t ns; int32_t* next; };
+
+static void emit_decoder_layer_fwd(Plan& p, const Dims& q, const LayerW& w, const bf16_t* x_in, const LayerActs& a, const Scratch& sc,
+                                   const TpSites& tp) {
+  const uint32_t M = q.M, d = q.d;
+  emit(p, "ln1", bytes_cost_us(4.0 * M * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_fwd(x_in, w.ln1_g, w.ln1_b, a.ln1, a.m1, a.r1, M, d, s, c); });
+  emit_gemm(p, "qkv", G(a.ln1, w.w_qkv, a.qkv, M, 3 * q.da, d, d, d, 3 * q.da).epi(SIF_EPI_BIAS, w.b_qkv));
+  emit_attention_fwd(p, q, a.qkv, sc.scores, a.prob, a.o, true);
+  emit_gemm(p, "attn_out", G(a.o, w.w_o, a.x_mid, M, d, q.da, q.da, q.da, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, w.b_o, x_in));
+  if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
+  emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_fwd(a.x_mid, w.ln2_g, w.ln2_b, a.ln2, a.m2, a.r2, M, d, s, c); });
+  emit_gemm(p, "mlp_up", G(a.ln2, w.w_fc, a.a, M, q.f, d, d, d, q.f).epi(SIF_EPI_GELU, w.b_fc, nullptr, a.z));
+  emit_gemm(p, "mlp_down", G(a.a, w.w_proj, a.x_out, M, d, q.f, q.f, q.f, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, w.b_proj, a.x_mid));
+  if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
+}
+
+// dx_out -> dx_in (both bf16 [M,d]); gradients of the layer's parameters into g.  `tmp` is a second [M,d] buffer.
+static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, const LayerG& g, const bf16_t* x_in, const LayerActs& a,
+                                   const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp) {
+  const uint32_t M = q.M, d = q.d, f = q.f, da = q.da;
+  emit_colsum(p, "db_proj", dx_out, d, g.b_proj, sc.part, M, d);
+  emit_gemm(p, "dw_proj", G(dx_out, a.a, g.w_proj, d, f, M, d, f, f).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_gemm(p, "dz", G(dx_out, w.w_proj, sc.dz, M, f, d, d, f, f).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_GELU_GRAD, nullptr, nullptr, a.z));
+  emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, sc.part, M, f);
+  emit_gemm(p, "dw_fc", G(sc.dz, a.ln2, g.w_fc, f, d, M, f, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_gemm(p, "dln2", G(sc.dz, w.w_fc, sc.dln, M, d, f, f, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+  if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
+  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, sc.part, M, d);
+  emit_colsum(p, "db_o", dx_mid, d, g.b_o, sc.part, M, d);
+  emit_gemm(p, "dw_o", G(dx_mid, a.o, g.w_o, d, da, M, d, da, da).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_gemm(p, "do", G(dx_mid, w.w_o, sc.d_o, M, da, d, d, da, da).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+  emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
+  emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, sc.part, M, 3 * da);
+  emit_gemm(p, "dw_qkv", G(sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, 3 * da, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_gemm(p, "dln1", G(sc.dqkv, w.w_qkv, sc.dln, M, d, 3 * da, 3 * da, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+  if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
+  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, sc.part, M, d);
+}
+
+// ------------------------------------------------------------------------------------------ training models
+static void put(TrainModel& tm, const std::string& name, void* p, uint64_t elems) { tm.tensors[name] = NamedTensor{p, elems}; }
+
+static sif_status build_mlp_train(TrainModel& tm, Arena& ar) {
+  const sif_model_shape& s = tm.desc.shape;
+  const ParamMap pm = param_map(s);
+  const uint32_t B = s.batch, di = s.d_in, dh = s.d_hidden, dout = s.d_out;
+  float* W = tm.desc.master_dev;
+  float* grads = (float*)ar.take(pm.n * 4);
+  float* z = (float*)ar.take((uint64_t)B * dh * 4);
+  float* h = (float*)ar.take((uint64_t)B * dh * 4);
+  float* y = (float*)ar.take((uint64_t)B * dout * 4);
+  float* dy = (float*)ar.take((uint64_t)B * dout * 4);
+  float* dz = (float*)ar.take((uint64_t)B * dh * 4);
+  float* loss = (float*)ar.take(256);
+  tm.workspace_bytes = ar.off;
+  if (!ar.base) return SIF_OK;
+  put(tm, "work", W, pm.n); put(tm, "grads", grads, pm.n); put(tm, "z", z, (uint64_t)B * dh); put(tm, "a", h, (uint64_t)B * dh);
+  put(tm, "y", y, (uint64_t)B * dout); put(tm, "loss", loss, 1);
+  float *w1 = W + pm.at("w1"), *b1 = W + pm.at("b1"), *w2 = W + pm.at("w2"), *b2 = W + pm.at("b2");
+  float *gw1 = grads + pm.at("w1"), *gb1 = grads + pm.at("b1"), *gw2 = grads + pm.at("w2"), *gb2 = grads + pm.at("b2");
+  TrainModel* t = &tm;
+  Plan& p = tm.plan;
+  emit(p, "fc1", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32((const float*)t->cur_inputs, di, 1, w1, 1, di, h, dh, B, dh, di, SIF_EPI_GELU, b1, z, st, c); });
+  emit(p, "fc2", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(h, dh, 1, w2, 1, dh, y, dout, B, dout, dh, SIF_EPI_BIAS, b2, nullptr, st, c); });
+  emit(p, "mse", 4, [=](hipStream_t st, const KCtl& c) { return launch_mse(y, (const float*)t->cur_targets, dy, t->cur_loss ? t->cur_loss : loss, B * dout, st, c); });
+  emit(p, "dw2", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(dy, 1, dout, h, dh, 1, gw2, dh, dout, dh, B, 0, nullptr, nullptr, st, c); });
+  emit(p, "db2", 4, [=](hipStream_t st, const KCtl& c) { return launch_colsum_f32(dy, dout, gb2, B, dout, st, c); });
+  emit(p, "dz", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(dy, dout, 1, w2, dh, 1, dz, dh, B, dh, dout, SIF_EPI_GELU_GRAD, nullptr, z, st, c); });
+  emit(p, "dw1", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(dz, 1, dh, (const float*)t->cur_inputs, di, 1, gw1, di, dh, di, B, 0, nullptr, nullptr, st, c); });
+  emit(p, "db1", 4, [=](hipStream_t st, const KCtl& c) { return launch_colsum_f32(dz, dh, gb1, B, dh, st, c); });
+  if (tm.desc.par_mode == SIF_PAR_FIXED && tm.desc.fixed_bubble_ns) emit_bubble(p, 0, tm.desc.fixed_bubble_ns);
+  const uint64_t n = pm.n;
+  const float lr = tm.desc.lr;
+  emit(p, "sgd", 4, [=](hipStream_t st, const KCtl& c) { return launch_sgd_f32(W, grads, n, lr, st, c); });
+  return SIF_OK;
+}
+
+static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t stream) {
+  const sif_model_shape& s = tm.desc.shape;
+  const ParamMap pm = param_map(s);
+  const Dims q = dims_of(s, s.batch, s.seq);
+  const uint32_t M = q.M, d = q.d, Vp = (s.vocab + 7) & ~7u;
+  const uint64_t ssz = (uint64_t)q.B * q.H * q.S * q.Sp;
+  bf16_t* work = (bf16_t*)ar.take(pm.n * 2);
+  bf16_t* grads = (bf16_t*)ar.take(pm.n * 2);
+  std::vector<LayerActs> acts(s.n_layers);
+  for (auto& a : acts) {
+    a.ln1 = (bf16_t*)ar.take((uint64_t)M * d * 2); a.qkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
+    a.prob = (bf16_t*)ar.take(ssz * 2); a.o = (bf16_t*)ar.take((uint64_t)M * q.da * 2);
+    a.x_mid = (bf16_t*)ar.take((uint64_t)M * d * 2); a.ln2 = (bf16_t*)ar.take((uint64_t)M * d * 2);
+    a.z = (bf16_t*)ar.take((uint64_t)M * q.f * 2); a.a = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
+    a.x_out = (bf16_t*)ar.take((uint64_t)M * d * 2);
+    a.m1 = (float*)ar.take((uint64_t)M * 4); a.r1 = (float*)ar.take((uint64_t)M * 4);
+    a.m2 = (float*)ar.take((uint64_t)M * 4); a.r2 = (float*)ar.take((uint64_t)M * 4);
+  }
+  Scratch sc;
+  sc.scores = (float*)ar.take(ssz * 4); sc.ds = (bf16_t*)ar.take(ssz * 2);
+  sc.dx_a = (bf16_t*)ar.take((uint64_t)M * d * 2); sc.dx_b = (bf16_t*)ar.take((uint64_t)M * d * 2);
+  sc.dln = (bf16_t*)ar.take((uint64_t)M * d * 2); sc.dqkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
+  sc.d_o = (bf16_t*)ar.take((uint64_t)M * q.da * 2); sc.dz = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
+  uint32_t widest = d > 3 * q.da ? d : 3 * q.da;
+  if (q.f > widest) widest = q.f;
+  sc.part = (float*)ar.take((uint64_t)2 * colsum_parts(M) * widest * 4);
+  bf16_t *x0 = (bf16_t*)ar.take((uint64_t)M * d * 2), *lnf = nullptr, *logits = nullptr;
+  float *mf = nullptr, *rf = nullptr, *loss_tok = nullptr, *loss = nullptr;
+  if (s.vocab) {
+    lnf = (bf16_t*)ar.take((uint64_t)M * d * 2);
+    logits = (bf16_t*)ar.take((uint64_t)M * Vp * 2);
+    mf = (float*)ar.take((uint64_t)M * 4); rf = (float*)ar.take((uint64_t)M * 4);
+    loss_tok = (float*)ar.take((uint64_t)M * 4); loss = (float*)ar.take(256);
+  }
+  tm.workspace_bytes = ar.off;
+  if (!ar.base) return SIF_OK;
+
+  put(tm, "work", work, pm.n); put(tm, "grads", grads, pm.n);
+  for (uint32_t l = 0; l < s.n_layers; ++l) {
+    const LayerActs& a = acts[l];
+    const std::string sfx = "." + std::to_string(l);
+    put(tm, "ln1" + sfx, a.ln1, (uint64_t)M * d); put(tm, "qkv" + sfx, a.qkv, (uint64_t)M * 3 * q.da); put(tm, "prob" + sfx, a.prob, ssz);
+    put(tm, "o" + sfx, a.o, (uint64_t)M * q.da); put(tm, "x_mid" + sfx, a.x_mid, (uint64_t)M * d); put(tm, "ln2" + sfx, a.ln2, (uint64_t)M * d);
+    put(tm, "z" + sfx, a.z, (uint64_t)M * q.f); put(tm, "a" + sfx, a.a, (uint64_t)M * q.f); put(tm, "x_out" + sfx, a.x_out, (uint64_t)M * d);
+  }
+  put(tm, "x0", x0, (uint64_t)M * d);
+  if (s.vocab) { put(tm, "logits", logits, (uint64_t)M * Vp); put(tm, "lnf", lnf, (uint64_t)M * d); put(tm, "loss", loss, 1); }
+
+  // gradients of position rows beyond seq are never written: clear the gradient buffer once
+  hipError_t e = hipMemsetAsync(grads, 0, pm.n * 2, stream);
+  if (e != hipSuccess) return fail_hip(e, "register: clear gradients");
+  sif_status st = launch_sgd_bf16(tm.desc.master_dev, nullptr, work, pm.n, 0.f, stream, no_ctl());
+  if (st != SIF_OK) return st;
+
+  // bubble sites
+  int32_t next_site = 0;
+  TpSites tp{false, 0, &next_site};
+  if (tm.desc.par_mode == SIF_PAR_TP) {
+    tp.on = true;
+    tp.ns = sif_collective_ns((uint64_t)M * d * 2, tm.desc.bw_bytes_per_s);
+    tm.max_bubble_ns = tp.ns;
+  }
+  TrainModel* t = &tm;
+  Plan& p = tm.plan;
+  const uint32_t seq = q.S, V = s.vocab;
+  const bf16_t* x_in = nullptr;
+  if (s.vocab) {
+    const bf16_t *wte = work + pm.at("wte"), *wpe = work + pm.at("wpe");
+    emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_fwd((const int32_t*)t->cur_inputs, wte, wpe, x0, M, seq, d, s2, c); });
+  } else {
+    // layer stack: the caller's activations become the input of the first layer
+    const uint64_t bytes = (uint64_t)M * d * 2;
+    emit(p, "stage_x", bytes_cost_us(2.0 * bytes), [=](hipStream_t s2, const KCtl& c) { return launch_copy(x0, t->cur_inputs, bytes, s2, c); });
+  }
+  x_in = x0;
+  for (uint32_t l = 0; l < s.n_layers; ++l) {
+    const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
+    emit_decoder_layer_fwd(p, q, w, x_in, acts[l], sc, tp);
+    x_in = acts[l].x_out;
+  }
+  const bf16_t* dx = nullptr;       // gradient flowing into the last layer
+  if (s.vocab) {
+    const bf16_t *wte = work + pm.at("wte"), *lnf_g = work + pm.at("lnf_g"), *lnf_b = work + pm.at("lnf_b");
+    const bf16_t* x_last = x_in;
+    emit(p, "lnf", bytes_cost_us(4.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_layernorm_fwd(x_last, lnf_g, lnf_b, lnf, mf, rf, M, d, s2, c); });
+    emit_gemm(p, "lm_head", G(lnf, wte, logits, M, V, d, d, d, Vp));
+    emit(p, "xent", bytes_cost_us(4.0 * M * Vp), [=](hipStream_t s2, const KCtl& c) { return launch_xent(logits, (const int32_t*)t->cur_targets, loss_tok, M, V, Vp, s2, c); });
+    emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
+    emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+    emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+    emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"), sc.part, M, d);
+    dx = sc.dx_a;
+  }
+  for (int32_t l = (int32_t)s.n_layers - 1; l >= 0; --l) {
+    const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
+    const LayerG g = layer_ptrs<LayerG, bf16_t>(grads, pm, l);
+    // dx_out in dx_a (or the caller's gradient for the top of a stack), dx_mid -> dx_b, dx_in -> dx_a
+    if (l == (int32_t)s.n_layers - 1 && !s.vocab) {
+      // top of a stack: the upstream gradient comes from the caller
+      const uint64_t bytes = (uint64_t)M * d * 2;
+      bf16_t* dst = sc.dx_a;
+      emit(p, "stage_dy", bytes_cost_us(2.0 * bytes), [=](hipStream_t s2, const KCtl& c) { return launch_copy(dst, t->cur_targets, bytes, s2, c); });
+      dx = sc.dx_a;
+    }
+    const bf16_t* xin_l = (l == 0) ? x0 : acts[l - 1].x_out;
+    emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[l], sc, dx, sc.dx_b, sc.dx_a, tp);
+    dx = sc.dx_a;
+  }
+  if (s.vocab) {
+    bf16_t *gwte = grads + pm.at("wte"), *gwpe = grads + pm.at("wpe");
+    const bf16_t* dx0 = sc.dx_a;
+    emit(p, "dwte_scatter", bytes_cost_us(4.0 * M * d) + 10.0, [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wte((const int32_t*)t->cur_inputs, dx0, gwte, M, d, s2, c); });
+    emit(p, "dwpe", bytes_cost_us(2.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wpe(dx0, gwpe, M, seq, d, s2, c); });
+  }
+  put(tm, "dx_in", sc.dx_a, (uint64_t)M * d);
+  if (tm.desc.par_mode == SIF_PAR_DP) {
+    const uint64_t ns = sif_collective_ns(pm.n * 2, tm.desc.bw_bytes_per_s);
+    emit_bubble(p, next_site++, ns);
+    tm.max_bubble_ns = ns;
+  } else if (tm.desc.par_mode == SIF_PAR_FIXED && tm.desc.fixed_bubble_ns) {
+    emit_bubble(p, next_site++, tm.desc.fixed_bubble_ns);
+    tm.max_bubble_ns = tm.desc.fixed_bubble_ns;
+  }
+  const uint64_t n = pm.n;
+  const float lr = tm.desc.lr;
+  float* master = tm.desc.master_dev;
+  emit(p, "sgd", bytes_cost_us(12.0 * n), [=](hipStream_t s2, const KCtl& c) { return launch_sgd_bf16(master, grads, work, n, lr, s2, c); });
+  return SIF_OK;
+}
+
+sif_status build_train_model(TrainModel& tm, hipStream_t stream) {
+  sif_status st = check_shape(tm.desc.shape, true);
+  if (st != SIF_OK) return st;
+  if (tm.desc.par_mode > SIF_PAR_TP) return fail(SIF_E_INVAL, "unknown par_mode");
+  if (tm.desc.par_mode == SIF_PAR_PP) return fail(SIF_E_INVAL, "pipeline-parallel steps are not built yet");
+  if ((tm.desc.par_mode == SIF_PAR_DP || tm.desc.par_mode == SIF_PAR_TP) && tm.desc.bw_bytes_per_s == 0) return fail(SIF_E_INVAL, "bw_bytes_per_s must be positive");
+  tm.n_params = model_n_params(tm.desc.shape);
+  Arena ar;
+  ar.base = (unsigned char*)tm.desc.workspace_dev;
+  tm.plan.clear();
+  tm.tensors.clear();
+  if (tm.desc.shape.kind == SIF_MODEL_MLP) {
+    if (tm.desc.par_mode == SIF_PAR_FIXED) tm.max_bubble_ns = tm.desc.fixed_bubble_ns;
+    return build_mlp_train(tm, ar);
+  }
+  if (tm.desc.shape.kind == SIF_MODEL_DECODER) return build_decoder_train(tm, ar, stream);
+  return fail(SIF_E_INVAL, "training model must be MLP or DECODER");
+}
+
+// ------------------------------------------------------------------------------------------ inference models
+static uint64_t layout_infer(InferModel& im, Arena& ar) {
+  const sif_model_shape& s = im.desc.shape;
+  if (s.kind == SIF_MODEL_MLP) {
+    im.bufs["h"] = ar.take((uint64_t)s.batch * s.d_hidden * 4);
+    im.calib_in = ar.take((uint64_t)s.batch * s.d_in * 4);
+    im.calib_out = ar.take((uint64_t)s.batch * s.d_out * 4);
+    return ar.off;
+  }
+  const Dims q = dims_of(s, s.batch, s.seq);
+  const uint64_t ssz = (uint64_t)q.B * q.H * q.S * q.Sp, M = q.M;
+  im.work = ar.take(im.n_params * 2);
+  im.bufs["x"] = ar.take(M * q.d * 2); im.bufs["t"] = ar.take(M * q.d * 2); im.bufs["x1"] = ar.take(M * q.d * 2);
+  im.bufs["qkv"] = ar.take(M * 3 * q.da * 2); im.bufs["scores"] = ar.take(ssz * 4); im.bufs["prob"] = ar.take(ssz * 2);
+  im.bufs["o"] = ar.take(M * q.da * 2); im.bufs["a"] = ar.take(M * q.f * 2);
+  im.calib_in = ar.take(M * 4);
+  im.calib_out = ar.take(M * q.d * 2);
+  return ar.off;
+}
+
+uint64_t infer_workspace_bytes(const sif_infer_desc& d) {
+  InferModel im;
+  im.desc = d;
+  im.n_params = model_n_params(d.shape);
+  Arena ar;
+  return layout_infer(im, ar);
+}
+
+sif_status build_infer_model(InferModel& im, hipStream_t stream) {
+  sif_status st = check_shape(im.desc.shape, false);
+  if (st != SIF_OK) return st;
+  if (im.desc.shape.kind == SIF_MODEL_DECODER) return fail(SIF_E_INVAL, "inference model must be MLP or ENCODER");
+  im.n_params = model_n_params(im.desc.shape);
+  Arena ar;
+  ar.base = (unsigned char*)im.desc.workspace_dev;
+  const uint64_t need = layout_infer(im, ar);
+  if (need > im.desc.workspace_bytes) return fail(SIF_E_NOMEM, "inference workspace too small: need %llu bytes", (unsigned long long)need);
+  const sif_model_shape& s = im.desc.shape;
+  const uint64_t in_bytes = s.kind == SIF_MODEL_MLP ? (uint64_t)s.batch * s.d_in * 4 : (uint64_t)s.batch * s.seq * 4;
+  hipError_t e = hipMemsetAsync(im.calib_in, 0, in_bytes, stream);
+  if (e != hipSuccess) return fail_hip(e, "register: clear calibration input");
+  if (s.kind == SIF_MODEL_ENCODER) return launch_sgd_bf16(const_cast<float*>(im.desc.master_dev), nullptr, im.work, im.n_params, 0.f, stream, no_ctl());
+  return SIF_OK;
+}
+
+sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_dev, uint32_t batch, uint32_t seq,
+                            uint32_t kernel_us_max, Plan& p) {
+  const sif_model_shape& s = im.desc.shape;
+  if (!in_dev || !out_dev) return fail(SIF_E_INVAL, "submit: null buffer");
+  if (batch == 0 || batch > s.batch) return fail(SIF_E_INVAL, "submit: batch must be in 1..%u", s.batch);
+  const ParamMap pm = param_map(s);
+  if (s.kind == SIF_MODEL_MLP) {
+    const float* W = im.desc.master_dev;
+    const float *w1 = W + pm.at("w1"), *b1 = W + pm.at("b1"), *w2 = W + pm.at("w2"), *b2 = W + pm.at("b2");
+    float* h = (float*)im.bufs.at("h");
+    const uint32_t di = s.d_in, dh = s.d_hidden, dout = s.d_out;
+    const float* x = (const float*)in_dev;
+    float* y = (float*)out_dev;
+    emit(p, "fc1", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(x, di, 1, w1, 1, di, h, dh, batch, dh, di, SIF_EPI_GELU, b1, nullptr, st, c); });
+    emit(p, "fc2", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(h, dh, 1, w2, 1, dh, y, dout, batch, dout, dh, SIF_EPI_BIAS, b2, nullptr, st, c); });
+    return SIF_OK;
+  }
+  if (seq == 0 || seq > s.seq) return fail(SIF_E_INVAL, "submit: seq must be in 1..%u", s.seq);
+  const Dims q = dims_of(s, batch, seq);
+  const uint32_t M = q.M, d = q.d;
+  const bf16_t* W = (const bf16_t*)im.work;
+  bf16_t *x = (bf16_t*)im.bufs.at("x"), *t = (bf16_t*)im.bufs.at("t"), *x1 = (bf16_t*)im.bufs.at("x1"), *qkv = (bf16_t*)im.bufs.at("qkv");
+  bf16_t *prob = (bf16_t*)im.bufs.at("prob"), *o = (bf16_t*)im.bufs.at("o"), *a = (bf16_t*)im.bufs.at("a");
+  float* scores = (float*)im.bufs.at("scores");
+  const bf16_t *wte = W + pm.at("wte"), *wpe = W + pm.at("wpe"), *eg = W + pm.at("emb_ln_g"), *eb = W + pm.at("emb_ln_b");
+  const int32_t* ids = (const int32_t*)in_dev;
+  emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd(ids, wte, wpe, t, M, seq, d, st, c); });
+  emit(p, "emb_ln", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, eg, eb, x, nullptr, nullptr, M, d, st, c); });
+  for (uint32_t l = 0; l < s.n_layers; ++l) {
+    const bf16_t *w_qkv = W + pm.at(L(l, "w_qkv")), *b_qkv = W + pm.at(L(l, "b_qkv")), *w_o = W + pm.at(L(l, "w_o")), *b_o = W + pm.at(L(l, "b_o"));
+    const bf16_t *g1 = W + pm.at(L(l, "ln1_g")), *be1 = W + pm.at(L(l, "ln1_b")), *w_fc = W + pm.at(L(l, "w_fc")), *b_fc = W + pm.at(L(l, "b_fc"));
+    const bf16_t *w_pr = W + pm.at(L(l, "w_proj")), *b_pr = W + pm.at(L(l, "b_proj")), *g2 = W + pm.at(L(l, "ln2_g")), *be2 = W + pm.at(L(l, "ln2_b"));
+    bf16_t* y = (l + 1 == s.n_layers) ? (bf16_t*)out_dev : x;
+    emit_gemm_rows(p, "qkv", G(x, w_qkv, qkv, M, 3 * q.da, d, d, d, 3 * q.da).epi(SIF_EPI_BIAS, b_qkv), kernel_us_max);
+    emit_attention_fwd(p, q, qkv, scores, prob, o, false);
+    emit_gemm_rows(p, "attn_out", G(o, w_o, t, M, d, q.da, q.da, q.da, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, b_o, x), kernel_us_max);
+    emit(p, "ln1", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g1, be1, x1, nullptr, nullptr, M, d, st, c); });
+    emit_gemm_rows(p, "mlp_up", G(x1, w_fc, a, M, q.f, d, d, d, q.f).epi(SIF_EPI_GELU, b_fc), kernel_us_max);
+    emit_gemm_rows(p, "mlp_down", G(a, w_pr, t, M, d, q.f, q.f, q.f, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, b_pr, x1), kernel_us_max);
+    emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g2, be2, y, nullptr, nullptr, M, d, st, c); });
+  }
+  return SIF_OK;
+}
+
+}  // namespace sif

@@ -445,6 +445,12 @@ __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* __restrict__ p,
   kernel_end(ctl, true);
 }
 
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, uint64_t nv, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (uint64_t)gridDim.x * 256) dst[i] = src[i];
+  kernel_end(ctl, true);
+}
+
 // ---------------------------------------------------------------------------------------------- launchers
 static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 #define REQ(cond, msg) do { if (!(cond)) return fail(SIF_E_INVAL, msg); } while (0)
@@ -582,6 +588,12 @@ sif_status launch_mse(const float* y, const float* t, float* d, float* loss, uin
   REQ(y && t && d && n > 0, "mse: null or empty");
   hipLaunchKernelGGL(mse_kernel, dim3(1), dim3(1024), 0, s, y, t, d, loss, n, c);
   return check_launch("mse");
+}
+
+sif_status launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s, const KCtl& c) {
+  REQ(dst && src && bytes > 0 && (bytes & 15) == 0 && al16(dst) && al16(src), "copy: needs 16-byte aligned buffers and size");
+  hipLaunchKernelGGL(copy_kernel, dim3(grid_for(bytes >> 4)), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, bytes >> 4, c);
+  return check_launch("copy");
 }
 
 sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c) {

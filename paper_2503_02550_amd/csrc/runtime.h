@@ -1,0 +1,106 @@
+// Host-side structures of the collocation runtime: streams with their activity records, kernel plans of the
+// registered models, and the context that owns the monitor and barrier threads.
+#pragma once
+#include <atomic>
+#include <condition_variable>
+#include <deque>
+#include <functional>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <thread>
+#include <unordered_map>
+#include <vector>
+
+#include "launch.h"
+
+namespace sif {
+
+// One stream and its device-side bookkeeping.
+struct StreamState {
+  hipStream_t stream = nullptr;
+  StreamRec* rec = nullptr;        // HBM
+  Slot* ring = nullptr;            // HBM, kRingSlots entries
+  uint32_t next_kseq = 1;          // launch numbers start at 1
+  uint32_t kind = 0;
+};
+
+// One kernel launch of a plan.
+struct Op {
+  std::function<sif_status(hipStream_t, const KCtl&)> fn;
+  const char* name = "";
+  double cost_us = 5.0;            // predicted duration (analytic estimate, replaced by calibration)
+  int32_t bubble_site = -1;        // training plans: >= 0 means "bubble of bubble_ns here" instead of a kernel
+  uint64_t bubble_ns = 0;
+};
+typedef std::vector<Op> Plan;
+
+// Bump allocator over a caller-owned workspace; with base == nullptr it only measures.
+struct Arena {
+  unsigned char* base = nullptr;
+  uint64_t off = 0;
+  void* take(uint64_t bytes) {
+    off = (off + 255) & ~uint64_t(255);
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+struct NamedTensor { void* ptr; uint64_t elems; };
+
+struct TrainModel {
+  sif_train_desc desc;
+  uint64_t n_params = 0;
+  Plan plan;                                        // one training step, bubbles included
+  std::unordered_map<std::string, NamedTensor> tensors;   // "name" or "name.<layer>"
+  const void** p_inputs = nullptr;                  // host cells the plan's closures read at launch time
+  const void* cur_inputs = nullptr;
+  const void* cur_targets = nullptr;
+  float* cur_loss = nullptr;
+  uint64_t max_bubble_ns = 0;
+  uint64_t workspace_bytes = 0;
+};
+
+struct InferModel {
+  sif_infer_desc desc;
+  uint64_t n_params = 0;
+  void* work = nullptr;                             // working copy of the weights
+  std::unordered_map<std::string, void*> bufs;
+  // cost per op of the plan for the registered (batch, seq), measured by calibration
+  std::vector<double> calib_cost_us;
+  double calib_total_us = 0.0;
+  uint32_t calib_batch = 0, calib_seq = 0;
+  void* calib_in = nullptr;
+  void* calib_out = nullptr;
+};
+
+struct Job {
+  sif_ticket ticket = 0;
+  int32_t model = -1;
+  bool online = false;
+  uint32_t batch = 0, seq = 0;
+  uint64_t t_arrival_ns = 0, t_done_ns = 0;
+  Plan plan;
+  uint32_t next_op = 0;          // next op to launch
+  uint32_t done_ops = 0;         // ops known to have run
+  int32_t result = 1;            // 1 pending, 0 done, < 0 error
+};
+
+struct InFlight { uint32_t kseq; Job* job; uint32_t op; };
+
+// Layout / plan builders (models.hip)
+uint64_t model_n_params(const sif_model_shape& s);
+sif_status build_train_model(TrainModel& tm, hipStream_t stream);
+uint64_t infer_workspace_bytes(const sif_infer_desc& d);
+sif_status build_infer_model(InferModel& im, hipStream_t stream);
+sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_dev, uint32_t batch, uint32_t seq,
+                            uint32_t kernel_us_max, Plan& out);
+
+// markers.hip
+sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,
+                         uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id);
+sif_status launch_step_marker(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id);
+sif_status launch_reset_skip(hipStream_t s, StreamRec* rec, Mirror* mir, uint32_t epoch);
+
+}  // namespace sif

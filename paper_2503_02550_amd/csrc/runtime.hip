@@ -1,0 +1,658 @@
+// The collocation runtime behind the C ABI: context, Bubble Monitor thread, Kernel Barrier thread, job queues.
+//
+// Mapping to the paper's components (Sec. 3.1, 3.3):
+//   monitoring library + Bubble Monitor : prologue/epilogue of every training kernel (monitor.h) keep the launch
+//       count in HBM and in a pinned host mailbox; the monitor thread samples it every period, keeps the sliding
+//       window and computes the zero-count Z_c.
+//   CUDA Kernel Scheduler               : the monitor thread evaluates Algorithm 1 on Z_c each period and
+//       publishes (tokens, status).  One process, so a pair of atomics replaces the UNIX socket.
+//   Kernel Barrier                      : the barrier thread owns the inference stream.  Offline: forwards queued
+//       kernels while the period's tokens last.  Online: pulls one request at a time while the status is idle
+//       and the predicted rest of the bubble holds it.  Launches are speculative: each kernel re-checks the
+//       training stream's state on the device (gate) and the first one that finds it busy poisons the rest of
+//       the window; the barrier then rewinds to that kernel and waits for the next grant.
+#include <algorithm>
+#include <chrono>
+#include <string.h>
+
+#include "runtime.h"
+
+using namespace sif;
+
+static inline uint64_t host_now_ns() {
+  return (uint64_t)std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
+static inline void cpu_relax(int n) { for (int i = 0; i < n; ++i) __builtin_ia32_pause(); }
+
+constexpr uint32_t kBubbleTable = 4096;
+
+struct sif_ctx {
+  sif_config cfg;
+  int device = 0;
+  StreamState T, I;
+  Mirror* mir = nullptr;
+  uint64_t tick_hz = 100000000ull;
+  uint64_t capacity = 0;
+
+  std::unique_ptr<TrainModel> train;
+  std::vector<std::unique_ptr<InferModel>> models;
+
+  std::atomic<uint64_t> bubble_ns[kBubbleTable];
+  uint32_t bubble_seq = 0;
+  uint32_t step_no = 0;
+
+  std::thread mon, bar;
+  std::atomic<bool> stop{false};
+  std::atomic<bool> paused{false};
+  std::atomic<uint32_t> collocate{1};
+
+  // published by the monitor thread
+  std::atomic<uint64_t> grant{0}, pool{0}, period_no{0};
+  std::atomic<int32_t> status{SIF_STATUS_BUSY};
+  std::atomic<uint32_t> zc{0};
+  std::atomic<uint64_t> edge_host_ns{0}, edge_len_ns{0};
+  std::atomic<uint32_t> edge_seq{0};
+
+  // jobs
+  std::mutex mu;
+  std::condition_variable cv;
+  std::deque<Job*> offline_q, online_q;
+  std::unordered_map<sif_ticket, std::unique_ptr<Job>> jobs;
+  sif_ticket next_ticket = 1;
+  std::vector<uint64_t> latencies;
+  std::mutex infer_mu;                 // serialises launches on the inference stream
+
+  // barrier thread state
+  std::deque<InFlight> inflight;
+  std::deque<Job*> run_online, run_offline;
+  uint64_t balance = 0, outstanding_us = 0, last_period = 0;
+  bool awaiting_reset = false;
+  uint32_t reset_epoch = 0;
+
+  std::atomic<uint64_t> offline_samples{0}, offline_batches{0}, online_done{0}, kernels_launched{0}, periods{0};
+  std::atomic<uint64_t> gate_violations{0};
+  uint64_t step_solo_ns = 0;
+
+  uint64_t ticks_to_ns(uint64_t t) const { return (uint64_t)((unsigned __int128)t * 1000000000ull / tick_hz); }
+  uint64_t ns_to_ticks(uint64_t ns) const { return (uint64_t)((unsigned __int128)ns * tick_hz / 1000000000ull); }
+};
+
+static KCtl make_ctl(sif_ctx* c, StreamState& st, uint32_t kind, uint32_t id, const StreamRec* gate, uint32_t cost_ticks) {
+  KCtl k{};
+  k.rec = st.rec; k.mir = c->mir; k.kseq = st.next_kseq++;
+  k.slot = st.ring + (k.kseq % kRingSlots);
+  k.gate = gate; k.cost_ticks = cost_ticks;
+  k.kind_id = (kind << 28) | (id & 0x0FFFFFFFu);
+  return k;
+}
+
+static inline uint32_t mload(const uint32_t* p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
+static inline uint64_t mload(const uint64_t* p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
+
+// ------------------------------------------------------------------------------------------------ monitor
+static void monitor_main(sif_ctx* c) {
+  (void)hipSetDevice(c->device);
+  const uint64_t period_ns = (uint64_t)c->cfg.period_us * 1000ull;
+  std::vector<uint32_t> window;
+  window.reserve(c->cfg.window);
+  uint32_t prev_launched = mload(&c->mir->t_launched);
+  uint32_t last_idle_seen = mload(&c->mir->idle_seq);
+  uint32_t pending_release = 0;
+  uint64_t release_at = 0, pool = 0;
+  uint64_t next_sample = host_now_ns() + period_ns;
+  while (!c->stop.load(std::memory_order_relaxed)) {
+    const uint64_t now = host_now_ns();
+    const uint32_t is = mload(&c->mir->idle_seq);
+    if (is != last_idle_seen) {            // a bubble began: time its release on the host clock
+      last_idle_seen = is;
+      const uint64_t len = c->bubble_ns[is % kBubbleTable].load(std::memory_order_acquire);
+      pending_release = is;
+      release_at = now + len;
+      c->edge_len_ns.store(len, std::memory_order_relaxed);
+      c->edge_host_ns.store(now, std::memory_order_relaxed);
+      c->edge_seq.store(is, std::memory_order_release);
+    }
+    if (pending_release != 0 && now >= release_at) {
+      __atomic_store_n(&c->mir->release_seq, pending_release, __ATOMIC_RELEASE);
+      pending_release = 0;
+    }
+    if (now >= next_sample) {
+      const uint32_t launched = mload(&c->mir->t_launched), completed = mload(&c->mir->t_completed);
+      uint32_t count = launched - prev_launched;
+      prev_launched = launched;
+      if (c->cfg.count_running && count == 0 && launched != completed) count = 1;
+      if (window.size() == c->cfg.window) window.erase(window.begin());
+      window.push_back(count);
+      const uint32_t zc = sif_zero_count(window.data(), (uint32_t)window.size());
+      uint64_t grant = 0;
+      int32_t status = SIF_STATUS_BUSY;
+      sif_alg1_step(&c->cfg.alg1, zc, &pool, &grant, &status);
+      c->zc.store(zc, std::memory_order_relaxed);
+      c->pool.store(pool, std::memory_order_relaxed);
+      c->grant.store(grant, std::memory_order_relaxed);
+      c->status.store(status, std::memory_order_relaxed);
+      c->period_no.fetch_add(1, std::memory_order_release);
+      c->periods.fetch_add(1, std::memory_order_relaxed);
+      next_sample += period_ns;
+      if (next_sample < now) next_sample = now + period_ns;
+    }
+    cpu_relax(20);
+  }
+  // never leave a bubble waiting for a host that is gone
+  __atomic_store_n(&c->mir->release_seq, 0xFFFFFFFFu, __ATOMIC_RELEASE);
+}
+
+// ------------------------------------------------------------------------------------------------ barrier
+static void finish_job(sif_ctx* c, Job* j, int32_t result) {
+  std::lock_guard<std::mutex> lk(c->mu);
+  j->t_done_ns = host_now_ns();
+  j->result = result;
+  if (result == 0) {
+    if (j->online) {
+      c->online_done.fetch_add(1);
+      c->latencies.push_back(j->t_done_ns > j->t_arrival_ns ? j->t_done_ns - j->t_arrival_ns : 0);
+    } else {
+      c->offline_batches.fetch_add(1);
+      c->offline_samples.fetch_add(j->batch);
+    }
+  }
+  j->plan.clear();
+  c->cv.notify_all();
+}
+
+static uint64_t predicted_remaining_ns(sif_ctx* c) {
+  const uint32_t seq = c->edge_seq.load(std::memory_order_acquire);
+  if (seq == 0 || mload(&c->mir->busy_seq) == seq || mload(&c->mir->idle_seq) != seq) return 0;
+  const uint64_t end = c->edge_host_ns.load(std::memory_order_relaxed) + c->edge_len_ns.load(std::memory_order_relaxed);
+  const uint64_t now = host_now_ns();
+  return end > now ? end - now : 0;
+}
+
+static double job_cost_us(const Job* j) {
+  double s = 0;
+  for (const Op& o : j->plan) s += o.cost_us;
+  return s;
+}
+
+static void barrier_main(sif_ctx* c) {
+  (void)hipSetDevice(c->device);
+  while (!c->stop.load(std::memory_order_relaxed)) {
+    if (c->paused.load(std::memory_order_acquire)) { std::this_thread::sleep_for(std::chrono::microseconds(50)); continue; }
+    std::unique_lock<std::mutex> il(c->infer_mu);
+    bool progressed = false;
+    const bool gated = (bool)c->train;
+    // 1. completions, in launch order
+    const uint32_t done = mload(&c->mir->i_done), skip = mload(&c->mir->i_skip_from);
+    while (!c->inflight.empty() && c->inflight.front().kseq <= done && (skip == kNone || c->inflight.front().kseq < skip)) {
+      InFlight f = c->inflight.front();
+      c->inflight.pop_front();
+      const double cost = f.job->plan[f.op].cost_us;
+      c->outstanding_us = c->outstanding_us > (uint64_t)cost ? c->outstanding_us - (uint64_t)cost : 0;
+      if (++f.job->done_ops == f.job->plan.size()) {
+        auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), f.job), q.end()); };
+        drop(c->run_online); drop(c->run_offline);
+        finish_job(c, f.job, 0);
+      }
+      progressed = true;
+    }
+    // 2. a kernel found the gate closed: everything from it on was (or will be) skipped; rewind and clear the poison
+    if (!c->awaiting_reset && skip != kNone) {
+      while (!c->inflight.empty() && c->inflight.back().kseq >= skip) {
+        InFlight f = c->inflight.back();
+        c->inflight.pop_back();
+        if (f.op < f.job->next_op) f.job->next_op = f.op;
+      }
+      c->outstanding_us = 0;
+      for (const InFlight& f : c->inflight) c->outstanding_us += (uint64_t)f.job->plan[f.op].cost_us;
+      c->balance = 0;
+      launch_reset_skip(c->I.stream, c->I.rec, c->mir, ++c->reset_epoch);
+      c->awaiting_reset = true;
+      progressed = true;
+    }
+    if (c->awaiting_reset) {
+      if (mload(&c->mir->i_reset_ack) == c->reset_epoch) c->awaiting_reset = false;
+      else { il.unlock(); cpu_relax(50); continue; }
+    }
+    // 3. a new period: the grant replaces the balance
+    const uint64_t pn = c->period_no.load(std::memory_order_acquire);
+    if (pn != c->last_period) { c->last_period = pn; c->balance = c->grant.load(std::memory_order_relaxed); }
+    // 4. admit jobs
+    if (c->collocate.load(std::memory_order_relaxed) || !gated) {
+      {
+        std::lock_guard<std::mutex> lk(c->mu);
+        if (!c->online_q.empty() && c->run_online.empty()) {
+          Job* j = c->online_q.front();
+          const uint64_t need = (uint64_t)(job_cost_us(j) * 1000.0);
+          if (!gated || sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), predicted_remaining_ns(c), need)) {
+            c->online_q.pop_front();
+            c->run_online.push_back(j);
+          }
+        }
+        while (!c->offline_q.empty() && c->run_offline.size() < 4) { c->run_offline.push_back(c->offline_q.front()); c->offline_q.pop_front(); }
+      }
+      // 5. release kernels
+      const uint64_t max_ahead = gated ? c->cfg.alg1.ul : ~0ull;
+      int budget = 64;
+      while (budget-- > 0) {
+        Job* j = nullptr;
+        bool online = false;
+        for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
+        if (j && gated && c->status.load(std::memory_order_relaxed) != SIF_STATUS_IDLE) j = nullptr;   // online kernels only while idle
+        if (!j) { online = false; for (Job* q : c->run_offline) if (q->next_op < q->plan.size()) { j = q; break; } }
+        if (!j) break;
+        Op& op = j->plan[j->next_op];
+        const uint64_t cost = (uint64_t)(op.cost_us + 0.999);
+        if (gated) {
+          if (!online && c->balance < cost) break;                              // token rule
+          if (c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
+        }
+        const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
+        KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
+        sif_status st = op.fn(c->I.stream, k);
+        if (st != SIF_OK) {
+          auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), j), q.end()); };
+          drop(c->run_online); drop(c->run_offline);
+          // launches of this job already in flight complete normally; forget them
+          c->inflight.erase(std::remove_if(c->inflight.begin(), c->inflight.end(), [&](const InFlight& f) { return f.job == j; }), c->inflight.end());
+          finish_job(c, j, st);
+          break;
+        }
+        c->kernels_launched.fetch_add(1, std::memory_order_relaxed);
+        c->inflight.push_back(InFlight{k.kseq, j, j->next_op});
+        j->next_op++;
+        c->outstanding_us += cost;
+        if (gated && !online) c->balance -= cost;
+        progressed = true;
+      }
+    }
+    il.unlock();
+    if (!progressed) cpu_relax(100);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ helpers
+static sif_status run_step(sif_ctx* c, const void* inputs, const void* targets, float* loss) {
+  TrainModel& tm = *c->train;
+  tm.cur_inputs = inputs; tm.cur_targets = targets; tm.cur_loss = loss;
+  hipStream_t s = c->T.stream;
+  KCtl k0 = make_ctl(c, c->T, kKindStep, c->step_no, nullptr, 0);
+  sif_status st = launch_step_marker(s, c->T.rec, c->mir, k0.slot, 0, k0.kind_id);
+  if (st != SIF_OK) return st;
+  for (size_t i = 0; i < tm.plan.size(); ++i) {
+    Op& op = tm.plan[i];
+    if (op.bubble_site >= 0) {
+      const uint32_t seq = ++c->bubble_seq;
+      c->bubble_ns[seq % kBubbleTable].store(op.bubble_ns, std::memory_order_release);
+      KCtl kb = make_ctl(c, c->T, kKindBubble, (uint32_t)op.bubble_site, nullptr, 0);
+      const uint64_t ticks = c->ns_to_ticks(op.bubble_ns);
+      st = launch_bubble(s, c->T.rec, c->mir, kb.slot, seq, (uint32_t)op.bubble_site, ticks, 4 * ticks + c->ns_to_ticks(100000000ull),
+                         c->cfg.device_timed_bubbles, kb.kind_id);
+    } else {
+      st = op.fn(s, make_ctl(c, c->T, kKindTrain, (uint32_t)i, nullptr, 0));
+    }
+    if (st != SIF_OK) return st;
+  }
+  KCtl k1 = make_ctl(c, c->T, kKindStep, c->step_no, nullptr, 0);
+  ++c->step_no;
+  return launch_step_marker(s, c->T.rec, c->mir, k1.slot, 1, k1.kind_id);
+}
+
+static uint64_t workspace_layout(uint64_t* rec_t, uint64_t* rec_i, uint64_t* ring_t, uint64_t* ring_i) {
+  uint64_t off = 0;
+  auto take = [&](uint64_t b) { off = (off + 255) & ~uint64_t(255); uint64_t o = off; off += b; return o; };
+  uint64_t a = take(sizeof(StreamRec)), b = take(sizeof(StreamRec)), r1 = take((uint64_t)kRingSlots * sizeof(Slot)), r2 = take((uint64_t)kRingSlots * sizeof(Slot));
+  if (rec_t) { *rec_t = a; *rec_i = b; *ring_t = r1; *ring_i = r2; }
+  return off;
+}
+
+#define HIPCHK(call, what) do { hipError_t e_ = (call); if (e_ != hipSuccess) return fail_hip(e_, what); } while (0)
+
+// ------------------------------------------------------------------------------------------------ C ABI
+extern "C" {
+
+uint64_t sif_now_ns(void) { return host_now_ns(); }
+
+sif_status sif_default_config(sif_config* cfg) {
+  if (!cfg) return fail(SIF_E_INVAL, "default_config: null");
+  memset(cfg, 0, sizeof(*cfg));
+  cfg->struct_size = sizeof(*cfg);
+  cfg->period_us = 100; cfg->window = 64; cfg->count_running = 1;
+  cfg->alg1.alpha = 1; cfg->alg1.beta = 3; cfg->alg1.gamma_num = 2; cfg->alg1.gamma_den = 1; cfg->alg1.m = 1;
+  cfg->alg1.t0 = 25; cfg->alg1.ll = 100; cfg->alg1.ul = 400;
+  cfg->kernel_us_max = 200; cfg->collocate = 1; cfg->device_timed_bubbles = 0; cfg->device_capacity_bytes = 0;
+  return SIF_OK;
+}
+
+uint64_t sif_ctx_workspace_bytes(void) { return workspace_layout(nullptr, nullptr, nullptr, nullptr); }
+
+sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_stream, void* workspace_dev, uint64_t workspace_bytes, sif_ctx** out) {
+  if (!cfg || !out || !workspace_dev) return fail(SIF_E_INVAL, "create: null argument");
+  if (cfg->struct_size != sizeof(sif_config)) return fail(SIF_E_INVAL, "create: config struct_size mismatch");
+  if (!train_stream || !infer_stream || train_stream == infer_stream) return fail(SIF_E_INVAL, "create: need two distinct streams");
+  if (cfg->period_us == 0 || cfg->window == 0 || cfg->window > 1024) return fail(SIF_E_INVAL, "create: period_us > 0 and 1 <= window <= 1024");
+  if (cfg->alg1.m == 0 || cfg->alg1.gamma_den == 0 || cfg->alg1.gamma_num == 0) return fail(SIF_E_INVAL, "create: alg1 m, gamma_num and gamma_den must be positive");
+  if (cfg->alg1.alpha > cfg->alg1.beta || cfg->alg1.ll > cfg->alg1.ul) return fail(SIF_E_INVAL, "create: need alpha <= beta and LL <= UL");
+  if ((uintptr_t)workspace_dev & 255) return fail(SIF_E_INVAL, "create: workspace must be 256-byte aligned");
+  if (workspace_bytes < sif_ctx_workspace_bytes()) return fail(SIF_E_NOMEM, "create: workspace too small");
+  std::unique_ptr<sif_ctx> c(new sif_ctx());
+  c->cfg = *cfg;
+  c->collocate.store(cfg->collocate);
+  HIPCHK(hipGetDevice(&c->device), "hipGetDevice");
+  int khz = 0;
+  HIPCHK(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device), "wall clock rate");
+  if (khz <= 0) return fail(SIF_E_DEVICE, "create: device reports no wall clock rate");
+  c->tick_hz = (uint64_t)khz * 1000ull;
+  size_t free_b = 0, total_b = 0;
+  HIPCHK(hipMemGetInfo(&free_b, &total_b), "hipMemGetInfo");
+  c->capacity = cfg->device_capacity_bytes ? cfg->device_capacity_bytes : (uint64_t)total_b;
+  for (auto& b : c->bubble_ns) b.store(0);
+  uint64_t o_rt, o_ri, o_gt, o_gi;
+  workspace_layout(&o_rt, &o_ri, &o_gt, &o_gi);
+  unsigned char* base = (unsigned char*)workspace_dev;
+  c->T.stream = (hipStream_t)train_stream; c->I.stream = (hipStream_t)infer_stream;
+  c->T.rec = (StreamRec*)(base + o_rt); c->I.rec = (StreamRec*)(base + o_ri);
+  c->T.ring = (Slot*)(base + o_gt); c->I.ring = (Slot*)(base + o_gi);
+  HIPCHK(hipMemset(workspace_dev, 0, sif_ctx_workspace_bytes()), "clear workspace");
+  StreamRec init{};
+  init.state = kStateBusy; init.skip_from = kNone;
+  HIPCHK(hipMemcpy(c->T.rec, &init, sizeof(init), hipMemcpyHostToDevice), "init record");
+  HIPCHK(hipMemcpy(c->I.rec, &init, sizeof(init), hipMemcpyHostToDevice), "init record");
+  void* mp = nullptr;
+  HIPCHK(hipHostMalloc(&mp, sizeof(Mirror), hipHostMallocCoherent), "hipHostMalloc mailbox");
+  memset(mp, 0, sizeof(Mirror));
+  c->mir = (Mirror*)mp;
+  c->mir->i_skip_from = kNone;
+  HIPCHK(hipDeviceSynchronize(), "create: synchronize");
+  sif_ctx* raw = c.release();
+  raw->mon = std::thread(monitor_main, raw);
+  raw->bar = std::thread(barrier_main, raw);
+  *out = raw;
+  return SIF_OK;
+}
+
+sif_status sif_destroy(sif_ctx* c) {
+  if (!c) return fail(SIF_E_INVAL, "destroy: null");
+  c->paused.store(true);
+  c->stop.store(true);
+  if (c->bar.joinable()) c->bar.join();
+  if (c->mon.joinable()) c->mon.join();
+  (void)hipSetDevice(c->device);
+  hipError_t e1 = hipStreamSynchronize(c->T.stream), e2 = hipStreamSynchronize(c->I.stream);
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    for (auto& kv : c->jobs) if (kv.second->result == 1) kv.second->result = SIF_E_CANCELLED;
+    c->cv.notify_all();
+  }
+  if (c->mir) (void)hipHostFree(c->mir);
+  delete c;
+  if (e1 != hipSuccess) return fail_hip(e1, "destroy: training stream");
+  if (e2 != hipSuccess) return fail_hip(e2, "destroy: inference stream");
+  return SIF_OK;
+}
+
+sif_status sif_set_collocate(sif_ctx* c, uint32_t on) {
+  if (!c) return fail(SIF_E_INVAL, "set_collocate: null");
+  c->collocate.store(on ? 1 : 0);
+  return SIF_OK;
+}
+
+uint64_t sif_model_n_params(const sif_model_shape* s) { return s ? model_n_params(*s) : 0; }
+
+uint64_t sif_train_workspace_bytes(const sif_train_desc* d) {
+  if (!d || d->struct_size != sizeof(sif_train_desc)) return 0;
+  TrainModel tm;
+  tm.desc = *d;
+  tm.desc.workspace_dev = nullptr;
+  if (build_train_model(tm, nullptr) != SIF_OK) return 0;
+  return tm.workspace_bytes;
+}
+
+sif_status sif_register_training_step(sif_ctx* c, const sif_train_desc* d, sif_handle* out) {
+  if (!c || !d || !out) return fail(SIF_E_INVAL, "register_training_step: null argument");
+  if (d->struct_size != sizeof(sif_train_desc)) return fail(SIF_E_INVAL, "register_training_step: struct_size mismatch");
+  if (c->train) return fail(SIF_E_INVAL, "register_training_step: a training instance is already registered");
+  if (!d->master_dev || !d->workspace_dev || ((uintptr_t)d->workspace_dev & 255) || ((uintptr_t)d->master_dev & 15)) return fail(SIF_E_INVAL, "register_training_step: master/workspace null or misaligned");
+  const uint64_t need = sif_train_workspace_bytes(d);
+  if (need == 0) return SIF_E_INVAL;      // text set by the builder
+  if (d->workspace_bytes < need) return fail(SIF_E_NOMEM, "register_training_step: workspace too small: need %llu bytes", (unsigned long long)need);
+  std::unique_ptr<TrainModel> tm(new TrainModel());
+  tm->desc = *d;
+  sif_status st = build_train_model(*tm, c->T.stream);
+  if (st != SIF_OK) return st;
+  HIPCHK(hipStreamSynchronize(c->T.stream), "register_training_step: synchronize");
+  std::lock_guard<std::mutex> il(c->infer_mu);
+  c->train = std::move(tm);
+  *out = 0;
+  return SIF_OK;
+}
+
+sif_status sif_run_training_step(sif_ctx* c, sif_handle h, const void* inputs_dev, const void* targets_dev, float* loss_dev) {
+  if (!c || !c->train || h != 0) return fail(SIF_E_INVAL, "run_training_step: no such training instance");
+  if (!inputs_dev || !targets_dev) return fail(SIF_E_INVAL, "run_training_step: null inputs or targets");
+  return run_step(c, inputs_dev, targets_dev, loss_dev);
+}
+
+sif_status sif_sync_training(sif_ctx* c) {
+  if (!c) return fail(SIF_E_INVAL, "sync_training: null");
+  HIPCHK(hipStreamSynchronize(c->T.stream), "sync_training");
+  return SIF_OK;
+}
+
+sif_status sif_train_tensor(sif_ctx* c, sif_handle h, const char* name, int32_t layer, void** ptr_dev, uint64_t* elems) {
+  if (!c || !c->train || h != 0 || !name || !ptr_dev) return fail(SIF_E_INVAL, "train_tensor: bad argument");
+  std::string key = name;
+  auto it = c->train->tensors.find(key);
+  if (it == c->train->tensors.end()) it = c->train->tensors.find(key + "." + std::to_string(layer));
+  if (it == c->train->tensors.end()) return fail(SIF_E_INVAL, "train_tensor: unknown tensor '%s'", name);
+  *ptr_dev = it->second.ptr;
+  if (elems) *elems = it->second.elems;
+  return SIF_OK;
+}
+
+uint64_t sif_infer_workspace_bytes(const sif_infer_desc* d) {
+  if (!d || d->struct_size != sizeof(sif_infer_desc)) return 0;
+  return infer_workspace_bytes(*d);
+}
+
+sif_status sif_register_inference_model(sif_ctx* c, const sif_infer_desc* d, sif_handle* out) {
+  if (!c || !d || !out) return fail(SIF_E_INVAL, "register_inference_model: null argument");
+  if (d->struct_size != sizeof(sif_infer_desc)) return fail(SIF_E_INVAL, "register_inference_model: struct_size mismatch");
+  if (!d->master_dev || !d->workspace_dev || ((uintptr_t)d->workspace_dev & 255) || ((uintptr_t)d->master_dev & 15)) return fail(SIF_E_INVAL, "register_inference_model: master/workspace null or misaligned");
+  // Principle-I: the peaks of all collocated instances must sum below the device capacity
+  std::vector<uint64_t> peaks;
+  if (c->train) peaks.push_back(c->train->workspace_bytes + c->train->n_params * 4);
+  for (auto& m : c->models) peaks.push_back(m->desc.peak_bytes);
+  peaks.push_back(d->peak_bytes);
+  if (!sif_principle_1(peaks.data(), (uint32_t)peaks.size(), c->capacity)) return fail(SIF_E_NOMEM, "register_inference_model: collocated peaks exceed the device capacity");
+  std::unique_ptr<InferModel> im(new InferModel());
+  im->desc = *d;
+  std::lock_guard<std::mutex> il(c->infer_mu);
+  sif_status st = build_infer_model(*im, c->I.stream);
+  if (st != SIF_OK) return st;
+  HIPCHK(hipStreamSynchronize(c->I.stream), "register_inference_model: synchronize");
+  c->models.push_back(std::move(im));
+  *out = (sif_handle)(c->models.size() - 1);
+  return SIF_OK;
+}
+
+static void apply_calibration(const InferModel& im, Job& j) {
+  if (im.calib_cost_us.size() != j.plan.size() || im.calib_batch == 0) return;
+  const double scale = ((double)j.batch * (j.seq ? j.seq : 1)) / ((double)im.calib_batch * (im.calib_seq ? im.calib_seq : 1));
+  for (size_t i = 0; i < j.plan.size(); ++i) {
+    const double base = im.calib_cost_us[i];
+    j.plan[i].cost_us = std::max(1.0, 2.0 + (base - 2.0) * scale);
+  }
+}
+
+static sif_status submit(sif_ctx* c, sif_handle model, const void* in_dev, void* out_dev, uint32_t batch, uint32_t seq, bool online,
+                         uint64_t t_arrival_ns, sif_ticket* out) {
+  if (!c || !out) return fail(SIF_E_INVAL, "submit: null argument");
+  if (model < 0 || (size_t)model >= c->models.size()) return fail(SIF_E_INVAL, "submit: no such model");
+  InferModel& im = *c->models[model];
+  if ((im.desc.online != 0) != online) return fail(SIF_E_INVAL, "submit: model was registered for the other mode");
+  std::unique_ptr<Job> j(new Job());
+  j->model = model; j->online = online; j->batch = batch; j->seq = im.desc.shape.kind == SIF_MODEL_MLP ? 1 : seq;
+  j->t_arrival_ns = t_arrival_ns ? t_arrival_ns : host_now_ns();
+  sif_status st = build_infer_plan(im, in_dev, out_dev, batch, seq, c->cfg.kernel_us_max, j->plan);
+  if (st != SIF_OK) return st;
+  apply_calibration(im, *j);
+  std::lock_guard<std::mutex> lk(c->mu);
+  if (c->offline_q.size() + c->online_q.size() >= 4096) return fail(SIF_E_AGAIN, "submit: queue full");
+  j->ticket = c->next_ticket++;
+  *out = j->ticket;
+  (online ? c->online_q : c->offline_q).push_back(j.get());
+  c->jobs[j->ticket] = std::move(j);
+  return SIF_OK;
+}
+
+sif_status sif_submit_offline_batch(sif_ctx* c, sif_handle model, const void* in_dev, void* out_dev, uint32_t batch, uint32_t seq, sif_ticket* out) {
+  return submit(c, model, in_dev, out_dev, batch, seq, false, 0, out);
+}
+
+sif_status sif_submit_online_request(sif_ctx* c, sif_handle model, const void* in_dev, void* out_dev, uint32_t seq, uint64_t t_arrival_ns, sif_ticket* out) {
+  return submit(c, model, in_dev, out_dev, 1, seq, true, t_arrival_ns, out);
+}
+
+sif_status sif_wait(sif_ctx* c, sif_ticket t, uint64_t timeout_ns) {
+  if (!c) return fail(SIF_E_INVAL, "wait: null");
+  std::unique_lock<std::mutex> lk(c->mu);
+  auto it = c->jobs.find(t);
+  if (it == c->jobs.end()) return fail(SIF_E_INVAL, "wait: unknown ticket");
+  Job* j = it->second.get();
+  const bool ok = c->cv.wait_for(lk, std::chrono::nanoseconds(timeout_ns), [&] { return j->result != 1; });
+  if (!ok) return fail(SIF_E_TIMEOUT, "wait: ticket %llu still pending", (unsigned long long)t);
+  const int32_t r = j->result;
+  c->jobs.erase(it);
+  if (r < 0) return fail(r, "wait: job failed or was cancelled");
+  return SIF_OK;
+}
+
+sif_status sif_calibrate(sif_ctx* c, uint32_t iters, const void* train_inputs_dev, const void* train_targets_dev) {
+  if (!c || iters == 0) return fail(SIF_E_INVAL, "calibrate: null context or zero iterations");
+  c->paused.store(true, std::memory_order_release);
+  std::unique_lock<std::mutex> il(c->infer_mu);
+  struct Unpause { sif_ctx* c; ~Unpause() { c->paused.store(false, std::memory_order_release); } } unpause{c};
+  HIPCHK(hipStreamSynchronize(c->I.stream), "calibrate: synchronize");
+  sif_status result = SIF_OK;
+  if (c->train && train_inputs_dev && train_targets_dev) {
+    sif_status st = run_step(c, train_inputs_dev, train_targets_dev, nullptr);
+    if (st != SIF_OK) return st;
+    HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
+    const uint64_t s0 = mload(&c->mir->step_ticks_sum);
+    for (uint32_t i = 0; i < iters; ++i) { st = run_step(c, train_inputs_dev, train_targets_dev, nullptr); if (st != SIF_OK) return st; }
+    HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
+    c->step_solo_ns = c->ticks_to_ns((mload(&c->mir->step_ticks_sum) - s0) / iters);
+  }
+  for (auto& mp : c->models) {
+    InferModel& im = *mp;
+    const sif_model_shape& s = im.desc.shape;
+    const uint32_t batch = im.desc.online ? 1 : s.batch;
+    Plan plan;
+    sif_status st = build_infer_plan(im, im.calib_in, im.calib_out, batch, s.seq, c->cfg.kernel_us_max, plan);
+    if (st != SIF_OK) return st;
+    std::vector<double> sum(plan.size(), 0.0);
+    std::vector<uint32_t> kseqs(plan.size());
+    std::vector<Slot> slots(plan.size());
+    for (uint32_t it = 0; it <= iters; ++it) {
+      for (size_t i = 0; i < plan.size(); ++i) {
+        KCtl k = make_ctl(c, c->I, kKindInfer, (uint32_t)i, nullptr, 0);
+        kseqs[i] = k.kseq;
+        st = plan[i].fn(c->I.stream, k);
+        if (st != SIF_OK) return st;
+      }
+      HIPCHK(hipStreamSynchronize(c->I.stream), "calibrate: synchronize");
+      if (it == 0) continue;       // warm-up
+      for (size_t i = 0; i < plan.size(); ++i) {
+        Slot sl;
+        HIPCHK(hipMemcpy(&sl, c->I.ring + (kseqs[i] % kRingSlots), sizeof(Slot), hipMemcpyDeviceToHost), "calibrate: read slot");
+        sum[i] += (double)c->ticks_to_ns(sl.t1 - sl.t0) / 1000.0;
+      }
+    }
+    im.calib_cost_us.resize(plan.size());
+    im.calib_total_us = 0;
+    for (size_t i = 0; i < plan.size(); ++i) { im.calib_cost_us[i] = std::max(1.0, sum[i] / iters + 2.0); im.calib_total_us += im.calib_cost_us[i]; }
+    im.calib_batch = batch; im.calib_seq = s.kind == SIF_MODEL_MLP ? 1 : s.seq;
+    if (im.desc.online && c->train && c->train->max_bubble_ns && !sif_principle_2((uint64_t)(im.calib_total_us * 1000.0), c->train->max_bubble_ns)) {
+      fail(SIF_W_SLO_RISK, "calibrate: an online request (%.0f us) is longer than the longest bubble", im.calib_total_us);
+      result = SIF_W_SLO_RISK;
+    }
+  }
+  return result;
+}
+
+sif_status sif_poll_stats(sif_ctx* c, sif_stats* out) {
+  if (!c || !out) return fail(SIF_E_INVAL, "poll_stats: null");
+  if (out->struct_size != sizeof(sif_stats)) return fail(SIF_E_INVAL, "poll_stats: struct_size mismatch");
+  const Mirror* m = c->mir;
+  out->status_now = (uint32_t)c->status.load(); out->zc_now = c->zc.load(); out->tokens_now = c->grant.load();
+  out->steps = mload(&m->steps);
+  out->step_ns_sum = c->ticks_to_ns(mload(&m->step_ticks_sum));
+  out->step_ns_last = c->ticks_to_ns(mload(&m->step_ticks_last));
+  out->step_solo_ns = c->step_solo_ns;
+  out->bubble_ns = c->ticks_to_ns(mload(&m->bubble_ticks));
+  out->filled_ns = c->ticks_to_ns(mload(&m->filled_ticks));
+  out->infer_busy_ns = c->ticks_to_ns(mload(&m->infer_ticks));
+  out->offline_samples = c->offline_samples.load(); out->offline_batches = c->offline_batches.load();
+  out->online_done = c->online_done.load();
+  out->kernels_launched = c->kernels_launched.load();
+  out->kernels_skipped = mload(&m->kernels_skipped);
+  out->kernels_run = mload(&m->kernels_run);
+  out->train_kernels = mload(&m->train_kernels);
+  out->gate_violations = c->gate_violations.load();
+  out->periods = c->periods.load();
+  out->online_p50_ns = out->online_p95_ns = 0;
+  std::vector<uint64_t> lat;
+  { std::lock_guard<std::mutex> lk(c->mu); lat = c->latencies; }
+  if (!lat.empty()) {
+    std::sort(lat.begin(), lat.end());
+    auto rank = [&](double p) { size_t r = (size_t)ceil(p * lat.size()); return lat[r == 0 ? 0 : r - 1]; };   // nearest rank
+    out->online_p50_ns = rank(0.50); out->online_p95_ns = rank(0.95);
+  }
+  return SIF_OK;
+}
+
+sif_status sif_reset_stats(sif_ctx* c) {
+  if (!c) return fail(SIF_E_INVAL, "reset_stats: null");
+  c->paused.store(true, std::memory_order_release);
+  std::unique_lock<std::mutex> il(c->infer_mu);
+  struct Unpause { sif_ctx* c; ~Unpause() { c->paused.store(false, std::memory_order_release); } } unpause{c};
+  HIPCHK(hipStreamSynchronize(c->T.stream), "reset_stats: training stream");
+  HIPCHK(hipStreamSynchronize(c->I.stream), "reset_stats: inference stream");
+  // zero the accumulators of both records (they start at the `steps` field) and of the mailbox
+  const size_t off = offsetof(StreamRec, steps), len = sizeof(StreamRec) - off;
+  HIPCHK(hipMemset((unsigned char*)c->T.rec + off, 0, len), "reset_stats");
+  HIPCHK(hipMemset((unsigned char*)c->I.rec + off, 0, len), "reset_stats");
+  Mirror* m = c->mir;
+  m->steps = m->step_ticks_sum = m->step_ticks_last = m->bubble_ticks = m->filled_ticks = m->infer_ticks = 0;
+  m->kernels_run = m->kernels_skipped = m->train_kernels = 0;
+  c->offline_samples = 0; c->offline_batches = 0; c->online_done = 0; c->kernels_launched = 0; c->periods = 0; c->gate_violations = 0;
+  { std::lock_guard<std::mutex> lk(c->mu); c->latencies.clear(); }
+  return SIF_OK;
+}
+
+sif_status sif_read_trace(sif_ctx* c, uint32_t which, sif_trace_rec* out, uint32_t max, uint32_t* n) {
+  if (!c || !n || which > 1 || (max && !out)) return fail(SIF_E_INVAL, "read_trace: bad argument");
+  c->paused.store(true, std::memory_order_release);
+  std::unique_lock<std::mutex> il(c->infer_mu);
+  struct Unpause { sif_ctx* c; ~Unpause() { c->paused.store(false, std::memory_order_release); } } unpause{c};
+  HIPCHK(hipStreamSynchronize(c->T.stream), "read_trace: training stream");
+  HIPCHK(hipStreamSynchronize(c->I.stream), "read_trace: inference stream");
+  StreamState& st = which == 0 ? c->T : c->I;
+  const uint32_t launched = st.next_kseq - 1;
+  uint32_t cnt = launched < kRingSlots - 1 ? launched : kRingSlots - 1;
+  if (cnt > max) cnt = max;
+  std::vector<Slot> ring(kRingSlots);
+  HIPCHK(hipMemcpy(ring.data(), st.ring, (size_t)kRingSlots * sizeof(Slot), hipMemcpyDeviceToHost), "read_trace: copy ring");
+  for (uint32_t i = 0; i < cnt; ++i) {
+    const uint32_t kseq = launched - cnt + 1 + i;
+    const Slot& s = ring[kseq % kRingSlots];
+    out[i].kind = s.kind_id >> 28; out[i].id = s.kind_id & 0x0FFFFFFFu;
+    out[i].decision = (out[i].kind == kKindTrain || out[i].kind == kKindInfer) ? (s.decision & 3u) : 1u;
+    out[i].reserved = kseq;
+    out[i].t0_ns = c->ticks_to_ns(s.t0); out[i].t1_ns = c->ticks_to_ns(s.t1);
+  }
+  *n = cnt;
+  return SIF_OK;
+}
+
+}  // extern "C"
