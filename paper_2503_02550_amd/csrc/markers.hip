@@ -73,6 +73,27 @@ __global__ __launch_bounds__(64) void reset_skip_kernel(StreamRec* rec, Mirror* 
   st_sys(&mir->i_reset_ack, epoch);
 }
 
+// Probe pair used once at context creation: does a kernel on the inference stream run while the training stream
+// is occupied?  (Two HIP streams can share one hardware queue, which would serialise them.)
+__global__ __launch_bounds__(64) void probe_spin_kernel(uint64_t ticks, uint64_t* out) {
+  if (threadIdx.x != 0) return;
+  const uint64_t t0 = now_ticks();
+  while (now_ticks() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+  out[0] = t0;
+  out[1] = now_ticks();
+}
+__global__ __launch_bounds__(64) void probe_stamp_kernel(uint64_t* out) {
+  if (threadIdx.x == 0) out[2] = now_ticks();
+}
+
+sif_status launch_probe(hipStream_t spin_stream, hipStream_t stamp_stream, uint64_t ticks, uint64_t* out) {
+  hipLaunchKernelGGL(probe_spin_kernel, dim3(1), dim3(64), 0, spin_stream, ticks, out);
+  sif_status st = check_launch("probe_spin");
+  if (st != SIF_OK) return st;
+  hipLaunchKernelGGL(probe_stamp_kernel, dim3(1), dim3(64), 0, stamp_stream, out);
+  return check_launch("probe_stamp");
+}
+
 sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,
                          uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
   hipLaunchKernelGGL(bubble_kernel, dim3(1), dim3(64), 0, s, rec, mir, slot, seq, site, ticks, max_ticks, device_timed, kind_id);

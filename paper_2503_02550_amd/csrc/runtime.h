@@ -87,7 +87,7 @@ struct Job {
   int32_t result = 1;            // 1 pending, 0 done, < 0 error
 };
 
-struct InFlight { uint32_t kseq; Job* job; uint32_t op; };
+struct InFlight { uint32_t kseq; Job* job; uint32_t op; uint32_t idle_seq; };
 
 // Layout / plan builders (models.hip)
 uint64_t model_n_params(const sif_model_shape& s);
@@ -101,6 +101,7 @@ sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_
 sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,
                          uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id);
 sif_status launch_step_marker(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id);
+sif_status launch_probe(hipStream_t spin_stream, hipStream_t stamp_stream, uint64_t ticks, uint64_t* out);
 sif_status launch_reset_skip(hipStream_t s, StreamRec* rec, Mirror* mir, uint32_t epoch);
 
 }  // namespace sif

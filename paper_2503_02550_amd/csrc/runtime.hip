@@ -67,6 +67,8 @@ struct sif_ctx {
   std::deque<Job*> run_online, run_offline;
   uint64_t balance = 0, outstanding_us = 0, last_period = 0;
   bool awaiting_reset = false;
+  bool hold = false;                   // after a skipped launch: release nothing until a new bubble begins
+  uint32_t hold_seq = 0;
   uint32_t reset_epoch = 0;
 
   std::atomic<uint64_t> offline_samples{0}, offline_batches{0}, online_done{0}, kernels_launched{0}, periods{0};
@@ -201,6 +203,8 @@ static void barrier_main(sif_ctx* c) {
         InFlight f = c->inflight.back();
         c->inflight.pop_back();
         if (f.op < f.job->next_op) f.job->next_op = f.op;
+        c->hold = true;                   // the bubble this launch was aimed at has no room left
+        c->hold_seq = f.idle_seq;
       }
       c->outstanding_us = 0;
       for (const InFlight& f : c->inflight) c->outstanding_us += (uint64_t)f.job->plan[f.op].cost_us;
@@ -216,8 +220,9 @@ static void barrier_main(sif_ctx* c) {
     // 3. a new period: the grant replaces the balance
     const uint64_t pn = c->period_no.load(std::memory_order_acquire);
     if (pn != c->last_period) { c->last_period = pn; c->balance = c->grant.load(std::memory_order_relaxed); }
+    if (c->hold && (!gated || mload(&c->mir->idle_seq) != c->hold_seq)) c->hold = false;
     // 4. admit jobs
-    if (c->collocate.load(std::memory_order_relaxed) || !gated) {
+    if ((c->collocate.load(std::memory_order_relaxed) && !c->hold) || !gated) {
       {
         std::lock_guard<std::mutex> lk(c->mu);
         if (!c->online_q.empty() && c->run_online.empty()) {
@@ -258,7 +263,7 @@ static void barrier_main(sif_ctx* c) {
           break;
         }
         c->kernels_launched.fetch_add(1, std::memory_order_relaxed);
-        c->inflight.push_back(InFlight{k.kseq, j, j->next_op});
+        c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq)});
         j->next_op++;
         c->outstanding_us += cost;
         if (gated && !online) c->balance -= cost;
@@ -363,6 +368,22 @@ sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_str
   c->mir = (Mirror*)mp;
   c->mir->i_skip_from = kNone;
   HIPCHK(hipDeviceSynchronize(), "create: synchronize");
+  // The two streams must be able to run concurrently: spin 300 us on the training stream and stamp the time on
+  // the inference stream; the stamp has to fall inside the spin.
+  {
+    uint64_t* probe = (uint64_t*)c->I.ring;
+    sif_status st = launch_probe(c->T.stream, c->I.stream, c->ns_to_ticks(300000), probe);
+    if (st != SIF_OK) { (void)hipHostFree(mp); return st; }
+    uint64_t h[3] = {0, 0, 0};
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(h, probe, sizeof(h), hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemset(probe, 0, sizeof(h));
+    if (e != hipSuccess) { (void)hipHostFree(mp); return fail_hip(e, "create: stream probe"); }
+    if (!(h[2] > h[0] && h[2] < h[1])) {
+      (void)hipHostFree(mp);
+      return fail(SIF_E_AGAIN, "create: the two streams do not run concurrently (they share a hardware queue); pass another pair");
+    }
+  }
   sif_ctx* raw = c.release();
   raw->mon = std::thread(monitor_main, raw);
   raw->bar = std::thread(barrier_main, raw);

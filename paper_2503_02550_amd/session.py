@@ -23,11 +23,20 @@ class Session:
         self.dev = torch.device(device)
         torch.cuda.set_device(self.dev)
         self.cfg = cfg if cfg is not None else B.sif_default_config()
-        self.st_train = torch.cuda.Stream(device=self.dev)
-        self.st_infer = torch.cuda.Stream(device=self.dev)
         self._ws = _u8(B.sif_ctx_workspace_bytes(), self.dev)
-        torch.cuda.synchronize()
-        self.ctx = B.sif_create(self.cfg, self.st_train, self.st_infer, _aligned(self._ws), B.sif_ctx_workspace_bytes())
+        self.st_train = torch.cuda.Stream(device=self.dev)
+        self.ctx = None
+        for _ in range(16):      # sif_create refuses a stream pair that shares a hardware queue (SIF_E_AGAIN)
+            self.st_infer = torch.cuda.Stream(device=self.dev)
+            torch.cuda.synchronize()
+            try:
+                self.ctx = B.sif_create(self.cfg, self.st_train, self.st_infer, _aligned(self._ws), B.sif_ctx_workspace_bytes())
+                break
+            except B.SifError as e:
+                if e.status != B.SIF_E_AGAIN:
+                    raise
+        if self.ctx is None:
+            raise RuntimeError("no pair of concurrent streams found")
         self.train = None
         self.models = []
 

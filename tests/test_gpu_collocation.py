@@ -1,0 +1,175 @@
+"""Scheduling invariants on the GPU (Sec. 2.2 "maintain the training throughput while concurrently providing
+additional inference services"): training results are bit-identical with and without collocation, inference
+outputs are bit-identical to a solo run and match the oracle, and no inference kernel starts outside a bubble."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as Y
+from oracle import encoder as OE
+from oracle import mlp as OM
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2503_02550_amd as S
+    from paper_2503_02550_amd import params as P
+    from paper_2503_02550_amd.session import Session, decoder_shape, encoder_shape, mlp_shape
+    from gpu_util import DEV, bf, f32, i32, up, q, assert_bf16_close, assert_f32_close
+
+
+def bubbles_and_kernels(s, after_launch=0):
+    """Bubble intervals of the training stream and the inference kernels launched after launch number
+    `after_launch` (the calibration run comes before it and is ungated by design)."""
+    tr = S.sif_read_trace(s.ctx, 0)
+    inf = [r for r in S.sif_read_trace(s.ctx, 1) if r[3] > after_launch]
+    bubbles = [(t0, t1) for kind, _, _, _, t0, t1 in tr if kind == 3]
+    ran = [(t0, t1) for kind, _, dec, _, t0, t1 in inf if kind == 2 and dec == 1]
+    skipped = sum(1 for kind, _, dec, _, _, _ in inf if kind == 2 and dec == 2)
+    return bubbles, ran, skipped
+
+
+def last_launch(s):
+    tr = S.sif_read_trace(s.ctx, 1)
+    return tr[-1][3] if tr else 0
+
+
+def assert_starts_inside_bubbles(bubbles, ran):
+    b0 = np.array([b[0] for b in bubbles]); b1 = np.array([b[1] for b in bubbles])
+    for t0, _ in ran:
+        i = np.searchsorted(b0, t0, side="right") - 1
+        assert i >= 0 and b0[i] <= t0 <= b1[i], ("inference kernel started outside a bubble", t0)
+
+
+def run_tiny(collocate, n_batches, steps=20):
+    """Tiny configuration: fp32 MLP training with a fixed 2 ms bubble per step, MLP inference batches of 8."""
+    c = Y.TINY_MLP
+    shape, ishape = mlp_shape(c["d_in"], c["d_hidden"], c["d_out"], c["train_batch"]), mlp_shape(c["d_in"], c["d_hidden"], c["d_out"], c["infer_batch"])
+    p_tr, p_inf = Y.mlp_params(0, c["d_in"], c["d_hidden"], c["d_out"]), Y.mlp_params(1, c["d_in"], c["d_hidden"], c["d_out"])
+    cfg = S.sif_default_config()
+    cfg.collocate = 1 if collocate else 0
+    with Session(cfg) as s:
+        s.register_training(shape, P.pack(shape, p_tr), par_mode=S.SIF_PAR_FIXED, lr=c["lr"], fixed_bubble_ns=c["bubble_ns"])
+        m = s.register_inference(ishape, P.pack(ishape, p_inf))
+        S.sif_calibrate(s.ctx, 2)
+        n_cal = last_launch(s)
+        xs = [f32(Y.activations(100 + i, c["infer_batch"], c["d_in"])) for i in range(n_batches)]
+        outs = [torch.zeros((c["infer_batch"], c["d_out"]), device=DEV) for _ in range(n_batches)]
+        batches = [tuple(f32(a) for a in Y.mlp_batch(0, st, c["train_batch"], c["d_in"], c["d_out"])) for st in range(steps)]
+        losses = torch.zeros(steps, device=DEV)
+        torch.cuda.synchronize()          # buffers are filled on torch's stream; the library uses its own two
+        tickets = [s.submit_offline(m, xs[i], outs[i], c["infer_batch"]) for i in range(n_batches)]
+        for st in range(steps):
+            s.step(batches[st][0], batches[st][1], losses[st:st + 1])
+        s.sync()
+        if collocate:
+            for t in tickets:
+                s.wait(t, 20.0)
+        stats = s.stats()
+        trace = bubbles_and_kernels(s, n_cal)
+        return up(s.train["master"]), up(losses), [up(o) for o in outs], stats, trace
+
+
+def test_tiny_configuration_invariants():
+    c = Y.TINY_MLP
+    w_solo, l_solo, _, st_solo, _ = run_tiny(False, 0)
+    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_tiny(True, 64)
+    assert np.array_equal(w_solo, w_col) and np.array_equal(l_solo, l_col)          # training untouched by collocation
+    assert st.steps == 20 and len(bubbles) == 20
+    assert all(b1 - b0 >= c["bubble_ns"] for b0, b1 in bubbles)                     # modelled wait is at least its length
+    assert st.offline_batches == 64 and st.offline_samples == 64 * c["infer_batch"]
+    assert len(ran) == 128 and st.kernels_run == 128 + 6                            # two kernels per batch, each ran once (+ calibration)
+    assert_starts_inside_bubbles(bubbles, ran)
+    # oracle and solo run
+    p_inf = {k: v.astype(np.float64) for k, v in Y.mlp_params(1, c["d_in"], c["d_hidden"], c["d_out"]).items()}
+    ishape = mlp_shape(c["d_in"], c["d_hidden"], c["d_out"], c["infer_batch"])
+    with Session() as s:                                                            # no training instance: solo inference
+        m = s.register_inference(ishape, P.pack(ishape, Y.mlp_params(1, c["d_in"], c["d_hidden"], c["d_out"])))
+        for i in (0, 17, 63):
+            x = Y.activations(100 + i, c["infer_batch"], c["d_in"])
+            X, out = f32(x), torch.zeros((c["infer_batch"], c["d_out"]), device=DEV)
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, X, out, c["infer_batch"]))
+            assert np.array_equal(up(out), outs[i])                                 # bit-identical to the solo run
+            assert_f32_close(outs[i], OM.mlp_forward(p_inf, x)[0], "tiny inference")
+    # training against the oracle: 20 SGD steps
+    ref = {k: v.astype(np.float64) for k, v in Y.mlp_params(0, c["d_in"], c["d_hidden"], c["d_out"]).items()}
+    for stp in range(20):
+        x, t = Y.mlp_batch(0, stp, c["train_batch"], c["d_in"], c["d_out"])
+        rl, ref, _ = OM.mlp_train_step(ref, x, t, c["lr"])
+        assert abs(l_col[stp] - rl) <= 1e-4 * abs(rl)
+    shape = mlp_shape(c["d_in"], c["d_hidden"], c["d_out"], c["train_batch"])
+    got = P.unpack(shape, w_col)
+    for k in ref:
+        assert_f32_close(got[k], ref[k], k)
+
+
+DEC = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=1000, max_pos=128, batch=4, seq=128, causal=True)
+ENC = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=500, max_pos=64, batch=8, seq=64)
+
+
+def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000):
+    shape, ishape = decoder_shape(DEC), encoder_shape(ENC)
+    cfg = S.sif_default_config()
+    cfg.collocate = 1 if collocate else 0
+    with Session(cfg) as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=bubble_ns)
+        m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)))
+        S.sif_calibrate(s.ctx, 2)
+        n_cal = last_launch(s)
+        ids = [i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])) for i in range(n_batches)]
+        outs = [torch.zeros((ENC["batch"], ENC["seq"], ENC["d_model"]), device=DEV, dtype=torch.bfloat16) for _ in range(n_batches)]
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        losses = torch.zeros(steps, device=DEV)
+        torch.cuda.synchronize()
+        tickets = [s.submit_offline(m, ids[i], outs[i], ENC["batch"], ENC["seq"]) for i in range(n_batches)]
+        for st in range(steps):
+            s.step(x, t, losses[st:st + 1])
+        s.sync()
+        if collocate:
+            for tk in tickets:
+                s.wait(tk, 20.0)
+        return up(s.train["master"]), up(losses), outs, s.stats(), bubbles_and_kernels(s, n_cal)
+
+
+def test_transformer_collocation_invariants():
+    w_solo, l_solo, _, _, _ = run_transformer(False, 0)
+    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_transformer(True, 6)
+    assert np.array_equal(w_solo, w_col) and np.array_equal(l_solo, l_col)
+    assert st.offline_batches == 6
+    assert_starts_inside_bubbles(bubbles, ran)
+    assert len(ran) + skipped == st.kernels_launched
+    assert st.filled_ns <= st.infer_busy_ns
+    ishape = encoder_shape(ENC)
+    master = Y.encoder_params(2, ENC, perturb=True)
+    w = OE.working_copy(master, "bf16")
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, master))
+        for i in (0, 5):
+            ids = Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])
+            I, out = i32(ids), torch.zeros_like(outs[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
+            assert torch.equal(out, outs[i])                                       # same bits as the solo run
+            assert_bf16_close(up(outs[i]), OE.encoder_forward(w, ids, ENC, "bf16"), "collocated encoder", elem_slack=1.5e-2)
+
+
+def test_training_that_never_idles_starves_inference_without_deadlock():
+    c = Y.TINY_MLP
+    shape, ishape = mlp_shape(c["d_in"], c["d_hidden"], c["d_out"], c["train_batch"]), mlp_shape(c["d_in"], c["d_hidden"], c["d_out"], c["infer_batch"])
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, Y.mlp_params(0, 256, 256, 256)), par_mode=S.SIF_PAR_NONE, lr=0.01)   # no bubbles
+        m = s.register_inference(ishape, P.pack(ishape, Y.mlp_params(1, 256, 256, 256)))
+        x, out = f32(Y.activations(1, 8, 256)), torch.zeros((8, 256), device=DEV)
+        xb, tb = (f32(a) for a in Y.mlp_batch(0, 0, 32, 256, 256))
+        torch.cuda.synchronize()
+        tk = s.submit_offline(m, x, out, 8)
+        for _ in range(200):
+            s.step(xb, tb)
+        s.sync()
+        st = s.stats()
+        assert st.kernels_run == 0 or st.offline_batches <= 1       # nothing may run while the training stream is busy
+        with pytest.raises(S.SifError) as e:
+            s.wait(tk, 0.05) if st.offline_batches == 0 else (_ for _ in ()).throw(S.SifError(S.SIF_E_TIMEOUT, "done"))
+        assert e.value.status == S.SIF_E_TIMEOUT
+    # destroy cancelled the pending ticket and returned

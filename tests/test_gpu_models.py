@@ -31,6 +31,7 @@ def test_mlp_training_steps_and_forward_match_oracle():
         for step in range(5):
             x, t = Y.mlp_batch(0, step, c["train_batch"], c["d_in"], c["d_out"])
             X, T = f32(x), f32(t)
+            torch.cuda.synchronize()
             s.step(X, T, loss)
             s.sync()
             rl, ref, rg = OM.mlp_train_step(ref, x, t, c["lr"])
@@ -47,6 +48,7 @@ def test_mlp_training_steps_and_forward_match_oracle():
         for b in (c["infer_batch"], 3):
             x = Y.activations(5, b, c["d_in"])
             X, out = f32(x), torch.zeros((b, c["d_out"]), device=DEV)
+            torch.cuda.synchronize()
             s.wait(s.submit_offline(m, X, out, b))
             y, _ = OM.mlp_forward({k: v.astype(np.float64) for k, v in p0.items()}, x)
             assert_f32_close(up(out), y, f"mlp forward batch {b}")
@@ -66,8 +68,9 @@ def test_decoder_training_step_matches_oracle_stage_by_stage(cfg):
     b, sq, d = cfg["batch"], cfg["seq"], cfg["d_model"]
     with Session() as s:
         s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_NONE, lr=0.01)
-        loss = torch.zeros(1, device=DEV)
-        s.step(i32(ids), i32(tg), loss)
+        loss, I, T = torch.zeros(1, device=DEV), i32(ids), i32(tg)
+        torch.cuda.synchronize()
+        s.step(I, T, loss)
         s.sync()
         # forward activations, layer by layer
         for l in range(cfg["n_layers"]):
@@ -108,7 +111,9 @@ def test_decoder_stack_with_local_heads_matches_oracle():
     ry, rdx, rgr, _ = OD.stack_fwd_bwd(w["layers"], q(x), q(dy), cfg, prec)
     with Session() as s:
         s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_TP, lr=0.0, bw_bytes_per_s=50_000_000_000)
-        s.step(bf(x), bf(dy))
+        X, DY = bf(x), bf(dy)
+        torch.cuda.synchronize()
+        s.step(X, DY)
         s.sync()
         assert_bf16_close(up(s.train_tensor("x_out", 1)).reshape(ry.shape), ry, "stack output", elem_slack=8e-3)
         assert rel_err(up(s.train_tensor("dx_in")).reshape(rdx.shape), rdx) <= 2e-2
@@ -132,8 +137,9 @@ def test_encoder_forward_matches_oracle(cfg):
         m = s.register_inference(shape, P.pack(shape, master))
         for b, sq in ((cfg["batch"], cfg["seq"]), (1, 5), (2, cfg["seq"] - 3)):
             ids = Y.token_ids(8 + b, b, sq, cfg["vocab"])
-            out = torch.zeros((b, sq, cfg["d_model"]), device=DEV, dtype=torch.bfloat16)
-            s.wait(s.submit_offline(m, i32(ids), out, b, sq))
+            I, out = i32(ids), torch.zeros((b, sq, cfg["d_model"]), device=DEV, dtype=torch.bfloat16)
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, b, sq))
             ref = OE.encoder_forward(w, ids, cfg, "bf16")
             assert_bf16_close(up(out), ref, f"encoder {b}x{sq}", elem_slack=1.5e-2)
 
