@@ -306,6 +306,10 @@ sif_status sif_sync_training(sif_ctx* ctx);
 sif_status sif_train_tensor(sif_ctx* ctx, sif_handle h, const char* name, int32_t layer, void** ptr_dev,
                             uint64_t* elems);
 
+/* Name of the index-th launch of the training step's kernel sequence ("qkv", "attn_scores", "bubble", ...), the
+ * same index a training-kernel trace record carries in `id`; null past the end. */
+const char* sif_train_op_name(sif_ctx* ctx, sif_handle h, uint32_t index);
+
 typedef struct sif_infer_desc {
   uint32_t struct_size;
   uint32_t online;               /* 0 = offline (token mechanism), 1 = online (pull-and-execute)        */
@@ -359,6 +363,14 @@ typedef struct sif_stats {
 sif_status sif_poll_stats(sif_ctx* ctx, sif_stats* out);
 /* Zeroes the accumulating counters (between measurement phases); requires both streams idle. */
 sif_status sif_reset_stats(sif_ctx* ctx);
+
+/* Event timing of the bf16 GEMM launches, for roofline reporting.  While on, every GEMM launch of both streams
+ * is bracketed by two HIP events on its own stream (at most 16384 launches per switch-on).  sif_profile_read
+ * (profiling switched off first; synchronises both streams) returns per layout variant v = a_layout*2 + b_layout
+ * the number of timed launches, their algorithmic floating-point operations (2mnk per batch; the lower triangle
+ * only for causal products) and the sum of their event-to-event times in seconds. */
+sif_status sif_profile_gemm(sif_ctx* ctx, uint32_t on);
+sif_status sif_profile_read(sif_ctx* ctx, uint64_t launches[4], double flops[4], double seconds[4]);
 
 /* One record of the device trace ring. */
 typedef struct sif_trace_rec {

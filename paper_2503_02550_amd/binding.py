@@ -399,3 +399,30 @@ def sif_read_trace(ctx, which, cap=65535):
     n = u32(0)
     check(lib.sif_read_trace(ctx, which, arr, cap, C.byref(n)))
     return [(arr[i].kind, arr[i].id, arr[i].decision, arr[i].reserved, arr[i].t0_ns, arr[i].t1_ns) for i in range(n.value)]
+
+
+_sig("sif_profile_gemm", i32, vp, u32)
+_sig("sif_profile_read", i32, vp, P(u64), P(C.c_double), P(C.c_double))
+
+
+def sif_profile_gemm(ctx, on):
+    return check(lib.sif_profile_gemm(ctx, 1 if on else 0))
+
+
+def sif_profile_read(ctx):
+    """Per GEMM layout variant (a_layout*2 + b_layout): (launches, algorithmic flops, seconds)."""
+    n, f, s = (u64 * 4)(), (C.c_double * 4)(), (C.c_double * 4)()
+    check(lib.sif_profile_read(ctx, n, f, s))
+    return [(n[i], f[i], s[i]) for i in range(4)]
+
+
+def sif_abi_version():
+    return lib.sif_abi_version()
+
+
+_sig("sif_train_op_name", C.c_char_p, vp, i32, u32)
+
+
+def sif_train_op_name(ctx, h, index):
+    n = lib.sif_train_op_name(ctx, h, index)
+    return n.decode() if n else None

@@ -97,12 +97,23 @@ static double gemm_cost_us(const sif_gemm_args& g) {
 }
 static double bytes_cost_us(double bytes) { return 3.0 + bytes / 2.0e6; }   // 2 TB/s plus launch latency
 
+// Floating-point operations the product needs: 2mnk per batch; a causal product touches only the lower
+// triangle of the square score matrix (s(s+1)/2 of its s*s entries).
+static double gemm_flops(const sif_gemm_args& g) {
+  const double batches = (double)g.batch_outer * g.batch_inner;
+  if (g.epilogue & SIF_EPI_CAUSAL_SKIP) return batches * 2.0 * g.k * (0.5 * g.m * (g.m + 1.0));
+  if (g.k_causal) return batches * 2.0 * g.n * (0.5 * g.m * (g.m + 1.0));
+  return batches * 2.0 * g.m * g.n * g.k;
+}
+
 static void emit_gemm(Plan& p, const char* name, const G& g) {
   Op op;
   op.name = name;
   const sif_gemm_args a = g.a;
   op.fn = [a](hipStream_t s, const KCtl& c) { return launch_gemm_bf16(&a, s, c); };
   op.cost_us = gemm_cost_us(a);
+  op.prof_class = (int32_t)(a.a_layout * 2 + a.b_layout);
+  op.flops = gemm_flops(a);
   p.push_back(std::move(op));
 }
 

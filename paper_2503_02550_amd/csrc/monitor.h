@@ -34,11 +34,13 @@ struct alignas(128) StreamRec {     // one per stream, in HBM
   uint64_t steps, step_ticks_sum, step_ticks_last;
   uint64_t bubble_ticks, filled_ticks, infer_ticks;
   uint64_t kernels_run, kernels_skipped, train_kernels;
+  // completion counters of the kernel currently running on this stream (see kernel_end)
+  uint32_t done_top;
+  alignas(128) uint32_t done_sub[64 * 32];
 };
 
 struct alignas(32) Slot {           // one per launch, ring indexed by launch number
-  uint32_t arrive;                  // blocks that entered the prologue
-  uint32_t done;                    // blocks that left the epilogue
+  uint32_t pad0, pad1;
   uint32_t decision;                // (launch number << 2) | 1 run | 2 skip
   uint32_t kind_id;                 // (kind << 28) | id
   uint64_t t0, t1;
@@ -48,7 +50,7 @@ struct Mirror {                     // pinned, coherent host memory
   // device -> host
   uint32_t t_launched, t_completed;
   uint32_t idle_seq, busy_seq, idle_site, pad0;
-  uint32_t i_done, i_skip_from, i_reset_ack, pad1;
+  uint32_t i_done, i_skip_from, i_reset_ack, gate_timeouts;
   uint64_t steps, step_ticks_sum, step_ticks_last;
   uint64_t bubble_ticks, filled_ticks, infer_ticks;
   uint64_t kernels_run, kernels_skipped, train_kernels;
@@ -81,6 +83,20 @@ template <typename T>
 __device__ __forceinline__ void st_sys(T* p, T v) {
   __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
+// Relaxed agent-scope accesses: they bypass the per-XCD L2 for this one word but imply no cache write-back or
+// invalidate (an acquire/release at agent scope costs a pass over the whole L2, too much to pay per block).
+template <typename T>
+__device__ __forceinline__ T ld_relaxed(const T* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void st_relaxed(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename T>
+__device__ __forceinline__ void st_sys_relaxed(T* p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 template <typename T>
 __device__ __forceinline__ T ld_sys(const T* p) {
   return __hip_atomic_load(p, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM);
@@ -105,38 +121,53 @@ __device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
 }
 
 // Kernel prologue.  Every thread calls it; returns false when the launch is skipped (the kernel must then do
-// nothing but call kernel_end(c, false)).  Deadlock-free: only blocks that arrived after the deciding block
-// wait, and the deciding block is running and waits for nothing.
+// nothing but call kernel_end(c, false)).
+//   * Block 0 of the grid stamps the start time and, for a gated launch, takes the decision and publishes it.
+//   * The other blocks of a gated launch read the published decision (a load, no read-modify-write: same-address
+//     atomics from thousands of blocks serialise at ~50 ns each).  Workgroups are dispatched in grid order, so
+//     block 0 is resident whenever any block is and waits for nothing; should the decision still not appear
+//     within the spin bound, the block poisons the window and skips, and the host re-runs the launch (every
+//     inference kernel writes only buffers it does not read, so a partial run can be repeated).
+//   * Blocks of an ungated launch never wait.
+__device__ __forceinline__ uint32_t linear_block() { return blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z); }
+
 __device__ __forceinline__ bool kernel_begin(const KCtl& c) {
   if (c.rec == nullptr) return true;
   __shared__ int s_run;
   if (first_thread()) {
     int run = 1;
-    uint32_t old = atomicAdd(&c.slot->arrive, 1u);
-    if (old == 0) {
+    if (linear_block() == 0) {
       uint64_t t0 = now_ticks();
       if (c.gate != nullptr) run = gate_decide(c, &t0) ? 1 : 0;
+      c.slot->kind_id = c.kind_id;
+      st_relaxed(&c.slot->t0, t0);
       if (run) {
-        st_agent(&c.slot->t0, t0);
-        c.slot->kind_id = c.kind_id;
-        st_agent(&c.rec->t_start, t0);
-        uint32_t l = ld_agent(&c.rec->launched) + 1;
-        st_agent(&c.rec->launched, l);
-        if ((c.kind_id >> 28) == kKindTrain) st_sys(&c.mir->t_launched, l);
+        st_relaxed(&c.rec->t_start, t0);
+        const uint32_t l = c.rec->launched + 1;
+        st_relaxed(&c.rec->launched, l);
+        if ((c.kind_id >> 28) == kKindTrain) st_sys_relaxed(&c.mir->t_launched, l);
       } else {
-        c.slot->t0 = t0;
         c.slot->t1 = t0;
-        c.slot->kind_id = c.kind_id;
         if (ld_agent(&c.rec->skip_from) == kNone) {
           st_agent(&c.rec->skip_from, c.kseq);
           st_sys(&c.mir->i_skip_from, c.kseq);
         }
+        st_sys(&c.mir->kernels_skipped, ++c.rec->kernels_skipped);
       }
-      st_agent(&c.slot->decision, (c.kseq << 2) | (run ? 1u : 2u));
-    } else {
-      uint32_t d;
-      while (((d = ld_agent(&c.slot->decision)) >> 2) != c.kseq) __builtin_amdgcn_s_sleep(2);
-      run = (d & 3u) == 1u;
+      st_relaxed(&c.slot->decision, (c.kseq << 2) | (run ? 1u : 2u));
+    } else if (c.gate != nullptr) {
+      uint32_t d = 0, spins = 0;
+      while (((d = ld_relaxed(&c.slot->decision)) >> 2) != c.kseq && ++spins < (1u << 18)) __builtin_amdgcn_s_sleep(4);
+      if ((d >> 2) == c.kseq) {
+        run = (d & 3u) == 1u;
+      } else {                           // block 0 never showed up: give the launch back to the host
+        run = 0;
+        if (ld_agent(&c.rec->skip_from) == kNone || ld_agent(&c.rec->skip_from) > c.kseq) {
+          st_agent(&c.rec->skip_from, c.kseq);
+          st_sys(&c.mir->i_skip_from, c.kseq);
+        }
+        st_sys(&c.mir->gate_timeouts, 1u);
+      }
     }
     s_run = run;
   }
@@ -144,44 +175,45 @@ __device__ __forceinline__ bool kernel_begin(const KCtl& c) {
   return s_run != 0;
 }
 
-// Kernel epilogue.  Every thread calls it after its last global store.  The last block to leave stamps the
-// end time, bumps the counters and re-arms the slot.
+// Kernel epilogue.  Every thread calls it after its last global store.  The last block of the grid to leave
+// stamps the end time and bumps the counters.  "Last" is found with a two-level count (64 sub-counters on
+// separate cache lines, then one top counter) so that no address sees more than blocks/64 + 64 atomics;
+// kernels of one stream never overlap, so the counters belong to the stream and the last block re-arms them.
 __device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
-  if (c.rec == nullptr) return;
+  if (c.rec == nullptr || !ran) return;
   __syncthreads();
   if (!first_thread()) return;
-  __threadfence();
-  uint32_t old = atomicAdd(&c.slot->done, 1u);
-  if (old + 1 != grid_blocks()) return;
-  c.slot->done = 0;
-  st_agent(&c.slot->arrive, 0u);
+  const uint32_t total = grid_blocks(), id = linear_block(), sub = id & 63u;
+  const uint32_t in_sub = (total - sub + 63u) >> 6;
+  uint32_t* cnt = c.rec->done_sub + sub * 32u;
+  if (atomicAdd(cnt, 1u) + 1u != in_sub) return;
+  *cnt = 0;
+  const uint32_t subs = total < 64u ? total : 64u;
+  if (atomicAdd(&c.rec->done_top, 1u) + 1u != subs) return;
+  c.rec->done_top = 0;
   Mirror* m = c.mir;
   StreamRec* r = c.rec;
-  if (!ran) {
-    st_sys(&m->kernels_skipped, ++r->kernels_skipped);
-    return;
-  }
-  uint64_t t1 = now_ticks();
-  uint64_t t0 = ld_agent(&c.slot->t0);
+  const uint64_t t1 = now_ticks();
+  const uint64_t t0 = ld_relaxed(&c.slot->t0);
   c.slot->t1 = t1;
-  st_agent(&c.rec->t_end, t1);
-  uint32_t done = ld_agent(&c.rec->completed) + 1;
-  st_agent(&c.rec->completed, done);
+  st_relaxed(&r->t_end, t1);
+  const uint32_t done = r->completed + 1;
+  st_relaxed(&r->completed, done);
   if ((c.kind_id >> 28) == kKindTrain) {
-    st_sys(&m->t_completed, done);
-    st_sys(&m->train_kernels, ++r->train_kernels);
+    st_sys_relaxed(&m->t_completed, done);
+    st_sys_relaxed(&m->train_kernels, ++r->train_kernels);
   } else {
     uint64_t dur = t1 - t0, fill = dur;
     if (c.gate != nullptr) {
-      uint64_t ib = ld_agent(&c.gate->t_idle_begin);
-      uint64_t end = (ld_agent(&c.gate->state) == kStateIdle) ? t1 : ld_agent(&c.gate->t_busy_begin);
-      uint64_t lo = t0 > ib ? t0 : ib, hi = t1 < end ? t1 : end;
+      const uint64_t ib = ld_agent(&c.gate->t_idle_begin);
+      const uint64_t end = (ld_agent(&c.gate->state) == kStateIdle) ? t1 : ld_agent(&c.gate->t_busy_begin);
+      const uint64_t lo = t0 > ib ? t0 : ib, hi = t1 < end ? t1 : end;
       fill = hi > lo ? hi - lo : 0;
     }
-    st_sys(&m->infer_ticks, r->infer_ticks += dur);
-    st_sys(&m->filled_ticks, r->filled_ticks += fill);
-    st_sys(&m->kernels_run, ++r->kernels_run);
-    st_sys(&m->i_done, c.kseq);
+    st_sys_relaxed(&m->infer_ticks, r->infer_ticks += dur);
+    st_sys_relaxed(&m->filled_ticks, r->filled_ticks += fill);
+    st_sys_relaxed(&m->kernels_run, ++r->kernels_run);
+    st_sys(&m->i_done, c.kseq);          // release: the kernel's results are complete before the host sees this
   }
 }
 

