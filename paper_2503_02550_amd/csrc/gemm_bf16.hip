@@ -9,8 +9,8 @@
 //
 // Tiling: 128x128 block tile, K step 64, 256 threads = 4 wavefronts in a 2x2 grid, each wavefront owns a 64x64
 // tile as 2x2 v_mfma_f32_32x32x16_bf16 accumulators.  Operand tiles are staged through LDS with K contiguous
-// (row stride 72 elements so that 16-byte reads of consecutive rows spread over the banks); an operand whose
-// memory layout has the other dimension contiguous is transposed while it is written to LDS.  Global loads of
+// (unpadded rows of 128 bytes, XOR-swizzled in 16-byte chunks so that reads and writes spread over the banks); an operand whose
+// memory layout has the other dimension contiguous is transposed in registers (4x8 blocks) on its way to LDS.  Global loads of
 // the next K step are issued before the MFMAs of the current one (register prefetch, two LDS buffers).
 //
 // Results do not depend on the grid: each output element is reduced over K in one fixed order by one
@@ -21,7 +21,7 @@
 
 namespace sif {
 
-constexpr int BM = 128, BN = 128, BK = 64, LDS_LD = BK + 8;
+constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int GEMM_THREADS = 256;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -29,56 +29,91 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct GemmP {
   const bf16_t* a; const bf16_t* b; void* c; const bf16_t* bias; const void* res; bf16_t* aux;
-  uint32_t m, n, k, lda, ldb, ldc, epi, k_causal, batch_inner;
+  uint32_t m, n, k, lda, ldb, ldc, epi, k_causal, batch_inner, tiles_m, tiles_n;
   long long a_so, a_si, b_so, b_si, c_so, c_si;
   float alpha;
 };
 
-// Loads one 128 x 64 operand tile into registers (4 x 16 bytes per thread).  LAYOUT 0: memory [row][k];
-// LAYOUT 1: memory [k][row].  Vectors outside the logical extents read as zero.
+// LDS tile: 128 rows x 64 k (bf16), 128 bytes per row = eight 16-byte chunks, no padding.  Chunk c of row r
+// lives at chunk position c ^ key(r).  The key makes eight consecutive rows use eight different chunk positions
+// (conflict-free 16-byte reads with 32 banks) and sixteen consecutive rows sixteen different (row parity, position)
+// pairs (conflict-free with 64 banks) for the same logical chunk, which is how the MFMA operands are read.
+__device__ __forceinline__ uint32_t swz_key(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
+__device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) { return row * BK + ((chunk ^ swz_key(row)) << 3); }
+
+// Loads one 128 x 64 operand tile into registers (4 x 16 bytes per thread).
+//   LAYOUT 0: memory [row][k]: thread vector v covers row v/8, k chunk v%8.
+//   LAYOUT 1: memory [k][row]: thread t covers rows 8*((t%64)/4).. +7 ... see store_tile; its four vectors are
+//             four consecutive k rows, eight tile rows wide.
+// Vectors outside the logical extents read as zero.
 template <int LAYOUT>
 __device__ __forceinline__ void load_tile(uint4 (&r)[4], const bf16_t* __restrict__ base, uint32_t ld, uint32_t row0,
                                           uint32_t rows, uint32_t k0, uint32_t k_end) {
+  if (LAYOUT == 0) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t v = threadIdx.x + i * GEMM_THREADS;
-    uint32_t rr, kk;
-    if (LAYOUT == 0) { rr = row0 + (v >> 3); kk = k0 + (v & 7) * 8; }
-    else { kk = k0 + (v >> 4); rr = row0 + (v & 15) * 8; }
-    bool ok = rr < rows && kk < k_end;
-    const bf16_t* p = LAYOUT == 0 ? base + (size_t)rr * ld + kk : base + (size_t)kk * ld + rr;
-    r[i] = ok ? *reinterpret_cast<const uint4*>(p) : make_uint4(0, 0, 0, 0);
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t v = threadIdx.x + i * GEMM_THREADS;
+      const uint32_t rr = row0 + (v >> 3), kk = k0 + (v & 7) * 8;
+      r[i] = (rr < rows && kk < k_end) ? *reinterpret_cast<const uint4*>(base + (size_t)rr * ld + kk) : make_uint4(0, 0, 0, 0);
+    }
+  } else {
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t rr = row0 + (lane >> 2) * 8, kq = (wave * 4 + (lane & 3)) * 4;     // 8 tile rows, 4 k rows
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t kk = k0 + kq + i;
+      r[i] = (rr < rows && kk < k_end) ? *reinterpret_cast<const uint4*>(base + (size_t)kk * ld + rr) : make_uint4(0, 0, 0, 0);
+    }
   }
 }
 
 template <int LAYOUT>
 __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&r)[4]) {
+  if (LAYOUT == 0) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t v = threadIdx.x + i * GEMM_THREADS;
-    if (LAYOUT == 0) {
-      uint32_t rr = v >> 3, kk = (v & 7) * 8;
-      *reinterpret_cast<uint4*>(lds + rr * LDS_LD + kk) = r[i];
-    } else {
-      uint32_t kk = v >> 4, rr = (v & 15) * 8;
-      uint32_t w[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t v = threadIdx.x + i * GEMM_THREADS;
+      *reinterpret_cast<uint4*>(lds + lds_off(v >> 3, v & 7)) = r[i];
+    }
+  } else {
+    // 4 (k) x 8 (row) block held as four row vectors -> eight 4-element k runs, one per tile row
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t r0 = (lane >> 2) * 8, kq = (wave * 4 + (lane & 3)) * 4;
+    const uint32_t w0[4] = {r[0].x, r[0].y, r[0].z, r[0].w}, w1[4] = {r[1].x, r[1].y, r[1].z, r[1].w};
+    const uint32_t w2[4] = {r[2].x, r[2].y, r[2].z, r[2].w}, w3[4] = {r[3].x, r[3].y, r[3].z, r[3].w};
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        lds[(rr + 2 * j) * LDS_LD + kk] = (bf16_t)(w[j] & 0xFFFFu);
-        lds[(rr + 2 * j + 1) * LDS_LD + kk] = (bf16_t)(w[j] >> 16);
-      }
+    for (int j = 0; j < 4; ++j) {
+      uint2 even, odd;
+      even.x = (w0[j] & 0xFFFFu) | (w1[j] << 16);  even.y = (w2[j] & 0xFFFFu) | (w3[j] << 16);
+      odd.x = (w0[j] >> 16) | (w1[j] & 0xFFFF0000u);  odd.y = (w2[j] >> 16) | (w3[j] & 0xFFFF0000u);
+      const uint32_t ra = r0 + 2 * j, rb = ra + 1;
+      *reinterpret_cast<uint2*>(lds + lds_off(ra, kq >> 3) + (kq & 7)) = even;
+      *reinterpret_cast<uint2*>(lds + lds_off(rb, kq >> 3) + (kq & 7)) = odd;
     }
   }
 }
 
 template <int ALAY, int BLAY>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);            // [2][BM][LDS_LD]
-  bf16_t* sB = sA + 2 * BM * LDS_LD;                           // [2][BN][LDS_LD]
+  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);            // [2][BM][BK], swizzled
+  bf16_t* sB = sA + 2 * BM * BK;                               // [2][BN][BK]
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
 
-  const uint32_t m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // Block -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
+  // every XCD a contiguous run of tiles, and walk each run in bands of 8 tile rows, so that the tiles an XCD works
+  // on at one time share their A and B panels in that XCD's L2.
+  uint32_t tile_m, tile_n;
+  {
+    const uint32_t total = p.tiles_m * p.tiles_n, pid = blockIdx.x;
+    const uint32_t per = (total + 7) / 8, tall = (total % 8) ? (total % 8) : 8, xcd = pid % 8, local = pid / 8;
+    const uint32_t logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+    const uint32_t width = 8 * p.tiles_n, group = logical / width, first = group * 8;
+    const uint32_t gsz = min(p.tiles_m - first, 8u), in = logical % width;
+    tile_m = first + in % gsz;
+    tile_n = in / gsz;
+  }
+  const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
   const bool skip = (p.epi & SIF_EPI_CAUSAL_SKIP) && n0 > m0 + BM - 1;
   if (!skip) {
     const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
@@ -98,29 +133,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmP p, KCtl c
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 ra[4], rb[4];
-    load_tile<ALAY>(ra, A, p.lda, m0, p.m, k_begin, k_end);
-    load_tile<BLAY>(rb, B, p.ldb, n0, p.n, k_begin, k_end);
-    store_tile<ALAY>(sA, ra);
-    store_tile<BLAY>(sB, rb);
-    __syncthreads();
-
-    int buf = 0;
-    for (uint32_t k0 = k_begin; k0 < k_end; k0 += BK) {
-      const bool more = k0 + BK < k_end;
-      if (more) {
-        load_tile<ALAY>(ra, A, p.lda, m0, p.m, k0 + BK, k_end);
-        load_tile<BLAY>(rb, B, p.ldb, n0, p.n, k0 + BK, k_end);
-      }
-      const bf16_t* cA = sA + buf * BM * LDS_LD + (wm * 64 + (lane & 31)) * LDS_LD + (lane >> 5) * 8;
-      const bf16_t* cB = sB + buf * BN * LDS_LD + (wn * 64 + (lane & 31)) * LDS_LD + (lane >> 5) * 8;
+    // Register prefetch two K steps deep: set[t & 1] carries tile t from global memory to LDS.  While tile t is
+    // multiplied out of LDS buffer t & 1, tile t+1 is landing in the other set and the load of tile t+2 is issued
+    // into the set tile t has just left, so every global load has two iterations of MFMA work to hide behind.
+    uint4 ra0[4], rb0[4], ra1[4], rb1[4];
+    const uint32_t fra = wm * 64 + (lane & 31), frb = wn * 64 + (lane & 31), kh = lane >> 5;
+    auto compute = [&](int buf) {
+      const bf16_t* cA = sA + buf * BM * BK;
+      const bf16_t* cB = sB + buf * BN * BK;
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8 fa[2], fb[2];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          fa[i] = *reinterpret_cast<const bf16x8*>(cA + i * 32 * LDS_LD + ks * 16);
-          fb[i] = *reinterpret_cast<const bf16x8*>(cB + i * 32 * LDS_LD + ks * 16);
+          fa[i] = *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh));
+          fb[i] = *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + i * 32, ks * 2 + kh));
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -128,41 +155,117 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmP p, KCtl c
           for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
-      if (more) {
-        store_tile<ALAY>(sA + (buf ^ 1) * BM * LDS_LD, ra);
-        store_tile<BLAY>(sB + (buf ^ 1) * BN * LDS_LD, rb);
-      }
+    };
+    load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
+    load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
+    load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
+    load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
+    store_tile<ALAY>(sA, ra0);
+    store_tile<BLAY>(sB, rb0);
+    __syncthreads();
+    for (uint32_t k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
+      // even tile (LDS buffer 0); tile k0+BK is in set 1; fetch tile k0+2BK into set 0
+      load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
+      load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
+      compute(0);
+      if (k0 + BK >= k_end) break;
+      store_tile<ALAY>(sA + BM * BK, ra1);
+      store_tile<BLAY>(sB + BN * BK, rb1);
       __syncthreads();
-      buf ^= 1;
+      // odd tile (LDS buffer 1); tile k0+2BK is in set 0; fetch tile k0+3BK into set 1
+      load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
+      load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
+      compute(1);
+      if (k0 + 2 * BK >= k_end) break;
+      store_tile<ALAY>(sA, ra0);
+      store_tile<BLAY>(sB, rb0);
+      __syncthreads();
     }
 
-    // Epilogue.  Accumulator element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
-    const uint32_t epi = p.epi;
-    const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
+    // Epilogue.  The accumulators go through LDS (fp32, the 64 KB of the operand buffers) so that every global
+    // access of the epilogue - bias, residual, auxiliary tensor, result - is a 16-byte vector along a row.
+    // Accumulator element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
+    __syncthreads();
+    float* sC = reinterpret_cast<float*>(smem_raw);              // [128][128], 16-byte chunks XOR-swizzled by row
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const uint32_t n = n0 + wn * 64 + j * 32 + (lane & 31);
-      if (n >= p.n) continue;
-      const float bias = (p.bias != nullptr) ? bf2f(p.bias[n]) : 0.f;
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const uint32_t m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          if (m >= p.m) continue;
-          const size_t idx = c_off + (size_t)m * p.ldc + n;
-          float v = acc[i][j][r] * p.alpha + bias;
-          if (epi & SIF_EPI_GELU) {
-            if (p.aux != nullptr) p.aux[idx] = f2bf(v);
-            v = gelu_f(v);
+          const uint32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          const uint32_t col = wn * 64 + j * 32 + (lane & 31);
+          sC[row * BN + ((((col >> 2) ^ (row & 31)) << 2) | (col & 3))] = acc[i][j][r];
+        }
+    __syncthreads();
+    const uint32_t epi = p.epi;
+    const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
+    const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
+#pragma unroll 2
+    for (int it = 0; it < 8; ++it) {
+      const uint32_t ch = threadIdx.x + it * GEMM_THREADS;       // 2048 chunks of 8 columns
+      const uint32_t row = ch >> 4, col = (ch & 15) * 8;
+      const uint32_t m = m0 + row, n = n0 + col;
+      if (m >= p.m || n >= p.n) continue;
+      float v[8];
+      {
+        const float4 q0 = *reinterpret_cast<const float4*>(sC + row * BN + ((((col >> 2)) ^ (row & 31)) << 2));
+        const float4 q1 = *reinterpret_cast<const float4*>(sC + row * BN + ((((col >> 2) + 1) ^ (row & 31)) << 2));
+        v[0] = q0.x; v[1] = q0.y; v[2] = q0.z; v[3] = q0.w; v[4] = q1.x; v[5] = q1.y; v[6] = q1.z; v[7] = q1.w;
+      }
+      const size_t idx = c_off + (size_t)m * p.ldc + n;
+      if (vec_ok) {
+        float b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (p.bias != nullptr) {
+          const uint4 q = *reinterpret_cast<const uint4*>(p.bias + n);
+          b[0] = bflo(q.x); b[1] = bfhi(q.x); b[2] = bflo(q.y); b[3] = bfhi(q.y); b[4] = bflo(q.z); b[5] = bfhi(q.z); b[6] = bflo(q.w); b[7] = bfhi(q.w);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = v[e] * p.alpha + b[e];
+        if (epi & SIF_EPI_GELU) {
+          if (p.aux != nullptr)
+            *reinterpret_cast<uint4*>(p.aux + idx) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+        }
+        if (epi & SIF_EPI_GELU_GRAD) {
+          const uint4 q = *reinterpret_cast<const uint4*>(p.aux + idx);
+          const float z[8] = {bflo(q.x), bfhi(q.x), bflo(q.y), bfhi(q.y), bflo(q.z), bfhi(q.z), bflo(q.w), bfhi(q.w)};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(z[e]);
+        }
+        if (epi & SIF_EPI_OUT_F32) {
+          float* cp = reinterpret_cast<float*>(p.c) + idx;
+          if (epi & SIF_EPI_RESIDUAL) {
+            const float* rp = reinterpret_cast<const float*>(p.res) + idx;
+            const float4 r0 = *reinterpret_cast<const float4*>(rp), r1 = *reinterpret_cast<const float4*>(rp + 4);
+            v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
           }
-          if (epi & SIF_EPI_GELU_GRAD) v *= gelu_grad_f(bf2f(p.aux[idx]));
+          *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
+          *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+          if (epi & SIF_EPI_RESIDUAL) {
+            const uint4 q = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
+            v[0] += bflo(q.x); v[1] += bfhi(q.x); v[2] += bflo(q.y); v[3] += bfhi(q.y); v[4] += bflo(q.z); v[5] += bfhi(q.z); v[6] += bflo(q.w); v[7] += bfhi(q.w);
+          }
+          *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + idx) =
+              make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+        }
+      } else {
+        // ragged N (or an output slice that is not 16-byte aligned): one element at a time
+        for (int e = 0; e < 8 && n + e < p.n; ++e) {
+          float x = v[e] * p.alpha + (p.bias != nullptr ? bf2f(p.bias[n + e]) : 0.f);
+          if (epi & SIF_EPI_GELU) {
+            if (p.aux != nullptr) p.aux[idx + e] = f2bf(x);
+            x = gelu_f(x);
+          }
+          if (epi & SIF_EPI_GELU_GRAD) x *= gelu_grad_f(bf2f(p.aux[idx + e]));
           if (epi & SIF_EPI_OUT_F32) {
-            if (epi & SIF_EPI_RESIDUAL) v += reinterpret_cast<const float*>(p.res)[idx];
-            reinterpret_cast<float*>(p.c)[idx] = v;
+            if (epi & SIF_EPI_RESIDUAL) x += reinterpret_cast<const float*>(p.res)[idx + e];
+            reinterpret_cast<float*>(p.c)[idx + e] = x;
           } else {
-            if (epi & SIF_EPI_RESIDUAL) v += bf2f(reinterpret_cast<const bf16_t*>(p.res)[idx]);
-            reinterpret_cast<bf16_t*>(p.c)[idx] = f2bf(v);
+            if (epi & SIF_EPI_RESIDUAL) x += bf2f(reinterpret_cast<const bf16_t*>(p.res)[idx + e]);
+            reinterpret_cast<bf16_t*>(p.c)[idx + e] = f2bf(x);
           }
         }
       }
@@ -189,6 +292,11 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   if ((a->epilogue & SIF_EPI_RESIDUAL) && !a->res_dev) return fail(SIF_E_INVAL, "gemm: RESIDUAL needs res");
   if ((a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) == SIF_EPI_BIAS && !a->bias_dev) return fail(SIF_E_INVAL, "gemm: BIAS needs bias");
   if (a->k_causal > 2) return fail(SIF_E_INVAL, "gemm: bad k_causal");
+  if ((a->n & 7) == 0) {
+    // vector epilogue: rows of C, the residual and the auxiliary tensor are accessed 8 elements at a time
+    if ((a->ldc & 7) || ((a->c_stride_outer | a->c_stride_inner) & 7)) return fail(SIF_E_INVAL, "gemm: ldc and the output batch strides must be multiples of 8 when n is");
+    if ((a->bias_dev && !aligned16(a->bias_dev)) || (a->res_dev && !aligned16(a->res_dev)) || (a->aux_dev && !aligned16(a->aux_dev))) return fail(SIF_E_INVAL, "gemm: bias, residual and aux must be 16-byte aligned");
+  }
   GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;
   p.bias = (a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) ? (const bf16_t*)a->bias_dev : nullptr;
@@ -197,9 +305,10 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   p.epi = a->epilogue; p.k_causal = a->k_causal; p.batch_inner = a->batch_inner;
   p.a_so = a->a_stride_outer; p.a_si = a->a_stride_inner; p.b_so = a->b_stride_outer; p.b_si = a->b_stride_inner;
   p.c_so = a->c_stride_outer; p.c_si = a->c_stride_inner; p.alpha = a->alpha;
-  dim3 grid((a->n + BN - 1) / BN, (a->m + BM - 1) / BM, a->batch_outer * a->batch_inner);
-  if (grid.y > 65535 || grid.z > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
-  const size_t lds = (size_t)2 * (BM + BN) * LDS_LD * sizeof(bf16_t);
+  p.tiles_n = (a->n + BN - 1) / BN; p.tiles_m = (a->m + BM - 1) / BM;
+  dim3 grid(p.tiles_m * p.tiles_n, 1, a->batch_outer * a->batch_inner);
+  if (grid.z > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
+  const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
   typedef void (*kern_t)(GemmP, KCtl);
   static const kern_t table[2][2] = {{gemm_bf16_kernel<0, 0>, gemm_bf16_kernel<0, 1>},
                                      {gemm_bf16_kernel<1, 0>, gemm_bf16_kernel<1, 1>}};
