@@ -4,6 +4,11 @@ if the library is missing, importing this module raises."""
 import ctypes as C
 import os
 
+# torch supplies the device memory and the streams this library works on, so both must use ONE HIP runtime: torch
+# ships its own libamdhip64 and has to be loaded first, or the library would bind to a second runtime instance
+# whose devices, streams and pointers are not torch's.
+import torch  # noqa: F401  (load order)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspecinf.so")
 if not os.path.exists(LIB_PATH):

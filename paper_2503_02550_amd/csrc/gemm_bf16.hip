@@ -43,32 +43,48 @@ __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) { retu
 
 // Loads one 128 x 64 operand tile into registers (4 x 16 bytes per thread).
 //   LAYOUT 0: memory [row][k]: thread vector v covers row v/8, k chunk v%8.
-//   LAYOUT 1: memory [k][row]: thread t covers rows 8*((t%64)/4).. +7 ... see store_tile; its four vectors are
-//             four consecutive k rows, eight tile rows wide.
-// Vectors outside the logical extents read as zero.
+//   LAYOUT 1: memory [k][row]: a thread covers eight tile rows and four consecutive k rows (see store_tile).
+// Vectors outside the logical extents read as zero.  The loads are unconditional (an out-of-range vector reads
+// the operand's first element instead and is zeroed afterwards), so that they can be issued back to back and
+// waited for selectively.
 template <int LAYOUT>
-__device__ __forceinline__ void load_tile(uint4 (&r)[4], const bf16_t* __restrict__ base, uint32_t ld, uint32_t row0,
-                                          uint32_t rows, uint32_t k0, uint32_t k_end) {
+__device__ __forceinline__ uint32_t load_tile(uint4 (&r)[4], const bf16_t* __restrict__ base, uint32_t ld, uint32_t row0,
+                                              uint32_t rows, uint32_t k0, uint32_t k_end) {
+  bool ok[4];
+  const bf16_t* ptr[4];
   if (LAYOUT == 0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t v = threadIdx.x + i * GEMM_THREADS;
       const uint32_t rr = row0 + (v >> 3), kk = k0 + (v & 7) * 8;
-      r[i] = (rr < rows && kk < k_end) ? *reinterpret_cast<const uint4*>(base + (size_t)rr * ld + kk) : make_uint4(0, 0, 0, 0);
+      ok[i] = rr < rows && kk < k_end;
+      ptr[i] = ok[i] ? base + (size_t)rr * ld + kk : base;
     }
   } else {
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t rr = row0 + (lane >> 2) * 8, kq = (wave * 4 + (lane & 3)) * 4;     // 8 tile rows, 4 k rows
+    const uint32_t rr = row0 + (lane >> 2) * 8, kq = (wave * 4 + (lane & 3)) * 4;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t kk = k0 + kq + i;
-      r[i] = (rr < rows && kk < k_end) ? *reinterpret_cast<const uint4*>(base + (size_t)kk * ld + rr) : make_uint4(0, 0, 0, 0);
+      ok[i] = rr < rows && kk < k_end;
+      ptr[i] = ok[i] ? base + (size_t)kk * ld + rr : base;
     }
   }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = *reinterpret_cast<const uint4*>(ptr[i]);
+  // bit i set = vector i is inside the operand; applied when the registers are written to LDS, not here, so that
+  // nothing waits for the loads before their data is needed
+  return (ok[0] ? 1u : 0u) | (ok[1] ? 2u : 0u) | (ok[2] ? 4u : 0u) | (ok[3] ? 8u : 0u);
 }
 
 template <int LAYOUT>
-__device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&r)[4]) {
+__device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], uint32_t okmask) {
+  uint4 r[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t keep = (okmask >> i) & 1u ? 0xFFFFFFFFu : 0u;
+    r[i] = make_uint4(rin[i].x & keep, rin[i].y & keep, rin[i].z & keep, rin[i].w & keep);
+  }
   if (LAYOUT == 0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -156,29 +172,29 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCt
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
     };
-    load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
-    load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
-    load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
-    load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
-    store_tile<ALAY>(sA, ra0);
-    store_tile<BLAY>(sB, rb0);
+    uint32_t oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
+    uint32_t okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
+    uint32_t oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
+    uint32_t okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
+    store_tile<ALAY>(sA, ra0, oka0);
+    store_tile<BLAY>(sB, rb0, okb0);
     __syncthreads();
     for (uint32_t k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
       // even tile (LDS buffer 0); tile k0+BK is in set 1; fetch tile k0+2BK into set 0
-      load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
-      load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
+      oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
+      okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
       compute(0);
       if (k0 + BK >= k_end) break;
-      store_tile<ALAY>(sA + BM * BK, ra1);
-      store_tile<BLAY>(sB + BN * BK, rb1);
+      store_tile<ALAY>(sA + BM * BK, ra1, oka1);
+      store_tile<BLAY>(sB + BN * BK, rb1, okb1);
       __syncthreads();
       // odd tile (LDS buffer 1); tile k0+2BK is in set 0; fetch tile k0+3BK into set 1
-      load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
-      load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
+      oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
+      okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
       compute(1);
       if (k0 + 2 * BK >= k_end) break;
-      store_tile<ALAY>(sA, ra0);
-      store_tile<BLAY>(sB, rb0);
+      store_tile<ALAY>(sA, ra0, oka0);
+      store_tile<BLAY>(sB, rb0, okb0);
       __syncthreads();
     }
 

@@ -121,16 +121,31 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
   kernel_end(ctl, true);
 }
 
+// Sum of `parts` rows of partial sums per column, in a fixed order: 1024 threads = 16 wavefronts x 64 columns;
+// wavefront w adds rows w, w+16, ... in ascending order, then the 16 partial sums are added in ascending w.
+__device__ __forceinline__ float fin_column(const float* __restrict__ part, uint32_t parts, uint32_t n, uint32_t col, float* sm) {
+  const uint32_t w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float s = 0.f;
+  if (col < n)
+    for (uint32_t p = w; p < parts; p += 16) s += part[(size_t)p * n + col];
+  __syncthreads();
+  sm[w * 64 + lane] = s;
+  __syncthreads();
+  float t = 0.f;
+  if (w == 0)
+    for (int i = 0; i < 16; ++i) t += sm[i * 64 + lane];
+  return t;
+}
+
 // out[c] = bf16(sum_p part[p][c]) for dg (first `parts` rows) and db (next `parts` rows).
-__global__ __launch_bounds__(256) void layernorm_bwd_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ dg,
-                                                                bf16_t* __restrict__ db, uint32_t parts, uint32_t d, KCtl ctl) {
+__global__ __launch_bounds__(1024) void layernorm_bwd_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ dg,
+                                                                 bf16_t* __restrict__ db, uint32_t parts, uint32_t d, KCtl ctl) {
+  __shared__ float sm[1024];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
-  const uint32_t c = blockIdx.x * 256 + threadIdx.x;
-  if (c < d) {
-    float sg = 0.f, sb = 0.f;
-    for (uint32_t p = 0; p < parts; ++p) { sg += part[(size_t)p * d + c]; sb += part[(size_t)(parts + p) * d + c]; }
-    dg[c] = f2bf(sg); db[c] = f2bf(sb);
-  }
+  const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const float sg = fin_column(part, parts, d, c, sm);
+  const float sb = fin_column(part + (size_t)parts * d, parts, d, c, sm);
+  if (threadIdx.x < 64 && c < d) { dg[c] = f2bf(sg); db[c] = f2bf(sb); }
   kernel_end(ctl, true);
 }
 
@@ -162,15 +177,13 @@ __global__ __launch_bounds__(256) void colsum_part_kernel(const bf16_t* __restri
   kernel_end(ctl, true);
 }
 
-__global__ __launch_bounds__(256) void colsum_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
-                                                         uint32_t parts, uint32_t n, KCtl ctl) {
+__global__ __launch_bounds__(1024) void colsum_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
+                                                          uint32_t parts, uint32_t n, KCtl ctl) {
+  __shared__ float sm[1024];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
-  const uint32_t c = blockIdx.x * 256 + threadIdx.x;
-  if (c < n) {
-    float s = 0.f;
-    for (uint32_t p = 0; p < parts; ++p) s += part[(size_t)p * n + c];
-    out[c] = f2bf(s);
-  }
+  const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const float t = fin_column(part, parts, n, c, sm);
+  if (threadIdx.x < 64 && c < n) out[c] = f2bf(t);
   kernel_end(ctl, true);
 }
 
@@ -479,7 +492,7 @@ sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g,
 
 sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c) {
   REQ(part && dg && db, "layernorm_bwd_fin: null");
-  hipLaunchKernelGGL(layernorm_bwd_fin_kernel, dim3((d + 255) / 256), dim3(256), 0, s, part, (bf16_t*)dg, (bf16_t*)db,
+  hipLaunchKernelGGL(layernorm_bwd_fin_kernel, dim3((d + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)dg, (bf16_t*)db,
                      colsum_parts(rows), d, c);
   return check_launch("layernorm_bwd_fin");
 }
@@ -494,7 +507,7 @@ sif_status launch_colsum_part(const void* x, uint32_t ld, float* part, uint32_t 
 
 sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c) {
   REQ(part && out, "colsum_fin: null");
-  hipLaunchKernelGGL(colsum_fin_kernel, dim3((n + 255) / 256), dim3(256), 0, s, part, (bf16_t*)out, colsum_parts(rows), n, c);
+  hipLaunchKernelGGL(colsum_fin_kernel, dim3((n + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)out, colsum_parts(rows), n, c);
   return check_launch("colsum_fin");
 }
 
