@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-sample", type=int, default=8, help="samples for the CPU oracle baseline (0 = skip)")
+    ap.add_argument("--online-requests", type=int, default=1000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--small", action="store_true", help="reduced shapes (development only; not a valid measurement)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -72,11 +73,15 @@ def main():
     dshape, eshape = decoder_shape(dec), encoder_shape(enc)
     to = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).to(dev).to(dt)
 
+    dec_master = P.pack(dshape, Y.decoder_params(1, dec))
+    enc_master = P.pack(eshape, Y.encoder_params(2, enc))
+    ids_np, tg_np = Y.token_ids(3, dec["batch"], dec["seq"], dec["vocab"]), Y.token_ids(4, dec["batch"], dec["seq"], dec["vocab"])
+
+    # ================= offline phase (configs[1]): the headline measurement =====================================
     with Session() as s:
-        s.register_training(dshape, P.pack(dshape, Y.decoder_params(1, dec)), par_mode=S.SIF_PAR_DP, lr=dec["lr"],
-                            bw_bytes_per_s=dec["bw_bytes_per_s"])
-        m = s.register_inference(eshape, P.pack(eshape, Y.encoder_params(2, enc)))
-        ids, tg = to(Y.token_ids(3, dec["batch"], dec["seq"], dec["vocab"]), torch.int32), to(Y.token_ids(4, dec["batch"], dec["seq"], dec["vocab"]), torch.int32)
+        s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
+        m = s.register_inference(eshape, enc_master)
+        ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
         eids = to(Y.token_ids(5, enc["batch"], enc["seq"], enc["vocab"]), torch.int32)
         outs = [torch.zeros((enc["batch"], enc["seq"], enc["d_model"]), device=dev, dtype=torch.bfloat16) for _ in range(4)]
         torch.cuda.synchronize()
@@ -86,7 +91,7 @@ def main():
             for _ in range(n):
                 s.step(ids, tg)
 
-        # ---- solo training: the barrier releases nothing --------------------------------------------------
+        # solo training: the barrier releases nothing
         S.sif_set_collocate(s.ctx, 0)
         run_steps(W)
         s.sync()
@@ -94,13 +99,13 @@ def main():
         run_steps(K)
         s.sync()
         solo_s = time.perf_counter() - t0
-        solo_dev_ns = s.stats().step_ns_last
 
-        # ---- collocated: offline batches queued ahead, released into the bubbles ---------------------------
+        # collocated: offline batches queued ahead, released into the bubbles
         S.sif_reset_stats(s.ctx)
         S.sif_set_collocate(s.ctx, 1)
         per_step = 16
-        tickets = [s.submit_offline(m, eids, outs[i % 4], enc["batch"], enc["seq"]) for i in range(min(4000, (K + W + 1) * per_step))]
+        for i in range(min(4000, (K + W + 1) * per_step)):
+            s.submit_offline(m, eids, outs[i % 4], enc["batch"], enc["seq"])
         run_steps(W)
         s.sync()
         st0 = s.stats()
@@ -113,6 +118,60 @@ def main():
         st1 = s.stats()
         S.sif_profile_gemm(s.ctx, 0)
         prof = S.sif_profile_read(s.ctx)
+
+    # ================= online phase (configs[4]): same training step, Poisson requests, batch 1 ==================
+    # Run at the configured 200 req/s and at a quarter of it: one 4.98 ms bubble per ~34 ms step holds only a few
+    # batch-1 requests (each is ~110 launch-bound kernels), so the configured rate can exceed what the bubbles of one
+    # GPU can serve; the second rate shows the latency of a load the bubbles do hold.
+    online = None
+    if args.online_requests > 0:
+        import threading
+        onl = dict(enc, batch=1, seq=Y.ONLINE["seq_max"])
+        oshape = encoder_shape(onl)
+        online = {}
+        with Session() as s:
+            s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
+            mo = s.register_inference(oshape, enc_master, online=True)
+            ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
+            oids = to(Y.token_ids(7, 1, Y.ONLINE["seq_max"], enc["vocab"]), torch.int32)
+            oouts = [torch.zeros((1, Y.ONLINE["seq_max"], enc["d_model"]), device=dev, dtype=torch.bfloat16) for _ in range(64)]
+            torch.cuda.synchronize()
+            slo = S.sif_calibrate(s.ctx, 3)
+            for _ in range(W):
+                s.step(ids, tg)
+            s.sync()
+            for rate, n_req in ((Y.ONLINE["rate_per_s"], args.online_requests), (Y.ONLINE["rate_per_s"] / 4, max(1, args.online_requests // 4))):
+                t_arr, seqs = Y.poisson_arrivals(6, rate, n_req, Y.ONLINE["seq_min"], Y.ONLINE["seq_max"])
+                S.sif_reset_stats(s.ctx)
+                t_start = S.sif_now_ns()
+
+                def submitter():
+                    for i in range(n_req):
+                        while S.sif_now_ns() - t_start < int(t_arr[i]):
+                            time.sleep(0.0002)
+                        s.submit_online(mo, oids, oouts[i % 64], int(seqs[i]), t_start + int(t_arr[i]))
+
+                th = threading.Thread(target=submitter)
+                th.start()
+                n_steps, t0 = 0, time.perf_counter()
+                while th.is_alive():
+                    s.step(ids, tg)
+                    s.sync()
+                    n_steps += 1
+                on_s = time.perf_counter() - t0
+                th.join()
+                drain = 0
+                while s.stats().online_done < n_req and drain < 400:      # bubbles for what is still queued
+                    s.step(ids, tg)
+                    s.sync()
+                    drain += 1
+                so = s.stats()
+                online[f"{rate:g}_req_per_s"] = {
+                    "requests": n_req, "served_during_arrivals_plus_drain": int(so.online_done), "drain_steps": drain,
+                    "p50_ms": so.online_p50_ns / 1e6, "p95_ms": so.online_p95_ns / 1e6,
+                    "ms_per_step": 1e3 * on_s / max(1, n_steps),
+                    "training_slowdown": (on_s / max(1, n_steps)) / (solo_s / K) - 1.0}
+            online["principle_2_ok"] = bool(slo == S.SIF_OK)
 
     samples = st1.offline_samples - st0.offline_samples
     bubble_ns = st1.bubble_ns - st0.bubble_ns
@@ -140,7 +199,8 @@ def main():
         "bubble_ms_per_step": bubble_ns / 1e6 / K,
         "inference_batches": int(st1.offline_batches - st0.offline_batches),
         "kernels_run": int(st1.kernels_run - st0.kernels_run), "kernels_skipped": int(st1.kernels_skipped - st0.kernels_skipped),
-        "online_p95_ms": None,
+        "online_p95_ms": online[f"{Y.ONLINE['rate_per_s']:g}_req_per_s"]["p95_ms"] if online else None,
+        "online": online,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "kernel": "gemm_bf16_kernel<0,0>", "launches": int(n00), "avg_us": (1e6 * t00 / n00) if n00 else None,

@@ -173,3 +173,60 @@ def test_training_that_never_idles_starves_inference_without_deadlock():
             s.wait(tk, 0.05) if st.offline_batches == 0 else (_ for _ in ()).throw(S.SifError(S.SIF_E_TIMEOUT, "done"))
         assert e.value.status == S.SIF_E_TIMEOUT
     # destroy cancelled the pending ticket and returned
+
+
+def test_online_requests_are_pulled_one_at_a_time_inside_bubbles():
+    """Online fill (Sec. 3.3 "Kernel Barrier", pull-and-execute): Poisson arrivals, batch 1, ragged lengths."""
+    import threading
+    import time
+    enc = dict(ENC, batch=1, seq=64)
+    shape, ishape = decoder_shape(DEC), encoder_shape(enc)
+    master = Y.encoder_params(2, enc, perturb=True)
+    n_req = 40
+    t_arr, seqs = Y.poisson_arrivals(7, 2000.0, n_req, 5, 64)          # 2000 req/s so that the test is short
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=2_000_000)
+        m = s.register_inference(ishape, P.pack(ishape, master), online=True)
+        assert S.sif_calibrate(s.ctx, 2) == S.SIF_OK                     # Principle-II holds: a request is shorter than a bubble
+        n_cal = last_launch(s)
+        ids = [i32(Y.token_ids(200 + i, 1, int(seqs[i]), enc["vocab"])) for i in range(n_req)]
+        outs = [torch.zeros((1, int(seqs[i]), enc["d_model"]), device=DEV, dtype=torch.bfloat16) for i in range(n_req)]
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        torch.cuda.synchronize()
+        tickets = [None] * n_req
+        t0 = S.sif_now_ns()
+
+        def submitter():
+            for i in range(n_req):
+                while S.sif_now_ns() - t0 < int(t_arr[i]):
+                    time.sleep(0.0002)
+                tickets[i] = s.submit_online(m, ids[i], outs[i], int(seqs[i]), t0 + int(t_arr[i]))
+
+        th = threading.Thread(target=submitter)
+        th.start()
+        steps = 0
+        while th.is_alive() or steps < 12:
+            s.step(x, t)
+            s.sync()
+            steps += 1
+        th.join()
+        for _ in range(6):                                             # a few more bubbles for the stragglers
+            s.step(x, t)
+        s.sync()
+        for tk in tickets:
+            s.wait(tk, 20.0)
+        st = s.stats()
+        bubbles, ran, skipped = bubbles_and_kernels(s, n_cal)
+        assert st.online_done == n_req and st.offline_batches == 0
+        assert 0 < st.online_p50_ns <= st.online_p95_ns
+        assert_starts_inside_bubbles(bubbles, ran)
+    w = OE.working_copy(master, "bf16")
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, master), online=True)
+        for i in (0, 11, 39):
+            idn = Y.token_ids(200 + i, 1, int(seqs[i]), enc["vocab"])
+            I, out = i32(idn), torch.zeros_like(outs[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_online(m, I, out, int(seqs[i])))
+            assert torch.equal(out, outs[i])
+            assert_bf16_close(up(outs[i]), OE.encoder_forward(w, idn, enc, "bf16"), "online request", elem_slack=1.5e-2)
