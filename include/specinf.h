@@ -185,6 +185,12 @@ sif_status sif_k_softmax_fwd(const float* s_dev, void* p_dev, uint32_t batch, ui
 sif_status sif_k_softmax_bwd(const float* dp_dev, const void* p_dev, void* ds_dev, uint32_t batch, uint32_t rows,
                              uint32_t cols, uint32_t ld, float scale, uint32_t causal, void* stream);
 
+/* Fused attention forward: o[b,s,h*dh:(h+1)*dh] = softmax(q k^T / sqrt(dh) [+ causal mask]) v per (batch, head),
+ * qkv bf16 [batch*seq][ld_qkv] with columns [q | k | v], each heads*d_head wide; o bf16 [batch*seq][ld_o].
+ * d_head must be 64 or 128.  Scores never leave the chip. */
+sif_status sif_k_attn_fwd(const void* qkv_dev, void* o_dev, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head,
+                          uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream);
+
 /* x[t,:] = wte[ids[t],:] + wpe[t % seq,:]   (bf16) */
 sif_status sif_k_embed_fwd(const int32_t* ids_dev, const void* wte_dev, const void* wpe_dev, void* x_dev,
                            uint32_t tokens, uint32_t seq, uint32_t d, void* stream);

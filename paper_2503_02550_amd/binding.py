@@ -431,3 +431,10 @@ _sig("sif_train_op_name", C.c_char_p, vp, i32, u32)
 def sif_train_op_name(ctx, h, index):
     n = lib.sif_train_op_name(ctx, h, index)
     return n.decode() if n else None
+
+
+_sig("sif_k_attn_fwd", i32, vp, vp, u32, u32, u32, u32, u32, u32, u32, vp)
+
+
+def sif_k_attn_fwd(qkv, o, batch, seq, heads, d_head, ld_qkv, ld_o, causal, stream=None):
+    return check(lib.sif_k_attn_fwd(ptr(qkv), ptr(o), batch, seq, heads, d_head, ld_qkv, ld_o, causal, stream_ptr(stream)))

@@ -529,7 +529,14 @@ sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_
     const bf16_t *w_pr = W + pm.at(L(l, "w_proj")), *b_pr = W + pm.at(L(l, "b_proj")), *g2 = W + pm.at(L(l, "ln2_g")), *be2 = W + pm.at(L(l, "ln2_b"));
     bf16_t* y = (l + 1 == s.n_layers) ? (bf16_t*)out_dev : x;
     emit_gemm_rows(p, "qkv", G(x, w_qkv, qkv, M, 3 * q.da, d, d, d, 3 * q.da).epi(SIF_EPI_BIAS, b_qkv), kernel_us_max);
-    emit_attention_fwd(p, q, qkv, scores, prob, o, false);
+    if (q.dh == 64 || q.dh == 128) {
+      // one fused kernel: scores stay on chip, two launches fewer per layer
+      const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh, da = q.da;
+      emit(p, "attn_fused", 4.0 + 4.0 * B * H * (double)S * S * dh / 3.0e8 + bytes_cost_us(8.0 * M * da),
+           [=](hipStream_t st, const KCtl& c) { return launch_attn_fwd(qkv, o, B, S, H, dh, 3 * da, da, 0, st, c); });
+    } else {
+      emit_attention_fwd(p, q, qkv, scores, prob, o, false);
+    }
     emit_gemm_rows(p, "attn_out", G(o, w_o, t, M, d, q.da, q.da, q.da, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, b_o, x), kernel_us_max);
     emit(p, "ln1", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g1, be1, x1, nullptr, nullptr, M, d, st, c); });
     emit_gemm_rows(p, "mlp_up", G(x1, w_fc, a, M, q.f, d, d, d, q.f).epi(SIF_EPI_GELU, b_fc), kernel_us_max);

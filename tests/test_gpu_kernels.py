@@ -258,3 +258,18 @@ def test_sgd_and_mse_and_colsum_f32():
     cs = torch.zeros(256, device=DEV)
     S.sif_k_colsum_f32(f32(y), 256, cs, 32, 256)
     assert_f32_close(up(cs), y.astype(np.float64).sum(0), "colsum f32", 1e-5)
+
+
+# ------------------------------------------------------------------------------------------------ fused attention
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("bsz,s,h,dh", [(2, 5, 2, 64), (3, 37, 2, 64), (2, 128, 3, 64), (2, 200, 2, 64), (1, 300, 2, 128), (2, 64, 1, 128)])
+def test_fused_attention_forward(bsz, s, h, dh, causal):
+    from oracle.decoder import attention_fwd
+    from oracle.numerics import Prec
+    da = h * dh
+    qkv = rnd(40, bsz, s, 3 * da)
+    Q = bf(qkv)
+    o = torch.full((bsz, s, da), 3.0, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_attn_fwd(Q, o, bsz, s, h, dh, 3 * da, da, causal)
+    ref, _ = attention_fwd(q(qkv), h, dh, bool(causal), Prec("bf16"))
+    assert_bf16_close(up(o), ref, f"fused attention s={s} dh={dh} causal={causal}", elem_slack=4e-3)
