@@ -297,8 +297,10 @@ sif_status sif_register_training_step(sif_ctx* ctx, const sif_train_desc* d, sif
 /* Enqueues one training step on the training stream and returns without waiting.
  *   MLP: inputs_dev fp32 [batch,d_in], targets_dev fp32 [batch,d_out].
  *   DECODER with vocab: inputs_dev / targets_dev int32 token ids [batch,seq].
- *   DECODER stack: inputs_dev fp32->(stored bf16) activations are taken as bf16 [batch,seq,d]; targets_dev is
- *   the upstream gradient, bf16 [batch,seq,d].
+ *   DECODER stack (vocab = 0): inputs_dev bf16 activations [batch,seq,d]; targets_dev the upstream gradient, bf16
+ *   [batch,seq,d].  With SIF_PAR_PP both carry pp_micro micro-batches, [pp_micro,batch,seq,d]; the step runs them
+ *   in the 1F1B order of stage pp_stage, accumulates the parameter gradients over the micro-batches and updates
+ *   once; outputs and input gradients of every micro-batch are kept as the tensors "y_all" and "dx_all".
  * loss_dev: fp32 device scalar written by the step (may be null).  Buffers must stay valid until the step
  * has run (sif_sync_training). */
 sif_status sif_run_training_step(sif_ctx* ctx, sif_handle h, const void* inputs_dev, const void* targets_dev,
@@ -307,7 +309,8 @@ sif_status sif_sync_training(sif_ctx* ctx);
 
 /* Device address of a named tensor inside the training workspace, for inspection after sif_sync_training:
  * "work" (working copy of all parameters), "grads" (all gradients, parameter layout; bf16 or fp32 as the
- * model), per layer: "ln1" "qkv" "prob" "o" "x_mid" "ln2" "z" "a" "x_out", and "logits", "x0".
+ * model), per layer: "ln1" "qkv" "prob" "o" "x_mid" "ln2" "z" "a" "x_out", and "logits", "x0", "dx_in", "y_all",
+ * "dx_all".
  * *elems = number of elements. */
 sif_status sif_train_tensor(sif_ctx* ctx, sif_handle h, const char* name, int32_t layer, void** ptr_dev,
                             uint64_t* elems);

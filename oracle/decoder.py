@@ -86,31 +86,39 @@ def _flat(t):
     return t.reshape(-1, t.shape[-1])
 
 
-def layer_bwd(p, dx_out, c, cfg, prec):
-    """Returns (dx_in, grads of this layer's parameters); every stored gradient is rounded by prec."""
+def layer_bwd(p, dx_out, c, cfg, prec, acc=None):
+    """Returns (dx_in, grads of this layer's parameters); every stored gradient is rounded by prec.
+    With `acc` (the gradients stored so far, micro-batch accumulation) each new gradient is added to the stored
+    one before it is rounded and stored again."""
     h, dh = cfg["n_heads"], cfg["d_head"]
     g = {}
+
+    def put(k, raw):
+        g[k] = prec.store(raw if acc is None else acc[k] + raw)
+
     dxo = _flat(dx_out)
-    g["b_proj"] = prec.store(dxo.sum(axis=0))
-    g["w_proj"] = prec.store(dxo.T @ _flat(c["a"]))
+    put("b_proj", dxo.sum(axis=0))
+    put("w_proj", dxo.T @ _flat(c["a"]))
     dz = prec.store((dx_out @ p["w_proj"]) * gelu_grad(c["z"]))
-    g["b_fc"] = prec.store(_flat(dz).sum(axis=0))
-    g["w_fc"] = prec.store(_flat(dz).T @ _flat(c["ln2"]))
+    put("b_fc", _flat(dz).sum(axis=0))
+    put("w_fc", _flat(dz).T @ _flat(c["ln2"]))
     dln2 = prec.store(dz @ p["w_fc"])
     dxl, dg, db = layernorm_bwd(dln2, c["x_mid"], p["ln2_g"], c["m2"], c["r2"])
-    g["ln2_g"], g["ln2_b"] = prec.store(dg), prec.store(db)
+    put("ln2_g", dg)
+    put("ln2_b", db)
     dx_mid = prec.store(dx_out + dxl)
 
     dxm = _flat(dx_mid)
-    g["b_o"] = prec.store(dxm.sum(axis=0))
-    g["w_o"] = prec.store(dxm.T @ _flat(c["o"]))
+    put("b_o", dxm.sum(axis=0))
+    put("w_o", dxm.T @ _flat(c["o"]))
     do = prec.store(dx_mid @ p["w_o"])
     dqkv = attention_bwd(do, c["qkv"], c["prob"], h, dh, prec)
-    g["b_qkv"] = prec.store(_flat(dqkv).sum(axis=0))
-    g["w_qkv"] = prec.store(_flat(dqkv).T @ _flat(c["ln1"]))
+    put("b_qkv", _flat(dqkv).sum(axis=0))
+    put("w_qkv", _flat(dqkv).T @ _flat(c["ln1"]))
     dln1 = prec.store(dqkv @ p["w_qkv"])
     dxl, dg, db = layernorm_bwd(dln1, c["x"], p["ln1_g"], c["m1"], c["r1"])
-    g["ln1_g"], g["ln1_b"] = prec.store(dg), prec.store(db)
+    put("ln1_g", dg)
+    put("ln1_b", db)
     dx_in = prec.store(dx_mid + dxl)
     return dx_in, g
 
@@ -136,6 +144,30 @@ def stack_fwd_bwd(layers, x, dy, cfg, prec):
     for i in reversed(range(len(layers))):
         dx, grads[i] = layer_bwd(layers[i], dx, caches[i], cfg, prec)
     return y, dx, grads, caches
+
+
+def stack_train_step_microbatched(master_layers, xs, dys, cfg, lr, prec_kind="bf16"):
+    """Pipeline-stage share of one training step: n_micro micro-batches (xs, dys: [n_micro, B, S, d]) go forward
+    and backward through the stage's blocks, parameter gradients accumulate over the micro-batches in the order
+    their backward passes run (0, 1, ...), then one SGD update.  The order in which forward and backward passes
+    interleave (1F1B) does not change any value: the parameters are constant within the step.
+    Returns (ys, dxs, new master layers, accumulated grads)."""
+    prec = Prec(prec_kind)
+    layers = working_copy({"layers": master_layers}, prec)["layers"]
+    ys, dxs, grads = [], [], [None] * len(layers)
+    for k in range(len(xs)):
+        x = prec.store(xs[k])
+        caches = []
+        for p in layers:
+            x, c = layer_fwd(p, x, cfg, prec)
+            caches.append(c)
+        ys.append(x)
+        dx = prec.store(dys[k])
+        for i in reversed(range(len(layers))):
+            dx, grads[i] = layer_bwd(layers[i], dx, caches[i], cfg, prec, grads[i])
+        dxs.append(dx)
+    new = sgd_update({"layers": master_layers}, {"layers": grads}, lr)["layers"]
+    return np.stack(ys), np.stack(dxs), new, grads
 
 
 def gpt_forward(w, ids, cfg, prec):

@@ -25,7 +25,7 @@ sif_status sif_k_layernorm_bwd(const void* dy, const void* x, const void* g, con
   if (!dg || !db) return fail(SIF_E_INVAL, "layernorm_bwd: null dg/db");
   sif_status st = launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, S(stream), no_ctl());
   if (st != SIF_OK) return st;
-  return launch_layernorm_bwd_fin(part, dg, db, rows, d, S(stream), no_ctl());
+  return launch_layernorm_bwd_fin(part, dg, db, rows, d, 0, S(stream), no_ctl());
 }
 
 uint32_t sif_colsum_parts(uint32_t rows) { return colsum_parts(rows); }
@@ -34,7 +34,7 @@ sif_status sif_k_colsum(const void* x, uint32_t ld, void* out, float* part, uint
   if (!out) return fail(SIF_E_INVAL, "colsum: null out");
   sif_status st = launch_colsum_part(x, ld, part, rows, n, S(stream), no_ctl());
   if (st != SIF_OK) return st;
-  return launch_colsum_fin(part, out, rows, n, S(stream), no_ctl());
+  return launch_colsum_fin(part, out, rows, n, 0, S(stream), no_ctl());
 }
 
 sif_status sif_k_softmax_fwd(const float* s, void* p, uint32_t batch, uint32_t rows, uint32_t cols, uint32_t ld_s,

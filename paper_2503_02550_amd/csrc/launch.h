@@ -24,11 +24,11 @@ sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, voi
 sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
                                    const void* res, void* dx, float* part, uint32_t rows, uint32_t d, hipStream_t s,
                                    const KCtl& c);
-sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, hipStream_t s,
+sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, uint32_t acc, hipStream_t s,
                                     const KCtl& c);
 sif_status launch_colsum_part(const void* x, uint32_t ld, float* part, uint32_t rows, uint32_t n, hipStream_t s,
                               const KCtl& c);
-sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c);
+sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, uint32_t acc, hipStream_t s, const KCtl& c);
 sif_status launch_softmax_fwd(const float* sc, void* p, uint32_t batch, uint32_t rows, uint32_t cols, uint32_t ld_s,
                               uint32_t ld_p, uint32_t causal, hipStream_t s, const KCtl& c);
 sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t batch, uint32_t rows, uint32_t cols,
@@ -51,6 +51,7 @@ sif_status launch_mse(const float* y, const float* t, float* d, float* loss, uin
 sif_status launch_colsum_f32(const float* x, uint32_t ld, float* out, uint32_t rows, uint32_t n, hipStream_t s,
                              const KCtl& c);
 sif_status launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s, const KCtl& c);
+sif_status launch_reduce_splits(const float* part, void* out, uint64_t n, uint32_t splits, uint32_t acc, hipStream_t s, const KCtl& c);
 sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c);
 
 uint32_t colsum_parts(uint32_t rows);

@@ -6,6 +6,7 @@
 //   inference : the same MLP forward, or a post-LN BERT-shaped encoder forward
 // Attention materialises the score matrix per (batch, head) with the batched GEMM; every reduction has a fixed
 // order, so a plan gives bit-identical results whenever and next to whatever it runs.
+#include <algorithm>
 #include <math.h>
 #include <string.h>
 
@@ -90,6 +91,9 @@ struct G {
   G& causal(uint32_t kc) { a.k_causal = kc; return *this; }
 };
 
+// scratch buffers of the backward pass, shared by all layers
+struct Scratch { float* scores; bf16_t* ds; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; float* part; float* split; uint64_t split_elems; };
+
 static double gemm_cost_us(const sif_gemm_args& g) {
   double flops = 2.0 * g.m * g.n * g.k * g.batch_outer * g.batch_inner;
   if (g.k_causal || (g.epilogue & SIF_EPI_CAUSAL_SKIP)) flops *= 0.55;
@@ -152,15 +156,40 @@ static void emit_bubble(Plan& p, int32_t site, uint64_t ns) {
   p.push_back(std::move(op));
 }
 
-static void emit_colsum(Plan& p, const char* name, const void* x, uint32_t ld, void* out, float* part, uint32_t rows, uint32_t n) {
+// Weight gradient dW[m_out, n_out] = A^T B with A stored [tokens][m_out], B stored [tokens][n_out].  The output has few
+// tiles and a long contraction (all tokens), so the contraction is cut into slices that run as a batch and write
+// fp32 partial products, which a second kernel adds in a fixed order: more blocks in flight, same result every run.
+static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t* b, bf16_t* dw, uint32_t m_out, uint32_t n_out,
+                       uint32_t tokens, const Scratch& sc, uint32_t acc) {
+  const uint32_t tiles = ((m_out + 127) / 128) * ((n_out + 127) / 128);
+  uint32_t splits = 1;
+  while (splits < 16 && tiles * splits * 2 <= 512 && tokens % (splits * 2) == 0 && (tokens / (splits * 2)) % 64 == 0 &&
+         (uint64_t)m_out * n_out * splits * 2 <= sc.split_elems)
+    splits *= 2;
+  if (splits == 1 || (n_out & 7)) {
+    G g(a, b, dw, m_out, n_out, tokens, m_out, n_out, n_out);
+    g.lay(SIF_A_ROW_M, SIF_B_ROW_N);
+    if (acc) g.epi(SIF_EPI_RESIDUAL, nullptr, dw);      // micro-batch accumulation: add to the stored gradient
+    emit_gemm(p, name, g);
+    return;
+  }
+  const uint32_t kper = tokens / splits;
+  emit_gemm(p, name, G(a, b, sc.split, m_out, n_out, kper, m_out, n_out, n_out).lay(SIF_A_ROW_M, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
+                         .batch(splits, 1, (int64_t)kper * m_out, 0, (int64_t)kper * n_out, 0, (int64_t)m_out * n_out, 0));
+  const float* part = sc.split;
+  const uint64_t n = (uint64_t)m_out * n_out;
+  emit(p, name, bytes_cost_us(4.0 * n * splits), [=](hipStream_t s, const KCtl& c) { return launch_reduce_splits(part, dw, n, splits, acc, s, c); });
+}
+
+static void emit_colsum(Plan& p, const char* name, const void* x, uint32_t ld, void* out, float* part, uint32_t rows, uint32_t n, uint32_t acc) {
   emit(p, name, bytes_cost_us(2.0 * rows * n), [=](hipStream_t s, const KCtl& c) { return launch_colsum_part(x, ld, part, rows, n, s, c); });
-  emit(p, name, 3.0, [=](hipStream_t s, const KCtl& c) { return launch_colsum_fin(part, out, rows, n, s, c); });
+  emit(p, name, 3.0, [=](hipStream_t s, const KCtl& c) { return launch_colsum_fin(part, out, rows, n, acc, s, c); });
 }
 
 static void emit_ln_bwd(Plan& p, const void* dy, const void* x, const void* g, const float* mean, const float* rstd, const void* res,
-                        void* dx, void* dg, void* db, float* part, uint32_t rows, uint32_t d) {
+                        void* dx, void* dg, void* db, float* part, uint32_t rows, uint32_t d, uint32_t acc) {
   emit(p, "ln_bwd", bytes_cost_us(8.0 * rows * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, s, c); });
-  emit(p, "ln_bwd_fin", 3.0, [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_fin(part, dg, db, rows, d, s, c); });
+  emit(p, "ln_bwd_fin", 3.0, [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_fin(part, dg, db, rows, d, acc, s, c); });
 }
 
 // ------------------------------------------------------------------------------------------ transformer block
@@ -212,7 +241,6 @@ struct LayerActs {       // saved by the forward pass of one decoder layer
 };
 struct LayerW { const bf16_t *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_fc, *b_fc, *w_proj, *b_proj; };
 struct LayerG { bf16_t *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_fc, *b_fc, *w_proj, *b_proj; };
-struct Scratch { float* scores; bf16_t* ds; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; float* part; };
 
 template <typename T, typename P>
 static T layer_ptrs(P* base, const ParamMap& pm, uint32_t l) {
@@ -242,25 +270,25 @@ static void emit_decoder_layer_fwd(Plan& p, const Dims& q, const LayerW& w, cons
 
 // dx_out -> dx_in (both bf16 [M,d]); gradients of the layer's parameters into g.  `tmp` is a second [M,d] buffer.
 static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, const LayerG& g, const bf16_t* x_in, const LayerActs& a,
-                                   const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp) {
+                                   const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp, uint32_t acc) {
   const uint32_t M = q.M, d = q.d, f = q.f, da = q.da;
-  emit_colsum(p, "db_proj", dx_out, d, g.b_proj, sc.part, M, d);
-  emit_gemm(p, "dw_proj", G(dx_out, a.a, g.w_proj, d, f, M, d, f, f).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_colsum(p, "db_proj", dx_out, d, g.b_proj, sc.part, M, d, acc);
+  emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, sc, acc);
   emit_gemm(p, "dz", G(dx_out, w.w_proj, sc.dz, M, f, d, d, f, f).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_GELU_GRAD, nullptr, nullptr, a.z));
-  emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, sc.part, M, f);
-  emit_gemm(p, "dw_fc", G(sc.dz, a.ln2, g.w_fc, f, d, M, f, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, sc.part, M, f, acc);
+  emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, sc, acc);
   emit_gemm(p, "dln2", G(sc.dz, w.w_fc, sc.dln, M, d, f, f, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
-  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, sc.part, M, d);
-  emit_colsum(p, "db_o", dx_mid, d, g.b_o, sc.part, M, d);
-  emit_gemm(p, "dw_o", G(dx_mid, a.o, g.w_o, d, da, M, d, da, da).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, sc.part, M, d, acc);
+  emit_colsum(p, "db_o", dx_mid, d, g.b_o, sc.part, M, d, acc);
+  emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, sc, acc);
   emit_gemm(p, "do", G(dx_mid, w.w_o, sc.d_o, M, da, d, d, da, da).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
-  emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, sc.part, M, 3 * da);
-  emit_gemm(p, "dw_qkv", G(sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, 3 * da, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+  emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, sc.part, M, 3 * da, acc);
+  emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, sc, acc);
   emit_gemm(p, "dln1", G(sc.dqkv, w.w_qkv, sc.dln, M, d, 3 * da, 3 * da, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
-  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, sc.part, M, d);
+  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, sc.part, M, d, acc);
 }
 
 // ------------------------------------------------------------------------------------------ training models
@@ -307,17 +335,26 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   const Dims q = dims_of(s, s.batch, s.seq);
   const uint32_t M = q.M, d = q.d, Vp = (s.vocab + 7) & ~7u;
   const uint64_t ssz = (uint64_t)q.B * q.H * q.S * q.Sp;
+  const bool pp = tm.desc.par_mode == SIF_PAR_PP;
+  // pipeline stage: n_micro micro-batches per step; a 1F1B stage holds the activations of at most
+  // (stages - stage) micro-batches at a time, so that many activation slots are enough
+  const uint32_t n_micro = pp ? tm.desc.pp_micro : 1;
+  const uint32_t n_slots = pp ? std::min(n_micro, tm.desc.pp_stages - tm.desc.pp_stage) : 1;
   bf16_t* work = (bf16_t*)ar.take(pm.n * 2);
   bf16_t* grads = (bf16_t*)ar.take(pm.n * 2);
-  std::vector<LayerActs> acts(s.n_layers);
-  for (auto& a : acts) {
-    a.ln1 = (bf16_t*)ar.take((uint64_t)M * d * 2); a.qkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
-    a.prob = (bf16_t*)ar.take(ssz * 2); a.o = (bf16_t*)ar.take((uint64_t)M * q.da * 2);
-    a.x_mid = (bf16_t*)ar.take((uint64_t)M * d * 2); a.ln2 = (bf16_t*)ar.take((uint64_t)M * d * 2);
-    a.z = (bf16_t*)ar.take((uint64_t)M * q.f * 2); a.a = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
-    a.x_out = (bf16_t*)ar.take((uint64_t)M * d * 2);
-    a.m1 = (float*)ar.take((uint64_t)M * 4); a.r1 = (float*)ar.take((uint64_t)M * 4);
-    a.m2 = (float*)ar.take((uint64_t)M * 4); a.r2 = (float*)ar.take((uint64_t)M * 4);
+  std::vector<std::vector<LayerActs>> acts(n_slots, std::vector<LayerActs>(s.n_layers));
+  std::vector<bf16_t*> x0(n_slots);
+  for (uint32_t sl = 0; sl < n_slots; ++sl) {
+    x0[sl] = (bf16_t*)ar.take((uint64_t)M * d * 2);
+    for (auto& a : acts[sl]) {
+      a.ln1 = (bf16_t*)ar.take((uint64_t)M * d * 2); a.qkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
+      a.prob = (bf16_t*)ar.take(ssz * 2); a.o = (bf16_t*)ar.take((uint64_t)M * q.da * 2);
+      a.x_mid = (bf16_t*)ar.take((uint64_t)M * d * 2); a.ln2 = (bf16_t*)ar.take((uint64_t)M * d * 2);
+      a.z = (bf16_t*)ar.take((uint64_t)M * q.f * 2); a.a = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
+      a.x_out = (bf16_t*)ar.take((uint64_t)M * d * 2);
+      a.m1 = (float*)ar.take((uint64_t)M * 4); a.r1 = (float*)ar.take((uint64_t)M * 4);
+      a.m2 = (float*)ar.take((uint64_t)M * 4); a.r2 = (float*)ar.take((uint64_t)M * 4);
+    }
   }
   Scratch sc;
   sc.scores = (float*)ar.take(ssz * 4); sc.ds = (bf16_t*)ar.take(ssz * 2);
@@ -327,7 +364,9 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   uint32_t widest = d > 3 * q.da ? d : 3 * q.da;
   if (q.f > widest) widest = q.f;
   sc.part = (float*)ar.take((uint64_t)2 * colsum_parts(M) * widest * 4);
-  bf16_t *x0 = (bf16_t*)ar.take((uint64_t)M * d * 2), *lnf = nullptr, *logits = nullptr;
+  sc.split_elems = (uint64_t)16 * 128 * 128 * 64;      // room for 512 tiles of 128x128 partial sums
+  sc.split = (float*)ar.take(sc.split_elems * 4);
+  bf16_t *lnf = nullptr, *logits = nullptr, *y_all = nullptr, *dx_all = nullptr;
   float *mf = nullptr, *rf = nullptr, *loss_tok = nullptr, *loss = nullptr;
   if (s.vocab) {
     lnf = (bf16_t*)ar.take((uint64_t)M * d * 2);
@@ -335,19 +374,25 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     mf = (float*)ar.take((uint64_t)M * 4); rf = (float*)ar.take((uint64_t)M * 4);
     loss_tok = (float*)ar.take((uint64_t)M * 4); loss = (float*)ar.take(256);
   }
+  if (pp) {
+    y_all = (bf16_t*)ar.take((uint64_t)n_micro * M * d * 2);
+    dx_all = (bf16_t*)ar.take((uint64_t)n_micro * M * d * 2);
+  }
   tm.workspace_bytes = ar.off;
   if (!ar.base) return SIF_OK;
 
   put(tm, "work", work, pm.n); put(tm, "grads", grads, pm.n);
-  for (uint32_t l = 0; l < s.n_layers; ++l) {
-    const LayerActs& a = acts[l];
+  for (uint32_t l = 0; l < s.n_layers; ++l) {      // named tensors refer to activation slot 0
+    const LayerActs& a = acts[0][l];
     const std::string sfx = "." + std::to_string(l);
     put(tm, "ln1" + sfx, a.ln1, (uint64_t)M * d); put(tm, "qkv" + sfx, a.qkv, (uint64_t)M * 3 * q.da); put(tm, "prob" + sfx, a.prob, ssz);
     put(tm, "o" + sfx, a.o, (uint64_t)M * q.da); put(tm, "x_mid" + sfx, a.x_mid, (uint64_t)M * d); put(tm, "ln2" + sfx, a.ln2, (uint64_t)M * d);
     put(tm, "z" + sfx, a.z, (uint64_t)M * q.f); put(tm, "a" + sfx, a.a, (uint64_t)M * q.f); put(tm, "x_out" + sfx, a.x_out, (uint64_t)M * d);
   }
-  put(tm, "x0", x0, (uint64_t)M * d);
+  put(tm, "x0", x0[0], (uint64_t)M * d);
+  put(tm, "dx_in", sc.dx_a, (uint64_t)M * d);
   if (s.vocab) { put(tm, "logits", logits, (uint64_t)M * Vp); put(tm, "lnf", lnf, (uint64_t)M * d); put(tm, "loss", loss, 1); }
+  if (pp) { put(tm, "y_all", y_all, (uint64_t)n_micro * M * d); put(tm, "dx_all", dx_all, (uint64_t)n_micro * M * d); }
 
   // gradients of position rows beyond seq are never written: clear the gradient buffer once
   hipError_t e = hipMemsetAsync(grads, 0, pm.n * 2, stream);
@@ -355,7 +400,6 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   sif_status st = launch_sgd_bf16(tm.desc.master_dev, nullptr, work, pm.n, 0.f, stream, no_ctl());
   if (st != SIF_OK) return st;
 
-  // bubble sites
   int32_t next_site = 0;
   TpSites tp{false, 0, &next_site};
   if (tm.desc.par_mode == SIF_PAR_TP) {
@@ -364,65 +408,120 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     tm.max_bubble_ns = tp.ns;
   }
   TrainModel* t = &tm;
-  Plan& p = tm.plan;
   const uint32_t seq = q.S, V = s.vocab;
-  const bf16_t* x_in = nullptr;
-  if (s.vocab) {
-    const bf16_t *wte = work + pm.at("wte"), *wpe = work + pm.at("wpe");
-    emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_fwd((const int32_t*)t->cur_inputs, wte, wpe, x0, M, seq, d, s2, c); });
-  } else {
-    // layer stack: the caller's activations become the input of the first layer
-    const uint64_t bytes = (uint64_t)M * d * 2;
-    emit(p, "stage_x", bytes_cost_us(2.0 * bytes), [=](hipStream_t s2, const KCtl& c) { return launch_copy(x0, t->cur_inputs, bytes, s2, c); });
-  }
-  x_in = x0;
-  for (uint32_t l = 0; l < s.n_layers; ++l) {
-    const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
-    emit_decoder_layer_fwd(p, q, w, x_in, acts[l], sc, tp);
-    x_in = acts[l].x_out;
-  }
-  const bf16_t* dx = nullptr;       // gradient flowing into the last layer
-  if (s.vocab) {
-    const bf16_t *wte = work + pm.at("wte"), *lnf_g = work + pm.at("lnf_g"), *lnf_b = work + pm.at("lnf_b");
-    const bf16_t* x_last = x_in;
-    emit(p, "lnf", bytes_cost_us(4.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_layernorm_fwd(x_last, lnf_g, lnf_b, lnf, mf, rf, M, d, s2, c); });
-    emit_gemm(p, "lm_head", G(lnf, wte, logits, M, V, d, d, d, Vp));
-    emit(p, "xent", bytes_cost_us(4.0 * M * Vp), [=](hipStream_t s2, const KCtl& c) { return launch_xent(logits, (const int32_t*)t->cur_targets, loss_tok, M, V, Vp, s2, c); });
-    emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
-    emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
-    emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
-    emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"), sc.part, M, d);
-    dx = sc.dx_a;
-  }
-  for (int32_t l = (int32_t)s.n_layers - 1; l >= 0; --l) {
-    const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
-    const LayerG g = layer_ptrs<LayerG, bf16_t>(grads, pm, l);
-    // dx_out in dx_a (or the caller's gradient for the top of a stack), dx_mid -> dx_b, dx_in -> dx_a
-    if (l == (int32_t)s.n_layers - 1 && !s.vocab) {
+  const uint64_t mb_bytes = (uint64_t)M * d * 2;
+
+  // forward pass of micro-batch k into activation slot k % n_slots
+  auto emit_forward = [&](Plan& p, uint32_t k) {
+    const uint32_t sl = k % n_slots;
+    bf16_t* xin0 = x0[sl];
+    if (s.vocab) {
+      const bf16_t *wte = work + pm.at("wte"), *wpe = work + pm.at("wpe");
+      emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_fwd((const int32_t*)t->cur_inputs, wte, wpe, xin0, M, seq, d, s2, c); });
+    } else {
+      // layer stack: the caller's activations become the input of the first layer
+      emit(p, "stage_x", bytes_cost_us(2.0 * mb_bytes), [=](hipStream_t s2, const KCtl& c) {
+        return launch_copy(xin0, (const unsigned char*)t->cur_inputs + (size_t)k * mb_bytes, mb_bytes, s2, c); });
+    }
+    const bf16_t* x_in = xin0;
+    for (uint32_t l = 0; l < s.n_layers; ++l) {
+      const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
+      emit_decoder_layer_fwd(p, q, w, x_in, acts[sl][l], sc, tp);
+      x_in = acts[sl][l].x_out;
+    }
+    if (pp) {
+      bf16_t* dst = y_all + (size_t)k * M * d;
+      emit(p, "save_y", bytes_cost_us(2.0 * mb_bytes), [=](hipStream_t s2, const KCtl& c) { return launch_copy(dst, x_in, mb_bytes, s2, c); });
+    }
+    return x_in;
+  };
+  // backward pass of micro-batch k; acc != 0 adds the parameter gradients to the stored ones
+  auto emit_backward = [&](Plan& p, uint32_t k, uint32_t acc, const bf16_t* dx_top) {
+    const uint32_t sl = k % n_slots;
+    const bf16_t* dx = dx_top;
+    if (!s.vocab) {
       // top of a stack: the upstream gradient comes from the caller
-      const uint64_t bytes = (uint64_t)M * d * 2;
       bf16_t* dst = sc.dx_a;
-      emit(p, "stage_dy", bytes_cost_us(2.0 * bytes), [=](hipStream_t s2, const KCtl& c) { return launch_copy(dst, t->cur_targets, bytes, s2, c); });
+      emit(p, "stage_dy", bytes_cost_us(2.0 * mb_bytes), [=](hipStream_t s2, const KCtl& c) {
+        return launch_copy(dst, (const unsigned char*)t->cur_targets + (size_t)k * mb_bytes, mb_bytes, s2, c); });
       dx = sc.dx_a;
     }
-    const bf16_t* xin_l = (l == 0) ? x0 : acts[l - 1].x_out;
-    emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[l], sc, dx, sc.dx_b, sc.dx_a, tp);
-    dx = sc.dx_a;
-  }
-  if (s.vocab) {
-    bf16_t *gwte = grads + pm.at("wte"), *gwpe = grads + pm.at("wpe");
-    const bf16_t* dx0 = sc.dx_a;
-    emit(p, "dwte_scatter", bytes_cost_us(4.0 * M * d) + 10.0, [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wte((const int32_t*)t->cur_inputs, dx0, gwte, M, d, s2, c); });
-    emit(p, "dwpe", bytes_cost_us(2.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wpe(dx0, gwpe, M, seq, d, s2, c); });
-  }
-  put(tm, "dx_in", sc.dx_a, (uint64_t)M * d);
-  if (tm.desc.par_mode == SIF_PAR_DP) {
-    const uint64_t ns = sif_collective_ns(pm.n * 2, tm.desc.bw_bytes_per_s);
-    emit_bubble(p, next_site++, ns);
-    tm.max_bubble_ns = ns;
-  } else if (tm.desc.par_mode == SIF_PAR_FIXED && tm.desc.fixed_bubble_ns) {
-    emit_bubble(p, next_site++, tm.desc.fixed_bubble_ns);
-    tm.max_bubble_ns = tm.desc.fixed_bubble_ns;
+    for (int32_t l = (int32_t)s.n_layers - 1; l >= 0; --l) {
+      const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
+      const LayerG g = layer_ptrs<LayerG, bf16_t>(grads, pm, l);
+      const bf16_t* xin_l = (l == 0) ? x0[sl] : acts[sl][l - 1].x_out;
+      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc);
+      dx = sc.dx_a;
+    }
+    if (pp) {
+      bf16_t* dst = dx_all + (size_t)k * M * d;
+      const bf16_t* src = sc.dx_a;
+      emit(p, "save_dx", bytes_cost_us(2.0 * mb_bytes), [=](hipStream_t s2, const KCtl& c) { return launch_copy(dst, src, mb_bytes, s2, c); });
+    }
+  };
+
+  Plan& p = tm.plan;
+  if (!pp) {
+    const bf16_t* x_last = emit_forward(p, 0);
+    const bf16_t* dx = nullptr;
+    if (s.vocab) {
+      const bf16_t *wte = work + pm.at("wte"), *lnf_g = work + pm.at("lnf_g"), *lnf_b = work + pm.at("lnf_b");
+      emit(p, "lnf", bytes_cost_us(4.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_layernorm_fwd(x_last, lnf_g, lnf_b, lnf, mf, rf, M, d, s2, c); });
+      emit_gemm(p, "lm_head", G(lnf, wte, logits, M, V, d, d, d, Vp));
+      emit(p, "xent", bytes_cost_us(4.0 * M * Vp), [=](hipStream_t s2, const KCtl& c) { return launch_xent(logits, (const int32_t*)t->cur_targets, loss_tok, M, V, Vp, s2, c); });
+      emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
+      emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+      emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+      emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"), sc.part, M, d, 0);
+      dx = sc.dx_a;
+    }
+    emit_backward(p, 0, 0, dx);
+    if (s.vocab) {
+      bf16_t *gwte = grads + pm.at("wte"), *gwpe = grads + pm.at("wpe");
+      const bf16_t* dx0 = sc.dx_a;
+      emit(p, "dwte_scatter", bytes_cost_us(4.0 * M * d) + 10.0, [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wte((const int32_t*)t->cur_inputs, dx0, gwte, M, d, s2, c); });
+      emit(p, "dwpe", bytes_cost_us(2.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wpe(dx0, gwpe, M, seq, d, s2, c); });
+    }
+    if (tm.desc.par_mode == SIF_PAR_DP) {
+      const uint64_t ns = sif_collective_ns(pm.n * 2, tm.desc.bw_bytes_per_s);
+      emit_bubble(p, next_site++, ns);
+      tm.max_bubble_ns = ns;
+    } else if (tm.desc.par_mode == SIF_PAR_FIXED && tm.desc.fixed_bubble_ns) {
+      emit_bubble(p, next_site++, tm.desc.fixed_bubble_ns);
+      tm.max_bubble_ns = tm.desc.fixed_bubble_ns;
+    }
+  } else {
+    // 1F1B order of this stage: (stages-1-stage) warm-up forwards, then one forward / one backward alternating,
+    // then the remaining backwards; idle intervals from the closed form of the schedule
+    Plan fwd_probe, bwd_probe;
+    emit_forward(fwd_probe, 0);
+    emit_backward(bwd_probe, 0, 0, nullptr);
+    double tf_us = 0, tb_us = 0;
+    for (const Op& o : fwd_probe) tf_us += o.cost_us;
+    for (const Op& o : bwd_probe) tb_us += o.cost_us;
+    const uint64_t tf = tm.desc.pp_tf_ns ? tm.desc.pp_tf_ns : (uint64_t)(tf_us * 1000.0);
+    const uint64_t tb = tm.desc.pp_tb_ns ? tm.desc.pp_tb_ns : (uint64_t)(tb_us * 1000.0);
+    int32_t kind[64], index[64];
+    uint64_t gap[64];
+    const int32_t ng = sif_pp_1f1b_bubbles(tm.desc.pp_stage, tm.desc.pp_stages, n_micro, tf, tb, kind, index, gap, 64);
+    if (ng < 0) return (sif_status)ng;
+    if (ng > 64) return fail(SIF_E_INVAL, "pipeline schedule has too many idle intervals");
+    auto gap_before = [&](int32_t kd, int32_t idx) {
+      for (int32_t i = 0; i < ng; ++i)
+        if (kind[i] == kd && (kd == 2 || index[i] == idx)) {
+          emit_bubble(p, next_site++, gap[i]);
+          if (gap[i] > tm.max_bubble_ns) tm.max_bubble_ns = gap[i];
+        }
+    };
+    const uint32_t warm = std::min(n_micro, tm.desc.pp_stages - 1 - tm.desc.pp_stage);
+    uint32_t f = 0, b = 0;
+    for (; f < warm; ++f) { gap_before(0, (int32_t)f); emit_forward(p, f); }
+    while (f < n_micro) {
+      gap_before(0, (int32_t)f); emit_forward(p, f); ++f;
+      gap_before(1, (int32_t)b); emit_backward(p, b, b > 0, nullptr); ++b;
+    }
+    for (; b < n_micro; ++b) { gap_before(1, (int32_t)b); emit_backward(p, b, b > 0, nullptr); }
+    gap_before(2, -1);
   }
   const uint64_t n = pm.n;
   const float lr = tm.desc.lr;
@@ -435,7 +534,11 @@ sif_status build_train_model(TrainModel& tm, hipStream_t stream) {
   sif_status st = check_shape(tm.desc.shape, true);
   if (st != SIF_OK) return st;
   if (tm.desc.par_mode > SIF_PAR_TP) return fail(SIF_E_INVAL, "unknown par_mode");
-  if (tm.desc.par_mode == SIF_PAR_PP) return fail(SIF_E_INVAL, "pipeline-parallel steps are not built yet");
+  if (tm.desc.par_mode == SIF_PAR_PP) {
+    if (tm.desc.shape.kind != SIF_MODEL_DECODER || tm.desc.shape.vocab) return fail(SIF_E_INVAL, "a pipeline stage is a decoder layer stack (vocab = 0)");
+    if (tm.desc.pp_stages == 0 || tm.desc.pp_stage >= tm.desc.pp_stages || tm.desc.pp_micro < tm.desc.pp_stages || tm.desc.pp_micro > 32)
+      return fail(SIF_E_INVAL, "pipeline: need stage < stages <= micro-batches <= 32");
+  }
   if ((tm.desc.par_mode == SIF_PAR_DP || tm.desc.par_mode == SIF_PAR_TP) && tm.desc.bw_bytes_per_s == 0) return fail(SIF_E_INVAL, "bw_bytes_per_s must be positive");
   tm.n_params = model_n_params(tm.desc.shape);
   Arena ar;

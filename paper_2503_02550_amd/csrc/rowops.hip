@@ -139,13 +139,13 @@ __device__ __forceinline__ float fin_column(const float* __restrict__ part, uint
 
 // out[c] = bf16(sum_p part[p][c]) for dg (first `parts` rows) and db (next `parts` rows).
 __global__ __launch_bounds__(1024) void layernorm_bwd_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ dg,
-                                                                 bf16_t* __restrict__ db, uint32_t parts, uint32_t d, KCtl ctl) {
+                                                                 bf16_t* __restrict__ db, uint32_t parts, uint32_t d, uint32_t acc, KCtl ctl) {
   __shared__ float sm[1024];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63);
   const float sg = fin_column(part, parts, d, c, sm);
   const float sb = fin_column(part + (size_t)parts * d, parts, d, c, sm);
-  if (threadIdx.x < 64 && c < d) { dg[c] = f2bf(sg); db[c] = f2bf(sb); }
+  if (threadIdx.x < 64 && c < d) { dg[c] = f2bf(acc ? bf2f(dg[c]) + sg : sg); db[c] = f2bf(acc ? bf2f(db[c]) + sb : sb); }
   kernel_end(ctl, true);
 }
 
@@ -178,12 +178,12 @@ __global__ __launch_bounds__(256) void colsum_part_kernel(const bf16_t* __restri
 }
 
 __global__ __launch_bounds__(1024) void colsum_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ out,
-                                                          uint32_t parts, uint32_t n, KCtl ctl) {
+                                                          uint32_t parts, uint32_t n, uint32_t acc, KCtl ctl) {
   __shared__ float sm[1024];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63);
   const float t = fin_column(part, parts, n, c, sm);
-  if (threadIdx.x < 64 && c < n) out[c] = f2bf(t);
+  if (threadIdx.x < 64 && c < n) out[c] = f2bf(acc ? bf2f(out[c]) + t : t);
   kernel_end(ctl, true);
 }
 
@@ -464,6 +464,23 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, cons
   kernel_end(ctl, true);
 }
 
+// out[i] = bf16([out[i] +] sum_s part[s][i]) in ascending s: joins the K slices of a split weight-gradient product.
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, bf16_t* __restrict__ out, uint64_t n,
+                                                            uint32_t splits, uint32_t acc, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint64_t nv = n >> 3;
+  for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < nv; v += (uint64_t)gridDim.x * 256) {
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (acc) unpack8(reinterpret_cast<const uint4*>(out)[v], a);       // micro-batch accumulation: start from the stored gradient
+    for (uint32_t s = 0; s < splits; ++s) {
+      const float4 x0 = reinterpret_cast<const float4*>(part + (size_t)s * n)[2 * v], x1 = reinterpret_cast<const float4*>(part + (size_t)s * n)[2 * v + 1];
+      a[0] += x0.x; a[1] += x0.y; a[2] += x0.z; a[3] += x0.w; a[4] += x1.x; a[5] += x1.y; a[6] += x1.z; a[7] += x1.w;
+    }
+    reinterpret_cast<uint4*>(out)[v] = pack8(a);
+  }
+  kernel_end(ctl, true);
+}
+
 // ---------------------------------------------------------------------------------------------- launchers
 static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 #define REQ(cond, msg) do { if (!(cond)) return fail(SIF_E_INVAL, msg); } while (0)
@@ -490,10 +507,10 @@ sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g,
   return check_launch("layernorm_bwd");
 }
 
-sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c) {
+sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, uint32_t acc, hipStream_t s, const KCtl& c) {
   REQ(part && dg && db, "layernorm_bwd_fin: null");
   hipLaunchKernelGGL(layernorm_bwd_fin_kernel, dim3((d + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)dg, (bf16_t*)db,
-                     colsum_parts(rows), d, c);
+                     colsum_parts(rows), d, acc, c);
   return check_launch("layernorm_bwd_fin");
 }
 
@@ -505,9 +522,9 @@ sif_status launch_colsum_part(const void* x, uint32_t ld, float* part, uint32_t 
   return check_launch("colsum_part");
 }
 
-sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c) {
+sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, uint32_t acc, hipStream_t s, const KCtl& c) {
   REQ(part && out, "colsum_fin: null");
-  hipLaunchKernelGGL(colsum_fin_kernel, dim3((n + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)out, colsum_parts(rows), n, c);
+  hipLaunchKernelGGL(colsum_fin_kernel, dim3((n + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)out, colsum_parts(rows), n, acc, c);
   return check_launch("colsum_fin");
 }
 
@@ -607,6 +624,12 @@ sif_status launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s
   REQ(dst && src && bytes > 0 && (bytes & 15) == 0 && al16(dst) && al16(src), "copy: needs 16-byte aligned buffers and size");
   hipLaunchKernelGGL(copy_kernel, dim3(grid_for(bytes >> 4)), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, bytes >> 4, c);
   return check_launch("copy");
+}
+
+sif_status launch_reduce_splits(const float* part, void* out, uint64_t n, uint32_t splits, uint32_t acc, hipStream_t s, const KCtl& c) {
+  REQ(part && out && n > 0 && splits > 0 && (n & 7) == 0 && al16(part) && al16(out), "reduce_splits: bad arguments");
+  hipLaunchKernelGGL(reduce_splits_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, part, (bf16_t*)out, n, splits, acc, c);
+  return check_launch("reduce_splits");
 }
 
 sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c) {

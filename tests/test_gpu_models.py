@@ -56,9 +56,10 @@ def test_mlp_training_steps_and_forward_match_oracle():
 
 DEC_SMALL = dict(n_layers=2, d_model=64, n_heads=4, d_head=16, d_ffn=256, vocab=211, max_pos=40, batch=3, seq=40, causal=True)
 DEC_TILES = dict(n_layers=2, d_model=256, n_heads=2, d_head=64, d_ffn=512, vocab=1000, max_pos=136, batch=2, seq=136, causal=True)
+DEC_SPLIT = dict(n_layers=2, d_model=128, n_heads=2, d_head=64, d_ffn=256, vocab=600, max_pos=128, batch=2, seq=128, causal=True)
 
 
-@pytest.mark.parametrize("cfg", [DEC_SMALL, DEC_TILES], ids=["small", "several-tiles-ragged"])
+@pytest.mark.parametrize("cfg", [DEC_SMALL, DEC_TILES, DEC_SPLIT], ids=["small", "several-tiles-ragged", "split-weight-gradients"])
 def test_decoder_training_step_matches_oracle_stage_by_stage(cfg):
     shape = decoder_shape(cfg)
     master = Y.decoder_params(1, cfg, perturb=True)
@@ -165,3 +166,38 @@ def test_registration_and_submit_errors():
         bad = encoder_shape(dict(cfg, d_model=60))
         with pytest.raises(S.SifError):
             s.register_inference(bad, master)
+
+
+def test_pipeline_stage_1f1b_step_matches_oracle():
+    """Pipeline-parallel stage share: micro-batches in 1F1B order, gradient accumulation, one update, the idle
+    intervals of the schedule as bubbles."""
+    from oracle import bubbles as OB
+    cfg = dict(n_layers=2, d_model=128, n_heads=2, d_head=64, d_ffn=256, vocab=0, max_pos=0, batch=2, seq=64, causal=True)
+    stages, micro, stage, tf, tb = 3, 4, 1, 300_000, 500_000
+    shape = decoder_shape(cfg)
+    master = Y.decoder_params(40, cfg, perturb=True)
+    xs, dys = Y.activations(41, micro, 2, 64, 128), Y.activations(42, micro, 2, 64, 128, scale=0.01)
+    rys, rdxs, rnew, rg = OD.stack_train_step_microbatched(master["layers"], q(xs), q(dys), cfg, 0.01, "bf16")
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_PP, lr=0.01, pp_stages=stages, pp_micro=micro,
+                            pp_stage=stage, pp_tf_ns=tf, pp_tb_ns=tb)
+        X, DY = bf(xs), bf(dys)
+        torch.cuda.synchronize()
+        s.step(X, DY)
+        s.sync()
+        assert_bf16_close(up(s.train_tensor("y_all")).reshape(rys.shape), rys, "stage outputs", elem_slack=8e-3)
+        assert rel_err(up(s.train_tensor("dx_all")).reshape(rdxs.shape), rdxs) <= 2e-2
+        got_g = P.unpack(shape, up(s.train_tensor("grads")))
+        got_p = P.unpack(shape, up(s.train["master"]))
+        for l in range(2):
+            for k in OD.LAYER_KEYS:
+                assert rel_err(got_g["layers"][l][k], rg[l][k]) <= 2e-2, (l, k)
+                assert rel_err(got_p["layers"][l][k], rnew[l][k]) <= 1e-4, (l, k)
+        bubbles = [(t1 - t0) for kind, _, _, _, t0, t1 in S.sif_read_trace(s.ctx, 0) if kind == 3]
+        want = [ns for _, ns in OB.pp_1f1b_bubbles(stage, stages, micro, tf, tb)]
+        assert len(bubbles) == len(want) == 4
+        # at least the modelled length; well below the device deadline (4x + 100 ms) that a lost host release would show
+        assert all(b >= w for b, w in zip(bubbles, want)) and all(b <= w + 50_000_000 for b, w in zip(bubbles, want)), (bubbles, want)
+    with pytest.raises(S.SifError):
+        with Session() as s:
+            s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_PP, pp_stages=4, pp_micro=3, pp_stage=0)

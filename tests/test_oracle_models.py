@@ -233,3 +233,24 @@ def test_encoder_invariants():
     ob = E.encoder_forward(wb, ids, ENC, "bf16")
     assert np.array_equal(bf16_round(ob), ob)
     assert np.max(np.abs(ob - out)) < 3e-2 * np.max(np.abs(out))
+
+
+def test_microbatched_stack_accumulates_like_one_big_batch():
+    # without rounding, accumulating parameter gradients over micro-batches equals the gradient of the
+    # concatenated batch (the loss is a sum over samples), and outputs / input gradients are per sample
+    cfg = SHARD
+    master = S.decoder_params(30, cfg, perturb=True)["layers"]
+    xs, dys = S.activations(31, 3, 2, 5, 16), S.activations(32, 3, 2, 5, 16)
+    ys, dxs, new, grads = D.stack_train_step_microbatched(master, xs, dys, cfg, 0.05, "f32")
+    layers = to64({"layers": master})["layers"]
+    y, dx, g_big, _ = D.stack_fwd_bwd(layers, xs.reshape(6, 5, 16), dys.reshape(6, 5, 16), cfg, Prec("f32"))
+    assert np.allclose(ys.reshape(6, 5, 16), y, atol=1e-12) and np.allclose(dxs.reshape(6, 5, 16), dx, atol=1e-12)
+    for l in range(2):
+        for k in D.LAYER_KEYS:
+            assert np.allclose(grads[l][k], g_big[l][k], atol=1e-12), (l, k)
+            assert np.allclose(new[l][k], layers[l][k] - 0.05 * g_big[l][k], atol=1e-12)
+    # bf16: every stored accumulated gradient is representable and close to the unrounded one
+    _, _, _, gb = D.stack_train_step_microbatched(master, xs, dys, cfg, 0.05, "bf16")
+    for k in D.LAYER_KEYS:
+        assert np.array_equal(bf16_round(gb[0][k]), gb[0][k])
+        assert np.max(np.abs(gb[0][k] - grads[0][k])) <= 3e-2 * np.max(np.abs(grads[0][k])), k
