@@ -22,6 +22,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# Average HBM bytes per dispatch of gemm_bf16_kernel<0,0> in this workload, from the FETCH_SIZE / WRITE_SIZE counter
+# runs summarised in profiles/bench_cfg2_hbm_traffic.md (counters cannot be read from inside a timed run).
+GEMM00_HBM_BYTES_PER_LAUNCH = 150.5e6
 
 
 def cpu_baseline(sample_batch):
@@ -51,6 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-sample", type=int, default=8, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=1000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
+    ap.add_argument("--allow-serial-streams", action="store_true", help="for runs under a counter-collecting profiler, which serialises all kernels")
     ap.add_argument("--small", action="store_true", help="reduced shapes (development only; not a valid measurement)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -78,7 +82,9 @@ def main():
     ids_np, tg_np = Y.token_ids(3, dec["batch"], dec["seq"], dec["vocab"]), Y.token_ids(4, dec["batch"], dec["seq"], dec["vocab"])
 
     # ================= offline phase (configs[1]): the headline measurement =====================================
-    with Session() as s:
+    cfg = S.sif_default_config()
+    cfg.allow_serial_streams = 1 if args.allow_serial_streams else 0
+    with Session(cfg) as s:
         s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
         m = s.register_inference(eshape, enc_master)
         ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
@@ -129,7 +135,7 @@ def main():
         onl = dict(enc, batch=1, seq=Y.ONLINE["seq_max"])
         oshape = encoder_shape(onl)
         online = {}
-        with Session() as s:
+        with Session(cfg) as s:
             s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
             mo = s.register_inference(oshape, enc_master, online=True)
             ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
@@ -202,7 +208,8 @@ def main():
         "online_p95_ms": online[f"{Y.ONLINE['rate_per_s']:g}_req_per_s"]["p95_ms"] if online else None,
         "online": online,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": GEMM00_HBM_BYTES_PER_LAUNCH,
+                     "algorithmic_flops_per_launch": (f00 / n00) if n00 else None,
                      "kernel": "gemm_bf16_kernel<0,0>", "launches": int(n00), "avg_us": (1e6 * t00 / n00) if n00 else None,
                      "all_gemm_variants_tflops": (all_f / all_t / 1e12) if all_t > 0 else None},
         "paper_context": "paper (4x A100-40GB): up to 14x offline throughput over TGS, 67% lower online p95 than MPS; not comparable",

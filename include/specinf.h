@@ -231,7 +231,8 @@ typedef struct sif_config {
   uint32_t kernel_us_max;    /* inference kernels predicted longer than this are split along rows      */
   uint32_t collocate;        /* 0: the barrier never releases anything (solo training / overhead run)  */
   uint32_t device_timed_bubbles; /* 0: bubbles are released by the host clock; 1: timed on the device  */
-  uint32_t reserved;
+  uint32_t allow_serial_streams; /* 1: accept a stream pair that does not run concurrently (counter-collecting
+                                    profilers serialise all kernels); nothing fills a bubble then            */
   uint64_t device_capacity_bytes; /* Principle-I capacity; 0 = total memory of the current device      */
 } sif_config;
 

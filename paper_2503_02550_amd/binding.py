@@ -80,7 +80,7 @@ class sif_gemm_args(C.Structure):
 class sif_config(C.Structure):
     _fields_ = [("struct_size", u32), ("period_us", u32), ("window", u32), ("count_running", u32),
                 ("alg1", sif_alg1_params), ("kernel_us_max", u32), ("collocate", u32), ("device_timed_bubbles", u32),
-                ("reserved", u32), ("device_capacity_bytes", u64)]
+                ("allow_serial_streams", u32), ("device_capacity_bytes", u64)]
 
 
 class sif_model_shape(C.Structure):

@@ -407,7 +407,7 @@ sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_str
     if (e == hipSuccess) e = hipMemcpy(h, probe, sizeof(h), hipMemcpyDeviceToHost);
     if (e == hipSuccess) e = hipMemset(probe, 0, sizeof(h));
     if (e != hipSuccess) { (void)hipHostFree(mp); return fail_hip(e, "create: stream probe"); }
-    if (!(h[2] > h[0] && h[2] < h[1])) {
+    if (!(h[2] > h[0] && h[2] < h[1]) && !cfg->allow_serial_streams) {
       (void)hipHostFree(mp);
       return fail(SIF_E_AGAIN, "create: the two streams do not run concurrently (they share a hardware queue); pass another pair");
     }
