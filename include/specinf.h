@@ -178,10 +178,12 @@ sif_status sif_k_colsum(const void* x_dev, uint32_t ld, void* out_dev, float* pa
                         void* stream);
 
 /* Row softmax of fp32 scores [batch][rows][ld_s] into bf16 probabilities [batch][rows][ld_p]; causal != 0
- * keeps columns j <= i only; columns >= cols (up to ld_p) are written as zeros. */
+ * keeps columns j <= i only.  Columns >= cols (up to ld_p) are written as zeros; with causal != 0 the zero fill of
+ * row i stops at the end of its 128-column tile, (i/128 + 1)*128, which is as far as a causal product reads. */
 sif_status sif_k_softmax_fwd(const float* s_dev, void* p_dev, uint32_t batch, uint32_t rows, uint32_t cols,
                              uint32_t ld_s, uint32_t ld_p, uint32_t causal, void* stream);
-/* dS = scale * P .* (dP - rowsum(dP .* P)), dP fp32, P and dS bf16 (causal: columns j > i written as 0) */
+/* dS = scale * P .* (dP - rowsum(dP .* P)), dP fp32, P and dS bf16 (causal: columns j > i written as 0, up to the
+ * end of the row's 128-column tile) */
 sif_status sif_k_softmax_bwd(const float* dp_dev, const void* p_dev, void* ds_dev, uint32_t batch, uint32_t rows,
                              uint32_t cols, uint32_t ld, float scale, uint32_t causal, void* stream);
 

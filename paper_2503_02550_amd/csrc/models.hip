@@ -467,7 +467,11 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     if (s.vocab) {
       const bf16_t *wte = work + pm.at("wte"), *lnf_g = work + pm.at("lnf_g"), *lnf_b = work + pm.at("lnf_b");
       emit(p, "lnf", bytes_cost_us(4.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_layernorm_fwd(x_last, lnf_g, lnf_b, lnf, mf, rf, M, d, s2, c); });
-      emit_gemm(p, "lm_head", G(lnf, wte, logits, M, V, d, d, d, Vp));
+      // The product is taken over the padded vocabulary when the rows after wte (the position table follows it in the
+      // working copy) can stand in for the padding rows: the epilogue then stores whole 16-byte vectors.  The padding
+      // columns of the logits are never read by the loss and are zeroed when it writes the gradient in place.
+      const uint32_t n_head = (Vp - V <= s.max_pos) ? Vp : V;
+      emit_gemm(p, "lm_head", G(lnf, wte, logits, M, n_head, d, d, d, Vp));
       emit(p, "xent", bytes_cost_us(4.0 * M * Vp), [=](hipStream_t s2, const KCtl& c) { return launch_xent(logits, (const int32_t*)t->cur_targets, loss_tok, M, V, Vp, s2, c); });
       emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
       emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));

@@ -161,7 +161,21 @@ __global__ __launch_bounds__(256) void colsum_part_kernel(const bf16_t* __restri
   const uint32_t r_begin = blockIdx.y * rows_per, r_end = min(rows, r_begin + rows_per);
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (c0 < n) {
-    for (uint32_t row = r_begin + wave; row < r_end; row += 4) {
+    // four rows in flight per wavefront; the additions keep ascending row order
+    uint32_t row = r_begin + wave;
+    for (; row + 12 < r_end; row += 16) {
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const uint4*>(x + (size_t)(row + 4 * u) * ld + c0);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        float f[8];
+        unpack8(v[u], f);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] += f[i];
+      }
+    }
+    for (; row < r_end; row += 4) {
       float f[8];
       unpack8(*reinterpret_cast<const uint4*>(x + (size_t)row * ld + c0), f);
 #pragma unroll
@@ -232,10 +246,13 @@ __global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restric
       for (int i = 0; i < 4; ++i) { v[t][i] = __expf(v[t][i] - mx); sum += v[t][i]; }
     const float inv = 1.0f / wave_sum(sum);
     bf16_t* pr = p + r * ld_p;
+    // a causal row is only ever read up to the end of its 128-column tile (the products that consume it stop at the
+    // diagonal tile), so the zero fill stops there too
+    const uint32_t w_end = causal ? min(ld_p, (row / 128 + 1) * 128) : ld_p;
 #pragma unroll
     for (int t = 0; t < SM_MAXT; ++t) {
       const uint32_t c = (t * 64 + lane) * 4;
-      if (c < ld_p) *reinterpret_cast<uint2*>(pr + c) = make_uint2(pack_bf2(v[t][0] * inv, v[t][1] * inv), pack_bf2(v[t][2] * inv, v[t][3] * inv));
+      if (c < w_end) *reinterpret_cast<uint2*>(pr + c) = make_uint2(pack_bf2(v[t][0] * inv, v[t][1] * inv), pack_bf2(v[t][2] * inv, v[t][3] * inv));
     }
   }
   kernel_end(ctl, true);
@@ -269,10 +286,11 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* __restric
       }
     }
     dot = wave_sum(dot);
+    const uint32_t w_end = causal ? min(ld, (row / 128 + 1) * 128) : ld;
 #pragma unroll
     for (int t = 0; t < SM_MAXT; ++t) {
       const uint32_t c = (t * 64 + lane) * 4;
-      if (c < ld) {
+      if (c < w_end) {
         float o[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) o[i] = scale * q[t][i] * (a[t][i] - dot);
