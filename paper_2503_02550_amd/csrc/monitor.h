@@ -66,7 +66,7 @@ struct KCtl {                       // by-value kernel argument
   uint32_t kseq;                    // launch number on this stream (>= 1)
   uint32_t cost_ticks;              // predicted duration
   uint32_t kind_id;
-  uint32_t pad;
+  uint32_t flags;                   // bit 0: last kernel of its job
 };
 
 __device__ __forceinline__ uint64_t now_ticks() { return wall_clock64(); }
@@ -109,13 +109,15 @@ __device__ __forceinline__ bool first_thread() { return threadIdx.x == 0 && thre
 // skipped, the training stream is inside a bubble, the predicted rest of the bubble holds this kernel, and
 // the bubble is still the same one after the start time was stamped.
 __device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
-  if (ld_agent(&c.rec->skip_from) != kNone) return false;
-  uint32_t st = ld_agent(&c.gate->state);
-  uint32_t sq = ld_agent(&c.gate->seq);
+  // Relaxed device-scope loads (an acquire would sweep the L2 on every inference kernel start); each value feeds a
+  // branch before the next step, which keeps the order state -> clock -> state.
+  if (ld_relaxed(&c.rec->skip_from) != kNone) return false;
+  const uint32_t st = ld_relaxed(&c.gate->state);
+  const uint32_t sq = ld_relaxed(&c.gate->seq);
   if (st != kStateIdle) return false;
-  uint64_t t = now_ticks();
-  if (t + c.cost_ticks > ld_agent(&c.gate->t_expected_end)) return false;
-  if (ld_agent(&c.gate->state) != kStateIdle || ld_agent(&c.gate->seq) != sq) return false;
+  const uint64_t t = now_ticks();
+  if (t + c.cost_ticks > ld_relaxed(&c.gate->t_expected_end)) return false;
+  if (ld_relaxed(&c.gate->state) != kStateIdle || ld_relaxed(&c.gate->seq) != sq) return false;
   *t0 = t;
   return true;
 }
@@ -148,11 +150,11 @@ __device__ __forceinline__ bool kernel_begin(const KCtl& c) {
         if ((c.kind_id >> 28) == kKindTrain) st_sys_relaxed(&c.mir->t_launched, l);
       } else {
         c.slot->t1 = t0;
-        if (ld_agent(&c.rec->skip_from) == kNone) {
-          st_agent(&c.rec->skip_from, c.kseq);
-          st_sys(&c.mir->i_skip_from, c.kseq);
+        if (ld_relaxed(&c.rec->skip_from) == kNone) {
+          st_relaxed(&c.rec->skip_from, c.kseq);
+          st_sys_relaxed(&c.mir->i_skip_from, c.kseq);
         }
-        st_sys(&c.mir->kernels_skipped, ++c.rec->kernels_skipped);
+        st_sys_relaxed(&c.mir->kernels_skipped, ++c.rec->kernels_skipped);
       }
       st_relaxed(&c.slot->decision, (c.kseq << 2) | (run ? 1u : 2u));
     } else if (c.gate != nullptr) {
@@ -205,15 +207,17 @@ __device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
   } else {
     uint64_t dur = t1 - t0, fill = dur;
     if (c.gate != nullptr) {
-      const uint64_t ib = ld_agent(&c.gate->t_idle_begin);
-      const uint64_t end = (ld_agent(&c.gate->state) == kStateIdle) ? t1 : ld_agent(&c.gate->t_busy_begin);
+      const uint64_t ib = ld_relaxed(&c.gate->t_idle_begin);
+      const uint64_t end = (ld_relaxed(&c.gate->state) == kStateIdle) ? t1 : ld_relaxed(&c.gate->t_busy_begin);
       const uint64_t lo = t0 > ib ? t0 : ib, hi = t1 < end ? t1 : end;
       fill = hi > lo ? hi - lo : 0;
     }
     st_sys_relaxed(&m->infer_ticks, r->infer_ticks += dur);
     st_sys_relaxed(&m->filled_ticks, r->filled_ticks += fill);
     st_sys_relaxed(&m->kernels_run, ++r->kernels_run);
-    st_sys(&m->i_done, c.kseq);          // release: the kernel's results are complete before the host sees this
+    // the last kernel of a job publishes with release order (its results must be visible before the host reports the
+    // job done); the others only report progress
+    if (c.flags & 1u) st_sys(&m->i_done, c.kseq); else st_sys_relaxed(&m->i_done, c.kseq);
   }
 }
 

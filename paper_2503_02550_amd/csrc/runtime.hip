@@ -122,8 +122,10 @@ static void monitor_main(sif_ctx* c) {
   const uint64_t period_ns = (uint64_t)c->cfg.period_us * 1000ull;
   std::vector<uint32_t> window;
   window.reserve(c->cfg.window);
-  uint32_t prev_launched = mload(&c->mir->t_launched);
-  uint32_t last_idle_seen = mload(&c->mir->idle_seq);
+  // The mailbox starts zeroed and bubble numbers start at 1.  These must not be read from the mailbox here: the
+  // thread may first run after the first bubble has begun, and would then never release it.
+  uint32_t prev_launched = 0;
+  uint32_t last_idle_seen = 0;
   uint32_t pending_release = 0;
   uint64_t release_at = 0, pool = 0;
   uint64_t next_sample = host_now_ns() + period_ns;
@@ -281,6 +283,7 @@ static void barrier_main(sif_ctx* c) {
         }
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
+        if (j->next_op + 1 == j->plan.size()) k.flags |= 1u;
         sif_status st = launch_op(c, op, c->I.stream, k);
         if (st != SIF_OK) {
           auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), j), q.end()); };
@@ -349,7 +352,7 @@ sif_status sif_default_config(sif_config* cfg) {
   if (!cfg) return fail(SIF_E_INVAL, "default_config: null");
   memset(cfg, 0, sizeof(*cfg));
   cfg->struct_size = sizeof(*cfg);
-  cfg->period_us = 100; cfg->window = 64; cfg->count_running = 1;
+  cfg->period_us = 25; cfg->window = 64; cfg->count_running = 1;
   cfg->alg1.alpha = 1; cfg->alg1.beta = 3; cfg->alg1.gamma_num = 2; cfg->alg1.gamma_den = 1; cfg->alg1.m = 1;
   cfg->alg1.t0 = 25; cfg->alg1.ll = 100; cfg->alg1.ul = 400;
   cfg->kernel_us_max = 200; cfg->collocate = 1; cfg->device_timed_bubbles = 0; cfg->device_capacity_bytes = 0;
