@@ -82,7 +82,7 @@ __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], u
   uint4 r[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const uint32_t keep = (okmask >> i) & 1u ? 0xFFFFFFFFu : 0u;
+    const uint32_t keep = (okmask >> i) & 1u ? 0xFFFFFFFFu : 0u;       // folds away for a constant all-ones mask
     r[i] = make_uint4(rin[i].x & keep, rin[i].y & keep, rin[i].z & keep, rin[i].w & keep);
   }
   if (LAYOUT == 0) {
@@ -108,6 +108,36 @@ __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], u
     }
   }
 }
+
+// Interior tiles (all 128 rows inside the operand, K range a whole number of K steps) need no bounds handling at
+// all: the tile's first element is a block-uniform pointer that advances by one K step per load, each thread adds
+// one constant 32-bit offset, and the four vectors of a thread differ by a block-uniform stride, so the address
+// arithmetic stays on the scalar unit and the vector ALU is left to the MFMAs and the transposes.
+template <int LAYOUT>
+struct InteriorStream {
+  const char* tile;          // first byte of the next tile
+  size_t step, vstride;      // bytes per K step; bytes between a thread's consecutive vectors
+  uint32_t voff;             // this thread's byte offset inside a tile
+  __device__ __forceinline__ InteriorStream(const bf16_t* b, uint32_t ld, uint32_t row0, uint32_t k_begin) {
+    if (LAYOUT == 0) {
+      tile = (const char*)(b + (size_t)row0 * ld + k_begin);
+      step = BK * sizeof(bf16_t);
+      vstride = (size_t)(GEMM_THREADS / 8) * ld * sizeof(bf16_t);
+      voff = ((threadIdx.x >> 3) * ld + (threadIdx.x & 7) * 8) * (uint32_t)sizeof(bf16_t);
+    } else {
+      const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+      tile = (const char*)(b + (size_t)k_begin * ld + row0);
+      step = (size_t)BK * ld * sizeof(bf16_t);
+      vstride = (size_t)ld * sizeof(bf16_t);
+      voff = ((wave * 4 + (lane & 3)) * 4 * ld + (lane >> 2) * 8) * (uint32_t)sizeof(bf16_t);
+    }
+  }
+  __device__ __forceinline__ void next(uint4 (&r)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = *reinterpret_cast<const uint4*>(tile + i * vstride + voff);
+    tile += step;
+  }
+};
 
 template <int ALAY, int BLAY>
 __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
@@ -172,31 +202,57 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCt
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
     };
-    uint32_t oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
-    uint32_t okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
-    uint32_t oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
-    uint32_t okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
-    store_tile<ALAY>(sA, ra0, oka0);
-    store_tile<BLAY>(sB, rb0, okb0);
-    __syncthreads();
-    for (uint32_t k0 = k_begin; k0 < k_end; k0 += 2 * BK) {
-      // even tile (LDS buffer 0); tile k0+BK is in set 1; fetch tile k0+2BK into set 0
-      oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
-      okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
-      compute(0);
-      if (k0 + BK >= k_end) break;
-      store_tile<ALAY>(sA + BM * BK, ra1, oka1);
-      store_tile<BLAY>(sB + BN * BK, rb1, okb1);
+    // The loop takes two K steps per trip (the register sets and LDS buffers alternate by name) and has no exit in
+    // its middle, so that the accumulators stay in the same registers throughout; an odd last tile is done after it.
+    const uint32_t nt = (k_end - k_begin + BK - 1) / BK;
+    const bool interior = m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0;
+    if (interior) {
+      InteriorStream<ALAY> ta(A, p.lda, m0, k_begin);
+      InteriorStream<BLAY> tb(B, p.ldb, n0, k_begin);
+      ta.next(ra0); tb.next(rb0);
+      if (nt > 1) { ta.next(ra1); tb.next(rb1); }
+      store_tile<ALAY>(sA, ra0, 0xFu);
+      store_tile<BLAY>(sB, rb0, 0xFu);
       __syncthreads();
-      // odd tile (LDS buffer 1); tile k0+2BK is in set 0; fetch tile k0+3BK into set 1
-      oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
-      okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
-      compute(1);
-      if (k0 + 2 * BK >= k_end) break;
+      for (uint32_t t = 0; t + 2 <= nt; t += 2) {
+        if (t + 2 < nt) { ta.next(ra0); tb.next(rb0); }
+        compute(0);
+        store_tile<ALAY>(sA + BM * BK, ra1, 0xFu);
+        store_tile<BLAY>(sB + BN * BK, rb1, 0xFu);
+        __syncthreads();
+        if (t + 3 < nt) { ta.next(ra1); tb.next(rb1); }
+        compute(1);
+        if (t + 2 < nt) {
+          store_tile<ALAY>(sA, ra0, 0xFu);
+          store_tile<BLAY>(sB, rb0, 0xFu);
+        }
+        __syncthreads();
+      }
+    } else {
+      uint32_t oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
+      uint32_t okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
+      uint32_t oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
+      uint32_t okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
       store_tile<ALAY>(sA, ra0, oka0);
       store_tile<BLAY>(sB, rb0, okb0);
       __syncthreads();
+      for (uint32_t t = 0; t + 2 <= nt; t += 2) {
+        const uint32_t k0 = k_begin + t * BK;
+        oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
+        okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
+        compute(0);
+        store_tile<ALAY>(sA + BM * BK, ra1, oka1);
+        store_tile<BLAY>(sB + BN * BK, rb1, okb1);
+        __syncthreads();
+        oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
+        okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
+        compute(1);
+        store_tile<ALAY>(sA, ra0, oka0);
+        store_tile<BLAY>(sB, rb0, okb0);
+        __syncthreads();
+      }
     }
+    if (nt & 1u) compute(0);
 
     // Epilogue.  The accumulators go through LDS (fp32, the 64 KB of the operand buffers) so that every global
     // access of the epilogue - bias, residual, auxiliary tensor, result - is a 16-byte vector along a row.
