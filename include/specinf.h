@@ -189,9 +189,19 @@ sif_status sif_k_softmax_bwd(const float* dp_dev, const void* p_dev, void* ds_de
 
 /* Fused attention forward: o[b,s,h*dh:(h+1)*dh] = softmax(q k^T / sqrt(dh) [+ causal mask]) v per (batch, head),
  * qkv bf16 [batch*seq][ld_qkv] with columns [q | k | v], each heads*d_head wide; o bf16 [batch*seq][ld_o].
- * d_head must be 64 or 128.  Scores never leave the chip. */
-sif_status sif_k_attn_fwd(const void* qkv_dev, void* o_dev, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head,
-                          uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream);
+ * d_head must be 64 or 128.  Scores never leave the chip.  lse_dev (device, fp32 [batch*heads][seq], may be NULL)
+ * receives log(sum_j exp(score_ij)) of the scaled, masked scores, which the backward pass needs. */
+sif_status sif_k_attn_fwd(const void* qkv_dev, void* o_dev, float* lse_dev, uint32_t batch, uint32_t seq, uint32_t heads,
+                          uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream);
+/* Fused attention backward: dqkv [batch*seq][ld_dqkv] (columns [dq | dk | dv]) from qkv, the forward's o and lse and
+ * the upstream gradient d_o [batch*seq][ld_o] (same layout and leading dimension as o).  The probabilities are
+ * recomputed as exp(score - lse) and rounded to bf16, dS = P .* (dP - delta) / sqrt(dh) likewise, as the training
+ * step of the collocated instance stores them (Sec. 4 workloads: transformer training); delta_dev (device, fp32
+ * [batch*heads][seq]) is scratch that receives rowsum(d_o .* o).  Two launches on `stream` (dq; dk and dv), no
+ * atomics: results do not depend on the launch configuration.  d_head must be 64 or 128. */
+sif_status sif_k_attn_bwd(const void* qkv_dev, const void* o_dev, const void* d_o_dev, const float* lse_dev, float* delta_dev,
+                          void* dqkv_dev, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
+                          uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal, void* stream);
 
 /* x[t,:] = wte[ids[t],:] + wpe[t % seq,:]   (bf16) */
 sif_status sif_k_embed_fwd(const int32_t* ids_dev, const void* wte_dev, const void* wpe_dev, void* x_dev,

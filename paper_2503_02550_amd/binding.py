@@ -433,8 +433,15 @@ def sif_train_op_name(ctx, h, index):
     return n.decode() if n else None
 
 
-_sig("sif_k_attn_fwd", i32, vp, vp, u32, u32, u32, u32, u32, u32, u32, vp)
+_sig("sif_k_attn_fwd", i32, vp, vp, vp, u32, u32, u32, u32, u32, u32, u32, vp)
+_sig("sif_k_attn_bwd", i32, vp, vp, vp, vp, vp, vp, u32, u32, u32, u32, u32, u32, u32, u32, vp)
 
 
-def sif_k_attn_fwd(qkv, o, batch, seq, heads, d_head, ld_qkv, ld_o, causal, stream=None):
-    return check(lib.sif_k_attn_fwd(ptr(qkv), ptr(o), batch, seq, heads, d_head, ld_qkv, ld_o, causal, stream_ptr(stream)))
+def sif_k_attn_fwd(qkv, o, batch, seq, heads, d_head, ld_qkv, ld_o, causal, lse=None, stream=None):
+    return check(lib.sif_k_attn_fwd(ptr(qkv), ptr(o), ptr(lse) if lse is not None else None, batch, seq, heads, d_head, ld_qkv, ld_o,
+                                    causal, stream_ptr(stream)))
+
+
+def sif_k_attn_bwd(qkv, o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv, causal, stream=None):
+    return check(lib.sif_k_attn_bwd(ptr(qkv), ptr(o), ptr(d_o), ptr(lse), ptr(delta), ptr(dqkv), batch, seq, heads, d_head, ld_qkv, ld_o,
+                                    ld_dqkv, causal, stream_ptr(stream)))

@@ -1,15 +1,21 @@
-// Fused attention forward for the inference instance: o = softmax(scale q k^T [+ causal mask]) v per (batch, head),
-// without materialising the score matrix in HBM (the unfused path writes and re-reads 4 + 2 bytes per score and
-// costs three launches per layer; an inference forward is a chain of short, launch-bound kernels, Sec. 3.3
-// "Kernel Barrier": "most kernel execution times under 1 ms").
+// Fused attention, forward and backward, without materialising the score matrix in HBM (the unfused path writes
+// and re-reads 4 + 2 bytes per score and costs three launches per layer forward, five backward; an inference
+// forward is a chain of short, launch-bound kernels, Sec. 3.3 "Kernel Barrier", and the training instance's step
+// time is what Principle II of Sec. 3.2 protects).
 //
-// One block = 128 query rows of one (batch, head), 4 wavefronts x 32 rows.  Keys/values are streamed in tiles of
-// 128 through LDS: K as [kv][d] (16-byte chunks XOR-swizzled), V transposed to [d][kv] on the way in.  Both
-// products are computed transposed, S^T = K Q^T and O^T = V^T P^T, so that a query row lives in one lane (and its
-// partner lane 32 further): the softmax reductions are in-register plus one cross-lane exchange, the running
-// maximum / sum / rescale of the streaming softmax are per-lane scalars, and the probabilities go from the
-// accumulator registers of the first product straight into the operand registers of the second (the k-index
-// permutation this implies is applied to the V^T operand reads).  bf16 operands, fp32 accumulation and softmax.
+//   forward    o = softmax(scale q k^T [+ causal mask]) v,  lse = log sum exp of the scaled, masked scores (optional)
+//   backward   delta = rowsum(do .* o),  P = exp(scale q k^T - lse),  dS = scale P .* (do v^T - delta)
+//              dq = dS k   (one kernel, a block per 128 query rows, keys streamed)
+//              dk = dS^T q,  dv = P^T do   (a second kernel, a block per 128 key rows, queries streamed)
+// Both backward kernels recompute P from q, k and lse; no atomics, each output element is reduced in one fixed order.
+//
+// Every product is arranged so that the operand produced on chip (P, dS) goes from the accumulator registers of
+// one MFMA straight into the B operand of the next: an accumulator tile holds column (lane % 32) and the rows
+// 8*(r/4) + 4*(lane/32) + r%4, so as a B operand [k][col] its k index is a permutation of the row index, which is
+// applied to the reads of the matching A operand (a transposed copy in LDS) instead.  In the forward and the dq
+// kernel the products are taken transposed (S^T = K Q^T, O^T = V^T P^T, dQ^T = K^T dS^T): a query row then lives
+// in one lane and its partner 32 further, and the softmax statistics are per-lane scalars.  bf16 operands, fp32
+// accumulation and softmax; P and dS are rounded to bf16 where the unfused path stores them.
 #include <math.h>
 
 #include "common.h"
@@ -20,21 +26,81 @@ namespace sif {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int AT_Q = 128, AT_KV = 128, AT_THREADS = 256, AT_VLD = AT_KV + 4;   // V^T rows padded by 8 bytes
+constexpr int AT_Q = 128, AT_KV = 128, AT_THREADS = 256, AT_VLD = AT_KV + 4;   // transposed rows padded by 8 bytes
+constexpr int AT_QB = 64, AT_QLD = AT_QB + 4;                                    // query rows per step of the dk/dv kernel
 
 __device__ __forceinline__ uint32_t at_key(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
 
+// ROWS x DH tile of a row-major bf16 matrix (rows row0.., 16-byte aligned, ld elements apart) into LDS as
+// [row][d] with the 16-byte chunks of a row XOR-swizzled; rows >= limit read as zero.
+template <int DH, int ROWS>
+__device__ __forceinline__ void at_load_rows(bf16_t* dst, const bf16_t* src, size_t ld, uint32_t row0, uint32_t limit) {
+  constexpr int CH = DH / 8;
+  for (uint32_t v = threadIdx.x; v < ROWS * CH; v += AT_THREADS) {
+    const uint32_t row = v / CH, c = v % CH;
+    uint4 x = make_uint4(0, 0, 0, 0);
+    if (row0 + row < limit) x = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + row) * ld + c * 8);
+    *reinterpret_cast<uint4*>(dst + row * DH + ((c ^ (at_key(row) % CH)) << 3)) = x;
+  }
+}
+// The same tile transposed, [d][row] with rows of ROWS + 4 elements: each thread takes 4 rows x 8 d columns and
+// writes eight 4-long runs.
+template <int DH, int ROWS>
+__device__ __forceinline__ void at_load_rows_t(bf16_t* dst, const bf16_t* src, size_t ld, uint32_t row0, uint32_t limit) {
+  constexpr int CH = DH / 8, LD = ROWS + 4;
+  for (uint32_t sb = threadIdx.x; sb < (ROWS / 4) * CH; sb += AT_THREADS) {
+    const uint32_t rq = (sb / CH) * 4, d0 = (sb % CH) * 8;
+    uint32_t w[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4 x = make_uint4(0, 0, 0, 0);
+      if (row0 + rq + i < limit) x = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + rq + i) * ld + d0);
+      w[i][0] = x.x; w[i][1] = x.y; w[i][2] = x.z; w[i][3] = x.w;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint2 even, odd;
+      even.x = (w[0][j] & 0xFFFFu) | (w[1][j] << 16);  even.y = (w[2][j] & 0xFFFFu) | (w[3][j] << 16);
+      odd.x = (w[0][j] >> 16) | (w[1][j] & 0xFFFF0000u);  odd.y = (w[2][j] >> 16) | (w[3][j] & 0xFFFF0000u);
+      *reinterpret_cast<uint2*>(dst + (d0 + 2 * j) * LD + rq) = even;
+      *reinterpret_cast<uint2*>(dst + (d0 + 2 * j + 1) * LD + rq) = odd;
+    }
+  }
+}
+// A operand (row, k = 8 consecutive d) from a swizzled [row][d] tile; chunk = k / 8.
+template <int DH>
+__device__ __forceinline__ bf16x8 at_frag(const bf16_t* tile, uint32_t row, uint32_t chunk) {
+  return *reinterpret_cast<const bf16x8*>(tile + row * DH + ((chunk ^ (at_key(row) % (DH / 8))) << 3));
+}
+// A operand (row d, k = the rows kb..kb+3 and kb+8..kb+11 of the original tile) from a transposed tile.
+__device__ __forceinline__ bf16x8 at_frag_t(const bf16_t* tile_t, uint32_t ld, uint32_t d, uint32_t kb) {
+  const bf16_t* vr = tile_t + d * ld + kb;
+  const uint2 lo = *reinterpret_cast<const uint2*>(vr), hi = *reinterpret_cast<const uint2*>(vr + 8);
+  uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
+  return *reinterpret_cast<bf16x8*>(&vv);
+}
+// eight accumulator values r0..r0+7 as a B operand
+__device__ __forceinline__ bf16x8 at_pack8(const float (&v)[16], int r0) {
+  uint4 pv = make_uint4(pack_bf2(v[r0], v[r0 + 1]), pack_bf2(v[r0 + 2], v[r0 + 3]), pack_bf2(v[r0 + 4], v[r0 + 5]), pack_bf2(v[r0 + 6], v[r0 + 7]));
+  return *reinterpret_cast<bf16x8*>(&pv);
+}
+__device__ __forceinline__ float at_round(float x) { return bf2f(f2bf(x)); }
+
+// Forward.  One block = 128 query rows of one (batch, head), 4 wavefronts x 32 rows; keys/values streamed in tiles
+// of 128 through LDS (K as [kv][d], V transposed to [d][kv]); running maximum / sum / rescale per lane.
 template <int DH, int CAUSAL>
-__global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, uint32_t S,
-                                                              uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, KCtl ctl) {
-  constexpr int KS = DH / 16, DT = DH / 32, CH = DH / 8;      // k steps of q k^T, 32-wide d tiles, 16-byte chunks per K row
+__global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse,
+                                                              uint32_t S, uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, KCtl ctl) {
+  constexpr int KS = DH / 16, DT = DH / 32;                   // k steps of q k^T, 32-wide d tiles
   __shared__ __align__(16) bf16_t sK[AT_KV * DH];
   __shared__ __align__(16) bf16_t sVt[DH * AT_VLD];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
   const uint32_t b = blockIdx.y / H, head = blockIdx.y % H, da = H * DH;
   const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
-  const uint32_t q_blk = blockIdx.x * AT_Q, q = q_blk + wave * 32 + qi;
+  // with a causal mask the last query block has the most keys: start the long blocks first
+  const uint32_t q_blk = (CAUSAL ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
+  const float c2 = scale * 1.44269504088896f;
 
   bf16x8 fq[KS];
   {
@@ -51,103 +117,87 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
   for (int d = 0; d < DT; ++d)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[d][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = -INFINITY, l_run = 0.f, l_true = 0.f;
 
   const uint32_t kv_end = CAUSAL ? min(S, q_blk + AT_Q) : S;
   for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
     __syncthreads();
-    // K tile: 128 rows x CH chunks
-    for (uint32_t v = threadIdx.x; v < AT_KV * CH; v += AT_THREADS) {
-      const uint32_t row = v / CH, c = v % CH, kv = kv0 + row;
-      uint4 x = make_uint4(0, 0, 0, 0);
-      if (kv < S) x = *reinterpret_cast<const uint4*>(base + da + (size_t)kv * ld_qkv + c * 8);
-      *reinterpret_cast<uint4*>(sK + row * DH + ((c ^ (at_key(row) % CH)) << 3)) = x;
-    }
-    // V tile transposed: each thread takes 4 kv rows x 8 d columns and writes eight 4-long kv runs
-    for (uint32_t sb = threadIdx.x; sb < (AT_KV / 4) * CH; sb += AT_THREADS) {
-      const uint32_t kvq = (sb / CH) * 4, d0 = (sb % CH) * 8;
-      uint32_t w[4][4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        uint4 x = make_uint4(0, 0, 0, 0);
-        if (kv0 + kvq + i < S) x = *reinterpret_cast<const uint4*>(base + 2 * da + (size_t)(kv0 + kvq + i) * ld_qkv + d0);
-        w[i][0] = x.x; w[i][1] = x.y; w[i][2] = x.z; w[i][3] = x.w;
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        uint2 even, odd;
-        even.x = (w[0][j] & 0xFFFFu) | (w[1][j] << 16);  even.y = (w[2][j] & 0xFFFFu) | (w[3][j] << 16);
-        odd.x = (w[0][j] >> 16) | (w[1][j] & 0xFFFF0000u);  odd.y = (w[2][j] >> 16) | (w[3][j] & 0xFFFF0000u);
-        *reinterpret_cast<uint2*>(sVt + (d0 + 2 * j) * AT_VLD + kvq) = even;
-        *reinterpret_cast<uint2*>(sVt + (d0 + 2 * j + 1) * AT_VLD + kvq) = odd;
-      }
-    }
+    at_load_rows<DH, AT_KV>(sK, base + da, ld_qkv, kv0, S);
+    at_load_rows_t<DH, AT_KV>(sVt, base + 2 * da, ld_qkv, kv0, S);
     __syncthreads();
 
-    // S^T tiles: rows = kv (32 per tile), columns = the wavefront's 32 query rows
+    // S^T tiles: rows = kv (32 per tile), columns = the wavefront's 32 query rows.  Under the causal mask the tiles
+    // of the diagonal block that lie wholly above the wavefront's rows are skipped.
+    const int t_end = CAUSAL ? min(4, (int)((qw + 31 - kv0) / 32) + 1) : 4;
+    const bool need_mask = kv0 + AT_KV > S || (CAUSAL && kv0 + AT_KV - 1 > qw);
     floatx16 sacc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
+      if (t >= t_end) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
-      const uint32_t row = t * 32 + qi;
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 fk = *reinterpret_cast<const bf16x8*>(sK + row * DH + ((((uint32_t)ks * 2 + h) ^ (at_key(row) % CH)) << 3));
-        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk, fq[ks], sacc[t], 0, 0, 0);
+      for (int ks = 0; ks < KS; ++ks)
+        sacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag<DH>(sK, t * 32 + qi, ks * 2 + h), fq[ks], sacc[t], 0, 0, 0);
+    }
+    // mask (only tiles that meet the diagonal or the end of the sequence), running maximum of the raw scores
+    float mx = -INFINITY;
+    if (need_mask) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        if (t >= t_end) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t kv = kv0 + t * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          const bool ok = kv < S && (!CAUSAL || kv <= q);
+          sacc[t][r] = ok ? sacc[t][r] : -INFINITY;
+        }
       }
     }
-    // mask, running maximum
-    float mx = -INFINITY;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
+      if (t >= t_end) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const uint32_t kv = kv0 + t * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        const bool ok = kv < S && (!CAUSAL || kv <= q);
-        sacc[t][r] = ok ? sacc[t][r] * scale : -INFINITY;
-        mx = fmaxf(mx, sacc[t][r]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;                       // base-2 exponent units: c2 = scale * log2(e) > 0
     const float m_new = fmaxf(m_run, mx);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;          // a fully masked row keeps everything at zero
-    const float alpha = __expf(m_run - m_use);                         // exp(-inf) = 0 on the first tile
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);        // 2^(-inf) = 0 on the first tile
     float rs = 0.f;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
+      if (t >= t_end) continue;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[t][r] = __expf(sacc[t][r] - m_use); rs += sacc[t][r]; }
+      for (int r = 0; r < 16; ++r) { sacc[t][r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], c2, -m_use)); rs += sacc[t][r]; }
+    }
     rs += __shfl_xor(rs, 32, 64);
     l_run = l_run * alpha + rs;
+    l_true = l_run;
     m_run = m_new;
 #pragma unroll
     for (int d = 0; d < DT; ++d)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[d][r] *= alpha;
-    // a single tile covers all keys: normalise before rounding, as the unfused path (and the oracle) do
+    // a single tile covers all keys: normalise before rounding, as the unfused path does
     const bool single = kv_end <= AT_KV;
     const float pn = single ? 1.0f / l_run : 1.0f;
 
     // O^T += V^T P^T.  Element e of step s2 in tile t is key  t*32 + 16*s2 + 8*(e/4) + 4*h + e%4.
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
+    for (int t = 0; t < 4; ++t) {
+      if (t >= t_end) continue;
+      float pt[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) pt[r] = sacc[t][r] * pn;
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        uint32_t pw[4];
+        const bf16x8 fp = at_pack8(pt, 8 * s2);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) pw[e] = pack_bf2(sacc[t][8 * s2 + 2 * e] * pn, sacc[t][8 * s2 + 2 * e + 1] * pn);
-        uint4 pv = make_uint4(pw[0], pw[1], pw[2], pw[3]);
-        const bf16x8 fp = *reinterpret_cast<bf16x8*>(&pv);
-        const uint32_t kvb = t * 32 + 16 * s2 + 4 * h;
-#pragma unroll
-        for (int d = 0; d < DT; ++d) {
-          const bf16_t* vr = sVt + (d * 32 + qi) * AT_VLD + kvb;
-          const uint2 lo = *reinterpret_cast<const uint2*>(vr), hi = *reinterpret_cast<const uint2*>(vr + 8);
-          uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
-          const bf16x8 fv = *reinterpret_cast<bf16x8*>(&vv);
-          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv, fp, oacc[d], 0, 0, 0);
-        }
+        for (int d = 0; d < DT; ++d)
+          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sVt, AT_VLD, d * 32 + qi, t * 32 + 16 * s2 + 4 * h), fp, oacc[d], 0, 0, 0);
       }
+    }
     if (single) l_run = 1.0f;
   }
 
@@ -162,24 +212,282 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
         *reinterpret_cast<uint2*>(op + dd) = make_uint2(pack_bf2(oacc[d][4 * g] * inv, oacc[d][4 * g + 1] * inv),
                                                         pack_bf2(oacc[d][4 * g + 2] * inv, oacc[d][4 * g + 3] * inv));
       }
+    if (lse != nullptr && h == 0) lse[(size_t)blockIdx.y * S + q] = (m_run + __log2f(l_true)) * 0.693147180559945f;
   }
   kernel_end(ctl, true);
 }
 
-sif_status launch_attn_fwd(const void* qkv, void* o, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
+// Backward, dq.  One block = 128 query rows of one (batch, head), a query row per lane pair as in the forward;
+// keys/values streamed in tiles of 128: K and V as [kv][d], K also transposed.  Also writes delta = rowsum(do .* o)
+// for the dk/dv kernel.
+template <int DH, int CAUSAL>
+__global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+                                                                 const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
+                                                                 float* __restrict__ delta, bf16_t* __restrict__ dqkv, uint32_t S, uint32_t H,
+                                                                 uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, float scale, KCtl ctl) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  __shared__ __align__(16) bf16_t sK[AT_KV * DH];
+  __shared__ __align__(16) bf16_t sV[AT_KV * DH];
+  __shared__ __align__(16) bf16_t sKt[DH * AT_VLD];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
+  const uint32_t b = blockIdx.y / H, head = blockIdx.y % H, da = H * DH;
+  const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
+  const uint32_t q_blk = (CAUSAL ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
+  const bool q_ok = q < S;
+  const float c2 = scale * 1.44269504088896f;
+
+  bf16x8 fq[KS], fdo[KS];
+  float dsum = 0.f;
+  {
+    const size_t row = (size_t)b * S + (q_ok ? q : 0);
+    const bf16_t* qp = base + (size_t)(q_ok ? q : 0) * ld_qkv;
+    const bf16_t* dop = d_o + row * ld_o + head * DH;
+    const bf16_t* op = o + row * ld_o + head * DH;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 vq = *reinterpret_cast<const uint4*>(qp + ks * 16 + h * 8);
+      uint4 vd = *reinterpret_cast<const uint4*>(dop + ks * 16 + h * 8);
+      const uint4 vo = *reinterpret_cast<const uint4*>(op + ks * 16 + h * 8);
+      if (!q_ok) { vq = make_uint4(0, 0, 0, 0); vd = make_uint4(0, 0, 0, 0); }
+      fq[ks] = *reinterpret_cast<bf16x8*>(&vq);
+      fdo[ks] = *reinterpret_cast<bf16x8*>(&vd);
+      dsum += bflo(vd.x) * bflo(vo.x) + bfhi(vd.x) * bfhi(vo.x) + bflo(vd.y) * bflo(vo.y) + bfhi(vd.y) * bfhi(vo.y) +
+              bflo(vd.z) * bflo(vo.z) + bfhi(vd.z) * bfhi(vo.z) + bflo(vd.w) * bflo(vo.w) + bfhi(vd.w) * bfhi(vo.w);
+    }
+  }
+  dsum += __shfl_xor(dsum, 32, 64);
+  const float lq2 = q_ok ? lse[(size_t)blockIdx.y * S + q] * 1.44269504088896f : INFINITY;     // base-2 units
+  if (q_ok && h == 0) delta[(size_t)blockIdx.y * S + q] = dsum;
+
+  floatx16 dqacc[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqacc[d][r] = 0.f;
+
+  const uint32_t kv_end = CAUSAL ? min(S, q_blk + AT_Q) : S;
+  for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
+    __syncthreads();
+    at_load_rows<DH, AT_KV>(sK, base + da, ld_qkv, kv0, S);
+    at_load_rows<DH, AT_KV>(sV, base + 2 * da, ld_qkv, kv0, S);
+    at_load_rows_t<DH, AT_KV>(sKt, base + da, ld_qkv, kv0, S);
+    __syncthreads();
+    const int t_end = CAUSAL ? min(4, (int)((qw + 31 - kv0) / 32) + 1) : 4;       // tiles wholly above the diagonal are skipped
+    const bool need_mask = kv0 + AT_KV > S || (CAUSAL && kv0 + AT_KV - 1 > qw);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (t >= t_end) continue;
+      floatx16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag<DH>(sK, t * 32 + qi, ks * 2 + h), fq[ks], sacc, 0, 0, 0);     // S^T
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag<DH>(sV, t * 32 + qi, ks * 2 + h), fdo[ks], pacc, 0, 0, 0);    // dP^T
+      }
+      float ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = at_round(__builtin_amdgcn_exp2f(fmaf(sacc[r], c2, -lq2)));
+        if (need_mask) {
+          const uint32_t kv = kv0 + t * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          p = (kv < S && (!CAUSAL || kv <= q)) ? p : 0.f;
+        }
+        ds[r] = p * scale * (pacc[r] - dsum);
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 fds = at_pack8(ds, 8 * s2);
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+          dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sKt, AT_VLD, d * 32 + qi, t * 32 + 16 * s2 + 4 * h), fds, dqacc[d], 0, 0, 0);
+      }
+    }
+  }
+  if (q_ok) {
+    bf16_t* op = dqkv + ((size_t)b * S + q) * ld_dqkv + head * DH;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        *reinterpret_cast<uint2*>(op + d * 32 + g * 8 + h * 4) =
+            make_uint2(pack_bf2(dqacc[d][4 * g], dqacc[d][4 * g + 1]), pack_bf2(dqacc[d][4 * g + 2], dqacc[d][4 * g + 3]));
+  }
+  kernel_end(ctl, true);
+}
+
+// Backward, dk and dv.  One block = 128 key rows of one (batch, head), a key row per lane pair (its K and V rows stay
+// in registers); queries streamed in steps of 64 rows: q and do as [q][d] and transposed, lse and delta beside them.
+template <int DH, int CAUSAL>
+__global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                                                  const float* __restrict__ lse, const float* __restrict__ delta,
+                                                                  bf16_t* __restrict__ dqkv, uint32_t S, uint32_t H, uint32_t ld_qkv,
+                                                                  uint32_t ld_o, uint32_t ld_dqkv, float scale, KCtl ctl) {
+  constexpr int KS = DH / 16, DT = DH / 32;
+  __shared__ __align__(16) bf16_t sQ[AT_QB * DH];
+  __shared__ __align__(16) bf16_t sDo[AT_QB * DH];
+  __shared__ __align__(16) bf16_t sQt[DH * AT_QLD];
+  __shared__ __align__(16) bf16_t sDot[DH * AT_QLD];
+  __shared__ __align__(16) float sL[AT_QB];
+  __shared__ __align__(16) float sD[AT_QB];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ki = lane & 31, h = lane >> 5;
+  const uint32_t b = blockIdx.y / H, head = blockIdx.y % H, da = H * DH;
+  const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
+  const bf16_t* dobase = d_o + (size_t)b * S * ld_o + head * DH;
+  const float* lrow = lse + (size_t)blockIdx.y * S;
+  const float* drow = delta + (size_t)blockIdx.y * S;
+  const uint32_t kv_blk = blockIdx.x * AT_KV, kw = kv_blk + wave * 32, kv = kw + ki;   // the first key block meets the most queries
+  const bool kv_ok = kv < S;
+  const float c2 = scale * 1.44269504088896f;
+
+  bf16x8 fk[KS], fv[KS];
+  {
+    const bf16_t* kp = base + da + (size_t)(kv_ok ? kv : 0) * ld_qkv;
+    const bf16_t* vp = kp + da;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 a = *reinterpret_cast<const uint4*>(kp + ks * 16 + h * 8), c = *reinterpret_cast<const uint4*>(vp + ks * 16 + h * 8);
+      if (!kv_ok) { a = make_uint4(0, 0, 0, 0); c = make_uint4(0, 0, 0, 0); }
+      fk[ks] = *reinterpret_cast<bf16x8*>(&a);
+      fv[ks] = *reinterpret_cast<bf16x8*>(&c);
+    }
+  }
+  floatx16 dkacc[DT], dvacc[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkacc[d][r] = 0.f; dvacc[d][r] = 0.f; }
+
+  for (uint32_t q0 = CAUSAL ? (kv_blk / AT_QB) * AT_QB : 0; q0 < S; q0 += AT_QB) {
+    __syncthreads();
+    at_load_rows<DH, AT_QB>(sQ, base, ld_qkv, q0, S);
+    at_load_rows<DH, AT_QB>(sDo, dobase, ld_o, q0, S);
+    at_load_rows_t<DH, AT_QB>(sQt, base, ld_qkv, q0, S);
+    at_load_rows_t<DH, AT_QB>(sDot, dobase, ld_o, q0, S);
+    if (threadIdx.x < AT_QB) {
+      const uint32_t qq = q0 + threadIdx.x;
+      sL[threadIdx.x] = qq < S ? lrow[qq] * 1.44269504088896f : INFINITY;         // base-2 units; a row past the end gets P = 2^(-inf) = 0
+      sD[threadIdx.x] = qq < S ? drow[qq] : 0.f;
+    }
+    __syncthreads();
+    // a wavefront whose 32 keys all lie after the 64 queries of this step has nothing to add
+    if (CAUSAL && kw > q0 + AT_QB - 1) continue;
+#pragma unroll
+    for (int u = 0; u < AT_QB / 32; ++u) {
+      if (CAUSAL && kw > q0 + u * 32 + 31) continue;            // these 32 queries all precede the wavefront's keys
+      const bool need_mask = CAUSAL && kw + 31 > q0 + u * 32;
+      floatx16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag<DH>(sQ, u * 32 + ki, ks * 2 + h), fk[ks], sacc, 0, 0, 0);     // S  [q][kv]
+        pacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag<DH>(sDo, u * 32 + ki, ks * 2 + h), fv[ks], pacc, 0, 0, 0);    // dP [q][kv]
+      }
+      float pr[16], ds[16];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 l4 = *reinterpret_cast<const float4*>(sL + u * 32 + g * 8 + h * 4);
+        const float4 d4 = *reinterpret_cast<const float4*>(sD + u * 32 + g * 8 + h * 4);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = g * 4 + e;
+          float p = at_round(__builtin_amdgcn_exp2f(fmaf(sacc[r], c2, -lv[e])));
+          if (need_mask) p = kv <= q0 + u * 32 + g * 8 + h * 4 + e ? p : 0.f;
+          pr[r] = p;
+          ds[r] = p * scale * (pacc[r] - dv[e]);
+        }
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 fp = at_pack8(pr, 8 * s2), fds = at_pack8(ds, 8 * s2);
+        const uint32_t qb = u * 32 + 16 * s2 + 4 * h;
+#pragma unroll
+        for (int d = 0; d < DT; ++d) {
+          dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sDot, AT_QLD, d * 32 + ki, qb), fp, dvacc[d], 0, 0, 0);     // dV^T
+          dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sQt, AT_QLD, d * 32 + ki, qb), fds, dkacc[d], 0, 0, 0);     // dK^T
+        }
+      }
+    }
+  }
+  if (kv_ok) {
+    bf16_t* kp = dqkv + ((size_t)b * S + kv) * ld_dqkv + da + head * DH;
+    bf16_t* vp = kp + da;
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint32_t dd = d * 32 + g * 8 + h * 4;
+        *reinterpret_cast<uint2*>(kp + dd) = make_uint2(pack_bf2(dkacc[d][4 * g], dkacc[d][4 * g + 1]), pack_bf2(dkacc[d][4 * g + 2], dkacc[d][4 * g + 3]));
+        *reinterpret_cast<uint2*>(vp + dd) = make_uint2(pack_bf2(dvacc[d][4 * g], dvacc[d][4 * g + 1]), pack_bf2(dvacc[d][4 * g + 2], dvacc[d][4 * g + 3]));
+      }
+  }
+  kernel_end(ctl, true);
+}
+
+static sif_status attn_check(const char* who, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head) {
+  if (!batch || !seq || !heads) return fail(SIF_E_INVAL, "%s: empty extent", who);
+  if (d_head != 64 && d_head != 128) return fail(SIF_E_INVAL, "%s: d_head must be 64 or 128", who);
+  if ((uint64_t)batch * heads > 65535) return fail(SIF_E_INVAL, "%s: batch*heads too large", who);
+  return SIF_OK;
+}
+static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+sif_status launch_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
                            uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c) {
-  if (!qkv || !o || !batch || !seq || !heads) return fail(SIF_E_INVAL, "attn_fwd: null or empty");
-  if (d_head != 64 && d_head != 128) return fail(SIF_E_INVAL, "attn_fwd: d_head must be 64 or 128");
+  if (!qkv || !o) return fail(SIF_E_INVAL, "attn_fwd: null operand");
+  if (sif_status st = attn_check("attn_fwd", batch, seq, heads, d_head)) return st;
   if ((ld_qkv & 7) || (ld_o & 7) || ld_qkv < 3 * heads * d_head || ld_o < heads * d_head) return fail(SIF_E_INVAL, "attn_fwd: bad leading dimensions");
-  if (((uintptr_t)qkv & 15) || ((uintptr_t)o & 15)) return fail(SIF_E_INVAL, "attn_fwd: pointers must be 16-byte aligned");
-  if (batch * heads > 65535) return fail(SIF_E_INVAL, "attn_fwd: batch*heads too large");
+  if (!al16(qkv) || !al16(o)) return fail(SIF_E_INVAL, "attn_fwd: pointers must be 16-byte aligned");
   const float scale = 1.0f / sqrtf((float)d_head);
   dim3 grid((seq + AT_Q - 1) / AT_Q, batch * heads);
-#define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_fwd_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (bf16_t*)o, seq, heads, ld_qkv, ld_o, scale, c)
+#define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_fwd_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, heads, ld_qkv, ld_o, scale, c)
   if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
   else { if (causal) AT_LAUNCH(128, 1); else AT_LAUNCH(128, 0); }
 #undef AT_LAUNCH
   return check_launch("attn_fwd");
+}
+
+static sif_status attn_bwd_check(const char* who, const void* qkv, const void* o, const void* d_o, const float* lse, const float* delta,
+                                 const void* dqkv, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
+                                 uint32_t ld_o, uint32_t ld_dqkv) {
+  if (!qkv || !o || !d_o || !lse || !delta || !dqkv) return fail(SIF_E_INVAL, "%s: null operand", who);
+  if (sif_status st = attn_check(who, batch, seq, heads, d_head)) return st;
+  if ((ld_qkv & 7) || (ld_o & 7) || (ld_dqkv & 7) || ld_qkv < 3 * heads * d_head || ld_dqkv < 3 * heads * d_head || ld_o < heads * d_head)
+    return fail(SIF_E_INVAL, "%s: bad leading dimensions", who);
+  if (!al16(qkv) || !al16(o) || !al16(d_o) || !al16(dqkv)) return fail(SIF_E_INVAL, "%s: pointers must be 16-byte aligned", who);
+  return SIF_OK;
+}
+
+sif_status launch_attn_bwd_dq(const void* qkv, const void* o, const void* d_o, const float* lse, float* delta, void* dqkv, uint32_t batch,
+                              uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal,
+                              hipStream_t s, const KCtl& c) {
+  if (sif_status st = attn_bwd_check("attn_bwd_dq", qkv, o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv)) return st;
+  const float scale = 1.0f / sqrtf((float)d_head);
+  dim3 grid((seq + AT_Q - 1) / AT_Q, batch * heads);
+#define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (const bf16_t*)o, \
+                                            (const bf16_t*)d_o, lse, delta, (bf16_t*)dqkv, seq, heads, ld_qkv, ld_o, ld_dqkv, scale, c)
+  if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
+  else { if (causal) AT_LAUNCH(128, 1); else AT_LAUNCH(128, 0); }
+#undef AT_LAUNCH
+  return check_launch("attn_bwd_dq");
+}
+
+sif_status launch_attn_bwd_dkv(const void* qkv, const void* d_o, const float* lse, const float* delta, void* dqkv, uint32_t batch, uint32_t seq,
+                               uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal, hipStream_t s,
+                               const KCtl& c) {
+  if (sif_status st = attn_bwd_check("attn_bwd_dkv", qkv, d_o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv)) return st;
+  const float scale = 1.0f / sqrtf((float)d_head);
+  dim3 grid((seq + AT_KV - 1) / AT_KV, batch * heads);
+#define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (const bf16_t*)d_o, lse, \
+                                            delta, (bf16_t*)dqkv, seq, heads, ld_qkv, ld_o, ld_dqkv, scale, c)
+  if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
+  else { if (causal) AT_LAUNCH(128, 1); else AT_LAUNCH(128, 0); }
+#undef AT_LAUNCH
+  return check_launch("attn_bwd_dkv");
 }
 
 }  // namespace sif

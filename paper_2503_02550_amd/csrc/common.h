@@ -10,15 +10,16 @@ namespace sif {
 typedef uint16_t bf16_t;
 
 __device__ __forceinline__ float bf2f(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (bf16_t)((u >> 16) | 0x40);   // NaN stays NaN
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// float -> bfloat16, round to nearest even, by the gfx950 conversion instruction (v_cvt_pk_bf16_f32 takes two values)
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float floatx2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
 __device__ __forceinline__ float bflo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bfhi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
-__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) { return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16); }
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
+  const floatx2_hw v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
+}
 
 // erf by the rational approximation 7.1.26 of Abramowitz & Stegun (|error| <= 1.5e-7), a dozen instructions
 // instead of the library routine's fifty: the GELU epilogue runs on every element of the widest activations.

@@ -47,9 +47,17 @@ sif_status sif_k_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t 
   return launch_softmax_bwd(dp, p, ds, batch, rows, cols, ld, scale, causal, S(stream), no_ctl());
 }
 
-sif_status sif_k_attn_fwd(const void* qkv, void* o, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
-                          uint32_t ld_o, uint32_t causal, void* stream) {
-  return launch_attn_fwd(qkv, o, batch, seq, heads, d_head, ld_qkv, ld_o, causal, S(stream), no_ctl());
+sif_status sif_k_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head,
+                          uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream) {
+  return launch_attn_fwd(qkv, o, lse, batch, seq, heads, d_head, ld_qkv, ld_o, causal, S(stream), no_ctl());
+}
+
+sif_status sif_k_attn_bwd(const void* qkv, const void* o, const void* d_o, const float* lse, float* delta, void* dqkv, uint32_t batch,
+                          uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal,
+                          void* stream) {
+  sif_status st = launch_attn_bwd_dq(qkv, o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv, causal, S(stream), no_ctl());
+  if (st != SIF_OK) return st;
+  return launch_attn_bwd_dkv(qkv, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv, causal, S(stream), no_ctl());
 }
 
 sif_status sif_k_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens, uint32_t seq,

@@ -33,8 +33,14 @@ sif_status launch_softmax_fwd(const float* sc, void* p, uint32_t batch, uint32_t
                               uint32_t ld_p, uint32_t causal, hipStream_t s, const KCtl& c);
 sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t batch, uint32_t rows, uint32_t cols,
                               uint32_t ld, float scale, uint32_t causal, hipStream_t s, const KCtl& c);
-sif_status launch_attn_fwd(const void* qkv, void* o, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
-                           uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c);
+sif_status launch_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head,
+                           uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c);
+sif_status launch_attn_bwd_dq(const void* qkv, const void* o, const void* d_o, const float* lse, float* delta, void* dqkv, uint32_t batch,
+                              uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal,
+                              hipStream_t s, const KCtl& c);
+sif_status launch_attn_bwd_dkv(const void* qkv, const void* d_o, const float* lse, const float* delta, void* dqkv, uint32_t batch, uint32_t seq,
+                               uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal, hipStream_t s,
+                               const KCtl& c);
 sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens,
                             uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c);
 sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t tokens, uint32_t d,

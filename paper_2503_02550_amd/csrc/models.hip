@@ -92,7 +92,7 @@ struct G {
 };
 
 // scratch buffers of the backward pass, shared by all layers
-struct Scratch { float* scores; bf16_t* ds; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; float* part; float* split; uint64_t split_elems; };
+struct Scratch { float* scores; bf16_t* ds; float* delta; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; float* part; float* split; uint64_t split_elems; };
 
 static double gemm_cost_us(const sif_gemm_args& g) {
   double flops = 2.0 * g.m * g.n * g.k * g.batch_outer * g.batch_inner;
@@ -235,10 +235,15 @@ static void emit_attention_bwd(Plan& p, const Dims& q, const bf16_t* qkv, const 
                               .batch(q.B, q.H, q.H * ss, ss, row3, q.dh, row3, q.dh));
 }
 
-struct LayerActs {       // saved by the forward pass of one decoder layer
+struct LayerActs {       // saved by the forward pass of one decoder layer (prob: unfused attention, lse: fused)
   bf16_t *ln1, *qkv, *prob, *o, *x_mid, *ln2, *z, *a, *x_out;
-  float *m1, *r1, *m2, *r2;
+  float *m1, *r1, *m2, *r2, *lse;
 };
+// head sizes the fused attention kernels are built for; other sizes take the three-launch path through HBM
+static bool fused_attention(uint32_t dh) { return dh == 64 || dh == 128; }
+static double attn_fused_cost_us(const Dims& q, double products, bool causal) {
+  return 4.0 + products * 2.0 * q.B * q.H * (double)q.S * q.S * q.dh * (causal ? 0.55 : 1.0) / 2.0e8;      // 200 TFLOP/s plus launch latency
+}
 struct LayerW { const bf16_t *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_fc, *b_fc, *w_proj, *b_proj; };
 struct LayerG { bf16_t *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o, *ln2_g, *ln2_b, *w_fc, *b_fc, *w_proj, *b_proj; };
 
@@ -259,7 +264,13 @@ static void emit_decoder_layer_fwd(Plan& p, const Dims& q, const LayerW& w, cons
   const uint32_t M = q.M, d = q.d;
   emit(p, "ln1", bytes_cost_us(4.0 * M * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_fwd(x_in, w.ln1_g, w.ln1_b, a.ln1, a.m1, a.r1, M, d, s, c); });
   emit_gemm(p, "qkv", G(a.ln1, w.w_qkv, a.qkv, M, 3 * q.da, d, d, d, 3 * q.da).epi(SIF_EPI_BIAS, w.b_qkv));
-  emit_attention_fwd(p, q, a.qkv, sc.scores, a.prob, a.o, true);
+  if (fused_attention(q.dh)) {
+    const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh, da = q.da;
+    emit(p, "attn_fused", attn_fused_cost_us(q, 2, true),
+         [=](hipStream_t s, const KCtl& c) { return launch_attn_fwd(a.qkv, a.o, a.lse, B, S, H, dh, 3 * da, da, 1, s, c); });
+  } else {
+    emit_attention_fwd(p, q, a.qkv, sc.scores, a.prob, a.o, true);
+  }
   emit_gemm(p, "attn_out", G(a.o, w.w_o, a.x_mid, M, d, q.da, q.da, q.da, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, w.b_o, x_in));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
   emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_fwd(a.x_mid, w.ln2_g, w.ln2_b, a.ln2, a.m2, a.r2, M, d, s, c); });
@@ -283,7 +294,17 @@ static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, cons
   emit_colsum(p, "db_o", dx_mid, d, g.b_o, sc.part, M, d, acc);
   emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, sc, acc);
   emit_gemm(p, "do", G(dx_mid, w.w_o, sc.d_o, M, da, d, d, da, da).lay(SIF_A_ROW_K, SIF_B_ROW_N));
-  emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
+  if (fused_attention(q.dh)) {
+    const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh;
+    emit(p, "attn_bwd_dq", attn_fused_cost_us(q, 3, true), [=](hipStream_t s, const KCtl& c) {
+      return launch_attn_bwd_dq(a.qkv, a.o, sc.d_o, a.lse, sc.delta, sc.dqkv, B, S, H, dh, 3 * da, da, 3 * da, 1, s, c);
+    });
+    emit(p, "attn_bwd_dkv", attn_fused_cost_us(q, 4, true), [=](hipStream_t s, const KCtl& c) {
+      return launch_attn_bwd_dkv(a.qkv, sc.d_o, a.lse, sc.delta, sc.dqkv, B, S, H, dh, 3 * da, da, 3 * da, 1, s, c);
+    });
+  } else {
+    emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
+  }
   emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, sc.part, M, 3 * da, acc);
   emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, sc, acc);
   emit_gemm(p, "dln1", G(sc.dqkv, w.w_qkv, sc.dln, M, d, 3 * da, 3 * da, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
@@ -335,6 +356,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   const Dims q = dims_of(s, s.batch, s.seq);
   const uint32_t M = q.M, d = q.d, Vp = (s.vocab + 7) & ~7u;
   const uint64_t ssz = (uint64_t)q.B * q.H * q.S * q.Sp;
+  const bool fused = fused_attention(q.dh);
   const bool pp = tm.desc.par_mode == SIF_PAR_PP;
   // pipeline stage: n_micro micro-batches per step; a 1F1B stage holds the activations of at most
   // (stages - stage) micro-batches at a time, so that many activation slots are enough
@@ -348,7 +370,9 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     x0[sl] = (bf16_t*)ar.take((uint64_t)M * d * 2);
     for (auto& a : acts[sl]) {
       a.ln1 = (bf16_t*)ar.take((uint64_t)M * d * 2); a.qkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
-      a.prob = (bf16_t*)ar.take(ssz * 2); a.o = (bf16_t*)ar.take((uint64_t)M * q.da * 2);
+      a.prob = fused ? nullptr : (bf16_t*)ar.take(ssz * 2);
+      a.lse = fused ? (float*)ar.take((uint64_t)q.B * q.H * q.S * 4) : nullptr;
+      a.o = (bf16_t*)ar.take((uint64_t)M * q.da * 2);
       a.x_mid = (bf16_t*)ar.take((uint64_t)M * d * 2); a.ln2 = (bf16_t*)ar.take((uint64_t)M * d * 2);
       a.z = (bf16_t*)ar.take((uint64_t)M * q.f * 2); a.a = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
       a.x_out = (bf16_t*)ar.take((uint64_t)M * d * 2);
@@ -357,7 +381,9 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     }
   }
   Scratch sc;
-  sc.scores = (float*)ar.take(ssz * 4); sc.ds = (bf16_t*)ar.take(ssz * 2);
+  sc.scores = fused ? nullptr : (float*)ar.take(ssz * 4);
+  sc.ds = fused ? nullptr : (bf16_t*)ar.take(ssz * 2);
+  sc.delta = fused ? (float*)ar.take((uint64_t)q.B * q.H * q.S * 4) : nullptr;
   sc.dx_a = (bf16_t*)ar.take((uint64_t)M * d * 2); sc.dx_b = (bf16_t*)ar.take((uint64_t)M * d * 2);
   sc.dln = (bf16_t*)ar.take((uint64_t)M * d * 2); sc.dqkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
   sc.d_o = (bf16_t*)ar.take((uint64_t)M * q.da * 2); sc.dz = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
@@ -385,7 +411,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   for (uint32_t l = 0; l < s.n_layers; ++l) {      // named tensors refer to activation slot 0
     const LayerActs& a = acts[0][l];
     const std::string sfx = "." + std::to_string(l);
-    put(tm, "ln1" + sfx, a.ln1, (uint64_t)M * d); put(tm, "qkv" + sfx, a.qkv, (uint64_t)M * 3 * q.da); put(tm, "prob" + sfx, a.prob, ssz);
+    put(tm, "ln1" + sfx, a.ln1, (uint64_t)M * d); put(tm, "qkv" + sfx, a.qkv, (uint64_t)M * 3 * q.da); if (fused) put(tm, "lse" + sfx, a.lse, (uint64_t)q.B * q.H * q.S); else put(tm, "prob" + sfx, a.prob, ssz);
     put(tm, "o" + sfx, a.o, (uint64_t)M * q.da); put(tm, "x_mid" + sfx, a.x_mid, (uint64_t)M * d); put(tm, "ln2" + sfx, a.ln2, (uint64_t)M * d);
     put(tm, "z" + sfx, a.z, (uint64_t)M * q.f); put(tm, "a" + sfx, a.a, (uint64_t)M * q.f); put(tm, "x_out" + sfx, a.x_out, (uint64_t)M * d);
   }
@@ -640,7 +666,7 @@ sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_
       // one fused kernel: scores stay on chip, two launches fewer per layer
       const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh, da = q.da;
       emit(p, "attn_fused", 4.0 + 4.0 * B * H * (double)S * S * dh / 3.0e8 + bytes_cost_us(8.0 * M * da),
-           [=](hipStream_t st, const KCtl& c) { return launch_attn_fwd(qkv, o, B, S, H, dh, 3 * da, da, 0, st, c); });
+           [=](hipStream_t st, const KCtl& c) { return launch_attn_fwd(qkv, o, nullptr, B, S, H, dh, 3 * da, da, 0, st, c); });
     } else {
       emit_attention_fwd(p, q, qkv, scores, prob, o, false);
     }

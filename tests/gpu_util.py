@@ -57,3 +57,16 @@ def assert_f32_close(got, ref, name="", tol=1e-4):
     assert np.all(np.isfinite(got)), name
     e = rel_err(got, ref)
     assert e <= tol, (name, e)
+
+
+def lse_reference(qkv64, h, dh, causal=True):
+    """log sum exp of the scaled, masked scores, written out from its definition on the bf16-rounded inputs."""
+    b, s, _ = qkv64.shape
+    da = h * dh
+    qh = qkv64[..., 0:da].reshape(b, s, h, dh).transpose(0, 2, 1, 3)
+    kh = qkv64[..., da:2 * da].reshape(b, s, h, dh).transpose(0, 2, 1, 3)
+    sc = qh @ kh.transpose(0, 1, 3, 2) / np.sqrt(dh)
+    if causal:
+        sc = np.where(np.tril(np.ones((s, s), dtype=bool)), sc, -np.inf)
+    mx = sc.max(axis=-1, keepdims=True)
+    return (mx + np.log(np.exp(sc - mx).sum(axis=-1, keepdims=True)))[..., 0].reshape(b * h, s)

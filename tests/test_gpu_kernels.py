@@ -9,7 +9,7 @@ pytestmark = pytest.mark.gpu
 
 if torch.cuda.is_available():
     import paper_2503_02550_amd as S
-    from gpu_util import DEV, bf, f32, i32, up, q, assert_bf16_close, assert_f32_close
+    from gpu_util import DEV, bf, f32, i32, up, q, assert_bf16_close, assert_f32_close, rel_err, lse_reference
 
 
 def rnd(seed, *shape, scale=1.0):
@@ -276,3 +276,29 @@ def test_fused_attention_forward(bsz, s, h, dh, causal):
     S.sif_k_attn_fwd(Q, o, bsz, s, h, dh, 3 * da, da, causal)
     ref, _ = attention_fwd(q(qkv), h, dh, bool(causal), Prec("bf16"))
     assert_bf16_close(up(o), ref, f"fused attention s={s} dh={dh} causal={causal}", elem_slack=4e-3)
+
+
+@pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("bsz,s,h,dh", [(2, 5, 2, 64), (3, 37, 2, 64), (2, 128, 3, 64), (2, 200, 2, 64), (1, 300, 2, 128), (2, 64, 1, 128),
+                                        (1, 520, 1, 64)])
+def test_fused_attention_backward(bsz, s, h, dh, causal):
+    from oracle.decoder import attention_bwd, attention_fwd
+    from oracle.numerics import Prec
+    da = h * dh
+    qkv, do = rnd(41, bsz, s, 3 * da), rnd(42, bsz, s, da)
+    Q, DO = bf(qkv), bf(do)
+    o = torch.zeros((bsz, s, da), device=DEV, dtype=torch.bfloat16)
+    lse = torch.full((bsz * h, s), 7.0, device=DEV)
+    delta = torch.zeros((bsz * h, s), device=DEV)
+    dqkv = torch.full((bsz, s, 3 * da), 5.0, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_attn_fwd(Q, o, bsz, s, h, dh, 3 * da, da, causal, lse=lse)
+    S.sif_k_attn_bwd(Q, o, DO, lse, delta, dqkv, bsz, s, h, dh, 3 * da, da, 3 * da, causal)
+    prec = Prec("bf16")
+    ref_o, p = attention_fwd(q(qkv), h, dh, bool(causal), prec)
+    ref = attention_bwd(q(do), q(qkv), p, h, dh, prec)
+    assert_f32_close(up(lse), lse_reference(q(qkv), h, dh, bool(causal)), "lse", tol=1e-5)
+    ref_delta = (q(do) * ref_o).reshape(bsz, s, h, dh).sum(-1).transpose(0, 2, 1).reshape(bsz * h, s)
+    assert rel_err(up(delta), ref_delta) <= 2e-2
+    got = up(dqkv)
+    for name, lo in (("dq", 0), ("dk", da), ("dv", 2 * da)):
+        assert_bf16_close(got[..., lo:lo + da], ref[..., lo:lo + da], f"fused attention {name} s={s} dh={dh} causal={causal}", elem_slack=6e-3)

@@ -16,8 +16,20 @@ if torch.cuda.is_available():
     import paper_2503_02550_amd as S
     from paper_2503_02550_amd import params as P
     from paper_2503_02550_amd.session import Session, decoder_shape, encoder_shape, mlp_shape
-    from gpu_util import DEV, bf, f32, i32, up, q, rel_err, assert_bf16_close, assert_f32_close
+    from gpu_util import DEV, bf, f32, i32, up, q, rel_err, assert_bf16_close, assert_f32_close, lse_reference
 
+
+
+def assert_update_close(p_got, p_ref, g_got, g_ref, lr, name):
+    """fp32 master parameters after p <- p - lr g.  The update is fp32 arithmetic on a gradient held in bf16: the two
+    sides' parameters may differ by lr times the difference of their gradients (bounded by the bf16 tolerance on the
+    gradients, 2e-2 of the largest) on top of the fp32 tolerance 1e-4."""
+    p_got, p_ref = np.asarray(p_got, np.float64), np.asarray(p_ref, np.float64)
+    bound = 1e-4 * np.max(np.abs(p_ref)) + lr * 2e-2 * np.max(np.abs(g_ref))
+    assert np.max(np.abs(p_got - p_ref)) <= bound, name
+    # and the device's own update, from the gradient it holds, is exact to fp32 rounding
+    step = (p_got - p_ref) + lr * (np.asarray(g_got, np.float64) - np.asarray(g_ref, np.float64))
+    assert np.max(np.abs(step)) <= 1e-6 * np.max(np.abs(p_ref)) + 1e-9, name
 
 def test_mlp_training_steps_and_forward_match_oracle():
     c = Y.TINY_MLP
@@ -78,9 +90,15 @@ def test_decoder_training_step_matches_oracle_stage_by_stage(cfg):
             for name in ("ln1", "qkv", "o", "x_mid", "ln2", "z", "a"):
                 got = up(s.train_tensor(name, l)).reshape(rc["layers"][l][name].shape)
                 assert_bf16_close(got, rc["layers"][l][name], f"L{l}.{name}", elem_slack=8e-3)
-            sp = (sq + 7) // 8 * 8
-            prob = up(s.train_tensor("prob", l)).reshape(b, cfg["n_heads"], sq, sp)[..., :sq]
-            assert_bf16_close(prob, rc["layers"][l]["prob"], f"L{l}.prob", elem_slack=8e-3)
+            if cfg["d_head"] in (64, 128):     # fused attention keeps log-sum-exp of the scores, not the probabilities
+                # the saved log-sum-exp of the scores, against its definition on the qkv the device holds (checked above)
+                lse = up(s.train_tensor("lse", l, dtype=torch.float32)).reshape(b * cfg["n_heads"], sq)
+                qkv_dev = up(s.train_tensor("qkv", l)).reshape(b, sq, -1)
+                assert rel_err(lse, lse_reference(qkv_dev, cfg["n_heads"], cfg["d_head"])) <= 1e-5
+            else:
+                sp = (sq + 7) // 8 * 8
+                prob = up(s.train_tensor("prob", l)).reshape(b, cfg["n_heads"], sq, sp)[..., :sq]
+                assert_bf16_close(prob, rc["layers"][l]["prob"], f"L{l}.prob", elem_slack=8e-3)
         assert abs(loss.item() - rl) <= 2e-2 * abs(rl)
         # gradients and updated parameters
         got_g = P.unpack(shape, up(s.train_tensor("grads")))
@@ -95,7 +113,7 @@ def test_decoder_training_step_matches_oracle_stage_by_stage(cfg):
             assert e <= 2e-2, (path, e)
             p_ref = rnew[path] if isinstance(path, str) else rnew["layers"][path[1]][path[2]]
             p_got = got_p[path] if isinstance(path, str) else got_p["layers"][path[1]][path[2]]
-            assert rel_err(p_got, p_ref) <= 1e-4, path
+            assert_update_close(p_got, p_ref, g_got, g_ref, 0.01, path)
             w_got = got_w[path] if isinstance(path, str) else got_w["layers"][path[1]][path[2]]
             assert np.array_equal(w_got, q(p_got)), path                # working copy = bf16(master)
         print("worst gradient error", worst)
@@ -192,7 +210,7 @@ def test_pipeline_stage_1f1b_step_matches_oracle():
         for l in range(2):
             for k in OD.LAYER_KEYS:
                 assert rel_err(got_g["layers"][l][k], rg[l][k]) <= 2e-2, (l, k)
-                assert rel_err(got_p["layers"][l][k], rnew[l][k]) <= 1e-4, (l, k)
+                assert_update_close(got_p["layers"][l][k], rnew[l][k], got_g["layers"][l][k], rg[l][k], 0.01, (l, k))
         bubbles = [(t1 - t0) for kind, _, _, _, t0, t1 in S.sif_read_trace(s.ctx, 0) if kind == 3]
         want = [ns for _, ns in OB.pp_1f1b_bubbles(stage, stages, micro, tf, tb)]
         assert len(bubbles) == len(want) == 4
