@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--cpu-sample", type=int, default=8, help="samples for the CPU oracle baseline (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=1000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--allow-serial-streams", action="store_true", help="for runs under a counter-collecting profiler, which serialises all kernels")
     ap.add_argument("--small", action="store_true", help="reduced shapes (development only; not a valid measurement)")
@@ -197,7 +197,7 @@ def main():
         "config": {"workload": "configs[1] data-parallel rank share: GPT decoder 12L d768 h12 seq1024 mb8 vocab50257 training step "
                                "+ 4.98 ms modelled all-reduce bubble, filled with BERT-base-shaped encoder inference 12L d768 seq128 batch32"
                                + (" [REDUCED --small]" if args.small else ""),
-                   "bubble_model": "gradient bytes / 50 GB/s, host-timed", "period_us": 100},
+                   "bubble_model": "gradient bytes / 50 GB/s, host-timed", "period_us": int(cfg.period_us)},
         "training_slowdown": slowdown,
         "slowdown_within_5pct": bool(slowdown <= 0.05),
         "solo_ms_per_step": 1e3 * solo_s / K,

@@ -7,22 +7,23 @@
 // forward products (A [M][K], B [N][K]), data gradients (B [K][N]), weight gradients (A [K][M], B [K][N]) and
 // the per-head attention products via two batch strides.
 //
-// Tiling: 128x128 block tile, K step 64, 256 threads = 4 wavefronts in a 2x2 grid, each wavefront owns a 64x64
-// tile as 2x2 v_mfma_f32_32x32x16_bf16 accumulators.  Operand tiles are staged through LDS with K contiguous
-// (unpadded rows of 128 bytes, XOR-swizzled in 16-byte chunks so that reads and writes spread over the banks); an operand whose
-// memory layout has the other dimension contiguous is transposed in registers (4x8 blocks) on its way to LDS.  Global loads of
-// the next K step are issued before the MFMAs of the current one (register prefetch, two LDS buffers).
+// Tiling: block tile BM x BN (128 x 128), K step 64, WM x WN (2 x 2) wavefronts, each owning a 64x64 tile as 2x2
+// v_mfma_f32_32x32x16_bf16 accumulators; two blocks per CU.  Operand tiles are staged through LDS with K contiguous
+// (unpadded rows of 128 bytes, XOR-swizzled in 16-byte chunks so that reads and writes spread over the banks); an
+// operand whose memory layout has the other dimension contiguous is transposed in registers (4x8 blocks) on its
+// way to LDS.  Global loads of the next K step are issued before the MFMAs of the current one (register prefetch,
+// two LDS buffers).  (A 256x256 tile with 128x64 per wavefront would need a quarter fewer LDS reads per MFMA, but
+// its 128 accumulator + 64 prefetch registers leave the compiler no room: it spills inside the K loop.)
 //
-// Results do not depend on the grid: each output element is reduced over K in one fixed order by one
-// wavefront, so launching a row range of the same problem gives bit-identical rows.
+// Results do not depend on the grid: each output element is reduced over K in one fixed order (ascending, 16 at a
+// time) by one wavefront, so launching a row range of the same problem gives bit-identical rows.
 #include "common.h"
 #include "specinf.h"
 #include "launch.h"
 
 namespace sif {
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int GEMM_THREADS = 256;
+constexpr int BK = 64;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
@@ -34,20 +35,27 @@ struct GemmP {
   float alpha;
 };
 
-// LDS tile: 128 rows x 64 k (bf16), 128 bytes per row = eight 16-byte chunks, no padding.  Chunk c of row r
+// LDS tile: rows x 64 k (bf16), 128 bytes per row = eight 16-byte chunks, no padding.  Chunk c of row r
 // lives at chunk position c ^ key(r).  The key makes eight consecutive rows use eight different chunk positions
 // (conflict-free 16-byte reads with 32 banks) and sixteen consecutive rows sixteen different (row parity, position)
 // pairs (conflict-free with 64 banks) for the same logical chunk, which is how the MFMA operands are read.
 __device__ __forceinline__ uint32_t swz_key(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
 __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) { return row * BK + ((chunk ^ swz_key(row)) << 3); }
 
-// Loads one 128 x 64 operand tile into registers (4 x 16 bytes per thread).
-//   LAYOUT 0: memory [row][k]: thread vector v covers row v/8, k chunk v%8.
-//   LAYOUT 1: memory [k][row]: a thread covers eight tile rows and four consecutive k rows (see store_tile).
-// Vectors outside the logical extents read as zero.  The loads are unconditional (an out-of-range vector reads
-// the operand's first element instead and is zeroed afterwards), so that they can be issued back to back and
-// waited for selectively.
-template <int LAYOUT>
+// How the threads of a block cover one operand tile of 32 * THREADS / 64 rows x 64 k, four 16-byte vectors each:
+//   LAYOUT 0: memory [row][k]: vector v = thread + i * THREADS covers row v/8, k chunk v%8.
+//   LAYOUT 1: memory [k][row]: a thread covers eight tile rows (one vector) at four consecutive k; four wavefronts
+//             span 128 rows x 64 k, further groups of four wavefronts the next 128 rows.
+struct KmajorPos { uint32_t r0, kq; };
+__device__ __forceinline__ KmajorPos kmajor_pos() {
+  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  return KmajorPos{((wave >> 2) * 16 + (lane >> 2)) * 8, ((wave & 3) * 4 + (lane & 3)) * 4};
+}
+
+// Loads one operand tile into registers.  Vectors outside the logical extents read as zero.  The loads are
+// unconditional (an out-of-range vector reads the operand's first element instead and is zeroed afterwards), so
+// that they can be issued back to back and waited for selectively.
+template <int LAYOUT, int THREADS>
 __device__ __forceinline__ uint32_t load_tile(uint4 (&r)[4], const bf16_t* __restrict__ base, uint32_t ld, uint32_t row0,
                                               uint32_t rows, uint32_t k0, uint32_t k_end) {
   bool ok[4];
@@ -55,17 +63,17 @@ __device__ __forceinline__ uint32_t load_tile(uint4 (&r)[4], const bf16_t* __res
   if (LAYOUT == 0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t v = threadIdx.x + i * GEMM_THREADS;
+      const uint32_t v = threadIdx.x + i * THREADS;
       const uint32_t rr = row0 + (v >> 3), kk = k0 + (v & 7) * 8;
       ok[i] = rr < rows && kk < k_end;
       ptr[i] = ok[i] ? base + (size_t)rr * ld + kk : base;
     }
   } else {
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t rr = row0 + (lane >> 2) * 8, kq = (wave * 4 + (lane & 3)) * 4;
+    const KmajorPos q = kmajor_pos();
+    const uint32_t rr = row0 + q.r0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t kk = k0 + kq + i;
+      const uint32_t kk = k0 + q.kq + i;
       ok[i] = rr < rows && kk < k_end;
       ptr[i] = ok[i] ? base + (size_t)kk * ld + rr : base;
     }
@@ -77,7 +85,7 @@ __device__ __forceinline__ uint32_t load_tile(uint4 (&r)[4], const bf16_t* __res
   return (ok[0] ? 1u : 0u) | (ok[1] ? 2u : 0u) | (ok[2] ? 4u : 0u) | (ok[3] ? 8u : 0u);
 }
 
-template <int LAYOUT>
+template <int LAYOUT, int THREADS>
 __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], uint32_t okmask) {
   uint4 r[4];
 #pragma unroll
@@ -88,13 +96,12 @@ __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], u
   if (LAYOUT == 0) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint32_t v = threadIdx.x + i * GEMM_THREADS;
+      const uint32_t v = threadIdx.x + i * THREADS;
       *reinterpret_cast<uint4*>(lds + lds_off(v >> 3, v & 7)) = r[i];
     }
   } else {
     // 4 (k) x 8 (row) block held as four row vectors -> eight 4-element k runs, one per tile row
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const uint32_t r0 = (lane >> 2) * 8, kq = (wave * 4 + (lane & 3)) * 4;
+    const KmajorPos q = kmajor_pos();
     const uint32_t w0[4] = {r[0].x, r[0].y, r[0].z, r[0].w}, w1[4] = {r[1].x, r[1].y, r[1].z, r[1].w};
     const uint32_t w2[4] = {r[2].x, r[2].y, r[2].z, r[2].w}, w3[4] = {r[3].x, r[3].y, r[3].z, r[3].w};
 #pragma unroll
@@ -102,18 +109,18 @@ __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], u
       uint2 even, odd;
       even.x = (w0[j] & 0xFFFFu) | (w1[j] << 16);  even.y = (w2[j] & 0xFFFFu) | (w3[j] << 16);
       odd.x = (w0[j] >> 16) | (w1[j] & 0xFFFF0000u);  odd.y = (w2[j] >> 16) | (w3[j] & 0xFFFF0000u);
-      const uint32_t ra = r0 + 2 * j, rb = ra + 1;
-      *reinterpret_cast<uint2*>(lds + lds_off(ra, kq >> 3) + (kq & 7)) = even;
-      *reinterpret_cast<uint2*>(lds + lds_off(rb, kq >> 3) + (kq & 7)) = odd;
+      const uint32_t ra = q.r0 + 2 * j, rb = ra + 1;
+      *reinterpret_cast<uint2*>(lds + lds_off(ra, q.kq >> 3) + (q.kq & 7)) = even;
+      *reinterpret_cast<uint2*>(lds + lds_off(rb, q.kq >> 3) + (q.kq & 7)) = odd;
     }
   }
 }
 
-// Interior tiles (all 128 rows inside the operand, K range a whole number of K steps) need no bounds handling at
+// Interior tiles (all rows inside the operand, K range a whole number of K steps) need no bounds handling at
 // all: the tile's first element is a block-uniform pointer that advances by one K step per load, each thread adds
 // one constant 32-bit offset, and the four vectors of a thread differ by a block-uniform stride, so the address
 // arithmetic stays on the scalar unit and the vector ALU is left to the MFMAs and the transposes.
-template <int LAYOUT>
+template <int LAYOUT, int THREADS>
 struct InteriorStream {
   const char* tile;          // first byte of the next tile
   size_t step, vstride;      // bytes per K step; bytes between a thread's consecutive vectors
@@ -122,14 +129,14 @@ struct InteriorStream {
     if (LAYOUT == 0) {
       tile = (const char*)(b + (size_t)row0 * ld + k_begin);
       step = BK * sizeof(bf16_t);
-      vstride = (size_t)(GEMM_THREADS / 8) * ld * sizeof(bf16_t);
+      vstride = (size_t)(THREADS / 8) * ld * sizeof(bf16_t);
       voff = ((threadIdx.x >> 3) * ld + (threadIdx.x & 7) * 8) * (uint32_t)sizeof(bf16_t);
     } else {
-      const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+      const KmajorPos q = kmajor_pos();
       tile = (const char*)(b + (size_t)k_begin * ld + row0);
       step = (size_t)BK * ld * sizeof(bf16_t);
       vstride = (size_t)ld * sizeof(bf16_t);
-      voff = ((wave * 4 + (lane & 3)) * 4 * ld + (lane >> 2) * 8) * (uint32_t)sizeof(bf16_t);
+      voff = (q.kq * ld + q.r0) * (uint32_t)sizeof(bf16_t);
     }
   }
   __device__ __forceinline__ void next(uint4 (&r)[4]) {
@@ -139,8 +146,73 @@ struct InteriorStream {
   }
 };
 
-template <int ALAY, int BLAY>
-__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
+// Epilogue of eight consecutive columns n..n+7 of row m (both inside the result): scale, bias, GELU, GELU' multiply,
+// residual, store; `vec` says that every access may be a 16-byte vector.
+__device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uint32_t m, uint32_t n, float (&v)[8], bool vec) {
+  const uint32_t epi = p.epi;
+  const size_t idx = c_off + (size_t)m * p.ldc + n;
+  if (vec) {
+    float b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (p.bias != nullptr) {
+      const uint4 q = *reinterpret_cast<const uint4*>(p.bias + n);
+      b[0] = bflo(q.x); b[1] = bfhi(q.x); b[2] = bflo(q.y); b[3] = bfhi(q.y); b[4] = bflo(q.z); b[5] = bfhi(q.z); b[6] = bflo(q.w); b[7] = bfhi(q.w);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = v[e] * p.alpha + b[e];
+    if (epi & SIF_EPI_GELU) {
+      if (p.aux != nullptr)
+        *reinterpret_cast<uint4*>(p.aux + idx) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+    }
+    if (epi & SIF_EPI_GELU_GRAD) {
+      const uint4 q = *reinterpret_cast<const uint4*>(p.aux + idx);
+      const float z[8] = {bflo(q.x), bfhi(q.x), bflo(q.y), bfhi(q.y), bflo(q.z), bfhi(q.z), bflo(q.w), bfhi(q.w)};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(z[e]);
+    }
+    if (epi & SIF_EPI_OUT_F32) {
+      float* cp = reinterpret_cast<float*>(p.c) + idx;
+      if (epi & SIF_EPI_RESIDUAL) {
+        const float* rp = reinterpret_cast<const float*>(p.res) + idx;
+        const float4 r0 = *reinterpret_cast<const float4*>(rp), r1 = *reinterpret_cast<const float4*>(rp + 4);
+        v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
+      }
+      *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      if (epi & SIF_EPI_RESIDUAL) {
+        const uint4 q = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
+        v[0] += bflo(q.x); v[1] += bfhi(q.x); v[2] += bflo(q.y); v[3] += bfhi(q.y); v[4] += bflo(q.z); v[5] += bfhi(q.z); v[6] += bflo(q.w); v[7] += bfhi(q.w);
+      }
+      *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + idx) =
+          make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+    }
+  } else {
+    // ragged N (or an output slice that is not 16-byte aligned): one element at a time
+    for (int e = 0; e < 8 && n + e < p.n; ++e) {
+      float x = v[e] * p.alpha + (p.bias != nullptr ? bf2f(p.bias[n + e]) : 0.f);
+      if (epi & SIF_EPI_GELU) {
+        if (p.aux != nullptr) p.aux[idx + e] = f2bf(x);
+        x = gelu_f(x);
+      }
+      if (epi & SIF_EPI_GELU_GRAD) x *= gelu_grad_f(bf2f(p.aux[idx + e]));
+      if (epi & SIF_EPI_OUT_F32) {
+        if (epi & SIF_EPI_RESIDUAL) x += reinterpret_cast<const float*>(p.res)[idx + e];
+        reinterpret_cast<float*>(p.c)[idx + e] = x;
+      } else {
+        if (epi & SIF_EPI_RESIDUAL) x += bf2f(reinterpret_cast<const bf16_t*>(p.res)[idx + e]);
+        reinterpret_cast<bf16_t*>(p.c)[idx + e] = f2bf(x);
+      }
+    }
+  }
+}
+
+template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE>
+__global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
+  constexpr int THREADS = 64 * WM * WN, TI = BM / (WM * 32), TJ = BN / (WN * 32), WCOLS = TJ * 32;
+  static_assert(BM * 8 == 4 * THREADS && BN * 8 == 4 * THREADS, "four 16-byte vectors per thread and operand tile");
+  static_assert(WCOLS == 64, "the epilogue staging is laid out for 64 columns per wavefront");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);            // [2][BM][BK], swizzled
   bf16_t* sB = sA + 2 * BM * BK;                               // [2][BN][BK]
@@ -170,12 +242,12 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCt
     if (p.k_causal == 2) k_begin = (m0 / BK) * BK;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    floatx16 acc[2][2];
+    const int wm = wave / WN, wn = wave % WN;
+    floatx16 acc[TI][TJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < TJ; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
@@ -183,170 +255,119 @@ __global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_bf16_kernel(GemmP p, KCt
     // multiplied out of LDS buffer t & 1, tile t+1 is landing in the other set and the load of tile t+2 is issued
     // into the set tile t has just left, so every global load has two iterations of MFMA work to hide behind.
     uint4 ra0[4], rb0[4], ra1[4], rb1[4];
-    const uint32_t fra = wm * 64 + (lane & 31), frb = wn * 64 + (lane & 31), kh = lane >> 5;
+    const uint32_t fra = wm * (TI * 32) + (lane & 31), frb = wn * (TJ * 32) + (lane & 31), kh = lane >> 5;
     auto compute = [&](int buf) {
       const bf16_t* cA = sA + buf * BM * BK;
       const bf16_t* cB = sB + buf * BN * BK;
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
-        bf16x8 fa[2], fb[2];
+        bf16x8 fa[TI], fb[TJ];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          fa[i] = *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh));
-          fb[i] = *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + i * 32, ks * 2 + kh));
-        }
+        for (int i = 0; i < TI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh));
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < TJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + j * 32, ks * 2 + kh));
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+        for (int i = 0; i < TI; ++i)
+#pragma unroll
+          for (int j = 0; j < TJ; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
       }
     };
     // The loop takes two K steps per trip (the register sets and LDS buffers alternate by name) and has no exit in
     // its middle, so that the accumulators stay in the same registers throughout; an odd last tile is done after it.
     const uint32_t nt = (k_end - k_begin + BK - 1) / BK;
-    const bool interior = m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0;
+    // without EDGE the launcher guarantees that every tile is interior
+    const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
     if (interior) {
-      InteriorStream<ALAY> ta(A, p.lda, m0, k_begin);
-      InteriorStream<BLAY> tb(B, p.ldb, n0, k_begin);
+      InteriorStream<ALAY, THREADS> ta(A, p.lda, m0, k_begin);
+      InteriorStream<BLAY, THREADS> tb(B, p.ldb, n0, k_begin);
       ta.next(ra0); tb.next(rb0);
       if (nt > 1) { ta.next(ra1); tb.next(rb1); }
-      store_tile<ALAY>(sA, ra0, 0xFu);
-      store_tile<BLAY>(sB, rb0, 0xFu);
+      store_tile<ALAY, THREADS>(sA, ra0, 0xFu);
+      store_tile<BLAY, THREADS>(sB, rb0, 0xFu);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         if (t + 2 < nt) { ta.next(ra0); tb.next(rb0); }
         compute(0);
-        store_tile<ALAY>(sA + BM * BK, ra1, 0xFu);
-        store_tile<BLAY>(sB + BN * BK, rb1, 0xFu);
+        store_tile<ALAY, THREADS>(sA + BM * BK, ra1, 0xFu);
+        store_tile<BLAY, THREADS>(sB + BN * BK, rb1, 0xFu);
         __syncthreads();
         if (t + 3 < nt) { ta.next(ra1); tb.next(rb1); }
         compute(1);
         if (t + 2 < nt) {
-          store_tile<ALAY>(sA, ra0, 0xFu);
-          store_tile<BLAY>(sB, rb0, 0xFu);
+          store_tile<ALAY, THREADS>(sA, ra0, 0xFu);
+          store_tile<BLAY, THREADS>(sB, rb0, 0xFu);
         }
         __syncthreads();
       }
-    } else {
-      uint32_t oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
-      uint32_t okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
-      uint32_t oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
-      uint32_t okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
-      store_tile<ALAY>(sA, ra0, oka0);
-      store_tile<BLAY>(sB, rb0, okb0);
+    } else if (EDGE) {
+      uint32_t oka0 = load_tile<ALAY, THREADS>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
+      uint32_t okb0 = load_tile<BLAY, THREADS>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
+      uint32_t oka1 = load_tile<ALAY, THREADS>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
+      uint32_t okb1 = load_tile<BLAY, THREADS>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
+      store_tile<ALAY, THREADS>(sA, ra0, oka0);
+      store_tile<BLAY, THREADS>(sB, rb0, okb0);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         const uint32_t k0 = k_begin + t * BK;
-        oka0 = load_tile<ALAY>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
-        okb0 = load_tile<BLAY>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
+        oka0 = load_tile<ALAY, THREADS>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
+        okb0 = load_tile<BLAY, THREADS>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
         compute(0);
-        store_tile<ALAY>(sA + BM * BK, ra1, oka1);
-        store_tile<BLAY>(sB + BN * BK, rb1, okb1);
+        store_tile<ALAY, THREADS>(sA + BM * BK, ra1, oka1);
+        store_tile<BLAY, THREADS>(sB + BN * BK, rb1, okb1);
         __syncthreads();
-        oka1 = load_tile<ALAY>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
-        okb1 = load_tile<BLAY>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
+        oka1 = load_tile<ALAY, THREADS>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
+        okb1 = load_tile<BLAY, THREADS>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
         compute(1);
-        store_tile<ALAY>(sA, ra0, oka0);
-        store_tile<BLAY>(sB, rb0, okb0);
+        store_tile<ALAY, THREADS>(sA, ra0, oka0);
+        store_tile<BLAY, THREADS>(sB, rb0, okb0);
         __syncthreads();
       }
     }
     if (nt & 1u) compute(0);
 
-    // Epilogue.  The accumulators go through LDS (fp32, the 64 KB of the operand buffers) so that every global
-    // access of the epilogue - bias, residual, auxiliary tensor, result - is a 16-byte vector along a row.
-    // Accumulator element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
+    // Epilogue.  Each wavefront passes its accumulators, 32 rows at a time, through a staging area of its own in
+    // LDS (fp32 [32][64], the operand buffers are free by now) so that every global access of the epilogue - bias,
+    // residual, auxiliary tensor, result - is a 16-byte vector along a row; no block-wide barrier is needed after
+    // the first.  Accumulator element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
+    // Chunk c (four floats) of staging row r lives at c ^ (8*((r/4)%2) | r%2): the two half-wavefronts of a store
+    // and the eight rows of a load then fall on different banks.
     __syncthreads();
-    float* sC = reinterpret_cast<float*>(smem_raw);              // [128][128], 16-byte chunks XOR-swizzled by row
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const uint32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-          const uint32_t col = wn * 64 + j * 32 + (lane & 31);
-          sC[row * BN + ((((col >> 2) ^ (row & 31)) << 2) | (col & 3))] = acc[i][j][r];
-        }
-    __syncthreads();
-    const uint32_t epi = p.epi;
+    float* sW = reinterpret_cast<float*>(smem_raw) + wave * (32 * WCOLS);
     const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
     const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
-#pragma unroll 2
-    for (int it = 0; it < 8; ++it) {
-      const uint32_t ch = threadIdx.x + it * GEMM_THREADS;       // 2048 chunks of 8 columns
-      const uint32_t row = ch >> 4, col = (ch & 15) * 8;
-      const uint32_t m = m0 + row, n = n0 + col;
-      if (m >= p.m || n >= p.n) continue;
-      float v[8];
-      {
-        const float4 q0 = *reinterpret_cast<const float4*>(sC + row * BN + ((((col >> 2)) ^ (row & 31)) << 2));
-        const float4 q1 = *reinterpret_cast<const float4*>(sC + row * BN + ((((col >> 2) + 1) ^ (row & 31)) << 2));
-        v[0] = q0.x; v[1] = q0.y; v[2] = q0.z; v[3] = q0.w; v[4] = q1.x; v[5] = q1.y; v[6] = q1.z; v[7] = q1.w;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), col = j * 32 + (lane & 31);
+          sW[row * WCOLS + ((((col >> 2) ^ ((((row >> 2) & 1) << 3) | (row & 1))) << 2) | (col & 3))] = acc[i][j][r];
+        }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < WCOLS / 16; ++it) {
+        const uint32_t ch = lane + it * 64, row = ch >> 3, c8 = ch & 7;      // 32 rows x 8 chunks of 8 columns
+        const uint32_t key = (((row >> 2) & 1) << 3) | (row & 1);
+        const float4 q0 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8) ^ key) << 2));
+        const float4 q1 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8 + 1) ^ key) << 2));
+        float v[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+        const uint32_t m = m0 + wm * (TI * 32) + i * 32 + row, n = n0 + wn * WCOLS + c8 * 8;
+        if (m < p.m && n < p.n) gemm_epilogue8(p, c_off, m, n, v, vec_ok);
       }
-      const size_t idx = c_off + (size_t)m * p.ldc + n;
-      if (vec_ok) {
-        float b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (p.bias != nullptr) {
-          const uint4 q = *reinterpret_cast<const uint4*>(p.bias + n);
-          b[0] = bflo(q.x); b[1] = bfhi(q.x); b[2] = bflo(q.y); b[3] = bfhi(q.y); b[4] = bflo(q.z); b[5] = bfhi(q.z); b[6] = bflo(q.w); b[7] = bfhi(q.w);
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = v[e] * p.alpha + b[e];
-        if (epi & SIF_EPI_GELU) {
-          if (p.aux != nullptr)
-            *reinterpret_cast<uint4*>(p.aux + idx) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
-        }
-        if (epi & SIF_EPI_GELU_GRAD) {
-          const uint4 q = *reinterpret_cast<const uint4*>(p.aux + idx);
-          const float z[8] = {bflo(q.x), bfhi(q.x), bflo(q.y), bfhi(q.y), bflo(q.z), bfhi(q.z), bflo(q.w), bfhi(q.w)};
-#pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(z[e]);
-        }
-        if (epi & SIF_EPI_OUT_F32) {
-          float* cp = reinterpret_cast<float*>(p.c) + idx;
-          if (epi & SIF_EPI_RESIDUAL) {
-            const float* rp = reinterpret_cast<const float*>(p.res) + idx;
-            const float4 r0 = *reinterpret_cast<const float4*>(rp), r1 = *reinterpret_cast<const float4*>(rp + 4);
-            v[0] += r0.x; v[1] += r0.y; v[2] += r0.z; v[3] += r0.w; v[4] += r1.x; v[5] += r1.y; v[6] += r1.z; v[7] += r1.w;
-          }
-          *reinterpret_cast<float4*>(cp) = make_float4(v[0], v[1], v[2], v[3]);
-          *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
-        } else {
-          if (epi & SIF_EPI_RESIDUAL) {
-            const uint4 q = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
-            v[0] += bflo(q.x); v[1] += bfhi(q.x); v[2] += bflo(q.y); v[3] += bfhi(q.y); v[4] += bflo(q.z); v[5] += bfhi(q.z); v[6] += bflo(q.w); v[7] += bfhi(q.w);
-          }
-          *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + idx) =
-              make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
-        }
-      } else {
-        // ragged N (or an output slice that is not 16-byte aligned): one element at a time
-        for (int e = 0; e < 8 && n + e < p.n; ++e) {
-          float x = v[e] * p.alpha + (p.bias != nullptr ? bf2f(p.bias[n + e]) : 0.f);
-          if (epi & SIF_EPI_GELU) {
-            if (p.aux != nullptr) p.aux[idx + e] = f2bf(x);
-            x = gelu_f(x);
-          }
-          if (epi & SIF_EPI_GELU_GRAD) x *= gelu_grad_f(bf2f(p.aux[idx + e]));
-          if (epi & SIF_EPI_OUT_F32) {
-            if (epi & SIF_EPI_RESIDUAL) x += reinterpret_cast<const float*>(p.res)[idx + e];
-            reinterpret_cast<float*>(p.c)[idx + e] = x;
-          } else {
-            if (epi & SIF_EPI_RESIDUAL) x += bf2f(reinterpret_cast<const bf16_t*>(p.res)[idx + e]);
-            reinterpret_cast<bf16_t*>(p.c)[idx + e] = f2bf(x);
-          }
-        }
-      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
   kernel_end(ctl, true);
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+typedef void (*gemm_kern_t)(GemmP, KCtl);
+struct GemmVariant { gemm_kern_t fn; bool attr_set; };
 
 sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KCtl& ctl) {
   if (a == nullptr || a->struct_size != sizeof(sif_gemm_args)) return fail(SIF_E_INVAL, "gemm: bad args struct");
@@ -369,6 +390,8 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
     if ((a->ldc & 7) || ((a->c_stride_outer | a->c_stride_inner) & 7)) return fail(SIF_E_INVAL, "gemm: ldc and the output batch strides must be multiples of 8 when n is");
     if ((a->bias_dev && !aligned16(a->bias_dev)) || (a->res_dev && !aligned16(a->res_dev)) || (a->aux_dev && !aligned16(a->aux_dev))) return fail(SIF_E_INVAL, "gemm: bias, residual and aux must be 16-byte aligned");
   }
+  const uint32_t bm = 128, bn = 128;
+  const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
   GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;
   p.bias = (a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) ? (const bf16_t*)a->bias_dev : nullptr;
@@ -377,21 +400,20 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   p.epi = a->epilogue; p.k_causal = a->k_causal; p.batch_inner = a->batch_inner;
   p.a_so = a->a_stride_outer; p.a_si = a->a_stride_inner; p.b_so = a->b_stride_outer; p.b_si = a->b_stride_inner;
   p.c_so = a->c_stride_outer; p.c_si = a->c_stride_inner; p.alpha = a->alpha;
-  p.tiles_n = (a->n + BN - 1) / BN; p.tiles_m = (a->m + BM - 1) / BM;
-  dim3 grid(p.tiles_m * p.tiles_n, 1, a->batch_outer * a->batch_inner);
-  if (grid.z > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
-  const size_t lds = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  typedef void (*kern_t)(GemmP, KCtl);
-  static const kern_t table[2][2] = {{gemm_bf16_kernel<0, 0>, gemm_bf16_kernel<0, 1>},
-                                     {gemm_bf16_kernel<1, 0>, gemm_bf16_kernel<1, 1>}};
-  kern_t kern = table[a->a_layout][a->b_layout];
-  static bool attr_set[2][2] = {{false, false}, {false, false}};
-  if (!attr_set[a->a_layout][a->b_layout]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  p.tiles_n = (a->n + bn - 1) / bn; p.tiles_m = (a->m + bm - 1) / bm;
+  if (batches > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
+  dim3 grid(p.tiles_m * p.tiles_n, 1, (uint32_t)batches);
+  const size_t lds = (size_t)2 * (bm + bn) * BK * sizeof(bf16_t);
+  static GemmVariant table[2][2] = {
+      {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, false}, {gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>, false}},
+      {{gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, false}, {gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>, false}}};
+  GemmVariant& v = table[a->a_layout][a->b_layout];
+  if (!v.attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return fail_hip(e, "gemm: hipFuncSetAttribute");
-    attr_set[a->a_layout][a->b_layout] = true;
+    v.attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(GEMM_THREADS), lds, stream, p, ctl);
+  hipLaunchKernelGGL(v.fn, grid, dim3(256), lds, stream, p, ctl);
   return check_launch("gemm_bf16");
 }
 
