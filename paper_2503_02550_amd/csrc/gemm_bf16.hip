@@ -10,8 +10,8 @@
 // Tiling: block tile BM x BN (128 x 128), K step 64, WM x WN (2 x 2) wavefronts, each owning a 64x64 tile as 2x2
 // v_mfma_f32_32x32x16_bf16 accumulators; two blocks per CU.  Operand tiles are staged through LDS with K contiguous
 // (unpadded rows of 128 bytes, XOR-swizzled in 16-byte chunks so that reads and writes spread over the banks); an
-// operand whose memory layout has the other dimension contiguous is transposed in registers (4x8 blocks) on its
-// way to LDS.  Global loads of the next K step are issued before the MFMAs of the current one (register prefetch,
+// operand whose memory layout has the other dimension contiguous is staged as it lies and transposed by the LDS
+// read itself (ds_read_b64_tr_b16).  Global loads of the next K step are issued before the MFMAs of the current one (register prefetch,
 // two LDS buffers).  (A 256x256 tile with 128x64 per wavefront would need a quarter fewer LDS reads per MFMA, but
 // its 128 accumulator + 64 prefetch registers leave the compiler no room: it spills inside the K loop.)
 //
@@ -42,38 +42,50 @@ struct GemmP {
 __device__ __forceinline__ uint32_t swz_key(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
 __device__ __forceinline__ uint32_t lds_off(uint32_t row, uint32_t chunk) { return row * BK + ((chunk ^ swz_key(row)) << 3); }
 
-// How the threads of a block cover one operand tile of 32 * THREADS / 64 rows x 64 k, four 16-byte vectors each:
-//   LAYOUT 0: memory [row][k]: vector v = thread + i * THREADS covers row v/8, k chunk v%8.
-//   LAYOUT 1: memory [k][row]: a thread covers eight tile rows (one vector) at four consecutive k; four wavefronts
-//             span 128 rows x 64 k, further groups of four wavefronts the next 128 rows.
-struct KmajorPos { uint32_t r0, kq; };
-__device__ __forceinline__ KmajorPos kmajor_pos() {
-  const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  return KmajorPos{((wave >> 2) * 16 + (lane >> 2)) * 8, ((wave & 3) * 4 + (lane & 3)) * 4};
+// A K-major operand (memory [k][row]) is staged as it lies in memory: LDS tile [64 k][ROWS], 2*ROWS bytes per k,
+// the 64-byte segments (32 rows) of k-row k stored at segment position seg ^ (k % 4).  The MFMA operand - eight
+// consecutive k for one row per lane - is then fetched with the transposing LDS read of gfx950
+// (ds_read_b64_tr_b16): within each group of 16 lanes, source lane s supplies the address of four consecutive rows
+// at k = k0 + s/4, rows r0 + 4*(s%4).., and lane i receives rows r0 + i at k0..k0+3.  Two such reads make one
+// operand; the four k-rows a half-wavefront touches lie in four different 64-byte bank groups.
+typedef short short4_lds __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t kmajor_off(uint32_t k, uint32_t row, uint32_t rows_pitch) {
+  return k * rows_pitch + ((((row >> 5) ^ (k & 3u)) << 5) | (row & 31u));
+}
+template <int ROWS>
+__device__ __forceinline__ bf16x8 kmajor_frag(const bf16_t* tile, uint32_t rowbase32, uint32_t kbase8) {
+  // rowbase32: first of the 32 operand rows (a multiple of 32); kbase8: first of this lane half's eight k
+  const uint32_t lane = threadIdx.x & 63, s = lane & 15, sw = s >> 2;
+  const bf16_t* p = tile + (kbase8 + sw) * ROWS + ((((rowbase32 >> 5) ^ sw) << 5) | (((lane >> 4) & 1u) * 16 + 4 * (s & 3u)));
+  typedef __attribute__((address_space(3))) short4_lds* lds_ptr;
+  const short4_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
+  const short4_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * ROWS));
+  typedef short short8_v __attribute__((ext_vector_type(8)));
+  const short8_v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
 }
 
+// How the threads of a block cover one operand tile (ROWS rows x 64 k), four 16-byte vectors each
+// (vector v = thread + i * THREADS):
+//   LAYOUT 0: memory [row][k]: row v/8, k chunk v%8.
+//   LAYOUT 1: memory [k][row]: k-row v/(ROWS/8), row chunk v%(ROWS/8).
 // Loads one operand tile into registers.  Vectors outside the logical extents read as zero.  The loads are
 // unconditional (an out-of-range vector reads the operand's first element instead and is zeroed afterwards), so
 // that they can be issued back to back and waited for selectively.
-template <int LAYOUT, int THREADS>
+template <int LAYOUT, int THREADS, int ROWS>
 __device__ __forceinline__ uint32_t load_tile(uint4 (&r)[4], const bf16_t* __restrict__ base, uint32_t ld, uint32_t row0,
                                               uint32_t rows, uint32_t k0, uint32_t k_end) {
   bool ok[4];
   const bf16_t* ptr[4];
-  if (LAYOUT == 0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t v = threadIdx.x + i * THREADS;
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t v = threadIdx.x + i * THREADS;
+    if (LAYOUT == 0) {
       const uint32_t rr = row0 + (v >> 3), kk = k0 + (v & 7) * 8;
       ok[i] = rr < rows && kk < k_end;
       ptr[i] = ok[i] ? base + (size_t)rr * ld + kk : base;
-    }
-  } else {
-    const KmajorPos q = kmajor_pos();
-    const uint32_t rr = row0 + q.r0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t kk = k0 + q.kq + i;
+    } else {
+      const uint32_t rr = row0 + (v % (ROWS / 8)) * 8, kk = k0 + v / (ROWS / 8);
       ok[i] = rr < rows && kk < k_end;
       ptr[i] = ok[i] ? base + (size_t)kk * ld + rr : base;
     }
@@ -85,42 +97,23 @@ __device__ __forceinline__ uint32_t load_tile(uint4 (&r)[4], const bf16_t* __res
   return (ok[0] ? 1u : 0u) | (ok[1] ? 2u : 0u) | (ok[2] ? 4u : 0u) | (ok[3] ? 8u : 0u);
 }
 
-template <int LAYOUT, int THREADS>
+template <int LAYOUT, int THREADS, int ROWS>
 __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], uint32_t okmask) {
-  uint4 r[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const uint32_t keep = (okmask >> i) & 1u ? 0xFFFFFFFFu : 0u;       // folds away for a constant all-ones mask
-    r[i] = make_uint4(rin[i].x & keep, rin[i].y & keep, rin[i].z & keep, rin[i].w & keep);
-  }
-  if (LAYOUT == 0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint32_t v = threadIdx.x + i * THREADS;
-      *reinterpret_cast<uint4*>(lds + lds_off(v >> 3, v & 7)) = r[i];
-    }
-  } else {
-    // 4 (k) x 8 (row) block held as four row vectors -> eight 4-element k runs, one per tile row
-    const KmajorPos q = kmajor_pos();
-    const uint32_t w0[4] = {r[0].x, r[0].y, r[0].z, r[0].w}, w1[4] = {r[1].x, r[1].y, r[1].z, r[1].w};
-    const uint32_t w2[4] = {r[2].x, r[2].y, r[2].z, r[2].w}, w3[4] = {r[3].x, r[3].y, r[3].z, r[3].w};
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint2 even, odd;
-      even.x = (w0[j] & 0xFFFFu) | (w1[j] << 16);  even.y = (w2[j] & 0xFFFFu) | (w3[j] << 16);
-      odd.x = (w0[j] >> 16) | (w1[j] & 0xFFFF0000u);  odd.y = (w2[j] >> 16) | (w3[j] & 0xFFFF0000u);
-      const uint32_t ra = q.r0 + 2 * j, rb = ra + 1;
-      *reinterpret_cast<uint2*>(lds + lds_off(ra, q.kq >> 3) + (q.kq & 7)) = even;
-      *reinterpret_cast<uint2*>(lds + lds_off(rb, q.kq >> 3) + (q.kq & 7)) = odd;
-    }
+    const uint4 r = make_uint4(rin[i].x & keep, rin[i].y & keep, rin[i].z & keep, rin[i].w & keep);
+    const uint32_t v = threadIdx.x + i * THREADS;
+    if (LAYOUT == 0) *reinterpret_cast<uint4*>(lds + lds_off(v >> 3, v & 7)) = r;
+    else *reinterpret_cast<uint4*>(lds + kmajor_off(v / (ROWS / 8), (v % (ROWS / 8)) * 8, ROWS)) = r;
   }
 }
 
 // Interior tiles (all rows inside the operand, K range a whole number of K steps) need no bounds handling at
 // all: the tile's first element is a block-uniform pointer that advances by one K step per load, each thread adds
 // one constant 32-bit offset, and the four vectors of a thread differ by a block-uniform stride, so the address
-// arithmetic stays on the scalar unit and the vector ALU is left to the MFMAs and the transposes.
-template <int LAYOUT, int THREADS>
+// arithmetic stays on the scalar unit and the vector ALU is left to the MFMAs.
+template <int LAYOUT, int THREADS, int ROWS>
 struct InteriorStream {
   const char* tile;          // first byte of the next tile
   size_t step, vstride;      // bytes per K step; bytes between a thread's consecutive vectors
@@ -132,11 +125,10 @@ struct InteriorStream {
       vstride = (size_t)(THREADS / 8) * ld * sizeof(bf16_t);
       voff = ((threadIdx.x >> 3) * ld + (threadIdx.x & 7) * 8) * (uint32_t)sizeof(bf16_t);
     } else {
-      const KmajorPos q = kmajor_pos();
       tile = (const char*)(b + (size_t)k_begin * ld + row0);
       step = (size_t)BK * ld * sizeof(bf16_t);
-      vstride = (size_t)ld * sizeof(bf16_t);
-      voff = (q.kq * ld + q.r0) * (uint32_t)sizeof(bf16_t);
+      vstride = (size_t)(THREADS / (ROWS / 8)) * ld * sizeof(bf16_t);
+      voff = ((threadIdx.x / (ROWS / 8)) * ld + (threadIdx.x % (ROWS / 8)) * 8) * (uint32_t)sizeof(bf16_t);
     }
   }
   __device__ __forceinline__ void next(uint4 (&r)[4]) {
@@ -263,9 +255,13 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8 fa[TI], fb[TJ];
 #pragma unroll
-        for (int i = 0; i < TI; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh));
+        for (int i = 0; i < TI; ++i)
+          fa[i] = ALAY == 0 ? *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh))
+                            : kmajor_frag<BM>(cA, wm * (TI * 32) + i * 32, ks * 16 + kh * 8);
 #pragma unroll
-        for (int j = 0; j < TJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + j * 32, ks * 2 + kh));
+        for (int j = 0; j < TJ; ++j)
+          fb[j] = BLAY == 0 ? *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + j * 32, ks * 2 + kh))
+                            : kmajor_frag<BN>(cB, wn * (TJ * 32) + j * 32, ks * 16 + kh * 8);
 #pragma unroll
         for (int i = 0; i < TI; ++i)
 #pragma unroll
@@ -279,48 +275,48 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // without EDGE the launcher guarantees that every tile is interior
     const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
     if (interior) {
-      InteriorStream<ALAY, THREADS> ta(A, p.lda, m0, k_begin);
-      InteriorStream<BLAY, THREADS> tb(B, p.ldb, n0, k_begin);
+      InteriorStream<ALAY, THREADS, BM> ta(A, p.lda, m0, k_begin);
+      InteriorStream<BLAY, THREADS, BN> tb(B, p.ldb, n0, k_begin);
       ta.next(ra0); tb.next(rb0);
       if (nt > 1) { ta.next(ra1); tb.next(rb1); }
-      store_tile<ALAY, THREADS>(sA, ra0, 0xFu);
-      store_tile<BLAY, THREADS>(sB, rb0, 0xFu);
+      store_tile<ALAY, THREADS, BM>(sA, ra0, 0xFu);
+      store_tile<BLAY, THREADS, BN>(sB, rb0, 0xFu);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         if (t + 2 < nt) { ta.next(ra0); tb.next(rb0); }
         compute(0);
-        store_tile<ALAY, THREADS>(sA + BM * BK, ra1, 0xFu);
-        store_tile<BLAY, THREADS>(sB + BN * BK, rb1, 0xFu);
+        store_tile<ALAY, THREADS, BM>(sA + BM * BK, ra1, 0xFu);
+        store_tile<BLAY, THREADS, BN>(sB + BN * BK, rb1, 0xFu);
         __syncthreads();
         if (t + 3 < nt) { ta.next(ra1); tb.next(rb1); }
         compute(1);
         if (t + 2 < nt) {
-          store_tile<ALAY, THREADS>(sA, ra0, 0xFu);
-          store_tile<BLAY, THREADS>(sB, rb0, 0xFu);
+          store_tile<ALAY, THREADS, BM>(sA, ra0, 0xFu);
+          store_tile<BLAY, THREADS, BN>(sB, rb0, 0xFu);
         }
         __syncthreads();
       }
     } else if (EDGE) {
-      uint32_t oka0 = load_tile<ALAY, THREADS>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
-      uint32_t okb0 = load_tile<BLAY, THREADS>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
-      uint32_t oka1 = load_tile<ALAY, THREADS>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
-      uint32_t okb1 = load_tile<BLAY, THREADS>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
-      store_tile<ALAY, THREADS>(sA, ra0, oka0);
-      store_tile<BLAY, THREADS>(sB, rb0, okb0);
+      uint32_t oka0 = load_tile<ALAY, THREADS, BM>(ra0, A, p.lda, m0, p.m, k_begin, k_end);
+      uint32_t okb0 = load_tile<BLAY, THREADS, BN>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
+      uint32_t oka1 = load_tile<ALAY, THREADS, BM>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
+      uint32_t okb1 = load_tile<BLAY, THREADS, BN>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
+      store_tile<ALAY, THREADS, BM>(sA, ra0, oka0);
+      store_tile<BLAY, THREADS, BN>(sB, rb0, okb0);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         const uint32_t k0 = k_begin + t * BK;
-        oka0 = load_tile<ALAY, THREADS>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
-        okb0 = load_tile<BLAY, THREADS>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
+        oka0 = load_tile<ALAY, THREADS, BM>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
+        okb0 = load_tile<BLAY, THREADS, BN>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
         compute(0);
-        store_tile<ALAY, THREADS>(sA + BM * BK, ra1, oka1);
-        store_tile<BLAY, THREADS>(sB + BN * BK, rb1, okb1);
+        store_tile<ALAY, THREADS, BM>(sA + BM * BK, ra1, oka1);
+        store_tile<BLAY, THREADS, BN>(sB + BN * BK, rb1, okb1);
         __syncthreads();
-        oka1 = load_tile<ALAY, THREADS>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
-        okb1 = load_tile<BLAY, THREADS>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
+        oka1 = load_tile<ALAY, THREADS, BM>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
+        okb1 = load_tile<BLAY, THREADS, BN>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
         compute(1);
-        store_tile<ALAY, THREADS>(sA, ra0, oka0);
-        store_tile<BLAY, THREADS>(sB, rb0, okb0);
+        store_tile<ALAY, THREADS, BM>(sA, ra0, oka0);
+        store_tile<BLAY, THREADS, BN>(sB, rb0, okb0);
         __syncthreads();
       }
     }
