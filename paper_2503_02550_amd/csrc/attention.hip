@@ -12,7 +12,7 @@
 // Every product is arranged so that the operand produced on chip (P, dS) goes from the accumulator registers of
 // one MFMA straight into the B operand of the next: an accumulator tile holds column (lane % 32) and the rows
 // 8*(r/4) + 4*(lane/32) + r%4, so as a B operand [k][col] its k index is a permutation of the row index, which is
-// applied to the reads of the matching A operand (a transposed copy in LDS) instead.  In the forward and the dq
+// applied to the reads of the matching A operand (fetched with the transposing LDS read) instead.  In the forward and the dq
 // kernel the products are taken transposed (S^T = K Q^T, O^T = V^T P^T, dQ^T = K^T dS^T): a query row then lives
 // in one lane and its partner 32 further, and the softmax statistics are per-lane scalars.  bf16 operands, fp32
 // accumulation and softmax; P and dS are rounded to bf16 where the unfused path stores them.
@@ -26,8 +26,8 @@ namespace sif {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int AT_Q = 128, AT_KV = 128, AT_THREADS = 256, AT_VLD = AT_KV + 4;   // transposed rows padded by 8 bytes
-constexpr int AT_QB = 64, AT_QLD = AT_QB + 4;                                    // query rows per step of the dk/dv kernel
+constexpr int AT_Q = 128, AT_KV = 128, AT_THREADS = 256;
+constexpr int AT_QB = 64;                                    // query rows per step of the dk/dv kernel
 
 __device__ __forceinline__ uint32_t at_key(uint32_t row) { return (row & 7u) ^ ((row >> 3) & 1u); }
 
@@ -43,41 +43,29 @@ __device__ __forceinline__ void at_load_rows(bf16_t* dst, const bf16_t* src, siz
     *reinterpret_cast<uint4*>(dst + row * DH + ((c ^ (at_key(row) % CH)) << 3)) = x;
   }
 }
-// The same tile transposed, [d][row] with rows of ROWS + 4 elements: each thread takes 4 rows x 8 d columns and
-// writes eight 4-long runs.
-template <int DH, int ROWS>
-__device__ __forceinline__ void at_load_rows_t(bf16_t* dst, const bf16_t* src, size_t ld, uint32_t row0, uint32_t limit) {
-  constexpr int CH = DH / 8, LD = ROWS + 4;
-  for (uint32_t sb = threadIdx.x; sb < (ROWS / 4) * CH; sb += AT_THREADS) {
-    const uint32_t rq = (sb / CH) * 4, d0 = (sb % CH) * 8;
-    uint32_t w[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      uint4 x = make_uint4(0, 0, 0, 0);
-      if (row0 + rq + i < limit) x = *reinterpret_cast<const uint4*>(src + (size_t)(row0 + rq + i) * ld + d0);
-      w[i][0] = x.x; w[i][1] = x.y; w[i][2] = x.z; w[i][3] = x.w;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint2 even, odd;
-      even.x = (w[0][j] & 0xFFFFu) | (w[1][j] << 16);  even.y = (w[2][j] & 0xFFFFu) | (w[3][j] << 16);
-      odd.x = (w[0][j] >> 16) | (w[1][j] & 0xFFFF0000u);  odd.y = (w[2][j] >> 16) | (w[3][j] & 0xFFFF0000u);
-      *reinterpret_cast<uint2*>(dst + (d0 + 2 * j) * LD + rq) = even;
-      *reinterpret_cast<uint2*>(dst + (d0 + 2 * j + 1) * LD + rq) = odd;
-    }
-  }
-}
 // A operand (row, k = 8 consecutive d) from a swizzled [row][d] tile; chunk = k / 8.
 template <int DH>
 __device__ __forceinline__ bf16x8 at_frag(const bf16_t* tile, uint32_t row, uint32_t chunk) {
   return *reinterpret_cast<const bf16x8*>(tile + row * DH + ((chunk ^ (at_key(row) % (DH / 8))) << 3));
 }
-// A operand (row d, k = the rows kb..kb+3 and kb+8..kb+11 of the original tile) from a transposed tile.
-__device__ __forceinline__ bf16x8 at_frag_t(const bf16_t* tile_t, uint32_t ld, uint32_t d, uint32_t kb) {
-  const bf16_t* vr = tile_t + d * ld + kb;
-  const uint2 lo = *reinterpret_cast<const uint2*>(vr), hi = *reinterpret_cast<const uint2*>(vr + 8);
-  uint4 vv = make_uint4(lo.x, lo.y, hi.x, hi.y);
-  return *reinterpret_cast<bf16x8*>(&vv);
+// A operand of a product that contracts over the tile's rows: operand row d (32 of them from dbase32, one per lane
+// and lane + 32), k = the tile rows kb..kb+3 and kb+8..kb+11 (kb already holds the lane half's offset of 4).  The
+// tile stays [row][d]; the transposing LDS read of gfx950 (ds_read_b64_tr_b16) does the rest: within a group of
+// 16 lanes, source lane s supplies the address of four consecutive d at tile row kb + s/4, d = d0 + 4*(s%4).., and
+// lane i receives d0 + i at the four tile rows.
+template <int DH>
+__device__ __forceinline__ bf16x8 at_frag_tr(const bf16_t* tile, uint32_t dbase32, uint32_t kb) {
+  typedef short short4_lds __attribute__((ext_vector_type(4)));
+  typedef short short8_v __attribute__((ext_vector_type(8)));
+  typedef __attribute__((address_space(3))) short4_lds* lds_ptr;
+  const uint32_t lane = threadIdx.x & 63, s = lane & 15;
+  const uint32_t row = kb + (s >> 2), d = dbase32 + ((lane >> 4) & 1u) * 16 + 4 * (s & 3u);
+  const bf16_t* p0 = tile + row * DH + ((((d >> 3) ^ (at_key(row) % (DH / 8))) << 3) | (d & 7u));
+  const bf16_t* p1 = tile + (row + 8) * DH + ((((d >> 3) ^ (at_key(row + 8) % (DH / 8))) << 3) | (d & 7u));
+  const short4_lds lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p0);
+  const short4_lds hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p1);
+  const short8_v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
 }
 // eight accumulator values r0..r0+7 as a B operand
 __device__ __forceinline__ bf16x8 at_pack8(const float (&v)[16], int r0) {
@@ -87,19 +75,20 @@ __device__ __forceinline__ bf16x8 at_pack8(const float (&v)[16], int r0) {
 __device__ __forceinline__ float at_round(float x) { return bf2f(f2bf(x)); }
 
 // Forward.  One block = 128 query rows of one (batch, head), 4 wavefronts x 32 rows; keys/values streamed in tiles
-// of 128 through LDS (K as [kv][d], V transposed to [d][kv]); running maximum / sum / rescale per lane.
+// of 128 through LDS (K and V as [kv][d]); running maximum / sum / rescale per lane.
 template <int DH, int CAUSAL>
 __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse,
                                                               uint32_t S, uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, KCtl ctl) {
   constexpr int KS = DH / 16, DT = DH / 32;                   // k steps of q k^T, 32-wide d tiles
   __shared__ __align__(16) bf16_t sK[AT_KV * DH];
-  __shared__ __align__(16) bf16_t sVt[DH * AT_VLD];
+  __shared__ __align__(16) bf16_t sV[AT_KV * DH];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
-  const uint32_t b = blockIdx.y / H, head = blockIdx.y % H, da = H * DH;
+  const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
   const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
-  // with a causal mask the last query block has the most keys: start the long blocks first
-  const uint32_t q_blk = (CAUSAL ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
+  // with a causal mask the last query block has the most keys: the grid's slow index is the query block, reversed,
+  // so that the long blocks of every (batch, head) start first
+  const uint32_t q_blk = (CAUSAL ? gridDim.y - 1 - blockIdx.y : blockIdx.y) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
   const float c2 = scale * 1.44269504088896f;
 
   bf16x8 fq[KS];
@@ -123,17 +112,15 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
   for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
     __syncthreads();
     at_load_rows<DH, AT_KV>(sK, base + da, ld_qkv, kv0, S);
-    at_load_rows_t<DH, AT_KV>(sVt, base + 2 * da, ld_qkv, kv0, S);
+    at_load_rows<DH, AT_KV>(sV, base + 2 * da, ld_qkv, kv0, S);
     __syncthreads();
 
-    // S^T tiles: rows = kv (32 per tile), columns = the wavefront's 32 query rows.  Under the causal mask the tiles
-    // of the diagonal block that lie wholly above the wavefront's rows are skipped.
-    const int t_end = CAUSAL ? min(4, (int)((qw + 31 - kv0) / 32) + 1) : 4;
+    // S^T tiles: rows = kv (32 per tile), columns = the wavefront's 32 query rows (straight-line code: the four
+    // accumulator chains interleave; skipping the tiles above the diagonal would cost more than it saves)
     const bool need_mask = kv0 + AT_KV > S || (CAUSAL && kv0 + AT_KV - 1 > qw);
     floatx16 sacc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (t >= t_end) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[t][r] = 0.f;
 #pragma unroll
@@ -145,8 +132,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
     if (need_mask) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        if (t >= t_end) continue;
-#pragma unroll
+  #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const uint32_t kv = kv0 + t * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
           const bool ok = kv < S && (!CAUSAL || kv <= q);
@@ -156,7 +142,6 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (t >= t_end) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[t][r]);
     }
@@ -167,7 +152,6 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
     float rs = 0.f;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (t >= t_end) continue;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[t][r] = __builtin_amdgcn_exp2f(fmaf(sacc[t][r], c2, -m_use)); rs += sacc[t][r]; }
     }
@@ -186,7 +170,6 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
     // O^T += V^T P^T.  Element e of step s2 in tile t is key  t*32 + 16*s2 + 8*(e/4) + 4*h + e%4.
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (t >= t_end) continue;
       float pt[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) pt[r] = sacc[t][r] * pn;
@@ -195,7 +178,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
         const bf16x8 fp = at_pack8(pt, 8 * s2);
 #pragma unroll
         for (int d = 0; d < DT; ++d)
-          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sVt, AT_VLD, d * 32 + qi, t * 32 + 16 * s2 + 4 * h), fp, oacc[d], 0, 0, 0);
+          oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_tr<DH>(sV, d * 32, t * 32 + 16 * s2 + 4 * h), fp, oacc[d], 0, 0, 0);
       }
     }
     if (single) l_run = 1.0f;
@@ -212,13 +195,13 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
         *reinterpret_cast<uint2*>(op + dd) = make_uint2(pack_bf2(oacc[d][4 * g] * inv, oacc[d][4 * g + 1] * inv),
                                                         pack_bf2(oacc[d][4 * g + 2] * inv, oacc[d][4 * g + 3] * inv));
       }
-    if (lse != nullptr && h == 0) lse[(size_t)blockIdx.y * S + q] = (m_run + __log2f(l_true)) * 0.693147180559945f;
+    if (lse != nullptr && h == 0) lse[(size_t)bh * S + q] = (m_run + __log2f(l_true)) * 0.693147180559945f;
   }
   kernel_end(ctl, true);
 }
 
 // Backward, dq.  One block = 128 query rows of one (batch, head), a query row per lane pair as in the forward;
-// keys/values streamed in tiles of 128: K and V as [kv][d], K also transposed.  Also writes delta = rowsum(do .* o)
+// keys/values streamed in tiles of 128, K and V as [kv][d].  Also writes delta = rowsum(do .* o)
 // for the dk/dv kernel.
 template <int DH, int CAUSAL>
 __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
@@ -228,12 +211,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
   constexpr int KS = DH / 16, DT = DH / 32;
   __shared__ __align__(16) bf16_t sK[AT_KV * DH];
   __shared__ __align__(16) bf16_t sV[AT_KV * DH];
-  __shared__ __align__(16) bf16_t sKt[DH * AT_VLD];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
-  const uint32_t b = blockIdx.y / H, head = blockIdx.y % H, da = H * DH;
+  const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
   const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
-  const uint32_t q_blk = (CAUSAL ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
+  const uint32_t q_blk = (CAUSAL ? gridDim.y - 1 - blockIdx.y : blockIdx.y) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
   const bool q_ok = q < S;
   const float c2 = scale * 1.44269504088896f;
 
@@ -257,8 +239,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
     }
   }
   dsum += __shfl_xor(dsum, 32, 64);
-  const float lq2 = q_ok ? lse[(size_t)blockIdx.y * S + q] * 1.44269504088896f : INFINITY;     // base-2 units
-  if (q_ok && h == 0) delta[(size_t)blockIdx.y * S + q] = dsum;
+  const float lq2 = q_ok ? lse[(size_t)bh * S + q] * 1.44269504088896f : INFINITY;     // base-2 units
+  if (q_ok && h == 0) delta[(size_t)bh * S + q] = dsum;
 
   floatx16 dqacc[DT];
 #pragma unroll
@@ -271,13 +253,10 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
     __syncthreads();
     at_load_rows<DH, AT_KV>(sK, base + da, ld_qkv, kv0, S);
     at_load_rows<DH, AT_KV>(sV, base + 2 * da, ld_qkv, kv0, S);
-    at_load_rows_t<DH, AT_KV>(sKt, base + da, ld_qkv, kv0, S);
     __syncthreads();
-    const int t_end = CAUSAL ? min(4, (int)((qw + 31 - kv0) / 32) + 1) : 4;       // tiles wholly above the diagonal are skipped
     const bool need_mask = kv0 + AT_KV > S || (CAUSAL && kv0 + AT_KV - 1 > qw);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      if (t >= t_end) continue;
       floatx16 sacc, pacc;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; pacc[r] = 0.f; }
@@ -301,7 +280,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
         const bf16x8 fds = at_pack8(ds, 8 * s2);
 #pragma unroll
         for (int d = 0; d < DT; ++d)
-          dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sKt, AT_VLD, d * 32 + qi, t * 32 + 16 * s2 + 4 * h), fds, dqacc[d], 0, 0, 0);
+          dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_tr<DH>(sK, d * 32, t * 32 + 16 * s2 + 4 * h), fds, dqacc[d], 0, 0, 0);
       }
     }
   }
@@ -318,7 +297,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
 }
 
 // Backward, dk and dv.  One block = 128 key rows of one (batch, head), a key row per lane pair (its K and V rows stay
-// in registers); queries streamed in steps of 64 rows: q and do as [q][d] and transposed, lse and delta beside them.
+// in registers); queries streamed in steps of 64 rows: q and do as [q][d], lse and delta beside them.
 template <int DH, int CAUSAL>
 __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
@@ -327,18 +306,16 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
   constexpr int KS = DH / 16, DT = DH / 32;
   __shared__ __align__(16) bf16_t sQ[AT_QB * DH];
   __shared__ __align__(16) bf16_t sDo[AT_QB * DH];
-  __shared__ __align__(16) bf16_t sQt[DH * AT_QLD];
-  __shared__ __align__(16) bf16_t sDot[DH * AT_QLD];
   __shared__ __align__(16) float sL[AT_QB];
   __shared__ __align__(16) float sD[AT_QB];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ki = lane & 31, h = lane >> 5;
-  const uint32_t b = blockIdx.y / H, head = blockIdx.y % H, da = H * DH;
+  const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
   const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
   const bf16_t* dobase = d_o + (size_t)b * S * ld_o + head * DH;
-  const float* lrow = lse + (size_t)blockIdx.y * S;
-  const float* drow = delta + (size_t)blockIdx.y * S;
-  const uint32_t kv_blk = blockIdx.x * AT_KV, kw = kv_blk + wave * 32, kv = kw + ki;   // the first key block meets the most queries
+  const float* lrow = lse + (size_t)bh * S;
+  const float* drow = delta + (size_t)bh * S;
+  const uint32_t kv_blk = blockIdx.y * AT_KV, kw = kv_blk + wave * 32, kv = kw + ki;   // the first key block meets the most queries
   const bool kv_ok = kv < S;
   const float c2 = scale * 1.44269504088896f;
 
@@ -364,8 +341,6 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
     __syncthreads();
     at_load_rows<DH, AT_QB>(sQ, base, ld_qkv, q0, S);
     at_load_rows<DH, AT_QB>(sDo, dobase, ld_o, q0, S);
-    at_load_rows_t<DH, AT_QB>(sQt, base, ld_qkv, q0, S);
-    at_load_rows_t<DH, AT_QB>(sDot, dobase, ld_o, q0, S);
     if (threadIdx.x < AT_QB) {
       const uint32_t qq = q0 + threadIdx.x;
       sL[threadIdx.x] = qq < S ? lrow[qq] * 1.44269504088896f : INFINITY;         // base-2 units; a row past the end gets P = 2^(-inf) = 0
@@ -407,8 +382,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
         const uint32_t qb = u * 32 + 16 * s2 + 4 * h;
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
-          dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sDot, AT_QLD, d * 32 + ki, qb), fp, dvacc[d], 0, 0, 0);     // dV^T
-          dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_t(sQt, AT_QLD, d * 32 + ki, qb), fds, dkacc[d], 0, 0, 0);     // dK^T
+          dvacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_tr<DH>(sDo, d * 32, qb), fp, dvacc[d], 0, 0, 0);     // dV^T
+          dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_tr<DH>(sQ, d * 32, qb), fds, dkacc[d], 0, 0, 0);     // dK^T
         }
       }
     }
@@ -431,7 +406,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
 static sif_status attn_check(const char* who, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head) {
   if (!batch || !seq || !heads) return fail(SIF_E_INVAL, "%s: empty extent", who);
   if (d_head != 64 && d_head != 128) return fail(SIF_E_INVAL, "%s: d_head must be 64 or 128", who);
-  if ((uint64_t)batch * heads > 65535) return fail(SIF_E_INVAL, "%s: batch*heads too large", who);
+  if ((seq + AT_Q - 1) / AT_Q > 65535) return fail(SIF_E_INVAL, "%s: sequence too long", who);
   return SIF_OK;
 }
 static bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -443,7 +418,7 @@ sif_status launch_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch,
   if ((ld_qkv & 7) || (ld_o & 7) || ld_qkv < 3 * heads * d_head || ld_o < heads * d_head) return fail(SIF_E_INVAL, "attn_fwd: bad leading dimensions");
   if (!al16(qkv) || !al16(o)) return fail(SIF_E_INVAL, "attn_fwd: pointers must be 16-byte aligned");
   const float scale = 1.0f / sqrtf((float)d_head);
-  dim3 grid((seq + AT_Q - 1) / AT_Q, batch * heads);
+  dim3 grid(batch * heads, (seq + AT_Q - 1) / AT_Q);
 #define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_fwd_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, heads, ld_qkv, ld_o, scale, c)
   if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
   else { if (causal) AT_LAUNCH(128, 1); else AT_LAUNCH(128, 0); }
@@ -467,7 +442,7 @@ sif_status launch_attn_bwd_dq(const void* qkv, const void* o, const void* d_o, c
                               hipStream_t s, const KCtl& c) {
   if (sif_status st = attn_bwd_check("attn_bwd_dq", qkv, o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv)) return st;
   const float scale = 1.0f / sqrtf((float)d_head);
-  dim3 grid((seq + AT_Q - 1) / AT_Q, batch * heads);
+  dim3 grid(batch * heads, (seq + AT_Q - 1) / AT_Q);
 #define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_bwd_dq_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (const bf16_t*)o, \
                                             (const bf16_t*)d_o, lse, delta, (bf16_t*)dqkv, seq, heads, ld_qkv, ld_o, ld_dqkv, scale, c)
   if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
@@ -481,7 +456,7 @@ sif_status launch_attn_bwd_dkv(const void* qkv, const void* d_o, const float* ls
                                const KCtl& c) {
   if (sif_status st = attn_bwd_check("attn_bwd_dkv", qkv, d_o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv)) return st;
   const float scale = 1.0f / sqrtf((float)d_head);
-  dim3 grid((seq + AT_KV - 1) / AT_KV, batch * heads);
+  dim3 grid(batch * heads, (seq + AT_KV - 1) / AT_KV);
 #define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_bwd_dkv_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (const bf16_t*)d_o, lse, \
                                             delta, (bf16_t*)dqkv, seq, heads, ld_qkv, ld_o, ld_dqkv, scale, c)
   if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
