@@ -52,6 +52,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--coalesce", type=int, default=2, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=1000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--allow-serial-streams", action="store_true", help="for runs under a counter-collecting profiler, which serialises all kernels")
@@ -86,7 +87,7 @@ def main():
     cfg.allow_serial_streams = 1 if args.allow_serial_streams else 0
     with Session(cfg) as s:
         s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
-        m = s.register_inference(eshape, enc_master)
+        m = s.register_inference(eshape, enc_master, coalesce=args.coalesce)
         ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
         eids = to(Y.token_ids(5, enc["batch"], enc["seq"], enc["vocab"]), torch.int32)
         outs = [torch.zeros((enc["batch"], enc["seq"], enc["d_model"]), device=dev, dtype=torch.bfloat16) for _ in range(4)]

@@ -340,6 +340,13 @@ typedef struct sif_infer_desc {
   void* workspace_dev;           /* >= sif_infer_workspace_bytes(): working copy + activations          */
   uint64_t workspace_bytes;
   uint64_t peak_bytes;           /* declared peak memory of this instance (Principle-I)                 */
+  uint32_t coalesce;             /* offline encoder models: up to this many queued requests of equal batch and seq
+                                    are released as ONE kernel sequence over their concatenated rows (0 or 1 = each
+                                    request by itself, at most 4).  Every kernel of the forward pass treats rows (or
+                                    whole sequences) independently, so each request's output is bit-identical to a
+                                    run by itself; the workspace is sized for coalesce * shape.batch rows.  Requests
+                                    are never held back to wait for partners.                              */
+  uint32_t reserved;
 } sif_infer_desc;
 
 uint64_t sif_infer_workspace_bytes(const sif_infer_desc* d);

@@ -98,7 +98,7 @@ class sif_train_desc(C.Structure):
 
 class sif_infer_desc(C.Structure):
     _fields_ = [("struct_size", u32), ("online", u32), ("shape", sif_model_shape), ("master_dev", vp),
-                ("workspace_dev", vp), ("workspace_bytes", u64), ("peak_bytes", u64)]
+                ("workspace_dev", vp), ("workspace_bytes", u64), ("peak_bytes", u64), ("coalesce", u32), ("reserved", u32)]
 
 
 class sif_stats(C.Structure):

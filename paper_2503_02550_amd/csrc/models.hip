@@ -592,8 +592,8 @@ static uint64_t layout_infer(InferModel& im, Arena& ar) {
     im.calib_out = ar.take((uint64_t)s.batch * s.d_out * 4);
     return ar.off;
   }
-  const Dims q = dims_of(s, s.batch, s.seq);
-  const uint64_t ssz = (uint64_t)q.B * q.H * q.S * q.Sp, M = q.M;
+  const Dims q = dims_of(s, s.batch * infer_coalesce(im.desc), s.seq);
+  const uint64_t ssz = fused_attention(q.dh) ? 8 : (uint64_t)q.B * q.H * q.S * q.Sp, M = q.M;      // scores: unfused attention only
   im.work = ar.take(im.n_params * 2);
   im.bufs["x"] = ar.take(M * q.d * 2); im.bufs["t"] = ar.take(M * q.d * 2); im.bufs["x1"] = ar.take(M * q.d * 2);
   im.bufs["qkv"] = ar.take(M * 3 * q.da * 2); im.bufs["scores"] = ar.take(ssz * 4); im.bufs["prob"] = ar.take(ssz * 2);
@@ -601,6 +601,11 @@ static uint64_t layout_infer(InferModel& im, Arena& ar) {
   im.calib_in = ar.take(M * 4);
   im.calib_out = ar.take(M * q.d * 2);
   return ar.off;
+}
+
+uint32_t infer_coalesce(const sif_infer_desc& d) {
+  if (d.online || d.shape.kind != SIF_MODEL_ENCODER || d.coalesce < 2) return 1;
+  return d.coalesce;
 }
 
 uint64_t infer_workspace_bytes(const sif_infer_desc& d) {
@@ -615,6 +620,7 @@ sif_status build_infer_model(InferModel& im, hipStream_t stream) {
   sif_status st = check_shape(im.desc.shape, false);
   if (st != SIF_OK) return st;
   if (im.desc.shape.kind == SIF_MODEL_DECODER) return fail(SIF_E_INVAL, "inference model must be MLP or ENCODER");
+  if (im.desc.coalesce > 4) return fail(SIF_E_INVAL, "inference model: coalesce must be at most 4");
   im.n_params = model_n_params(im.desc.shape);
   Arena ar;
   ar.base = (unsigned char*)im.desc.workspace_dev;
@@ -628,10 +634,14 @@ sif_status build_infer_model(InferModel& im, hipStream_t stream) {
   return SIF_OK;
 }
 
-sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_dev, uint32_t batch, uint32_t seq,
+sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_io, uint32_t batch, uint32_t seq,
                             uint32_t kernel_us_max, Plan& p) {
   const sif_model_shape& s = im.desc.shape;
-  if (!in_dev || !out_dev) return fail(SIF_E_INVAL, "submit: null buffer");
+  if (!io || n_io == 0 || n_io > infer_coalesce(im.desc)) return fail(SIF_E_INVAL, "submit: bad request count");
+  for (uint32_t i = 0; i < n_io; ++i) if (!io[i].in_dev || !io[i].out_dev) return fail(SIF_E_INVAL, "submit: null buffer");
+  const void* in_dev = io[0].in_dev;
+  void* out_dev = io[0].out_dev;
+  (void)out_dev;
   if (batch == 0 || batch > s.batch) return fail(SIF_E_INVAL, "submit: batch must be in 1..%u", s.batch);
   const ParamMap pm = param_map(s);
   if (s.kind == SIF_MODEL_MLP) {
@@ -645,22 +655,29 @@ sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_
     emit(p, "fc2", 5, [=](hipStream_t st, const KCtl& c) { return launch_gemm_f32(h, dh, 1, w2, 1, dh, y, dout, batch, dout, dh, SIF_EPI_BIAS, b2, nullptr, st, c); });
     return SIF_OK;
   }
+  if (n_io != 1 && s.kind != SIF_MODEL_ENCODER) return fail(SIF_E_INVAL, "submit: only encoder requests can be coalesced");
   if (seq == 0 || seq > s.seq) return fail(SIF_E_INVAL, "submit: seq must be in 1..%u", s.seq);
-  const Dims q = dims_of(s, batch, seq);
-  const uint32_t M = q.M, d = q.d;
+  // n_io requests of batch x seq rows each run as one sequence over their concatenated rows: every kernel below treats
+  // rows (LayerNorm, GEMM) or whole sequences (attention) independently, so a request's result does not depend on
+  // what it is concatenated with.  Only the first and the last kernel touch the requests' own buffers.
+  const Dims q = dims_of(s, batch * n_io, seq);
+  const uint32_t M = q.M, d = q.d, M1 = batch * seq;
   const bf16_t* W = (const bf16_t*)im.work;
   bf16_t *x = (bf16_t*)im.bufs.at("x"), *t = (bf16_t*)im.bufs.at("t"), *x1 = (bf16_t*)im.bufs.at("x1"), *qkv = (bf16_t*)im.bufs.at("qkv");
   bf16_t *prob = (bf16_t*)im.bufs.at("prob"), *o = (bf16_t*)im.bufs.at("o"), *a = (bf16_t*)im.bufs.at("a");
   float* scores = (float*)im.bufs.at("scores");
   const bf16_t *wte = W + pm.at("wte"), *wpe = W + pm.at("wpe"), *eg = W + pm.at("emb_ln_g"), *eb = W + pm.at("emb_ln_b");
-  const int32_t* ids = (const int32_t*)in_dev;
-  emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd(ids, wte, wpe, t, M, seq, d, st, c); });
+  for (uint32_t r = 0; r < n_io; ++r) {
+    const int32_t* ids = (const int32_t*)io[r].in_dev;
+    bf16_t* tr = t + (size_t)r * M1 * d;
+    emit(p, "embed", bytes_cost_us(6.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd(ids, wte, wpe, tr, M1, seq, d, st, c); });
+  }
   emit(p, "emb_ln", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, eg, eb, x, nullptr, nullptr, M, d, st, c); });
   for (uint32_t l = 0; l < s.n_layers; ++l) {
     const bf16_t *w_qkv = W + pm.at(L(l, "w_qkv")), *b_qkv = W + pm.at(L(l, "b_qkv")), *w_o = W + pm.at(L(l, "w_o")), *b_o = W + pm.at(L(l, "b_o"));
     const bf16_t *g1 = W + pm.at(L(l, "ln1_g")), *be1 = W + pm.at(L(l, "ln1_b")), *w_fc = W + pm.at(L(l, "w_fc")), *b_fc = W + pm.at(L(l, "b_fc"));
     const bf16_t *w_pr = W + pm.at(L(l, "w_proj")), *b_pr = W + pm.at(L(l, "b_proj")), *g2 = W + pm.at(L(l, "ln2_g")), *be2 = W + pm.at(L(l, "ln2_b"));
-    bf16_t* y = (l + 1 == s.n_layers) ? (bf16_t*)out_dev : x;
+    const bool last = l + 1 == s.n_layers;
     emit_gemm_rows(p, "qkv", G(x, w_qkv, qkv, M, 3 * q.da, d, d, d, 3 * q.da).epi(SIF_EPI_BIAS, b_qkv), kernel_us_max);
     if (q.dh == 64 || q.dh == 128) {
       // one fused kernel: scores stay on chip, two launches fewer per layer
@@ -674,7 +691,15 @@ sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_
     emit(p, "ln1", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g1, be1, x1, nullptr, nullptr, M, d, st, c); });
     emit_gemm_rows(p, "mlp_up", G(x1, w_fc, a, M, q.f, d, d, d, q.f).epi(SIF_EPI_GELU, b_fc), kernel_us_max);
     emit_gemm_rows(p, "mlp_down", G(a, w_pr, t, M, d, q.f, q.f, q.f, d).epi(SIF_EPI_BIAS | SIF_EPI_RESIDUAL, b_pr, x1), kernel_us_max);
-    emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g2, be2, y, nullptr, nullptr, M, d, st, c); });
+    if (!last) {
+      emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g2, be2, x, nullptr, nullptr, M, d, st, c); });
+    } else {
+      for (uint32_t r = 0; r < n_io; ++r) {
+        const bf16_t* tr = t + (size_t)r * M1 * d;
+        void* y = io[r].out_dev;
+        emit(p, "ln2", bytes_cost_us(4.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(tr, g2, be2, y, nullptr, nullptr, M1, d, st, c); });
+      }
+    }
   }
   return SIF_OK;
 }

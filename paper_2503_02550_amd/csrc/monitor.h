@@ -19,7 +19,7 @@ enum : uint32_t { kKindTrain = 1, kKindInfer = 2, kKindBubble = 3, kKindStep = 4
 
 struct alignas(128) StreamRec {     // one per stream, in HBM
   uint32_t state;                   // training stream: kStateBusy / kStateIdle (inside a bubble)
-  uint32_t seq;                     // number of the current / last bubble
+  uint32_t seq;                     // number of the current / last bubble (state and seq: one aligned 64-bit word)
   uint32_t site;                    // its site in the step
   uint32_t launched;                // kernels started on this stream
   uint32_t completed;               // kernels finished
@@ -109,15 +109,19 @@ __device__ __forceinline__ bool first_thread() { return threadIdx.x == 0 && thre
 // skipped, the training stream is inside a bubble, the predicted rest of the bubble holds this kernel, and
 // the bubble is still the same one after the start time was stamped.
 __device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
-  // Relaxed device-scope loads (an acquire would sweep the L2 on every inference kernel start); each value feeds a
-  // branch before the next step, which keeps the order state -> clock -> state.
-  if (ld_relaxed(&c.rec->skip_from) != kNone) return false;
-  const uint32_t st = ld_relaxed(&c.gate->state);
-  const uint32_t sq = ld_relaxed(&c.gate->seq);
-  if (st != kStateIdle) return false;
+  // Relaxed device-scope loads (an acquire would sweep the L2 on every inference kernel start).  state and seq are
+  // read as one 64-bit word; the three loads of the first round are independent and travel together, so the
+  // decision costs two memory round trips: {state|seq, predicted end, poison} -> clock -> {state|seq} again.  A
+  // predicted end that belongs to an older bubble than the state just read lies in the past and only makes the
+  // decision conservative.
+  const uint64_t* ss = reinterpret_cast<const uint64_t*>(&c.gate->state);
+  const uint64_t s0 = ld_relaxed(ss);
+  const uint64_t t_end = ld_relaxed(&c.gate->t_expected_end);
+  const uint32_t poison = ld_relaxed(&c.rec->skip_from);
+  if (poison != kNone || (uint32_t)s0 != kStateIdle) return false;
   const uint64_t t = now_ticks();
-  if (t + c.cost_ticks > ld_relaxed(&c.gate->t_expected_end)) return false;
-  if (ld_relaxed(&c.gate->state) != kStateIdle || ld_relaxed(&c.gate->seq) != sq) return false;
+  if (t + c.cost_ticks > t_end) return false;
+  if (ld_relaxed(ss) != s0) return false;
   *t0 = t;
   return true;
 }

@@ -69,8 +69,10 @@ struct InferModel {
   uint64_t n_params = 0;
   void* work = nullptr;                             // working copy of the weights
   std::unordered_map<std::string, void*> bufs;
-  // cost per op of the plan for the registered (batch, seq), measured by calibration
+  // cost per op of the plan for the registered (batch, seq), measured by calibration: [n - 1] for n coalesced
+  // requests (calib_cost_us = the single-request plan)
   std::vector<double> calib_cost_us;
+  std::vector<std::vector<double>> calib_cost_us_n;
   double calib_total_us = 0.0;
   uint32_t calib_batch = 0, calib_seq = 0;
   void* calib_in = nullptr;
@@ -83,6 +85,9 @@ struct Job {
   bool online = false;
   uint32_t batch = 0, seq = 0;
   uint64_t t_arrival_ns = 0, t_done_ns = 0;
+  const void* in_dev = nullptr;
+  void* out_dev = nullptr;
+  std::vector<Job*> parts;       // a coalesced job: the submitted requests it runs (it has no ticket of its own)
   Plan plan;
   uint32_t next_op = 0;          // next op to launch
   uint32_t done_ops = 0;         // ops known to have run
@@ -96,8 +101,11 @@ uint64_t model_n_params(const sif_model_shape& s);
 sif_status build_train_model(TrainModel& tm, hipStream_t stream);
 uint64_t infer_workspace_bytes(const sif_infer_desc& d);
 sif_status build_infer_model(InferModel& im, hipStream_t stream);
-sif_status build_infer_plan(const InferModel& im, const void* in_dev, void* out_dev, uint32_t batch, uint32_t seq,
+struct InferIO { const void* in_dev; void* out_dev; };
+// One kernel sequence for `n_io` requests of `batch` x `seq` each (n_io > 1: encoder models only)
+sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_io, uint32_t batch, uint32_t seq,
                             uint32_t kernel_us_max, Plan& out);
+uint32_t infer_coalesce(const sif_infer_desc& d);
 
 // markers.hip
 sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,

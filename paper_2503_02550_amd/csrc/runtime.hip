@@ -65,6 +65,7 @@ struct sif_ctx {
   // barrier thread state
   std::deque<InFlight> inflight;
   std::deque<Job*> run_online, run_offline;
+  std::vector<std::unique_ptr<Job>> groups;      // coalesced jobs in flight (guarded by mu)
   uint64_t balance = 0, outstanding_us = 0, last_period = 0;
   bool awaiting_reset = false;
   bool hold = false;                   // after a skipped launch: release nothing until a new bubble begins
@@ -172,7 +173,16 @@ static void monitor_main(sif_ctx* c) {
 }
 
 // ------------------------------------------------------------------------------------------------ barrier
+static void apply_calibration(const InferModel& im, Job& j);
+
 static void finish_job(sif_ctx* c, Job* j, int32_t result) {
+  if (!j->parts.empty()) {          // a coalesced job: its requests finish together, then it is dropped
+    const std::vector<Job*> parts = j->parts;
+    for (Job* p : parts) finish_job(c, p, result);
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->groups.erase(std::remove_if(c->groups.begin(), c->groups.end(), [&](const std::unique_ptr<Job>& g) { return g.get() == j; }), c->groups.end());
+    return;
+  }
   std::lock_guard<std::mutex> lk(c->mu);
   j->t_done_ns = host_now_ns();
   j->result = result;
@@ -260,7 +270,36 @@ static void barrier_main(sif_ctx* c) {
             c->run_online.push_back(j);
           }
         }
-        while (!c->offline_q.empty() && c->run_offline.size() < 4) { c->run_offline.push_back(c->offline_q.front()); c->offline_q.pop_front(); }
+        while (!c->offline_q.empty() && c->run_offline.size() < 4) {
+          Job* j = c->offline_q.front();
+          c->offline_q.pop_front();
+          // requests of equal shape that are queued behind it join it (never waited for)
+          const InferModel& im = *c->models[j->model];
+          std::vector<Job*> parts{j};
+          while (parts.size() < infer_coalesce(im.desc) && !c->offline_q.empty()) {
+            Job* n = c->offline_q.front();
+            if (n->model != j->model || n->batch != j->batch || n->seq != j->seq) break;
+            c->offline_q.pop_front();
+            parts.push_back(n);
+          }
+          if (parts.size() > 1) {
+            std::unique_ptr<Job> g(new Job());
+            g->ticket = j->ticket; g->model = j->model; g->batch = j->batch * (uint32_t)parts.size(); g->seq = j->seq;
+            g->t_arrival_ns = j->t_arrival_ns;
+            InferIO io[4];
+            for (size_t r = 0; r < parts.size(); ++r) io[r] = InferIO{parts[r]->in_dev, parts[r]->out_dev};
+            if (build_infer_plan(im, io, (uint32_t)parts.size(), j->batch, j->seq, c->cfg.kernel_us_max, g->plan) == SIF_OK) {
+              g->parts = parts;
+              apply_calibration(im, *g);
+              for (Job* p : parts) p->plan.clear();
+              c->run_offline.push_back(g.get());
+              c->groups.push_back(std::move(g));
+              continue;
+            }
+            for (size_t r = parts.size(); r-- > 1;) c->offline_q.push_front(parts[r]);      // could not be merged: one by one
+          }
+          c->run_offline.push_back(j);
+        }
       }
       // 5. release kernels
       const uint64_t max_ahead = gated ? c->cfg.alg1.ul : ~0ull;
@@ -534,10 +573,13 @@ sif_status sif_register_inference_model(sif_ctx* c, const sif_infer_desc* d, sif
 }
 
 static void apply_calibration(const InferModel& im, Job& j) {
-  if (im.calib_cost_us.size() != j.plan.size() || im.calib_batch == 0) return;
+  const size_t n = j.parts.empty() ? 1 : j.parts.size();
+  if (n > im.calib_cost_us_n.size() || im.calib_batch == 0) return;
+  const std::vector<double>& cal = im.calib_cost_us_n[n - 1];
+  if (cal.size() != j.plan.size()) return;
   const double scale = ((double)j.batch * (j.seq ? j.seq : 1)) / ((double)im.calib_batch * (im.calib_seq ? im.calib_seq : 1));
   for (size_t i = 0; i < j.plan.size(); ++i) {
-    const double base = im.calib_cost_us[i];
+    const double base = cal[i];
     j.plan[i].cost_us = std::max(1.0, 2.0 + (base - 2.0) * scale);
   }
 }
@@ -551,7 +593,9 @@ static sif_status submit(sif_ctx* c, sif_handle model, const void* in_dev, void*
   std::unique_ptr<Job> j(new Job());
   j->model = model; j->online = online; j->batch = batch; j->seq = im.desc.shape.kind == SIF_MODEL_MLP ? 1 : seq;
   j->t_arrival_ns = t_arrival_ns ? t_arrival_ns : host_now_ns();
-  sif_status st = build_infer_plan(im, in_dev, out_dev, batch, seq, c->cfg.kernel_us_max, j->plan);
+  j->in_dev = in_dev; j->out_dev = out_dev;
+  const InferIO io{in_dev, out_dev};
+  sif_status st = build_infer_plan(im, &io, 1, batch, seq, c->cfg.kernel_us_max, j->plan);
   if (st != SIF_OK) return st;
   apply_calibration(im, *j);
   std::lock_guard<std::mutex> lk(c->mu);
@@ -605,30 +649,42 @@ sif_status sif_calibrate(sif_ctx* c, uint32_t iters, const void* train_inputs_de
     InferModel& im = *mp;
     const sif_model_shape& s = im.desc.shape;
     const uint32_t batch = im.desc.online ? 1 : s.batch;
-    Plan plan;
-    sif_status st = build_infer_plan(im, im.calib_in, im.calib_out, batch, s.seq, c->cfg.kernel_us_max, plan);
-    if (st != SIF_OK) return st;
-    std::vector<double> sum(plan.size(), 0.0);
-    std::vector<uint32_t> kseqs(plan.size());
-    std::vector<Slot> slots(plan.size());
-    for (uint32_t it = 0; it <= iters; ++it) {
-      for (size_t i = 0; i < plan.size(); ++i) {
-        KCtl k = make_ctl(c, c->I, kKindInfer, (uint32_t)i, nullptr, 0);
-        kseqs[i] = k.kseq;
-        st = plan[i].fn(c->I.stream, k);
-        if (st != SIF_OK) return st;
+    const uint32_t n_max = infer_coalesce(im.desc);
+    im.calib_cost_us_n.assign(n_max, std::vector<double>());
+    for (uint32_t n = 1; n <= n_max; ++n) {        // the plan of one request and of each number of coalesced requests
+      Plan plan;
+      InferIO io[4];
+      const uint64_t rows1 = (uint64_t)batch * s.seq;
+      for (uint32_t r = 0; r < n; ++r) {
+        io[r].in_dev = (const unsigned char*)im.calib_in + (s.kind == SIF_MODEL_MLP ? 0 : r * rows1 * 4);
+        io[r].out_dev = (unsigned char*)im.calib_out + (s.kind == SIF_MODEL_MLP ? 0 : r * rows1 * s.d_model * 2);
       }
-      HIPCHK(hipStreamSynchronize(c->I.stream), "calibrate: synchronize");
-      if (it == 0) continue;       // warm-up
-      for (size_t i = 0; i < plan.size(); ++i) {
-        Slot sl;
-        HIPCHK(hipMemcpy(&sl, c->I.ring + (kseqs[i] % kRingSlots), sizeof(Slot), hipMemcpyDeviceToHost), "calibrate: read slot");
-        sum[i] += (double)c->ticks_to_ns(sl.t1 - sl.t0) / 1000.0;
+      sif_status st = build_infer_plan(im, io, n, batch, s.seq, c->cfg.kernel_us_max, plan);
+      if (st != SIF_OK) return st;
+      std::vector<double> sum(plan.size(), 0.0);
+      std::vector<uint32_t> kseqs(plan.size());
+      for (uint32_t it = 0; it <= iters; ++it) {
+        for (size_t i = 0; i < plan.size(); ++i) {
+          KCtl k = make_ctl(c, c->I, kKindInfer, (uint32_t)i, nullptr, 0);
+          kseqs[i] = k.kseq;
+          st = plan[i].fn(c->I.stream, k);
+          if (st != SIF_OK) return st;
+        }
+        HIPCHK(hipStreamSynchronize(c->I.stream), "calibrate: synchronize");
+        if (it == 0) continue;       // warm-up
+        for (size_t i = 0; i < plan.size(); ++i) {
+          Slot sl;
+          HIPCHK(hipMemcpy(&sl, c->I.ring + (kseqs[i] % kRingSlots), sizeof(Slot), hipMemcpyDeviceToHost), "calibrate: read slot");
+          sum[i] += (double)c->ticks_to_ns(sl.t1 - sl.t0) / 1000.0;
+        }
       }
+      std::vector<double>& cal = im.calib_cost_us_n[n - 1];
+      cal.resize(plan.size());
+      for (size_t i = 0; i < plan.size(); ++i) cal[i] = std::max(1.0, sum[i] / iters + 2.0);
     }
-    im.calib_cost_us.resize(plan.size());
+    im.calib_cost_us = im.calib_cost_us_n[0];
     im.calib_total_us = 0;
-    for (size_t i = 0; i < plan.size(); ++i) { im.calib_cost_us[i] = std::max(1.0, sum[i] / iters + 2.0); im.calib_total_us += im.calib_cost_us[i]; }
+    for (double v : im.calib_cost_us) im.calib_total_us += v;
     im.calib_batch = batch; im.calib_seq = s.kind == SIF_MODEL_MLP ? 1 : s.seq;
     if (im.desc.online && c->train && c->train->max_bubble_ns && !sif_principle_2((uint64_t)(im.calib_total_us * 1000.0), c->train->max_bubble_ns)) {
       fail(SIF_W_SLO_RISK, "calibrate: an online request (%.0f us) is longer than the longest bubble", im.calib_total_us);

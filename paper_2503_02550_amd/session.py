@@ -76,10 +76,10 @@ class Session:
         raise RuntimeError("tensor outside the known buffers")
 
     # ---- inference -------------------------------------------------------------------------------------
-    def register_inference(self, shape, master_flat, online=False, peak_bytes=None):
+    def register_inference(self, shape, master_flat, online=False, peak_bytes=None, coalesce=0):
         d = B.sif_infer_desc()
         d.struct_size = C.sizeof(d)
-        d.online, d.shape = (1 if online else 0), shape
+        d.online, d.shape, d.coalesce = (1 if online else 0), shape, coalesce
         need = B.sif_infer_workspace_bytes(d)
         master = torch.from_numpy(np.ascontiguousarray(master_flat, dtype=np.float32)).to(self.dev)
         ws = _u8(need, self.dev)

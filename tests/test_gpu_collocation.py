@@ -108,13 +108,13 @@ DEC = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=1000
 ENC = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=500, max_pos=64, batch=8, seq=64)
 
 
-def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000):
+def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000, coalesce=0):
     shape, ishape = decoder_shape(DEC), encoder_shape(ENC)
     cfg = S.sif_default_config()
-    cfg.collocate = 1 if collocate else 0
+    cfg.collocate = 1 if (collocate and not coalesce) else 0
     with Session(cfg) as s:
         s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=bubble_ns)
-        m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)))
+        m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)), coalesce=coalesce)
         S.sif_calibrate(s.ctx, 2)
         n_cal = last_launch(s)
         ids = [i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])) for i in range(n_batches)]
@@ -123,6 +123,8 @@ def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000):
         losses = torch.zeros(steps, device=DEV)
         torch.cuda.synchronize()
         tickets = [s.submit_offline(m, ids[i], outs[i], ENC["batch"], ENC["seq"]) for i in range(n_batches)]
+        if collocate and coalesce:
+            S.sif_set_collocate(s.ctx, 1)      # all requests are queued before the barrier admits the first
         for st in range(steps):
             s.step(x, t, losses[st:st + 1])
         s.sync()
@@ -152,6 +154,28 @@ def test_transformer_collocation_invariants():
             s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
             assert torch.equal(out, outs[i])                                       # same bits as the solo run
             assert_bf16_close(up(outs[i]), OE.encoder_forward(w, ids, ENC, "bf16"), "collocated encoder", elem_slack=1.5e-2)
+
+
+def test_coalesced_offline_requests_give_the_same_bits_as_single_ones():
+    """Queued requests of equal shape run as one kernel sequence over their concatenated rows; every request's
+    output must be what a run by itself gives, and the scheduling invariants hold as before."""
+    w_solo, l_solo, _, _, _ = run_transformer(False, 0)
+    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_transformer(True, 6, coalesce=3)
+    assert np.array_equal(w_solo, w_col) and np.array_equal(l_solo, l_col)
+    assert st.offline_batches == 6 and st.offline_samples == 6 * ENC["batch"]
+    assert_starts_inside_bubbles(bubbles, ran)
+    assert len(ran) + skipped == st.kernels_launched
+    # two groups of three: 3 embeddings + their LayerNorm + 2 layers x 7 kernels, the last LayerNorm once per request
+    assert len(ran) == 2 * (3 + 1 + 2 * 7 - 1 + 3)
+    ishape = encoder_shape(ENC)
+    master = Y.encoder_params(2, ENC, perturb=True)
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, master))
+        for i in range(6):
+            I, out = i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])), torch.zeros_like(outs[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
+            assert torch.equal(out, outs[i]), i
 
 
 def test_training_that_never_idles_starves_inference_without_deadlock():
