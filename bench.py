@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # Average HBM bytes per dispatch of gemm_bf16_kernel<0,0> in this workload, from the FETCH_SIZE / WRITE_SIZE counter
 # runs summarised in profiles/bench_cfg2_hbm_traffic.md (counters cannot be read from inside a timed run).
-GEMM00_HBM_BYTES_PER_LAUNCH = 150.5e6
+GEMM00_HBM_BYTES_PER_LAUNCH = 131.9e6
 
 
 def cpu_baseline(sample_batch):
@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--coalesce", type=int, default=2, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
+    ap.add_argument("--coalesce", type=int, default=4, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=1000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--allow-serial-streams", action="store_true", help="for runs under a counter-collecting profiler, which serialises all kernels")

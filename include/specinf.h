@@ -394,10 +394,10 @@ sif_status sif_poll_stats(sif_ctx* ctx, sif_stats* out);
 sif_status sif_reset_stats(sif_ctx* ctx);
 
 /* Event timing of the bf16 GEMM launches, for roofline reporting.  While on, every GEMM launch of both streams
- * is bracketed by two HIP events on its own stream (at most 16384 launches per switch-on).  sif_profile_read
- * (profiling switched off first; synchronises both streams) returns per layout variant v = a_layout*2 + b_layout
- * the number of timed launches, their algorithmic floating-point operations (2mnk per batch; the lower triangle
- * only for causal products) and the sum of their event-to-event times in seconds. */
+ * is bracketed by two HIP events on its own stream (at most 16384 launches per switch-on).  sif_profile_read (profiling switched off first; synchronises both streams)
+ * returns per layout variant v = a_layout*2 + b_layout the number of timed launches, their algorithmic
+ * floating-point operations (2mnk per batch; the lower triangle only for causal products) and the sum of their
+ * event-to-event times in seconds.  Inference launches that the device gate skipped are left out. */
 sif_status sif_profile_gemm(sif_ctx* ctx, uint32_t on);
 sif_status sif_profile_read(sif_ctx* ctx, uint64_t launches[4], double flops[4], double seconds[4]);
 

@@ -81,6 +81,7 @@ struct sif_ctx {
   std::vector<hipEvent_t> prof_ev;      // 2 per timed launch
   std::vector<int32_t> prof_class;
   std::vector<double> prof_flops;
+  std::vector<uint32_t> prof_kseq;      // launch number on the inference stream, 0 for a training launch
   std::atomic<uint32_t> prof_n{0};
 
   uint64_t ticks_to_ns(uint64_t t) const { return (uint64_t)((unsigned __int128)t * 1000000000ull / tick_hz); }
@@ -105,6 +106,7 @@ static sif_status launch_op(sif_ctx* c, Op& op, hipStream_t s, const KCtl& k) {
     if (i < kProfMax) {
       c->prof_class[i] = op.prof_class;
       c->prof_flops[i] = op.flops;
+      c->prof_kseq[i] = k.gate != nullptr ? k.kseq : 0;      // gated launches may be skipped on the device: checked when read
       (void)hipEventRecord(c->prof_ev[2 * i], s);
       const sif_status st = op.fn(s, k);
       (void)hipEventRecord(c->prof_ev[2 * i + 1], s);
@@ -751,6 +753,7 @@ sif_status sif_profile_gemm(sif_ctx* c, uint32_t on) {
     for (auto& e : c->prof_ev) HIPCHK(hipEventCreate(&e), "profile_gemm: hipEventCreate");
     c->prof_class.assign(kProfMax, -1);
     c->prof_flops.assign(kProfMax, 0.0);
+    c->prof_kseq.assign(kProfMax, 0);
   }
   if (on) c->prof_n.store(0);
   c->prof_on.store(on != 0);
@@ -764,7 +767,14 @@ sif_status sif_profile_read(sif_ctx* c, uint64_t launches[4], double flops[4], d
   HIPCHK(hipStreamSynchronize(c->I.stream), "profile_read: inference stream");
   for (int i = 0; i < 4; ++i) { launches[i] = 0; flops[i] = 0; seconds[i] = 0; }
   const uint32_t n = std::min(c->prof_n.load(), kProfMax);
+  // a launch the device gate skipped did no work: leave it out (its re-run is timed by itself)
+  std::vector<Slot> ring(kRingSlots);
+  HIPCHK(hipMemcpy(ring.data(), c->I.ring, (size_t)kRingSlots * sizeof(Slot), hipMemcpyDeviceToHost), "profile_read: copy ring");
   for (uint32_t i = 0; i < n; ++i) {
+    if (c->prof_kseq[i] != 0) {
+      const Slot& sl = ring[c->prof_kseq[i] % kRingSlots];
+      if ((sl.decision >> 2) != c->prof_kseq[i] || (sl.decision & 3u) != 1u) continue;
+    }
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) != hipSuccess) continue;
     const int k = c->prof_class[i];
