@@ -248,7 +248,7 @@ typedef struct sif_config {
   uint64_t device_capacity_bytes; /* Principle-I capacity; 0 = total memory of the current device      */
 } sif_config;
 
-/* Fills *cfg with the defaults (P = 25 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 25, LL = 100, UL = 400
+/* Fills *cfg with the defaults (P = 25 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 200, LL = 400, UL = 800
  * tokens, kernel_us_max 200, collocate 1). */
 sif_status sif_default_config(sif_config* cfg);
 
