@@ -264,13 +264,18 @@ static void barrier_main(sif_ctx* c) {
     if ((c->collocate.load(std::memory_order_relaxed) && !c->hold) || !gated) {
       {
         std::lock_guard<std::mutex> lk(c->mu);
-        if (!c->online_q.empty() && c->run_online.empty()) {
+        // Online pull-and-execute: requests are pulled one at a time, in arrival order, each only if the status is
+        // idle and the predicted rest of the bubble, less what the requests already pulled still need, holds it.
+        while (!c->online_q.empty() && c->run_online.size() < 8) {
           Job* j = c->online_q.front();
           const uint64_t need = (uint64_t)(job_cost_us(j) * 1000.0);
-          if (!gated || sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), predicted_remaining_ns(c), need)) {
-            c->online_q.pop_front();
-            c->run_online.push_back(j);
-          }
+          uint64_t pending = 0;
+          for (const Job* q : c->run_online)
+            for (size_t i = q->done_ops; i < q->plan.size(); ++i) pending += (uint64_t)(q->plan[i].cost_us * 1000.0);
+          const uint64_t rest = predicted_remaining_ns(c);
+          if (gated && !sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), rest > pending ? rest - pending : 0, need)) break;
+          c->online_q.pop_front();
+          c->run_online.push_back(j);
         }
         while (!c->offline_q.empty() && c->run_offline.size() < 4) {
           Job* j = c->offline_q.front();
