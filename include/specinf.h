@@ -167,11 +167,13 @@ sif_status sif_k_gemm_f32(const float* a_dev, int64_t a_sm, int64_t a_sk, const 
  * mean_dev / rstd_dev: fp32 [rows] or null (not saved). */
 sif_status sif_k_layernorm_fwd(const void* x_dev, const void* g_dev, const void* b_dev, void* y_dev,
                                float* mean_dev, float* rstd_dev, uint32_t rows, uint32_t d, void* stream);
-/* dx = res + LNbwd(dy) (res_dev may be null), dg/db = column sums; part_dev is fp32 scratch of
- * 2 * sif_colsum_parts(rows) * d floats.  Fixed summation order (no atomics). */
+/* dx = res + LNbwd(dy) (res_dev may be null), dg/db = column sums of dy .* xhat and dy.  dsum_dev (bf16 [d], may
+ * be null) receives the column sums of the stored dx: in a transformer block dx is the upstream gradient of the
+ * bias added just before the residual sum this LayerNorm reads, so this is that bias's gradient.  part_dev is
+ * fp32 scratch of (dsum_dev ? 3 : 2) * sif_colsum_parts(rows) * d floats.  Fixed summation order (no atomics). */
 sif_status sif_k_layernorm_bwd(const void* dy_dev, const void* x_dev, const void* g_dev, const float* mean_dev,
                                const float* rstd_dev, const void* res_dev, void* dx_dev, void* dg_dev,
-                               void* db_dev, float* part_dev, uint32_t rows, uint32_t d, void* stream);
+                               void* db_dev, void* dsum_dev, float* part_dev, uint32_t rows, uint32_t d, void* stream);
 uint32_t sif_colsum_parts(uint32_t rows);
 /* out[n] = sum_m x[m,n]  (bf16 in/out, fp32 fixed-order accumulation); part_dev: sif_colsum_parts(rows)*n floats */
 sif_status sif_k_colsum(const void* x_dev, uint32_t ld, void* out_dev, float* part_dev, uint32_t rows, uint32_t n,

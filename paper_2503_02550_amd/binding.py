@@ -135,7 +135,7 @@ _sig("sif_pp_1f1b_bubbles", i32, u32, u32, u32, u64, u64, P(i32), P(i32), P(u64)
 _sig("sif_k_gemm_bf16", i32, P(sif_gemm_args), vp)
 _sig("sif_k_gemm_f32", i32, vp, i64, i64, vp, i64, i64, vp, i64, u32, u32, u32, u32, vp, vp, vp)
 _sig("sif_k_layernorm_fwd", i32, vp, vp, vp, vp, vp, vp, u32, u32, vp)
-_sig("sif_k_layernorm_bwd", i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, vp)
+_sig("sif_k_layernorm_bwd", i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, vp)
 _sig("sif_colsum_parts", u32, u32)
 _sig("sif_k_colsum", i32, vp, u32, vp, vp, u32, u32, vp)
 _sig("sif_k_softmax_fwd", i32, vp, vp, u32, u32, u32, u32, u32, u32, vp)
@@ -219,9 +219,9 @@ def sif_k_layernorm_fwd(x, g, b, y, mean, rstd, rows, d, stream=None):
     return check(lib.sif_k_layernorm_fwd(ptr(x), ptr(g), ptr(b), ptr(y), ptr(mean), ptr(rstd), rows, d, stream_ptr(stream)))
 
 
-def sif_k_layernorm_bwd(dy, x, g, mean, rstd, res, dx, dg, db, part, rows, d, stream=None):
+def sif_k_layernorm_bwd(dy, x, g, mean, rstd, res, dx, dg, db, part, rows, d, dsum=None, stream=None):
     return check(lib.sif_k_layernorm_bwd(ptr(dy), ptr(x), ptr(g), ptr(mean), ptr(rstd), ptr(res), ptr(dx), ptr(dg),
-                                         ptr(db), ptr(part), rows, d, stream_ptr(stream)))
+                                         ptr(db), ptr(dsum) if dsum is not None else None, ptr(part), rows, d, stream_ptr(stream)))
 
 
 def sif_colsum_parts(rows):

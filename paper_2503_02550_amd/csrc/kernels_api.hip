@@ -20,12 +20,12 @@ sif_status sif_k_layernorm_fwd(const void* x, const void* g, const void* b, void
 }
 
 sif_status sif_k_layernorm_bwd(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                               const void* res, void* dx, void* dg, void* db, float* part, uint32_t rows, uint32_t d,
+                               const void* res, void* dx, void* dg, void* db, void* dsum, float* part, uint32_t rows, uint32_t d,
                                void* stream) {
   if (!dg || !db) return fail(SIF_E_INVAL, "layernorm_bwd: null dg/db");
-  sif_status st = launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, S(stream), no_ctl());
+  sif_status st = launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, dsum != nullptr, S(stream), no_ctl());
   if (st != SIF_OK) return st;
-  return launch_layernorm_bwd_fin(part, dg, db, rows, d, 0, S(stream), no_ctl());
+  return launch_layernorm_bwd_fin(part, dg, db, dsum, rows, d, 0, S(stream), no_ctl());
 }
 
 uint32_t sif_colsum_parts(uint32_t rows) { return colsum_parts(rows); }

@@ -22,10 +22,10 @@ sif_status launch_gemm_f32(const float* a, int64_t a_sm, int64_t a_sk, const flo
 sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
                                 uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c);
 sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                                   const void* res, void* dx, float* part, uint32_t rows, uint32_t d, hipStream_t s,
+                                   const void* res, void* dx, float* part, uint32_t rows, uint32_t d, uint32_t with_sum, hipStream_t s,
                                    const KCtl& c);
-sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, uint32_t acc, hipStream_t s,
-                                    const KCtl& c);
+sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, void* dsum, uint32_t rows, uint32_t d, uint32_t acc,
+                                    hipStream_t s, const KCtl& c);
 sif_status launch_colsum_part(const void* x, uint32_t ld, float* part, uint32_t rows, uint32_t n, hipStream_t s,
                               const KCtl& c);
 sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32_t n, uint32_t acc, hipStream_t s, const KCtl& c);

@@ -186,10 +186,12 @@ static void emit_colsum(Plan& p, const char* name, const void* x, uint32_t ld, v
   emit(p, name, 3.0, [=](hipStream_t s, const KCtl& c) { return launch_colsum_fin(part, out, rows, n, acc, s, c); });
 }
 
+// dsum (may be null): gradient of the bias whose upstream gradient is this LayerNorm backward's output dx
 static void emit_ln_bwd(Plan& p, const void* dy, const void* x, const void* g, const float* mean, const float* rstd, const void* res,
-                        void* dx, void* dg, void* db, float* part, uint32_t rows, uint32_t d, uint32_t acc) {
-  emit(p, "ln_bwd", bytes_cost_us(8.0 * rows * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, s, c); });
-  emit(p, "ln_bwd_fin", 3.0, [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_fin(part, dg, db, rows, d, acc, s, c); });
+                        void* dx, void* dg, void* db, void* dsum, float* part, uint32_t rows, uint32_t d, uint32_t acc) {
+  const uint32_t ws = dsum != nullptr;
+  emit(p, "ln_bwd", bytes_cost_us(8.0 * rows * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, ws, s, c); });
+  emit(p, "ln_bwd_fin", 3.0, [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_fin(part, dg, db, dsum, rows, d, acc, s, c); });
 }
 
 // ------------------------------------------------------------------------------------------ transformer block
@@ -280,18 +282,21 @@ static void emit_decoder_layer_fwd(Plan& p, const Dims& q, const LayerW& w, cons
 }
 
 // dx_out -> dx_in (both bf16 [M,d]); gradients of the layer's parameters into g.  `tmp` is a second [M,d] buffer.
+// The gradients of b_proj and b_o are column sums of dx_out and dx_mid, which LayerNorm backward kernels write:
+// they come from those kernels.  have_db_proj: the producer of dx_out has already written g.b_proj;
+// db_proj_below: where this layer's last kernel puts the b_proj gradient of the layer below (null: none).
 static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, const LayerG& g, const bf16_t* x_in, const LayerActs& a,
-                                   const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp, uint32_t acc) {
+                                   const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp, uint32_t acc,
+                                   bool have_db_proj, bf16_t* db_proj_below) {
   const uint32_t M = q.M, d = q.d, f = q.f, da = q.da;
-  emit_colsum(p, "db_proj", dx_out, d, g.b_proj, sc.part, M, d, acc);
+  if (!have_db_proj) emit_colsum(p, "db_proj", dx_out, d, g.b_proj, sc.part, M, d, acc);
   emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, sc, acc);
   emit_gemm(p, "dz", G(dx_out, w.w_proj, sc.dz, M, f, d, d, f, f).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_GELU_GRAD, nullptr, nullptr, a.z));
   emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, sc.part, M, f, acc);
   emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, sc, acc);
   emit_gemm(p, "dln2", G(sc.dz, w.w_fc, sc.dln, M, d, f, f, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
-  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, sc.part, M, d, acc);
-  emit_colsum(p, "db_o", dx_mid, d, g.b_o, sc.part, M, d, acc);
+  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, g.b_o, sc.part, M, d, acc);
   emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, sc, acc);
   emit_gemm(p, "do", G(dx_mid, w.w_o, sc.d_o, M, da, d, d, da, da).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (fused_attention(q.dh)) {
@@ -309,7 +314,7 @@ static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, cons
   emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, sc, acc);
   emit_gemm(p, "dln1", G(sc.dqkv, w.w_qkv, sc.dln, M, d, 3 * da, 3 * da, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
-  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, sc.part, M, d, acc);
+  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, db_proj_below, sc.part, M, d, acc);
 }
 
 // ------------------------------------------------------------------------------------------ training models
@@ -389,7 +394,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   sc.d_o = (bf16_t*)ar.take((uint64_t)M * q.da * 2); sc.dz = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
   uint32_t widest = d > 3 * q.da ? d : 3 * q.da;
   if (q.f > widest) widest = q.f;
-  sc.part = (float*)ar.take((uint64_t)2 * colsum_parts(M) * widest * 4);
+  sc.part = (float*)ar.take((uint64_t)3 * colsum_parts(M) * widest * 4);
   sc.split_elems = (uint64_t)16 * 128 * 128 * 64;      // room for 512 tiles of 128x128 partial sums
   sc.split = (float*)ar.take(sc.split_elems * 4);
   bf16_t *lnf = nullptr, *logits = nullptr, *y_all = nullptr, *dx_all = nullptr;
@@ -476,7 +481,9 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       const LayerW w = layer_ptrs<LayerW, const bf16_t>(work, pm, l);
       const LayerG g = layer_ptrs<LayerG, bf16_t>(grads, pm, l);
       const bf16_t* xin_l = (l == 0) ? x0[sl] : acts[sl][l - 1].x_out;
-      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc);
+      const bool have_db_proj = s.vocab != 0 || l + 1 < (int32_t)s.n_layers;     // the final LayerNorm or the layer above wrote it
+      bf16_t* below = l > 0 ? grads + pm.at(L((uint32_t)l - 1, "b_proj")) : nullptr;
+      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc, have_db_proj, below);
       dx = sc.dx_a;
     }
     if (pp) {
@@ -502,7 +509,8 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
       emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
       emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
-      emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"), sc.part, M, d, 0);
+      emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"),
+                  grads + pm.at(L(s.n_layers - 1, "b_proj")), sc.part, M, d, 0);
       dx = sc.dx_a;
     }
     emit_backward(p, 0, 0, dx);

@@ -46,51 +46,76 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __rest
 }
 
 constexpr int LN_MAXV = 8;   // vectors of 8 columns per lane: d <= 4096
-uint32_t colsum_parts(uint32_t rows) { uint32_t p = (rows + 31) / 32; return p < 1 ? 1 : (p > 512 ? 512 : p); }
+uint32_t colsum_parts(uint32_t rows) { uint32_t p = (rows + 15) / 16; return p < 1 ? 1 : (p > 512 ? 512 : p); }
 
 // dx = res + rstd * (dy*g - mean(dy*g) - xhat * mean(dy*g*xhat)); per-block partial column sums of dy*xhat and
-// dy are written to part[blk][d] and part[parts+blk][d].  Block b handles rows b, b+parts, ... in wave order.
+// dy are written to part[blk][d] and part[parts+blk][d], and with WITH_SUM those of the rounded dx to
+// part[2*parts+blk][d] (dx is the upstream gradient of the bias that was added just before this LayerNorm's input
+// went into a residual sum: its column sums are that bias's gradient, and come for free here).  Block b handles
+// rows b*rows_per.., its wavefronts interleaved.  MAXV = vectors of 8 columns per lane; up to 4 the row stays in
+// registers between the two passes.
+template <int MAXV, bool WITH_SUM>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __restrict__ dy, const bf16_t* __restrict__ x,
                                                             const bf16_t* __restrict__ g, const float* __restrict__ mean,
                                                             const float* __restrict__ rstd, const bf16_t* __restrict__ res,
                                                             bf16_t* __restrict__ dx, float* __restrict__ part,
                                                             uint32_t rows, uint32_t d, uint32_t parts, KCtl ctl) {
+  constexpr bool CACHE = MAXV <= 4;
+  constexpr int NSUM = WITH_SUM ? 3 : 2;
   __shared__ float sred[4 * 512];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nv = d >> 3;
   const uint32_t rows_per = (rows + parts - 1) / parts;
   const uint32_t r_begin = blockIdx.x * rows_per, r_end = min(rows, r_begin + rows_per);
-  float ag[LN_MAXV][8], ab[LN_MAXV][8];
+  float acc[NSUM][MAXV][8];
 #pragma unroll
-  for (int t = 0; t < LN_MAXV; ++t)
+  for (int w = 0; w < NSUM; ++w)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { ag[t][i] = 0.f; ab[t][i] = 0.f; }
+    for (int t = 0; t < MAXV; ++t)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[w][t][i] = 0.f;
+  uint4 cg[CACHE ? MAXV : 1];
+  if (CACHE) {
+#pragma unroll
+    for (int t = 0; t < MAXV; ++t) cg[t] = (lane + 64 * t < nv) ? reinterpret_cast<const uint4*>(g)[lane + 64 * t] : make_uint4(0, 0, 0, 0);
+  }
   for (uint32_t row = r_begin + wave; row < r_end; row += 4) {
     const uint4* dyr = reinterpret_cast<const uint4*>(dy + (size_t)row * d);
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
     const float mu = mean[row], rs = rstd[row];
+    uint4 cdy[CACHE ? MAXV : 1], cx[CACHE ? MAXV : 1];
+    if (CACHE) {
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t) {
+        const uint32_t v = lane + 64 * t;
+        cdy[t] = v < nv ? dyr[v] : make_uint4(0, 0, 0, 0);
+        cx[t] = v < nv ? xr[v] : make_uint4(0, 0, 0, 0);
+      }
+    }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int t = 0; t < LN_MAXV; ++t) {
+    for (int t = 0; t < MAXV; ++t) {
       const uint32_t v = lane + 64 * t;
       if (v < nv) {
         float fdy[8], fx[8], fg[8];
-        unpack8(dyr[v], fdy); unpack8(xr[v], fx); unpack8(reinterpret_cast<const uint4*>(g)[v], fg);
+        unpack8(CACHE ? cdy[t] : dyr[v], fdy); unpack8(CACHE ? cx[t] : xr[v], fx);
+        unpack8(CACHE ? cg[t] : reinterpret_cast<const uint4*>(g)[v], fg);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float xh = (fx[i] - mu) * rs, dxh = fdy[i] * fg[i];
           s1 += dxh; s2 += dxh * xh;
-          ag[t][i] += fdy[i] * xh; ab[t][i] += fdy[i];
+          acc[0][t][i] += fdy[i] * xh; acc[1][t][i] += fdy[i];
         }
       }
     }
     const float m1 = wave_sum(s1) / (float)d, m2 = wave_sum(s2) / (float)d;
 #pragma unroll
-    for (int t = 0; t < LN_MAXV; ++t) {
+    for (int t = 0; t < MAXV; ++t) {
       const uint32_t v = lane + 64 * t;
       if (v < nv) {
         float fdy[8], fx[8], fg[8], fr[8], o[8];
-        unpack8(dyr[v], fdy); unpack8(xr[v], fx); unpack8(reinterpret_cast<const uint4*>(g)[v], fg);
+        unpack8(CACHE ? cdy[t] : dyr[v], fdy); unpack8(CACHE ? cx[t] : xr[v], fx);
+        unpack8(CACHE ? cg[t] : reinterpret_cast<const uint4*>(g)[v], fg);
         if (res != nullptr) unpack8(reinterpret_cast<const uint4*>(res + (size_t)row * d)[v], fr);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -98,16 +123,25 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
           o[i] = rs * (fdy[i] * fg[i] - m1 - xh * m2);
           if (res != nullptr) o[i] += fr[i];
         }
-        reinterpret_cast<uint4*>(dx + (size_t)row * d)[v] = pack8(o);
+        const uint4 packed = pack8(o);
+        reinterpret_cast<uint4*>(dx + (size_t)row * d)[v] = packed;
+        if (WITH_SUM) {
+          unpack8(packed, o);                  // the column sums are those of the stored (rounded) values
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc[NSUM - 1][t][i] += o[i];
+        }
       }
     }
   }
   // combine the four wavefronts in order 0,1,2,3, 512 columns at a time
-  for (int t = 0; t < LN_MAXV; ++t) {
+#pragma unroll
+  for (int t = 0; t < MAXV; ++t) {
     if ((uint32_t)(64 * t) >= nv) break;
-    for (int which = 0; which < 2; ++which) {
+#pragma unroll
+    for (int which = 0; which < NSUM; ++which) {
       __syncthreads();
-      for (int i = 0; i < 8; ++i) sred[wave * 512 + lane * 8 + i] = which ? ab[t][i] : ag[t][i];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sred[wave * 512 + lane * 8 + i] = acc[which][t][i];
       __syncthreads();
       for (uint32_t cidx = threadIdx.x; cidx < 512; cidx += 256) {
         const uint32_t col = 512 * t + cidx;
@@ -126,8 +160,16 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
 __device__ __forceinline__ float fin_column(const float* __restrict__ part, uint32_t parts, uint32_t n, uint32_t col, float* sm) {
   const uint32_t w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   float s = 0.f;
-  if (col < n)
-    for (uint32_t p = w; p < parts; p += 16) s += part[(size_t)p * n + col];
+  if (col < n) {
+    // eight loads in flight, added in ascending row order
+    for (uint32_t p = w; p < parts; p += 16 * 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (p + 16 * u < parts) ? part[(size_t)(p + 16 * u) * n + col] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+  }
   __syncthreads();
   sm[w * 64 + lane] = s;
   __syncthreads();
@@ -137,15 +179,22 @@ __device__ __forceinline__ float fin_column(const float* __restrict__ part, uint
   return t;
 }
 
-// out[c] = bf16(sum_p part[p][c]) for dg (first `parts` rows) and db (next `parts` rows).
+// out[c] = bf16(sum_p part[p][c]) for dg (first `parts` rows), db (next `parts` rows) and, if dsum != null, the
+// column sums of dx (third `parts` rows).
 __global__ __launch_bounds__(1024) void layernorm_bwd_fin_kernel(const float* __restrict__ part, bf16_t* __restrict__ dg,
-                                                                 bf16_t* __restrict__ db, uint32_t parts, uint32_t d, uint32_t acc, KCtl ctl) {
+                                                                 bf16_t* __restrict__ db, bf16_t* __restrict__ dsum, uint32_t parts,
+                                                                 uint32_t d, uint32_t acc, KCtl ctl) {
   __shared__ float sm[1024];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63);
   const float sg = fin_column(part, parts, d, c, sm);
   const float sb = fin_column(part + (size_t)parts * d, parts, d, c, sm);
-  if (threadIdx.x < 64 && c < d) { dg[c] = f2bf(acc ? bf2f(dg[c]) + sg : sg); db[c] = f2bf(acc ? bf2f(db[c]) + sb : sb); }
+  const float ss = dsum != nullptr ? fin_column(part + (size_t)2 * parts * d, parts, d, c, sm) : 0.f;
+  if (threadIdx.x < 64 && c < d) {
+    dg[c] = f2bf(acc ? bf2f(dg[c]) + sg : sg);
+    db[c] = f2bf(acc ? bf2f(db[c]) + sb : sb);
+    if (dsum != nullptr) dsum[c] = f2bf(acc ? bf2f(dsum[c]) + ss : ss);
+  }
   kernel_end(ctl, true);
 }
 
@@ -513,21 +562,25 @@ sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, voi
   return check_launch("layernorm_fwd");
 }
 
-sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
-                                   const void* res, void* dx, float* part, uint32_t rows, uint32_t d, hipStream_t s,
-                                   const KCtl& c) {
+sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd, const void* res,
+                                   void* dx, float* part, uint32_t rows, uint32_t d, uint32_t with_sum, hipStream_t s, const KCtl& c) {
   REQ(dy && x && g && mean && rstd && dx && part && rows > 0, "layernorm_bwd: null or empty");
   REQ((d & 7) == 0 && d <= 8 * 64 * LN_MAXV, "layernorm_bwd: d must be a multiple of 8 and <= 4096");
   REQ(al16(dy) && al16(x) && al16(g) && al16(dx) && (res == nullptr || al16(res)), "layernorm_bwd: pointers must be 16-byte aligned");
   const uint32_t parts = colsum_parts(rows);
-  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(parts), dim3(256), 0, s, (const bf16_t*)dy, (const bf16_t*)x, (const bf16_t*)g,
-                     mean, rstd, (const bf16_t*)res, (bf16_t*)dx, part, rows, d, parts, c);
+#define LNB(V, W) hipLaunchKernelGGL((layernorm_bwd_kernel<V, W>), dim3(parts), dim3(256), 0, s, (const bf16_t*)dy, (const bf16_t*)x, \
+                                     (const bf16_t*)g, mean, rstd, (const bf16_t*)res, (bf16_t*)dx, part, rows, d, parts, c)
+  if (d <= 1024) { if (with_sum) LNB(2, true); else LNB(2, false); }
+  else if (d <= 2048) { if (with_sum) LNB(4, true); else LNB(4, false); }
+  else { if (with_sum) LNB(8, true); else LNB(8, false); }
+#undef LNB
   return check_launch("layernorm_bwd");
 }
 
-sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, uint32_t rows, uint32_t d, uint32_t acc, hipStream_t s, const KCtl& c) {
+sif_status launch_layernorm_bwd_fin(const float* part, void* dg, void* db, void* dsum, uint32_t rows, uint32_t d, uint32_t acc, hipStream_t s,
+                                    const KCtl& c) {
   REQ(part && dg && db, "layernorm_bwd_fin: null");
-  hipLaunchKernelGGL(layernorm_bwd_fin_kernel, dim3((d + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)dg, (bf16_t*)db,
+  hipLaunchKernelGGL(layernorm_bwd_fin_kernel, dim3((d + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)dg, (bf16_t*)db, (bf16_t*)dsum,
                      colsum_parts(rows), d, acc, c);
   return check_launch("layernorm_bwd_fin");
 }

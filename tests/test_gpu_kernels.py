@@ -143,12 +143,16 @@ def test_layernorm_fwd_bwd(rows, d):
     assert_f32_close(up(mean), rm[:, 0], "mean", 1e-5)
     assert_f32_close(up(rstd), rr[:, 0], "rstd", 1e-5)
     dx, dg, db = torch.zeros_like(X), torch.zeros(d, device=DEV, dtype=torch.bfloat16), torch.zeros(d, device=DEV, dtype=torch.bfloat16)
-    part = torch.zeros(2 * S.sif_colsum_parts(rows) * d, device=DEV)
-    S.sif_k_layernorm_bwd(DY, X, G, mean, rstd, R, dx, dg, db, part, rows, d)
+    part = torch.zeros(3 * S.sif_colsum_parts(rows) * d, device=DEV)
+    dsum = torch.full((d,), 9.0, device=DEV, dtype=torch.bfloat16)
+    S.sif_k_layernorm_bwd(DY, X, G, mean, rstd, R, dx, dg, db, part, rows, d, dsum=dsum)
     rdx, rdg, rdb = N.layernorm_bwd(q(dy), q(x), q(g), rm, rr)
     assert_bf16_close(up(dx), q(res) + rdx, "ln dx")
     assert_bf16_close(up(dg), rdg, "ln dg")
     assert_bf16_close(up(db), rdb, "ln db")
+    # column sums of the stored dx (the gradient of a bias added upstream of the residual sum)
+    assert_bf16_close(up(dsum), up(dx).sum(axis=0), "ln column sums of dx")
+    assert_bf16_close(up(dsum), q(q(res) + rdx).sum(axis=0), "ln column sums of dx vs oracle", elem_slack=8e-3)
     S.sif_k_layernorm_bwd(DY, X, G, mean, rstd, None, dx, dg, db, part, rows, d)
     assert_bf16_close(up(dx), rdx, "ln dx no residual")
 
