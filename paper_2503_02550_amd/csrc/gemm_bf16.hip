@@ -138,6 +138,47 @@ struct InteriorStream {
   }
 };
 
+// Interior tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
+// store instructions).  One such instruction writes the 64 lanes' 16 bytes to consecutive LDS addresses, 1 KB per
+// wavefront, so the lane's position in the tile is fixed and the swizzle is applied to what it fetches: lane l of
+// wavefront w, instruction i covers
+//   LAYOUT 0: tile row 32*i + 8*w + l/8, chunk position l%8 = logical chunk (l%8) ^ key(row)
+//   LAYOUT 1: k-row 16*i + 4*w + l/16, 16-byte unit l%16 = segment position (l%16)/4 -> logical segment ^ (k%4)
+// key and k%4 do not depend on i, so the four fetches of a thread differ by a block-uniform stride.
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
+template <int LAYOUT, int ROWS>
+struct DmaStream {
+  const char* tile;
+  size_t step, vstride;
+  uint32_t voff;
+  __device__ __forceinline__ DmaStream(const bf16_t* b, uint32_t ld, uint32_t row0, uint32_t k_begin) {
+    static_assert(ROWS == 128, "the lane mapping below covers 128 tile rows with 256 threads");
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (LAYOUT == 0) {
+      const uint32_t r = wave * 8 + (lane >> 3), c = (lane & 7u) ^ swz_key(r);
+      tile = (const char*)(b + (size_t)row0 * ld + k_begin);
+      step = BK * sizeof(bf16_t);
+      vstride = (size_t)32 * ld * sizeof(bf16_t);
+      voff = (r * ld + c * 8) * (uint32_t)sizeof(bf16_t);
+    } else {
+      const uint32_t k = wave * 4 + (lane >> 4), u = lane & 15u, seg = (u >> 2) ^ (k & 3u);
+      tile = (const char*)(b + (size_t)k_begin * ld + row0);
+      step = (size_t)BK * ld * sizeof(bf16_t);
+      vstride = (size_t)16 * ld * sizeof(bf16_t);
+      voff = (k * ld + seg * 32 + (u & 3u) * 8) * (uint32_t)sizeof(bf16_t);
+    }
+  }
+  // fetches the next tile into `stage` (a whole tile buffer of ROWS x 64 elements)
+  __device__ __forceinline__ void next(bf16_t* stage) {
+    const uint32_t wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + i * vstride + voff), (lds_void_ptr)(stage + i * 2048 + wave * 512), 16, 0, 0);
+    tile += step;
+  }
+};
+
 // Epilogue of eight consecutive columns n..n+7 of row m (both inside the result): scale, bias, GELU, GELU' multiply,
 // residual, store; `vec` says that every access may be a 16-byte vector.
 __device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uint32_t m, uint32_t n, float (&v)[8], bool vec) {
@@ -205,9 +246,11 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   constexpr int THREADS = 64 * WM * WN, TI = BM / (WM * 32), TJ = BN / (WN * 32), WCOLS = TJ * 32;
   static_assert(BM * 8 == 4 * THREADS && BN * 8 == 4 * THREADS, "four 16-byte vectors per thread and operand tile");
   static_assert(WCOLS == 64, "the epilogue staging is laid out for 64 columns per wavefront");
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* sA = reinterpret_cast<bf16_t*>(smem_raw);            // [2][BM][BK], swizzled
-  bf16_t* sB = sA + 2 * BM * BK;                               // [2][BN][BK]
+  // two tile buffers per operand, as four objects so that the compiler can tell a buffer being filled from the one being read
+  __shared__ __align__(1024) bf16_t sA0[BM * BK];
+  __shared__ __align__(1024) bf16_t sA1[BM * BK];
+  __shared__ __align__(1024) bf16_t sB0[BN * BK];
+  __shared__ __align__(1024) bf16_t sB1[BN * BK];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
 
   // Block -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
@@ -248,9 +291,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // into the set tile t has just left, so every global load has two iterations of MFMA work to hide behind.
     uint4 ra0[4], rb0[4], ra1[4], rb1[4];
     const uint32_t fra = wm * (TI * 32) + (lane & 31), frb = wn * (TJ * 32) + (lane & 31), kh = lane >> 5;
-    auto compute = [&](int buf) {
-      const bf16_t* cA = sA + buf * BM * BK;
-      const bf16_t* cB = sB + buf * BN * BK;
+    auto compute = [&](const bf16_t* cA, const bf16_t* cB) {
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
         bf16x8 fa[TI], fb[TJ];
@@ -275,25 +316,18 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // without EDGE the launcher guarantees that every tile is interior
     const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
     if (interior) {
-      InteriorStream<ALAY, THREADS, BM> ta(A, p.lda, m0, k_begin);
-      InteriorStream<BLAY, THREADS, BN> tb(B, p.ldb, n0, k_begin);
-      ta.next(ra0); tb.next(rb0);
-      if (nt > 1) { ta.next(ra1); tb.next(rb1); }
-      store_tile<ALAY, THREADS, BM>(sA, ra0, 0xFu);
-      store_tile<BLAY, THREADS, BN>(sB, rb0, 0xFu);
+      // tile t+1 is fetched into the other pair of buffers while tile t is multiplied; the other block of the CU
+      // covers what the fetch latency exceeds one K step
+      DmaStream<ALAY, BM> ta(A, p.lda, m0, k_begin);
+      DmaStream<BLAY, BN> tb(B, p.ldb, n0, k_begin);
+      ta.next(sA0); tb.next(sB0);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
-        if (t + 2 < nt) { ta.next(ra0); tb.next(rb0); }
-        compute(0);
-        store_tile<ALAY, THREADS, BM>(sA + BM * BK, ra1, 0xFu);
-        store_tile<BLAY, THREADS, BN>(sB + BN * BK, rb1, 0xFu);
+        ta.next(sA1); tb.next(sB1);
+        compute(sA0, sB0);
         __syncthreads();
-        if (t + 3 < nt) { ta.next(ra1); tb.next(rb1); }
-        compute(1);
-        if (t + 2 < nt) {
-          store_tile<ALAY, THREADS, BM>(sA, ra0, 0xFu);
-          store_tile<BLAY, THREADS, BN>(sB, rb0, 0xFu);
-        }
+        if (t + 2 < nt) { ta.next(sA0); tb.next(sB0); }
+        compute(sA1, sB1);
         __syncthreads();
       }
     } else if (EDGE) {
@@ -301,26 +335,26 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       uint32_t okb0 = load_tile<BLAY, THREADS, BN>(rb0, B, p.ldb, n0, p.n, k_begin, k_end);
       uint32_t oka1 = load_tile<ALAY, THREADS, BM>(ra1, A, p.lda, m0, p.m, k_begin + BK, k_end);       // reads as zero past k_end
       uint32_t okb1 = load_tile<BLAY, THREADS, BN>(rb1, B, p.ldb, n0, p.n, k_begin + BK, k_end);
-      store_tile<ALAY, THREADS, BM>(sA, ra0, oka0);
-      store_tile<BLAY, THREADS, BN>(sB, rb0, okb0);
+      store_tile<ALAY, THREADS, BM>(sA0, ra0, oka0);
+      store_tile<BLAY, THREADS, BN>(sB0, rb0, okb0);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         const uint32_t k0 = k_begin + t * BK;
         oka0 = load_tile<ALAY, THREADS, BM>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
         okb0 = load_tile<BLAY, THREADS, BN>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
-        compute(0);
-        store_tile<ALAY, THREADS, BM>(sA + BM * BK, ra1, oka1);
-        store_tile<BLAY, THREADS, BN>(sB + BN * BK, rb1, okb1);
+        compute(sA0, sB0);
+        store_tile<ALAY, THREADS, BM>(sA1, ra1, oka1);
+        store_tile<BLAY, THREADS, BN>(sB1, rb1, okb1);
         __syncthreads();
         oka1 = load_tile<ALAY, THREADS, BM>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
         okb1 = load_tile<BLAY, THREADS, BN>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
-        compute(1);
-        store_tile<ALAY, THREADS, BM>(sA, ra0, oka0);
-        store_tile<BLAY, THREADS, BN>(sB, rb0, okb0);
+        compute(sA1, sB1);
+        store_tile<ALAY, THREADS, BM>(sA0, ra0, oka0);
+        store_tile<BLAY, THREADS, BN>(sB0, rb0, okb0);
         __syncthreads();
       }
     }
-    if (nt & 1u) compute(0);
+    if (nt & 1u) compute(sA0, sB0);
 
     // Epilogue.  Each wavefront passes its accumulators, 32 rows at a time, through a staging area of its own in
     // LDS (fp32 [32][64], the operand buffers are free by now) so that every global access of the epilogue - bias,
@@ -329,7 +363,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // Chunk c (four floats) of staging row r lives at c ^ (8*((r/4)%2) | r%2): the two half-wavefronts of a store
     // and the eight rows of a load then fall on different banks.
     __syncthreads();
-    float* sW = reinterpret_cast<float*>(smem_raw) + wave * (32 * WCOLS);
+    float* sW = reinterpret_cast<float*>(wave < 2 ? sA0 : sA1) + (wave & 1) * (32 * WCOLS);
     const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
     const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
 #pragma unroll
@@ -361,9 +395,6 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
-
-typedef void (*gemm_kern_t)(GemmP, KCtl);
-struct GemmVariant { gemm_kern_t fn; bool attr_set; };
 
 sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KCtl& ctl) {
   if (a == nullptr || a->struct_size != sizeof(sif_gemm_args)) return fail(SIF_E_INVAL, "gemm: bad args struct");
@@ -399,17 +430,10 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   p.tiles_n = (a->n + bn - 1) / bn; p.tiles_m = (a->m + bm - 1) / bm;
   if (batches > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
   dim3 grid(p.tiles_m * p.tiles_n, 1, (uint32_t)batches);
-  const size_t lds = (size_t)2 * (bm + bn) * BK * sizeof(bf16_t);
-  static GemmVariant table[2][2] = {
-      {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, false}, {gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>, false}},
-      {{gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, false}, {gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>, false}}};
-  GemmVariant& v = table[a->a_layout][a->b_layout];
-  if (!v.attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return fail_hip(e, "gemm: hipFuncSetAttribute");
-    v.attr_set = true;
-  }
-  hipLaunchKernelGGL(v.fn, grid, dim3(256), lds, stream, p, ctl);
+  typedef void (*gemm_kern_fn)(GemmP, KCtl);
+  static const gemm_kern_fn table[2][2] = {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>},
+                                           {gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>}};
+  hipLaunchKernelGGL(table[a->a_layout][a->b_layout], grid, dim3(256), 0, stream, p, ctl);
   return check_launch("gemm_bf16");
 }
 
