@@ -151,6 +151,9 @@ typedef struct sif_gemm_args {
   const void* bias_dev;        /* bf16 [N] or null                                                      */
   const void* res_dev;         /* residual, or null                                                     */
   void* aux_dev;               /* see SIF_EPI_GELU / SIF_EPI_GELU_GRAD                                  */
+  uint32_t tile;               /* block tile edge: 0 = chosen from the shape, 128, or 256 (256: k a multiple of 64, no
+                                  k_causal, no SIF_EPI_CAUSAL_SKIP).  The result has the same bits whichever is used. */
+  uint32_t reserved;
 } sif_gemm_args;
 
 /* bf16 matrix product on the MFMA units, fp32 accumulation. */

@@ -7,16 +7,19 @@
 // forward products (A [M][K], B [N][K]), data gradients (B [K][N]), weight gradients (A [K][M], B [K][N]) and
 // the per-head attention products via two batch strides.
 //
-// Tiling: block tile BM x BN (128 x 128), K step 64, WM x WN (2 x 2) wavefronts, each owning a 64x64 tile as 2x2
-// v_mfma_f32_32x32x16_bf16 accumulators; two blocks per CU.  Operand tiles are staged through LDS with K contiguous
-// (unpadded rows of 128 bytes, XOR-swizzled in 16-byte chunks so that reads and writes spread over the banks); an
-// operand whose memory layout has the other dimension contiguous is staged as it lies and transposed by the LDS
-// read itself (ds_read_b64_tr_b16).  Global loads of the next K step are issued before the MFMAs of the current one (register prefetch,
-// two LDS buffers).  (A 256x256 tile with 128x64 per wavefront would need a quarter fewer LDS reads per MFMA, but
-// its 128 accumulator + 64 prefetch registers leave the compiler no room: it spills inside the K loop.)
+// Tiling: block tile BM x BN, K step 64, WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) tile as a grid of
+// v_mfma_f32_32x32x16_bf16 accumulators.  128x128 with 2x2 wavefronts (64x64 each), two blocks per CU, is the
+// working configuration; 256x256 with 2x4 wavefronts (128x64 each: six operand reads from LDS per eight MFMAs
+// instead of eight, half the global fetches per MFMA), one block per CU, takes over for products with many tiles
+// and a long K.  Operand tiles are staged through LDS with K contiguous (unpadded rows of 128 bytes, XOR-swizzled
+// in 16-byte chunks so that reads and writes spread over the banks); an operand whose memory layout has the other
+// dimension contiguous is staged as it lies and transposed by the LDS read itself (ds_read_b64_tr_b16).  Interior
+// tiles are fetched from global memory straight into LDS, tile t+1 while tile t is multiplied; tiles on a ragged
+// edge of the 128x128 configuration go through registers (two K steps of prefetch) so that they can be zero-filled.
 //
-// Results do not depend on the grid: each output element is reduced over K in one fixed order (ascending, 16 at a
-// time) by one wavefront, so launching a row range of the same problem gives bit-identical rows.
+// Results depend neither on the grid nor on the tile configuration: each output element is reduced over K in one
+// fixed order (ascending, 16 at a time) by one wavefront, so launching a row range of the same problem, or the other
+// configuration, gives bit-identical values.
 #include "common.h"
 #include "specinf.h"
 #include "launch.h"
@@ -144,29 +147,34 @@ struct InteriorStream {
 // wavefront w, instruction i covers
 //   LAYOUT 0: tile row 32*i + 8*w + l/8, chunk position l%8 = logical chunk (l%8) ^ key(row)
 //   LAYOUT 1: k-row 16*i + 4*w + l/16, 16-byte unit l%16 = segment position (l%16)/4 -> logical segment ^ (k%4)
-// key and k%4 do not depend on i, so the four fetches of a thread differ by a block-uniform stride.
+// (with 256 threads; 512 threads cover twice the rows or k-rows per instruction).
 typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(1))) const void* global_void_ptr;
-template <int LAYOUT, int ROWS>
+template <int LAYOUT, int ROWS, int THREADS>
 struct DmaStream {
   const char* tile;
-  size_t step, vstride;
-  uint32_t voff;
-  __device__ __forceinline__ DmaStream(const bf16_t* b, uint32_t ld, uint32_t row0, uint32_t k_begin) {
-    static_assert(ROWS == 128, "the lane mapping below covers 128 tile rows with 256 threads");
-    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  size_t step;
+  uint32_t voff[4];
+  // rows >= `rows` (a ragged last tile) fetch the tile's first row instead: what they produce is never stored
+  __device__ __forceinline__ DmaStream(const bf16_t* b, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k_begin) {
     if (LAYOUT == 0) {
-      const uint32_t r = wave * 8 + (lane >> 3), c = (lane & 7u) ^ swz_key(r);
       tile = (const char*)(b + (size_t)row0 * ld + k_begin);
       step = BK * sizeof(bf16_t);
-      vstride = (size_t)32 * ld * sizeof(bf16_t);
-      voff = (r * ld + c * 8) * (uint32_t)sizeof(bf16_t);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t r = i * (THREADS / 8) + (threadIdx.x >> 3), c = (threadIdx.x & 7u) ^ swz_key(r);
+        voff[i] = ((row0 + r < rows ? r : 0u) * ld + c * 8) * (uint32_t)sizeof(bf16_t);
+      }
     } else {
-      const uint32_t k = wave * 4 + (lane >> 4), u = lane & 15u, seg = (u >> 2) ^ (k & 3u);
+      constexpr uint32_t UR = ROWS / 8;          // 16-byte units per k-row
       tile = (const char*)(b + (size_t)k_begin * ld + row0);
       step = (size_t)BK * ld * sizeof(bf16_t);
-      vstride = (size_t)16 * ld * sizeof(bf16_t);
-      voff = (k * ld + seg * 32 + (u & 3u) * 8) * (uint32_t)sizeof(bf16_t);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const uint32_t k = i * (THREADS / UR) + threadIdx.x / UR, u = threadIdx.x % UR, seg = (u >> 2) ^ (k & 3u);
+        const uint32_t r = seg * 32 + (u & 3u) * 8;
+        voff[i] = (k * ld + (row0 + r < rows ? r : 0u)) * (uint32_t)sizeof(bf16_t);
+      }
     }
   }
   // fetches the next tile into `stage` (a whole tile buffer of ROWS x 64 elements)
@@ -174,7 +182,7 @@ struct DmaStream {
     const uint32_t wave = threadIdx.x >> 6;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + i * vstride + voff), (lds_void_ptr)(stage + i * 2048 + wave * 512), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + voff[i]), (lds_void_ptr)(stage + i * (THREADS * 8) + wave * 512), 16, 0, 0);
     tile += step;
   }
 };
@@ -318,8 +326,8 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     if (interior) {
       // tile t+1 is fetched into the other pair of buffers while tile t is multiplied; the other block of the CU
       // covers what the fetch latency exceeds one K step
-      DmaStream<ALAY, BM> ta(A, p.lda, m0, k_begin);
-      DmaStream<BLAY, BN> tb(B, p.ldb, n0, k_begin);
+      DmaStream<ALAY, BM, THREADS> ta(A, p.lda, m0, p.m, k_begin);
+      DmaStream<BLAY, BN, THREADS> tb(B, p.ldb, n0, p.n, k_begin);
       ta.next(sA0); tb.next(sB0);
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
@@ -363,7 +371,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // Chunk c (four floats) of staging row r lives at c ^ (8*((r/4)%2) | r%2): the two half-wavefronts of a store
     // and the eight rows of a load then fall on different banks.
     __syncthreads();
-    float* sW = reinterpret_cast<float*>(wave < 2 ? sA0 : sA1) + (wave & 1) * (32 * WCOLS);
+    float* sW = reinterpret_cast<float*>(wave < WM * WN / 2 ? sA0 : sA1) + (wave % (WM * WN / 2)) * (32 * WCOLS);
     const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
     const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
 #pragma unroll
@@ -417,8 +425,19 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
     if ((a->ldc & 7) || ((a->c_stride_outer | a->c_stride_inner) & 7)) return fail(SIF_E_INVAL, "gemm: ldc and the output batch strides must be multiples of 8 when n is");
     if ((a->bias_dev && !aligned16(a->bias_dev)) || (a->res_dev && !aligned16(a->res_dev)) || (a->aux_dev && !aligned16(a->aux_dev))) return fail(SIF_E_INVAL, "gemm: bias, residual and aux must be 16-byte aligned");
   }
-  const uint32_t bm = 128, bn = 128;
+  // 256x256 tiles (one block of eight wavefronts per CU, 128x64 per wavefront: a quarter fewer LDS reads and half
+  // the global fetches per MFMA); they need whole K steps and no causal skipping
   const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
+  const bool causal = a->k_causal != 0 || (a->epilogue & SIF_EPI_CAUSAL_SKIP);
+  const uint64_t tiles256 = (uint64_t)((a->m + 255) / 256) * ((a->n + 255) / 256) * batches;
+  const bool can_big = !causal && (a->k % BK) == 0;
+  if (a->tile != 0 && a->tile != 128 && a->tile != 256) return fail(SIF_E_INVAL, "gemm: tile must be 0, 128 or 256");
+  if (a->tile == 256 && !can_big) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
+  // measured on gfx950: they win from about four rounds of tiles and K of 2048 on (8192 x 8192 x 2048: 937 against 867
+  // TFLOP/s, 8192^3: 1115 against 967); with fewer tiles or a short K their longer prologue and epilogue, which no
+  // second block on the CU overlaps, cost more than the main loop gains
+  const bool big = a->tile == 256 || (a->tile == 0 && can_big && tiles256 >= 1024 && a->k >= 2048);
+  const uint32_t bm = big ? 256 : 128, bn = bm;
   GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;
   p.bias = (a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) ? (const bf16_t*)a->bias_dev : nullptr;
@@ -433,7 +452,10 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   typedef void (*gemm_kern_fn)(GemmP, KCtl);
   static const gemm_kern_fn table[2][2] = {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>},
                                            {gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>}};
-  hipLaunchKernelGGL(table[a->a_layout][a->b_layout], grid, dim3(256), 0, stream, p, ctl);
+  static const gemm_kern_fn table256[2][2] = {{gemm_bf16_kernel<0, 0, 256, 256, 2, 4, false>, gemm_bf16_kernel<0, 1, 256, 256, 2, 4, false>},
+                                              {gemm_bf16_kernel<1, 0, 256, 256, 2, 4, false>, gemm_bf16_kernel<1, 1, 256, 256, 2, 4, false>}};
+  if (big) hipLaunchKernelGGL(table256[a->a_layout][a->b_layout], grid, dim3(512), 0, stream, p, ctl);
+  else hipLaunchKernelGGL(table[a->a_layout][a->b_layout], grid, dim3(256), 0, stream, p, ctl);
   return check_launch("gemm_bf16");
 }
 

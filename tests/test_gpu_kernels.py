@@ -96,6 +96,24 @@ def test_gemm_bf16_row_range_is_bit_identical():
     assert torch.equal(full, part)
 
 
+@pytest.mark.parametrize("al,bl", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("m,n,k", [(256, 256, 64), (520, 776, 192), (1024, 512, 448)])
+def test_gemm_bf16_large_tiles_give_the_same_bits(al, bl, m, n, k):
+    """The 256x256 configuration (chosen automatically only for very large products) against the 128x128 one and the
+    definition, ragged M and N included."""
+    a, b = rnd(30, m, k), rnd(31, n, k)
+    A = bf(a if al == 0 else a.T.copy())
+    B = bf(b if bl == 0 else b.T.copy())
+    bias = bf(rnd(32, n))
+    c128, c256 = (torch.zeros((m, n), device=DEV, dtype=torch.bfloat16) for _ in range(2))
+    for tile, c in ((128, c128), (256, c256)):
+        S.sif_k_gemm_bf16(A, B, c, m, n, k, A.shape[1], B.shape[1], n, a_layout=al, b_layout=bl, epilogue=S.SIF_EPI_BIAS, bias=bias, tile=tile)
+    assert torch.equal(c128, c256)
+    assert_bf16_close(up(c256), q(a) @ q(b).T + q(rnd(32, n)), f"gemm 256 tiles {al}{bl}")
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16(A, B, c256, m, n, k - 8, A.shape[1], B.shape[1], n, a_layout=al, b_layout=bl, tile=256)
+
+
 def test_gemm_bf16_rejects_bad_arguments():
     A = bf(rnd(12, 16, 16))
     c = torch.zeros((16, 16), device=DEV, dtype=torch.bfloat16)
