@@ -188,29 +188,26 @@ struct DmaStream {
 };
 
 // Epilogue of eight consecutive columns n..n+7 of row m (both inside the result): scale, bias, GELU, GELU' multiply,
-// residual, store; `vec` says that every access may be a 16-byte vector.
-__device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uint32_t m, uint32_t n, float (&v)[8], bool vec) {
+// residual, store; `vec` says that every access may be a 16-byte vector, and then b holds the eight bias values,
+// aux_q the eight auxiliary values (GELU_GRAD) and res_q the eight bf16 residual values.
+__device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uint32_t m, uint32_t n, float (&v)[8], const float (&b)[8], bool vec,
+                                               const uint4& aux_q, const uint4& res_q) {
   const uint32_t epi = p.epi;
   const size_t idx = c_off + (size_t)m * p.ldc + n;
   if (vec) {
-    float b[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (p.bias != nullptr) {
-      const uint4 q = *reinterpret_cast<const uint4*>(p.bias + n);
-      b[0] = bflo(q.x); b[1] = bfhi(q.x); b[2] = bflo(q.y); b[3] = bfhi(q.y); b[4] = bflo(q.z); b[5] = bfhi(q.z); b[6] = bflo(q.w); b[7] = bfhi(q.w);
-    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = v[e] * p.alpha + b[e];
     if (epi & SIF_EPI_GELU) {
       if (p.aux != nullptr)
         *reinterpret_cast<uint4*>(p.aux + idx) = make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+      for (int e = 0; e < 8; ++e) v[e] = gelu_fast(v[e]);
     }
     if (epi & SIF_EPI_GELU_GRAD) {
-      const uint4 q = *reinterpret_cast<const uint4*>(p.aux + idx);
+      const uint4 q = aux_q;                  // fetched before the staging pass
       const float z[8] = {bflo(q.x), bfhi(q.x), bflo(q.y), bfhi(q.y), bflo(q.z), bfhi(q.z), bflo(q.w), bfhi(q.w)};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(z[e]);
+      for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(z[e]);
     }
     if (epi & SIF_EPI_OUT_F32) {
       float* cp = reinterpret_cast<float*>(p.c) + idx;
@@ -223,7 +220,7 @@ __device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uin
       *reinterpret_cast<float4*>(cp + 4) = make_float4(v[4], v[5], v[6], v[7]);
     } else {
       if (epi & SIF_EPI_RESIDUAL) {
-        const uint4 q = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
+        const uint4 q = res_q;                // fetched before the staging pass
         v[0] += bflo(q.x); v[1] += bfhi(q.x); v[2] += bflo(q.y); v[3] += bfhi(q.y); v[4] += bflo(q.z); v[5] += bfhi(q.z); v[6] += bflo(q.w); v[7] += bfhi(q.w);
       }
       *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + idx) =
@@ -235,9 +232,9 @@ __device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uin
       float x = v[e] * p.alpha + (p.bias != nullptr ? bf2f(p.bias[n + e]) : 0.f);
       if (epi & SIF_EPI_GELU) {
         if (p.aux != nullptr) p.aux[idx + e] = f2bf(x);
-        x = gelu_f(x);
+        x = gelu_fast(x);
       }
-      if (epi & SIF_EPI_GELU_GRAD) x *= gelu_grad_f(bf2f(p.aux[idx + e]));
+      if (epi & SIF_EPI_GELU_GRAD) x *= gelu_grad_fast(bf2f(p.aux[idx + e]));
       if (epi & SIF_EPI_OUT_F32) {
         if (epi & SIF_EPI_RESIDUAL) x += reinterpret_cast<const float*>(p.res)[idx + e];
         reinterpret_cast<float*>(p.c)[idx + e] = x;
@@ -294,6 +291,14 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // A lane stores the same eight columns in every pass of the epilogue: their bias is fetched once, here, so that
+    // the main loop hides the latency.
+    uint4 bias_q = make_uint4(0, 0, 0, 0);
+    {
+      const uint32_t n = n0 + wn * WCOLS + (lane & 7) * 8;
+      const size_t c_off0 = (size_t)(bo * p.c_so + bi * p.c_si);
+      if ((p.n & 7) == 0 && (c_off0 & 7) == 0 && p.bias != nullptr && n < p.n) bias_q = *reinterpret_cast<const uint4*>(p.bias + n);
+    }
     // Register prefetch two K steps deep: set[t & 1] carries tile t from global memory to LDS.  While tile t is
     // multiplied out of LDS buffer t & 1, tile t+1 is landing in the other set and the load of tile t+2 is issued
     // into the set tile t has just left, so every global load has two iterations of MFMA work to hide behind.
@@ -374,8 +379,22 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     float* sW = reinterpret_cast<float*>(wave < WM * WN / 2 ? sA0 : sA1) + (wave % (WM * WN / 2)) * (32 * WCOLS);
     const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
     const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
+    const float bias8[8] = {bflo(bias_q.x), bfhi(bias_q.x), bflo(bias_q.y), bfhi(bias_q.y), bflo(bias_q.z), bfhi(bias_q.z), bflo(bias_q.w), bfhi(bias_q.w)};
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
+      // what the epilogue reads from global memory for this pass is requested before the staging, not inside it
+      uint4 aux_q[WCOLS / 16], res_q[WCOLS / 16];
+#pragma unroll
+      for (int it = 0; it < WCOLS / 16; ++it) {
+        const uint32_t ch = lane + it * 64, row = ch >> 3, c8 = ch & 7;
+        const uint32_t m = m0 + wm * (TI * 32) + i * 32 + row, n = n0 + wn * WCOLS + c8 * 8;
+        aux_q[it] = make_uint4(0, 0, 0, 0); res_q[it] = make_uint4(0, 0, 0, 0);
+        if (vec_ok && m < p.m && n < p.n) {
+          const size_t idx = c_off + (size_t)m * p.ldc + n;
+          if (p.epi & SIF_EPI_GELU_GRAD) aux_q[it] = *reinterpret_cast<const uint4*>(p.aux + idx);
+          if ((p.epi & (SIF_EPI_RESIDUAL | SIF_EPI_OUT_F32)) == SIF_EPI_RESIDUAL) res_q[it] = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
+        }
+      }
 #pragma unroll
       for (int j = 0; j < TJ; ++j)
 #pragma unroll
@@ -393,7 +412,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
         const float4 q1 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8 + 1) ^ key) << 2));
         float v[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
         const uint32_t m = m0 + wm * (TI * 32) + i * 32 + row, n = n0 + wn * WCOLS + c8 * 8;
-        if (m < p.m && n < p.n) gemm_epilogue8(p, c_off, m, n, v, vec_ok);
+        if (m < p.m && n < p.n) gemm_epilogue8(p, c_off, m, n, v, bias8, vec_ok, aux_q[it], res_q[it]);
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
