@@ -7,8 +7,8 @@
 //   CUDA Kernel Scheduler               : the monitor thread evaluates Algorithm 1 on Z_c each period and
 //       publishes (tokens, status).  One process, so a pair of atomics replaces the UNIX socket.
 //   Kernel Barrier                      : the barrier thread owns the inference stream.  Offline: forwards queued
-//       kernels while the period's tokens last.  Online: pulls one request at a time while the status is idle
-//       and the predicted rest of the bubble holds it.  Launches are speculative: each kernel re-checks the
+//       kernels while the period's tokens last.  Online: pulls requests in arrival order while the status is
+//       idle and the predicted rest of the bubble holds them.  Launches are speculative: each kernel re-checks the
 //       training stream's state on the device (gate) and the first one that finds it busy poisons the rest of
 //       the window; the barrier then rewinds to that kernel and waits for the next grant.
 #include <algorithm>
