@@ -61,5 +61,12 @@ sif_status launch_reduce_splits(const float* part, void* out, uint64_t n, uint32
 sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c);
 
 uint32_t colsum_parts(uint32_t rows);
+// one set of partial column sums awaiting its finalize: part = nsum consecutive blocks of [parts][n] floats, out[s]
+// (bf16 [n], may be null) receives the s-th sum
+struct FinItem { const float* part; uint16_t* out[3]; uint32_t parts, n, nsum, pad; };
+// one split product awaiting the sum of its K slices: part = splits blocks of n floats, out bf16 [n] (n a multiple of 8)
+struct RedItem { const float* part; uint16_t* out; uint64_t n; uint32_t splits, pad; };
+sif_status launch_reduce_splits_batch(const RedItem* items_dev, uint32_t n_items, uint32_t acc, hipStream_t s, const KCtl& c);
+sif_status launch_fin_batch(const FinItem* items_dev, uint32_t n_items, uint32_t max_n, uint32_t acc, hipStream_t s, const KCtl& c);
 
 }  // namespace sif

@@ -92,7 +92,7 @@ struct G {
 };
 
 // scratch buffers of the backward pass, shared by all layers
-struct Scratch { float* scores; bf16_t* ds; float* delta; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; float* part; float* split; uint64_t split_elems; };
+struct Scratch { float* scores; bf16_t* ds; float* delta; bf16_t *dx_a, *dx_b, *dln, *dqkv, *d_o, *dz; };
 
 static double gemm_cost_us(const sif_gemm_args& g) {
   double flops = 2.0 * g.m * g.n * g.k * g.batch_outer * g.batch_inner;
@@ -159,14 +159,43 @@ static void emit_bubble(Plan& p, int32_t site, uint64_t ns) {
 // Weight gradient dW[m_out, n_out] = A^T B with A stored [tokens][m_out], B stored [tokens][n_out].  The output has few
 // tiles and a long contraction (all tokens), so the contraction is cut into slices that run as a batch and write
 // fp32 partial products, which a second kernel adds in a fixed order: more blocks in flight, same result every run.
-static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t* b, bf16_t* dw, uint32_t m_out, uint32_t n_out,
-                       uint32_t tokens, const Scratch& sc, uint32_t acc) {
+// K slices of a weight-gradient product: few output tiles (d x d .. d x 4d) but a long K (the tokens), so the
+// product is cut along K into `splits` launches-in-one (a batch index) with fp32 partial results, summed afterwards.
+static uint32_t wgrad_splits(uint32_t m_out, uint32_t n_out, uint32_t tokens) {
   const uint32_t tiles = ((m_out + 127) / 128) * ((n_out + 127) / 128);
   uint32_t splits = 1;
-  while (splits < 16 && tiles * splits * 2 <= 512 && tokens % (splits * 2) == 0 && (tokens / (splits * 2)) % 64 == 0 &&
-         (uint64_t)m_out * n_out * splits * 2 <= sc.split_elems)
-    splits *= 2;
-  if (splits == 1 || (n_out & 7)) {
+  while (splits < 16 && tiles * splits * 2 <= 512 && tokens % (splits * 2) == 0 && (tokens / (splits * 2)) % 64 == 0) splits *= 2;
+  return (n_out & 7) ? 1 : splits;
+}
+
+// The partial results of all split products of a backward pass are summed by ONE launch at its end (RedPlan works
+// like FinPlan below: the first pass emitted records the items, later passes reuse the buffers in the same order).
+struct RedPlan {
+  float* pool = nullptr;
+  uint64_t pool_floats = 0, used = 0;
+  std::vector<RedItem> items;
+  RedItem* dev = nullptr;
+  uint32_t max_items = 0;
+  size_t cursor = 0;
+  bool recorded = false, overflow = false;
+  float* take(uint64_t n, uint32_t splits, bf16_t* out) {
+    if (recorded) {
+      if (cursor >= items.size()) { overflow = true; return pool; }
+      return const_cast<float*>(items[cursor++].part);
+    }
+    if (used + n * splits > pool_floats || items.size() >= max_items) { overflow = true; return pool; }
+    RedItem it;
+    it.part = pool ? pool + used : nullptr; it.out = out; it.n = n; it.splits = splits; it.pad = 0;
+    used += n * splits;
+    items.push_back(it);
+    return const_cast<float*>(it.part);
+  }
+};
+
+static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t* b, bf16_t* dw, uint32_t m_out, uint32_t n_out,
+                       uint32_t tokens, RedPlan& rp, uint32_t acc) {
+  const uint32_t splits = wgrad_splits(m_out, n_out, tokens);
+  if (splits == 1) {
     G g(a, b, dw, m_out, n_out, tokens, m_out, n_out, n_out);
     g.lay(SIF_A_ROW_M, SIF_B_ROW_N);
     if (acc) g.epi(SIF_EPI_RESIDUAL, nullptr, dw);      // micro-batch accumulation: add to the stored gradient
@@ -174,24 +203,72 @@ static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t*
     return;
   }
   const uint32_t kper = tokens / splits;
-  emit_gemm(p, name, G(a, b, sc.split, m_out, n_out, kper, m_out, n_out, n_out).lay(SIF_A_ROW_M, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
+  float* part = rp.take((uint64_t)m_out * n_out, splits, dw);
+  emit_gemm(p, name, G(a, b, part, m_out, n_out, kper, m_out, n_out, n_out).lay(SIF_A_ROW_M, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
                          .batch(splits, 1, (int64_t)kper * m_out, 0, (int64_t)kper * n_out, 0, (int64_t)m_out * n_out, 0));
-  const float* part = sc.split;
-  const uint64_t n = (uint64_t)m_out * n_out;
-  emit(p, name, bytes_cost_us(4.0 * n * splits), [=](hipStream_t s, const KCtl& c) { return launch_reduce_splits(part, dw, n, splits, acc, s, c); });
 }
 
-static void emit_colsum(Plan& p, const char* name, const void* x, uint32_t ld, void* out, float* part, uint32_t rows, uint32_t n, uint32_t acc) {
+// Column sums (bias gradients) and the LayerNorm parameter gradients are computed as per-block partial sums by
+// the kernel that reads the rows, and finalized by ONE launch at the end of a backward pass instead of one small
+// launch each (49 per step of the 12-layer decoder).  FinPlan hands every producer its own partial buffer and
+// collects what the batched finalize has to do.  The first backward pass that is emitted records the items; the
+// passes emitted after it (further micro-batches) find the same producers in the same order and reuse the buffers.
+struct FinPlan {
+  float* pool = nullptr;          // partial sums of one backward pass
+  uint64_t pool_floats = 0, used = 0;
+  std::vector<FinItem> items;
+  FinItem* dev = nullptr;         // the items on the device (uploaded when the plan is complete)
+  uint32_t max_items = 0, max_n = 0;
+  size_t cursor = 0;
+  bool open = false, recorded = false, overflow = false;
+  void begin() { open = true; cursor = 0; }
+  // partial buffer for a producer of `nsum` sums over `n` columns
+  float* take(uint32_t parts, uint32_t n, uint32_t nsum, bf16_t* o0, bf16_t* o1, bf16_t* o2) {
+    if (recorded) {
+      if (cursor >= items.size()) { overflow = true; return pool; }
+      return const_cast<float*>(items[cursor++].part);
+    }
+    const uint64_t need = (uint64_t)parts * n * nsum;
+    if (used + need > pool_floats || items.size() >= max_items) { overflow = true; return pool; }
+    FinItem it;
+    it.part = pool ? pool + used : nullptr; it.out[0] = o0; it.out[1] = o1; it.out[2] = o2;
+    it.parts = parts; it.n = n; it.nsum = nsum; it.pad = 0;
+    used += need;
+    if (n > max_n) max_n = n;
+    items.push_back(it);
+    return const_cast<float*>(it.part);
+  }
+};
+
+static void emit_colsum(Plan& p, const char* name, const void* x, uint32_t ld, void* out, FinPlan& fp, uint32_t rows, uint32_t n) {
+  float* part = fp.take(colsum_parts(rows), n, 1, (bf16_t*)out, nullptr, nullptr);
   emit(p, name, bytes_cost_us(2.0 * rows * n), [=](hipStream_t s, const KCtl& c) { return launch_colsum_part(x, ld, part, rows, n, s, c); });
-  emit(p, name, 3.0, [=](hipStream_t s, const KCtl& c) { return launch_colsum_fin(part, out, rows, n, acc, s, c); });
 }
 
 // dsum (may be null): gradient of the bias whose upstream gradient is this LayerNorm backward's output dx
 static void emit_ln_bwd(Plan& p, const void* dy, const void* x, const void* g, const float* mean, const float* rstd, const void* res,
-                        void* dx, void* dg, void* db, void* dsum, float* part, uint32_t rows, uint32_t d, uint32_t acc) {
+                        void* dx, void* dg, void* db, void* dsum, FinPlan& fp, uint32_t rows, uint32_t d) {
   const uint32_t ws = dsum != nullptr;
+  float* part = fp.take(colsum_parts(rows), d, ws ? 3 : 2, (bf16_t*)dg, (bf16_t*)db, (bf16_t*)dsum);
   emit(p, "ln_bwd", bytes_cost_us(8.0 * rows * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, ws, s, c); });
-  emit(p, "ln_bwd_fin", 3.0, [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_fin(part, dg, db, dsum, rows, d, acc, s, c); });
+}
+
+// the one finalize launch of a backward pass; acc: add to the stored gradients (micro-batch accumulation)
+static void emit_fin_batch(Plan& p, FinPlan& fp, RedPlan& rp, uint32_t acc) {
+  const FinItem* dev = fp.dev;
+  const uint32_t n_items = (uint32_t)fp.items.size(), max_n = fp.max_n;
+  emit(p, "grad_fin", 10.0, [=](hipStream_t s, const KCtl& c) { return launch_fin_batch(dev, n_items, max_n, acc, s, c); });
+  fp.recorded = true;
+  fp.open = false;
+  if (!rp.items.empty()) {
+    const RedItem* rdev = rp.dev;
+    const uint32_t rn = (uint32_t)rp.items.size();
+    double bytes = 0;
+    for (const RedItem& it : rp.items) bytes += 4.0 * it.n * it.splits + 2.0 * it.n;
+    emit(p, "wgrad_sum", bytes_cost_us(bytes), [=](hipStream_t s, const KCtl& c) { return launch_reduce_splits_batch(rdev, rn, acc, s, c); });
+  }
+  rp.recorded = true;
+  rp.cursor = 0;
 }
 
 // ------------------------------------------------------------------------------------------ transformer block
@@ -287,17 +364,17 @@ static void emit_decoder_layer_fwd(Plan& p, const Dims& q, const LayerW& w, cons
 // db_proj_below: where this layer's last kernel puts the b_proj gradient of the layer below (null: none).
 static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, const LayerG& g, const bf16_t* x_in, const LayerActs& a,
                                    const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp, uint32_t acc,
-                                   bool have_db_proj, bf16_t* db_proj_below) {
+                                   bool have_db_proj, bf16_t* db_proj_below, FinPlan& fp, RedPlan& rp) {
   const uint32_t M = q.M, d = q.d, f = q.f, da = q.da;
-  if (!have_db_proj) emit_colsum(p, "db_proj", dx_out, d, g.b_proj, sc.part, M, d, acc);
-  emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, sc, acc);
+  if (!have_db_proj) emit_colsum(p, "db_proj", dx_out, d, g.b_proj, fp, M, d);
+  emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, rp, acc);
   emit_gemm(p, "dz", G(dx_out, w.w_proj, sc.dz, M, f, d, d, f, f).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_GELU_GRAD, nullptr, nullptr, a.z));
-  emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, sc.part, M, f, acc);
-  emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, sc, acc);
+  emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, fp, M, f);
+  emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, rp, acc);
   emit_gemm(p, "dln2", G(sc.dz, w.w_fc, sc.dln, M, d, f, f, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
-  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, g.b_o, sc.part, M, d, acc);
-  emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, sc, acc);
+  emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, g.b_o, fp, M, d);
+  emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, rp, acc);
   emit_gemm(p, "do", G(dx_mid, w.w_o, sc.d_o, M, da, d, d, da, da).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (fused_attention(q.dh)) {
     const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh;
@@ -310,11 +387,11 @@ static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, cons
   } else {
     emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
   }
-  emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, sc.part, M, 3 * da, acc);
-  emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, sc, acc);
+  emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, fp, M, 3 * da);
+  emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, rp, acc);
   emit_gemm(p, "dln1", G(sc.dqkv, w.w_qkv, sc.dln, M, d, 3 * da, 3 * da, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
-  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, db_proj_below, sc.part, M, d, acc);
+  emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, db_proj_below, fp, M, d);
 }
 
 // ------------------------------------------------------------------------------------------ training models
@@ -392,11 +469,23 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   sc.dx_a = (bf16_t*)ar.take((uint64_t)M * d * 2); sc.dx_b = (bf16_t*)ar.take((uint64_t)M * d * 2);
   sc.dln = (bf16_t*)ar.take((uint64_t)M * d * 2); sc.dqkv = (bf16_t*)ar.take((uint64_t)M * 3 * q.da * 2);
   sc.d_o = (bf16_t*)ar.take((uint64_t)M * q.da * 2); sc.dz = (bf16_t*)ar.take((uint64_t)M * q.f * 2);
-  uint32_t widest = d > 3 * q.da ? d : 3 * q.da;
-  if (q.f > widest) widest = q.f;
-  sc.part = (float*)ar.take((uint64_t)3 * colsum_parts(M) * widest * 4);
-  sc.split_elems = (uint64_t)16 * 128 * 128 * 64;      // room for 512 tiles of 128x128 partial sums
-  sc.split = (float*)ar.take(sc.split_elems * 4);
+  // partial sums of one backward pass: per layer two LayerNorm backwards (three sums over d each), the fc and qkv
+  // bias gradients, and one more LayerNorm backward (final LayerNorm) or column sum (top of a stack)
+  FinPlan fp;
+  fp.max_items = 4 * s.n_layers + 2;
+  fp.pool_floats = (uint64_t)colsum_parts(M) * ((uint64_t)s.n_layers * (6 * d + q.f + 3 * q.da) + 3 * d);
+  fp.pool = (float*)ar.take(fp.pool_floats * 4);
+  fp.dev = (FinItem*)ar.take((uint64_t)fp.max_items * sizeof(FinItem));
+  RedPlan rp;
+  rp.max_items = 4 * s.n_layers;
+  {
+    const uint32_t da = q.da, f = q.f;
+    const uint64_t per_layer = (uint64_t)d * f * wgrad_splits(d, f, M) + (uint64_t)f * d * wgrad_splits(f, d, M) +
+                               (uint64_t)d * da * wgrad_splits(d, da, M) + (uint64_t)3 * da * d * wgrad_splits(3 * da, d, M);
+    rp.pool_floats = per_layer * s.n_layers;
+  }
+  rp.pool = (float*)ar.take(rp.pool_floats * 4);
+  rp.dev = (RedItem*)ar.take((uint64_t)rp.max_items * sizeof(RedItem));
   bf16_t *lnf = nullptr, *logits = nullptr, *y_all = nullptr, *dx_all = nullptr;
   float *mf = nullptr, *rf = nullptr, *loss_tok = nullptr, *loss = nullptr;
   if (s.vocab) {
@@ -469,6 +558,8 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   // backward pass of micro-batch k; acc != 0 adds the parameter gradients to the stored ones
   auto emit_backward = [&](Plan& p, uint32_t k, uint32_t acc, const bf16_t* dx_top) {
     const uint32_t sl = k % n_slots;
+    if (!fp.open) fp.begin();
+    rp.cursor = 0;
     const bf16_t* dx = dx_top;
     if (!s.vocab) {
       // top of a stack: the upstream gradient comes from the caller
@@ -483,9 +574,10 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       const bf16_t* xin_l = (l == 0) ? x0[sl] : acts[sl][l - 1].x_out;
       const bool have_db_proj = s.vocab != 0 || l + 1 < (int32_t)s.n_layers;     // the final LayerNorm or the layer above wrote it
       bf16_t* below = l > 0 ? grads + pm.at(L((uint32_t)l - 1, "b_proj")) : nullptr;
-      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc, have_db_proj, below);
+      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc, have_db_proj, below, fp, rp);
       dx = sc.dx_a;
     }
+    emit_fin_batch(p, fp, rp, acc);
     if (pp) {
       bf16_t* dst = dx_all + (size_t)k * M * d;
       const bf16_t* src = sc.dx_a;
@@ -509,8 +601,9 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
       emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
       emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+      fp.begin();                  // the final LayerNorm's gradients are finalized with the layers'
       emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"),
-                  grads + pm.at(L(s.n_layers - 1, "b_proj")), sc.part, M, d, 0);
+                  grads + pm.at(L(s.n_layers - 1, "b_proj")), fp, M, d);
       dx = sc.dx_a;
     }
     emit_backward(p, 0, 0, dx);
@@ -560,6 +653,15 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     }
     for (; b < n_micro; ++b) { gap_before(1, (int32_t)b); emit_backward(p, b, b > 0, nullptr); }
     gap_before(2, -1);
+  }
+  if (fp.overflow || rp.overflow) return fail(SIF_E_INVAL, "training plan: a partial-result pool does not match the plan");
+  if (!rp.items.empty()) {
+    hipError_t e = hipMemcpy(rp.dev, rp.items.data(), rp.items.size() * sizeof(RedItem), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, "training plan: upload of the split-product table");
+  }
+  if (!fp.items.empty()) {
+    hipError_t e = hipMemcpy(fp.dev, fp.items.data(), fp.items.size() * sizeof(FinItem), hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, "training plan: upload of the finalize table");
   }
   const uint64_t n = pm.n;
   const float lr = tm.desc.lr;

@@ -250,6 +250,24 @@ __global__ __launch_bounds__(1024) void colsum_fin_kernel(const float* __restric
   kernel_end(ctl, true);
 }
 
+// Finalize of many partial-sum sets in one launch (all the bias and LayerNorm parameter gradients of a backward
+// pass): grid (column blocks of 64, items); item i sums its `parts` partial rows per column for each of its nsum
+// outputs, in the same fixed order as the single kernels above.
+__global__ __launch_bounds__(1024) void fin_batch_kernel(const FinItem* __restrict__ items, uint32_t acc, KCtl ctl) {
+  __shared__ float sm[1024];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const FinItem it = items[blockIdx.y];
+  if (blockIdx.x * 64 < it.n) {                       // uniform over the block
+    const uint32_t c = blockIdx.x * 64 + (threadIdx.x & 63);
+    for (uint32_t s = 0; s < it.nsum; ++s) {
+      const float t = fin_column(it.part + (size_t)s * it.parts * it.n, it.parts, it.n, c, sm);
+      bf16_t* out = it.out[s];
+      if (threadIdx.x < 64 && c < it.n && out != nullptr) out[c] = f2bf(acc ? bf2f(out[c]) + t : t);
+    }
+  }
+  kernel_end(ctl, true);
+}
+
 __global__ __launch_bounds__(256) void colsum_f32_kernel(const float* __restrict__ x, uint32_t ld, float* __restrict__ out,
                                                          uint32_t rows, uint32_t n, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
@@ -548,6 +566,24 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
   kernel_end(ctl, true);
 }
 
+// The same for all split products of a backward pass in one launch: grid (blocks, items).
+__global__ __launch_bounds__(256) void reduce_splits_batch_kernel(const RedItem* __restrict__ items, uint32_t acc, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const RedItem it = items[blockIdx.y];
+  const uint64_t nv = it.n >> 3;
+  for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < nv; v += (uint64_t)gridDim.x * 256) {
+    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (acc) unpack8(reinterpret_cast<const uint4*>(it.out)[v], a);
+    for (uint32_t s = 0; s < it.splits; ++s) {
+      const float4* ps = reinterpret_cast<const float4*>(it.part + (size_t)s * it.n);
+      const float4 x0 = ps[2 * v], x1 = ps[2 * v + 1];
+      a[0] += x0.x; a[1] += x0.y; a[2] += x0.z; a[3] += x0.w; a[4] += x1.x; a[5] += x1.y; a[6] += x1.z; a[7] += x1.w;
+    }
+    reinterpret_cast<uint4*>(it.out)[v] = pack8(a);
+  }
+  kernel_end(ctl, true);
+}
+
 // ---------------------------------------------------------------------------------------------- launchers
 static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 #define REQ(cond, msg) do { if (!(cond)) return fail(SIF_E_INVAL, msg); } while (0)
@@ -597,6 +633,12 @@ sif_status launch_colsum_fin(const float* part, void* out, uint32_t rows, uint32
   REQ(part && out, "colsum_fin: null");
   hipLaunchKernelGGL(colsum_fin_kernel, dim3((n + 63) / 64), dim3(1024), 0, s, part, (bf16_t*)out, colsum_parts(rows), n, acc, c);
   return check_launch("colsum_fin");
+}
+
+sif_status launch_fin_batch(const FinItem* items_dev, uint32_t n_items, uint32_t max_n, uint32_t acc, hipStream_t s, const KCtl& c) {
+  REQ(items_dev && n_items > 0 && n_items <= 65535 && max_n > 0, "fin_batch: bad arguments");
+  hipLaunchKernelGGL(fin_batch_kernel, dim3((max_n + 63) / 64, n_items), dim3(1024), 0, s, items_dev, acc, c);
+  return check_launch("fin_batch");
 }
 
 sif_status launch_colsum_f32(const float* x, uint32_t ld, float* out, uint32_t rows, uint32_t n, hipStream_t s, const KCtl& c) {
@@ -701,6 +743,12 @@ sif_status launch_reduce_splits(const float* part, void* out, uint64_t n, uint32
   REQ(part && out && n > 0 && splits > 0 && (n & 7) == 0 && al16(part) && al16(out), "reduce_splits: bad arguments");
   hipLaunchKernelGGL(reduce_splits_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, part, (bf16_t*)out, n, splits, acc, c);
   return check_launch("reduce_splits");
+}
+
+sif_status launch_reduce_splits_batch(const RedItem* items_dev, uint32_t n_items, uint32_t acc, hipStream_t s, const KCtl& c) {
+  REQ(items_dev && n_items > 0 && n_items <= 65535, "reduce_splits_batch: bad arguments");
+  hipLaunchKernelGGL(reduce_splits_batch_kernel, dim3(128, n_items), dim3(256), 0, s, items_dev, acc, c);
+  return check_launch("reduce_splits_batch");
 }
 
 sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c) {
