@@ -398,8 +398,10 @@ sif_status sif_poll_stats(sif_ctx* ctx, sif_stats* out);
 /* Zeroes the accumulating counters (between measurement phases); requires both streams idle. */
 sif_status sif_reset_stats(sif_ctx* ctx);
 
-/* Event timing of the bf16 GEMM launches, for roofline reporting.  While on, every GEMM launch of both streams
- * is bracketed by two HIP events on its own stream (at most 16384 launches per switch-on).  sif_profile_read (profiling switched off first; synchronises both streams)
+/* Event timing of the bf16 GEMM launches, for roofline reporting.  While on (on = 1: every GEMM launch of both
+ * streams; on = 2: only the variant with both operands K-contiguous, a_layout = b_layout = 0, so that a timed region
+ * carries fewer event records) a launch is bracketed by two HIP events on its own stream (at most 16384 launches per
+ * switch-on).  sif_profile_read (profiling switched off first; synchronises both streams)
  * returns per layout variant v = a_layout*2 + b_layout the number of timed launches, their algorithmic
  * floating-point operations (2mnk per batch; the lower triangle only for causal products) and the sum of their
  * event-to-event times in seconds.  Inference launches that the device gate skipped are left out. */

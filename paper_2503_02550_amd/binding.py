@@ -412,7 +412,7 @@ _sig("sif_profile_read", i32, vp, P(u64), P(C.c_double), P(C.c_double))
 
 
 def sif_profile_gemm(ctx, on):
-    return check(lib.sif_profile_gemm(ctx, 1 if on else 0))
+    return check(lib.sif_profile_gemm(ctx, int(on)))
 
 
 def sif_profile_read(ctx):

@@ -77,7 +77,7 @@ struct sif_ctx {
   uint64_t step_solo_ns = 0;
 
   // optional event timing of the GEMM launches (sif_profile_gemm)
-  std::atomic<bool> prof_on{false};
+  std::atomic<uint32_t> prof_on{0};        // 0 off, 1 every GEMM launch, 2 only the variant with both operands K-contiguous
   std::vector<hipEvent_t> prof_ev;      // 2 per timed launch
   std::vector<int32_t> prof_class;
   std::vector<double> prof_flops;
@@ -101,7 +101,8 @@ constexpr uint32_t kProfMax = 16384;
 
 // Launches one op; when GEMM profiling is on, brackets it with two events on its own stream.
 static sif_status launch_op(sif_ctx* c, Op& op, hipStream_t s, const KCtl& k) {
-  if (op.prof_class >= 0 && c->prof_on.load(std::memory_order_relaxed)) {
+  const uint32_t prof_mode = c->prof_on.load(std::memory_order_relaxed);
+  if (op.prof_class >= 0 && (prof_mode == 1 || (prof_mode == 2 && op.prof_class == 0))) {
     const uint32_t i = c->prof_n.fetch_add(1, std::memory_order_relaxed);
     if (i < kProfMax) {
       c->prof_class[i] = op.prof_class;
@@ -761,7 +762,7 @@ sif_status sif_profile_gemm(sif_ctx* c, uint32_t on) {
     c->prof_kseq.assign(kProfMax, 0);
   }
   if (on) c->prof_n.store(0);
-  c->prof_on.store(on != 0);
+  c->prof_on.store(on > 2 ? 1u : on);
   return SIF_OK;
 }
 
