@@ -54,7 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--coalesce", type=int, default=4, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
-    ap.add_argument("--online-requests", type=int, default=1000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
+    ap.add_argument("--online-requests", type=int, default=2000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--allow-serial-streams", action="store_true", help="for runs under a counter-collecting profiler, which serialises all kernels")
     ap.add_argument("--small", action="store_true", help="reduced shapes (development only; not a valid measurement)")
     args = ap.parse_args()
@@ -111,6 +111,18 @@ def main():
         solo_s = time.perf_counter() - t0
         S.sif_profile_gemm(s.ctx, 0)
 
+        # collocation switched on with nothing to run: what the monitor and barrier threads cost the training step
+        S.sif_set_collocate(s.ctx, 1)
+        run_steps(W)
+        s.sync()
+        S.sif_profile_gemm(s.ctx, 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(K)
+        s.sync()
+        idle_s = time.perf_counter() - t0
+        S.sif_profile_gemm(s.ctx, 0)
+
         # collocated: offline batches queued ahead, released into the bubbles
         S.sif_reset_stats(s.ctx)
         S.sif_set_collocate(s.ctx, 1)
@@ -129,6 +141,23 @@ def main():
         st1 = s.stats()
         S.sif_profile_gemm(s.ctx, 0)
         prof = S.sif_profile_read(s.ctx)
+        # scheduler latencies from the device trace of the timed steps: bubble start -> first inference kernel start,
+        # bubble end -> end of the last inference kernel that began inside it (how far it runs into training time)
+        tr_t, tr_i = S.sif_read_trace(s.ctx, 0), S.sif_read_trace(s.ctx, 1)
+        bub = [(a, b) for kind, _, _, _, a, b in tr_t if kind == 3][-K:]
+        ran = sorted((a, b) for kind, _, dec_, _, a, b in tr_i if kind == 2 and dec_ == 1)
+        first_us, over_us = [], []
+        import bisect
+        starts = [a for a, _ in ran]
+        for b0, b1 in bub:
+            lo, hi = bisect.bisect_left(starts, b0), bisect.bisect_right(starts, b1)
+            if hi > lo:
+                first_us.append((ran[lo][0] - b0) / 1e3)
+                over_us.append(max(0.0, (max(e for _, e in ran[lo:hi]) - b1) / 1e3))
+        sched = {"bubbles": len(bub), "bubbles_with_inference": len(first_us),
+                 "first_kernel_after_bubble_start_us_p50": float(np.median(first_us)) if first_us else None,
+                 "overrun_past_bubble_end_us_p50": float(np.median(over_us)) if over_us else None,
+                 "overrun_past_bubble_end_us_max": float(max(over_us)) if over_us else None}
         # all four GEMM variants, over a few more (untimed) collocated steps
         S.sif_profile_gemm(s.ctx, 1)
         run_steps(3)
@@ -216,6 +245,9 @@ def main():
         "bubble_ms_per_step": bubble_ns / 1e6 / K,
         "inference_batches": int(st1.offline_batches - st0.offline_batches),
         "kernels_run": int(st1.kernels_run - st0.kernels_run), "kernels_skipped": int(st1.kernels_skipped - st0.kernels_skipped),
+        "gate_violations": int(st1.gate_violations),
+        "collocated_idle_overhead": (idle_s - solo_s) / solo_s,      # collocation on, nothing queued, against solo
+        "scheduler_latency": sched,
         "online_p95_ms": online[f"{Y.ONLINE['rate_per_s']:g}_req_per_s"]["p95_ms"] if online else None,
         "online": online,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
