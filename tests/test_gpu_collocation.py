@@ -254,3 +254,61 @@ def test_online_requests_are_pulled_one_at_a_time_inside_bubbles():
             s.wait(s.submit_online(m, I, out, int(seqs[i])))
             assert torch.equal(out, outs[i])
             assert_bf16_close(up(outs[i]), OE.encoder_forward(w, idn, enc, "bf16"), "online request", elem_slack=1.5e-2)
+
+
+def test_online_requests_take_priority_and_offline_batches_fill_the_rest():
+    """Both kinds of inference instance on one GPU: queued online requests are served before the offline backlog, the
+    offline batches use what the online load leaves of the bubbles, and every output has the bits of a solo run."""
+    enc_on = dict(ENC, batch=1, seq=64)
+    shape, off_shape, on_shape = decoder_shape(DEC), encoder_shape(ENC), encoder_shape(enc_on)
+    m_off, m_on = Y.encoder_params(2, ENC, perturb=True), Y.encoder_params(8, enc_on, perturb=True)
+    n_off, n_on = 16, 6
+    cfg = S.sif_default_config()
+    cfg.collocate = 0
+    with Session(cfg) as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=1_500_000)
+        h_off = s.register_inference(off_shape, P.pack(off_shape, m_off))
+        h_on = s.register_inference(on_shape, P.pack(on_shape, m_on), online=True)
+        S.sif_calibrate(s.ctx, 2)
+        n_cal = last_launch(s)
+        ids_off = [i32(Y.token_ids(300 + i, ENC["batch"], ENC["seq"], ENC["vocab"])) for i in range(n_off)]
+        out_off = [torch.zeros((ENC["batch"], ENC["seq"], ENC["d_model"]), device=DEV, dtype=torch.bfloat16) for _ in range(n_off)]
+        seqs = [64, 17, 40, 64, 5, 33]
+        ids_on = [i32(Y.token_ids(400 + i, 1, seqs[i], ENC["vocab"])) for i in range(n_on)]
+        out_on = [torch.zeros((1, seqs[i], ENC["d_model"]), device=DEV, dtype=torch.bfloat16) for i in range(n_on)]
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        torch.cuda.synchronize()
+        tk = [s.submit_offline(h_off, ids_off[i], out_off[i], ENC["batch"], ENC["seq"]) for i in range(n_off)]     # the backlog comes first
+        tk += [s.submit_online(h_on, ids_on[i], out_on[i], seqs[i]) for i in range(n_on)]
+        S.sif_set_collocate(s.ctx, 1)
+        online_done_at, offline_done_at = None, None
+        for step in range(60):
+            s.step(x, t)
+            s.sync()
+            st = s.stats()
+            if online_done_at is None and st.online_done == n_on:
+                online_done_at = (step, st.offline_batches)
+            if offline_done_at is None and st.offline_batches == n_off:
+                offline_done_at = step
+            if online_done_at is not None and offline_done_at is not None:
+                break
+        for k in tk:
+            s.wait(k, 20.0)
+        assert online_done_at is not None and offline_done_at is not None
+        assert online_done_at[1] < n_off, "the online requests waited for the whole offline backlog"
+        bubbles, ran, skipped = bubbles_and_kernels(s, n_cal)
+        assert_starts_inside_bubbles(bubbles, ran)
+        assert s.stats().gate_violations == 0
+    with Session() as s:
+        h_off = s.register_inference(off_shape, P.pack(off_shape, m_off))
+        h_on = s.register_inference(on_shape, P.pack(on_shape, m_on), online=True)
+        for i in (0, n_off - 1):
+            out = torch.zeros_like(out_off[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(h_off, ids_off[i], out, ENC["batch"], ENC["seq"]))
+            assert torch.equal(out, out_off[i])
+        for i in range(n_on):
+            out = torch.zeros_like(out_on[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_online(h_on, ids_on[i], out, seqs[i]))
+            assert torch.equal(out, out_on[i])
