@@ -56,7 +56,9 @@ struct sif_ctx {
   // jobs
   std::mutex mu;
   std::condition_variable cv;
-  std::deque<Job*> offline_q, online_q;
+  std::deque<Job*> online_q;
+  std::vector<std::deque<Job*>> offline_q;      // one FIFO per inference instance (indexed like models)
+  size_t offline_queued = 0;
   std::unordered_map<sif_ticket, std::unique_ptr<Job>> jobs;
   sif_ticket next_ticket = 1;
   std::vector<uint64_t> latencies;
@@ -66,7 +68,9 @@ struct sif_ctx {
   std::deque<InFlight> inflight;
   std::deque<Job*> run_online, run_offline;
   std::vector<std::unique_ptr<Job>> groups;      // coalesced jobs in flight (guarded by mu)
-  uint64_t balance = 0, outstanding_us = 0, last_period = 0;
+  std::vector<uint64_t> balance;                 // per offline instance: what is left of the period's grant
+  size_t rr_next = 0;                            // instance the next offline kernel is looked for first
+  uint64_t outstanding_us = 0, last_period = 0;
   bool awaiting_reset = false;
   bool hold = false;                   // after a skipped launch: release nothing until a new bubble begins
   uint32_t hold_seq = 0;
@@ -248,7 +252,7 @@ static void barrier_main(sif_ctx* c) {
       }
       c->outstanding_us = 0;
       for (const InFlight& f : c->inflight) c->outstanding_us += (uint64_t)f.job->plan[f.op].cost_us;
-      c->balance = 0;
+      std::fill(c->balance.begin(), c->balance.end(), 0);
       launch_reset_skip(c->I.stream, c->I.rec, c->mir, ++c->reset_epoch);
       c->awaiting_reset = true;
       progressed = true;
@@ -259,7 +263,8 @@ static void barrier_main(sif_ctx* c) {
     }
     // 3. a new period: the grant replaces the balance
     const uint64_t pn = c->period_no.load(std::memory_order_acquire);
-    if (pn != c->last_period) { c->last_period = pn; c->balance = c->grant.load(std::memory_order_relaxed); }
+    // (the grant is already the per-instance share pool / m of Algorithm 1; every offline instance gets it)
+    if (pn != c->last_period) { c->last_period = pn; std::fill(c->balance.begin(), c->balance.end(), c->grant.load(std::memory_order_relaxed)); }
     if (c->hold && (!gated || mload(&c->mir->idle_seq) != c->hold_seq)) c->hold = false;
     // 4. admit jobs
     if ((c->collocate.load(std::memory_order_relaxed) && !c->hold) || !gated) {
@@ -278,35 +283,42 @@ static void barrier_main(sif_ctx* c) {
           c->online_q.pop_front();
           c->run_online.push_back(j);
         }
-        while (!c->offline_q.empty() && c->run_offline.size() < 4) {
-          Job* j = c->offline_q.front();
-          c->offline_q.pop_front();
-          // requests of equal shape that are queued behind it join it (never waited for)
-          const InferModel& im = *c->models[j->model];
-          std::vector<Job*> parts{j};
-          while (parts.size() < infer_coalesce(im.desc) && !c->offline_q.empty()) {
-            Job* n = c->offline_q.front();
-            if (n->model != j->model || n->batch != j->batch || n->seq != j->seq) break;
-            c->offline_q.pop_front();
-            parts.push_back(n);
-          }
-          if (parts.size() > 1) {
-            std::unique_ptr<Job> g(new Job());
-            g->ticket = j->ticket; g->model = j->model; g->batch = j->batch * (uint32_t)parts.size(); g->seq = j->seq;
-            g->t_arrival_ns = j->t_arrival_ns;
-            InferIO io[4];
-            for (size_t r = 0; r < parts.size(); ++r) io[r] = InferIO{parts[r]->in_dev, parts[r]->out_dev};
-            if (build_infer_plan(im, io, (uint32_t)parts.size(), j->batch, j->seq, c->cfg.kernel_us_max, g->plan) == SIF_OK) {
-              g->parts = parts;
-              apply_calibration(im, *g);
-              for (Job* p : parts) p->plan.clear();
-              c->run_offline.push_back(g.get());
-              c->groups.push_back(std::move(g));
-              continue;
+        // at most two jobs per offline instance are admitted at a time, so that no instance's backlog keeps another out
+        for (size_t mdl = 0; mdl < c->offline_q.size(); ++mdl) {
+          std::deque<Job*>& oq = c->offline_q[mdl];
+          auto admitted = [&] { size_t n = 0; for (Job* q : c->run_offline) n += (size_t)q->model == mdl; return n; };
+          while (!oq.empty() && admitted() < 2) {
+            Job* j = oq.front();
+            oq.pop_front();
+            --c->offline_queued;
+            // requests of equal shape that are queued behind it join it (never waited for)
+            const InferModel& im = *c->models[j->model];
+            std::vector<Job*> parts{j};
+            while (parts.size() < infer_coalesce(im.desc) && !oq.empty()) {
+              Job* n = oq.front();
+              if (n->batch != j->batch || n->seq != j->seq) break;
+              oq.pop_front();
+              --c->offline_queued;
+              parts.push_back(n);
             }
-            for (size_t r = parts.size(); r-- > 1;) c->offline_q.push_front(parts[r]);      // could not be merged: one by one
+            if (parts.size() > 1) {
+              std::unique_ptr<Job> g(new Job());
+              g->ticket = j->ticket; g->model = j->model; g->batch = j->batch * (uint32_t)parts.size(); g->seq = j->seq;
+              g->t_arrival_ns = j->t_arrival_ns;
+              InferIO io[4];
+              for (size_t r = 0; r < parts.size(); ++r) io[r] = InferIO{parts[r]->in_dev, parts[r]->out_dev};
+              if (build_infer_plan(im, io, (uint32_t)parts.size(), j->batch, j->seq, c->cfg.kernel_us_max, g->plan) == SIF_OK) {
+                g->parts = parts;
+                apply_calibration(im, *g);
+                for (Job* p : parts) p->plan.clear();
+                c->run_offline.push_back(g.get());
+                c->groups.push_back(std::move(g));
+                continue;
+              }
+              for (size_t r = parts.size(); r-- > 1;) { oq.push_front(parts[r]); ++c->offline_queued; }      // could not be merged: one by one
+            }
+            c->run_offline.push_back(j);
           }
-          c->run_offline.push_back(j);
         }
       }
       // 5. release kernels
@@ -317,17 +329,28 @@ static void barrier_main(sif_ctx* c) {
         bool online = false;
         for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
         if (j && gated && c->status.load(std::memory_order_relaxed) != SIF_STATUS_IDLE) j = nullptr;   // online kernels only while idle
-        if (!j) { online = false; for (Job* q : c->run_offline) if (q->next_op < q->plan.size()) { j = q; break; } }
-        if (!j) break;
-        Op& op = j->plan[j->next_op];
         // a kernel predicted longer than the largest possible grant is charged the whole grant, so that the head of
         // the queue can always be forwarded in the stable phase
         const uint64_t cap = std::max<uint64_t>(1, c->cfg.alg1.ul / c->cfg.alg1.m);
-        const uint64_t cost = std::min<uint64_t>((uint64_t)(op.cost_us + 0.999), cap);
-        if (gated) {
-          if (!online && c->balance < cost) break;                              // token rule
-          if (c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
+        auto cost_of = [&](const Job* q) { return std::min<uint64_t>((uint64_t)(q->plan[q->next_op].cost_us + 0.999), cap); };
+        if (!j) {
+          // Offline: every instance spends its own balance, FIFO within the instance (its head kernel blocks the
+          // rest of its queue); the instances take turns, and one that is out of tokens does not hold up the others.
+          online = false;
+          const size_t nm = c->balance.size();
+          for (size_t r = 0; r < nm && !j; ++r) {
+            const size_t mdl = (c->rr_next + r) % nm;
+            for (Job* q : c->run_offline) {
+              if ((size_t)q->model != mdl || q->next_op >= q->plan.size()) continue;
+              if (!gated || c->balance[mdl] >= cost_of(q)) { j = q; c->rr_next = (mdl + 1) % nm; }   // token rule
+              break;
+            }
+          }
         }
+        if (!j) break;
+        Op& op = j->plan[j->next_op];
+        const uint64_t cost = cost_of(j);
+        if (gated && c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
         if (j->next_op + 1 == j->plan.size()) k.flags |= 1u;
@@ -344,7 +367,7 @@ static void barrier_main(sif_ctx* c) {
         c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq)});
         j->next_op++;
         c->outstanding_us += cost;
-        if (gated && !online) c->balance -= cost;
+        if (gated && !online) c->balance[j->model] -= cost;
         progressed = true;
       }
     }
@@ -576,6 +599,11 @@ sif_status sif_register_inference_model(sif_ctx* c, const sif_infer_desc* d, sif
   if (st != SIF_OK) return st;
   HIPCHK(hipStreamSynchronize(c->I.stream), "register_inference_model: synchronize");
   c->models.push_back(std::move(im));
+  {
+    std::lock_guard<std::mutex> lk(c->mu);
+    c->offline_q.emplace_back();
+    c->balance.push_back(0);
+  }
   *out = (sif_handle)(c->models.size() - 1);
   return SIF_OK;
 }
@@ -607,10 +635,11 @@ static sif_status submit(sif_ctx* c, sif_handle model, const void* in_dev, void*
   if (st != SIF_OK) return st;
   apply_calibration(im, *j);
   std::lock_guard<std::mutex> lk(c->mu);
-  if (c->offline_q.size() + c->online_q.size() >= 4096) return fail(SIF_E_AGAIN, "submit: queue full");
+  if (c->offline_queued + c->online_q.size() >= 4096) return fail(SIF_E_AGAIN, "submit: queue full");
   j->ticket = c->next_ticket++;
   *out = j->ticket;
-  (online ? c->online_q : c->offline_q).push_back(j.get());
+  if (online) c->online_q.push_back(j.get());
+  else { c->offline_q[model].push_back(j.get()); ++c->offline_queued; }
   c->jobs[j->ticket] = std::move(j);
   return SIF_OK;
 }

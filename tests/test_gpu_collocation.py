@@ -312,3 +312,53 @@ def test_online_requests_take_priority_and_offline_batches_fill_the_rest():
             torch.cuda.synchronize()
             s.wait(s.submit_online(h_on, ids_on[i], out, seqs[i]))
             assert torch.equal(out, out_on[i])
+
+
+def test_two_offline_instances_share_the_grant_and_neither_starves():
+    """m = 2 inference instances (Algorithm 1 divides the pool by m; Fig. 7's setting): each spends its own share of
+    every grant, so an instance with a short queue is not kept waiting by the other's backlog."""
+    shape, ishape = decoder_shape(DEC), encoder_shape(ENC)
+    masters = [Y.encoder_params(2, ENC, perturb=True), Y.encoder_params(9, ENC, perturb=True)]
+    n_a, n_b = 14, 3
+    cfg = S.sif_default_config()
+    cfg.collocate = 0
+    cfg.alg1.m = 2
+    with Session(cfg) as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=1_500_000)
+        h = [s.register_inference(ishape, P.pack(ishape, m)) for m in masters]
+        S.sif_calibrate(s.ctx, 2)
+        n_cal = last_launch(s)
+        ids = [i32(Y.token_ids(500 + i, ENC["batch"], ENC["seq"], ENC["vocab"])) for i in range(n_a + n_b)]
+        outs = [torch.zeros((ENC["batch"], ENC["seq"], ENC["d_model"]), device=DEV, dtype=torch.bfloat16) for _ in range(n_a + n_b)]
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        torch.cuda.synchronize()
+        tk_a = [s.submit_offline(h[0], ids[i], outs[i], ENC["batch"], ENC["seq"]) for i in range(n_a)]
+        tk_b = [s.submit_offline(h[1], ids[n_a + i], outs[n_a + i], ENC["batch"], ENC["seq"]) for i in range(n_b)]
+        S.sif_set_collocate(s.ctx, 1)
+        b_done_with = None
+        for step in range(80):
+            s.step(x, t)
+            s.sync()
+            while tk_b:                                   # an instance finishes its requests in order
+                try:
+                    s.wait(tk_b[0], 0.0)
+                    tk_b.pop(0)
+                except S.SifError:
+                    break
+            if not tk_b and b_done_with is None:
+                b_done_with = int(s.stats().offline_batches)
+            if s.stats().offline_batches == n_a + n_b:
+                break
+        for k in tk_a:
+            s.wait(k, 20.0)
+        assert b_done_with is not None and b_done_with < n_a + n_b - 2, "the short queue waited for the long one"
+        bubbles, ran, skipped = bubbles_and_kernels(s, n_cal)
+        assert_starts_inside_bubbles(bubbles, ran)
+    for which, rng in ((0, (0, n_a - 1)), (1, (n_a, n_a + n_b - 1))):
+        with Session() as s:
+            hm = s.register_inference(ishape, P.pack(ishape, masters[which]))
+            for i in rng:
+                I, out = i32(Y.token_ids(500 + i, ENC["batch"], ENC["seq"], ENC["vocab"])), torch.zeros_like(outs[i])
+                torch.cuda.synchronize()
+                s.wait(s.submit_offline(hm, I, out, ENC["batch"], ENC["seq"]))
+                assert torch.equal(out, outs[i]), (which, i)
