@@ -361,7 +361,9 @@ uint64_t sif_infer_workspace_bytes(const sif_infer_desc* d);
 sif_status sif_register_inference_model(sif_ctx* ctx, const sif_infer_desc* d, sif_handle* out);
 
 /* Runs the registered models alone (no collocation, gates open) `iters` times to measure per-kernel costs,
- * the solo step time and the bubble lengths; blocks until done.  Returns SIF_W_SLO_RISK if an online model's
+ * the solo step time and the bubble lengths (a pipeline stage registered without pp_tf_ns / pp_tb_ns gets the idle
+ * intervals of its schedule re-sized from the measured forward and backward time of a micro-batch, which needs the
+ * training inputs here); blocks until done.  Returns SIF_W_SLO_RISK if an online model's
  * batch-1 time exceeds the longest bubble (Principle-II). */
 sif_status sif_calibrate(sif_ctx* ctx, uint32_t iters, const void* train_inputs_dev, const void* train_targets_dev);
 

@@ -112,35 +112,6 @@ __device__ __forceinline__ void store_tile(bf16_t* lds, const uint4 (&rin)[4], u
   }
 }
 
-// Interior tiles (all rows inside the operand, K range a whole number of K steps) need no bounds handling at
-// all: the tile's first element is a block-uniform pointer that advances by one K step per load, each thread adds
-// one constant 32-bit offset, and the four vectors of a thread differ by a block-uniform stride, so the address
-// arithmetic stays on the scalar unit and the vector ALU is left to the MFMAs.
-template <int LAYOUT, int THREADS, int ROWS>
-struct InteriorStream {
-  const char* tile;          // first byte of the next tile
-  size_t step, vstride;      // bytes per K step; bytes between a thread's consecutive vectors
-  uint32_t voff;             // this thread's byte offset inside a tile
-  __device__ __forceinline__ InteriorStream(const bf16_t* b, uint32_t ld, uint32_t row0, uint32_t k_begin) {
-    if (LAYOUT == 0) {
-      tile = (const char*)(b + (size_t)row0 * ld + k_begin);
-      step = BK * sizeof(bf16_t);
-      vstride = (size_t)(THREADS / 8) * ld * sizeof(bf16_t);
-      voff = ((threadIdx.x >> 3) * ld + (threadIdx.x & 7) * 8) * (uint32_t)sizeof(bf16_t);
-    } else {
-      tile = (const char*)(b + (size_t)k_begin * ld + row0);
-      step = (size_t)BK * ld * sizeof(bf16_t);
-      vstride = (size_t)(THREADS / (ROWS / 8)) * ld * sizeof(bf16_t);
-      voff = ((threadIdx.x / (ROWS / 8)) * ld + (threadIdx.x % (ROWS / 8)) * 8) * (uint32_t)sizeof(bf16_t);
-    }
-  }
-  __device__ __forceinline__ void next(uint4 (&r)[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r[i] = *reinterpret_cast<const uint4*>(tile + i * vstride + voff);
-    tile += step;
-  }
-};
-
 // Interior tiles go from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, no LDS
 // store instructions).  One such instruction writes the 64 lanes' 16 bytes to consecutive LDS addresses, 1 KB per
 // wavefront, so the lane's position in the tile is fixed and the swizzle is applied to what it fetches: lane l of

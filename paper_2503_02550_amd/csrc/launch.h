@@ -57,7 +57,6 @@ sif_status launch_mse(const float* y, const float* t, float* d, float* loss, uin
 sif_status launch_colsum_f32(const float* x, uint32_t ld, float* out, uint32_t rows, uint32_t n, hipStream_t s,
                              const KCtl& c);
 sif_status launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s, const KCtl& c);
-sif_status launch_reduce_splits(const float* part, void* out, uint64_t n, uint32_t splits, uint32_t acc, hipStream_t s, const KCtl& c);
 sif_status launch_fill_u32(uint32_t* p, uint32_t v, uint64_t n, hipStream_t s, const KCtl& c);
 
 uint32_t colsum_parts(uint32_t rows);

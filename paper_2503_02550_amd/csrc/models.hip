@@ -156,9 +156,7 @@ static void emit_bubble(Plan& p, int32_t site, uint64_t ns) {
   p.push_back(std::move(op));
 }
 
-// Weight gradient dW[m_out, n_out] = A^T B with A stored [tokens][m_out], B stored [tokens][n_out].  The output has few
-// tiles and a long contraction (all tokens), so the contraction is cut into slices that run as a batch and write
-// fp32 partial products, which a second kernel adds in a fixed order: more blocks in flight, same result every run.
+// Weight gradient dW[m_out, n_out] = A^T B with A stored [tokens][m_out], B stored [tokens][n_out].
 // K slices of a weight-gradient product: few output tiles (d x d .. d x 4d) but a long K (the tokens), so the
 // product is cut along K into `splits` launches-in-one (a batch index) with fp32 partial results, summed afterwards.
 static uint32_t wgrad_splits(uint32_t m_out, uint32_t n_out, uint32_t tokens) {
@@ -641,18 +639,20 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       for (int32_t i = 0; i < ng; ++i)
         if (kind[i] == kd && (kd == 2 || index[i] == idx)) {
           emit_bubble(p, next_site++, gap[i]);
+          p.back().pp_kind = kind[i]; p.back().pp_index = index[i];
           if (gap[i] > tm.max_bubble_ns) tm.max_bubble_ns = gap[i];
         }
     };
     const uint32_t warm = std::min(n_micro, tm.desc.pp_stages - 1 - tm.desc.pp_stage);
     uint32_t f = 0, b = 0;
-    for (; f < warm; ++f) { gap_before(0, (int32_t)f); emit_forward(p, f); }
-    while (f < n_micro) {
-      gap_before(0, (int32_t)f); emit_forward(p, f); ++f;
-      gap_before(1, (int32_t)b); emit_backward(p, b, b > 0, nullptr); ++b;
-    }
-    for (; b < n_micro; ++b) { gap_before(1, (int32_t)b); emit_backward(p, b, b > 0, nullptr); }
+    auto mark = [&](size_t from, int32_t pass) { for (size_t i = from; i < p.size(); ++i) p[i].pp_pass = pass; };
+    auto fwd = [&](uint32_t k) { gap_before(0, (int32_t)k); const size_t at = p.size(); emit_forward(p, k); mark(at, 2 * (int32_t)k); };
+    auto bwd = [&](uint32_t k) { gap_before(1, (int32_t)k); const size_t at = p.size(); emit_backward(p, k, k > 0, nullptr); mark(at, 2 * (int32_t)k + 1); };
+    for (; f < warm; ++f) fwd(f);
+    while (f < n_micro) { fwd(f); ++f; bwd(b); ++b; }
+    for (; b < n_micro; ++b) bwd(b);
     gap_before(2, -1);
+    tm.pp_times_estimated = tm.desc.pp_tf_ns == 0 || tm.desc.pp_tb_ns == 0;
   }
   if (fp.overflow || rp.overflow) return fail(SIF_E_INVAL, "training plan: a partial-result pool does not match the plan");
   if (!rp.items.empty()) {

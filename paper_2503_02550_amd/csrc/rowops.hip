@@ -549,24 +549,8 @@ __global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, cons
   kernel_end(ctl, true);
 }
 
-// out[i] = bf16([out[i] +] sum_s part[s][i]) in ascending s: joins the K slices of a split weight-gradient product.
-__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, bf16_t* __restrict__ out, uint64_t n,
-                                                            uint32_t splits, uint32_t acc, KCtl ctl) {
-  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
-  const uint64_t nv = n >> 3;
-  for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < nv; v += (uint64_t)gridDim.x * 256) {
-    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (acc) unpack8(reinterpret_cast<const uint4*>(out)[v], a);       // micro-batch accumulation: start from the stored gradient
-    for (uint32_t s = 0; s < splits; ++s) {
-      const float4 x0 = reinterpret_cast<const float4*>(part + (size_t)s * n)[2 * v], x1 = reinterpret_cast<const float4*>(part + (size_t)s * n)[2 * v + 1];
-      a[0] += x0.x; a[1] += x0.y; a[2] += x0.z; a[3] += x0.w; a[4] += x1.x; a[5] += x1.y; a[6] += x1.z; a[7] += x1.w;
-    }
-    reinterpret_cast<uint4*>(out)[v] = pack8(a);
-  }
-  kernel_end(ctl, true);
-}
-
-// The same for all split products of a backward pass in one launch: grid (blocks, items).
+// out[i] = bf16([out[i] +] sum_s part[s][i]) in ascending s joins the K slices of a split weight-gradient product;
+// all split products of a backward pass are done in one launch: grid (blocks, items).
 __global__ __launch_bounds__(256) void reduce_splits_batch_kernel(const RedItem* __restrict__ items, uint32_t acc, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const RedItem it = items[blockIdx.y];
@@ -737,12 +721,6 @@ sif_status launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s
   REQ(dst && src && bytes > 0 && (bytes & 15) == 0 && al16(dst) && al16(src), "copy: needs 16-byte aligned buffers and size");
   hipLaunchKernelGGL(copy_kernel, dim3(grid_for(bytes >> 4)), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, bytes >> 4, c);
   return check_launch("copy");
-}
-
-sif_status launch_reduce_splits(const float* part, void* out, uint64_t n, uint32_t splits, uint32_t acc, hipStream_t s, const KCtl& c) {
-  REQ(part && out && n > 0 && splits > 0 && (n & 7) == 0 && al16(part) && al16(out), "reduce_splits: bad arguments");
-  hipLaunchKernelGGL(reduce_splits_kernel, dim3(grid_for(n >> 3)), dim3(256), 0, s, part, (bf16_t*)out, n, splits, acc, c);
-  return check_launch("reduce_splits");
 }
 
 sif_status launch_reduce_splits_batch(const RedItem* items_dev, uint32_t n_items, uint32_t acc, hipStream_t s, const KCtl& c) {

@@ -34,6 +34,9 @@ struct Op {
   uint64_t bubble_ns = 0;
   int32_t prof_class = -1;         // >= 0: GEMM layout variant (a_layout*2 + b_layout), timed with events when profiling
   double flops = 0.0;              // algorithmic floating-point operations of the launch
+  // pipeline-stage plans: a kernel belongs to pass 2*micro_batch + (0 forward, 1 backward); a bubble is the idle
+  // interval (pp_kind, pp_index) of the 1F1B schedule (see sif_pp_1f1b_bubbles)
+  int32_t pp_pass = -1, pp_kind = -1, pp_index = 0;
 };
 typedef std::vector<Op> Plan;
 
@@ -62,6 +65,8 @@ struct TrainModel {
   float* cur_loss = nullptr;
   uint64_t max_bubble_ns = 0;
   uint64_t workspace_bytes = 0;
+  std::vector<uint32_t> last_kseq;                  // launch number of each op in the most recent step
+  bool pp_times_estimated = false;                  // pipeline bubbles were sized from the cost model, not from the caller
 };
 
 struct InferModel {

@@ -384,6 +384,7 @@ static sif_status run_step(sif_ctx* c, const void* inputs, const void* targets, 
   KCtl k0 = make_ctl(c, c->T, kKindStep, c->step_no, nullptr, 0);
   sif_status st = launch_step_marker(s, c->T.rec, c->mir, k0.slot, 0, k0.kind_id);
   if (st != SIF_OK) return st;
+  tm.last_kseq.assign(tm.plan.size(), 0);
   for (size_t i = 0; i < tm.plan.size(); ++i) {
     Op& op = tm.plan[i];
     if (op.bubble_site >= 0) {
@@ -394,7 +395,9 @@ static sif_status run_step(sif_ctx* c, const void* inputs, const void* targets, 
       st = launch_bubble(s, c->T.rec, c->mir, kb.slot, seq, (uint32_t)op.bubble_site, ticks, 4 * ticks + c->ns_to_ticks(100000000ull),
                          c->cfg.device_timed_bubbles, kb.kind_id);
     } else {
-      st = launch_op(c, op, s, make_ctl(c, c->T, kKindTrain, (uint32_t)i, nullptr, 0));
+      const KCtl k = make_ctl(c, c->T, kKindTrain, (uint32_t)i, nullptr, 0);
+      tm.last_kseq[i] = k.kseq;
+      st = launch_op(c, op, s, k);
     }
     if (st != SIF_OK) return st;
   }
@@ -677,6 +680,39 @@ sif_status sif_calibrate(sif_ctx* c, uint32_t iters, const void* train_inputs_de
     sif_status st = run_step(c, train_inputs_dev, train_targets_dev, nullptr);
     if (st != SIF_OK) return st;
     HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
+    // A pipeline stage whose per-micro-batch times were not given: take them from the step just run (first to last
+    // kernel of micro-batch 0's forward and backward pass) and size the schedule's idle intervals from them.
+    if (c->train->desc.par_mode == SIF_PAR_PP && c->train->pp_times_estimated) {
+      TrainModel& tm = *c->train;
+      std::vector<Slot> ring(kRingSlots);
+      HIPCHK(hipMemcpy(ring.data(), c->T.ring, (size_t)kRingSlots * sizeof(Slot), hipMemcpyDeviceToHost), "calibrate: read the trace");
+      uint64_t lo[2] = {~0ull, ~0ull}, hi[2] = {0, 0};
+      for (size_t i = 0; i < tm.plan.size(); ++i) {
+        const int32_t pass = tm.plan[i].pp_pass;
+        if (pass != 0 && pass != 1) continue;
+        const Slot& sl = ring[tm.last_kseq[i] % kRingSlots];
+        lo[pass] = std::min(lo[pass], sl.t0); hi[pass] = std::max(hi[pass], sl.t1);
+      }
+      if (hi[0] > lo[0] && hi[1] > lo[1]) {
+        const uint64_t tf = c->ticks_to_ns(hi[0] - lo[0]), tb = c->ticks_to_ns(hi[1] - lo[1]);
+        int32_t kind[64], index[64];
+        uint64_t gap[64];
+        const int32_t ng = sif_pp_1f1b_bubbles(tm.desc.pp_stage, tm.desc.pp_stages, tm.desc.pp_micro, tf, tb, kind, index, gap, 64);
+        if (ng > 0 && ng <= 64) {
+          tm.max_bubble_ns = 0;
+          for (Op& op : tm.plan) {
+            if (op.bubble_site < 0 || op.pp_kind < 0) continue;
+            for (int32_t g = 0; g < ng; ++g)
+              if (kind[g] == op.pp_kind && (op.pp_kind == 2 || index[g] == op.pp_index)) { op.bubble_ns = gap[g]; op.cost_us = gap[g] / 1000.0; }
+            tm.max_bubble_ns = std::max(tm.max_bubble_ns, op.bubble_ns);
+          }
+          tm.pp_times_estimated = false;
+          st = run_step(c, train_inputs_dev, train_targets_dev, nullptr);      // once with the new intervals before timing
+          if (st != SIF_OK) return st;
+          HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
+        }
+      }
+    }
     const uint64_t s0 = mload(&c->mir->step_ticks_sum);
     for (uint32_t i = 0; i < iters; ++i) { st = run_step(c, train_inputs_dev, train_targets_dev, nullptr); if (st != SIF_OK) return st; }
     HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");

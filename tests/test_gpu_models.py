@@ -219,3 +219,34 @@ def test_pipeline_stage_1f1b_step_matches_oracle():
     with pytest.raises(S.SifError):
         with Session() as s:
             s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_PP, pp_stages=4, pp_micro=3, pp_stage=0)
+
+
+def test_pipeline_stage_sizes_its_bubbles_from_measured_pass_times():
+    """Registered without per-micro-batch times, a stage measures them during calibration; its idle intervals then
+    add up to (stages - 1)(t_f + t_b), the textbook total of the 1F1B schedule, with t_f + t_b = compute time / micro-batches."""
+    cfg = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=0, max_pos=0, batch=2, seq=128, causal=True)
+    stages, micro, stage = 4, 6, 1
+    shape = decoder_shape(cfg)
+    master = Y.decoder_params(44, cfg)
+    xs, dys = Y.activations(45, micro, 2, 128, 256), Y.activations(46, micro, 2, 128, 256, scale=0.01)
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_PP, lr=0.01, pp_stages=stages, pp_micro=micro, pp_stage=stage)
+        X, DY = bf(xs), bf(dys)
+        torch.cuda.synchronize()
+        S.sif_calibrate(s.ctx, 2, X, DY)
+        s.step(X, DY)
+        s.sync()
+        tr = [r for r in S.sif_read_trace(s.ctx, 0)]
+        last_step = [i for i, r in enumerate(tr) if r[0] == 4][-2:]                 # the step's begin and end markers
+        recs = tr[last_step[0] + 1:last_step[1]]
+        bubbles = [(t1 - t0) for kind, _, _, _, t0, t1 in recs if kind == 3]
+        span = recs[-1][5] - recs[0][4]
+        compute = span - sum(bubbles)
+        want_total = (stages - 1) * compute / micro
+        assert len(bubbles) == len(OB_bubbles(stage, stages, micro))
+        assert 0.7 * want_total <= sum(bubbles) <= 1.3 * want_total, (sum(bubbles), want_total)
+
+
+def OB_bubbles(stage, stages, micro):
+    from oracle import bubbles as OB
+    return OB.pp_1f1b_bubbles(stage, stages, micro, 1000, 2000)
