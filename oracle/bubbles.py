@@ -73,3 +73,41 @@ def pp_1f1b_bubbles(stage, n_stages, n_micro, t_f_ns, t_b_ns):
     if s > 0:
         out.append((("end", None), s * t_b_ns))
     return out
+
+
+def dp_gradient_buckets(group_bytes, cap_bytes):
+    """Data parallel with bucketed gradient exchange (a reading beyond the configuration's single exposed
+    all-reduce; Sec. 2.1 only says that communication leaves the GPU idle).
+
+    `group_bytes[i]` = gradient bytes that become final together, listed in the order in which backward
+    finalizes them.  Groups are appended to the open bucket; the bucket is closed as soon as it holds at least
+    `cap_bytes` (so a group larger than the cap closes the bucket it joins), and whatever is open at the end
+    forms the last bucket.  Returns a list of buckets, each a list of group indices.
+    """
+    assert cap_bytes > 0
+    buckets, cur, held = [], [], 0
+    for i, b in enumerate(group_bytes):
+        cur.append(i)
+        held += int(b)
+        if held >= cap_bytes:
+            buckets.append(cur)
+            cur, held = [], 0
+    if cur:
+        buckets.append(cur)
+    return buckets
+
+
+def dp_overlapped_wait(ready_ns, dur_ns, end_ns):
+    """Exposed wait of a bucketed all-reduce that runs beside backward.
+
+    Bucket k can be sent once its gradients are final (`ready_ns[k]`) and the bucket before it has been sent (one
+    exchange at a time, in bucket order); sending it takes `dur_ns[k]`.  Backward ends at `end_ns`, and the
+    optimizer has to wait until the last bucket has arrived: the wait is what is left of the exchange then, zero
+    if it is already over.  Integer nanoseconds throughout.
+    """
+    assert len(ready_ns) == len(dur_ns)
+    finish = 0
+    for r, d in zip(ready_ns, dur_ns):
+        start = max(int(r), finish)
+        finish = start + int(d)
+    return max(0, finish - int(end_ns))

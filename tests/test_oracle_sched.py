@@ -3,6 +3,7 @@ forms, and a discrete-event simulation of the 1F1B pipeline written independentl
 import itertools
 import os
 
+import numpy as np
 import pytest
 
 import synth_inputs as S
@@ -145,3 +146,65 @@ def test_pp_closed_form_against_event_simulation(p, m, tf, tb):
             gaps.append((("end", None), t_end - t))
         assert gaps == B.pp_1f1b_bubbles(s, p, m, tf, tb), s
         assert sum(g for _, g in gaps) == (p - 1) * (tf + tb)
+
+
+# ---- bucketed gradient exchange beside backward (data parallel, overlapped)
+def test_dp_buckets_rule():
+    assert B.dp_gradient_buckets([10, 10, 10, 10, 10], 25) == [[0, 1, 2], [3, 4]]
+    assert B.dp_gradient_buckets([10, 10, 10, 10, 10], 20) == [[0, 1], [2, 3], [4]]
+    assert B.dp_gradient_buckets([100, 1, 1], 25) == [[0], [1, 2]]                # an oversized group closes its bucket
+    assert B.dp_gradient_buckets([1, 100, 1], 25) == [[0, 1], [2]]
+    assert B.dp_gradient_buckets([3, 4], 10 ** 9) == [[0, 1]]                     # cap never reached: one bucket
+    assert B.dp_gradient_buckets([], 5) == []
+    for sizes in itertools.product([1, 7, 30], repeat=5):
+        for cap in (1, 8, 25, 64):
+            bk = B.dp_gradient_buckets(list(sizes), cap)
+            assert [i for b in bk for i in b] == list(range(5))                   # a partition that keeps the order
+            for b in bk[:-1]:
+                tot = sum(sizes[i] for i in b)
+                assert tot >= cap and tot - sizes[b[-1]] < cap                    # closed exactly when the cap is reached
+
+
+def simulate_link(ready, dur, end):
+    """Tick-by-tick simulation of one link that sends the buckets in order, one at a time."""
+    t, k, left, busy = 0, 0, 0, False
+    n = len(ready)
+    while k < n:
+        if not busy and ready[k] <= t:
+            busy, left = True, dur[k]
+        if busy and left == 0:
+            busy = False
+            k += 1
+            continue
+        if busy:
+            left -= 1
+        t += 1
+    return max(0, t - end)
+
+
+def test_dp_overlapped_wait_against_tick_simulation_and_closed_forms():
+    rng = np.random.default_rng(77)
+    for _ in range(300):
+        n = int(rng.integers(1, 6))
+        ready = sorted(int(v) for v in rng.integers(0, 40, n))
+        dur = [int(v) for v in rng.integers(0, 15, n)]
+        end = ready[-1] + int(rng.integers(0, 10))
+        got = B.dp_overlapped_wait(ready, dur, end)
+        assert got == simulate_link(ready, dur, end), (ready, dur, end)
+        # max-plus closed form of the recursion: the last bucket arrives at max_j (ready_j + sum of dur from j on)
+        assert got == max(0, max(ready[j] + sum(dur[j:]) for j in range(n)) - end)
+        assert got <= sum(dur)                                      # never worse than no overlap at all
+        assert got >= max(0, ready[-1] + dur[-1] - end)             # the last bucket cannot start before it is ready
+    # nothing overlaps when every gradient is final only at the end of backward: the whole exchange is exposed
+    assert B.dp_overlapped_wait([50, 50, 50], [7, 8, 9], 50) == 24
+    # everything final at time 0: the exchange has had the whole of backward to itself
+    assert B.dp_overlapped_wait([0, 0, 0], [7, 8, 9], 20) == 4 and B.dp_overlapped_wait([0, 0, 0], [7, 8, 9], 30) == 0
+    # an exchange that takes no time exposes nothing
+    assert B.dp_overlapped_wait([3, 9, 12], [0, 0, 0], 12) == 0
+    # a slow link behind a fast backward: the backlog of the earlier buckets delays the last one
+    assert B.dp_overlapped_wait([10, 20, 30], [100, 100, 100], 30) == 10 + 300 - 30
+    # one bucket = the unbucketed exchange of the configuration
+    n_params = 124_439_808
+    (_, whole), = B.dp_bubbles(n_params, 2, 50_000_000_000)
+    assert B.dp_overlapped_wait([1000], [whole], 1000) == whole
+
