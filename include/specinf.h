@@ -105,6 +105,18 @@ uint64_t sif_collective_ns(uint64_t n_bytes, uint64_t bw_bytes_per_s);
 int32_t sif_pp_1f1b_bubbles(uint32_t stage, uint32_t n_stages, uint32_t n_micro, uint64_t tf_ns, uint64_t tb_ns,
                             int32_t* kind, int32_t* index, uint64_t* ns, uint32_t max);
 
+/* Data parallel with a bucketed gradient exchange that runs beside backward (a reading that goes beyond the single
+ * exposed all-reduce; Sec. 2.1 names communication as the source of the idle time).  group_bytes[i] = gradient bytes
+ * that become final together, in the order backward finalizes them.  A bucket is closed as soon as it holds at
+ * least cap_bytes; what is open at the end is the last bucket.  Writes the bucket number of every group and returns
+ * the number of buckets, or a negative sif_status (cap_bytes = 0, null array). */
+int32_t sif_dp_gradient_buckets(const uint64_t* group_bytes, uint32_t n_groups, uint64_t cap_bytes,
+                                uint32_t* bucket_of_group);
+
+/* Exposed wait of that exchange: bucket k is sent once it is ready (ready_ns[k]) and bucket k-1 has been sent, and
+ * takes dur_ns[k]; returns what is left of the exchange when backward ends at end_ns (0 if it is over by then). */
+uint64_t sif_dp_overlapped_wait(const uint64_t* ready_ns, const uint64_t* dur_ns, uint32_t n, uint64_t end_ns);
+
 /* ====================================================================================================
  * 2. Single kernels (raw launchers).  Each enqueues one kernel on `stream` (a hipStream_t, may be null =
  *    default stream) and returns without synchronising.  Used by the model code below and by the parity
@@ -304,6 +316,12 @@ typedef struct sif_train_desc {
   float* master_dev;             /* fp32 [n_params], caller-initialised, updated in place by each step  */
   void* workspace_dev;           /* >= sif_train_workspace_bytes(), 256-byte aligned                    */
   uint64_t workspace_bytes;
+  uint64_t dp_bucket_bytes;      /* DP, decoder: 0 = one exposed all-reduce of all gradients after backward;
+                                    > 0 = the gradients are exchanged in buckets of at least this size beside
+                                    backward (sif_dp_gradient_buckets over: per layer, last to first, the layer's
+                                    gradients (the final LayerNorm's ride with the last layer), then the
+                                    embeddings), each as soon as it is final, and only what is left of the
+                                    exchange when backward ends is waited for (sif_dp_overlapped_wait)        */
 } sif_train_desc;
 
 uint64_t sif_train_workspace_bytes(const sif_train_desc* d);
@@ -332,6 +350,10 @@ sif_status sif_sync_training(sif_ctx* ctx);
  * *elems = number of elements. */
 sif_status sif_train_tensor(sif_ctx* ctx, sif_handle h, const char* name, int32_t layer, void** ptr_dev,
                             uint64_t* elems);
+
+/* Bucket `index` of the bucketed gradient exchange (dp_bucket_bytes > 0): its gradient bytes and the index, in the
+ * step's kernel sequence, of the launch whose end makes it final.  SIF_E_INVAL past the last bucket. */
+sif_status sif_train_dp_bucket(sif_ctx* ctx, sif_handle h, uint32_t index, uint64_t* bytes, uint32_t* ready_launch);
 
 /* Name of the index-th launch of the training step's kernel sequence ("qkv", "attn_scores", "bubble", ...), the
  * same index a training-kernel trace record carries in `id`; null past the end. */

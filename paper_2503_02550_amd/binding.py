@@ -94,7 +94,7 @@ class sif_train_desc(C.Structure):
     _fields_ = [("struct_size", u32), ("par_mode", u32), ("shape", sif_model_shape), ("lr", f32),
                 ("pp_stages", u32), ("pp_micro", u32), ("pp_stage", u32),
                 ("bw_bytes_per_s", u64), ("fixed_bubble_ns", u64), ("pp_tf_ns", u64), ("pp_tb_ns", u64),
-                ("master_dev", vp), ("workspace_dev", vp), ("workspace_bytes", u64)]
+                ("master_dev", vp), ("workspace_dev", vp), ("workspace_bytes", u64), ("dp_bucket_bytes", u64)]
 
 
 class sif_infer_desc(C.Structure):
@@ -133,6 +133,8 @@ _sig("sif_principle_1", i32, P(u64), u32, u64)
 _sig("sif_principle_2", i32, u64, u64)
 _sig("sif_collective_ns", u64, u64, u64)
 _sig("sif_pp_1f1b_bubbles", i32, u32, u32, u32, u64, u64, P(i32), P(i32), P(u64), u32)
+_sig("sif_dp_gradient_buckets", i32, P(u64), u32, u64, P(u32))
+_sig("sif_dp_overlapped_wait", u64, P(u64), P(u64), u32, u64)
 _sig("sif_k_gemm_bf16", i32, P(sif_gemm_args), vp)
 _sig("sif_k_gemm_f32", i32, vp, i64, i64, vp, i64, i64, vp, i64, u32, u32, u32, u32, vp, vp, vp)
 _sig("sif_k_layernorm_fwd", i32, vp, vp, vp, vp, vp, vp, u32, u32, vp)
@@ -192,6 +194,20 @@ def sif_pp_1f1b_bubbles(stage, n_stages, n_micro, tf_ns, tb_ns, cap=64):
     kind, idx, ns = (i32 * cap)(), (i32 * cap)(), (u64 * cap)()
     n = check(lib.sif_pp_1f1b_bubbles(stage, n_stages, n_micro, tf_ns, tb_ns, kind, idx, ns, cap))
     return [(kind[i], idx[i], ns[i]) for i in range(min(n, cap))]
+
+
+def sif_dp_gradient_buckets(group_bytes, cap_bytes):
+    """Bucket number of every group."""
+    n = len(group_bytes)
+    gb, out = (u64 * max(n, 1))(*group_bytes), (u32 * max(n, 1))()
+    nb = check(lib.sif_dp_gradient_buckets(gb, n, cap_bytes, out))
+    return nb, [out[i] for i in range(n)]
+
+
+def sif_dp_overlapped_wait(ready_ns, dur_ns, end_ns):
+    n = len(ready_ns)
+    assert len(dur_ns) == n
+    return lib.sif_dp_overlapped_wait((u64 * max(n, 1))(*ready_ns), (u64 * max(n, 1))(*dur_ns), n, end_ns)
 
 
 # ---- single kernels -------------------------------------------------------------------------------------
@@ -427,6 +443,17 @@ def sif_abi_version():
 
 
 _sig("sif_train_op_name", C.c_char_p, vp, i32, u32)
+_sig("sif_train_dp_bucket", i32, vp, i32, u32, P(u64), P(u32))
+
+
+def sif_train_dp_buckets(ctx, h):
+    """[(bytes, index of the launch that finalizes the bucket)] of a step with a bucketed gradient exchange."""
+    out = []
+    while True:
+        b, r = u64(), u32()
+        if lib.sif_train_dp_bucket(ctx, h, len(out), C.byref(b), C.byref(r)) != 0:
+            return out
+        out.append((b.value, r.value))
 
 
 def sif_train_op_name(ctx, h, index):

@@ -12,16 +12,16 @@
 
 namespace sif {
 
-__global__ __launch_bounds__(64) void bubble_kernel(StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site,
-                                                    uint64_t ticks, uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
-  if (threadIdx.x != 0) return;
-  const uint64_t t0 = now_ticks();
+// t0: when the stream went idle; ticks: how long the bubble lasts (device-timed) or is expected to last.
+__device__ __forceinline__ void bubble_wait(StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t t0, uint64_t ticks,
+                                            uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
   st_agent(&rec->seq, seq);
   st_agent(&rec->site, site);
   st_agent(&rec->t_idle_begin, t0);
   st_agent(&rec->t_expected_end, t0 + ticks);
   st_agent(&rec->state, kStateIdle);
   st_sys(&mir->idle_site, site);
+  st_sys(&mir->idle_len_ticks, ticks);
   st_sys(&mir->idle_seq, seq);
   const uint64_t deadline = t0 + (device_timed ? ticks : max_ticks);
   while (now_ticks() < deadline) {
@@ -38,6 +38,36 @@ __global__ __launch_bounds__(64) void bubble_kernel(StreamRec* rec, Mirror* mir,
   slot->decision = 1;
   slot->t0 = t0;
   slot->t1 = t1;
+}
+
+__global__ __launch_bounds__(64) void bubble_kernel(StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site,
+                                                    uint64_t ticks, uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
+  if (threadIdx.x != 0) return;
+  bubble_wait(rec, mir, slot, seq, site, now_ticks(), ticks, max_ticks, device_timed, kind_id);
+}
+
+// The wait at the end of backward when the gradients are exchanged in buckets beside it.  Bucket k can be sent once
+// the launch that finalized it has ended (its end stamp lies in the trace ring, `back[k]` launches before this
+// one) and bucket k-1 has been sent, and takes ticks[k]; the stream idles for what is left of the exchange now.
+// If the exchange is already over there is no bubble: the stream never goes idle and the record has zero length.
+__global__ __launch_bounds__(64) void bubble_overlap_kernel(StreamRec* rec, Mirror* mir, Slot* ring, uint32_t kseq, DpBucketArgs b, uint32_t seq,
+                                                            uint32_t site, uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
+  if (threadIdx.x != 0) return;
+  const uint64_t t0 = now_ticks();
+  uint64_t finish = 0;
+  for (uint32_t k = 0; k < b.n; ++k) {
+    const uint64_t ready = ld_relaxed(&ring[(kseq - b.back[k]) % kRingSlots].t1);
+    finish = (ready > finish ? ready : finish) + b.ticks[k];
+  }
+  Slot* slot = ring + (kseq % kRingSlots);
+  if (finish <= t0) {
+    slot->kind_id = kind_id;
+    slot->decision = 1;
+    slot->t0 = t0;
+    slot->t1 = t0;
+    return;
+  }
+  bubble_wait(rec, mir, slot, seq, site, t0, finish - t0, max_ticks, device_timed, kind_id);
 }
 
 __global__ __launch_bounds__(64) void step_marker_kernel(StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id) {
@@ -98,6 +128,15 @@ sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot,
                          uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
   hipLaunchKernelGGL(bubble_kernel, dim3(1), dim3(64), 0, s, rec, mir, slot, seq, site, ticks, max_ticks, device_timed, kind_id);
   return check_launch("bubble");
+}
+
+sif_status launch_bubble_overlap(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* ring, uint32_t kseq, const DpBucketArgs& b, uint32_t seq,
+                                 uint32_t site, uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id) {
+  if (b.n == 0 || b.n > kMaxDpBuckets) return fail(SIF_E_INVAL, "bubble: bucket count out of range");
+  for (uint32_t k = 0; k < b.n; ++k)
+    if (b.back[k] == 0 || b.back[k] >= kRingSlots || b.back[k] >= kseq) return fail(SIF_E_INVAL, "bubble: a bucket's producer lies outside the trace ring");
+  hipLaunchKernelGGL(bubble_overlap_kernel, dim3(1), dim3(64), 0, s, rec, mir, ring, kseq, b, seq, site, max_ticks, device_timed, kind_id);
+  return check_launch("bubble_overlap");
 }
 
 sif_status launch_step_marker(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id) {

@@ -251,20 +251,28 @@ static void emit_ln_bwd(Plan& p, const void* dy, const void* x, const void* g, c
   emit(p, "ln_bwd", bytes_cost_us(8.0 * rows * d), [=](hipStream_t s, const KCtl& c) { return launch_layernorm_bwd_dx(dy, x, g, mean, rstd, res, dx, part, rows, d, ws, s, c); });
 }
 
-// the one finalize launch of a backward pass; acc: add to the stored gradients (micro-batch accumulation)
-static void emit_fin_batch(Plan& p, FinPlan& fp, RedPlan& rp, uint32_t acc) {
-  const FinItem* dev = fp.dev;
-  const uint32_t n_items = (uint32_t)fp.items.size(), max_n = fp.max_n;
-  emit(p, "grad_fin", 10.0, [=](hipStream_t s, const KCtl& c) { return launch_fin_batch(dev, n_items, max_n, acc, s, c); });
-  fp.recorded = true;
-  fp.open = false;
-  if (!rp.items.empty()) {
-    const RedItem* rdev = rp.dev;
-    const uint32_t rn = (uint32_t)rp.items.size();
+// finalize launches for the producers [f0, f1) and the split products [r0, r1); acc: add to the stored gradients
+// (micro-batch accumulation)
+static void emit_fin_range(Plan& p, const FinPlan& fp, const RedPlan& rp, uint32_t acc, size_t f0, size_t f1, size_t r0, size_t r1) {
+  if (f1 > f0) {
+    const FinItem* dev = fp.dev + f0;
+    const uint32_t n_items = (uint32_t)(f1 - f0), max_n = fp.max_n;
+    emit(p, "grad_fin", 10.0, [=](hipStream_t s, const KCtl& c) { return launch_fin_batch(dev, n_items, max_n, acc, s, c); });
+  }
+  if (r1 > r0) {
+    const RedItem* rdev = rp.dev + r0;
+    const uint32_t rn = (uint32_t)(r1 - r0);
     double bytes = 0;
-    for (const RedItem& it : rp.items) bytes += 4.0 * it.n * it.splits + 2.0 * it.n;
+    for (size_t i = r0; i < r1; ++i) bytes += 4.0 * rp.items[i].n * rp.items[i].splits + 2.0 * rp.items[i].n;
     emit(p, "wgrad_sum", bytes_cost_us(bytes), [=](hipStream_t s, const KCtl& c) { return launch_reduce_splits_batch(rdev, rn, acc, s, c); });
   }
+}
+
+// the finalize launches of a whole backward pass (one of each kind)
+static void emit_fin_batch(Plan& p, FinPlan& fp, RedPlan& rp, uint32_t acc) {
+  emit_fin_range(p, fp, rp, acc, 0, fp.items.size(), 0, rp.items.size());
+  fp.recorded = true;
+  fp.open = false;
   rp.recorded = true;
   rp.cursor = 0;
 }
@@ -529,6 +537,30 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   const uint32_t seq = q.S, V = s.vocab;
   const uint64_t mb_bytes = (uint64_t)M * d * 2;
 
+  // Bucketed gradient exchange beside backward: the gradient groups in the order they become final (the layers from
+  // the last to the first, the final LayerNorm with the last layer; then the embeddings), their buckets, and per
+  // bucket the op that finalizes it (filled in while the plan is emitted).
+  const bool overlap = tm.desc.par_mode == SIF_PAR_DP && tm.desc.dp_bucket_bytes > 0;
+  std::vector<uint64_t> group_bytes;
+  std::vector<uint32_t> bucket_of;
+  uint32_t n_buckets = 0;
+  tm.dp_buckets.clear();
+  if (overlap) {
+    const uint64_t emb = s.vocab ? ((uint64_t)s.vocab + s.max_pos) * d : 0, lnf_n = s.vocab ? 2ull * d : 0;
+    const uint64_t per_layer = (pm.n - emb - lnf_n) / s.n_layers;
+    for (uint32_t l = 0; l < s.n_layers; ++l) group_bytes.push_back(2 * (per_layer + (l == 0 ? lnf_n : 0)));
+    if (s.vocab) group_bytes.push_back(2 * emb);
+    bucket_of.resize(group_bytes.size());
+    const int32_t nb = sif_dp_gradient_buckets(group_bytes.data(), (uint32_t)group_bytes.size(), tm.desc.dp_bucket_bytes, bucket_of.data());
+    if (nb < 0) return (sif_status)nb;
+    if ((uint32_t)nb > kMaxDpBuckets) return fail(SIF_E_INVAL, "dp_bucket_bytes gives %d buckets, at most %u are supported", nb, kMaxDpBuckets);
+    n_buckets = (uint32_t)nb;
+    tm.dp_buckets.assign(n_buckets, TrainModel::DpBucket{0, 0, 0});
+    for (size_t g = 0; g < group_bytes.size(); ++g) tm.dp_buckets[bucket_of[g]].bytes += group_bytes[g];
+    for (auto& b : tm.dp_buckets) b.dur_ns = sif_collective_ns(b.bytes, tm.desc.bw_bytes_per_s);
+  }
+  auto closes_bucket = [&](size_t g) { return g + 1 == group_bytes.size() || bucket_of[g + 1] != bucket_of[g]; };
+
   // forward pass of micro-batch k into activation slot k % n_slots
   auto emit_forward = [&](Plan& p, uint32_t k) {
     const uint32_t sl = k % n_slots;
@@ -558,6 +590,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     const uint32_t sl = k % n_slots;
     if (!fp.open) fp.begin();
     rp.cursor = 0;
+    size_t fin_done = 0, red_done = 0;
     const bf16_t* dx = dx_top;
     if (!s.vocab) {
       // top of a stack: the upstream gradient comes from the caller
@@ -574,8 +607,19 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       bf16_t* below = l > 0 ? grads + pm.at(L((uint32_t)l - 1, "b_proj")) : nullptr;
       emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc, have_db_proj, below, fp, rp);
       dx = sc.dx_a;
+      const size_t grp = s.n_layers - 1 - (size_t)l;
+      if (overlap && closes_bucket(grp)) {       // the bucket is complete: finalize what it holds, its exchange can start
+        emit_fin_range(p, fp, rp, acc, fin_done, fp.items.size(), red_done, rp.items.size());
+        fin_done = fp.items.size(); red_done = rp.items.size();
+        tm.dp_buckets[bucket_of[grp]].ready_op = (uint32_t)p.size() - 1;
+      }
     }
-    emit_fin_batch(p, fp, rp, acc);
+    if (overlap) {
+      emit_fin_range(p, fp, rp, acc, fin_done, fp.items.size(), red_done, rp.items.size());
+      fp.recorded = true; fp.open = false; rp.recorded = true; rp.cursor = 0;
+    } else {
+      emit_fin_batch(p, fp, rp, acc);
+    }
     if (pp) {
       bf16_t* dst = dx_all + (size_t)k * M * d;
       const bf16_t* src = sc.dx_a;
@@ -611,7 +655,20 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       emit(p, "dwte_scatter", bytes_cost_us(4.0 * M * d) + 10.0, [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wte((const int32_t*)t->cur_inputs, dx0, gwte, M, d, s2, c); });
       emit(p, "dwpe", bytes_cost_us(2.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wpe(dx0, gwpe, M, seq, d, s2, c); });
     }
-    if (tm.desc.par_mode == SIF_PAR_DP) {
+    if (overlap) {
+      // The embeddings' gradients are final with the last launch of backward.  The bubble's length is decided on the
+      // device; what is stored here is the cost model's estimate of it (calibration replaces it by a measured one).
+      if (s.vocab) tm.dp_buckets[bucket_of.back()].ready_op = (uint32_t)p.size() - 1;
+      std::vector<uint64_t> ready(n_buckets), dur(n_buckets);
+      std::vector<double> until(p.size());
+      double acc_us = 0;
+      for (size_t i = 0; i < p.size(); ++i) { acc_us += p[i].cost_us; until[i] = acc_us; }
+      for (uint32_t b = 0; b < n_buckets; ++b) { ready[b] = (uint64_t)(until[tm.dp_buckets[b].ready_op] * 1000.0); dur[b] = tm.dp_buckets[b].dur_ns; }
+      const uint64_t ns = sif_dp_overlapped_wait(ready.data(), dur.data(), n_buckets, (uint64_t)(acc_us * 1000.0));
+      emit_bubble(p, next_site++, ns);
+      p.back().dp_overlap = true;
+      tm.max_bubble_ns = ns;
+    } else if (tm.desc.par_mode == SIF_PAR_DP) {
       const uint64_t ns = sif_collective_ns(pm.n * 2, tm.desc.bw_bytes_per_s);
       emit_bubble(p, next_site++, ns);
       tm.max_bubble_ns = ns;

@@ -56,6 +56,8 @@ struct Mirror {                     // pinned, coherent host memory
   uint64_t kernels_run, kernels_skipped, train_kernels;
   // host -> device
   uint32_t release_seq, pad2;
+  // device -> host: length of the bubble announced by idle_seq, where the device decides it (written before idle_seq)
+  uint64_t idle_len_ticks;
 };
 
 struct KCtl {                       // by-value kernel argument

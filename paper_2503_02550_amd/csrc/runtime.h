@@ -37,6 +37,7 @@ struct Op {
   // pipeline-stage plans: a kernel belongs to pass 2*micro_batch + (0 forward, 1 backward); a bubble is the idle
   // interval (pp_kind, pp_index) of the 1F1B schedule (see sif_pp_1f1b_bubbles)
   int32_t pp_pass = -1, pp_kind = -1, pp_index = 0;
+  bool dp_overlap = false;         // bubble whose length the device derives from the bucketed gradient exchange
 };
 typedef std::vector<Op> Plan;
 
@@ -67,6 +68,10 @@ struct TrainModel {
   uint64_t workspace_bytes = 0;
   std::vector<uint32_t> last_kseq;                  // launch number of each op in the most recent step
   bool pp_times_estimated = false;                  // pipeline bubbles were sized from the cost model, not from the caller
+  // bucketed gradient exchange beside backward (dp_bucket_bytes > 0): per bucket its bytes, the op whose end makes
+  // it final and how long the exchange of the bucket takes
+  struct DpBucket { uint64_t bytes; uint32_t ready_op; uint64_t dur_ns; };
+  std::vector<DpBucket> dp_buckets;
 };
 
 struct InferModel {
@@ -115,6 +120,12 @@ uint32_t infer_coalesce(const sif_infer_desc& d);
 // markers.hip
 sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,
                          uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id);
+// Buckets of an overlapped gradient exchange as the bubble kernel sees them: how many launches before the bubble
+// each bucket's last producer ran, and how many ticks its exchange takes.
+constexpr uint32_t kMaxDpBuckets = 48;
+struct DpBucketArgs { uint32_t n; uint32_t back[kMaxDpBuckets]; uint64_t ticks[kMaxDpBuckets]; };
+sif_status launch_bubble_overlap(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* ring, uint32_t kseq, const DpBucketArgs& b, uint32_t seq,
+                                 uint32_t site, uint64_t max_ticks, uint32_t device_timed, uint32_t kind_id);
 sif_status launch_step_marker(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t end, uint32_t kind_id);
 sif_status launch_probe(hipStream_t spin_stream, hipStream_t stamp_stream, uint64_t ticks, uint64_t* out);
 sif_status launch_reset_skip(hipStream_t s, StreamRec* rec, Mirror* mir, uint32_t epoch);

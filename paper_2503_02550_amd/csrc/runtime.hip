@@ -121,6 +121,8 @@ static sif_status launch_op(sif_ctx* c, Op& op, hipStream_t s, const KCtl& k) {
   return op.fn(s, k);
 }
 
+constexpr uint64_t kLenFromDevice = ~0ull;     // bubble table entry: the device decides the length and reports it
+
 static inline uint32_t mload(const uint32_t* p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
 static inline uint64_t mload(const uint64_t* p) { return __atomic_load_n(p, __ATOMIC_ACQUIRE); }
 
@@ -142,7 +144,8 @@ static void monitor_main(sif_ctx* c) {
     const uint32_t is = mload(&c->mir->idle_seq);
     if (is != last_idle_seen) {            // a bubble began: time its release on the host clock
       last_idle_seen = is;
-      const uint64_t len = c->bubble_ns[is % kBubbleTable].load(std::memory_order_acquire);
+      uint64_t len = c->bubble_ns[is % kBubbleTable].load(std::memory_order_acquire);
+      if (len == kLenFromDevice) len = c->ticks_to_ns(mload(&c->mir->idle_len_ticks));     // written before idle_seq
       pending_release = is;
       release_at = now + len;
       c->edge_len_ns.store(len, std::memory_order_relaxed);
@@ -389,11 +392,28 @@ static sif_status run_step(sif_ctx* c, const void* inputs, const void* targets, 
     Op& op = tm.plan[i];
     if (op.bubble_site >= 0) {
       const uint32_t seq = ++c->bubble_seq;
-      c->bubble_ns[seq % kBubbleTable].store(op.bubble_ns, std::memory_order_release);
       KCtl kb = make_ctl(c, c->T, kKindBubble, (uint32_t)op.bubble_site, nullptr, 0);
-      const uint64_t ticks = c->ns_to_ticks(op.bubble_ns);
-      st = launch_bubble(s, c->T.rec, c->mir, kb.slot, seq, (uint32_t)op.bubble_site, ticks, 4 * ticks + c->ns_to_ticks(100000000ull),
-                         c->cfg.device_timed_bubbles, kb.kind_id);
+      tm.last_kseq[i] = kb.kseq;
+      if (op.dp_overlap) {
+        // what is left of the bucketed gradient exchange: the device works it out from the end stamps of the
+        // launches that finalized the buckets, and reports the length to the monitor thread
+        c->bubble_ns[seq % kBubbleTable].store(kLenFromDevice, std::memory_order_release);
+        DpBucketArgs ba{};
+        ba.n = (uint32_t)tm.dp_buckets.size();
+        uint64_t total = 0;
+        for (uint32_t b = 0; b < ba.n; ++b) {
+          ba.back[b] = kb.kseq - tm.last_kseq[tm.dp_buckets[b].ready_op];
+          ba.ticks[b] = c->ns_to_ticks(tm.dp_buckets[b].dur_ns);
+          total += ba.ticks[b];
+        }
+        st = launch_bubble_overlap(s, c->T.rec, c->mir, c->T.ring, kb.kseq, ba, seq, (uint32_t)op.bubble_site,
+                                   4 * total + c->ns_to_ticks(100000000ull), c->cfg.device_timed_bubbles, kb.kind_id);
+      } else {
+        c->bubble_ns[seq % kBubbleTable].store(op.bubble_ns, std::memory_order_release);
+        const uint64_t ticks = c->ns_to_ticks(op.bubble_ns);
+        st = launch_bubble(s, c->T.rec, c->mir, kb.slot, seq, (uint32_t)op.bubble_site, ticks, 4 * ticks + c->ns_to_ticks(100000000ull),
+                           c->cfg.device_timed_bubbles, kb.kind_id);
+      }
     } else {
       const KCtl k = make_ctl(c, c->T, kKindTrain, (uint32_t)i, nullptr, 0);
       tm.last_kseq[i] = k.kseq;
@@ -575,6 +595,14 @@ sif_status sif_train_tensor(sif_ctx* c, sif_handle h, const char* name, int32_t 
   return SIF_OK;
 }
 
+sif_status sif_train_dp_bucket(sif_ctx* c, sif_handle h, uint32_t index, uint64_t* bytes, uint32_t* ready_launch) {
+  if (!c || !c->train || h != 0 || !bytes || !ready_launch) return fail(SIF_E_INVAL, "train_dp_bucket: bad handle or null output");
+  if (index >= c->train->dp_buckets.size()) return fail(SIF_E_INVAL, "train_dp_bucket: the step has %zu buckets", c->train->dp_buckets.size());
+  *bytes = c->train->dp_buckets[index].bytes;
+  *ready_launch = c->train->dp_buckets[index].ready_op;
+  return SIF_OK;
+}
+
 const char* sif_train_op_name(sif_ctx* c, sif_handle h, uint32_t index) {
   if (!c || !c->train || h != 0 || index >= c->train->plan.size()) return nullptr;
   return c->train->plan[index].name;
@@ -717,6 +745,16 @@ sif_status sif_calibrate(sif_ctx* c, uint32_t iters, const void* train_inputs_de
     for (uint32_t i = 0; i < iters; ++i) { st = run_step(c, train_inputs_dev, train_targets_dev, nullptr); if (st != SIF_OK) return st; }
     HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
     c->step_solo_ns = c->ticks_to_ns((mload(&c->mir->step_ticks_sum) - s0) / iters);
+    // a bubble whose length the device decides: keep what the last solo step showed as its predicted length
+    for (size_t i = 0; i < c->train->plan.size(); ++i) {
+      Op& op = c->train->plan[i];
+      if (!op.dp_overlap) continue;
+      Slot sl;
+      HIPCHK(hipMemcpy(&sl, c->T.ring + (c->train->last_kseq[i] % kRingSlots), sizeof(Slot), hipMemcpyDeviceToHost), "calibrate: read slot");
+      op.bubble_ns = c->ticks_to_ns(sl.t1 - sl.t0);
+      op.cost_us = op.bubble_ns / 1000.0;
+      c->train->max_bubble_ns = op.bubble_ns;
+    }
   }
   for (auto& mp : c->models) {
     InferModel& im = *mp;

@@ -78,4 +78,24 @@ int32_t sif_pp_1f1b_bubbles(uint32_t stage, uint32_t n_stages, uint32_t n_micro,
   return (int32_t)cnt;
 }
 
+int32_t sif_dp_gradient_buckets(const uint64_t* group_bytes, uint32_t n_groups, uint64_t cap_bytes, uint32_t* bucket_of_group) {
+  if (cap_bytes == 0 || (n_groups > 0 && (!group_bytes || !bucket_of_group))) return sif::fail(SIF_E_INVAL, "dp buckets: zero cap or null array");
+  uint32_t bucket = 0;
+  uint64_t held = 0;
+  bool open = false;
+  for (uint32_t i = 0; i < n_groups; ++i) {
+    bucket_of_group[i] = bucket;
+    held += group_bytes[i];
+    open = true;
+    if (held >= cap_bytes) { ++bucket; held = 0; open = false; }
+  }
+  return (int32_t)(bucket + (open ? 1u : 0u));
+}
+
+uint64_t sif_dp_overlapped_wait(const uint64_t* ready_ns, const uint64_t* dur_ns, uint32_t n, uint64_t end_ns) {
+  uint64_t finish = 0;
+  for (uint32_t k = 0; ready_ns != nullptr && dur_ns != nullptr && k < n; ++k) finish = (ready_ns[k] > finish ? ready_ns[k] : finish) + dur_ns[k];
+  return finish > end_ns ? finish - end_ns : 0;
+}
+
 }  // extern "C"

@@ -42,12 +42,13 @@ class Session:
 
     # ---- training --------------------------------------------------------------------------------------
     def register_training(self, shape, master_flat, par_mode=B.SIF_PAR_NONE, lr=0.01, bw_bytes_per_s=0, fixed_bubble_ns=0,
-                          pp_stages=0, pp_micro=0, pp_stage=0, pp_tf_ns=0, pp_tb_ns=0):
+                          pp_stages=0, pp_micro=0, pp_stage=0, pp_tf_ns=0, pp_tb_ns=0, dp_bucket_bytes=0):
         d = B.sif_train_desc()
         d.struct_size = C.sizeof(d)
         d.par_mode, d.shape, d.lr = par_mode, shape, lr
         d.bw_bytes_per_s, d.fixed_bubble_ns = bw_bytes_per_s, fixed_bubble_ns
         d.pp_stages, d.pp_micro, d.pp_stage, d.pp_tf_ns, d.pp_tb_ns = pp_stages, pp_micro, pp_stage, pp_tf_ns, pp_tb_ns
+        d.dp_bucket_bytes = dp_bucket_bytes
         need = B.sif_train_workspace_bytes(d)
         master = torch.from_numpy(np.ascontiguousarray(master_flat, dtype=np.float32)).to(self.dev)
         ws = _u8(need, self.dev)

@@ -94,6 +94,24 @@ def test_bubble_model_matches_oracle():
         S.sif_pp_1f1b_bubbles(0, 4, 3, 1, 1)
 
 
+def test_bucketed_gradient_exchange_matches_oracle():
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(0, 9))
+        sizes = [int(v) for v in rng.integers(1, 60, n)]
+        cap = int(rng.integers(1, 90))
+        nb, of = S.sif_dp_gradient_buckets(sizes, cap)
+        want = OB.dp_gradient_buckets(sizes, cap)
+        assert nb == len(want)
+        assert of == [b for b, grp in enumerate(want) for _ in grp]
+        ready = sorted(int(v) for v in rng.integers(0, 10 ** 7, n))
+        dur = [int(v) for v in rng.integers(0, 10 ** 6, n)]
+        end = (ready[-1] if n else 0) + int(rng.integers(0, 10 ** 5))
+        assert S.sif_dp_overlapped_wait(ready, dur, end) == OB.dp_overlapped_wait(ready, dur, end)
+    with pytest.raises(S.SifError):
+        S.sif_dp_gradient_buckets([1, 2], 0)
+
+
 def test_param_layout_counts():
     from paper_2503_02550_amd import params as P
     from paper_2503_02550_amd.session import decoder_shape, encoder_shape, mlp_shape

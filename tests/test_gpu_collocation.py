@@ -362,3 +362,93 @@ def test_two_offline_instances_share_the_grant_and_neither_starves():
                 torch.cuda.synchronize()
                 s.wait(s.submit_offline(hm, I, out, ENC["batch"], ENC["seq"]))
                 assert torch.equal(out, outs[i]), (which, i)
+
+
+# ---- bucketed gradient exchange beside backward (data parallel, overlapped): only the tail of it is a bubble
+DEC4 = dict(n_layers=4, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=1000, max_pos=128, batch=4, seq=128, causal=True)
+
+
+def dec4_groups():
+    """Gradient bytes in the order backward finalizes them: layers last to first (the final LayerNorm with the last
+    layer), then the embeddings."""
+    d, f = DEC4["d_model"], DEC4["d_ffn"]
+    layer = 2 * d + 3 * d * d + 3 * d + d * d + d + 2 * d + f * d + f + d * f + d
+    return [2 * (layer + (2 * d if l == 0 else 0)) for l in range(DEC4["n_layers"])] + [2 * (DEC4["vocab"] + DEC4["max_pos"]) * d]
+
+
+def run_overlapped(bucket_bytes, bw, device_timed, steps=3, n_batches=0, calibrate=False):
+    from oracle import bubbles as OB
+    shape, ishape = decoder_shape(DEC4), encoder_shape(ENC)
+    cfg = S.sif_default_config()
+    cfg.device_timed_bubbles = 1 if device_timed else 0
+    with Session(cfg) as s:
+        h = s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC4)), par_mode=S.SIF_PAR_DP, lr=0.01, bw_bytes_per_s=bw,
+                                dp_bucket_bytes=bucket_bytes)
+        x, t = i32(Y.token_ids(3, DEC4["batch"], DEC4["seq"], DEC4["vocab"])), i32(Y.token_ids(4, DEC4["batch"], DEC4["seq"], DEC4["vocab"]))
+        outs, ids, tickets, n_cal = [], [], [], 0
+        if n_batches:
+            m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)))
+        if calibrate:                     # three training steps of its own, then the inference model's kernels
+            torch.cuda.synchronize()
+            S.sif_calibrate(s.ctx, 2, x, t)
+            n_cal = last_launch(s)
+        if n_batches:
+            ids = [i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])) for i in range(n_batches)]
+            outs = [torch.zeros((ENC["batch"], ENC["seq"], ENC["d_model"]), device=DEV, dtype=torch.bfloat16) for _ in range(n_batches)]
+        torch.cuda.synchronize()
+        tickets = [s.submit_offline(m, ids[i], outs[i], ENC["batch"], ENC["seq"]) for i in range(n_batches)]
+        for _ in range(steps):
+            s.step(x, t)
+        s.sync()
+        for tk in tickets:
+            s.wait(tk, 20.0)
+        buckets = S.sif_train_dp_buckets(s.ctx, h) if bucket_bytes else []
+        tr = S.sif_read_trace(s.ctx, 0)
+        marks = [i for i, r in enumerate(tr) if r[0] == 4]
+        last = tr[marks[-2] + 1:marks[-1]] if len(marks) >= 2 else tr      # the last step: between its two markers
+        return up(s.train["master"]), buckets, last, s.stats(), (bubbles_and_kernels(s, n_cal) if n_batches else None), outs
+
+
+def test_overlapped_gradient_exchange_exposes_only_its_tail():
+    from oracle import bubbles as OB
+    cap, bw = 3_000_000, 10_000_000_000
+    groups = dec4_groups()
+    want_buckets = OB.dp_gradient_buckets(groups, cap)
+    assert len(want_buckets) == 3
+    w_plain, _, last_plain, _, _, _ = run_overlapped(0, bw, True)
+    for device_timed in (True, False):
+        w, buckets, last, st, _, _ = run_overlapped(cap, bw, device_timed)
+        assert np.array_equal(w, w_plain)                                  # finalizing per bucket changes no gradient bit
+        assert [b for b, _ in buckets] == [sum(groups[g] for g in grp) for grp in want_buckets]
+        end_of = {rid: t1 for kind, rid, _, _, _, t1 in last if kind == 1}
+        (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
+        ready = [end_of[r] for _, r in buckets]
+        assert ready == sorted(ready) and ready[-1] <= b0
+        dur = [OB.collective_ns(b, bw) for b, _ in buckets]
+        want = OB.dp_overlapped_wait(ready, dur, b0)
+        whole, = [t1 - t0 for kind, _, _, _, t0, t1 in last_plain if kind == 3]
+        assert 0 < want < whole                                             # part of the exchange hid behind backward
+        got = b1 - b0
+        assert want - 500 <= got <= want + (6_000 if device_timed else 300_000), (got, want, device_timed)
+    # a link so fast that the exchange is over when backward ends: no bubble at all, the stream never goes idle
+    _, _, last, st, _, _ = run_overlapped(cap, 10 ** 15, True)
+    (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
+    assert b1 == b0 and st.bubble_ns == 0
+
+
+def test_inference_fills_the_tail_of_an_overlapped_exchange():
+    cap, bw = 3_000_000, 2_000_000_000          # ~1.6 ms per two-layer bucket: a tail long enough for the encoder's kernels
+    w_solo, _, _, _, _, _ = run_overlapped(cap, bw, False)
+    w_col, _, _, st, (bubbles, ran, skipped), outs = run_overlapped(cap, bw, False, steps=8, n_batches=4, calibrate=True)
+    w_ref, _, _, _, _, _ = run_overlapped(cap, bw, False, steps=8, calibrate=True)
+    assert np.array_equal(w_col, w_ref) and not np.array_equal(w_col, w_solo)
+    assert st.offline_batches == 4 and st.gate_violations == 0
+    assert_starts_inside_bubbles(bubbles, ran)
+    ishape = encoder_shape(ENC)
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)))
+        for i in range(4):
+            I, out = i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])), torch.zeros_like(outs[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
+            assert torch.equal(out, outs[i])
