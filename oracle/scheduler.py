@@ -95,3 +95,30 @@ def principle_1(peak_bytes, capacity_bytes):
 def principle_2(min_exec_ns, max_bubble_ns):
     """Collocation Principle-II (Sec. 3.2): a batch-1 online request must be shorter than the longest bubble."""
     return min_exec_ns < max_bubble_ns
+
+
+# ---- concurrent filling with feedback (Sec. 5.2, the outlook given for pipeline parallelism) ---------------
+# The paper's stated plan for pipeline-parallel training: run inference beside training as much as possible
+# until the Bubble Monitor sees that training iterations have become longer.  It gives no rule; the reading
+# taken here is additive increase / multiplicative decrease on a share of wall time, in parts per million:
+#   * `share` = fraction of a busy period during which an inference kernel may be running;
+#   * after every training iteration: if it took longer than ref * (1 + eps) the share is halved, otherwise it
+#     grows by `add` up to `cap`;
+#   * the barrier keeps a time account: every period adds period * share (the whole period while the status is
+#     idle), never above `burst`; a kernel is forwarded iff the account holds its predicted time, which is then
+#     taken off.
+# Parity unpinned against the paper (it prints neither a rule nor constants).
+PPM = 1_000_000
+
+
+def feedback_share(share_ppm, step_ns, ref_ns, eps_ppm, add_ppm, cap_ppm=PPM):
+    """Share of busy time granted to inference after an iteration that took step_ns (reference ref_ns)."""
+    if step_ns * PPM > ref_ns * (PPM + eps_ppm):      # the iteration has lengthened: back off
+        return share_ppm // 2
+    return min(cap_ppm, share_ppm + add_ppm)
+
+
+def concurrent_account(balance_ns, share_ppm, idle, period_ns, burst_ns):
+    """Time account of the barrier after one period."""
+    gain = period_ns if idle else (period_ns * share_ppm) // PPM
+    return min(burst_ns, balance_ns + gain)

@@ -208,3 +208,60 @@ def test_dp_overlapped_wait_against_tick_simulation_and_closed_forms():
     (_, whole), = B.dp_bubbles(n_params, 2, 50_000_000_000)
     assert B.dp_overlapped_wait([1000], [whole], 1000) == whole
 
+
+# ---- concurrent filling with feedback
+def test_feedback_share_rule_and_its_closed_forms():
+    P = K.PPM
+    assert K.feedback_share(200_000, 1_021, 1_000, 20_000, 50_000) == 100_000       # 2.1 % longer: halved
+    assert K.feedback_share(200_000, 1_020, 1_000, 20_000, 50_000) == 250_000       # exactly at the threshold: not longer
+    assert K.feedback_share(980_000, 900, 1_000, 20_000, 50_000) == P               # capped
+    assert K.feedback_share(1, 2_000, 1_000, 20_000, 50_000) == 0                   # halving reaches zero
+    # k good iterations from zero: min(cap, k * add); then h bad ones: floor division by 2^h
+    s = 0
+    for k in range(1, 30):
+        s = K.feedback_share(s, 100, 100, 0, 70_000, 600_000)
+        assert s == min(600_000, 70_000 * k)
+    for h in range(1, 8):
+        s = K.feedback_share(s, 101, 100, 0, 70_000, 600_000)
+        assert s == 600_000 >> h
+    # exhaustive: never outside [0, cap], monotone in the iteration time
+    for share in range(0, 1_000_001, 125_000):
+        prev = None
+        for step in range(90, 121):
+            v = K.feedback_share(share, step, 100, 50_000, 125_000)
+            assert 0 <= v <= P
+            assert prev is None or v <= prev
+            prev = v
+
+
+def test_feedback_holds_a_linear_plant_near_its_threshold():
+    """Plant: an iteration takes ref * (1 + kappa * share).  The share climbs by `add` until the threshold share
+    eps / kappa is passed, is halved, and climbs again: the slowdown never exceeds eps + kappa * add, and the
+    long-run share stays between a third of the threshold share and the threshold share plus one increment."""
+    ref, eps, add = 100_000_000, 20_000, 10_000
+    for kappa_ppm in (100_000, 400_000, 900_000):            # slowdown per unit share
+        star = eps * K.PPM // kappa_ppm                      # share at which the threshold is met
+        share, shares, worst = 0, [], 0
+        for _ in range(2000):
+            step = ref + ref * kappa_ppm // K.PPM * share // K.PPM
+            worst = max(worst, step)
+            share = K.feedback_share(share, step, ref, eps, add)
+            shares.append(share)
+        assert worst <= ref + ref * (eps + kappa_ppm * add // K.PPM) // K.PPM + 1
+        tail = shares[500:]
+        assert max(tail) <= min(K.PPM, star + add)
+        if star + add < K.PPM:
+            assert sum(tail) / len(tail) >= star / 3
+
+
+def test_concurrent_account():
+    assert K.concurrent_account(0, 100_000, False, 25_000, 10 ** 9) == 2_500
+    assert K.concurrent_account(0, 100_000, True, 25_000, 10 ** 9) == 25_000        # an idle period counts in full
+    assert K.concurrent_account(190_000, 1_000_000, False, 25_000, 200_000) == 200_000   # burst cap
+    assert K.concurrent_account(7, 0, False, 25_000, 200_000) == 7                  # no share, nothing gained
+    # n busy periods at a constant share: floor per period, so n * floor(period * share)
+    b = 0
+    for n in range(1, 50):
+        b = K.concurrent_account(b, 333_333, False, 25_000, 10 ** 9)
+        assert b == n * (25_000 * 333_333 // K.PPM)
+
