@@ -117,6 +117,18 @@ int32_t sif_dp_gradient_buckets(const uint64_t* group_bytes, uint32_t n_groups, 
  * takes dur_ns[k]; returns what is left of the exchange when backward ends at end_ns (0 if it is over by then). */
 uint64_t sif_dp_overlapped_wait(const uint64_t* ready_ns, const uint64_t* dur_ns, uint32_t n, uint64_t end_ns);
 
+/* Concurrent filling with feedback (Sec. 5.2: the outlook for pipeline parallelism is to run inference beside
+ * training as much as possible until the Bubble Monitor sees the training iterations lengthen; the rule itself is
+ * this library's reading).  share_ppm = the fraction of a busy period, in parts per million, during which an
+ * inference kernel may run.  After an iteration of step_ns against the reference ref_ns: halved if
+ * step_ns > ref_ns * (1 + eps), else raised by add_ppm up to cap_ppm. */
+uint32_t sif_feedback_share(uint32_t share_ppm, uint64_t step_ns, uint64_t ref_ns, uint32_t eps_ppm, uint32_t add_ppm,
+                            uint32_t cap_ppm);
+/* The barrier's time account for the busy phases after one period: + period_ns * share, never above burst_ns.  A
+ * kernel that Algorithm 1's tokens do not cover is forwarded iff the account holds its predicted time, which is
+ * then taken off. */
+uint64_t sif_concurrent_account(uint64_t balance_ns, uint32_t share_ppm, uint64_t period_ns, uint64_t burst_ns);
+
 /* ====================================================================================================
  * 2. Single kernels (raw launchers).  Each enqueues one kernel on `stream` (a hipStream_t, may be null =
  *    default stream) and returns without synchronising.  Used by the model code below and by the parity
@@ -263,10 +275,20 @@ typedef struct sif_config {
   uint32_t allow_serial_streams; /* 1: accept a stream pair that does not run concurrently (counter-collecting
                                     profilers serialise all kernels); nothing fills a bubble then            */
   uint64_t device_capacity_bytes; /* Principle-I capacity; 0 = total memory of the current device      */
+  uint32_t feedback;         /* 1: concurrent filling with feedback: bubbles are filled as without it; an offline
+                                kernel that Algorithm 1's tokens do not cover is forwarded against a time account
+                                (sif_concurrent_account) and then starts whatever the training stream does; the share
+                                of busy time follows sif_feedback_share after every training iteration during which
+                                the barrier forwarded a kernel.  Reference = the shortest iteration seen since the
+                                last sif_calibrate, starting from its solo iteration time when it was given training
+                                inputs.  Online requests are handled as without it.                         */
+  uint32_t feedback_eps_ppm; /* an iteration counts as lengthened beyond ref * (1 + eps)                      */
+  uint32_t feedback_add_ppm; /* increase of the share after an iteration that did not lengthen               */
+  uint32_t feedback_cap_ppm; /* largest share                                                                 */
 } sif_config;
 
 /* Fills *cfg with the defaults (P = 25 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 200, LL = 400, UL = 800
- * tokens, kernel_us_max 200, collocate 1). */
+ * tokens, kernel_us_max 200, collocate 1, feedback 0 with eps 2 %, add 2 %, cap 100 %). */
 sif_status sif_default_config(sif_config* cfg);
 
 /* Bytes of device workspace sif_create needs (activity records, trace rings). */
@@ -402,7 +424,8 @@ uint64_t sif_now_ns(void);
 
 typedef struct sif_stats {
   uint32_t struct_size;
-  uint32_t status_now, zc_now, reserved;
+  uint32_t status_now, zc_now;
+  uint32_t concurrent_share_ppm;  /* concurrent filling with feedback: the share of busy time now granted  */
   uint64_t tokens_now;
   uint64_t steps;                 /* training steps completed                                           */
   uint64_t step_ns_sum, step_ns_last, step_solo_ns;

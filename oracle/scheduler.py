@@ -104,9 +104,9 @@ def principle_2(min_exec_ns, max_bubble_ns):
 #   * `share` = fraction of a busy period during which an inference kernel may be running;
 #   * after every training iteration: if it took longer than ref * (1 + eps) the share is halved, otherwise it
 #     grows by `add` up to `cap`;
-#   * the barrier keeps a time account: every period adds period * share (the whole period while the status is
-#     idle), never above `burst`; a kernel is forwarded iff the account holds its predicted time, which is then
-#     taken off.
+#   * bubbles keep being filled under Algorithm 1's tokens; beside that the barrier keeps a time account for the
+#     busy phases: every period adds period * share, never above `burst`; a kernel that the tokens do not cover
+#     is forwarded iff the account holds its predicted time, which is then taken off.
 # Parity unpinned against the paper (it prints neither a rule nor constants).
 PPM = 1_000_000
 
@@ -118,7 +118,6 @@ def feedback_share(share_ppm, step_ns, ref_ns, eps_ppm, add_ppm, cap_ppm=PPM):
     return min(cap_ppm, share_ppm + add_ppm)
 
 
-def concurrent_account(balance_ns, share_ppm, idle, period_ns, burst_ns):
+def concurrent_account(balance_ns, share_ppm, period_ns, burst_ns):
     """Time account of the barrier after one period."""
-    gain = period_ns if idle else (period_ns * share_ppm) // PPM
-    return min(burst_ns, balance_ns + gain)
+    return min(burst_ns, balance_ns + (period_ns * share_ppm) // PPM)

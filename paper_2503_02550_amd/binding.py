@@ -81,7 +81,8 @@ class sif_gemm_args(C.Structure):
 class sif_config(C.Structure):
     _fields_ = [("struct_size", u32), ("period_us", u32), ("window", u32), ("count_running", u32),
                 ("alg1", sif_alg1_params), ("kernel_us_max", u32), ("collocate", u32), ("device_timed_bubbles", u32),
-                ("allow_serial_streams", u32), ("device_capacity_bytes", u64)]
+                ("allow_serial_streams", u32), ("device_capacity_bytes", u64),
+                ("feedback", u32), ("feedback_eps_ppm", u32), ("feedback_add_ppm", u32), ("feedback_cap_ppm", u32)]
 
 
 class sif_model_shape(C.Structure):
@@ -103,7 +104,7 @@ class sif_infer_desc(C.Structure):
 
 
 class sif_stats(C.Structure):
-    _fields_ = [("struct_size", u32), ("status_now", u32), ("zc_now", u32), ("reserved", u32), ("tokens_now", u64),
+    _fields_ = [("struct_size", u32), ("status_now", u32), ("zc_now", u32), ("concurrent_share_ppm", u32), ("tokens_now", u64),
                 ("steps", u64), ("step_ns_sum", u64), ("step_ns_last", u64), ("step_solo_ns", u64),
                 ("bubble_ns", u64), ("filled_ns", u64), ("infer_busy_ns", u64),
                 ("offline_samples", u64), ("offline_batches", u64),
@@ -133,6 +134,8 @@ _sig("sif_principle_1", i32, P(u64), u32, u64)
 _sig("sif_principle_2", i32, u64, u64)
 _sig("sif_collective_ns", u64, u64, u64)
 _sig("sif_pp_1f1b_bubbles", i32, u32, u32, u32, u64, u64, P(i32), P(i32), P(u64), u32)
+_sig("sif_feedback_share", u32, u32, u64, u64, u32, u32, u32)
+_sig("sif_concurrent_account", u64, u64, u32, u64, u64)
 _sig("sif_dp_gradient_buckets", i32, P(u64), u32, u64, P(u32))
 _sig("sif_dp_overlapped_wait", u64, P(u64), P(u64), u32, u64)
 _sig("sif_k_gemm_bf16", i32, P(sif_gemm_args), vp)
@@ -194,6 +197,14 @@ def sif_pp_1f1b_bubbles(stage, n_stages, n_micro, tf_ns, tb_ns, cap=64):
     kind, idx, ns = (i32 * cap)(), (i32 * cap)(), (u64 * cap)()
     n = check(lib.sif_pp_1f1b_bubbles(stage, n_stages, n_micro, tf_ns, tb_ns, kind, idx, ns, cap))
     return [(kind[i], idx[i], ns[i]) for i in range(min(n, cap))]
+
+
+def sif_feedback_share(share_ppm, step_ns, ref_ns, eps_ppm, add_ppm, cap_ppm=1_000_000):
+    return lib.sif_feedback_share(share_ppm, step_ns, ref_ns, eps_ppm, add_ppm, cap_ppm)
+
+
+def sif_concurrent_account(balance_ns, share_ppm, period_ns, burst_ns):
+    return lib.sif_concurrent_account(balance_ns, share_ppm, period_ns, burst_ns)
 
 
 def sif_dp_gradient_buckets(group_bytes, cap_bytes):

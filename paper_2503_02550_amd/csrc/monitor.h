@@ -68,7 +68,7 @@ struct KCtl {                       // by-value kernel argument
   uint32_t kseq;                    // launch number on this stream (>= 1)
   uint32_t cost_ticks;              // predicted duration
   uint32_t kind_id;
-  uint32_t flags;                   // bit 0: last kernel of its job
+  uint32_t flags;                   // bit 0: last kernel of its job; bit 1: gated on the poison only (runs beside training)
 };
 
 __device__ __forceinline__ uint64_t now_ticks() { return wall_clock64(); }
@@ -120,6 +120,11 @@ __device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
   const uint64_t s0 = ld_relaxed(ss);
   const uint64_t t_end = ld_relaxed(&c.gate->t_expected_end);
   const uint32_t poison = ld_relaxed(&c.rec->skip_from);
+  if (c.flags & 2u) {               // concurrent filling: only the order within the speculation window is kept
+    if (poison != kNone) return false;
+    *t0 = now_ticks();
+    return true;
+  }
   if (poison != kNone || (uint32_t)s0 != kStateIdle) return false;
   const uint64_t t = now_ticks();
   if (t + c.cost_ticks > t_end) return false;

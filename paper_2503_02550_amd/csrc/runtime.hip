@@ -79,6 +79,10 @@ struct sif_ctx {
   std::atomic<uint64_t> offline_samples{0}, offline_batches{0}, online_done{0}, kernels_launched{0}, periods{0};
   std::atomic<uint64_t> gate_violations{0};
   uint64_t step_solo_ns = 0;
+  // concurrent filling with feedback: the share is set by the monitor thread after every training iteration, the
+  // time account is kept by the barrier thread
+  std::atomic<uint32_t> share_ppm{0};
+  uint64_t conc_account_ns = 0;
 
   // optional event timing of the GEMM launches (sif_profile_gemm)
   std::atomic<uint32_t> prof_on{0};        // 0 off, 1 every GEMM launch, 2 only the variant with both operands K-contiguous
@@ -139,8 +143,31 @@ static void monitor_main(sif_ctx* c) {
   uint32_t pending_release = 0;
   uint64_t release_at = 0, pool = 0;
   uint64_t next_sample = host_now_ns() + period_ns;
+  uint64_t steps_seen = mload(&c->mir->steps), launched_seen = c->kernels_launched.load(std::memory_order_relaxed);
+  uint64_t cal_seen = 0, ref = 0;        // feedback: calibrated solo iteration time last seen, reference in use
   while (!c->stop.load(std::memory_order_relaxed)) {
     const uint64_t now = host_now_ns();
+    if (c->cfg.feedback) {                 // a training iteration ended: has it lengthened?
+      const uint64_t steps = mload(&c->mir->steps);
+      if (steps != steps_seen) {
+        steps_seen = steps;
+        // Reference: the shortest iteration seen since the last calibration, starting from the calibrated solo time
+        // (the first iterations of a process run long, and a reference taken from them alone would hide a slowdown).
+        const uint64_t cal = __atomic_load_n(&c->step_solo_ns, __ATOMIC_RELAXED);
+        if (cal != cal_seen) { cal_seen = cal; ref = cal; }
+        const uint64_t step_ns = c->ticks_to_ns(mload(&c->mir->step_ticks_last));
+        if (!c->paused.load(std::memory_order_relaxed)) {
+          if (ref == 0 || step_ns < ref) ref = step_ns;
+          // an iteration during which the barrier forwarded nothing says nothing about the share
+          const uint64_t launched = c->kernels_launched.load(std::memory_order_relaxed);
+          const bool served = launched != launched_seen;
+          launched_seen = launched;
+          if (served && c->collocate.load(std::memory_order_relaxed))
+            c->share_ppm.store(sif_feedback_share(c->share_ppm.load(std::memory_order_relaxed), step_ns, ref, c->cfg.feedback_eps_ppm,
+                                                  c->cfg.feedback_add_ppm, c->cfg.feedback_cap_ppm), std::memory_order_relaxed);
+        }
+      }
+    }
     const uint32_t is = mload(&c->mir->idle_seq);
     if (is != last_idle_seen) {            // a bubble began: time its release on the host clock
       last_idle_seen = is;
@@ -267,15 +294,28 @@ static void barrier_main(sif_ctx* c) {
     // 3. a new period: the grant replaces the balance
     const uint64_t pn = c->period_no.load(std::memory_order_acquire);
     // (the grant is already the per-instance share pool / m of Algorithm 1; every offline instance gets it)
-    if (pn != c->last_period) { c->last_period = pn; std::fill(c->balance.begin(), c->balance.end(), c->grant.load(std::memory_order_relaxed)); }
+    if (pn != c->last_period) {
+      if (c->cfg.feedback) {      // the periods that went by feed the time account (one call per period, as the rule is stated)
+        const uint64_t burst = 1000ull * std::max<uint64_t>(c->cfg.kernel_us_max, c->cfg.alg1.ul);
+        const uint32_t share = c->share_ppm.load(std::memory_order_relaxed);
+        for (uint64_t k = std::min<uint64_t>(pn - c->last_period, 64); k > 0; --k)
+          c->conc_account_ns = sif_concurrent_account(c->conc_account_ns, share, (uint64_t)c->cfg.period_us * 1000ull, burst);
+      }
+      c->last_period = pn;
+      std::fill(c->balance.begin(), c->balance.end(), c->grant.load(std::memory_order_relaxed));
+    }
     if (c->hold && (!gated || mload(&c->mir->idle_seq) != c->hold_seq)) c->hold = false;
-    // 4. admit jobs
-    if ((c->collocate.load(std::memory_order_relaxed) && !c->hold) || !gated) {
+    // 4. admit jobs.  Two ways lead to the inference stream: into a bubble (Algorithm 1's tokens, the device gate
+    // checks the bubble; closed after a skipped launch until the next bubble begins), and, with concurrent filling,
+    // beside training against the time account (the device gate checks only the order of the launches).
+    const bool feedback = gated && c->cfg.feedback != 0 && c->collocate.load(std::memory_order_relaxed);
+    const bool into_bubbles = (c->collocate.load(std::memory_order_relaxed) && !c->hold) || !gated;
+    if (into_bubbles || feedback) {
       {
         std::lock_guard<std::mutex> lk(c->mu);
         // Online pull-and-execute: requests are pulled one at a time, in arrival order, each only if the status is
         // idle and the predicted rest of the bubble, less what the requests already pulled still need, holds it.
-        while (!c->online_q.empty() && c->run_online.size() < 8) {
+        while (into_bubbles && !c->online_q.empty() && c->run_online.size() < 8) {
           Job* j = c->online_q.front();
           const uint64_t need = (uint64_t)(job_cost_us(j) * 1000.0);
           uint64_t pending = 0;
@@ -329,8 +369,9 @@ static void barrier_main(sif_ctx* c) {
       int budget = 64;
       while (budget-- > 0) {
         Job* j = nullptr;
-        bool online = false;
-        for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
+        bool online = false, beside = false;
+        if (into_bubbles)
+          for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
         if (j && gated && c->status.load(std::memory_order_relaxed) != SIF_STATUS_IDLE) j = nullptr;   // online kernels only while idle
         // a kernel predicted longer than the largest possible grant is charged the whole grant, so that the head of
         // the queue can always be forwarded in the stable phase
@@ -345,7 +386,8 @@ static void barrier_main(sif_ctx* c) {
             const size_t mdl = (c->rr_next + r) % nm;
             for (Job* q : c->run_offline) {
               if ((size_t)q->model != mdl || q->next_op >= q->plan.size()) continue;
-              if (!gated || c->balance[mdl] >= cost_of(q)) { j = q; c->rr_next = (mdl + 1) % nm; }   // token rule
+              if (!gated || (into_bubbles && c->balance[mdl] >= cost_of(q))) { j = q; c->rr_next = (mdl + 1) % nm; }   // token rule
+              else if (feedback && c->conc_account_ns >= 1000ull * cost_of(q)) { j = q; beside = true; c->rr_next = (mdl + 1) % nm; }
               break;
             }
           }
@@ -357,6 +399,7 @@ static void barrier_main(sif_ctx* c) {
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
         if (j->next_op + 1 == j->plan.size()) k.flags |= 1u;
+        if (beside) k.flags |= 2u;        // paid from the time account: starts whatever the training stream does
         sif_status st = launch_op(c, op, c->I.stream, k);
         if (st != SIF_OK) {
           auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), j), q.end()); };
@@ -370,7 +413,8 @@ static void barrier_main(sif_ctx* c) {
         c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq)});
         j->next_op++;
         c->outstanding_us += cost;
-        if (gated && !online) c->balance[j->model] -= cost;
+        if (beside) c->conc_account_ns -= std::min<uint64_t>(c->conc_account_ns, 1000ull * cost);
+        else if (gated && !online) c->balance[j->model] -= cost;
         progressed = true;
       }
     }
@@ -449,6 +493,7 @@ sif_status sif_default_config(sif_config* cfg) {
   cfg->alg1.alpha = 1; cfg->alg1.beta = 3; cfg->alg1.gamma_num = 2; cfg->alg1.gamma_den = 1; cfg->alg1.m = 1;
   cfg->alg1.t0 = 200; cfg->alg1.ll = 400; cfg->alg1.ul = 800;
   cfg->kernel_us_max = 200; cfg->collocate = 1; cfg->device_timed_bubbles = 0; cfg->device_capacity_bytes = 0;
+  cfg->feedback = 0; cfg->feedback_eps_ppm = 20000; cfg->feedback_add_ppm = 20000; cfg->feedback_cap_ppm = 1000000;
   return SIF_OK;
 }
 
@@ -461,6 +506,7 @@ sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_str
   if (cfg->period_us == 0 || cfg->window == 0 || cfg->window > 1024) return fail(SIF_E_INVAL, "create: period_us > 0 and 1 <= window <= 1024");
   if (cfg->alg1.m == 0 || cfg->alg1.gamma_den == 0 || cfg->alg1.gamma_num == 0) return fail(SIF_E_INVAL, "create: alg1 m, gamma_num and gamma_den must be positive");
   if (cfg->alg1.alpha > cfg->alg1.beta || cfg->alg1.ll > cfg->alg1.ul) return fail(SIF_E_INVAL, "create: need alpha <= beta and LL <= UL");
+  if (cfg->feedback_cap_ppm > 1000000) return fail(SIF_E_INVAL, "create: feedback_cap_ppm is a share, at most 1000000");
   if ((uintptr_t)workspace_dev & 255) return fail(SIF_E_INVAL, "create: workspace must be 256-byte aligned");
   if (workspace_bytes < sif_ctx_workspace_bytes()) return fail(SIF_E_NOMEM, "create: workspace too small");
   std::unique_ptr<sif_ctx> c(new sif_ctx());
@@ -741,10 +787,16 @@ sif_status sif_calibrate(sif_ctx* c, uint32_t iters, const void* train_inputs_de
         }
       }
     }
-    const uint64_t s0 = mload(&c->mir->step_ticks_sum);
-    for (uint32_t i = 0; i < iters; ++i) { st = run_step(c, train_inputs_dev, train_targets_dev, nullptr); if (st != SIF_OK) return st; }
-    HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
-    c->step_solo_ns = c->ticks_to_ns((mload(&c->mir->step_ticks_sum) - s0) / iters);
+    // the solo iteration time: the shortest of `iters` steps, each measured on the device between its two markers
+    // (the first step after a pause of the stream tends to run long, which a mean over few steps would carry)
+    uint64_t best = ~0ull;
+    for (uint32_t i = 0; i < iters; ++i) {
+      st = run_step(c, train_inputs_dev, train_targets_dev, nullptr);
+      if (st != SIF_OK) return st;
+      HIPCHK(hipStreamSynchronize(c->T.stream), "calibrate: synchronize");
+      best = std::min(best, mload(&c->mir->step_ticks_last));
+    }
+    __atomic_store_n(&c->step_solo_ns, c->ticks_to_ns(best), __ATOMIC_RELAXED);
     // a bubble whose length the device decides: keep what the last solo step showed as its predicted length
     for (size_t i = 0; i < c->train->plan.size(); ++i) {
       Op& op = c->train->plan[i];
@@ -810,6 +862,7 @@ sif_status sif_poll_stats(sif_ctx* c, sif_stats* out) {
   if (out->struct_size != sizeof(sif_stats)) return fail(SIF_E_INVAL, "poll_stats: struct_size mismatch");
   const Mirror* m = c->mir;
   out->status_now = (uint32_t)c->status.load(); out->zc_now = c->zc.load(); out->tokens_now = c->grant.load();
+  out->concurrent_share_ppm = c->share_ppm.load();
   out->steps = mload(&m->steps);
   out->step_ns_sum = c->ticks_to_ns(mload(&m->step_ticks_sum));
   out->step_ns_last = c->ticks_to_ns(mload(&m->step_ticks_last));

@@ -98,4 +98,17 @@ uint64_t sif_dp_overlapped_wait(const uint64_t* ready_ns, const uint64_t* dur_ns
   return finish > end_ns ? finish - end_ns : 0;
 }
 
+uint32_t sif_feedback_share(uint32_t share_ppm, uint64_t step_ns, uint64_t ref_ns, uint32_t eps_ppm, uint32_t add_ppm, uint32_t cap_ppm) {
+  const unsigned __int128 lhs = (unsigned __int128)step_ns * 1000000u, rhs = (unsigned __int128)ref_ns * (1000000ull + eps_ppm);
+  if (lhs > rhs) return share_ppm / 2;
+  const uint64_t up = (uint64_t)share_ppm + add_ppm;
+  return (uint32_t)(up < cap_ppm ? up : cap_ppm);
+}
+
+uint64_t sif_concurrent_account(uint64_t balance_ns, uint32_t share_ppm, uint64_t period_ns, uint64_t burst_ns) {
+  const uint64_t gain = (uint64_t)(((unsigned __int128)period_ns * share_ppm) / 1000000u);
+  const uint64_t b = balance_ns + gain;
+  return b < burst_ns ? b : burst_ns;
+}
+
 }  // extern "C"

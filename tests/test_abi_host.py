@@ -112,6 +112,24 @@ def test_bucketed_gradient_exchange_matches_oracle():
         S.sif_dp_gradient_buckets([1, 2], 0)
 
 
+def test_feedback_rules_match_oracle():
+    from oracle import scheduler as OKS
+    rng = np.random.default_rng(9)
+    for _ in range(3000):
+        share = int(rng.integers(0, 1_000_001))
+        ref = int(rng.integers(1, 2 ** 40))
+        step = int(ref * (1 + rng.uniform(-0.1, 0.1))) if rng.random() < 0.8 else int(rng.integers(1, 2 ** 40))
+        eps, add, cap = int(rng.integers(0, 200_000)), int(rng.integers(0, 300_000)), int(rng.integers(0, 1_000_001))
+        assert S.sif_feedback_share(share, step, ref, eps, add, cap) == OKS.feedback_share(share, step, ref, eps, add, cap)
+        bal, period, burst = int(rng.integers(0, 10 ** 9)), int(rng.integers(1, 10 ** 7)), int(rng.integers(0, 10 ** 9))
+        assert S.sif_concurrent_account(bal, share, period, burst) == OKS.concurrent_account(bal, share, period, burst)
+    # the threshold itself is "not lengthened", one nanosecond more is
+    assert S.sif_feedback_share(400_000, 1_020_000, 1_000_000, 20_000, 0, 1_000_000) == 400_000
+    assert S.sif_feedback_share(400_000, 1_020_001, 1_000_000, 20_000, 0, 1_000_000) == 200_000
+    # products beyond 64 bits
+    assert S.sif_feedback_share(10, 2 ** 63, 2 ** 63 - 1, 0, 5, 100) == OKS.feedback_share(10, 2 ** 63, 2 ** 63 - 1, 0, 5, 100) == 5
+
+
 def test_param_layout_counts():
     from paper_2503_02550_amd import params as P
     from paper_2503_02550_amd.session import decoder_shape, encoder_shape, mlp_shape

@@ -452,3 +452,56 @@ def test_inference_fills_the_tail_of_an_overlapped_exchange():
             torch.cuda.synchronize()
             s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
             assert torch.equal(out, outs[i])
+
+
+# ---- concurrent filling with feedback: offline kernels run beside training, paced by a share of busy time
+def run_feedback(feedback, n_batches, steps=12):
+    shape, ishape = decoder_shape(DEC), encoder_shape(ENC)
+    cfg = S.sif_default_config()
+    cfg.feedback, cfg.feedback_add_ppm, cfg.feedback_eps_ppm, cfg.feedback_cap_ppm = (1 if feedback else 0), 250_000, 100_000, 750_000
+    with Session(cfg) as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=300_000)
+        m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)))
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        torch.cuda.synchronize()
+        S.sif_calibrate(s.ctx, 2, x, t)
+        n_cal = last_launch(s)
+        ids = [i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])) for i in range(n_batches)]
+        outs = [torch.zeros((ENC["batch"], ENC["seq"], ENC["d_model"]), device=DEV, dtype=torch.bfloat16) for _ in range(n_batches)]
+        torch.cuda.synchronize()
+        tickets = [s.submit_offline(m, ids[i], outs[i], ENC["batch"], ENC["seq"]) for i in range(n_batches)]
+        shares = []
+        for _ in range(steps):
+            s.step(x, t)
+            s.sync()
+            shares.append(s.stats().concurrent_share_ppm)
+        for tk in tickets:
+            s.wait(tk, 20.0)
+        return up(s.train["master"]), outs, s.stats(), bubbles_and_kernels(s, n_cal), shares
+
+
+def test_concurrent_filling_with_feedback_keeps_every_result_bit():
+    w_ref, _, _, _, _ = run_feedback(False, 0)
+    w_fb, outs, st, (bubbles, ran, skipped), shares = run_feedback(True, 24)
+    assert np.array_equal(w_ref, w_fb)                         # training does not see what runs beside it
+    assert st.offline_batches == 24
+    assert all(0 <= v <= 750_000 for v in shares) and max(shares) > 0
+    b0 = np.array([b[0] for b in bubbles]); b1 = np.array([b[1] for b in bubbles])
+    outside = 0
+    for t0, _ in ran:
+        i = np.searchsorted(b0, t0, side="right") - 1
+        outside += not (i >= 0 and b0[i] <= t0 <= b1[i])
+    assert outside > 0                                          # kernels did start while training was busy
+    assert st.filled_ns < st.infer_busy_ns
+    ishape = encoder_shape(ENC)
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)))
+        for i in (0, 11, 23):
+            I, out = i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])), torch.zeros_like(outs[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
+            assert torch.equal(out, outs[i])
+    # without the option the same load stays inside the bubbles
+    _, _, st0, (bubbles0, ran0, _), shares0 = run_feedback(False, 2)
+    assert_starts_inside_bubbles(bubbles0, ran0)
+    assert max(shares0) == 0

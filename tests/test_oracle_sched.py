@@ -255,13 +255,13 @@ def test_feedback_holds_a_linear_plant_near_its_threshold():
 
 
 def test_concurrent_account():
-    assert K.concurrent_account(0, 100_000, False, 25_000, 10 ** 9) == 2_500
-    assert K.concurrent_account(0, 100_000, True, 25_000, 10 ** 9) == 25_000        # an idle period counts in full
-    assert K.concurrent_account(190_000, 1_000_000, False, 25_000, 200_000) == 200_000   # burst cap
-    assert K.concurrent_account(7, 0, False, 25_000, 200_000) == 7                  # no share, nothing gained
+    assert K.concurrent_account(0, 100_000, 25_000, 10 ** 9) == 2_500
+    assert K.concurrent_account(0, 1_000_000, 25_000, 10 ** 9) == 25_000            # full share: the whole period
+    assert K.concurrent_account(190_000, 1_000_000, 25_000, 200_000) == 200_000     # burst cap
+    assert K.concurrent_account(7, 0, 25_000, 200_000) == 7                         # no share, nothing gained
     # n busy periods at a constant share: floor per period, so n * floor(period * share)
     b = 0
     for n in range(1, 50):
-        b = K.concurrent_account(b, 333_333, False, 25_000, 10 ** 9)
+        b = K.concurrent_account(b, 333_333, 25_000, 10 ** 9)
         assert b == n * (25_000 * 333_333 // K.PPM)
 
