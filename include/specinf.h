@@ -391,7 +391,7 @@ typedef struct sif_infer_desc {
   uint64_t peak_bytes;           /* declared peak memory of this instance (Principle-I)                 */
   uint32_t coalesce;             /* offline encoder models: up to this many queued requests of equal batch and seq
                                     are released as ONE kernel sequence over their concatenated rows (0 or 1 = each
-                                    request by itself, at most 4).  Every kernel of the forward pass treats rows (or
+                                    request by itself, at most 8).  Every kernel of the forward pass treats rows (or
                                     whole sequences) independently, so each request's output is bit-identical to a
                                     run by itself; the workspace is sized for coalesce * shape.batch rows.  Requests
                                     are never held back to wait for partners.                              */

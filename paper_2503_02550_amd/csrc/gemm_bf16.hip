@@ -150,7 +150,8 @@ struct DmaStream {
   }
   // fetches the next tile into `stage` (a whole tile buffer of ROWS x 64 elements)
   __device__ __forceinline__ void next(bf16_t* stage) {
-    const uint32_t wave = threadIdx.x >> 6;
+    // the LDS address of a fetch is taken from a scalar register: say that the wavefront number is uniform
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + voff[i]), (lds_void_ptr)(stage + i * (THREADS * 8) + wave * 512), 16, 0, 0);
@@ -217,6 +218,24 @@ __device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uin
   }
 }
 
+// Scheduling pipeline of one K step, from MFMA number G on (NS slices of NM MFMAs): after each MFMA its share of the
+// next slice's ND LDS reads and of the step's FETCHES global -> LDS fetches.
+template <int V> struct Int { static constexpr int value = V; };
+template <int NM, int ND, int NS, int FETCHES, int G>
+__device__ __forceinline__ void sched_pipeline() {
+  if constexpr (G < NS * NM) {
+    constexpr int ks = G / NM, m = G % NM;
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (ks + 1 < NS) {
+      constexpr int d0 = (m * ND) / NM, d1 = ((m + 1) * ND) / NM;
+      if constexpr (d1 > d0) __builtin_amdgcn_sched_group_barrier(0x100, d1 - d0, 0);
+    }
+    constexpr int f0 = (G * FETCHES) / (NS * NM), f1 = ((G + 1) * FETCHES) / (NS * NM);
+    if constexpr (f1 > f0) __builtin_amdgcn_sched_group_barrier(0x010, f1 - f0, 0);
+    sched_pipeline<NM, ND, NS, FETCHES, G + 1>();
+  }
+}
+
 template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE>
 __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
   constexpr int THREADS = 64 * WM * WN, TI = BM / (WM * 32), TJ = BN / (WN * 32), WCOLS = TJ * 32;
@@ -275,24 +294,38 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // into the set tile t has just left, so every global load has two iterations of MFMA work to hide behind.
     uint4 ra0[4], rb0[4], ra1[4], rb1[4];
     const uint32_t fra = wm * (TI * 32) + (lane & 31), frb = wn * (TJ * 32) + (lane & 31), kh = lane >> 5;
-    auto compute = [&](const bf16_t* cA, const bf16_t* cB) {
+    // Fragments of K slice ks + 1 are read from LDS into a second register set before the MFMAs of slice ks are
+    // issued, so that an LDS read has four MFMAs (128 cycles) to land behind instead of being waited for at once.
+    auto load_frags = [&](const bf16_t* cA, const bf16_t* cB, int ks, bf16x8 (&fa)[TI], bf16x8 (&fb)[TJ]) {
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        bf16x8 fa[TI], fb[TJ];
+      for (int i = 0; i < TI; ++i)
+        fa[i] = ALAY == 0 ? *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh))
+                          : kmajor_frag<BM>(cA, wm * (TI * 32) + i * 32, ks * 16 + kh * 8);
 #pragma unroll
-        for (int i = 0; i < TI; ++i)
-          fa[i] = ALAY == 0 ? *reinterpret_cast<const bf16x8*>(cA + lds_off(fra + i * 32, ks * 2 + kh))
-                            : kmajor_frag<BM>(cA, wm * (TI * 32) + i * 32, ks * 16 + kh * 8);
+      for (int j = 0; j < TJ; ++j)
+        fb[j] = BLAY == 0 ? *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + j * 32, ks * 2 + kh))
+                          : kmajor_frag<BN>(cB, wn * (TJ * 32) + j * 32, ks * 16 + kh * 8);
+    };
+    // `fetches` says how many global -> LDS fetches were issued just before (they sit in the same scheduling region).
+    // The order wanted for one K step: the reads of slice 0, then per slice its MFMAs with the LDS reads of the next
+    // slice and a share of the fetches spread evenly between them.  A wavefront issues in order, and a fetch that finds
+    // the memory pipeline full holds up the MFMAs behind it, so the fetches must not come in one burst (after a barrier
+    // every wavefront of the CU would issue its burst at the same time).
+    auto compute = [&](const bf16_t* cA, const bf16_t* cB, auto fetches) {
+      constexpr int NS = BK / 16, NM = TI * TJ, ND = (ALAY == 0 ? 1 : 2) * TI + (BLAY == 0 ? 1 : 2) * TJ;
+      bf16x8 fa[2][TI], fb[2][TJ];
+      load_frags(cA, cB, 0, fa[0], fb[0]);
 #pragma unroll
-        for (int j = 0; j < TJ; ++j)
-          fb[j] = BLAY == 0 ? *reinterpret_cast<const bf16x8*>(cB + lds_off(frb + j * 32, ks * 2 + kh))
-                            : kmajor_frag<BN>(cB, wn * (TJ * 32) + j * 32, ks * 16 + kh * 8);
+      for (int ks = 0; ks < NS; ++ks) {
+        if (ks + 1 < NS) load_frags(cA, cB, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
 #pragma unroll
         for (int i = 0; i < TI; ++i)
 #pragma unroll
           for (int j = 0; j < TJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
       }
+      __builtin_amdgcn_sched_group_barrier(0x100, ND, 0);                 // LDS reads of slice 0
+      sched_pipeline<NM, ND, NS, decltype(fetches)::value, 0>();
     };
     // The loop takes two K steps per trip (the register sets and LDS buffers alternate by name) and has no exit in
     // its middle, so that the accumulators stay in the same registers throughout; an odd last tile is done after it.
@@ -308,10 +341,10 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         ta.next(sA1); tb.next(sB1);
-        compute(sA0, sB0);
+        compute(sA0, sB0, Int<8>());
         __syncthreads();
         if (t + 2 < nt) { ta.next(sA0); tb.next(sB0); }
-        compute(sA1, sB1);
+        compute(sA1, sB1, Int<8>());
         __syncthreads();
       }
     } else if (EDGE) {
@@ -326,19 +359,19 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
         const uint32_t k0 = k_begin + t * BK;
         oka0 = load_tile<ALAY, THREADS, BM>(ra0, A, p.lda, m0, p.m, k0 + 2 * BK, k_end);
         okb0 = load_tile<BLAY, THREADS, BN>(rb0, B, p.ldb, n0, p.n, k0 + 2 * BK, k_end);
-        compute(sA0, sB0);
+        compute(sA0, sB0, Int<0>());
         store_tile<ALAY, THREADS, BM>(sA1, ra1, oka1);
         store_tile<BLAY, THREADS, BN>(sB1, rb1, okb1);
         __syncthreads();
         oka1 = load_tile<ALAY, THREADS, BM>(ra1, A, p.lda, m0, p.m, k0 + 3 * BK, k_end);
         okb1 = load_tile<BLAY, THREADS, BN>(rb1, B, p.ldb, n0, p.n, k0 + 3 * BK, k_end);
-        compute(sA1, sB1);
+        compute(sA1, sB1, Int<0>());
         store_tile<ALAY, THREADS, BM>(sA0, ra0, oka0);
         store_tile<BLAY, THREADS, BN>(sB0, rb0, okb0);
         __syncthreads();
       }
     }
-    if (nt & 1u) compute(sA0, sB0);
+    if (nt & 1u) compute(sA0, sB0, Int<0>());
 
     // Epilogue.  Each wavefront passes its accumulators, 32 rows at a time, through a staging area of its own in
     // LDS (fp32 [32][64], the operand buffers are free by now) so that every global access of the epilogue - bias,

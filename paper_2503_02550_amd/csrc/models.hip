@@ -787,7 +787,7 @@ sif_status build_infer_model(InferModel& im, hipStream_t stream) {
   sif_status st = check_shape(im.desc.shape, false);
   if (st != SIF_OK) return st;
   if (im.desc.shape.kind == SIF_MODEL_DECODER) return fail(SIF_E_INVAL, "inference model must be MLP or ENCODER");
-  if (im.desc.coalesce > 4) return fail(SIF_E_INVAL, "inference model: coalesce must be at most 4");
+  if (im.desc.coalesce > kMaxCoalesce) return fail(SIF_E_INVAL, "inference model: coalesce must be at most %u", kMaxCoalesce);
   im.n_params = model_n_params(im.desc.shape);
   Arena ar;
   ar.base = (unsigned char*)im.desc.workspace_dev;

@@ -116,6 +116,7 @@ struct InferIO { const void* in_dev; void* out_dev; };
 sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_io, uint32_t batch, uint32_t seq,
                             uint32_t kernel_us_max, Plan& out);
 uint32_t infer_coalesce(const sif_infer_desc& d);
+constexpr uint32_t kMaxCoalesce = 8;      // most requests one coalesced kernel sequence serves
 
 // markers.hip
 sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,

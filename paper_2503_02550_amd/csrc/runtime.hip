@@ -348,7 +348,7 @@ static void barrier_main(sif_ctx* c) {
               std::unique_ptr<Job> g(new Job());
               g->ticket = j->ticket; g->model = j->model; g->batch = j->batch * (uint32_t)parts.size(); g->seq = j->seq;
               g->t_arrival_ns = j->t_arrival_ns;
-              InferIO io[4];
+              InferIO io[kMaxCoalesce];
               for (size_t r = 0; r < parts.size(); ++r) io[r] = InferIO{parts[r]->in_dev, parts[r]->out_dev};
               if (build_infer_plan(im, io, (uint32_t)parts.size(), j->batch, j->seq, c->cfg.kernel_us_max, g->plan) == SIF_OK) {
                 g->parts = parts;
@@ -816,7 +816,7 @@ sif_status sif_calibrate(sif_ctx* c, uint32_t iters, const void* train_inputs_de
     im.calib_cost_us_n.assign(n_max, std::vector<double>());
     for (uint32_t n = 1; n <= n_max; ++n) {        // the plan of one request and of each number of coalesced requests
       Plan plan;
-      InferIO io[4];
+      InferIO io[kMaxCoalesce];
       const uint64_t rows1 = (uint64_t)batch * s.seq;
       for (uint32_t r = 0; r < n; ++r) {
         io[r].in_dev = (const unsigned char*)im.calib_in + (s.kind == SIF_MODEL_MLP ? 0 : r * rows1 * 4);
