@@ -456,10 +456,14 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   const bool can_big = !causal && (a->k % BK) == 0;
   if (a->tile != 0 && a->tile != 128 && a->tile != 256) return fail(SIF_E_INVAL, "gemm: tile must be 0, 128 or 256");
   if (a->tile == 256 && !can_big) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
-  // measured on gfx950: they win from about four rounds of tiles and K of 2048 on (8192 x 8192 x 2048: 937 against 867
-  // TFLOP/s, 8192^3: 1115 against 967); with fewer tiles or a short K their longer prologue and epilogue, which no
-  // second block on the CU overlaps, cost more than the main loop gains
-  const bool big = a->tile == 256 || (a->tile == 0 && can_big && tiles256 >= 1024 && a->k >= 2048);
+  // measured on gfx950: with one block per CU nothing overlaps their prologue and epilogue, and a last, partly filled
+  // round of tiles costs a whole round.  They win when at least two rounds of tiles fill the 256 CUs evenly
+  // (16384 x 3072 x 768: 81 against 98 us, 8192 x 50304 x 768: 753 against 1017 us, 8192^3: 1220 against 955
+  // TFLOP/s) or K is long (50304 x 768 x 8192, 2.3 rounds: 657 against 751 us); 2.25 rounds of a short K lose
+  // (16384 x 2304 x 768: 93 against 77 us).
+  const uint64_t rounds_up = (tiles256 + 255) / 256;
+  const bool even = tiles256 * 10 >= rounds_up * 256 * 9;           // the last round is at least 90 % full on average
+  const bool big = a->tile == 256 || (a->tile == 0 && can_big && tiles256 >= 512 && (even || a->k >= 4096));
   const uint32_t bm = big ? 256 : 128, bn = bm;
   GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;

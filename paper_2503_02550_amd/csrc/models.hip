@@ -97,7 +97,7 @@ struct Scratch { float* scores; bf16_t* ds; float* delta; bf16_t *dx_a, *dx_b, *
 static double gemm_cost_us(const sif_gemm_args& g) {
   double flops = 2.0 * g.m * g.n * g.k * g.batch_outer * g.batch_inner;
   if (g.k_causal || (g.epilogue & SIF_EPI_CAUSAL_SKIP)) flops *= 0.55;
-  return 4.0 + flops / 3.0e8;          // 300 TFLOP/s plus launch latency
+  return 4.0 + flops / 6.0e8;          // 600 TFLOP/s plus launch latency
 }
 static double bytes_cost_us(double bytes) { return 3.0 + bytes / 2.0e6; }   // 2 TB/s plus launch latency
 
