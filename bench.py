@@ -53,6 +53,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--coalesce", type=int, default=4, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
+    ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time)")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=2000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--dp-bucket-mb", type=float, default=0.0,
@@ -181,7 +182,7 @@ def main():
         online = {}
         with Session(cfg) as s:
             s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
-            mo = s.register_inference(oshape, enc_master, online=True)
+            mo = s.register_inference(oshape, enc_master, online=True, coalesce=args.online_coalesce)
             ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
             oids = to(Y.token_ids(7, 1, Y.ONLINE["seq_max"], enc["vocab"]), torch.int32)
             oouts = [torch.zeros((1, Y.ONLINE["seq_max"], enc["d_model"]), device=dev, dtype=torch.bfloat16) for _ in range(64)]

@@ -222,6 +222,11 @@ sif_status sif_k_softmax_bwd(const float* dp_dev, const void* p_dev, void* ds_de
  * receives log(sum_j exp(score_ij)) of the scaled, masked scores, which the backward pass needs. */
 sif_status sif_k_attn_fwd(const void* qkv_dev, void* o_dev, float* lse_dev, uint32_t batch, uint32_t seq, uint32_t heads,
                           uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream);
+/* The same for n_seqs sequences of unequal length stored back to back: sequence i occupies rows seq_starts[i] ..
+ * seq_starts[i+1] of qkv and o (seq_starts: HOST array of n_seqs + 1 ascending row numbers, read during the call;
+ * 1 <= n_seqs <= 64, no empty sequence).  Each sequence's result has the bits it has when run by itself. */
+sif_status sif_k_attn_fwd_varlen(const void* qkv_dev, void* o_dev, const uint32_t* seq_starts, uint32_t n_seqs, uint32_t heads,
+                                 uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream);
 /* Fused attention backward: dqkv [batch*seq][ld_dqkv] (columns [dq | dk | dv]) from qkv, the forward's o and lse and
  * the upstream gradient d_o [batch*seq][ld_o] (same layout and leading dimension as o).  The probabilities are
  * recomputed as exp(score - lse) and rounded to bf16, dS = P .* (dP - delta) / sqrt(dh) likewise, as the training
@@ -389,12 +394,15 @@ typedef struct sif_infer_desc {
   void* workspace_dev;           /* >= sif_infer_workspace_bytes(): working copy + activations          */
   uint64_t workspace_bytes;
   uint64_t peak_bytes;           /* declared peak memory of this instance (Principle-I)                 */
-  uint32_t coalesce;             /* offline encoder models: up to this many queued requests of equal batch and seq
-                                    are released as ONE kernel sequence over their concatenated rows (0 or 1 = each
-                                    request by itself, at most 8).  Every kernel of the forward pass treats rows (or
-                                    whole sequences) independently, so each request's output is bit-identical to a
-                                    run by itself; the workspace is sized for coalesce * shape.batch rows.  Requests
-                                    are never held back to wait for partners.                              */
+  uint32_t coalesce;             /* encoder models: up to this many queued requests are released as ONE kernel
+                                    sequence over their concatenated rows (0 or 1 = each request by itself, at most 8).
+                                    Offline: requests of equal batch and seq.  Online: the requests that wait at the
+                                    moment one is pulled, whatever their lengths (fewer if the predicted rest of the
+                                    bubble does not hold them all); attention is told where each sequence begins.
+                                    Every kernel of the forward pass treats rows (or whole sequences) independently,
+                                    so each request's output is bit-identical to a run by itself; the workspace is
+                                    sized for coalesce * shape.batch * shape.seq rows.  Requests are never held back
+                                    to wait for partners.                                                   */
   uint32_t reserved;
 } sif_infer_desc;
 

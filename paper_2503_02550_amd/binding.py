@@ -481,6 +481,15 @@ def sif_k_attn_fwd(qkv, o, batch, seq, heads, d_head, ld_qkv, ld_o, causal, lse=
                                     causal, stream_ptr(stream)))
 
 
+_sig("sif_k_attn_fwd_varlen", i32, vp, vp, P(u32), u32, u32, u32, u32, u32, u32, vp)
+
+
+def sif_k_attn_fwd_varlen(qkv, o, seq_starts, heads, d_head, ld_qkv, ld_o, causal, stream=None):
+    n = len(seq_starts) - 1
+    arr = (u32 * (n + 1))(*seq_starts)
+    return check(lib.sif_k_attn_fwd_varlen(ptr(qkv), ptr(o), arr, n, heads, d_head, ld_qkv, ld_o, causal, stream_ptr(stream)))
+
+
 def sif_k_attn_bwd(qkv, o, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv, causal, stream=None):
     return check(lib.sif_k_attn_bwd(ptr(qkv), ptr(o), ptr(d_o), ptr(lse), ptr(delta), ptr(dqkv), batch, seq, heads, d_head, ld_qkv, ld_o,
                                     ld_dqkv, causal, stream_ptr(stream)))

@@ -17,6 +17,7 @@
 // in one lane and its partner 32 further, and the softmax statistics are per-lane scalars.  bf16 operands, fp32
 // accumulation and softmax; P and dS are rounded to bf16 where the unfused path stores them.
 #include <math.h>
+#include <algorithm>
 
 #include "common.h"
 #include "launch.h"
@@ -78,18 +79,23 @@ __device__ __forceinline__ float at_round(float x) { return bf2f(f2bf(x)); }
 // of 128 through LDS (K and V as [kv][d]); running maximum / sum / rescale per lane.
 template <int DH, int CAUSAL>
 __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse,
-                                                              uint32_t S, uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, KCtl ctl) {
+                                                              uint32_t S, uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, AttnSeqs seqs,
+                                                              KCtl ctl) {
   constexpr int KS = DH / 16, DT = DH / 32;                   // k steps of q k^T, 32-wide d tiles
   __shared__ __align__(16) bf16_t sK[AT_KV * DH];
   __shared__ __align__(16) bf16_t sV[AT_KV * DH];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
   const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
-  const bf16_t* base = qkv + (size_t)b * S * ld_qkv + head * DH;
+  // sequences of equal length S back to back, or (seqs.n > 0) sequence b in rows seqs.start[b] .. seqs.start[b+1]
+  size_t row0 = (size_t)b * S;
+  if (seqs.n != 0) { row0 = seqs.start[b]; S = seqs.start[b + 1] - seqs.start[b]; }
+  const bf16_t* base = qkv + row0 * ld_qkv + head * DH;
   // with a causal mask the last query block has the most keys: the grid's slow index is the query block, reversed,
   // so that the long blocks of every (batch, head) start first
   const uint32_t q_blk = (CAUSAL ? gridDim.y - 1 - blockIdx.y : blockIdx.y) * AT_Q, qw = q_blk + wave * 32, q = qw + qi;
   const float c2 = scale * 1.44269504088896f;
+  if (q_blk >= S) { kernel_end(ctl, true); return; }       // the grid is sized for the longest sequence
 
   bf16x8 fq[KS];
   {
@@ -186,7 +192,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
 
   if (q < S) {
     const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
-    bf16_t* op = o + ((size_t)b * S + q) * ld_o + head * DH;
+    bf16_t* op = o + (row0 + q) * ld_o + head * DH;
 #pragma unroll
     for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -419,11 +425,40 @@ sif_status launch_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch,
   if (!al16(qkv) || !al16(o)) return fail(SIF_E_INVAL, "attn_fwd: pointers must be 16-byte aligned");
   const float scale = 1.0f / sqrtf((float)d_head);
   dim3 grid(batch * heads, (seq + AT_Q - 1) / AT_Q);
-#define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_fwd_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, heads, ld_qkv, ld_o, scale, c)
+  AttnSeqs seqs;
+  seqs.n = 0;
+#define AT_LAUNCH(DH, C) hipLaunchKernelGGL((attn_fwd_kernel<DH, C>), grid, dim3(AT_THREADS), 0, s, (const bf16_t*)qkv, (bf16_t*)o, lse, seq, heads, ld_qkv, ld_o, scale, seqs, c)
+  if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
+  else { if (causal) AT_LAUNCH(128, 1); else AT_LAUNCH(128, 0); }
+  return check_launch("attn_fwd");
+}
+
+sif_status launch_attn_fwd_varlen(const void* qkv, void* o, const uint32_t* starts, uint32_t n_seqs, uint32_t heads, uint32_t d_head,
+                                  uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c) {
+  if (!qkv || !o || !starts) return fail(SIF_E_INVAL, "attn_fwd_varlen: null operand");
+  if (n_seqs == 0 || n_seqs > kAttnMaxSeqs) return fail(SIF_E_INVAL, "attn_fwd_varlen: 1 to %u sequences", kAttnMaxSeqs);
+  AttnSeqs seqs;
+  seqs.n = n_seqs;
+  uint32_t longest = 0;
+  for (uint32_t i = 0; i <= n_seqs; ++i) {
+    seqs.start[i] = starts[i];
+    if (i > 0) {
+      if (starts[i] <= starts[i - 1]) return fail(SIF_E_INVAL, "attn_fwd_varlen: sequence starts must ascend (no empty sequence)");
+      longest = std::max(longest, starts[i] - starts[i - 1]);
+    }
+  }
+  for (uint32_t i = n_seqs + 1; i <= kAttnMaxSeqs; ++i) seqs.start[i] = starts[n_seqs];
+  if (sif_status st = attn_check("attn_fwd_varlen", n_seqs, longest, heads, d_head)) return st;
+  if ((ld_qkv & 7) || (ld_o & 7) || ld_qkv < 3 * heads * d_head || ld_o < heads * d_head) return fail(SIF_E_INVAL, "attn_fwd_varlen: bad leading dimensions");
+  if (!al16(qkv) || !al16(o)) return fail(SIF_E_INVAL, "attn_fwd_varlen: pointers must be 16-byte aligned");
+  const float scale = 1.0f / sqrtf((float)d_head);
+  float* lse = nullptr;
+  const uint32_t seq = longest;
+  dim3 grid(n_seqs * heads, (longest + AT_Q - 1) / AT_Q);
   if (d_head == 64) { if (causal) AT_LAUNCH(64, 1); else AT_LAUNCH(64, 0); }
   else { if (causal) AT_LAUNCH(128, 1); else AT_LAUNCH(128, 0); }
 #undef AT_LAUNCH
-  return check_launch("attn_fwd");
+  return check_launch("attn_fwd_varlen");
 }
 
 static sif_status attn_bwd_check(const char* who, const void* qkv, const void* o, const void* d_o, const float* lse, const float* delta,

@@ -52,6 +52,11 @@ sif_status sif_k_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch, 
   return launch_attn_fwd(qkv, o, lse, batch, seq, heads, d_head, ld_qkv, ld_o, causal, S(stream), no_ctl());
 }
 
+sif_status sif_k_attn_fwd_varlen(const void* qkv, void* o, const uint32_t* seq_starts, uint32_t n_seqs, uint32_t heads, uint32_t d_head,
+                                 uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, void* stream) {
+  return launch_attn_fwd_varlen(qkv, o, seq_starts, n_seqs, heads, d_head, ld_qkv, ld_o, causal, S(stream), no_ctl());
+}
+
 sif_status sif_k_attn_bwd(const void* qkv, const void* o, const void* d_o, const float* lse, float* delta, void* dqkv, uint32_t batch,
                           uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal,
                           void* stream) {

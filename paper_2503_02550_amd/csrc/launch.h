@@ -33,6 +33,12 @@ sif_status launch_softmax_fwd(const float* sc, void* p, uint32_t batch, uint32_t
                               uint32_t ld_p, uint32_t causal, hipStream_t s, const KCtl& c);
 sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t batch, uint32_t rows, uint32_t cols,
                               uint32_t ld, float scale, uint32_t causal, hipStream_t s, const KCtl& c);
+// Sequences of unequal length in one attention launch: sequence i occupies rows start[i] .. start[i+1] (n = 0:
+// equal lengths, see launch_attn_fwd)
+constexpr uint32_t kAttnMaxSeqs = 64;
+struct AttnSeqs { uint32_t n; uint32_t start[kAttnMaxSeqs + 1]; };
+sif_status launch_attn_fwd_varlen(const void* qkv, void* o, const uint32_t* starts, uint32_t n_seqs, uint32_t heads, uint32_t d_head,
+                                  uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c);
 sif_status launch_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head,
                            uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c);
 sif_status launch_attn_bwd_dq(const void* qkv, const void* o, const void* d_o, const float* lse, float* delta, void* dqkv, uint32_t batch,

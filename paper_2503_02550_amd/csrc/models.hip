@@ -771,7 +771,7 @@ static uint64_t layout_infer(InferModel& im, Arena& ar) {
 }
 
 uint32_t infer_coalesce(const sif_infer_desc& d) {
-  if (d.online || d.shape.kind != SIF_MODEL_ENCODER || d.coalesce < 2) return 1;
+  if (d.shape.kind != SIF_MODEL_ENCODER || d.coalesce < 2) return 1;
   return d.coalesce;
 }
 
@@ -827,8 +827,22 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
   // n_io requests of batch x seq rows each run as one sequence over their concatenated rows: every kernel below treats
   // rows (LayerNorm, GEMM) or whole sequences (attention) independently, so a request's result does not depend on
   // what it is concatenated with.  Only the first and the last kernel touch the requests' own buffers.
-  const Dims q = dims_of(s, batch * n_io, seq);
-  const uint32_t M = q.M, d = q.d, M1 = batch * seq;
+  // Requests of one sequence each may differ in length: their rows still lie back to back, and attention is told where
+  // each sequence begins.
+  Dims q = dims_of(s, batch * n_io, seq);
+  std::vector<uint32_t> rows_of(n_io), row0(n_io + 1, 0);
+  bool ragged = false;
+  for (uint32_t r = 0; r < n_io; ++r) {
+    const uint32_t sr = io[r].seq ? io[r].seq : seq;
+    if (sr == 0 || sr > seq) return fail(SIF_E_INVAL, "submit: a request's seq must be in 1..%u", seq);
+    ragged = ragged || sr != seq;
+    rows_of[r] = batch * sr;
+    row0[r + 1] = row0[r] + rows_of[r];
+  }
+  if (ragged && (batch != 1 || !(q.dh == 64 || q.dh == 128) || n_io > kAttnMaxSeqs))
+    return fail(SIF_E_INVAL, "submit: requests of different lengths need batch 1 and d_head 64 or 128");
+  q.M = row0[n_io];
+  const uint32_t M = q.M, d = q.d;
   const bf16_t* W = (const bf16_t*)im.work;
   bf16_t *x = (bf16_t*)im.bufs.at("x"), *t = (bf16_t*)im.bufs.at("t"), *x1 = (bf16_t*)im.bufs.at("x1"), *qkv = (bf16_t*)im.bufs.at("qkv");
   bf16_t *prob = (bf16_t*)im.bufs.at("prob"), *o = (bf16_t*)im.bufs.at("o"), *a = (bf16_t*)im.bufs.at("a");
@@ -836,8 +850,9 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
   const bf16_t *wte = W + pm.at("wte"), *wpe = W + pm.at("wpe"), *eg = W + pm.at("emb_ln_g"), *eb = W + pm.at("emb_ln_b");
   for (uint32_t r = 0; r < n_io; ++r) {
     const int32_t* ids = (const int32_t*)io[r].in_dev;
-    bf16_t* tr = t + (size_t)r * M1 * d;
-    emit(p, "embed", bytes_cost_us(6.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd(ids, wte, wpe, tr, M1, seq, d, st, c); });
+    bf16_t* tr = t + (size_t)row0[r] * d;
+    const uint32_t M1 = rows_of[r], sr = M1 / batch;
+    emit(p, "embed", bytes_cost_us(6.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd(ids, wte, wpe, tr, M1, sr, d, st, c); });
   }
   emit(p, "emb_ln", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, eg, eb, x, nullptr, nullptr, M, d, st, c); });
   for (uint32_t l = 0; l < s.n_layers; ++l) {
@@ -849,8 +864,13 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
     if (q.dh == 64 || q.dh == 128) {
       // one fused kernel: scores stay on chip, two launches fewer per layer
       const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh, da = q.da;
-      emit(p, "attn_fused", 4.0 + 4.0 * B * H * (double)S * S * dh / 3.0e8 + bytes_cost_us(8.0 * M * da),
-           [=](hipStream_t st, const KCtl& c) { return launch_attn_fwd(qkv, o, nullptr, B, S, H, dh, 3 * da, da, 0, st, c); });
+      const double cost = 4.0 + 4.0 * B * H * (double)S * S * dh / 3.0e8 + bytes_cost_us(8.0 * M * da);
+      if (ragged) {
+        const std::vector<uint32_t> starts = row0;
+        emit(p, "attn_fused", cost, [=](hipStream_t st, const KCtl& c) { return launch_attn_fwd_varlen(qkv, o, starts.data(), n_io, H, dh, 3 * da, da, 0, st, c); });
+      } else {
+        emit(p, "attn_fused", cost, [=](hipStream_t st, const KCtl& c) { return launch_attn_fwd(qkv, o, nullptr, B, S, H, dh, 3 * da, da, 0, st, c); });
+      }
     } else {
       emit_attention_fwd(p, q, qkv, scores, prob, o, false);
     }
@@ -862,8 +882,9 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
       emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g2, be2, x, nullptr, nullptr, M, d, st, c); });
     } else {
       for (uint32_t r = 0; r < n_io; ++r) {
-        const bf16_t* tr = t + (size_t)r * M1 * d;
+        const bf16_t* tr = t + (size_t)row0[r] * d;
         void* y = io[r].out_dev;
+        const uint32_t M1 = rows_of[r];
         emit(p, "ln2", bytes_cost_us(4.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(tr, g2, be2, y, nullptr, nullptr, M1, d, st, c); });
       }
     }

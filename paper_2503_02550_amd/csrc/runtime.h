@@ -111,8 +111,9 @@ uint64_t model_n_params(const sif_model_shape& s);
 sif_status build_train_model(TrainModel& tm, hipStream_t stream);
 uint64_t infer_workspace_bytes(const sif_infer_desc& d);
 sif_status build_infer_model(InferModel& im, hipStream_t stream);
-struct InferIO { const void* in_dev; void* out_dev; };
-// One kernel sequence for `n_io` requests of `batch` x `seq` each (n_io > 1: encoder models only)
+struct InferIO { const void* in_dev; void* out_dev; uint32_t seq = 0; };      // seq: this request's own length (0 = the common one)
+// One kernel sequence for `n_io` requests of `batch` x `seq` each (n_io > 1: encoder models only).  Requests of one
+// sequence each (batch = 1) may differ in length (InferIO::seq); `seq` is then the longest.
 sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_io, uint32_t batch, uint32_t seq,
                             uint32_t kernel_us_max, Plan& out);
 uint32_t infer_coalesce(const sif_infer_desc& d);

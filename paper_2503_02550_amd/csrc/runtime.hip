@@ -317,12 +317,43 @@ static void barrier_main(sif_ctx* c) {
         // idle and the predicted rest of the bubble, less what the requests already pulled still need, holds it.
         while (into_bubbles && !c->online_q.empty() && c->run_online.size() < 8) {
           Job* j = c->online_q.front();
-          const uint64_t need = (uint64_t)(job_cost_us(j) * 1000.0);
           uint64_t pending = 0;
           for (const Job* q : c->run_online)
             for (size_t i = q->done_ops; i < q->plan.size(); ++i) pending += (uint64_t)(q->plan[i].cost_us * 1000.0);
           const uint64_t rest = predicted_remaining_ns(c);
-          if (gated && !sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), rest > pending ? rest - pending : 0, need)) break;
+          const uint64_t room = rest > pending ? rest - pending : 0;
+          // Requests of the same instance that wait behind it may run with it as one kernel sequence (their rows back
+          // to back, whatever their lengths): as many as are queued, fewer if the rest of the bubble does not hold them.
+          const InferModel& im = *c->models[j->model];
+          size_t n = 1;
+          while (n < infer_coalesce(im.desc) && n < c->online_q.size() && c->online_q[n]->model == j->model) ++n;
+          std::unique_ptr<Job> g;
+          for (; n > 1; n = (n + 1) / 2) {
+            g.reset(new Job());
+            g->ticket = j->ticket; g->model = j->model; g->online = true; g->batch = 1; g->t_arrival_ns = j->t_arrival_ns;
+            InferIO io[kMaxCoalesce];
+            uint32_t longest = 0, rows = 0;
+            for (size_t r = 0; r < n; ++r) {
+              const Job* q = c->online_q[r];
+              io[r].in_dev = q->in_dev; io[r].out_dev = q->out_dev; io[r].seq = q->seq;
+              longest = std::max(longest, q->seq);
+              rows += q->seq;
+            }
+            if (build_infer_plan(im, io, (uint32_t)n, 1, longest, c->cfg.kernel_us_max, g->plan) != SIF_OK) { g.reset(); continue; }
+            g->seq = rows;                 // the calibrated costs scale with the rows the sequence covers
+            g->parts.assign(c->online_q.begin(), c->online_q.begin() + (ptrdiff_t)n);
+            apply_calibration(im, *g);
+            if (!gated || sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), room, (uint64_t)(job_cost_us(g.get()) * 1000.0))) break;
+            g.reset();
+          }
+          if (g) {
+            for (size_t r = 0; r < n; ++r) { c->online_q.front()->plan.clear(); c->online_q.pop_front(); }
+            c->run_online.push_back(g.get());
+            c->groups.push_back(std::move(g));
+            continue;
+          }
+          const uint64_t need = (uint64_t)(job_cost_us(j) * 1000.0);
+          if (gated && !sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), room, need)) break;
           c->online_q.pop_front();
           c->run_online.push_back(j);
         }
@@ -690,7 +721,10 @@ static void apply_calibration(const InferModel& im, Job& j) {
   if (n > im.calib_cost_us_n.size() || im.calib_batch == 0) return;
   const std::vector<double>& cal = im.calib_cost_us_n[n - 1];
   if (cal.size() != j.plan.size()) return;
-  const double scale = ((double)j.batch * (j.seq ? j.seq : 1)) / ((double)im.calib_batch * (im.calib_seq ? im.calib_seq : 1));
+  // rows this job covers against the rows the calibration run covered (a coalesced job of requests of different
+  // lengths carries its total row count in seq, with batch 1)
+  const bool ragged_group = j.online && n > 1;
+  const double scale = ((double)j.batch * (j.seq ? j.seq : 1)) / ((double)im.calib_batch * (ragged_group ? n : 1) * (im.calib_seq ? im.calib_seq : 1));
   for (size_t i = 0; i < j.plan.size(); ++i) {
     const double base = cal[i];
     j.plan[i].cost_us = std::max(1.0, 2.0 + (base - 2.0) * scale);

@@ -505,3 +505,50 @@ def test_concurrent_filling_with_feedback_keeps_every_result_bit():
     _, _, st0, (bubbles0, ran0, _), shares0 = run_feedback(False, 2)
     assert_starts_inside_bubbles(bubbles0, ran0)
     assert max(shares0) == 0
+
+
+def test_online_requests_that_wait_together_run_as_one_sequence():
+    """Online requests of different lengths that are queued when one is pulled run as one kernel sequence over their
+    rows laid back to back; each output has the bits of a run by itself, every kernel still starts inside a bubble,
+    and far fewer kernels are launched than one sequence per request would take."""
+    enc = dict(ENC, batch=1, seq=64)
+    shape, ishape = decoder_shape(DEC), encoder_shape(enc)
+    master = Y.encoder_params(2, enc, perturb=True)
+    lens = [64, 5, 33, 17, 64, 48, 1, 29, 60, 12, 7, 40]
+    n_req = len(lens)
+    per_request = 2 + 7 * enc["n_layers"]                    # embed, its LayerNorm, seven kernels per layer
+    cfg = S.sif_default_config()
+    cfg.collocate = 0
+    with Session(cfg) as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=2_000_000)
+        m = s.register_inference(ishape, P.pack(ishape, master), online=True, coalesce=8)
+        assert S.sif_calibrate(s.ctx, 2) == S.SIF_OK
+        n_cal = last_launch(s)
+        ids = [i32(Y.token_ids(300 + i, 1, lens[i], enc["vocab"])) for i in range(n_req)]
+        outs = [torch.zeros((1, lens[i], enc["d_model"]), device=DEV, dtype=torch.bfloat16) for i in range(n_req)]
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        torch.cuda.synchronize()
+        tickets = [s.submit_online(m, ids[i], outs[i], lens[i]) for i in range(n_req)]      # all wait before the first bubble
+        S.sif_reset_stats(s.ctx)
+        S.sif_set_collocate(s.ctx, 1)
+        for _ in range(8):
+            s.step(x, t)
+        s.sync()
+        for tk in tickets:
+            s.wait(tk, 20.0)
+        st = s.stats()
+        bubbles, ran, skipped = bubbles_and_kernels(s, n_cal)
+        assert st.online_done == n_req
+        assert_starts_inside_bubbles(bubbles, ran)
+        assert len(ran) < n_req * per_request // 2, (len(ran), n_req * per_request)
+    w = OE.working_copy(master, "bf16")
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, master), online=True)
+        for i in range(n_req):
+            idn = Y.token_ids(300 + i, 1, lens[i], enc["vocab"])
+            I, out = i32(idn), torch.zeros_like(outs[i])
+            torch.cuda.synchronize()
+            s.wait(s.submit_online(m, I, out, lens[i]))
+            assert torch.equal(out, outs[i]), i
+            if i in (0, 6, 9):
+                assert_bf16_close(up(outs[i]), OE.encoder_forward(w, idn, enc, "bf16"), "coalesced online request", elem_slack=1.5e-2)

@@ -301,6 +301,34 @@ def test_fused_attention_forward(bsz, s, h, dh, causal):
 
 
 @pytest.mark.parametrize("causal", [0, 1])
+@pytest.mark.parametrize("lens,h,dh", [([5, 130, 1, 64], 2, 64), ([256, 33, 129, 128, 7, 200, 32, 255], 3, 64), ([40], 2, 128), ([300, 17], 1, 128)])
+def test_fused_attention_forward_sequences_of_unequal_length(lens, h, dh, causal):
+    """Sequences stored back to back: each one's result is the oracle's for that sequence alone, and has the very bits
+    of a launch that holds only that sequence; rows of the output that belong to no sequence are not written."""
+    from oracle.decoder import attention_fwd
+    from oracle.numerics import Prec
+    da, total = h * dh, sum(lens)
+    qkv = rnd(43, total + 3, 3 * da)                       # three rows after the last sequence
+    Q = bf(qkv)
+    o = torch.full((total + 3, da), 3.0, device=DEV, dtype=torch.bfloat16)
+    starts = [0]
+    for n in lens:
+        starts.append(starts[-1] + n)
+    S.sif_k_attn_fwd_varlen(Q, o, starts, h, dh, 3 * da, da, causal)
+    got = up(o)
+    assert np.all(got[total:] == 3.0)
+    for i, n in enumerate(lens):
+        rows = slice(starts[i], starts[i + 1])
+        ref, _ = attention_fwd(q(qkv[rows])[None], h, dh, bool(causal), Prec("bf16"))
+        assert_bf16_close(got[rows], ref[0], f"sequence {i} of {lens}, dh={dh} causal={causal}", elem_slack=4e-3)
+        alone = torch.zeros((n, da), device=DEV, dtype=torch.bfloat16)
+        S.sif_k_attn_fwd(Q[rows].contiguous(), alone, 1, n, h, dh, 3 * da, da, causal)
+        assert np.array_equal(got[rows], up(alone))
+    with pytest.raises(S.SifError):
+        S.sif_k_attn_fwd_varlen(Q, o, [0, 5, 5], h, dh, 3 * da, da, causal)          # an empty sequence
+
+
+@pytest.mark.parametrize("causal", [0, 1])
 @pytest.mark.parametrize("bsz,s,h,dh", [(2, 5, 2, 64), (3, 37, 2, 64), (2, 128, 3, 64), (2, 200, 2, 64), (1, 300, 2, 128), (2, 64, 1, 128),
                                         (1, 520, 1, 64)])
 def test_fused_attention_backward(bsz, s, h, dh, causal):
