@@ -721,10 +721,9 @@ static void apply_calibration(const InferModel& im, Job& j) {
   if (n > im.calib_cost_us_n.size() || im.calib_batch == 0) return;
   const std::vector<double>& cal = im.calib_cost_us_n[n - 1];
   if (cal.size() != j.plan.size()) return;
-  // rows this job covers against the rows the calibration run covered (a coalesced job of requests of different
-  // lengths carries its total row count in seq, with batch 1)
-  const bool ragged_group = j.online && n > 1;
-  const double scale = ((double)j.batch * (j.seq ? j.seq : 1)) / ((double)im.calib_batch * (ragged_group ? n : 1) * (im.calib_seq ? im.calib_seq : 1));
+  // rows this job covers against the rows the calibration run of n requests covered (a coalesced offline job carries
+  // n times the batch, one of online requests of different lengths its total row count in seq with batch 1)
+  const double scale = ((double)j.batch * (j.seq ? j.seq : 1)) / ((double)im.calib_batch * n * (im.calib_seq ? im.calib_seq : 1));
   for (size_t i = 0; i < j.plan.size(); ++i) {
     const double base = cal[i];
     j.plan[i].cost_us = std::max(1.0, 2.0 + (base - 2.0) * scale);
