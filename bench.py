@@ -52,7 +52,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--coalesce", type=int, default=4, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
+    ap.add_argument("--coalesce", type=int, default=8, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time)")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=2000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
