@@ -18,7 +18,10 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 }
 
 // ---------------------------------------------------------------------------------------------- LayerNorm
-// One wavefront per row, 4 rows per block.
+// One wavefront per row, 4 rows per block.  MAXV > 0: the row (at most MAXV vectors of 8 columns per lane) is read
+// once and kept in registers for the three passes (mean, variance, output); MAXV = 0: any width, three reads.
+// Both variants add in the same order, so they give the same bits.
+template <int MAXV>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
                                                             const bf16_t* __restrict__ b, bf16_t* __restrict__ y,
                                                             float* __restrict__ mean_out, float* __restrict__ rstd_out,
@@ -27,20 +30,50 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __rest
   const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, nv = d >> 3;
   if (row < rows) {
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
-    float s = 0.f, f[8];
-    for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) s += f[i]; }
-    const float mean = wave_sum(s) / (float)d;
-    float q = 0.f;
-    for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) { float t = f[i] - mean; q += t * t; } }
-    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + kLnEps);
     uint4* yr = reinterpret_cast<uint4*>(y + (size_t)row * d);
-    for (uint32_t v = lane; v < nv; v += 64) {
-      float fg[8], fb[8], o[8];
-      unpack8(xr[v], f); unpack8(reinterpret_cast<const uint4*>(g)[v], fg); unpack8(reinterpret_cast<const uint4*>(b)[v], fb);
-      for (int i = 0; i < 8; ++i) o[i] = (f[i] - mean) * rstd * fg[i] + fb[i];
-      yr[v] = pack8(o);
+    float s = 0.f, f[8];
+    if constexpr (MAXV > 0) {
+      uint4 cx[MAXV], cg[MAXV], cb[MAXV];
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t) {
+        const uint32_t v = lane + 64 * t;
+        const bool in = v < nv;
+        cx[t] = in ? xr[v] : make_uint4(0, 0, 0, 0);
+        cg[t] = in ? reinterpret_cast<const uint4*>(g)[v] : make_uint4(0, 0, 0, 0);
+        cb[t] = in ? reinterpret_cast<const uint4*>(b)[v] : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t)
+        if (lane + 64 * t < nv) { unpack8(cx[t], f); for (int i = 0; i < 8; ++i) s += f[i]; }
+      const float mean = wave_sum(s) / (float)d;
+      float q = 0.f;
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t)
+        if (lane + 64 * t < nv) { unpack8(cx[t], f); for (int i = 0; i < 8; ++i) { float u = f[i] - mean; q += u * u; } }
+      const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + kLnEps);
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t)
+        if (lane + 64 * t < nv) {
+          float fg[8], fb[8], o[8];
+          unpack8(cx[t], f); unpack8(cg[t], fg); unpack8(cb[t], fb);
+          for (int i = 0; i < 8; ++i) o[i] = (f[i] - mean) * rstd * fg[i] + fb[i];
+          yr[lane + 64 * t] = pack8(o);
+        }
+      if (lane == 0 && mean_out != nullptr) { mean_out[row] = mean; rstd_out[row] = rstd; }
+    } else {
+      for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) s += f[i]; }
+      const float mean = wave_sum(s) / (float)d;
+      float q = 0.f;
+      for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) { float t = f[i] - mean; q += t * t; } }
+      const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + kLnEps);
+      for (uint32_t v = lane; v < nv; v += 64) {
+        float fg[8], fb[8], o[8];
+        unpack8(xr[v], f); unpack8(reinterpret_cast<const uint4*>(g)[v], fg); unpack8(reinterpret_cast<const uint4*>(b)[v], fb);
+        for (int i = 0; i < 8; ++i) o[i] = (f[i] - mean) * rstd * fg[i] + fb[i];
+        yr[v] = pack8(o);
+      }
+      if (lane == 0 && mean_out != nullptr) { mean_out[row] = mean; rstd_out[row] = rstd; }
     }
-    if (lane == 0 && mean_out != nullptr) { mean_out[row] = mean; rstd_out[row] = rstd; }
   }
   kernel_end(ctl, true);
 }
@@ -577,8 +610,10 @@ sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, voi
   REQ(x && g && b && y && rows > 0 && d > 0, "layernorm_fwd: null or empty");
   REQ((d & 7) == 0 && al16(x) && al16(g) && al16(b) && al16(y), "layernorm_fwd: d must be a multiple of 8, pointers 16-byte aligned");
   REQ((mean == nullptr) == (rstd == nullptr), "layernorm_fwd: mean and rstd go together");
-  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g,
-                     (const bf16_t*)b, (bf16_t*)y, mean, rstd, rows, d, c);
+#define LNF(V) hipLaunchKernelGGL((layernorm_fwd_kernel<V>), dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, \
+                                  (const bf16_t*)b, (bf16_t*)y, mean, rstd, rows, d, c)
+  if (d <= 1024) LNF(2); else if (d <= 2048) LNF(4); else LNF(0);
+#undef LNF
   return check_launch("layernorm_fwd");
 }
 
