@@ -213,8 +213,7 @@ __device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
   const uint32_t done = r->completed + 1;
   st_relaxed(&r->completed, done);
   if ((c.kind_id >> 28) == kKindTrain) {
-    st_sys_relaxed(&m->t_completed, done);
-    st_sys_relaxed(&m->train_kernels, ++r->train_kernels);
+    st_sys_relaxed(&m->t_completed, done);          // also the count of training kernels run (the host takes differences)
   } else {
     uint64_t dur = t1 - t0, fill = dur;
     if (c.gate != nullptr) {
@@ -223,11 +222,17 @@ __device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
       const uint64_t lo = t0 > ib ? t0 : ib, hi = t1 < end ? t1 : end;
       fill = hi > lo ? hi - lo : 0;
     }
-    st_sys_relaxed(&m->infer_ticks, r->infer_ticks += dur);
-    st_sys_relaxed(&m->filled_ticks, r->filled_ticks += fill);
-    st_sys_relaxed(&m->kernels_run, ++r->kernels_run);
-    // the last kernel of a job publishes with release order (its results must be visible before the host reports the
-    // job done); the others only report progress
+    r->infer_ticks += dur;
+    r->filled_ticks += fill;
+    ++r->kernels_run;
+    // The statistics travel to the host mailbox with the last kernel of a job and with every eighth launch (each
+    // store to host memory lengthens the end of the kernel); the progress word travels every time.  The last kernel
+    // of a job publishes it with release order (its results must be visible before the host reports the job done).
+    if ((c.flags & 1u) || (c.kseq & 7u) == 0u) {
+      st_sys_relaxed(&m->infer_ticks, r->infer_ticks);
+      st_sys_relaxed(&m->filled_ticks, r->filled_ticks);
+      st_sys_relaxed(&m->kernels_run, r->kernels_run);
+    }
     if (c.flags & 1u) st_sys(&m->i_done, c.kseq); else st_sys_relaxed(&m->i_done, c.kseq);
   }
 }

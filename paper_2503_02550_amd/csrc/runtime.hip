@@ -79,6 +79,7 @@ struct sif_ctx {
   std::atomic<uint64_t> offline_samples{0}, offline_batches{0}, online_done{0}, kernels_launched{0}, periods{0};
   std::atomic<uint64_t> gate_violations{0};
   uint64_t step_solo_ns = 0;
+  uint32_t train_kernels_base = 0;          // completed training kernels at the last sif_reset_stats
   // concurrent filling with feedback: the share is set by the monitor thread after every training iteration, the
   // time account is kept by the barrier thread
   std::atomic<uint32_t> share_ppm{0};
@@ -908,7 +909,7 @@ sif_status sif_poll_stats(sif_ctx* c, sif_stats* out) {
   out->kernels_launched = c->kernels_launched.load();
   out->kernels_skipped = mload(&m->kernels_skipped);
   out->kernels_run = mload(&m->kernels_run);
-  out->train_kernels = mload(&m->train_kernels);
+  out->train_kernels = (uint32_t)(mload(&m->t_completed) - c->train_kernels_base);
   out->gate_violations = c->gate_violations.load() + mload(&m->gate_timeouts);
   out->periods = c->periods.load();
   out->online_p50_ns = out->online_p95_ns = 0;
@@ -935,7 +936,8 @@ sif_status sif_reset_stats(sif_ctx* c) {
   HIPCHK(hipMemset((unsigned char*)c->I.rec + off, 0, len), "reset_stats");
   Mirror* m = c->mir;
   m->steps = m->step_ticks_sum = m->step_ticks_last = m->bubble_ticks = m->filled_ticks = m->infer_ticks = 0;
-  m->kernels_run = m->kernels_skipped = m->train_kernels = 0;
+  m->kernels_run = m->kernels_skipped = 0;
+  c->train_kernels_base = mload(&m->t_completed);
   c->offline_samples = 0; c->offline_batches = 0; c->online_done = 0; c->kernels_launched = 0; c->periods = 0; c->gate_violations = 0;
   { std::lock_guard<std::mutex> lk(c->mu); c->latencies.clear(); }
   return SIF_OK;
