@@ -10,8 +10,8 @@
 // Tiling: block tile BM x BN, K step 64, WM x WN wavefronts, each owning a (BM/WM) x (BN/WN) tile as a grid of
 // v_mfma_f32_32x32x16_bf16 accumulators.  128x128 with 2x2 wavefronts (64x64 each), two blocks per CU, is the
 // working configuration; 256x256 with 2x4 wavefronts (128x64 each: six operand reads from LDS per eight MFMAs
-// instead of eight, half the global fetches per MFMA), one block per CU, takes over for products with many tiles
-// and a long K.  Operand tiles are staged through LDS with K contiguous (unpadded rows of 128 bytes, XOR-swizzled
+// instead of eight, half the global fetches per MFMA), one block per CU, takes over where a fitted timing model
+// says so (many tiles in whole rounds, or a long K).  Operand tiles are staged through LDS with K contiguous (unpadded rows of 128 bytes, XOR-swizzled
 // in 16-byte chunks so that reads and writes spread over the banks); an operand whose memory layout has the other
 // dimension contiguous is staged as it lies and transposed by the LDS read itself (ds_read_b64_tr_b16).  Interior
 // tiles are fetched from global memory straight into LDS, tile t+1 while tile t is multiplied; tiles on a ragged
@@ -20,6 +20,8 @@
 // Results depend neither on the grid nor on the tile configuration: each output element is reduced over K in one
 // fixed order (ascending, 16 at a time) by one wavefront, so launching a row range of the same problem, or the other
 // configuration, gives bit-identical values.
+#include <algorithm>
+
 #include "common.h"
 #include "specinf.h"
 #include "launch.h"
@@ -123,16 +125,17 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef __attribute__((address_space(1))) const void* global_void_ptr;
 template <int LAYOUT, int ROWS, int THREADS>
 struct DmaStream {
+  static constexpr int NV = ROWS * 8 / THREADS;       // 16-byte vectors per thread and tile
   const char* tile;
   size_t step;
-  uint32_t voff[4];
+  uint32_t voff[NV];
   // rows >= `rows` (a ragged last tile) fetch the tile's first row instead: what they produce is never stored
   __device__ __forceinline__ DmaStream(const bf16_t* b, uint32_t ld, uint32_t row0, uint32_t rows, uint32_t k_begin) {
     if (LAYOUT == 0) {
       tile = (const char*)(b + (size_t)row0 * ld + k_begin);
       step = BK * sizeof(bf16_t);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NV; ++i) {
         const uint32_t r = i * (THREADS / 8) + (threadIdx.x >> 3), c = (threadIdx.x & 7u) ^ swz_key(r);
         voff[i] = ((row0 + r < rows ? r : 0u) * ld + c * 8) * (uint32_t)sizeof(bf16_t);
       }
@@ -141,7 +144,7 @@ struct DmaStream {
       tile = (const char*)(b + (size_t)k_begin * ld + row0);
       step = (size_t)BK * ld * sizeof(bf16_t);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NV; ++i) {
         const uint32_t k = i * (THREADS / UR) + threadIdx.x / UR, u = threadIdx.x % UR, seg = (u >> 2) ^ (k & 3u);
         const uint32_t r = seg * 32 + (u & 3u) * 8;
         voff[i] = (k * ld + (row0 + r < rows ? r : 0u)) * (uint32_t)sizeof(bf16_t);
@@ -153,7 +156,7 @@ struct DmaStream {
     // the LDS address of a fetch is taken from a scalar register: say that the wavefront number is uniform
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < NV; ++i)
       __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + voff[i]), (lds_void_ptr)(stage + i * (THREADS * 8) + wave * 512), 16, 0, 0);
     tile += step;
   }
@@ -239,7 +242,9 @@ __device__ __forceinline__ void sched_pipeline() {
 template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE>
 __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
   constexpr int THREADS = 64 * WM * WN, TI = BM / (WM * 32), TJ = BN / (WN * 32), WCOLS = TJ * 32;
-  static_assert(BM * 8 == 4 * THREADS && BN * 8 == 4 * THREADS, "four 16-byte vectors per thread and operand tile");
+  static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "whole 16-byte vectors per thread and operand tile");
+  static_assert(!EDGE || (BM * 8 == 4 * THREADS && BN * 8 == 4 * THREADS), "the register path moves four vectors per thread and operand");
+  constexpr int FETCHES = (BM + BN) * 8 / THREADS;      // global -> LDS fetches per thread and K step
   static_assert(WCOLS == 64, "the epilogue staging is laid out for 64 columns per wavefront");
   // two tile buffers per operand, as four objects so that the compiler can tell a buffer being filled from the one being read
   __shared__ __align__(1024) bf16_t sA0[BM * BK];
@@ -341,10 +346,10 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         ta.next(sA1); tb.next(sB1);
-        compute(sA0, sB0, Int<8>());
+        compute(sA0, sB0, Int<FETCHES>());
         __syncthreads();
         if (t + 2 < nt) { ta.next(sA0); tb.next(sB0); }
-        compute(sA1, sB1, Int<8>());
+        compute(sA1, sB1, Int<FETCHES>());
         __syncthreads();
       }
     } else if (EDGE) {
@@ -456,14 +461,18 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   const bool can_big = !causal && (a->k % BK) == 0;
   if (a->tile != 0 && a->tile != 128 && a->tile != 256) return fail(SIF_E_INVAL, "gemm: tile must be 0, 128 or 256");
   if (a->tile == 256 && !can_big) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
-  // measured on gfx950: with one block per CU nothing overlaps their prologue and epilogue, and a last, partly filled
-  // round of tiles costs a whole round.  They win when at least two rounds of tiles fill the 256 CUs evenly
-  // (16384 x 3072 x 768: 81 against 98 us, 8192 x 50304 x 768: 753 against 1017 us, 8192^3: 1220 against 955
-  // TFLOP/s) or K is long (50304 x 768 x 8192, 2.3 rounds: 657 against 751 us); 2.25 rounds of a short K lose
-  // (16384 x 2304 x 768: 93 against 77 us).
-  const uint64_t rounds_up = (tiles256 + 255) / 256;
-  const bool even = tiles256 * 10 >= rounds_up * 256 * 9;           // the last round is at least 90 % full on average
-  const bool big = a->tile == 256 || (a->tile == 0 && can_big && tiles256 >= 512 && (even || a->k >= 4096));
+  // Which configuration is faster follows a two-line model fitted to measurements on gfx950 (time of one round of
+  // tiles over the chip, us, K in steps of 64): 128x128, two blocks per CU: 1.0 + 1.19 steps, and a CU that holds a
+  // single block runs it faster, so a partly filled round costs about its share (never less than 0.85 of a round);
+  // 256x256, one block per CU: 8.7 + 1.53 steps for four times the outputs per block, nothing overlaps its prologue
+  // and epilogue, and a partly filled last round costs a whole one.  (16384 x 3072 x 768: 82 against 94 us, 8192 x
+  // 50304 x 768: 753 against 1017, 16384 x 768 x 3072: 80 against 85, 8192^3: 900 against 1150; the other way round
+  // 16384 x 2304 x 768: 78 against 73, 8192 x 768 x 3072: 75 against 51, 8192 x 768 x 50304: 1221 against 830.)
+  const uint64_t tiles128 = (uint64_t)((a->m + 127) / 128) * ((a->n + 127) / 128) * batches;
+  const double steps = (double)(a->k / BK);
+  const double t128 = (1.0 + 1.19 * steps) * std::max(0.85, (double)tiles128 / 512.0);
+  const double t256 = (8.7 + 1.53 * steps) * (double)((tiles256 + 255) / 256);
+  const bool big = a->tile == 256 || (a->tile == 0 && can_big && t256 < t128);
   const uint32_t bm = big ? 256 : 128, bn = bm;
   GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;

@@ -99,7 +99,7 @@ def test_gemm_bf16_row_range_is_bit_identical():
 @pytest.mark.parametrize("al,bl", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("m,n,k", [(256, 256, 64), (520, 776, 192), (1024, 512, 448)])
 def test_gemm_bf16_large_tiles_give_the_same_bits(al, bl, m, n, k):
-    """The 256x256 configuration (chosen automatically only for very large products) against the 128x128 one and the
+    """The 256x256 configuration (chosen automatically only for large products) against the 128x128 one and the
     definition, ragged M and N included."""
     a, b = rnd(30, m, k), rnd(31, n, k)
     A = bf(a if al == 0 else a.T.copy())
