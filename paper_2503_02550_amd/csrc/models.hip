@@ -110,15 +110,47 @@ static double gemm_flops(const sif_gemm_args& g) {
   return batches * 2.0 * g.m * g.n * g.k;
 }
 
-static void emit_gemm(Plan& p, const char* name, const G& g) {
+static Op make_gemm_op(const char* name, const sif_gemm_args& a) {
   Op op;
   op.name = name;
-  const sif_gemm_args a = g.a;
   op.fn = [a](hipStream_t s, const KCtl& c) { return launch_gemm_bf16(&a, s, c); };
   op.cost_us = gemm_cost_us(a);
   op.prof_class = (int32_t)(a.a_layout * 2 + a.b_layout);
   op.flops = gemm_flops(a);
-  p.push_back(std::move(op));
+  op.gemm = a;
+  op.row_split = a.a_layout == SIF_A_ROW_K && a.batch_outer * a.batch_inner == 1 && a.k_causal == 0 && !(a.epilogue & SIF_EPI_CAUSAL_SKIP);
+  return op;
+}
+
+static void emit_gemm(Plan& p, const char* name, const G& g) { p.push_back(make_gemm_op(name, g.a)); }
+
+// rows [r0, r0 + rows) of a product whose rows are independent
+static sif_gemm_args gemm_row_range(const sif_gemm_args& g, uint32_t r0, uint32_t rows) {
+  sif_gemm_args part = g;
+  const size_t csz = (g.epilogue & SIF_EPI_OUT_F32) ? 4 : 2;
+  part.m = rows;
+  part.a_dev = (const bf16_t*)g.a_dev + (size_t)r0 * g.lda;
+  part.c_dev = (unsigned char*)g.c_dev + (size_t)r0 * g.ldc * csz;
+  if (g.res_dev) part.res_dev = (const unsigned char*)g.res_dev + (size_t)r0 * g.ldc * csz;
+  if (g.aux_dev) part.aux_dev = (bf16_t*)g.aux_dev + (size_t)r0 * g.ldc;
+  return part;
+}
+
+uint32_t gemm_round_rows(const sif_gemm_args& a) {
+  // wide products run on 256x256 tiles, one per CU; narrow ones on 128x128 tiles, two per CU
+  if (a.n >= 2048) return 256 * std::max(1u, 256u / ((a.n + 255) / 256));
+  return 128 * std::max(1u, 512u / ((a.n + 127) / 128));
+}
+
+void split_gemm_rows(const Op& op, uint32_t rows_first, Op& first, Op& rest) {
+  const sif_gemm_args& g = op.gemm;
+  first = make_gemm_op(op.name, gemm_row_range(g, 0, rows_first));
+  rest = make_gemm_op(op.name, gemm_row_range(g, rows_first, g.m - rows_first));
+  const double share = (double)rows_first / (double)g.m;
+  // each part pays the fixed part of a launch (prologue, epilogue, a last round that is not full) again, and a part of
+  // one or two rounds of tiles runs a little below the rate of the whole
+  first.cost_us = std::max(1.0, op.cost_us * share * 1.1) + 6.0;
+  rest.cost_us = std::max(1.0, op.cost_us * (1.0 - share)) + 6.0;
 }
 
 // A GEMM whose rows are independent (A [M][K] row-major, C [M][N]) split into row ranges of at most
@@ -132,15 +164,8 @@ static void emit_gemm_rows(Plan& p, const char* name, const G& g, uint32_t kerne
   uint32_t pieces = (uint32_t)ceil(cost / kernel_us_max);
   uint32_t rows_per = ((g.a.m + pieces - 1) / pieces + 127) / 128 * 128;
   for (uint32_t r0 = 0; r0 < g.a.m; r0 += rows_per) {
-    G part = g;
     const uint32_t rows = (g.a.m - r0 < rows_per) ? g.a.m - r0 : rows_per;
-    const size_t csz = (g.a.epilogue & SIF_EPI_OUT_F32) ? 4 : 2;
-    part.a.m = rows;
-    part.a.a_dev = (const bf16_t*)g.a.a_dev + (size_t)r0 * g.a.lda;
-    part.a.c_dev = (unsigned char*)g.a.c_dev + (size_t)r0 * g.a.ldc * csz;
-    if (g.a.res_dev) part.a.res_dev = (const unsigned char*)g.a.res_dev + (size_t)r0 * g.a.ldc * csz;
-    if (g.a.aux_dev) part.a.aux_dev = (bf16_t*)g.a.aux_dev + (size_t)r0 * g.a.ldc;
-    emit_gemm(p, name, part);
+    p.push_back(make_gemm_op(name, gemm_row_range(g.a, r0, rows)));
   }
 }
 

@@ -38,6 +38,10 @@ struct Op {
   // interval (pp_kind, pp_index) of the 1F1B schedule (see sif_pp_1f1b_bubbles)
   int32_t pp_pass = -1, pp_kind = -1, pp_index = 0;
   bool dp_overlap = false;         // bubble whose length the device derives from the bucketed gradient exchange
+  // a matrix product whose rows are independent (A [M][K] row-major, one batch) can be cut into two launches over
+  // row ranges, with the same bits: `gemm` holds its arguments
+  bool row_split = false;
+  sif_gemm_args gemm{};
 };
 typedef std::vector<Op> Plan;
 
@@ -117,6 +121,10 @@ struct InferIO { const void* in_dev; void* out_dev; uint32_t seq = 0; };      //
 sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_io, uint32_t batch, uint32_t seq,
                             uint32_t kernel_us_max, Plan& out);
 uint32_t infer_coalesce(const sif_infer_desc& d);
+// Rows of a row-splittable product that fill the chip with one whole round of tiles (the unit it is cut in)
+uint32_t gemm_round_rows(const sif_gemm_args& a);
+// Cuts `op` (row_split) into its first `rows_first` rows (a multiple of 128, 0 < rows_first < m) and the rest
+void split_gemm_rows(const Op& op, uint32_t rows_first, Op& first, Op& rest);
 constexpr uint32_t kMaxCoalesce = 8;      // most requests one coalesced kernel sequence serves
 
 // markers.hip

@@ -425,6 +425,26 @@ static void barrier_main(sif_ctx* c) {
           }
         }
         if (!j) break;
+        // The end of a bubble: a product that the predicted rest of the bubble does not hold any more, but whole
+        // rounds of its tiles would, is cut in two along its rows (same bits); the first part goes out now.
+        if (gated && !online && !beside && j->plan[j->next_op].row_split) {
+          const Op& whole = j->plan[j->next_op];
+          const uint64_t rest_ns = predicted_remaining_ns(c), ahead_ns = c->outstanding_us * 1000ull;
+          if (rest_ns > ahead_ns) {
+            const double avail_us = (double)(rest_ns - ahead_ns) / 1000.0 - 10.0;
+            const uint32_t unit = gemm_round_rows(whole.gemm);
+            const double per_unit = whole.cost_us * unit / (double)whole.gemm.m;
+            if (whole.cost_us > avail_us && avail_us >= per_unit + 6.0) {
+              const uint64_t rows_first = (uint64_t)((avail_us - 6.0) / per_unit) * unit;
+              if (rows_first > 0 && rows_first < whole.gemm.m) {
+                Op first, rest;
+                split_gemm_rows(whole, (uint32_t)rows_first, first, rest);
+                j->plan[j->next_op] = std::move(first);
+                j->plan.insert(j->plan.begin() + (ptrdiff_t)j->next_op + 1, std::move(rest));
+              }
+            }
+          }
+        }
         Op& op = j->plan[j->next_op];
         const uint64_t cost = cost_of(j);
         if (gated && c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
