@@ -91,3 +91,67 @@ def test_dp_decoder_full_size_step_properties_and_sampled_forward():
     ref_loss0, ref_d = cross_entropy_mean(ref_logits, tg[0])
     # the device holds dlogits = (softmax - onehot) / tokens after the step; compare that gradient for sample 0
     assert_bf16_close(solo["dlogits"], ref_d / cfg["batch"], "dlogits of sample 0", elem_slack=2e-2)
+
+
+def test_fill_in_the_benchmark_configuration_keeps_the_bits_of_a_run_alone():
+    """configs[1] as bench.py runs it: the full-size decoder step with its 4.98 ms bubble, the full-size fill encoder
+    with eight requests coalesced, kernels up to 300 us, products cut along their rows at the end of a bubble.  Every
+    batch (distinct inputs) must come out with the bits of a run by itself, sampled rows must match the oracle, every
+    inference kernel must start inside a bubble, and training must not notice (same loss bits as a solo step)."""
+    cfg, ecfg = Y.DP_DECODER, Y.FILL_ENCODER
+    shape, eshape = decoder_shape(cfg), encoder_shape(ecfg)
+    flat = P.pack(shape, Y.decoder_params(1, cfg))
+    emaster_np = Y.encoder_params(2, ecfg)
+    emaster = P.pack(eshape, emaster_np)
+    ids, tg = Y.token_ids(3, cfg["batch"], cfg["seq"], cfg["vocab"]), Y.token_ids(4, cfg["batch"], cfg["seq"], cfg["vocab"])
+    n_batches = 20
+    eids = [Y.token_ids(100 + i, ecfg["batch"], ecfg["seq"], ecfg["vocab"]) for i in range(n_batches)]
+    losses = {}
+    for collocate in (0, 1):
+        c = S.sif_default_config()
+        c.collocate = 0
+        with Session(c) as s:
+            s.register_training(shape, flat, par_mode=S.SIF_PAR_DP, lr=cfg["lr"], bw_bytes_per_s=cfg["bw_bytes_per_s"])
+            m = s.register_inference(eshape, emaster, coalesce=8)
+            S.sif_calibrate(s.ctx, 2)
+            n_cal = S.sif_read_trace(s.ctx, 1)[-1][3]
+            I, T = i32(ids), i32(tg)
+            E = [i32(e) for e in eids]
+            outs = [torch.zeros((ecfg["batch"], ecfg["seq"], ecfg["d_model"]), device=DEV, dtype=torch.bfloat16) for _ in range(n_batches)]
+            loss = torch.zeros(3, device=DEV)
+            torch.cuda.synchronize()
+            tickets = [s.submit_offline(m, E[i], outs[i], ecfg["batch"], ecfg["seq"]) for i in range(n_batches)] if collocate else []
+            S.sif_set_collocate(s.ctx, collocate)
+            for st in range(3):
+                s.step(I, T, loss[st:st + 1])
+            s.sync()
+            losses[collocate] = up(loss)
+            if not collocate:
+                continue
+            extra = 0
+            while s.stats().offline_batches < n_batches and extra < 40:
+                s.step(I, T)
+                s.sync()
+                extra += 1
+            for tk in tickets:
+                s.wait(tk, 30.0)
+            tr = S.sif_read_trace(s.ctx, 0)
+            inf = [r for r in S.sif_read_trace(s.ctx, 1) if r[3] > n_cal]
+            b0 = np.array([t0 for kind, _, _, _, t0, _ in tr if kind == 3]); b1 = np.array([t1 for kind, _, _, _, _, t1 in tr if kind == 3])
+            for kind, _, dec, _, t0, _ in inf:
+                if kind == 2 and dec == 1:
+                    i = np.searchsorted(b0, t0, side="right") - 1
+                    assert i >= 0 and b0[i] <= t0 <= b1[i]
+            got = [o.cpu() for o in outs]
+    assert np.array_equal(losses[0], losses[1])
+    w = OE.working_copy(emaster_np, "bf16")
+    with Session() as s:
+        m = s.register_inference(eshape, emaster)
+        for i in (0, 7, 8, 19):
+            I, out = i32(eids[i]), torch.zeros((ecfg["batch"], ecfg["seq"], ecfg["d_model"]), device=DEV, dtype=torch.bfloat16)
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, ecfg["batch"], ecfg["seq"]))
+            assert torch.equal(out.cpu(), got[i]), i
+    for i, b in ((0, 3), (19, 31)):
+        ref = OE.encoder_forward(w, eids[i][b:b + 1], ecfg, "bf16")
+        assert_bf16_close(got[i][b:b + 1].float().numpy(), ref, f"batch {i} sample {b}", elem_slack=2e-2)
