@@ -515,6 +515,58 @@ __global__ __launch_bounds__(1024) void xent_kernel(bf16_t* __restrict__ logits,
   kernel_end(ctl, true);
 }
 
+// The same with the row kept in registers (at most MAXV vectors of 8 columns per thread) instead of LDS: several
+// blocks fit on a CU, so one row's reductions overlap the others' loads and stores.
+template <int MAXV, int THREADS>
+__global__ __launch_bounds__(THREADS) void xent_reg_kernel(bf16_t* __restrict__ logits, const int32_t* __restrict__ targets,
+                                                        float* __restrict__ loss, uint32_t tokens, uint32_t vocab, uint32_t ld, KCtl ctl) {
+  __shared__ float sred[16];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t t = blockIdx.x, nv = ld >> 3;
+  uint4* gr = reinterpret_cast<uint4*>(logits + (size_t)t * ld);
+  const int32_t tg = targets[t];
+  const float at_target = bf2f(logits[(size_t)t * ld + tg]);      // read before anything is written back
+  uint4 row[MAXV];
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const uint32_t v = threadIdx.x + k * THREADS;
+    row[k] = v < nv ? gr[v] : make_uint4(0, 0, 0, 0);
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const uint32_t v = threadIdx.x + k * THREADS;
+    float f[8];
+    unpack8(row[k], f);
+    if (v < nv) for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) mx = fmaxf(mx, f[i]);
+  }
+  mx = block_max(mx, sred);
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const uint32_t v = threadIdx.x + k * THREADS;
+    float f[8];
+    unpack8(row[k], f);
+    if (v < nv) for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) sum += __expf(f[i] - mx);
+  }
+  sum = block_sum(sum, sred);
+  const float inv = 1.0f / sum, invn = 1.0f / (float)tokens;
+  if (threadIdx.x == 0) loss[t] = (mx + __logf(sum)) - at_target;
+#pragma unroll
+  for (int k = 0; k < MAXV; ++k) {
+    const uint32_t v = threadIdx.x + k * THREADS;
+    if (v >= nv) continue;
+    float f[8], o[8];
+    unpack8(row[k], f);
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t c = v * 8 + i;
+      o[i] = c < vocab ? (__expf(f[i] - mx) * inv - (c == (uint32_t)tg ? 1.f : 0.f)) * invn : 0.f;
+    }
+    gr[v] = pack8(o);
+  }
+  kernel_end(ctl, true);
+}
+
 __global__ __launch_bounds__(1024) void reduce_sum_kernel(const float* __restrict__ x, float* __restrict__ out, uint32_t n, float scale, KCtl ctl) {
   __shared__ float sred[16];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
@@ -710,6 +762,10 @@ sif_status launch_xent(void* logits, const int32_t* targets, float* loss, uint32
                        hipStream_t s, const KCtl& c) {
   REQ(logits && targets && loss && tokens > 0 && vocab > 0, "xent: null or empty");
   REQ((ld & 7) == 0 && ld >= vocab && al16(logits), "xent: ld must be a multiple of 8 and >= vocab");
+  if (ld <= 8 * 1024 * 8) {          // the row fits in the registers of a block of 1024 threads, two such blocks per CU
+    hipLaunchKernelGGL((xent_reg_kernel<8, 1024>), dim3(tokens), dim3(1024), 0, s, (bf16_t*)logits, targets, loss, tokens, vocab, ld, c);
+    return check_launch("xent");
+  }
   const size_t lds = (size_t)ld * sizeof(bf16_t);
   REQ(lds <= 144 * 1024, "xent: row does not fit in LDS (vocab <= 73728)");
   static bool attr_set = false;
