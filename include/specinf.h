@@ -177,7 +177,10 @@ typedef struct sif_gemm_args {
   void* aux_dev;               /* see SIF_EPI_GELU / SIF_EPI_GELU_GRAD                                  */
   uint32_t tile;               /* block tile edge: 0 = chosen from the shape, 128, or 256 (256: k a multiple of 64, no
                                   k_causal, no SIF_EPI_CAUSAL_SKIP).  The result has the same bits whichever is used. */
-  uint32_t reserved;
+  uint32_t k_limit;            /* 0, or the whole K of a product that batch_inner cuts into slices of k along K (the
+                                  operands' inner batch strides step along K, the results of the slices go to
+                                  separate outputs): slice i then contracts only k_limit - i*k (at most k)
+                                  elements, so the last slice may be shorter than the others.  128-wide tiles only */
 } sif_gemm_args;
 
 /* bf16 matrix product on the MFMA units, fp32 accumulation. */

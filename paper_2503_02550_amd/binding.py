@@ -75,7 +75,7 @@ class sif_gemm_args(C.Structure):
                 ("c_stride_outer", i64), ("c_stride_inner", i64),
                 ("alpha", f32), ("k_causal", u32),
                 ("a_dev", vp), ("b_dev", vp), ("c_dev", vp), ("bias_dev", vp), ("res_dev", vp), ("aux_dev", vp),
-                ("tile", u32), ("reserved", u32)]
+                ("tile", u32), ("k_limit", u32)]
 
 
 class sif_config(C.Structure):
@@ -224,7 +224,7 @@ def sif_dp_overlapped_wait(ready_ns, dur_ns, end_ns):
 # ---- single kernels -------------------------------------------------------------------------------------
 def sif_k_gemm_bf16(a, b, c, m, n, k, lda, ldb, ldc, a_layout=SIF_A_ROW_K, b_layout=SIF_B_ROW_K, epilogue=0,
                     bias=None, res=None, aux=None, alpha=1.0, batch_outer=1, batch_inner=1,
-                    a_strides=(0, 0), b_strides=(0, 0), c_strides=(0, 0), k_causal=0, tile=0, stream=None):
+                    a_strides=(0, 0), b_strides=(0, 0), c_strides=(0, 0), k_causal=0, tile=0, k_limit=0, stream=None):
     g = sif_gemm_args()
     g.struct_size = C.sizeof(sif_gemm_args)
     g.a_layout, g.b_layout, g.epilogue = a_layout, b_layout, epilogue
@@ -233,7 +233,7 @@ def sif_k_gemm_bf16(a, b, c, m, n, k, lda, ldb, ldc, a_layout=SIF_A_ROW_K, b_lay
     g.a_stride_outer, g.a_stride_inner = a_strides
     g.b_stride_outer, g.b_stride_inner = b_strides
     g.c_stride_outer, g.c_stride_inner = c_strides
-    g.alpha, g.k_causal, g.tile = alpha, k_causal, tile
+    g.alpha, g.k_causal, g.tile, g.k_limit = alpha, k_causal, tile, k_limit
     g.a_dev, g.b_dev, g.c_dev, g.bias_dev, g.res_dev, g.aux_dev = ptr(a), ptr(b), ptr(c), ptr(bias), ptr(res), ptr(aux)
     return check(lib.sif_k_gemm_bf16(C.byref(g), stream_ptr(stream)))
 

@@ -35,7 +35,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct GemmP {
   const bf16_t* a; const bf16_t* b; void* c; const bf16_t* bias; const void* res; bf16_t* aux;
-  uint32_t m, n, k, lda, ldb, ldc, epi, k_causal, batch_inner, tiles_m, tiles_n;
+  uint32_t m, n, k, lda, ldb, ldc, epi, k_causal, batch_inner, tiles_m, tiles_n, k_limit;
   long long a_so, a_si, b_so, b_si, c_so, c_si;
   float alpha;
 };
@@ -273,6 +273,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     const bf16_t* A = p.a + bo * p.a_so + bi * p.a_si;
     const bf16_t* B = p.b + bo * p.b_so + bi * p.b_si;
     uint32_t k_begin = 0, k_end = p.k;
+    if (p.k_limit != 0) k_end = min(p.k, p.k_limit - bi * p.k);      // slices of one long K: the last may be shorter
     if (p.k_causal == 1) k_end = min(p.k, m0 + BM);
     if (p.k_causal == 2) k_begin = (m0 / BK) * BK;
 
@@ -448,6 +449,8 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   if ((a->epilogue & SIF_EPI_RESIDUAL) && !a->res_dev) return fail(SIF_E_INVAL, "gemm: RESIDUAL needs res");
   if ((a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) == SIF_EPI_BIAS && !a->bias_dev) return fail(SIF_E_INVAL, "gemm: BIAS needs bias");
   if (a->k_causal > 2) return fail(SIF_E_INVAL, "gemm: bad k_causal");
+  if (a->k_limit != 0 && (a->k_causal != 0 || (uint64_t)(a->batch_inner - 1) * a->k >= a->k_limit || a->k_limit > (uint64_t)a->batch_inner * a->k || a->tile == 256))
+    return fail(SIF_E_INVAL, "gemm: k_limit must lie in the last of the batch_inner slices of k (no k_causal, no 256-wide tiles)");
   if ((a->n & 7) == 0) {
     // vector epilogue: rows of C, the residual and the auxiliary tensor are accessed 8 elements at a time
     if ((a->ldc & 7) || ((a->c_stride_outer | a->c_stride_inner) & 7)) return fail(SIF_E_INVAL, "gemm: ldc and the output batch strides must be multiples of 8 when n is");
@@ -458,7 +461,7 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
   const bool causal = a->k_causal != 0 || (a->epilogue & SIF_EPI_CAUSAL_SKIP);
   const uint64_t tiles256 = (uint64_t)((a->m + 255) / 256) * ((a->n + 255) / 256) * batches;
-  const bool can_big = !causal && (a->k % BK) == 0;
+  const bool can_big = !causal && (a->k % BK) == 0 && a->k_limit == 0;
   if (a->tile != 0 && a->tile != 128 && a->tile != 256) return fail(SIF_E_INVAL, "gemm: tile must be 0, 128 or 256");
   if (a->tile == 256 && !can_big) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
   // Which configuration is faster follows a two-line model fitted to measurements on gfx950 (time of one round of
@@ -479,7 +482,7 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   p.bias = (a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) ? (const bf16_t*)a->bias_dev : nullptr;
   p.res = a->res_dev; p.aux = (bf16_t*)a->aux_dev;
   p.m = a->m; p.n = a->n; p.k = a->k; p.lda = a->lda; p.ldb = a->ldb; p.ldc = a->ldc;
-  p.epi = a->epilogue; p.k_causal = a->k_causal; p.batch_inner = a->batch_inner;
+  p.epi = a->epilogue; p.k_causal = a->k_causal; p.batch_inner = a->batch_inner; p.k_limit = a->k_limit;
   p.a_so = a->a_stride_outer; p.a_si = a->a_stride_inner; p.b_so = a->b_stride_outer; p.b_si = a->b_stride_inner;
   p.c_so = a->c_stride_outer; p.c_si = a->c_stride_inner; p.alpha = a->alpha;
   p.tiles_n = (a->n + bn - 1) / bn; p.tiles_m = (a->m + bm - 1) / bm;

@@ -89,6 +89,7 @@ struct G {
   }
   G& alpha(float v) { a.alpha = v; return *this; }
   G& causal(uint32_t kc) { a.k_causal = kc; return *this; }
+  G& k_limit(uint32_t kl) { a.k_limit = kl; return *this; }
 };
 
 // scratch buffers of the backward pass, shared by all layers
@@ -519,6 +520,27 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   rp.dev = (RedItem*)ar.take((uint64_t)rp.max_items * sizeof(RedItem));
   bf16_t *lnf = nullptr, *logits = nullptr, *y_all = nullptr, *dx_all = nullptr;
   float *mf = nullptr, *rf = nullptr, *loss_tok = nullptr, *loss = nullptr;
+  // The LM head's data gradient [M][d] contracts the whole vocabulary: few output tiles and a very long K.  It is cut
+  // along K into slices whose tiles fill whole rounds of block slots, summed by one small launch right behind it.
+  uint32_t head_splits = 1, head_kper = 0;
+  float* head_part = nullptr;
+  RedItem* head_item = nullptr;
+  if (s.vocab) {
+    const uint32_t tiles = ((M + 127) / 128) * ((d + 127) / 128);
+    double best = 0.0;
+    for (uint32_t k = 1; k <= 8 && tiles < 512 && s.vocab >= 8192; ++k) {
+      const double fill = (double)tiles * k / (512.0 * ((tiles * k + 511) / 512));      // share of the rounds' slots in use
+      if (fill > best * 1.02) { best = fill; head_splits = k; }
+    }
+    if (head_splits > 1) {
+      head_kper = ((s.vocab + head_splits - 1) / head_splits + 63) / 64 * 64;
+      if ((uint64_t)(head_splits - 1) * head_kper >= s.vocab) head_splits = 1;
+    }
+    if (head_splits > 1) {
+      head_part = (float*)ar.take((uint64_t)head_splits * M * d * 4);
+      head_item = (RedItem*)ar.take(sizeof(RedItem));
+    }
+  }
   if (s.vocab) {
     lnf = (bf16_t*)ar.take((uint64_t)M * d * 2);
     logits = (bf16_t*)ar.take((uint64_t)M * Vp * 2);
@@ -667,7 +689,18 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       emit(p, "xent", bytes_cost_us(4.0 * M * Vp), [=](hipStream_t s2, const KCtl& c) { return launch_xent(logits, (const int32_t*)t->cur_targets, loss_tok, M, V, Vp, s2, c); });
       emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
       emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
-      emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+      if (head_splits > 1) {
+        emit_gemm(p, "dlnf", G(logits, wte, head_part, M, d, head_kper, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
+                                 .batch(1, head_splits, 0, head_kper, 0, (int64_t)head_kper * d, 0, (int64_t)M * d).k_limit(V));
+        RedItem it;
+        it.part = head_part; it.out = sc.dln; it.n = (uint64_t)M * d; it.splits = head_splits; it.pad = 0;
+        hipError_t e2 = hipMemcpy(head_item, &it, sizeof(it), hipMemcpyHostToDevice);
+        if (e2 != hipSuccess) return fail_hip(e2, "training plan: upload of the LM-head slice table");
+        const RedItem* hi = head_item;
+        emit(p, "dlnf_sum", bytes_cost_us(4.0 * M * d * head_splits + 2.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_reduce_splits_batch(hi, 1, 0, s2, c); });
+      } else {
+        emit_gemm(p, "dlnf", G(logits, wte, sc.dln, M, d, V, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
+      }
       fp.begin();                  // the final LayerNorm's gradients are finalized with the layers'
       emit_ln_bwd(p, sc.dln, x_last, lnf_g, mf, rf, nullptr, sc.dx_a, grads + pm.at("lnf_g"), grads + pm.at("lnf_b"),
                   grads + pm.at(L(s.n_layers - 1, "b_proj")), fp, M, d);

@@ -114,6 +114,29 @@ def test_gemm_bf16_large_tiles_give_the_same_bits(al, bl, m, n, k):
         S.sif_k_gemm_bf16(A, B, c256, m, n, k - 8, A.shape[1], B.shape[1], n, a_layout=al, b_layout=bl, tile=256)
 
 
+@pytest.mark.parametrize("bl", [0, 1])
+def test_gemm_bf16_slices_of_one_long_k(bl):
+    """batch_inner cuts K into slices whose results go to separate fp32 outputs; with k_limit the last slice is
+    shorter than the others (and here not a multiple of 8).  The slices add up to the whole product."""
+    m, n, kper, slices, k_total = 200, 136, 192, 4, 3 * 192 + 77
+    ld = (k_total + 7) // 8 * 8
+    a = np.zeros((m, ld), np.float32); a[:, :k_total] = rnd(33, m, k_total)
+    b = rnd(34, n, ld) if bl == 0 else rnd(34, ld, n)
+    A, B = bf(a), bf(b)
+    part = torch.full((slices, m, n), 9.0, device=DEV)
+    S.sif_k_gemm_bf16(A, B, part, m, n, kper, ld, B.shape[1], n, b_layout=bl, epilogue=S.SIF_EPI_OUT_F32, batch_inner=slices,
+                      a_strides=(0, kper), b_strides=(0, kper if bl == 0 else kper * n), c_strides=(0, m * n), k_limit=k_total)
+    got = up(part)
+    bq = q(b)[:, :k_total] if bl == 0 else q(b)[:k_total].T
+    for i in range(slices):
+        lo, hi = i * kper, min(k_total, (i + 1) * kper)
+        assert_f32_close(got[i], q(a)[:, lo:hi] @ bq[:, lo:hi].T, f"slice {i}", tol=1e-4)
+    assert_f32_close(got.sum(0), q(a)[:, :k_total] @ bq.T, "sum of the slices", tol=1e-4)
+    with pytest.raises(S.SifError):                      # k_limit must lie in the last slice
+        S.sif_k_gemm_bf16(A, B, part, m, n, kper, ld, B.shape[1], n, b_layout=bl, epilogue=S.SIF_EPI_OUT_F32, batch_inner=slices,
+                          a_strides=(0, kper), b_strides=(0, kper), c_strides=(0, m * n), k_limit=2 * kper)
+
+
 def test_gemm_bf16_rejects_bad_arguments():
     A = bf(rnd(12, 16, 16))
     c = torch.zeros((16, 16), device=DEV, dtype=torch.bfloat16)

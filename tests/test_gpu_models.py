@@ -69,9 +69,12 @@ def test_mlp_training_steps_and_forward_match_oracle():
 DEC_SMALL = dict(n_layers=2, d_model=64, n_heads=4, d_head=16, d_ffn=256, vocab=211, max_pos=40, batch=3, seq=40, causal=True)
 DEC_TILES = dict(n_layers=2, d_model=256, n_heads=2, d_head=64, d_ffn=512, vocab=1000, max_pos=136, batch=2, seq=136, causal=True)
 DEC_SPLIT = dict(n_layers=2, d_model=128, n_heads=2, d_head=64, d_ffn=256, vocab=600, max_pos=128, batch=2, seq=128, causal=True)
+# a vocabulary long enough for the LM head's data gradient to be cut along K (ragged last slice: 8203 = 7 * 1088 + 587)
+DEC_VOCAB = dict(n_layers=1, d_model=64, n_heads=1, d_head=64, d_ffn=128, vocab=8203, max_pos=72, batch=2, seq=72, causal=True)
 
 
-@pytest.mark.parametrize("cfg", [DEC_SMALL, DEC_TILES, DEC_SPLIT], ids=["small", "several-tiles-ragged", "split-weight-gradients"])
+@pytest.mark.parametrize("cfg", [DEC_SMALL, DEC_TILES, DEC_SPLIT, DEC_VOCAB],
+                         ids=["small", "several-tiles-ragged", "split-weight-gradients", "vocabulary-cut-along-k"])
 def test_decoder_training_step_matches_oracle_stage_by_stage(cfg):
     shape = decoder_shape(cfg)
     master = Y.decoder_params(1, cfg, perturb=True)
