@@ -44,6 +44,24 @@ __device__ __forceinline__ void at_load_rows(bf16_t* dst, const bf16_t* src, siz
     *reinterpret_cast<uint4*>(dst + row * DH + ((c ^ (at_key(row) % CH)) << 3)) = x;
   }
 }
+// The same tile fetched from global memory straight into LDS (global_load_lds_dwordx4: no staging registers, the
+// fetch of the next tile runs while the current one is used).  One instruction writes the 64 lanes' 16 bytes to
+// consecutive LDS addresses, so a lane's place in the tile is fixed and the swizzle is applied to what it fetches.
+// Rows >= limit cannot be zero-filled: they fetch row limit - 1 instead (finite data), and every use of such a row is
+// either masked (scores) or multiplied by a probability of zero.
+template <int DH, int ROWS>
+__device__ __forceinline__ void at_dma_rows(bf16_t* dst, const bf16_t* src, size_t ld, uint32_t row0, uint32_t limit) {
+  typedef __attribute__((address_space(3))) void* lds_void_ptr;
+  typedef __attribute__((address_space(1))) const void* global_void_ptr;
+  constexpr int CH = DH / 8, RPI = 64 / CH;                  // chunks per row, rows per instruction and wavefront
+  const uint32_t lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll
+  for (int i = 0; i < ROWS / (RPI * (AT_THREADS / 64)); ++i) {
+    const uint32_t first = (i * (AT_THREADS / 64) + wave) * RPI, row = first + lane / CH, c = (lane % CH) ^ (at_key(row) % CH);
+    const uint32_t r = row0 + row < limit ? row0 + row : limit - 1;
+    __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (size_t)r * ld + c * 8), (lds_void_ptr)(dst + first * DH), 16, 0, 0);
+  }
+}
 // A operand (row, k = 8 consecutive d) from a swizzled [row][d] tile; chunk = k / 8.
 template <int DH>
 __device__ __forceinline__ bf16x8 at_frag(const bf16_t* tile, uint32_t row, uint32_t chunk) {
@@ -82,8 +100,13 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
                                                               uint32_t S, uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, AttnSeqs seqs,
                                                               KCtl ctl) {
   constexpr int KS = DH / 16, DT = DH / 32;                   // k steps of q k^T, 32-wide d tiles
-  __shared__ __align__(16) bf16_t sK[AT_KV * DH];
-  __shared__ __align__(16) bf16_t sV[AT_KV * DH];
+  // d_head 64: two K and two V tile buffers (as four objects, so that the compiler can tell the one being filled from
+  // the one being read), the next tile is fetched while the current one is used; d_head 128: LDS holds one of each
+  constexpr bool DB = DH == 64;
+  __shared__ __align__(1024) bf16_t sK0[AT_KV * DH];
+  __shared__ __align__(1024) bf16_t sV0[AT_KV * DH];
+  __shared__ __align__(1024) bf16_t sK1[DB ? AT_KV * DH : 8];
+  __shared__ __align__(1024) bf16_t sV1[DB ? AT_KV * DH : 8];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
   const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
@@ -115,12 +138,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
   float m_run = -INFINITY, l_run = 0.f, l_true = 0.f;
 
   const uint32_t kv_end = CAUSAL ? min(S, q_blk + AT_Q) : S;
-  for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
-    __syncthreads();
-    at_load_rows<DH, AT_KV>(sK, base + da, ld_qkv, kv0, S);
-    at_load_rows<DH, AT_KV>(sV, base + 2 * da, ld_qkv, kv0, S);
-    __syncthreads();
-
+  auto tile = [&](const bf16_t* sK, const bf16_t* sV, const uint32_t kv0) {
     // S^T tiles: rows = kv (32 per tile), columns = the wavefront's 32 query rows (straight-line code: the four
     // accumulator chains interleave; skipping the tiles above the diagonal would cost more than it saves)
     const bool need_mask = kv0 + AT_KV > S || (CAUSAL && kv0 + AT_KV - 1 > qw);
@@ -188,6 +206,35 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
       }
     }
     if (single) l_run = 1.0f;
+  };
+  if constexpr (DB) {
+    at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, 0, S);
+    at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, 0, S);
+    for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += 2 * AT_KV) {
+      __syncthreads();                                   // tile kv0 has landed, nobody reads buffer 1 any more
+      const bool more = kv0 + AT_KV < kv_end;
+      if (more) {
+        at_dma_rows<DH, AT_KV>(sK1, base + da, ld_qkv, kv0 + AT_KV, S);
+        at_dma_rows<DH, AT_KV>(sV1, base + 2 * da, ld_qkv, kv0 + AT_KV, S);
+      }
+      tile(sK0, sV0, kv0);
+      if (more) {
+        __syncthreads();                                 // tile kv0 + 128 has landed, nobody reads buffer 0 any more
+        if (kv0 + 2 * AT_KV < kv_end) {
+          at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, kv0 + 2 * AT_KV, S);
+          at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, kv0 + 2 * AT_KV, S);
+        }
+        tile(sK1, sV1, kv0 + AT_KV);
+      }
+    }
+  } else {
+    for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
+      __syncthreads();
+      at_load_rows<DH, AT_KV>(sK0, base + da, ld_qkv, kv0, S);
+      at_load_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, kv0, S);
+      __syncthreads();
+      tile(sK0, sV0, kv0);
+    }
   }
 
   if (q < S) {
@@ -215,8 +262,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
                                                                  float* __restrict__ delta, bf16_t* __restrict__ dqkv, uint32_t S, uint32_t H,
                                                                  uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, float scale, KCtl ctl) {
   constexpr int KS = DH / 16, DT = DH / 32;
-  __shared__ __align__(16) bf16_t sK[AT_KV * DH];
-  __shared__ __align__(16) bf16_t sV[AT_KV * DH];
+  constexpr bool DB = DH == 64;                               // two tile buffers each, as in the forward kernel
+  __shared__ __align__(1024) bf16_t sK0[AT_KV * DH];
+  __shared__ __align__(1024) bf16_t sV0[AT_KV * DH];
+  __shared__ __align__(1024) bf16_t sK1[DB ? AT_KV * DH : 8];
+  __shared__ __align__(1024) bf16_t sV1[DB ? AT_KV * DH : 8];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, qi = lane & 31, h = lane >> 5;
   const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
@@ -255,11 +305,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
     for (int r = 0; r < 16; ++r) dqacc[d][r] = 0.f;
 
   const uint32_t kv_end = CAUSAL ? min(S, q_blk + AT_Q) : S;
-  for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
-    __syncthreads();
-    at_load_rows<DH, AT_KV>(sK, base + da, ld_qkv, kv0, S);
-    at_load_rows<DH, AT_KV>(sV, base + 2 * da, ld_qkv, kv0, S);
-    __syncthreads();
+  auto tile = [&](const bf16_t* sK, const bf16_t* sV, const uint32_t kv0) {
     const bool need_mask = kv0 + AT_KV > S || (CAUSAL && kv0 + AT_KV - 1 > qw);
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -289,6 +335,35 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
           dqacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_tr<DH>(sK, d * 32, t * 32 + 16 * s2 + 4 * h), fds, dqacc[d], 0, 0, 0);
       }
     }
+  };
+  if constexpr (DB) {
+    at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, 0, S);
+    at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, 0, S);
+    for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += 2 * AT_KV) {
+      __syncthreads();                                   // tile kv0 has landed, nobody reads buffer 1 any more
+      const bool more = kv0 + AT_KV < kv_end;
+      if (more) {
+        at_dma_rows<DH, AT_KV>(sK1, base + da, ld_qkv, kv0 + AT_KV, S);
+        at_dma_rows<DH, AT_KV>(sV1, base + 2 * da, ld_qkv, kv0 + AT_KV, S);
+      }
+      tile(sK0, sV0, kv0);
+      if (more) {
+        __syncthreads();
+        if (kv0 + 2 * AT_KV < kv_end) {
+          at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, kv0 + 2 * AT_KV, S);
+          at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, kv0 + 2 * AT_KV, S);
+        }
+        tile(sK1, sV1, kv0 + AT_KV);
+      }
+    }
+  } else {
+    for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += AT_KV) {
+      __syncthreads();
+      at_load_rows<DH, AT_KV>(sK0, base + da, ld_qkv, kv0, S);
+      at_load_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, kv0, S);
+      __syncthreads();
+      tile(sK0, sV0, kv0);
+    }
   }
   if (q_ok) {
     bf16_t* op = dqkv + ((size_t)b * S + q) * ld_dqkv + head * DH;
@@ -310,10 +385,15 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
                                                                   bf16_t* __restrict__ dqkv, uint32_t S, uint32_t H, uint32_t ld_qkv,
                                                                   uint32_t ld_o, uint32_t ld_dqkv, float scale, KCtl ctl) {
   constexpr int KS = DH / 16, DT = DH / 32;
-  __shared__ __align__(16) bf16_t sQ[AT_QB * DH];
-  __shared__ __align__(16) bf16_t sDo[AT_QB * DH];
-  __shared__ __align__(16) float sL[AT_QB];
-  __shared__ __align__(16) float sD[AT_QB];
+  constexpr bool DB = DH == 64;                               // two buffers of everything that is streamed, as in the forward kernel
+  __shared__ __align__(1024) bf16_t sQ0[AT_QB * DH];
+  __shared__ __align__(1024) bf16_t sDo0[AT_QB * DH];
+  __shared__ __align__(1024) bf16_t sQ1[DB ? AT_QB * DH : 8];
+  __shared__ __align__(1024) bf16_t sDo1[DB ? AT_QB * DH : 8];
+  __shared__ __align__(16) float sL0[AT_QB];
+  __shared__ __align__(16) float sD0[AT_QB];
+  __shared__ __align__(16) float sL1[AT_QB];
+  __shared__ __align__(16) float sD1[AT_QB];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6, ki = lane & 31, h = lane >> 5;
   const uint32_t bh = blockIdx.x, b = bh / H, head = bh % H, da = H * DH;
@@ -343,21 +423,20 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkacc[d][r] = 0.f; dvacc[d][r] = 0.f; }
 
-  for (uint32_t q0 = CAUSAL ? (kv_blk / AT_QB) * AT_QB : 0; q0 < S; q0 += AT_QB) {
-    __syncthreads();
-    at_load_rows<DH, AT_QB>(sQ, base, ld_qkv, q0, S);
-    at_load_rows<DH, AT_QB>(sDo, dobase, ld_o, q0, S);
+  // lse (base-2 units; a row past the end gets P = 2^(-inf) = 0) and delta of the 64 queries from q0 on
+  auto load_vectors = [&](float* sL, float* sD, const uint32_t q0) {
     if (threadIdx.x < AT_QB) {
       const uint32_t qq = q0 + threadIdx.x;
-      sL[threadIdx.x] = qq < S ? lrow[qq] * 1.44269504088896f : INFINITY;         // base-2 units; a row past the end gets P = 2^(-inf) = 0
+      sL[threadIdx.x] = qq < S ? lrow[qq] * 1.44269504088896f : INFINITY;
       sD[threadIdx.x] = qq < S ? drow[qq] : 0.f;
     }
-    __syncthreads();
+  };
+  auto tile = [&](const bf16_t* sQ, const bf16_t* sDo, const float* sL, const float* sD, const uint32_t q0) {
     // a wavefront whose 32 keys all lie after the 64 queries of this step has nothing to add
-    if (CAUSAL && kw > q0 + AT_QB - 1) continue;
+    if (CAUSAL && kw > q0 + AT_QB - 1) return;
 #pragma unroll
     for (int u = 0; u < AT_QB / 32; ++u) {
-      if (CAUSAL && kw > q0 + u * 32 + 31) continue;            // these 32 queries all precede the wavefront's keys
+      if (CAUSAL && kw > q0 + u * 32 + 31) continue;            // these 32 queries all precede the wavefront's keys (next u)
       const bool need_mask = CAUSAL && kw + 31 > q0 + u * 32;
       floatx16 sacc, pacc;
 #pragma unroll
@@ -392,6 +471,42 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
           dkacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at_frag_tr<DH>(sQ, d * 32, qb), fds, dkacc[d], 0, 0, 0);     // dK^T
         }
       }
+    }
+  };
+  const uint32_t q_first = CAUSAL ? (kv_blk / AT_QB) * AT_QB : 0;
+  if constexpr (DB) {
+    if (q_first < S) {
+      at_dma_rows<DH, AT_QB>(sQ0, base, ld_qkv, q_first, S);
+      at_dma_rows<DH, AT_QB>(sDo0, dobase, ld_o, q_first, S);
+      load_vectors(sL0, sD0, q_first);
+    }
+    for (uint32_t q0 = q_first; q0 < S; q0 += 2 * AT_QB) {
+      __syncthreads();                                   // step q0 has landed, nobody reads buffer 1 any more
+      const bool more = q0 + AT_QB < S;
+      if (more) {
+        at_dma_rows<DH, AT_QB>(sQ1, base, ld_qkv, q0 + AT_QB, S);
+        at_dma_rows<DH, AT_QB>(sDo1, dobase, ld_o, q0 + AT_QB, S);
+        load_vectors(sL1, sD1, q0 + AT_QB);
+      }
+      tile(sQ0, sDo0, sL0, sD0, q0);
+      if (more) {
+        __syncthreads();
+        if (q0 + 2 * AT_QB < S) {
+          at_dma_rows<DH, AT_QB>(sQ0, base, ld_qkv, q0 + 2 * AT_QB, S);
+          at_dma_rows<DH, AT_QB>(sDo0, dobase, ld_o, q0 + 2 * AT_QB, S);
+          load_vectors(sL0, sD0, q0 + 2 * AT_QB);
+        }
+        tile(sQ1, sDo1, sL1, sD1, q0 + AT_QB);
+      }
+    }
+  } else {
+    for (uint32_t q0 = q_first; q0 < S; q0 += AT_QB) {
+      __syncthreads();
+      at_load_rows<DH, AT_QB>(sQ0, base, ld_qkv, q0, S);
+      at_load_rows<DH, AT_QB>(sDo0, dobase, ld_o, q0, S);
+      load_vectors(sL0, sD0, q0);
+      __syncthreads();
+      tile(sQ0, sDo0, sL0, sD0, q0);
     }
   }
   if (kv_ok) {
