@@ -96,7 +96,7 @@ __device__ __forceinline__ float at_round(float x) { return bf2f(f2bf(x)); }
 // Forward.  One block = 128 query rows of one (batch, head), 4 wavefronts x 32 rows; keys/values streamed in tiles
 // of 128 through LDS (K and V as [kv][d]); running maximum / sum / rescale per lane.
 template <int DH, int CAUSAL>
-__global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse,
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o, float* __restrict__ lse,
                                                               uint32_t S, uint32_t H, uint32_t ld_qkv, uint32_t ld_o, float scale, AttnSeqs seqs,
                                                               KCtl ctl) {
   constexpr int KS = DH / 16, DT = DH / 32;                   // k steps of q k^T, 32-wide d tiles
@@ -211,6 +211,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
     at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, 0, S);
     at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, 0, S);
     for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += 2 * AT_KV) {
+      wait_fetches();
       __syncthreads();                                   // tile kv0 has landed, nobody reads buffer 1 any more
       const bool more = kv0 + AT_KV < kv_end;
       if (more) {
@@ -219,6 +220,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
       }
       tile(sK0, sV0, kv0);
       if (more) {
+        wait_fetches();
         __syncthreads();                                 // tile kv0 + 128 has landed, nobody reads buffer 0 any more
         if (kv0 + 2 * AT_KV < kv_end) {
           at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, kv0 + 2 * AT_KV, S);
@@ -257,7 +259,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_fwd_kernel(const bf16_t* __re
 // keys/values streamed in tiles of 128, K and V as [kv][d].  Also writes delta = rowsum(do .* o)
 // for the dk/dv kernel.
 template <int DH, int CAUSAL>
-__global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+__global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
                                                                  const bf16_t* __restrict__ d_o, const float* __restrict__ lse,
                                                                  float* __restrict__ delta, bf16_t* __restrict__ dqkv, uint32_t S, uint32_t H,
                                                                  uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, float scale, KCtl ctl) {
@@ -340,6 +342,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
     at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, 0, S);
     at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, 0, S);
     for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += 2 * AT_KV) {
+      wait_fetches();
       __syncthreads();                                   // tile kv0 has landed, nobody reads buffer 1 any more
       const bool more = kv0 + AT_KV < kv_end;
       if (more) {
@@ -348,6 +351,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
       }
       tile(sK0, sV0, kv0);
       if (more) {
+        wait_fetches();
         __syncthreads();
         if (kv0 + 2 * AT_KV < kv_end) {
           at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, kv0 + 2 * AT_KV, S);
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dq_kernel(const bf16_t* _
 // Backward, dk and dv.  One block = 128 key rows of one (batch, head), a key row per lane pair (its K and V rows stay
 // in registers); queries streamed in steps of 64 rows: q and do as [q][d], lse and delta beside them.
 template <int DH, int CAUSAL>
-__global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+__global__ __launch_bounds__(AT_THREADS, DH == 64 ? 2 : 1) void attn_bwd_dkv_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
                                                                   const float* __restrict__ lse, const float* __restrict__ delta,
                                                                   bf16_t* __restrict__ dqkv, uint32_t S, uint32_t H, uint32_t ld_qkv,
                                                                   uint32_t ld_o, uint32_t ld_dqkv, float scale, KCtl ctl) {
@@ -481,6 +485,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
       load_vectors(sL0, sD0, q_first);
     }
     for (uint32_t q0 = q_first; q0 < S; q0 += 2 * AT_QB) {
+      wait_fetches();
       __syncthreads();                                   // step q0 has landed, nobody reads buffer 1 any more
       const bool more = q0 + AT_QB < S;
       if (more) {
@@ -490,6 +495,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_bwd_dkv_kernel(const bf16_t* 
       }
       tile(sQ0, sDo0, sL0, sD0, q0);
       if (more) {
+        wait_fetches();
         __syncthreads();
         if (q0 + 2 * AT_QB < S) {
           at_dma_rows<DH, AT_QB>(sQ0, base, ld_qkv, q0 + 2 * AT_QB, S);

@@ -88,4 +88,11 @@ __device__ __forceinline__ float block_max(float v, float* sm) {
   return t;
 }
 
+// Waits until every global -> LDS fetch (and every other vector memory operation) this wavefront has issued is
+// complete: s_waitcnt vmcnt(0), the other counters left alone.  A barrier that hands fetched tiles to the other
+// wavefronts of the block needs it in front: __syncthreads() by itself orders LDS accesses, but the compiler waits for
+// a wavefront's own fetches only where that wavefront reads the buffer, which may be after the barrier, and then
+// another wavefront's part of the tile need not have landed.
+__device__ __forceinline__ void wait_fetches() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 }  // namespace sif

@@ -344,13 +344,16 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       DmaStream<ALAY, BM, THREADS> ta(A, p.lda, m0, p.m, k_begin);
       DmaStream<BLAY, BN, THREADS> tb(B, p.ldb, n0, p.n, k_begin);
       ta.next(sA0); tb.next(sB0);
+      wait_fetches();
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         ta.next(sA1); tb.next(sB1);
         compute(sA0, sB0, Int<FETCHES>());
+        wait_fetches();          // every wavefront's part of the next tile has landed before the barrier lets anyone read it
         __syncthreads();
         if (t + 2 < nt) { ta.next(sA0); tb.next(sB0); }
         compute(sA1, sB1, Int<FETCHES>());
+        wait_fetches();
         __syncthreads();
       }
     } else if (EDGE) {

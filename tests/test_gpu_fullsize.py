@@ -73,7 +73,9 @@ def test_dp_decoder_full_size_step_properties_and_sampled_forward():
                                 dlogits=logits_d, stats=s.stats(), outs=[o.cpu() for o in outs]))
     solo, col = results
     # 1. collocation leaves training untouched, bit for bit, at full size
-    assert torch.equal(solo["master2"], col["master2"]) and torch.equal(solo["grads1"], col["grads1"]) and np.array_equal(solo["loss"], col["loss"])
+    assert np.array_equal(solo["loss"], col["loss"]), (solo["loss"], col["loss"])
+    assert torch.equal(solo["grads1"], col["grads1"])
+    assert torch.equal(solo["master2"], col["master2"])
     assert col["stats"].offline_batches >= 1 and torch.equal(col["outs"][0], col["outs"][1])       # same input -> same bits
     # 2. SGD closed form on the fp32 masters: theta1 = theta0 - lr * g (g = stored bf16 gradient)
     theta0 = torch.from_numpy(flat)
