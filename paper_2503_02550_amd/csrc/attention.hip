@@ -62,6 +62,33 @@ __device__ __forceinline__ void at_dma_rows(bf16_t* dst, const bf16_t* src, size
     __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (size_t)r * ld + c * 8), (lds_void_ptr)(dst + first * DH), 16, 0, 0);
   }
 }
+// A wavefront's 32 x DH results, held transposed in MFMA accumulators (element r of tile d in lane (qi, h) is column
+// d*32 + (r/4)*8 + h*4 + r%4 of row qi), times mul, to global memory as whole rows.  Stored straight from the
+// accumulators a lane would write 8 bytes at a time and every 128-byte line of the output would be touched by eight
+// store instructions, 16 bytes each.  So the tile passes through 32*DH elements of LDS that belong to this wavefront
+// alone (16-byte chunks of a row swizzled with the row) and leaves as 16-byte vectors, a row of 128 bytes per eight
+// lanes.  dst = row 0, column 0 of the tile; only the first `rows` rows exist.
+template <int DH>
+__device__ __forceinline__ void at_store_tile(bf16_t* stage, const floatx16 (&acc)[DH / 32], float mul, bf16_t* dst, size_t ld, uint32_t rows) {
+  constexpr int CH = DH / 8;
+  const uint32_t lane = threadIdx.x & 63, qi = lane & 31, h = lane >> 5;
+#pragma unroll
+  for (int d = 0; d < DH / 32; ++d)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<uint2*>(stage + qi * DH + (((d * 4 + g) ^ (qi & 7u)) << 3) + h * 4) =
+          make_uint2(pack_bf2(acc[d][4 * g] * mul, acc[d][4 * g + 1] * mul), pack_bf2(acc[d][4 * g + 2] * mul, acc[d][4 * g + 3] * mul));
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+#pragma unroll
+  for (int it = 0; it < 32 * CH / 64; ++it) {
+    const uint32_t idx = lane + it * 64, row = idx / CH, c = idx % CH;
+    const uint4 v = *reinterpret_cast<const uint4*>(stage + row * DH + ((c ^ (row & 7u)) << 3));
+    if (row < rows) *reinterpret_cast<uint4*>(dst + (size_t)row * ld + c * 8) = v;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
 // A operand (row, k = 8 consecutive d) from a swizzled [row][d] tile; chunk = k / 8.
 template <int DH>
 __device__ __forceinline__ bf16x8 at_frag(const bf16_t* tile, uint32_t row, uint32_t chunk) {
@@ -239,19 +266,10 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
     }
   }
 
-  if (q < S) {
-    const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
-    bf16_t* op = o + (row0 + q) * ld_o + head * DH;
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const uint32_t dd = d * 32 + g * 8 + h * 4;
-        *reinterpret_cast<uint2*>(op + dd) = make_uint2(pack_bf2(oacc[d][4 * g] * inv, oacc[d][4 * g + 1] * inv),
-                                                        pack_bf2(oacc[d][4 * g + 2] * inv, oacc[d][4 * g + 3] * inv));
-      }
-    if (lse != nullptr && h == 0) lse[(size_t)bh * S + q] = (m_run + __log2f(l_true)) * 0.693147180559945f;
-  }
+  __syncthreads();                                         // nobody reads the last K/V tile any more: sK0 stages the output
+  at_store_tile<DH>(sK0 + wave * (32 * DH), oacc, l_run > 0.f ? 1.0f / l_run : 0.f, o + (row0 + qw) * ld_o + head * DH, ld_o,
+                    qw < S ? S - qw : 0u);
+  if (q < S && lse != nullptr && h == 0) lse[(size_t)bh * S + q] = (m_run + __log2f(l_true)) * 0.693147180559945f;
   kernel_end(ctl, true);
 }
 
@@ -369,15 +387,8 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_bwd_dq_kernel(const bf16_t
       tile(sK0, sV0, kv0);
     }
   }
-  if (q_ok) {
-    bf16_t* op = dqkv + ((size_t)b * S + q) * ld_dqkv + head * DH;
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
-        *reinterpret_cast<uint2*>(op + d * 32 + g * 8 + h * 4) =
-            make_uint2(pack_bf2(dqacc[d][4 * g], dqacc[d][4 * g + 1]), pack_bf2(dqacc[d][4 * g + 2], dqacc[d][4 * g + 3]));
-  }
+  __syncthreads();                                         // nobody reads the last K/V tile any more: sK0 stages dq
+  at_store_tile<DH>(sK0 + wave * (32 * DH), dqacc, 1.0f, dqkv + ((size_t)b * S + qw) * ld_dqkv + head * DH, ld_dqkv, qw < S ? S - qw : 0u);
   kernel_end(ctl, true);
 }
 
@@ -515,17 +526,13 @@ __global__ __launch_bounds__(AT_THREADS, DH == 64 ? 2 : 1) void attn_bwd_dkv_ker
       tile(sQ0, sDo0, sL0, sD0, q0);
     }
   }
-  if (kv_ok) {
-    bf16_t* kp = dqkv + ((size_t)b * S + kv) * ld_dqkv + da + head * DH;
-    bf16_t* vp = kp + da;
-#pragma unroll
-    for (int d = 0; d < DT; ++d)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const uint32_t dd = d * 32 + g * 8 + h * 4;
-        *reinterpret_cast<uint2*>(kp + dd) = make_uint2(pack_bf2(dkacc[d][4 * g], dkacc[d][4 * g + 1]), pack_bf2(dkacc[d][4 * g + 2], dkacc[d][4 * g + 3]));
-        *reinterpret_cast<uint2*>(vp + dd) = make_uint2(pack_bf2(dvacc[d][4 * g], dvacc[d][4 * g + 1]), pack_bf2(dvacc[d][4 * g + 2], dvacc[d][4 * g + 3]));
-      }
+  __syncthreads();                                         // nobody reads the last Q/dO step any more: its buffers stage dk, then dv
+  {
+    bf16_t* stage = (wave < 2 ? sQ0 : sDo0) + (wave & 1) * (32 * DH);
+    bf16_t* kp = dqkv + ((size_t)b * S + kw) * ld_dqkv + da + head * DH;
+    const uint32_t rows = kw < S ? S - kw : 0u;
+    at_store_tile<DH>(stage, dkacc, 1.0f, kp, ld_dqkv, rows);
+    at_store_tile<DH>(stage, dvacc, 1.0f, kp + da, ld_dqkv, rows);
   }
   kernel_end(ctl, true);
 }
