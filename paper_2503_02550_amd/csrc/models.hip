@@ -108,6 +108,7 @@ static double gemm_flops(const sif_gemm_args& g) {
   const double batches = (double)g.batch_outer * g.batch_inner;
   if (g.epilogue & SIF_EPI_CAUSAL_SKIP) return batches * 2.0 * g.k * (0.5 * g.m * (g.m + 1.0));
   if (g.k_causal) return batches * 2.0 * g.n * (0.5 * g.m * (g.m + 1.0));
+  if (g.k_limit) return (double)g.batch_outer * 2.0 * g.m * g.n * g.k_limit;       // slices of one long K, the last one shorter
   return batches * 2.0 * g.m * g.n * g.k;
 }
 
@@ -185,11 +186,20 @@ static void emit_bubble(Plan& p, int32_t site, uint64_t ns) {
 // Weight gradient dW[m_out, n_out] = A^T B with A stored [tokens][m_out], B stored [tokens][n_out].
 // K slices of a weight-gradient product: few output tiles (d x d .. d x 4d) but a long K (the tokens), so the
 // product is cut along K into `splits` launches-in-one (a batch index) with fp32 partial results, summed afterwards.
-static uint32_t wgrad_splits(uint32_t m_out, uint32_t n_out, uint32_t tokens) {
+// As many slices as fill one round of 128x128 tiles at two blocks per CU (at most 8: every slice writes and the sum
+// reads m_out x n_out floats); a slice is a whole number of 64-wide K steps, the last one takes what is left
+// (768 x 3072 over 8192 tokens: 3 slices of 2752, 2752, 2688 = 432 blocks, 50 us; 2 slices = 288 blocks, 61 us).
+static uint32_t wgrad_splits(uint32_t m_out, uint32_t n_out, uint32_t tokens, uint32_t* kper_out = nullptr) {
   const uint32_t tiles = ((m_out + 127) / 128) * ((n_out + 127) / 128);
-  uint32_t splits = 1;
-  while (splits < 16 && tiles * splits * 2 <= 512 && tokens % (splits * 2) == 0 && (tokens / (splits * 2)) % 64 == 0) splits *= 2;
-  return (n_out & 7) ? 1 : splits;
+  const uint32_t want = std::min<uint32_t>(8, 512 / std::max<uint32_t>(1, tiles));
+  uint32_t kper = tokens, splits = 1;
+  if ((n_out & 7) == 0 && want >= 2 && tokens >= 256) {
+    kper = ((tokens + want - 1) / want + 63) / 64 * 64;
+    splits = (tokens + kper - 1) / kper;
+    if (splits < 2) { kper = tokens; splits = 1; }
+  }
+  if (kper_out) *kper_out = kper;
+  return splits;
 }
 
 // The partial results of all split products of a backward pass are summed by ONE launch at its end (RedPlan works
@@ -218,7 +228,8 @@ struct RedPlan {
 
 static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t* b, bf16_t* dw, uint32_t m_out, uint32_t n_out,
                        uint32_t tokens, RedPlan& rp, uint32_t acc) {
-  const uint32_t splits = wgrad_splits(m_out, n_out, tokens);
+  uint32_t kper = tokens;
+  const uint32_t splits = wgrad_splits(m_out, n_out, tokens, &kper);
   if (splits == 1) {
     G g(a, b, dw, m_out, n_out, tokens, m_out, n_out, n_out);
     g.lay(SIF_A_ROW_M, SIF_B_ROW_N);
@@ -226,10 +237,9 @@ static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t*
     emit_gemm(p, name, g);
     return;
   }
-  const uint32_t kper = tokens / splits;
   float* part = rp.take((uint64_t)m_out * n_out, splits, dw);
   emit_gemm(p, name, G(a, b, part, m_out, n_out, kper, m_out, n_out, n_out).lay(SIF_A_ROW_M, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
-                         .batch(splits, 1, (int64_t)kper * m_out, 0, (int64_t)kper * n_out, 0, (int64_t)m_out * n_out, 0));
+                         .batch(1, splits, 0, (int64_t)kper * m_out, 0, (int64_t)kper * n_out, 0, (int64_t)m_out * n_out).k_limit(tokens));
 }
 
 // Column sums (bias gradients) and the LayerNorm parameter gradients are computed as per-block partial sums by
