@@ -55,6 +55,7 @@ def main():
     ap.add_argument("--coalesce", type=int, default=16, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time)")
     ap.add_argument("--kernel-us-max", type=int, default=600, help="longest kernel the planner emits, us (the 4.98 ms bubble of this workload takes long kernels; the library's default of 300 is for shorter bubbles)")
+    ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 10)")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=2000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--dp-bucket-mb", type=float, default=0.0,
@@ -92,6 +93,8 @@ def main():
     cfg.allow_serial_streams = 1 if args.allow_serial_streams else 0
     if args.kernel_us_max:
         cfg.kernel_us_max = args.kernel_us_max
+    if args.period_us:
+        cfg.period_us = args.period_us
     with Session(cfg) as s:
         s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"],
                             dp_bucket_bytes=int(args.dp_bucket_mb * 2 ** 20))
