@@ -19,8 +19,10 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t s, const KCtl& c
 sif_status launch_gemm_f32(const float* a, int64_t a_sm, int64_t a_sk, const float* b, int64_t b_sk, int64_t b_sn,
                            float* c, int64_t ldc, uint32_t m, uint32_t n, uint32_t k, uint32_t epi, const float* bias,
                            float* aux, hipStream_t s, const KCtl& ctl);
+// segs (optional): the output rows go to the segments' buffers instead of y
+struct RowSegs;
 sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
-                                uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c);
+                                uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c, const RowSegs* segs = nullptr);
 sif_status launch_layernorm_bwd_dx(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
                                    const void* res, void* dx, float* part, uint32_t rows, uint32_t d, uint32_t with_sum, hipStream_t s,
                                    const KCtl& c);
@@ -37,6 +39,16 @@ sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t
 // equal lengths, see launch_attn_fwd)
 constexpr uint32_t kAttnMaxSeqs = 64;
 struct AttnSeqs { uint32_t n; uint32_t start[kAttnMaxSeqs + 1]; };
+
+// Rows of several requests laid back to back: segment r is rows row0[r] .. row0[r+1] and has a buffer of its own
+// (the token ids an embedding reads, or the place a LayerNorm writes).  n = 0: no segments, one buffer for all rows.
+constexpr uint32_t kMaxRowSegs = 16;
+struct RowSegs {
+  uint32_t n;
+  uint32_t row0[kMaxRowSegs + 1];
+  uint32_t seq[kMaxRowSegs];         // embedding: the sequence length within the segment (position = row in segment % seq)
+  void* ptr[kMaxRowSegs];
+};
 sif_status launch_attn_fwd_varlen(const void* qkv, void* o, const uint32_t* starts, uint32_t n_seqs, uint32_t heads, uint32_t d_head,
                                   uint32_t ld_qkv, uint32_t ld_o, uint32_t causal, hipStream_t s, const KCtl& c);
 sif_status launch_attn_fwd(const void* qkv, void* o, float* lse, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head,
@@ -47,6 +59,8 @@ sif_status launch_attn_bwd_dq(const void* qkv, const void* o, const void* d_o, c
 sif_status launch_attn_bwd_dkv(const void* qkv, const void* d_o, const float* lse, const float* delta, void* dqkv, uint32_t batch, uint32_t seq,
                                uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal, hipStream_t s,
                                const KCtl& c);
+// token ids per segment (segs.ptr), positions restart with every sequence of a segment
+sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const void* wpe, void* x, uint32_t d, hipStream_t s, const KCtl& c);
 sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens,
                             uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c);
 sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t tokens, uint32_t d,

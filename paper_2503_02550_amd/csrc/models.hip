@@ -916,12 +916,16 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
   bf16_t *prob = (bf16_t*)im.bufs.at("prob"), *o = (bf16_t*)im.bufs.at("o"), *a = (bf16_t*)im.bufs.at("a");
   float* scores = (float*)im.bufs.at("scores");
   const bf16_t *wte = W + pm.at("wte"), *wpe = W + pm.at("wpe"), *eg = W + pm.at("emb_ln_g"), *eb = W + pm.at("emb_ln_b");
+  // the first and the last kernel serve all requests of the sequence at once: a table says which rows are whose
+  static_assert(kMaxRowSegs >= kMaxCoalesce, "one row segment per coalesced request");
+  RowSegs in_segs, out_segs;
+  in_segs.n = out_segs.n = n_io;
+  for (uint32_t r = 0; r <= n_io; ++r) in_segs.row0[r] = out_segs.row0[r] = row0[r];
   for (uint32_t r = 0; r < n_io; ++r) {
-    const int32_t* ids = (const int32_t*)io[r].in_dev;
-    bf16_t* tr = t + (size_t)row0[r] * d;
-    const uint32_t M1 = rows_of[r], sr = M1 / batch;
-    emit(p, "embed", bytes_cost_us(6.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd(ids, wte, wpe, tr, M1, sr, d, st, c); });
+    in_segs.ptr[r] = const_cast<void*>(io[r].in_dev); out_segs.ptr[r] = io[r].out_dev;
+    in_segs.seq[r] = out_segs.seq[r] = rows_of[r] / batch;
   }
+  emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd_segs(in_segs, wte, wpe, t, d, st, c); });
   emit(p, "emb_ln", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, eg, eb, x, nullptr, nullptr, M, d, st, c); });
   for (uint32_t l = 0; l < s.n_layers; ++l) {
     const bf16_t *w_qkv = W + pm.at(L(l, "w_qkv")), *b_qkv = W + pm.at(L(l, "b_qkv")), *w_o = W + pm.at(L(l, "w_o")), *b_o = W + pm.at(L(l, "b_o"));
@@ -949,12 +953,7 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
     if (!last) {
       emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g2, be2, x, nullptr, nullptr, M, d, st, c); });
     } else {
-      for (uint32_t r = 0; r < n_io; ++r) {
-        const bf16_t* tr = t + (size_t)row0[r] * d;
-        void* y = io[r].out_dev;
-        const uint32_t M1 = rows_of[r];
-        emit(p, "ln2", bytes_cost_us(4.0 * M1 * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(tr, g2, be2, y, nullptr, nullptr, M1, d, st, c); });
-      }
+      emit(p, "ln2", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, g2, be2, nullptr, nullptr, nullptr, M, d, st, c, &out_segs); });
     }
   }
   return SIF_OK;

@@ -25,12 +25,18 @@ template <int MAXV>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
                                                             const bf16_t* __restrict__ b, bf16_t* __restrict__ y,
                                                             float* __restrict__ mean_out, float* __restrict__ rstd_out,
-                                                            uint32_t rows, uint32_t d, KCtl ctl) {
+                                                            uint32_t rows, uint32_t d, RowSegs segs, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
-  const uint32_t row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, nv = d >> 3;
+  // the row is the same for the whole wavefront: as a scalar it can index the segment table in the kernel arguments
+  const uint32_t row = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6)), lane = threadIdx.x & 63, nv = d >> 3;
   if (row < rows) {
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
     uint4* yr = reinterpret_cast<uint4*>(y + (size_t)row * d);
+    if (segs.n != 0) {
+      uint32_t r = 0;
+      while (r + 1 < segs.n && row >= segs.row0[r + 1]) ++r;
+      yr = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(segs.ptr[r]) + (size_t)(row - segs.row0[r]) * d);
+    }
     float s = 0.f, f[8];
     if constexpr (MAXV > 0) {
       uint4 cx[MAXV], cg[MAXV], cb[MAXV];
@@ -421,6 +427,30 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restric
   kernel_end(ctl, true);
 }
 
+// The same for several requests whose rows lie back to back in x: segment r reads its own token ids, positions
+// restart with every sequence of seq[r] tokens.
+__global__ __launch_bounds__(256) void embed_fwd_segs_kernel(RowSegs segs, const bf16_t* __restrict__ wte, const bf16_t* __restrict__ wpe,
+                                                             bf16_t* __restrict__ x, uint32_t tokens, uint32_t d, KCtl ctl) {
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6)), lane = threadIdx.x & 63, nv = d >> 3;
+  if (t < tokens) {
+    uint32_t r = 0;
+    while (r + 1 < segs.n && t >= segs.row0[r + 1]) ++r;
+    const uint32_t local = t - segs.row0[r];
+    const int32_t id = reinterpret_cast<const int32_t*>(segs.ptr[r])[local];
+    const uint4* a = reinterpret_cast<const uint4*>(wte + (size_t)id * d);
+    const uint4* b = reinterpret_cast<const uint4*>(wpe + (size_t)(local % segs.seq[r]) * d);
+    uint4* o = reinterpret_cast<uint4*>(x + (size_t)t * d);
+    for (uint32_t v = lane; v < nv; v += 64) {
+      float fa[8], fb[8], q[8];
+      unpack8(a[v], fa); unpack8(b[v], fb);
+      for (int i = 0; i < 8; ++i) q[i] = fa[i] + fb[i];
+      o[v] = pack8(q);
+    }
+  }
+  kernel_end(ctl, true);
+}
+
 constexpr int EB_MAXC = 16;   // columns per thread: d <= 4096
 
 // Block t owns token t.  If an earlier token has the same id the block has nothing to do; otherwise it adds the
@@ -657,13 +687,25 @@ __global__ __launch_bounds__(256) void reduce_splits_batch_kernel(const RedItem*
 static bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 #define REQ(cond, msg) do { if (!(cond)) return fail(SIF_E_INVAL, msg); } while (0)
 
+static sif_status check_segs(const char* who, const RowSegs& segs, uint32_t rows) {
+  if (segs.n == 0 || segs.n > kMaxRowSegs || segs.row0[0] != 0 || segs.row0[segs.n] != rows) return fail(SIF_E_INVAL, "%s: bad row segments", who);
+  for (uint32_t r = 0; r < segs.n; ++r)
+    if (segs.row0[r + 1] <= segs.row0[r] || segs.ptr[r] == nullptr || !al16(segs.ptr[r])) return fail(SIF_E_INVAL, "%s: bad row segments", who);
+  return SIF_OK;
+}
+
 sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, void* y, float* mean, float* rstd,
-                                uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c) {
-  REQ(x && g && b && y && rows > 0 && d > 0, "layernorm_fwd: null or empty");
+                                uint32_t rows, uint32_t d, hipStream_t s, const KCtl& c, const RowSegs* segs) {
+  REQ(x && g && b && (y || segs) && rows > 0 && d > 0, "layernorm_fwd: null or empty");
   REQ((d & 7) == 0 && al16(x) && al16(g) && al16(b) && al16(y), "layernorm_fwd: d must be a multiple of 8, pointers 16-byte aligned");
   REQ((mean == nullptr) == (rstd == nullptr), "layernorm_fwd: mean and rstd go together");
+  RowSegs sg = {};
+  if (segs != nullptr) {
+    if (sif_status st = check_segs("layernorm_fwd", *segs, rows)) return st;
+    sg = *segs;
+  }
 #define LNF(V) hipLaunchKernelGGL((layernorm_fwd_kernel<V>), dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, \
-                                  (const bf16_t*)b, (bf16_t*)y, mean, rstd, rows, d, c)
+                                  (const bf16_t*)b, (bf16_t*)y, mean, rstd, rows, d, sg, c)
   if (d <= 1024) LNF(2); else if (d <= 2048) LNF(4); else LNF(0);
 #undef LNF
   return check_launch("layernorm_fwd");
@@ -742,6 +784,16 @@ sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe
   REQ(ids && wte && wpe && x && tokens > 0 && seq > 0, "embed_fwd: null or empty");
   REQ((d & 7) == 0 && al16(wte) && al16(wpe) && al16(x), "embed_fwd: d must be a multiple of 8, pointers 16-byte aligned");
   hipLaunchKernelGGL(embed_fwd_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, ids, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, seq, d, c);
+  return check_launch("embed_fwd");
+}
+
+sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const void* wpe, void* x, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(wte && wpe && x && segs.n > 0 && segs.n <= kMaxRowSegs, "embed_fwd: null or empty");
+  REQ((d & 7) == 0 && al16(wte) && al16(wpe) && al16(x), "embed_fwd: d must be a multiple of 8, pointers 16-byte aligned");
+  const uint32_t tokens = segs.row0[segs.n];
+  if (sif_status st = check_segs("embed_fwd", segs, tokens)) return st;
+  for (uint32_t r = 0; r < segs.n; ++r) REQ(segs.seq[r] > 0, "embed_fwd: empty sequence");
+  hipLaunchKernelGGL(embed_fwd_segs_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, segs, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, d, c);
   return check_launch("embed_fwd");
 }
 
