@@ -62,6 +62,22 @@ __device__ __forceinline__ void at_dma_rows(bf16_t* dst, const bf16_t* src, size
     __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (size_t)r * ld + c * 8), (lds_void_ptr)(dst + first * DH), 16, 0, 0);
   }
 }
+// 32 rows fetched the same way by ONE wavefront into 32*DH elements of LDS of its own (rows swizzled by their number
+// within the 32): whole 128-byte rows per fetch, where a lane that reads its own row from global memory fetches 16
+// bytes of it per instruction.
+template <int DH>
+__device__ __forceinline__ void at_dma_rows_wave(bf16_t* dst, const bf16_t* src, size_t ld, uint32_t row0, uint32_t limit) {
+  typedef __attribute__((address_space(3))) void* lds_void_ptr;
+  typedef __attribute__((address_space(1))) const void* global_void_ptr;
+  constexpr int CH = DH / 8, RPI = 64 / CH;
+  const uint32_t lane = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 32 / RPI; ++i) {
+    const uint32_t first = i * RPI, row = first + lane / CH, c = (lane % CH) ^ (at_key(row) % CH);
+    const uint32_t r = row0 + row < limit ? row0 + row : limit - 1;
+    __builtin_amdgcn_global_load_lds((global_void_ptr)(src + (size_t)r * ld + c * 8), (lds_void_ptr)(dst + first * DH), 16, 0, 0);
+  }
+}
 // A wavefront's 32 x DH results, held transposed in MFMA accumulators (element r of tile d in lane (qi, h) is column
 // d*32 + (r/4)*8 + h*4 + r%4 of row qi), times mul, to global memory as whole rows.  Stored straight from the
 // accumulators a lane would write 8 bytes at a time and every 128-byte line of the output would be touched by eight
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
   if (q_blk >= S) { kernel_end(ctl, true); return; }       // the grid is sized for the longest sequence
 
   bf16x8 fq[KS];
-  {
+  if constexpr (!DB) {
     const bf16_t* qp = base + (size_t)(q < S ? q : 0) * ld_qkv;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -235,8 +251,16 @@ __global__ __launch_bounds__(AT_THREADS, 2) void attn_fwd_kernel(const bf16_t* _
     if (single) l_run = 1.0f;
   };
   if constexpr (DB) {
+    // The wavefront's 32 query rows pass through its own quarter of buffer 1, which nobody fetches into before the
+    // first barrier of the loop; by then the fragments are in registers.  (Rows past the end of the sequence hold a
+    // copy of its last row: their results are not stored.)
+    bf16_t* sQ = sK1 + __builtin_amdgcn_readfirstlane(wave) * (32 * DH);
+    at_dma_rows_wave<DH>(sQ, base, ld_qkv, qw, S);
     at_dma_rows<DH, AT_KV>(sK0, base + da, ld_qkv, 0, S);
     at_dma_rows<DH, AT_KV>(sV0, base + 2 * da, ld_qkv, 0, S);
+    wait_fetches();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) fq[ks] = at_frag<DH>(sQ, qi, ks * 2 + h);
     for (uint32_t kv0 = 0; kv0 < kv_end; kv0 += 2 * AT_KV) {
       wait_fetches();
       __syncthreads();                                   // tile kv0 has landed, nobody reads buffer 1 any more

@@ -375,3 +375,40 @@ def test_fused_attention_backward(bsz, s, h, dh, causal):
     got = up(dqkv)
     for name, lo in (("dq", 0), ("dk", da), ("dv", 2 * da)):
         assert_bf16_close(got[..., lo:lo + da], ref[..., lo:lo + da], f"fused attention {name} s={s} dh={dh} causal={causal}", elem_slack=6e-3)
+
+
+def test_tiles_fetched_into_lds_give_the_same_bits_beside_other_kernels():
+    """The attention kernels and the GEMM fetch their tiles global -> LDS in parts, one part per wavefront, and a
+    barrier publishes the tile: every wavefront has to wait for its own part in front of that barrier.  When it did
+    not, the results were right on a quiet device and changed now and then once other kernels kept the memory system
+    busy.  Here the kernels run many times on one stream while copies run on another; every result must have the bits
+    of the quiet run."""
+    bsz, s, h, dh = 16, 512, 12, 64
+    da = h * dh
+    Q, DO = bf(rnd(51, bsz, s, 3 * da)), bf(rnd(52, bsz, s, da))
+    m, n, k = 2048, 2304, 768
+    A, B = bf(rnd(53, m, k)), bf(rnd(54, n, k))
+
+    def run(stream):
+        o = torch.zeros((bsz, s, da), device=DEV, dtype=torch.bfloat16)
+        lse, delta = torch.zeros((bsz * h, s), device=DEV), torch.zeros((bsz * h, s), device=DEV)
+        dqkv = torch.zeros((bsz, s, 3 * da), device=DEV, dtype=torch.bfloat16)
+        c = torch.zeros((m, n), device=DEV, dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        S.sif_k_attn_fwd(Q, o, bsz, s, h, dh, 3 * da, da, 1, lse=lse, stream=stream)
+        S.sif_k_attn_bwd(Q, o, DO, lse, delta, dqkv, bsz, s, h, dh, 3 * da, da, 3 * da, 1, stream=stream)
+        S.sif_k_gemm_bf16(A, B, c, m, n, k, k, k, n, stream=stream)
+        return o, lse, dqkv, c
+
+    quiet = [t.cpu() for t in run(None)]
+    torch.cuda.synchronize()
+    side, main = torch.cuda.Stream(), torch.cuda.Stream()
+    big = torch.zeros(64 * 2 ** 20, device=DEV)
+    for rep in range(12):
+        with torch.cuda.stream(side):
+            for _ in range(4):
+                big.add_(1.0)                      # 256 MB read and written per pass, beside the kernels under test
+        got = run(main)
+        torch.cuda.synchronize()
+        for name, a, b in zip(("o", "lse", "dqkv", "c"), quiet, got):
+            assert torch.equal(a, b.cpu()), f"{name} differs from the quiet run in repetition {rep}"
