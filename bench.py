@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time)")
     ap.add_argument("--kernel-us-max", type=int, default=600, help="longest kernel the planner emits, us (the 4.98 ms bubble of this workload takes long kernels; the library's default of 300 is for shorter bubbles)")
     ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 10)")
+    ap.add_argument("--feedback-eps-ppm", type=int, default=40000, help="online run with concurrent filling: step time allowed above its running minimum, ppm")
+    ap.add_argument("--feedback-add-ppm", type=int, default=50000, help="online run with concurrent filling: share of busy time added per step while within the allowance, ppm")
     ap.add_argument("--cpu-sample", type=int, default=128, help="samples for the CPU oracle baseline (0 = skip)")
     ap.add_argument("--online-requests", type=int, default=2000, help="online phase (configs[4]): Poisson requests at 200/s; 0 = skip")
     ap.add_argument("--dp-bucket-mb", type=float, default=0.0,
@@ -190,49 +192,62 @@ def main():
         onl = dict(enc, batch=1, seq=Y.ONLINE["seq_max"])
         oshape = encoder_shape(onl)
         online = {}
-        with Session(cfg) as s:
-            s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
-            mo = s.register_inference(oshape, enc_master, online=True, coalesce=args.online_coalesce)
-            ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
-            oids = to(Y.token_ids(7, 1, Y.ONLINE["seq_max"], enc["vocab"]), torch.int32)
-            oouts = [torch.zeros((1, Y.ONLINE["seq_max"], enc["d_model"]), device=dev, dtype=torch.bfloat16) for _ in range(64)]
-            torch.cuda.synchronize()
-            slo = S.sif_calibrate(s.ctx, 3)
-            for _ in range(W):
-                s.step(ids, tg)
-            s.sync()
-            for rate, n_req in ((Y.ONLINE["rate_per_s"], args.online_requests), (Y.ONLINE["rate_per_s"] / 4, max(1, args.online_requests // 4))):
-                t_arr, seqs = Y.poisson_arrivals(6, rate, n_req, Y.ONLINE["seq_min"], Y.ONLINE["seq_max"])
-                S.sif_reset_stats(s.ctx)
-                t_start = S.sif_now_ns()
-
-                def submitter():
-                    for i in range(n_req):
-                        while S.sif_now_ns() - t_start < int(t_arr[i]):
-                            time.sleep(0.0002)
-                        s.submit_online(mo, oids, oouts[i % 64], int(seqs[i]), t_start + int(t_arr[i]))
-
-                th = threading.Thread(target=submitter)
-                th.start()
-                n_steps, t0 = 0, time.perf_counter()
-                while th.is_alive():
+        def online_phase(ocfg, runs, suffix):
+            with Session(ocfg) as s:
+                s.register_training(dshape, dec_master, par_mode=S.SIF_PAR_DP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
+                mo = s.register_inference(oshape, enc_master, online=True, coalesce=args.online_coalesce)
+                ids, tg = to(ids_np, torch.int32), to(tg_np, torch.int32)
+                oids = to(Y.token_ids(7, 1, Y.ONLINE["seq_max"], enc["vocab"]), torch.int32)
+                oouts = [torch.zeros((1, Y.ONLINE["seq_max"], enc["d_model"]), device=dev, dtype=torch.bfloat16) for _ in range(64)]
+                torch.cuda.synchronize()
+                slo = S.sif_calibrate(s.ctx, 3)
+                for _ in range(W + (20 if ocfg.feedback else 0)):      # the share of concurrent filling settles over some steps
                     s.step(ids, tg)
-                    s.sync()
-                    n_steps += 1
-                on_s = time.perf_counter() - t0
-                th.join()
-                drain = 0
-                while s.stats().online_done < n_req and drain < 400:      # bubbles for what is still queued
-                    s.step(ids, tg)
-                    s.sync()
-                    drain += 1
-                so = s.stats()
-                online[f"{rate:g}_req_per_s"] = {
-                    "requests": n_req, "served_during_arrivals_plus_drain": int(so.online_done), "drain_steps": drain,
-                    "p50_ms": so.online_p50_ns / 1e6, "p95_ms": so.online_p95_ns / 1e6,
-                    "ms_per_step": 1e3 * on_s / max(1, n_steps),
-                    "training_slowdown": (on_s / max(1, n_steps)) / (solo_s / K) - 1.0}
-            online["principle_2_ok"] = bool(slo == S.SIF_OK)
+                s.sync()
+                for rate, n_req in runs:
+                    t_arr, seqs = Y.poisson_arrivals(6, rate, n_req, Y.ONLINE["seq_min"], Y.ONLINE["seq_max"])
+                    S.sif_reset_stats(s.ctx)
+                    t_start = S.sif_now_ns()
+
+                    def submitter():
+                        for i in range(n_req):
+                            while S.sif_now_ns() - t_start < int(t_arr[i]):
+                                time.sleep(0.0002)
+                            s.submit_online(mo, oids, oouts[i % 64], int(seqs[i]), t_start + int(t_arr[i]))
+
+                    th = threading.Thread(target=submitter)
+                    th.start()
+                    n_steps, t0 = 0, time.perf_counter()
+                    while th.is_alive():
+                        s.step(ids, tg)
+                        s.sync()
+                        n_steps += 1
+                    on_s = time.perf_counter() - t0
+                    th.join()
+                    drain = 0
+                    while s.stats().online_done < n_req and drain < 400:      # bubbles for what is still queued
+                        s.step(ids, tg)
+                        s.sync()
+                        drain += 1
+                    so = s.stats()
+                    online[f"{rate:g}_req_per_s{suffix}"] = {
+                        "requests": n_req, "served_during_arrivals_plus_drain": int(so.online_done), "drain_steps": drain,
+                        "p50_ms": so.online_p50_ns / 1e6, "p95_ms": so.online_p95_ns / 1e6,
+                        "ms_per_step": 1e3 * on_s / max(1, n_steps),
+                        "training_slowdown": (on_s / max(1, n_steps)) / (solo_s / K) - 1.0}
+                    if ocfg.feedback:
+                        online[f"{rate:g}_req_per_s{suffix}"]["concurrent_share_ppm"] = int(so.concurrent_share_ppm)
+                return slo
+
+        slo = online_phase(cfg, ((Y.ONLINE["rate_per_s"], args.online_requests), (Y.ONLINE["rate_per_s"] / 4, max(1, args.online_requests // 4))), "")
+        # The same load with concurrent filling (this build's reading of the paper's outlook): a request need not wait
+        # for the next bubble, its kernels run beside training, paced by the share of busy time that the feedback
+        # controller allows (training step at most 4 % longer than its running minimum).
+        fcfg = S.sif_default_config()
+        fcfg.allow_serial_streams, fcfg.kernel_us_max, fcfg.period_us, fcfg.feedback = cfg.allow_serial_streams, cfg.kernel_us_max, cfg.period_us, 1
+        fcfg.feedback_eps_ppm, fcfg.feedback_add_ppm = args.feedback_eps_ppm, args.feedback_add_ppm
+        online_phase(fcfg, ((Y.ONLINE["rate_per_s"], args.online_requests),), "_beside_training")
+        online["principle_2_ok"] = bool(slo == S.SIF_OK)
 
     samples = st1.offline_samples - st0.offline_samples
     bubble_ns = st1.bubble_ns - st0.bubble_ns

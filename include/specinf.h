@@ -289,7 +289,9 @@ typedef struct sif_config {
                                 of busy time follows sif_feedback_share after every training iteration during which
                                 the barrier forwarded a kernel.  Reference = the shortest iteration seen since the
                                 last sif_calibrate, starting from its solo iteration time when it was given training
-                                inputs.  Online requests are handled as without it.                         */
+                                inputs.  An online request is pulled outside a bubble too, as soon as the account
+                                is in credit, and its kernels are paid from it one by one (before offline ones);
+                                inside a bubble it is handled as without the option.                        */
   uint32_t feedback_eps_ppm; /* an iteration counts as lengthened beyond ref * (1 + eps)                      */
   uint32_t feedback_add_ppm; /* increase of the share after an iteration that did not lengthen               */
   uint32_t feedback_cap_ppm; /* largest share                                                                 */

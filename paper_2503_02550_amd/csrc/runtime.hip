@@ -316,7 +316,10 @@ static void barrier_main(sif_ctx* c) {
         std::lock_guard<std::mutex> lk(c->mu);
         // Online pull-and-execute: requests are pulled one at a time, in arrival order, each only if the status is
         // idle and the predicted rest of the bubble, less what the requests already pulled still need, holds it.
-        while (into_bubbles && !c->online_q.empty() && c->run_online.size() < 8) {
+        // With concurrent filling an online request need not wait for a bubble: outside one it is pulled as soon as the
+        // time account is in credit, and its kernels are paid from that account one by one as they are released.
+        const bool beside_ok = feedback && c->status.load(std::memory_order_relaxed) != SIF_STATUS_IDLE && c->conc_account_ns > 0;
+        while ((into_bubbles || beside_ok) && !c->online_q.empty() && c->run_online.size() < 8) {
           Job* j = c->online_q.front();
           uint64_t pending = 0;
           for (const Job* q : c->run_online)
@@ -344,7 +347,7 @@ static void barrier_main(sif_ctx* c) {
             g->seq = rows;                 // the calibrated costs scale with the rows the sequence covers
             g->parts.assign(c->online_q.begin(), c->online_q.begin() + (ptrdiff_t)n);
             apply_calibration(im, *g);
-            if (!gated || sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), room, (uint64_t)(job_cost_us(g.get()) * 1000.0))) break;
+            if (!gated || beside_ok || sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), room, (uint64_t)(job_cost_us(g.get()) * 1000.0))) break;
             g.reset();
           }
           if (g) {
@@ -354,7 +357,7 @@ static void barrier_main(sif_ctx* c) {
             continue;
           }
           const uint64_t need = (uint64_t)(job_cost_us(j) * 1000.0);
-          if (gated && !sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), room, need)) break;
+          if (gated && !beside_ok && !sif_online_pull_ok(c->status.load(std::memory_order_relaxed), (uint32_t)c->online_q.size(), room, need)) break;
           c->online_q.pop_front();
           c->run_online.push_back(j);
         }
@@ -402,13 +405,18 @@ static void barrier_main(sif_ctx* c) {
       while (budget-- > 0) {
         Job* j = nullptr;
         bool online = false, beside = false;
-        if (into_bubbles)
-          for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
-        if (j && gated && c->status.load(std::memory_order_relaxed) != SIF_STATUS_IDLE) j = nullptr;   // online kernels only while idle
         // a kernel predicted longer than the largest possible grant is charged the whole grant, so that the head of
         // the queue can always be forwarded in the stable phase
         const uint64_t cap = std::max<uint64_t>(1, c->cfg.alg1.ul / c->cfg.alg1.m);
         auto cost_of = [&](const Job* q) { return std::min<uint64_t>((uint64_t)(q->plan[q->next_op].cost_us + 0.999), cap); };
+        if (into_bubbles || feedback)
+          for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
+        // online kernels without tokens only while idle (and not after a skipped launch, until the next bubble begins);
+        // otherwise, with concurrent filling, beside training against the time account
+        if (j && gated && (!into_bubbles || c->status.load(std::memory_order_relaxed) != SIF_STATUS_IDLE)) {
+          if (feedback && c->conc_account_ns >= 1000ull * cost_of(j)) beside = true;
+          else j = nullptr;
+        }
         if (!j) {
           // Offline: every instance spends its own balance, FIFO within the instance (its head kernel blocks the
           // rest of its queue); the instances take turns, and one that is out of tokens does not hold up the others.

@@ -575,3 +575,67 @@ def test_online_requests_that_wait_together_run_as_one_sequence():
             assert torch.equal(out, outs[i]), i
             if i in (0, 6, 9):
                 assert_bf16_close(up(outs[i]), OE.encoder_forward(w, idn, enc, "bf16"), "coalesced online request", elem_slack=1.5e-2)
+
+
+def test_online_requests_run_beside_training_with_concurrent_filling():
+    """With concurrent filling on, an online request does not wait for the next bubble: its kernels are released
+    beside training against the time account.  The training result keeps its bits, every output has the bits of a run
+    by itself, kernels did start outside the bubbles, and without the option the same requests start inside bubbles
+    only."""
+    enc = dict(ENC, batch=1, seq=64)
+    shape, ishape = decoder_shape(DEC), encoder_shape(enc)
+    master = Y.encoder_params(2, enc, perturb=True)
+    lens = [64, 5, 33, 17, 64, 48, 1, 29]
+    n_req = len(lens)
+    res = {}
+    for feedback in (0, 1):
+        cfg = S.sif_default_config()
+        cfg.collocate = 0
+        cfg.feedback, cfg.feedback_add_ppm, cfg.feedback_eps_ppm, cfg.feedback_cap_ppm = feedback, 250_000, 100_000, 750_000
+        with Session(cfg) as s:
+            s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=300_000)
+            m = s.register_inference(ishape, P.pack(ishape, master), online=True, coalesce=4)
+            x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+            S.sif_calibrate(s.ctx, 2, x, t)
+            n_cal = last_launch(s)
+            ids = [i32(Y.token_ids(300 + i, 1, lens[i], enc["vocab"])) for i in range(n_req)]
+            outs = [torch.zeros((1, lens[i], enc["d_model"]), device=DEV, dtype=torch.bfloat16) for i in range(n_req)]
+            torch.cuda.synchronize()
+            S.sif_reset_stats(s.ctx)
+            S.sif_set_collocate(s.ctx, 1)
+            tickets = []
+            for step in range(12):
+                if step >= 2 and len(tickets) < n_req:         # the account is in credit after the first steps
+                    tickets.append(s.submit_online(m, ids[len(tickets)], outs[len(tickets)], lens[len(tickets)]))
+                s.step(x, t)
+                s.sync()
+            w = up(s.train["master"])
+            extra = 0
+            while s.stats().online_done < n_req and extra < 60:
+                s.step(x, t)
+                s.sync()
+                extra += 1
+            for tk in tickets:
+                s.wait(tk, 20.0)
+            st = s.stats()
+            assert st.online_done == n_req
+            res[feedback] = (w, [o.cpu() for o in outs], bubbles_and_kernels(s, n_cal), st)
+    assert np.array_equal(res[0][0], res[1][0])                # training does not see what runs beside it
+    bubbles0, ran0, _ = res[0][2]
+    assert_starts_inside_bubbles(bubbles0, ran0)
+    bubbles, ran, _ = res[1][2]
+    b0 = np.array([b[0] for b in bubbles]); b1 = np.array([b[1] for b in bubbles])
+    outside = 0
+    for t0, _ in ran:
+        i = np.searchsorted(b0, t0, side="right") - 1
+        outside += not (i >= 0 and b0[i] <= t0 <= b1[i])
+    assert outside > 0
+    for i in range(n_req):
+        assert torch.equal(res[0][1][i], res[1][1][i]), i     # and both are what a run by itself gives (tested above for the bubbles' path)
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, master), online=True)
+        for i in (0, 6):
+            I, out = i32(Y.token_ids(300 + i, 1, lens[i], enc["vocab"])), torch.zeros_like(res[1][1][i], device=DEV)
+            torch.cuda.synchronize()
+            s.wait(s.submit_online(m, I, out, lens[i]))
+            assert torch.equal(out.cpu(), res[1][1][i]), i
