@@ -28,7 +28,7 @@ os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # Average HBM bytes per dispatch of gemm_bf16_kernel<0,0> in this workload, from the FETCH_SIZE / WRITE_SIZE counter
 # runs summarised in profiles/bench_cfg2_hbm_traffic.md (counters cannot be read from inside a timed run).
-GEMM00_HBM_BYTES_PER_LAUNCH = 366.2e6
+GEMM00_HBM_BYTES_PER_LAUNCH = 365.2e6
 
 
 def cpu_baseline(sample_batch):
@@ -60,6 +60,7 @@ def main():
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time)")
     ap.add_argument("--kernel-us-max", type=int, default=600, help="longest kernel the planner emits, us (the 4.98 ms bubble of this workload takes long kernels; the library's default of 300 is for shorter bubbles)")
     ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 10)")
+    ap.add_argument("--skip-concurrent", action="store_true", help="leave out the extra phase with concurrent filling (profiles of the headline phase: it is then the last thing the process does)")
     ap.add_argument("--feedback", action="store_true", help="offline phase with concurrent filling as well (kernels beside training within the allowance)")
     ap.add_argument("--feedback-eps-ppm", type=int, default=30000, help="online run with concurrent filling: step time allowed above its running minimum, ppm")
     ap.add_argument("--online-feedback-eps-ppm", type=int, default=40000, help="the same allowance for the online run with concurrent filling")
@@ -190,7 +191,7 @@ def main():
     # Not the headline: `value` is the paper's method, bubbles only.  Here the barrier also releases offline kernels
     # beside training, paced by the share of busy time that the feedback controller allows.
     concurrent = None
-    if not args.feedback and not args.allow_serial_streams:
+    if not args.feedback and not args.allow_serial_streams and not args.skip_concurrent:
         fcfg = S.sif_default_config()
         fcfg.kernel_us_max, fcfg.period_us, fcfg.feedback = cfg.kernel_us_max, cfg.period_us, 1
         fcfg.feedback_eps_ppm, fcfg.feedback_add_ppm = args.feedback_eps_ppm, args.feedback_add_ppm
