@@ -393,6 +393,55 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
     const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
     const float bias8[8] = {bflo(bias_q.x), bfhi(bias_q.x), bflo(bias_q.y), bfhi(bias_q.y), bflo(bias_q.z), bfhi(bias_q.z), bflo(bias_q.w), bfhi(bias_q.w)};
+    // Epilogues that read nothing but the bias (plain, bias, bias + GELU without the pre-activation output) are
+    // finished in the accumulator layout, where a lane's column is fixed, and staged as bf16: two vertically adjacent
+    // results share a 32-bit word, the staging area is [16 row pairs][64 columns] words, half the LDS traffic of the
+    // fp32 staging below.  A lane then reads eight words = eight columns of two rows, separates the rows with byte
+    // permutes and stores two 16-byte row vectors.  The arithmetic per element is the same as in gemm_epilogue8.
+    const bool packed = vec_ok && (p.epi & (SIF_EPI_RESIDUAL | SIF_EPI_GELU_GRAD | SIF_EPI_OUT_F32)) == 0 &&
+                        !((p.epi & SIF_EPI_GELU) && p.aux != nullptr);
+    if (packed) {
+      uint32_t* sP = reinterpret_cast<uint32_t*>(sW);
+      float bcol[TJ];
+#pragma unroll
+      for (int j = 0; j < TJ; ++j) {
+        const uint32_t n = n0 + wn * WCOLS + j * 32 + (lane & 31);
+        bcol[j] = (p.bias != nullptr && n < p.n) ? bf2f(p.bias[n]) : 0.f;
+      }
+      const uint32_t hh = lane >> 5;
+#pragma unroll
+      for (int i = 0; i < TI; ++i) {
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; r += 2) {
+            float x0 = acc[i][j][r] * p.alpha + bcol[j], x1 = acc[i][j][r + 1] * p.alpha + bcol[j];
+            if (p.epi & SIF_EPI_GELU) { x0 = gelu_fast(x0); x1 = gelu_fast(x1); }
+            const uint32_t pr = (r >> 2) * 4 + hh * 2 + ((r & 3) >> 1), col = (j * 32 + (lane & 31)) ^ (hh << 5);
+            sP[pr * WCOLS + col] = pack_bf2(x0, x1);
+          }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          const uint32_t item = lane + it * 64, pr = item >> 3, c8 = item & 7;     // 16 row pairs x 8 chunks of 8 columns
+          const uint32_t pos = (c8 ^ (((pr >> 1) & 1u) << 2)) * 8;
+          const uint4 w0 = *reinterpret_cast<const uint4*>(sP + pr * WCOLS + pos), w1 = *reinterpret_cast<const uint4*>(sP + pr * WCOLS + pos + 4);
+          const uint4 even = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x05040100), __builtin_amdgcn_perm(w0.w, w0.z, 0x05040100),
+                                        __builtin_amdgcn_perm(w1.y, w1.x, 0x05040100), __builtin_amdgcn_perm(w1.w, w1.z, 0x05040100));
+          const uint4 odd = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x07060302), __builtin_amdgcn_perm(w0.w, w0.z, 0x07060302),
+                                       __builtin_amdgcn_perm(w1.y, w1.x, 0x07060302), __builtin_amdgcn_perm(w1.w, w1.z, 0x07060302));
+          const uint32_t m = m0 + wm * (TI * 32) + i * 32 + 2 * pr, n = n0 + wn * WCOLS + c8 * 8;
+          bf16_t* cp = reinterpret_cast<bf16_t*>(p.c) + c_off + (size_t)m * p.ldc + n;
+          if (n < p.n) {
+            if (m < p.m) *reinterpret_cast<uint4*>(cp) = even;
+            if (m + 1 < p.m) *reinterpret_cast<uint4*>(cp + p.ldc) = odd;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    } else
 #pragma unroll
     for (int i = 0; i < TI; ++i) {
       // what the epilogue reads from global memory for this pass is requested before the staging, not inside it
