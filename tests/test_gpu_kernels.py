@@ -412,3 +412,21 @@ def test_tiles_fetched_into_lds_give_the_same_bits_beside_other_kernels():
         torch.cuda.synchronize()
         for name, a, b in zip(("o", "lse", "dqkv", "c"), quiet, got):
             assert torch.equal(a, b.cpu()), f"{name} differs from the quiet run in repetition {rep}"
+
+
+@pytest.mark.parametrize("tile", [128, 256])
+def test_gemm_bf16_packed_and_fp32_staged_epilogues_give_the_same_bits(tile):
+    """Epilogues that read only the bias are finished in the accumulator layout and staged as bf16; with the
+    pre-activation output requested the same product takes the fp32-staged path.  Both must give the same bits."""
+    m, n, k = 520, 776, 192
+    a, b, bias = rnd(61, m, k), rnd(62, n, k), rnd(63, n)
+    A, B, BI = bf(a), bf(b), bf(bias)
+    c0 = torch.zeros((m, n), device=DEV, dtype=torch.bfloat16)
+    c1, z = torch.zeros_like(c0), torch.zeros_like(c0)
+    S.sif_k_gemm_bf16(A, B, c0, m, n, k, k, k, n, epilogue=S.SIF_EPI_GELU, bias=BI, tile=tile)
+    S.sif_k_gemm_bf16(A, B, c1, m, n, k, k, k, n, epilogue=S.SIF_EPI_GELU, bias=BI, aux=z, tile=tile)
+    torch.cuda.synchronize()
+    assert torch.equal(c0, c1)
+    acc = q(a) @ q(b).T + q(bias)
+    assert_bf16_close(up(z), acc, "pre-activation")
+    assert_bf16_close(up(c0), N.gelu(acc), "gelu epilogue", elem_slack=1e-2)
