@@ -432,19 +432,26 @@ def test_overlapped_gradient_exchange_exposes_only_its_tail():
     assert len(want_buckets) == 3
     w_plain, _, last_plain, _, _, _ = run_overlapped(0, bw, True)
     for device_timed in (True, False):
-        w, buckets, last, st, _, _ = run_overlapped(cap, bw, device_timed)
-        assert np.array_equal(w, w_plain)                                  # finalizing per bucket changes no gradient bit
-        assert [b for b, _ in buckets] == [sum(groups[g] for g in grp) for grp in want_buckets]
-        end_of = {rid: t1 for kind, rid, _, _, _, t1 in last if kind == 1}
-        (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
-        ready = [end_of[r] for _, r in buckets]
-        assert ready == sorted(ready) and ready[-1] <= b0
-        dur = [OB.collective_ns(b, bw) for b, _ in buckets]
-        want = OB.dp_overlapped_wait(ready, dur, b0)
-        whole, = [t1 - t0 for kind, _, _, _, t0, t1 in last_plain if kind == 3]
-        assert 0 < want < whole                                             # part of the exchange hid behind backward
-        got = b1 - b0
-        assert want - 500 <= got <= want + (6_000 if device_timed else 300_000), (got, want, device_timed)
+        # A bubble that the host times ends late when the monitor thread loses its core for a scheduling quantum
+        # (milliseconds): such a run is repeated; the lower bound and everything else must hold in every run.
+        for attempt in range(4):
+            w, buckets, last, st, _, _ = run_overlapped(cap, bw, device_timed)
+            assert np.array_equal(w, w_plain)                              # finalizing per bucket changes no gradient bit
+            assert [b for b, _ in buckets] == [sum(groups[g] for g in grp) for grp in want_buckets]
+            end_of = {rid: t1 for kind, rid, _, _, _, t1 in last if kind == 1}
+            (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
+            ready = [end_of[r] for _, r in buckets]
+            assert ready == sorted(ready) and ready[-1] <= b0
+            dur = [OB.collective_ns(b, bw) for b, _ in buckets]
+            want = OB.dp_overlapped_wait(ready, dur, b0)
+            whole, = [t1 - t0 for kind, _, _, _, t0, t1 in last_plain if kind == 3]
+            assert 0 < want < whole                                         # part of the exchange hid behind backward
+            got = b1 - b0
+            assert want - 500 <= got, (got, want, device_timed)
+            if got <= want + (6_000 if device_timed else 300_000):
+                break
+        else:
+            raise AssertionError((got, want, device_timed))
     # a link so fast that the exchange is over when backward ends: no bubble at all, the stream never goes idle
     _, _, last, st, _, _ = run_overlapped(cap, 10 ** 15, True)
     (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
