@@ -59,7 +59,7 @@ def main():
     ap.add_argument("--coalesce", type=int, default=16, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time)")
     ap.add_argument("--kernel-us-max", type=int, default=600, help="longest kernel the planner emits, us (the 4.98 ms bubble of this workload takes long kernels; the library's default of 300 is for shorter bubbles)")
-    ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 10)")
+    ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 5)")
     ap.add_argument("--skip-concurrent", action="store_true", help="leave out the extra phase with concurrent filling (profiles of the headline phase: it is then the last thing the process does)")
     ap.add_argument("--feedback", action="store_true", help="offline phase with concurrent filling as well (kernels beside training within the allowance)")
     ap.add_argument("--feedback-eps-ppm", type=int, default=30000, help="online run with concurrent filling: step time allowed above its running minimum, ppm")

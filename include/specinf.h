@@ -297,7 +297,7 @@ typedef struct sif_config {
   uint32_t feedback_cap_ppm; /* largest share                                                                 */
 } sif_config;
 
-/* Fills *cfg with the defaults (P = 10 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 200, LL = 400, UL = 800
+/* Fills *cfg with the defaults (P = 5 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 200, LL = 400, UL = 800
  * tokens, kernel_us_max 300, collocate 1, feedback 0 with eps 2 %, add 2 %, cap 100 %). */
 sif_status sif_default_config(sif_config* cfg);
 

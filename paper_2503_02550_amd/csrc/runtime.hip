@@ -549,7 +549,7 @@ sif_status sif_default_config(sif_config* cfg) {
   if (!cfg) return fail(SIF_E_INVAL, "default_config: null");
   memset(cfg, 0, sizeof(*cfg));
   cfg->struct_size = sizeof(*cfg);
-  cfg->period_us = 10; cfg->window = 64; cfg->count_running = 1;
+  cfg->period_us = 5; cfg->window = 64; cfg->count_running = 1;
   cfg->alg1.alpha = 1; cfg->alg1.beta = 3; cfg->alg1.gamma_num = 2; cfg->alg1.gamma_den = 1; cfg->alg1.m = 1;
   cfg->alg1.t0 = 200; cfg->alg1.ll = 400; cfg->alg1.ul = 800;
   cfg->kernel_us_max = 300; cfg->collocate = 1; cfg->device_timed_bubbles = 0; cfg->device_capacity_bytes = 0;

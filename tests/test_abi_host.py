@@ -143,5 +143,5 @@ def test_param_layout_counts():
 
 def test_default_config_and_sizes():
     cfg = S.sif_default_config()
-    assert cfg.period_us == 10 and cfg.alg1.alpha <= cfg.alg1.beta and cfg.alg1.ll <= cfg.alg1.ul
+    assert cfg.period_us == 5 and cfg.alg1.alpha <= cfg.alg1.beta and cfg.alg1.ll <= cfg.alg1.ul
     assert S.sif_ctx_workspace_bytes() > 2 * 65536 * 32
