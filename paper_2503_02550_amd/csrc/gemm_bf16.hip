@@ -251,6 +251,8 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   __shared__ __align__(1024) bf16_t sA1[BM * BK];
   __shared__ __align__(1024) bf16_t sB0[BN * BK];
   __shared__ __align__(1024) bf16_t sB1[BN * BK];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+
   // Block -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
   // every XCD a contiguous run of tiles, and walk each run in bands of 8 tile rows, so that the tiles an XCD works
   // on at one time share their A and B panels in that XCD's L2.
@@ -266,25 +268,15 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   }
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
   const bool skip = (p.epi & SIF_EPI_CAUSAL_SKIP) && n0 > m0 + BM - 1;
-  const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
-  const bf16_t* A = p.a + bo * p.a_so + bi * p.a_si;
-  const bf16_t* B = p.b + bo * p.b_so + bi * p.b_si;
-  uint32_t k_begin = 0, k_end = p.k;
-  if (p.k_limit != 0) k_end = min(p.k, p.k_limit - bi * p.k);      // slices of one long K: the last may be shorter
-  if (p.k_causal == 1) k_end = min(p.k, m0 + BM);
-  if (p.k_causal == 2) k_begin = (m0 / BK) * BK;
-  const uint32_t nt = (k_end - k_begin + BK - 1) / BK;
-  // without EDGE the launcher guarantees that every tile is interior
-  const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
-  // Interior tiles: tile t+1 is fetched into the other pair of buffers while tile t is multiplied; the other block of
-  // the CU covers what the fetch latency exceeds one K step.  The first tile is sent for before the prologue, so that
-  // it travels while the gate of a speculative launch decides (two memory round trips): a fetch changes nothing
-  // outside this block's LDS, and a block that is then told to skip only waits for it to land.
-  DmaStream<ALAY, BM, THREADS> ta(A, p.lda, m0, p.m, k_begin);
-  DmaStream<BLAY, BN, THREADS> tb(B, p.ldb, n0, p.n, k_begin);
-  if (!skip && interior) { ta.next(sA0); tb.next(sB0); }
-  if (!kernel_begin(ctl)) { wait_fetches(); kernel_end(ctl, false); return; }
   if (!skip) {
+    const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
+    const bf16_t* A = p.a + bo * p.a_so + bi * p.a_si;
+    const bf16_t* B = p.b + bo * p.b_so + bi * p.b_si;
+    uint32_t k_begin = 0, k_end = p.k;
+    if (p.k_limit != 0) k_end = min(p.k, p.k_limit - bi * p.k);      // slices of one long K: the last may be shorter
+    if (p.k_causal == 1) k_end = min(p.k, m0 + BM);
+    if (p.k_causal == 2) k_begin = (m0 / BK) * BK;
+
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / WN, wn = wave % WN;
     floatx16 acc[TI][TJ];
@@ -343,7 +335,15 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     };
     // The loop takes two K steps per trip (the register sets and LDS buffers alternate by name) and has no exit in
     // its middle, so that the accumulators stay in the same registers throughout; an odd last tile is done after it.
+    const uint32_t nt = (k_end - k_begin + BK - 1) / BK;
+    // without EDGE the launcher guarantees that every tile is interior
+    const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
     if (interior) {
+      // tile t+1 is fetched into the other pair of buffers while tile t is multiplied; the other block of the CU
+      // covers what the fetch latency exceeds one K step
+      DmaStream<ALAY, BM, THREADS> ta(A, p.lda, m0, p.m, k_begin);
+      DmaStream<BLAY, BN, THREADS> tb(B, p.ldb, n0, p.n, k_begin);
+      ta.next(sA0); tb.next(sB0);
       wait_fetches();
       __syncthreads();
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
