@@ -437,7 +437,8 @@ static void barrier_main(sif_ctx* c) {
         // rounds of its tiles would, is cut in two along its rows (same bits); the first part goes out now.
         if (gated && !online && !beside && j->plan[j->next_op].row_split) {
           const Op& whole = j->plan[j->next_op];
-          const uint64_t rest_ns = predicted_remaining_ns(c), ahead_ns = c->outstanding_us * 1000ull;
+          // what is in flight takes its predicted time plus the gap between dependent kernels of a stream, each
+          const uint64_t rest_ns = predicted_remaining_ns(c), ahead_ns = c->outstanding_us * 1000ull + 5000ull * c->inflight.size();
           if (rest_ns > ahead_ns) {
             const double avail_us = (double)(rest_ns - ahead_ns) / 1000.0 - 10.0;
             const uint32_t unit = gemm_round_rows(whole.gemm);
