@@ -108,7 +108,7 @@ struct Job {
   int32_t result = 1;            // 1 pending, 0 done, < 0 error
 };
 
-struct InFlight { uint32_t kseq; Job* job; uint32_t op; uint32_t idle_seq; };
+struct InFlight { uint32_t kseq; Job* job; uint32_t op; uint32_t idle_seq; uint64_t cost_us; };      // cost_us: what the launch added to outstanding_us
 
 // Layout / plan builders (models.hip)
 uint64_t model_n_params(const sif_model_shape& s);

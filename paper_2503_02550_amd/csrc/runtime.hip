@@ -263,8 +263,7 @@ static void barrier_main(sif_ctx* c) {
     while (!c->inflight.empty() && c->inflight.front().kseq <= done && (skip == kNone || c->inflight.front().kseq < skip)) {
       InFlight f = c->inflight.front();
       c->inflight.pop_front();
-      const double cost = f.job->plan[f.op].cost_us;
-      c->outstanding_us = c->outstanding_us > (uint64_t)cost ? c->outstanding_us - (uint64_t)cost : 0;
+      c->outstanding_us = c->outstanding_us > f.cost_us ? c->outstanding_us - f.cost_us : 0;      // exactly what its launch added
       if (++f.job->done_ops == f.job->plan.size()) {
         auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), f.job), q.end()); };
         drop(c->run_online); drop(c->run_offline);
@@ -282,7 +281,7 @@ static void barrier_main(sif_ctx* c) {
         c->hold_seq = f.idle_seq;
       }
       c->outstanding_us = 0;
-      for (const InFlight& f : c->inflight) c->outstanding_us += (uint64_t)f.job->plan[f.op].cost_us;
+      for (const InFlight& f : c->inflight) c->outstanding_us += f.cost_us;
       std::fill(c->balance.begin(), c->balance.end(), 0);
       launch_reset_skip(c->I.stream, c->I.rec, c->mir, ++c->reset_epoch);
       c->awaiting_reset = true;
@@ -457,6 +456,13 @@ static void barrier_main(sif_ctx* c) {
         Op& op = j->plan[j->next_op];
         const uint64_t cost = cost_of(j);
         if (gated && c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
+        // What the device gate is bound to refuse is not launched: behind what is in flight (its predicted time and the
+        // gap after each kernel), this kernel would end after the predicted end of the bubble.  The gate still decides;
+        // this spares launches whose empty blocks would pass through the CUs beside the training kernels that follow.
+        if (gated && !beside) {
+          const uint64_t rest_ns = predicted_remaining_ns(c);
+          if (rest_ns < 1000ull * c->outstanding_us + 5000ull * c->inflight.size() + (uint64_t)(op.cost_us * 1000.0)) break;
+        }
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
         if (j->next_op + 1 == j->plan.size()) k.flags |= 1u;
@@ -471,7 +477,7 @@ static void barrier_main(sif_ctx* c) {
           break;
         }
         c->kernels_launched.fetch_add(1, std::memory_order_relaxed);
-        c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq)});
+        c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq), cost});
         j->next_op++;
         c->outstanding_us += cost;
         if (beside) c->conc_account_ns -= std::min<uint64_t>(c->conc_account_ns, 1000ull * cost);
