@@ -28,7 +28,7 @@ os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # Average HBM bytes per dispatch of gemm_bf16_kernel<0,0> in this workload, from the FETCH_SIZE / WRITE_SIZE counter
 # runs summarised in profiles/bench_cfg2_hbm_traffic.md (counters cannot be read from inside a timed run).
-GEMM00_HBM_BYTES_PER_LAUNCH = 365.0e6
+GEMM00_HBM_BYTES_PER_LAUNCH = 368.1e6
 
 
 def cpu_baseline(sample_batch):
