@@ -145,3 +145,14 @@ def test_default_config_and_sizes():
     cfg = S.sif_default_config()
     assert cfg.period_us == 5 and cfg.alg1.alpha <= cfg.alg1.beta and cfg.alg1.ll <= cfg.alg1.ul
     assert S.sif_ctx_workspace_bytes() > 2 * 65536 * 32
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it must say so and exit with an error before touching a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
