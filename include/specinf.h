@@ -209,6 +209,16 @@ uint32_t sif_colsum_parts(uint32_t rows);
 sif_status sif_k_colsum(const void* x_dev, uint32_t ld, void* out_dev, float* part_dev, uint32_t rows, uint32_t n,
                         void* stream);
 
+/* sif_k_colsum for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the partial sums live in a device array inside the library, 4 MiB on every GPU
+ * the library runs on, held until the process ends.  Same kernels, same bits as sif_k_colsum.  Calls no hipMalloc,
+ * hipFree or other allocating routine.  SIF_E_NOMEM (nothing launched) if sif_colsum_parts(rows) * n exceeds
+ * sif_colsum_static_max_floats() (2^20); SIF_E_INVAL as sif_k_colsum.  All calls on one GPU share the one array, which
+ * keeps the last call's contents (every element that is read is written first by the same call): two calls that
+ * overlap on one GPU (different streams, no ordering between them) race; calls on one stream are safe. */
+sif_status sif_k_colsum_static(const void* x_dev, uint32_t ld, void* out_dev, uint32_t rows, uint32_t n, void* stream);
+uint64_t sif_colsum_static_max_floats(void);
+
 /* Row softmax of fp32 scores [batch][rows][ld_s] into bf16 probabilities [batch][rows][ld_p]; causal != 0
  * keeps columns j <= i only.  Columns >= cols (up to ld_p) are written as zeros; with causal != 0 the zero fill of
  * row i stops at the end of its 128-column tile, (i/128 + 1)*128, which is as far as a causal product reads. */

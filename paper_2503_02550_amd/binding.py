@@ -144,6 +144,8 @@ _sig("sif_k_layernorm_fwd", i32, vp, vp, vp, vp, vp, vp, u32, u32, vp)
 _sig("sif_k_layernorm_bwd", i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, vp)
 _sig("sif_colsum_parts", u32, u32)
 _sig("sif_k_colsum", i32, vp, u32, vp, vp, u32, u32, vp)
+_sig("sif_k_colsum_static", i32, vp, u32, vp, u32, u32, vp)
+_sig("sif_colsum_static_max_floats", u64)
 _sig("sif_k_softmax_fwd", i32, vp, vp, u32, u32, u32, u32, u32, u32, vp)
 _sig("sif_k_softmax_bwd", i32, vp, vp, vp, u32, u32, u32, u32, f32, u32, vp)
 _sig("sif_k_embed_fwd", i32, vp, vp, vp, vp, u32, u32, u32, vp)
@@ -258,6 +260,14 @@ def sif_colsum_parts(rows):
 
 def sif_k_colsum(x, ld, out, part, rows, n, stream=None):
     return check(lib.sif_k_colsum(ptr(x), ld, ptr(out), ptr(part), rows, n, stream_ptr(stream)))
+
+
+def sif_k_colsum_static(x, ld, out, rows, n, stream=None):
+    return check(lib.sif_k_colsum_static(ptr(x), ld, ptr(out), rows, n, stream_ptr(stream)))
+
+
+def sif_colsum_static_max_floats():
+    return lib.sif_colsum_static_max_floats()
 
 
 def sif_k_softmax_fwd(s, p, batch, rows, cols, ld_s, ld_p, causal, stream=None):
