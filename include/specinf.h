@@ -55,7 +55,13 @@ const char* sif_last_error(void);
 int32_t sif_abi_version(void);
 
 /* ====================================================================================================
- * 1. Scheduler rules as pure host functions (no GPU needed).  The runtime threads call exactly these.
+ * 1. Scheduler rules as pure host functions (no GPU needed).  The monitor thread calls sif_zero_count and
+ *    sif_alg1_step once per period; the barrier thread takes the offline token decision with sif_kb_release (one
+ *    kernel at a time, charged sif_kb_charge) and the online decision with sif_online_pull_ok.  Around the token
+ *    rule the barrier applies rules of its own, none of them the paper's: a bound on the predicted time of
+ *    forwarded but unfinished kernels, no launch that the device gate is bound to refuse, nothing after a skipped
+ *    launch until the next bubble begins, and turns between several instances.  sif_sched_run_trace drives the
+ *    monitor -> Algorithm 1 -> token chain, the very objects the threads keep, over a recorded trace.
  * ==================================================================================================== */
 
 /* Constants of Algorithm 1 (inputs alpha, beta, gamma, m, UL, LL of the listing) plus the seed t0 that the
@@ -85,6 +91,36 @@ sif_status sif_alg1_step(const sif_alg1_params* p, uint32_t zc, uint64_t* pool, 
  * are forwarded (a kernel is forwarded iff balance >= cost, then balance -= cost; the head blocks the rest).
  * *balance_left may be null. */
 uint32_t sif_kb_release(const uint32_t* costs, uint32_t n, uint64_t balance, uint64_t* balance_left);
+
+/* What a kernel predicted to run predicted_us microseconds is charged: one token per microsecond, but never more
+ * than the largest grant an instance can receive, floor(UL / m) (at least 1), so that the head of a queue can always
+ * be forwarded in the stable phase (this build's reading: the paper says only "proportionate to its size"). */
+uint32_t sif_kb_charge(uint64_t predicted_us, uint64_t ul, uint32_t m);
+
+/* The chain Bubble Monitor -> Algorithm 1 -> offline Kernel Barrier (Sec. 3.3) over a trace, without a GPU: for each
+ * of the n_periods per-period counts of training kernels the window of `window` entries gives Z_c, Algorithm 1 the
+ * pool, grant and status, the grant replaces the balance of the one inference instance, and kernels are forwarded
+ * from the head of the FIFO `costs` (tokens each) while the balance covers them.  Runs the same window and token
+ * objects the monitor and barrier threads keep.  Per period t (null outputs are skipped): zc_out[t], pool_out[t],
+ * grant_out[t], status_out[t], released_out[t] = kernels forwarded in that period. */
+sif_status sif_sched_run_trace(const sif_alg1_params* p, uint32_t window, const uint32_t* counts, uint32_t n_periods,
+                               const uint32_t* costs, uint32_t n_costs, uint32_t* zc_out, uint64_t* pool_out,
+                               uint64_t* grant_out, int32_t* status_out, uint32_t* released_out);
+
+/* The invariant "no inference kernel starts outside a detected bubble": 1 iff a kernel that started at t0 violated
+ * it, given the interval [bubble_begin, bubble_end] of the bubble the device gate admitted it to (all three on the
+ * device clock; bubble_end = 0: the bubble was not over yet when the check was made). */
+int32_t sif_gate_violation(uint64_t t0, uint64_t bubble_begin, uint64_t bubble_end);
+
+/* Latency histogram of the statistics: sixteen buckets per power of two (values below 16 ns one bucket each), so a
+ * bucket is at most 1/16 wider than its lower edge.  sif_latency_bucket: the bucket a latency falls into;
+ * sif_latency_bucket_lower_ns: a bucket's lower edge; sif_latency_buckets: how many there are. */
+uint32_t sif_latency_bucket(uint64_t ns);
+uint64_t sif_latency_bucket_lower_ns(uint32_t bucket);
+uint32_t sif_latency_buckets(void);
+/* Nearest-rank percentile (0 < p <= 1) of the values counted in counts[0..n_buckets): the rank-ceil(p * total) value's
+ * bucket, reported as the middle of the values that bucket holds; 0 if nothing was counted. */
+uint64_t sif_latency_percentile(const uint64_t* counts, uint32_t n_buckets, double p);
 
 /* Kernel Barrier, online rule: 1 iff status is idle, a request waits and the predicted rest of the bubble
  * holds the predicted request time. */
@@ -243,7 +279,7 @@ sif_status sif_k_attn_fwd_varlen(const void* qkv_dev, void* o_dev, const uint32_
 /* Fused attention backward: dqkv [batch*seq][ld_dqkv] (columns [dq | dk | dv]) from qkv, the forward's o and lse and
  * the upstream gradient d_o [batch*seq][ld_o] (same layout and leading dimension as o).  The probabilities are
  * recomputed as exp(score - lse) and rounded to bf16, dS = P .* (dP - delta) / sqrt(dh) likewise, as the training
- * step of the collocated instance stores them (Sec. 4 workloads: transformer training); delta_dev (device, fp32
+ * step of the collocated instance stores them (Sec. 5.1 workloads: transformer training); delta_dev (device, fp32
  * [batch*heads][seq]) is scratch that receives rowsum(d_o .* o).  Two launches on `stream` (dq; dk and dv), no
  * atomics: results do not depend on the launch configuration.  d_head must be 64 or 128. */
 sif_status sif_k_attn_bwd(const void* qkv_dev, const void* o_dev, const void* d_o_dev, const float* lse_dev, float* delta_dev,
@@ -305,10 +341,20 @@ typedef struct sif_config {
   uint32_t feedback_eps_ppm; /* an iteration counts as lengthened beyond ref * (1 + eps)                      */
   uint32_t feedback_add_ppm; /* increase of the share after an iteration that did not lengthen               */
   uint32_t feedback_cap_ppm; /* largest share                                                                 */
+  uint32_t gate_spin_log2;   /* 0 = default (18).  A block of a speculatively launched inference kernel waits at most
+                                2^gate_spin_log2 polls for the decision of the launch's first block, then gives the
+                                launch back to the host (it is run again).  Tests set 0 < value <= 30 small to force
+                                that path; every kernel still exits normally.                                  */
+  uint32_t gate_spin_every;  /* 0 or 1: gate_spin_log2 applies to every launch; n > 1: only to launches whose number on
+                                the inference stream is a multiple of n (the others wait the default time), so that a
+                                launch that was given back gets through when it is run again                    */
 } sif_config;
 
 /* Fills *cfg with the defaults (P = 5 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 200, LL = 400, UL = 800
- * tokens, kernel_us_max 300, collocate 1, feedback 0 with eps 2 %, add 2 %, cap 100 %). */
+ * tokens, kernel_us_max 300, collocate 1, feedback 0 with eps 2 %, add 2 %, cap 100 %).  With these constants a
+ * period's grant (up to 800 us of predicted kernel time per 5 us period) never limits what is forwarded: the
+ * speculation bound, the predicted end of the bubble and the device gate do.  Tokens limit the releases when UL is
+ * of the order of the period (e.g. P = 100, t0 = 25, LL = 50, UL = 100). */
 sif_status sif_default_config(sif_config* cfg);
 
 /* Bytes of device workspace sif_create needs (activity records, trace rings). */
@@ -368,7 +414,8 @@ typedef struct sif_train_desc {
 
 uint64_t sif_train_workspace_bytes(const sif_train_desc* d);
 
-/* Registers the training instance (one per context).  Builds the kernel sequence and the bubble sites, makes
+/* Sec. 3.1 (the training instance whose kernels the monitoring library counts) and Sec. 2.1 (where its idle phases
+ * come from).  Registers the training instance (one per context).  Builds the kernel sequence and the bubble sites, makes
  * the working copy of the parameters (one cast kernel per tensor group on the training stream) and returns. */
 sif_status sif_register_training_step(sif_ctx* ctx, const sif_train_desc* d, sif_handle* out);
 
@@ -423,7 +470,7 @@ typedef struct sif_infer_desc {
 
 uint64_t sif_infer_workspace_bytes(const sif_infer_desc* d);
 
-/* Registers an inference instance.  SIF_E_NOMEM if the declared peaks of all instances plus the training
+/* Sec. 3.2 (collocation policy).  Registers an inference instance.  SIF_E_NOMEM if the declared peaks of all instances plus the training
  * workspace exceed the device capacity (Principle-I). */
 sif_status sif_register_inference_model(sif_ctx* ctx, const sif_infer_desc* d, sif_handle* out);
 
@@ -434,7 +481,8 @@ sif_status sif_register_inference_model(sif_ctx* ctx, const sif_infer_desc* d, s
  * batch-1 time exceeds the longest bubble (Principle-II). */
 sif_status sif_calibrate(sif_ctx* ctx, uint32_t iters, const void* train_inputs_dev, const void* train_targets_dev);
 
-/* Queues one offline batch / one online request (non-blocking, any thread).  in_dev: int32 ids [batch,seq]
+/* Sec. 3.3 "Kernel Barrier": an offline batch is served by the token mechanism, an online request by
+ * pull-and-execute.  Queues one offline batch / one online request (non-blocking, any thread).  in_dev: int32 ids [batch,seq]
  * (ENCODER) or fp32 [batch,d_in] (MLP); out_dev: bf16 [batch,seq,d] or fp32 [batch,d_out]. */
 sif_status sif_submit_offline_batch(sif_ctx* ctx, sif_handle model, const void* in_dev, void* out_dev,
                                     uint32_t batch, uint32_t seq, sif_ticket* out);
@@ -445,6 +493,7 @@ sif_status sif_wait(sif_ctx* ctx, sif_ticket t, uint64_t timeout_ns);
 /* Host monotonic clock used for t_arrival_ns and the latency statistics. */
 uint64_t sif_now_ns(void);
 
+/* Sec. 5.1 "Metrics" (training and inference throughput, request latency percentiles) and Sec. 5.4 (overhead). */
 typedef struct sif_stats {
   uint32_t struct_size;
   uint32_t status_now, zc_now;
@@ -458,12 +507,19 @@ typedef struct sif_stats {
   uint64_t offline_samples, offline_batches;
   uint64_t online_done, online_p50_ns, online_p95_ns;
   uint64_t kernels_launched, kernels_skipped, kernels_run;
-  uint64_t gate_violations;       /* inference kernels that ran although the gate was closed (must be 0) */
+  uint64_t gate_violations;       /* inference kernels admitted into a bubble whose start stamp lies outside that
+                                     bubble's own begin / end stamps (must be 0; Sec. 2.2: training must not be
+                                     disturbed).  Checked by the barrier thread for every such kernel that ran.    */
   uint64_t train_kernels;
   uint64_t periods;               /* monitor periods evaluated                                           */
+  uint64_t gate_checked;          /* kernel starts that check has judged so far (violations included)    */
+  uint64_t gate_unchecked;        /* starts whose stamps did not reach the host within 200 ms            */
+  uint64_t gate_timeouts;         /* != 0: a block gave up waiting for its launch's gate decision (the launch was
+                                     run again; see sif_config.gate_spin_log2)                           */
 } sif_stats;
 
-/* Snapshot of the counters; never blocks, never touches a stream. */
+/* Snapshot of the counters; takes no lock and touches no stream (the counters are atomics, the latency percentiles
+ * come from a fixed-bucket histogram: nearest rank, reported as the middle of the bucket, within 1/32 of the value). */
 sif_status sif_poll_stats(sif_ctx* ctx, sif_stats* out);
 /* Zeroes the accumulating counters (between measurement phases); requires both streams idle. */
 sif_status sif_reset_stats(sif_ctx* ctx);
@@ -477,6 +533,22 @@ sif_status sif_reset_stats(sif_ctx* ctx);
  * event-to-event times in seconds.  Inference launches that the device gate skipped are left out. */
 sif_status sif_profile_gemm(sif_ctx* ctx, uint32_t on);
 sif_status sif_profile_read(sif_ctx* ctx, uint64_t launches[4], double flops[4], double seconds[4]);
+
+/* What the Kernel Barrier forwarded while a training instance was registered: one record per launch, in launch order.
+ * The newest 65536 are kept. */
+typedef struct sif_release_rec {
+  uint64_t period;      /* number of the monitor period whose grant was the balance at that moment         */
+  uint64_t grant;       /* that grant (tokens per instance)                                                */
+  uint32_t model;       /* inference instance                                                              */
+  uint32_t charge;      /* tokens taken (sif_kb_charge of the predicted time)                              */
+  uint32_t launch;      /* launch number on the inference stream (sif_trace_rec.reserved)                  */
+  uint32_t kind;        /* 0 offline, paid with tokens (Sec. 3.3 token mechanism); 1 kernel of a pulled online
+                           request (no tokens); 2 beside training, paid from the time account (feedback) */
+} sif_release_rec;
+/* Copies the newest records to out[0..max), oldest first; pauses the barrier thread meanwhile. */
+sif_status sif_read_release_log(sif_ctx* ctx, sif_release_rec* out, uint32_t max, uint32_t* n);
+/* Counts of the online latency histogram (buckets as sif_latency_bucket numbers them); takes no lock. */
+sif_status sif_read_latency_histogram(sif_ctx* ctx, uint64_t* counts, uint32_t max, uint32_t* n);
 
 /* One record of the device trace ring. */
 typedef struct sif_trace_rec {

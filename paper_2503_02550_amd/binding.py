@@ -82,7 +82,8 @@ class sif_config(C.Structure):
     _fields_ = [("struct_size", u32), ("period_us", u32), ("window", u32), ("count_running", u32),
                 ("alg1", sif_alg1_params), ("kernel_us_max", u32), ("collocate", u32), ("device_timed_bubbles", u32),
                 ("allow_serial_streams", u32), ("device_capacity_bytes", u64),
-                ("feedback", u32), ("feedback_eps_ppm", u32), ("feedback_add_ppm", u32), ("feedback_cap_ppm", u32)]
+                ("feedback", u32), ("feedback_eps_ppm", u32), ("feedback_add_ppm", u32), ("feedback_cap_ppm", u32),
+                ("gate_spin_log2", u32), ("gate_spin_every", u32)]
 
 
 class sif_model_shape(C.Structure):
@@ -110,7 +111,12 @@ class sif_stats(C.Structure):
                 ("offline_samples", u64), ("offline_batches", u64),
                 ("online_done", u64), ("online_p50_ns", u64), ("online_p95_ns", u64),
                 ("kernels_launched", u64), ("kernels_skipped", u64), ("kernels_run", u64),
-                ("gate_violations", u64), ("train_kernels", u64), ("periods", u64)]
+                ("gate_violations", u64), ("train_kernels", u64), ("periods", u64),
+                ("gate_checked", u64), ("gate_unchecked", u64), ("gate_timeouts", u64)]
+
+
+class sif_release_rec(C.Structure):
+    _fields_ = [("period", u64), ("grant", u64), ("model", u32), ("charge", u32), ("launch", u32), ("kind", u32)]
 
 
 class sif_trace_rec(C.Structure):
@@ -130,6 +136,13 @@ _sig("sif_zero_count", u32, P(u32), u32)
 _sig("sif_alg1_step", i32, P(sif_alg1_params), u32, P(u64), P(u64), P(i32))
 _sig("sif_kb_release", u32, P(u32), u32, u64, P(u64))
 _sig("sif_online_pull_ok", i32, i32, u32, u64, u64)
+_sig("sif_kb_charge", u32, u64, u64, u32)
+_sig("sif_sched_run_trace", i32, P(sif_alg1_params), u32, P(u32), u32, P(u32), u32, P(u32), P(u64), P(u64), P(i32), P(u32))
+_sig("sif_gate_violation", i32, u64, u64, u64)
+_sig("sif_latency_bucket", u32, u64)
+_sig("sif_latency_bucket_lower_ns", u64, u32)
+_sig("sif_latency_buckets", u32)
+_sig("sif_latency_percentile", u64, P(u64), u32, C.c_double)
 _sig("sif_principle_1", i32, P(u64), u32, u64)
 _sig("sif_principle_2", i32, u64, u64)
 _sig("sif_collective_ns", u64, u64, u64)
@@ -176,6 +189,41 @@ def sif_kb_release(costs, balance):
     left = u64(0)
     n = lib.sif_kb_release(arr, len(costs), balance, C.byref(left))
     return n, left.value
+
+
+def sif_kb_charge(predicted_us, ul, m):
+    return lib.sif_kb_charge(predicted_us, ul, m)
+
+
+def sif_sched_run_trace(params, window, counts, costs):
+    """Monitor -> Algorithm 1 -> offline barrier over a trace of per-period counts.  Returns one tuple per period:
+    (Z_c, pool, grant, status, kernels forwarded)."""
+    n, nc = len(counts), len(costs)
+    cnt, cst = (u32 * max(1, n))(*counts), (u32 * max(1, nc))(*costs)
+    zc, pool, grant, status, rel = (u32 * max(1, n))(), (u64 * max(1, n))(), (u64 * max(1, n))(), (i32 * max(1, n))(), (u32 * max(1, n))()
+    check(lib.sif_sched_run_trace(C.byref(params), window, cnt, n, cst, nc, zc, pool, grant, status, rel))
+    return [(zc[i], pool[i], grant[i], status[i], rel[i]) for i in range(n)]
+
+
+def sif_gate_violation(t0, bubble_begin, bubble_end):
+    return bool(lib.sif_gate_violation(t0, bubble_begin, bubble_end))
+
+
+def sif_latency_bucket(ns):
+    return lib.sif_latency_bucket(ns)
+
+
+def sif_latency_bucket_lower_ns(bucket):
+    return lib.sif_latency_bucket_lower_ns(bucket)
+
+
+def sif_latency_buckets():
+    return lib.sif_latency_buckets()
+
+
+def sif_latency_percentile(counts, p):
+    arr = (u64 * max(1, len(counts)))(*counts)
+    return lib.sif_latency_percentile(arr, len(counts), p)
 
 
 def sif_online_pull_ok(status, queue_len, remaining_ns, request_ns):
@@ -332,6 +380,8 @@ _sig("sif_wait", i32, vp, u64, u64)
 _sig("sif_poll_stats", i32, vp, P(sif_stats))
 _sig("sif_reset_stats", i32, vp)
 _sig("sif_read_trace", i32, vp, u32, P(sif_trace_rec), u32, P(u32))
+_sig("sif_read_release_log", i32, vp, P(sif_release_rec), u32, P(u32))
+_sig("sif_read_latency_histogram", i32, vp, P(u64), u32, P(u32))
 
 
 def sif_now_ns():
@@ -442,6 +492,23 @@ def sif_read_trace(ctx, which, cap=65535):
     n = u32(0)
     check(lib.sif_read_trace(ctx, which, arr, cap, C.byref(n)))
     return [(arr[i].kind, arr[i].id, arr[i].decision, arr[i].reserved, arr[i].t0_ns, arr[i].t1_ns) for i in range(n.value)]
+
+
+def sif_read_release_log(ctx, cap=65536):
+    """Returns a list of (period, grant, model, charge, launch number, kind), oldest first."""
+    arr = (sif_release_rec * cap)()
+    n = u32(0)
+    check(lib.sif_read_release_log(ctx, arr, cap, C.byref(n)))
+    return [(arr[i].period, arr[i].grant, arr[i].model, arr[i].charge, arr[i].launch, arr[i].kind) for i in range(n.value)]
+
+
+def sif_read_latency_histogram(ctx):
+    """Counts per bucket of the online latency histogram."""
+    cap = lib.sif_latency_buckets()
+    arr = (u64 * cap)()
+    n = u32(0)
+    check(lib.sif_read_latency_histogram(ctx, arr, cap, C.byref(n)))
+    return [arr[i] for i in range(n.value)]
 
 
 _sig("sif_profile_gemm", i32, vp, u32)

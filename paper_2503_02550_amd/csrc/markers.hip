@@ -20,6 +20,10 @@ __device__ __forceinline__ void bubble_wait(StreamRec* rec, Mirror* mir, Slot* s
   st_agent(&rec->t_idle_begin, t0);
   st_agent(&rec->t_expected_end, t0 + ticks);
   st_agent(&rec->state, kStateIdle);
+  // the bubble's own stamps for the host's check of inference kernel starts: entry cleared, then tagged
+  st_sys(&mir->bub_end[seq % kBubbleStamps], (uint64_t)0);
+  st_sys(&mir->bub_begin[seq % kBubbleStamps], t0);
+  st_sys(&mir->bub_tag[seq % kBubbleStamps], seq);
   st_sys(&mir->idle_site, site);
   st_sys(&mir->idle_len_ticks, ticks);
   st_sys(&mir->idle_seq, seq);
@@ -31,6 +35,7 @@ __device__ __forceinline__ void bubble_wait(StreamRec* rec, Mirror* mir, Slot* s
   st_agent(&rec->state, kStateBusy);
   const uint64_t t1 = now_ticks();
   st_agent(&rec->t_busy_begin, t1);
+  st_sys(&mir->bub_end[seq % kBubbleStamps], t1);
   rec->bubble_ticks += t1 - t0;
   st_sys(&mir->bubble_ticks, rec->bubble_ticks);
   st_sys(&mir->busy_seq, seq);
@@ -96,8 +101,13 @@ __global__ __launch_bounds__(64) void step_marker_kernel(StreamRec* rec, Mirror*
 }
 
 // Clears the poison of the inference stream after the host has taken note of the first skipped launch.
+// It runs alone on the stream, so it also re-arms the completion counters: a launch some of whose blocks gave up
+// waiting for the gate decision leaves them short of their full count.
 __global__ __launch_bounds__(64) void reset_skip_kernel(StreamRec* rec, Mirror* mir, uint32_t epoch) {
+  st_relaxed(&rec->done_sub[threadIdx.x * 32u], 0u);
+  __syncthreads();
   if (threadIdx.x != 0) return;
+  st_relaxed(&rec->done_top, 0u);
   st_agent(&rec->skip_from, kNone);
   st_sys(&mir->i_skip_from, kNone);
   st_sys(&mir->i_reset_ack, epoch);

@@ -58,7 +58,18 @@ struct Mirror {                     // pinned, coherent host memory
   uint32_t release_seq, pad2;
   // device -> host: length of the bubble announced by idle_seq, where the device decides it (written before idle_seq)
   uint64_t idle_len_ticks;
+  // device -> host, for the check of "an inference kernel starts only inside a detected bubble" (the barrier thread
+  // makes it when a kernel completes).  Bubble b (numbered from 1) stamps its begin and end, on the device clock, into
+  // entry b % kBubbleStamps; bub_tag says which bubble an entry belongs to and bub_end is 0 until that bubble is over.
+  // A gated inference kernel that runs leaves one word in i_gate[launch number % kGateStamps]:
+  //   bits 63..24 its start time (low 40 bits), 23..8 its launch number (low 16 bits), 7..0 the number of the bubble
+  //   the gate saw (low 8 bits)
+  // - one store, so the host never sees half of it.
+  uint64_t bub_begin[64], bub_end[64];
+  uint32_t bub_tag[64];
+  uint64_t i_gate[1024];
 };
+constexpr uint32_t kBubbleStamps = 64, kGateStamps = 1024;
 
 struct KCtl {                       // by-value kernel argument
   StreamRec* rec;                   // this stream's record; nullptr = unmonitored launch
@@ -68,8 +79,10 @@ struct KCtl {                       // by-value kernel argument
   uint32_t kseq;                    // launch number on this stream (>= 1)
   uint32_t cost_ticks;              // predicted duration
   uint32_t kind_id;
-  uint32_t flags;                   // bit 0: last kernel of its job; bit 1: gated on the poison only (runs beside training)
+  uint32_t flags;                   // bit 0: last kernel of its job; bit 1: gated on the poison only (runs beside training);
+                                    // bits 8..15: 0, or 1 + log2 of the bound on the spins a block waits for block 0's decision
 };
+constexpr uint32_t kDefaultSpinLog2 = 18;
 
 __device__ __forceinline__ uint64_t now_ticks() { return wall_clock64(); }
 
@@ -110,7 +123,7 @@ __device__ __forceinline__ bool first_thread() { return threadIdx.x == 0 && thre
 // Decision of the first block of a gated launch: run only if no earlier launch of this speculation window was
 // skipped, the training stream is inside a bubble, the predicted rest of the bubble holds this kernel, and
 // the bubble is still the same one after the start time was stamped.
-__device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
+__device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0, uint32_t* bubble) {
   // Relaxed device-scope loads (an acquire would sweep the L2 on every inference kernel start).  state and seq are
   // read as one 64-bit word; the three loads of the first round are independent and travel together, so the
   // decision costs two memory round trips: {state|seq, predicted end, poison} -> clock -> {state|seq} again.  A
@@ -130,6 +143,7 @@ __device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
   if (t + c.cost_ticks > t_end) return false;
   if (ld_relaxed(ss) != s0) return false;
   *t0 = t;
+  *bubble = (uint32_t)(s0 >> 32);
   return true;
 }
 
@@ -140,7 +154,10 @@ __device__ __forceinline__ bool gate_decide(const KCtl& c, uint64_t* t0) {
 //     atomics from thousands of blocks serialise at ~50 ns each).  Workgroups are dispatched in grid order, so
 //     block 0 is resident whenever any block is and waits for nothing; should the decision still not appear
 //     within the spin bound, the block poisons the window and skips, and the host re-runs the launch (every
-//     inference kernel writes only buffers it does not read, so a partial run can be repeated).
+//     inference kernel writes only buffers it does not read, so a partial run can be repeated).  A block that gave
+//     up does not count itself in kernel_end, so a launch that block 0 then lets run never reaches its full count:
+//     it is never reported done, and the kernel that clears the poison (it runs alone on the stream) re-arms the
+//     completion counters it left behind.
 //   * Blocks of an ungated launch never wait.
 __device__ __forceinline__ uint32_t linear_block() { return blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z); }
 
@@ -151,10 +168,14 @@ __device__ __forceinline__ bool kernel_begin(const KCtl& c) {
     int run = 1;
     if (linear_block() == 0) {
       uint64_t t0 = now_ticks();
-      if (c.gate != nullptr) run = gate_decide(c, &t0) ? 1 : 0;
+      uint32_t bubble = 0;
+      if (c.gate != nullptr) run = gate_decide(c, &t0, &bubble) ? 1 : 0;
       c.slot->kind_id = c.kind_id;
       st_relaxed(&c.slot->t0, t0);
       if (run) {
+        // what the host needs to check this start against the bubble's own stamps (not for launches beside training)
+        if (c.gate != nullptr && !(c.flags & 2u))
+          st_sys_relaxed(&c.mir->i_gate[c.kseq % kGateStamps], (t0 << 24) | ((uint64_t)(c.kseq & 0xFFFFu) << 8) | (bubble & 0xFFu));
         st_relaxed(&c.rec->t_start, t0);
         const uint32_t l = c.rec->launched + 1;
         st_relaxed(&c.rec->launched, l);
@@ -169,8 +190,9 @@ __device__ __forceinline__ bool kernel_begin(const KCtl& c) {
       }
       st_relaxed(&c.slot->decision, (c.kseq << 2) | (run ? 1u : 2u));
     } else if (c.gate != nullptr) {
+      const uint32_t lg = (c.flags >> 8) & 0xFFu, bound = 1u << (lg ? (lg - 1u > 30u ? 30u : lg - 1u) : kDefaultSpinLog2);
       uint32_t d = 0, spins = 0;
-      while (((d = ld_relaxed(&c.slot->decision)) >> 2) != c.kseq && ++spins < (1u << 18)) __builtin_amdgcn_s_sleep(4);
+      while (((d = ld_relaxed(&c.slot->decision)) >> 2) != c.kseq && ++spins < bound) __builtin_amdgcn_s_sleep(4);
       if ((d >> 2) == c.kseq) {
         run = (d & 3u) == 1u;
       } else {                           // block 0 never showed up: give the launch back to the host
@@ -226,14 +248,15 @@ __device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
     r->filled_ticks += fill;
     ++r->kernels_run;
     // The statistics travel to the host mailbox with the last kernel of a job and with every eighth launch (each
-    // store to host memory lengthens the end of the kernel); the progress word travels every time.  The last kernel
-    // of a job publishes it with release order (its results must be visible before the host reports the job done).
+    // store to host memory lengthens the end of the kernel); the progress word travels every time.  It says that the
+    // last block is about to leave, not that the kernel's results are visible: the host reports a job done only after
+    // an event recorded behind its last kernel has completed.
     if ((c.flags & 1u) || (c.kseq & 7u) == 0u) {
       st_sys_relaxed(&m->infer_ticks, r->infer_ticks);
       st_sys_relaxed(&m->filled_ticks, r->filled_ticks);
       st_sys_relaxed(&m->kernels_run, r->kernels_run);
     }
-    if (c.flags & 1u) st_sys(&m->i_done, c.kseq); else st_sys_relaxed(&m->i_done, c.kseq);
+    st_sys_relaxed(&m->i_done, c.kseq);
   }
 }
 

@@ -108,7 +108,9 @@ struct Job {
   int32_t result = 1;            // 1 pending, 0 done, < 0 error
 };
 
-struct InFlight { uint32_t kseq; Job* job; uint32_t op; uint32_t idle_seq; uint64_t cost_us; };      // cost_us: what the launch added to outstanding_us
+// cost_us: what the launch added to outstanding_us; ev: index of the completion event recorded behind it (the last
+// kernel of a job) or -1; check_gate: admitted into a bubble, so its start is checked against that bubble's stamps
+struct InFlight { uint32_t kseq; Job* job; uint32_t op; uint32_t idle_seq; uint64_t cost_us; int32_t ev; bool check_gate; };
 
 // Layout / plan builders (models.hip)
 uint64_t model_n_params(const sif_model_shape& s);

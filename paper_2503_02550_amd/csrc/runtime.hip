@@ -16,6 +16,7 @@
 #include <string.h>
 
 #include "runtime.h"
+#include "kb_rules.h"
 
 using namespace sif;
 
@@ -61,14 +62,25 @@ struct sif_ctx {
   size_t offline_queued = 0;
   std::unordered_map<sif_ticket, std::unique_ptr<Job>> jobs;
   sif_ticket next_ticket = 1;
-  std::vector<uint64_t> latencies;
+  LatencyHist latency;                 // online request latencies (lock-free: the statistics call never waits)
   std::mutex infer_mu;                 // serialises launches on the inference stream
 
   // barrier thread state
   std::deque<InFlight> inflight;
   std::deque<Job*> run_online, run_offline;
   std::vector<std::unique_ptr<Job>> groups;      // coalesced jobs in flight (guarded by mu)
-  std::vector<uint64_t> balance;                 // per offline instance: what is left of the period's grant
+  std::vector<KbTokens> tokens;                  // per offline instance: what is left of the period's grant
+  // events recorded behind the last kernel of each job: a job is reported done once its event has completed, i.e.
+  // once the stream has passed that kernel and its results are visible to every later reader
+  std::vector<hipEvent_t> done_ev;
+  std::vector<int32_t> done_ev_free;
+  // starts of gated kernels that have completed, waiting to be checked against their bubble's own stamps
+  struct GateCheck { uint32_t kseq, b8; uint64_t give_up_ns, t0, begin; bool have; };
+  std::deque<GateCheck> gate_pending;
+  // what the barrier forwarded, newest kReleaseLog entries (written by the barrier thread only)
+  std::vector<sif_release_rec> release_log;
+  uint64_t release_n = 0;
+  uint64_t period_grant = 0;                     // the grant that the balances were last set to
   size_t rr_next = 0;                            // instance the next offline kernel is looked for first
   uint64_t outstanding_us = 0, last_period = 0;
   bool awaiting_reset = false;
@@ -77,7 +89,7 @@ struct sif_ctx {
   uint32_t reset_epoch = 0;
 
   std::atomic<uint64_t> offline_samples{0}, offline_batches{0}, online_done{0}, kernels_launched{0}, periods{0};
-  std::atomic<uint64_t> gate_violations{0};
+  std::atomic<uint64_t> gate_violations{0}, gate_checked{0}, gate_unchecked{0};
   uint64_t step_solo_ns = 0;
   uint32_t train_kernels_base = 0;          // completed training kernels at the last sif_reset_stats
   // concurrent filling with feedback: the share is set by the monitor thread after every training iteration, the
@@ -107,6 +119,7 @@ static KCtl make_ctl(sif_ctx* c, StreamState& st, uint32_t kind, uint32_t id, co
 }
 
 constexpr uint32_t kProfMax = 16384;
+constexpr uint32_t kReleaseLog = 1u << 16;
 
 // Launches one op; when GEMM profiling is on, brackets it with two events on its own stream.
 static sif_status launch_op(sif_ctx* c, Op& op, hipStream_t s, const KCtl& k) {
@@ -135,8 +148,7 @@ static inline uint64_t mload(const uint64_t* p) { return __atomic_load_n(p, __AT
 static void monitor_main(sif_ctx* c) {
   (void)hipSetDevice(c->device);
   const uint64_t period_ns = (uint64_t)c->cfg.period_us * 1000ull;
-  std::vector<uint32_t> window;
-  window.reserve(c->cfg.window);
+  BmWindow window(c->cfg.window);
   // The mailbox starts zeroed and bubble numbers start at 1.  These must not be read from the mailbox here: the
   // thread may first run after the first bubble has begun, and would then never release it.
   uint32_t prev_launched = 0;
@@ -189,9 +201,7 @@ static void monitor_main(sif_ctx* c) {
       uint32_t count = launched - prev_launched;
       prev_launched = launched;
       if (c->cfg.count_running && count == 0 && launched != completed) count = 1;
-      if (window.size() == c->cfg.window) window.erase(window.begin());
-      window.push_back(count);
-      const uint32_t zc = sif_zero_count(window.data(), (uint32_t)window.size());
+      const uint32_t zc = window.push(count);
       uint64_t grant = 0;
       int32_t status = SIF_STATUS_BUSY;
       sif_alg1_step(&c->cfg.alg1, zc, &pool, &grant, &status);
@@ -227,7 +237,7 @@ static void finish_job(sif_ctx* c, Job* j, int32_t result) {
   if (result == 0) {
     if (j->online) {
       c->online_done.fetch_add(1);
-      c->latencies.push_back(j->t_done_ns > j->t_arrival_ns ? j->t_done_ns - j->t_arrival_ns : 0);
+      c->latency.add(j->t_done_ns > j->t_arrival_ns ? j->t_done_ns - j->t_arrival_ns : 0);
     } else {
       c->offline_batches.fetch_add(1);
       c->offline_samples.fetch_add(j->batch);
@@ -243,6 +253,50 @@ static uint64_t predicted_remaining_ns(sif_ctx* c) {
   const uint64_t end = c->edge_host_ns.load(std::memory_order_relaxed) + c->edge_len_ns.load(std::memory_order_relaxed);
   const uint64_t now = host_now_ns();
   return end > now ? end - now : 0;
+}
+
+// ---- the invariant "an inference kernel starts only inside a detected bubble", checked from the stamps -------------
+// A gated kernel that ran left its start time and the number of the bubble its gate saw in the mailbox; the bubble
+// kernel left its own begin and end stamps there.  Stage one (as soon as the kernel is known to have completed) reads
+// the kernel's word and the bubble's begin; stage two waits for the bubble's end.
+static void gate_check_stage_one(const Mirror* m, sif_ctx::GateCheck& g) {
+  const uint64_t w = mload(&m->i_gate[g.kseq % kGateStamps]);
+  if (((w >> 8) & 0xFFFFu) != (g.kseq & 0xFFFFu)) return;            // the word has not arrived yet
+  const uint32_t b8 = (uint32_t)(w & 0xFFu), e = b8 % kBubbleStamps;
+  if ((mload(&m->bub_tag[e]) & 0xFFu) != b8) return;
+  const uint64_t begin = mload(&m->bub_begin[e]);
+  if ((mload(&m->bub_tag[e]) & 0xFFu) != b8) return;                  // the entry was not recycled meanwhile
+  // the start time travels as its low 40 bits: rebuild it next to the bubble's begin
+  const int64_t rel = (int64_t)(((w >> 24) - (begin & 0xFFFFFFFFFFull)) << 24) >> 24;
+  g.t0 = begin + (uint64_t)rel; g.begin = begin; g.b8 = b8; g.have = true;
+}
+
+static void process_gate_checks(sif_ctx* c, bool last_pass) {
+  const uint64_t now = host_now_ns();
+  const Mirror* m = c->mir;
+  while (!c->gate_pending.empty()) {
+    sif_ctx::GateCheck& g = c->gate_pending.front();
+    if (!g.have) gate_check_stage_one(m, g);
+    int verdict = -1;                                                   // -1 undecided, 0 inside, 1 violation
+    if (g.have) {
+      if (sif_gate_violation(g.t0, g.begin, 0)) verdict = 1;
+      else {
+        const uint32_t e = g.b8 % kBubbleStamps;
+        const uint64_t end = mload(&m->bub_end[e]);
+        if (end != 0 && (mload(&m->bub_tag[e]) & 0xFFu) == g.b8 && mload(&m->bub_begin[e]) == g.begin) verdict = sif_gate_violation(g.t0, g.begin, end);
+        // a kernel that is known to have completed while its bubble is still not over began before that end
+        else if (last_pass || now >= g.give_up_ns) verdict = 0;
+      }
+    } else if (last_pass || now >= g.give_up_ns) {
+      c->gate_unchecked.fetch_add(1, std::memory_order_relaxed);        // its stamps never arrived
+      c->gate_pending.pop_front();
+      continue;
+    }
+    if (verdict < 0) break;
+    if (verdict == 1) c->gate_violations.fetch_add(1, std::memory_order_relaxed);
+    c->gate_checked.fetch_add(1, std::memory_order_relaxed);
+    c->gate_pending.pop_front();
+  }
 }
 
 static double job_cost_us(const Job* j) {
@@ -262,8 +316,25 @@ static void barrier_main(sif_ctx* c) {
     const uint32_t done = mload(&c->mir->i_done), skip = mload(&c->mir->i_skip_from);
     while (!c->inflight.empty() && c->inflight.front().kseq <= done && (skip == kNone || c->inflight.front().kseq < skip)) {
       InFlight f = c->inflight.front();
+      if (f.ev >= 0) {
+        // the last kernel of a job: the job is done when the stream has passed it (its results are then visible to
+        // whoever reads them next), not when its last block says it is about to leave
+        const hipError_t q = hipEventQuery(c->done_ev[f.ev]);
+        if (q == hipErrorNotReady) { (void)hipGetLastError(); break; }      // "not ready" must not show up as the next launch's error
+        c->done_ev_free.push_back(f.ev);
+        if (q != hipSuccess) {
+          c->inflight.pop_front();
+          auto drop = [&](std::deque<Job*>& qq) { qq.erase(std::remove(qq.begin(), qq.end(), f.job), qq.end()); };
+          drop(c->run_online); drop(c->run_offline);
+          c->inflight.erase(std::remove_if(c->inflight.begin(), c->inflight.end(), [&](const InFlight& g) { return g.job == f.job; }), c->inflight.end());
+          finish_job(c, f.job, fail_hip(q, "barrier: completion event"));
+          progressed = true;
+          continue;
+        }
+      }
       c->inflight.pop_front();
       c->outstanding_us = c->outstanding_us > f.cost_us ? c->outstanding_us - f.cost_us : 0;      // exactly what its launch added
+      if (f.check_gate) c->gate_pending.push_back(sif_ctx::GateCheck{f.kseq, 0, host_now_ns() + 200000000ull, 0, 0, false});
       if (++f.job->done_ops == f.job->plan.size()) {
         auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), f.job), q.end()); };
         drop(c->run_online); drop(c->run_offline);
@@ -271,18 +342,20 @@ static void barrier_main(sif_ctx* c) {
       }
       progressed = true;
     }
+    if (!c->gate_pending.empty()) process_gate_checks(c, false);
     // 2. a kernel found the gate closed: everything from it on was (or will be) skipped; rewind and clear the poison
     if (!c->awaiting_reset && skip != kNone) {
       while (!c->inflight.empty() && c->inflight.back().kseq >= skip) {
         InFlight f = c->inflight.back();
         c->inflight.pop_back();
+        if (f.ev >= 0) c->done_ev_free.push_back(f.ev);
         if (f.op < f.job->next_op) f.job->next_op = f.op;
         c->hold = true;                   // the bubble this launch was aimed at has no room left
         c->hold_seq = f.idle_seq;
       }
       c->outstanding_us = 0;
       for (const InFlight& f : c->inflight) c->outstanding_us += f.cost_us;
-      std::fill(c->balance.begin(), c->balance.end(), 0);
+      for (KbTokens& t : c->tokens) t.clear();
       launch_reset_skip(c->I.stream, c->I.rec, c->mir, ++c->reset_epoch);
       c->awaiting_reset = true;
       progressed = true;
@@ -302,7 +375,8 @@ static void barrier_main(sif_ctx* c) {
           c->conc_account_ns = sif_concurrent_account(c->conc_account_ns, share, (uint64_t)c->cfg.period_us * 1000ull, burst);
       }
       c->last_period = pn;
-      std::fill(c->balance.begin(), c->balance.end(), c->grant.load(std::memory_order_relaxed));
+      c->period_grant = c->grant.load(std::memory_order_relaxed);
+      for (KbTokens& t : c->tokens) t.new_period(c->period_grant);
     }
     if (c->hold && (!gated || mload(&c->mir->idle_seq) != c->hold_seq)) c->hold = false;
     // 4. admit jobs.  Two ways lead to the inference stream: into a bubble (Algorithm 1's tokens, the device gate
@@ -404,10 +478,8 @@ static void barrier_main(sif_ctx* c) {
       while (budget-- > 0) {
         Job* j = nullptr;
         bool online = false, beside = false;
-        // a kernel predicted longer than the largest possible grant is charged the whole grant, so that the head of
-        // the queue can always be forwarded in the stable phase
-        const uint64_t cap = std::max<uint64_t>(1, c->cfg.alg1.ul / c->cfg.alg1.m);
-        auto cost_of = [&](const Job* q) { return std::min<uint64_t>((uint64_t)(q->plan[q->next_op].cost_us + 0.999), cap); };
+        // what the next kernel of a job is charged: its predicted microseconds, at most the largest possible grant
+        auto cost_of = [&](const Job* q) { return (uint64_t)sif_kb_charge((uint64_t)(q->plan[q->next_op].cost_us + 0.999), c->cfg.alg1.ul, c->cfg.alg1.m); };
         if (into_bubbles || feedback)
           for (Job* q : c->run_online) if (q->next_op < q->plan.size()) { j = q; online = true; break; }
         // online kernels without tokens only while idle (and not after a skipped launch, until the next bubble begins);
@@ -420,12 +492,12 @@ static void barrier_main(sif_ctx* c) {
           // Offline: every instance spends its own balance, FIFO within the instance (its head kernel blocks the
           // rest of its queue); the instances take turns, and one that is out of tokens does not hold up the others.
           online = false;
-          const size_t nm = c->balance.size();
+          const size_t nm = c->tokens.size();
           for (size_t r = 0; r < nm && !j; ++r) {
             const size_t mdl = (c->rr_next + r) % nm;
             for (Job* q : c->run_offline) {
               if ((size_t)q->model != mdl || q->next_op >= q->plan.size()) continue;
-              if (!gated || (into_bubbles && c->balance[mdl] >= cost_of(q))) { j = q; c->rr_next = (mdl + 1) % nm; }   // token rule
+              if (!gated || (into_bubbles && c->tokens[mdl].covers((uint32_t)cost_of(q)))) { j = q; c->rr_next = (mdl + 1) % nm; }   // token rule
               else if (feedback && c->conc_account_ns >= 1000ull * cost_of(q)) { j = q; beside = true; c->rr_next = (mdl + 1) % nm; }
               break;
             }
@@ -455,19 +527,33 @@ static void barrier_main(sif_ctx* c) {
         }
         Op& op = j->plan[j->next_op];
         const uint64_t cost = cost_of(j);
-        if (gated && c->outstanding_us + cost > max_ahead && !c->inflight.empty()) break;   // bounded speculation depth
+        if (gated && !kb_depth_ok(c->outstanding_us, cost, max_ahead, c->inflight.size())) break;   // bounded speculation depth
         // What the device gate is bound to refuse is not launched: behind what is in flight (its predicted time and the
         // gap after each kernel), this kernel would end after the predicted end of the bubble.  The gate still decides;
         // this spares launches whose empty blocks would pass through the CUs beside the training kernels that follow.
-        if (gated && !beside) {
-          const uint64_t rest_ns = predicted_remaining_ns(c);
-          if (rest_ns < 1000ull * c->outstanding_us + 5000ull * c->inflight.size() + (uint64_t)(op.cost_us * 1000.0)) break;
-        }
+        if (gated && !beside && !kb_fits_bubble(predicted_remaining_ns(c), c->outstanding_us, c->inflight.size(), op.cost_us)) break;
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
-        if (j->next_op + 1 == j->plan.size()) k.flags |= 1u;
+        const bool last_of_job = j->next_op + 1 == j->plan.size();
+        if (last_of_job) k.flags |= 1u;
         if (beside) k.flags |= 2u;        // paid from the time account: starts whatever the training stream does
+        if (c->cfg.gate_spin_log2 && (c->cfg.gate_spin_every < 2 || k.kseq % c->cfg.gate_spin_every == 0))
+          k.flags |= (std::min<uint32_t>(c->cfg.gate_spin_log2, 30u) + 1u) << 8;
         sif_status st = launch_op(c, op, c->I.stream, k);
+        int32_t ev = -1;
+        if (st == SIF_OK && last_of_job) {
+          if (c->done_ev_free.empty()) {
+            hipEvent_t e = nullptr;
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess) { c->done_ev.push_back(e); c->done_ev_free.push_back((int32_t)c->done_ev.size() - 1); }
+          }
+          if (c->done_ev_free.empty()) st = fail(SIF_E_DEVICE, "barrier: no completion event");
+          else {
+            ev = c->done_ev_free.back();
+            c->done_ev_free.pop_back();
+            const hipError_t e = hipEventRecord(c->done_ev[ev], c->I.stream);
+            if (e != hipSuccess) { c->done_ev_free.push_back(ev); ev = -1; st = fail_hip(e, "barrier: hipEventRecord"); }
+          }
+        }
         if (st != SIF_OK) {
           auto drop = [&](std::deque<Job*>& q) { q.erase(std::remove(q.begin(), q.end(), j), q.end()); };
           drop(c->run_online); drop(c->run_offline);
@@ -477,11 +563,17 @@ static void barrier_main(sif_ctx* c) {
           break;
         }
         c->kernels_launched.fetch_add(1, std::memory_order_relaxed);
-        c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq), cost});
+        c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq), cost, ev, gated && !beside});
         j->next_op++;
         c->outstanding_us += cost;
+        const bool by_tokens = !beside && gated && !online;
         if (beside) c->conc_account_ns -= std::min<uint64_t>(c->conc_account_ns, 1000ull * cost);
-        else if (gated && !online) c->balance[j->model] -= cost;
+        else if (by_tokens) c->tokens[j->model].spend((uint32_t)cost);
+        if (gated) {
+          sif_release_rec& r = c->release_log[c->release_n++ % kReleaseLog];
+          r.period = c->last_period; r.grant = c->period_grant;
+          r.model = (uint32_t)j->model; r.charge = (uint32_t)cost; r.launch = k.kseq; r.kind = beside ? 2u : (online ? 1u : 0u);
+        }
         progressed = true;
       }
     }
@@ -560,6 +652,7 @@ sif_status sif_default_config(sif_config* cfg) {
   cfg->alg1.alpha = 1; cfg->alg1.beta = 3; cfg->alg1.gamma_num = 2; cfg->alg1.gamma_den = 1; cfg->alg1.m = 1;
   cfg->alg1.t0 = 200; cfg->alg1.ll = 400; cfg->alg1.ul = 800;
   cfg->kernel_us_max = 300; cfg->collocate = 1; cfg->device_timed_bubbles = 0; cfg->device_capacity_bytes = 0;
+  cfg->gate_spin_log2 = 0; cfg->gate_spin_every = 0;
   cfg->feedback = 0; cfg->feedback_eps_ppm = 20000; cfg->feedback_add_ppm = 20000; cfg->feedback_cap_ppm = 1000000;
   return SIF_OK;
 }
@@ -601,26 +694,38 @@ sif_status sif_create(const sif_config* cfg, void* train_stream, void* infer_str
   HIPCHK(hipMemcpy(c->I.rec, &init, sizeof(init), hipMemcpyHostToDevice), "init record");
   void* mp = nullptr;
   HIPCHK(hipHostMalloc(&mp, sizeof(Mirror), hipHostMallocCoherent), "hipHostMalloc mailbox");
+  // whatever fails from here on gives the mailbox and the events back
+  struct Undo {
+    void* mp; sif_ctx* c; bool armed;
+    ~Undo() { if (!armed) return; for (hipEvent_t e : c->done_ev) (void)hipEventDestroy(e); c->done_ev.clear(); (void)hipHostFree(mp); c->mir = nullptr; }
+  } undo{mp, c.get(), true};
   memset(mp, 0, sizeof(Mirror));
   c->mir = (Mirror*)mp;
   c->mir->i_skip_from = kNone;
+  for (int i = 0; i < 64; ++i) {
+    hipEvent_t e = nullptr;
+    HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming), "create: hipEventCreate");
+    c->done_ev.push_back(e);
+    c->done_ev_free.push_back(i);
+  }
+  c->release_log.assign(kReleaseLog, sif_release_rec{});
   HIPCHK(hipDeviceSynchronize(), "create: synchronize");
   // The two streams must be able to run concurrently: spin 300 us on the training stream and stamp the time on
   // the inference stream; the stamp has to fall inside the spin.
   {
     uint64_t* probe = (uint64_t*)c->I.ring;
     sif_status st = launch_probe(c->T.stream, c->I.stream, c->ns_to_ticks(300000), probe);
-    if (st != SIF_OK) { (void)hipHostFree(mp); return st; }
+    if (st != SIF_OK) return st;
     uint64_t h[3] = {0, 0, 0};
     hipError_t e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipMemcpy(h, probe, sizeof(h), hipMemcpyDeviceToHost);
     if (e == hipSuccess) e = hipMemset(probe, 0, sizeof(h));
-    if (e != hipSuccess) { (void)hipHostFree(mp); return fail_hip(e, "create: stream probe"); }
+    if (e != hipSuccess) return fail_hip(e, "create: stream probe");
     if (!(h[2] > h[0] && h[2] < h[1]) && !cfg->allow_serial_streams) {
-      (void)hipHostFree(mp);
       return fail(SIF_E_AGAIN, "create: the two streams do not run concurrently (they share a hardware queue); pass another pair");
     }
   }
+  undo.armed = false;
   sif_ctx* raw = c.release();
   raw->mon = std::thread(monitor_main, raw);
   raw->bar = std::thread(barrier_main, raw);
@@ -641,8 +746,10 @@ sif_status sif_destroy(sif_ctx* c) {
     for (auto& kv : c->jobs) if (kv.second->result == 1) kv.second->result = SIF_E_CANCELLED;
     c->cv.notify_all();
   }
+  process_gate_checks(c, true);
   if (c->mir) (void)hipHostFree(c->mir);
   for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->done_ev) (void)hipEventDestroy(e);
   delete c;
   if (e1 != hipSuccess) return fail_hip(e1, "destroy: training stream");
   if (e2 != hipSuccess) return fail_hip(e2, "destroy: inference stream");
@@ -746,7 +853,7 @@ sif_status sif_register_inference_model(sif_ctx* c, const sif_infer_desc* d, sif
   {
     std::lock_guard<std::mutex> lk(c->mu);
     c->offline_q.emplace_back();
-    c->balance.push_back(0);
+    c->tokens.emplace_back();
   }
   *out = (sif_handle)(c->models.size() - 1);
   return SIF_OK;
@@ -945,16 +1052,14 @@ sif_status sif_poll_stats(sif_ctx* c, sif_stats* out) {
   out->kernels_skipped = mload(&m->kernels_skipped);
   out->kernels_run = mload(&m->kernels_run);
   out->train_kernels = (uint32_t)(mload(&m->t_completed) - c->train_kernels_base);
-  out->gate_violations = c->gate_violations.load() + mload(&m->gate_timeouts);
+  out->gate_violations = c->gate_violations.load();
+  out->gate_checked = c->gate_checked.load();
+  out->gate_unchecked = c->gate_unchecked.load();
+  out->gate_timeouts = mload(&m->gate_timeouts);
   out->periods = c->periods.load();
-  out->online_p50_ns = out->online_p95_ns = 0;
-  std::vector<uint64_t> lat;
-  { std::lock_guard<std::mutex> lk(c->mu); lat = c->latencies; }
-  if (!lat.empty()) {
-    std::sort(lat.begin(), lat.end());
-    auto rank = [&](double p) { size_t r = (size_t)ceil(p * lat.size()); return lat[r == 0 ? 0 : r - 1]; };   // nearest rank
-    out->online_p50_ns = rank(0.50); out->online_p95_ns = rank(0.95);
-  }
+  // nearest-rank percentiles from the histogram (bucket middles: within 1/32 of the exact value); no lock is taken
+  out->online_p50_ns = c->latency.percentile(0.50);
+  out->online_p95_ns = c->latency.percentile(0.95);
   return SIF_OK;
 }
 
@@ -973,8 +1078,12 @@ sif_status sif_reset_stats(sif_ctx* c) {
   m->steps = m->step_ticks_sum = m->step_ticks_last = m->bubble_ticks = m->filled_ticks = m->infer_ticks = 0;
   m->kernels_run = m->kernels_skipped = 0;
   c->train_kernels_base = mload(&m->t_completed);
-  c->offline_samples = 0; c->offline_batches = 0; c->online_done = 0; c->kernels_launched = 0; c->periods = 0; c->gate_violations = 0;
-  { std::lock_guard<std::mutex> lk(c->mu); c->latencies.clear(); }
+  process_gate_checks(c, true);               // both streams are idle: every pending start can be judged now
+  c->offline_samples = 0; c->offline_batches = 0; c->online_done = 0; c->kernels_launched = 0; c->periods = 0;
+  c->gate_violations = 0; c->gate_checked = 0; c->gate_unchecked = 0;
+  m->gate_timeouts = 0;
+  c->latency.clear();
+  c->release_n = 0;
   return SIF_OK;
 }
 
@@ -1037,6 +1146,26 @@ sif_status sif_read_trace(sif_ctx* c, uint32_t which, sif_trace_rec* out, uint32
     out[i].reserved = kseq;
     out[i].t0_ns = c->ticks_to_ns(s.t0); out[i].t1_ns = c->ticks_to_ns(s.t1);
   }
+  *n = cnt;
+  return SIF_OK;
+}
+
+sif_status sif_read_release_log(sif_ctx* c, sif_release_rec* out, uint32_t max, uint32_t* n) {
+  if (!c || !n || (max && !out)) return fail(SIF_E_INVAL, "read_release_log: bad argument");
+  c->paused.store(true, std::memory_order_release);
+  std::unique_lock<std::mutex> il(c->infer_mu);
+  struct Unpause { sif_ctx* c; ~Unpause() { c->paused.store(false, std::memory_order_release); } } unpause{c};
+  const uint64_t have = std::min<uint64_t>(c->release_n, kReleaseLog);
+  const uint32_t cnt = (uint32_t)std::min<uint64_t>(have, max);
+  for (uint32_t i = 0; i < cnt; ++i) out[i] = c->release_log[(c->release_n - cnt + i) % kReleaseLog];
+  *n = cnt;
+  return SIF_OK;
+}
+
+sif_status sif_read_latency_histogram(sif_ctx* c, uint64_t* counts, uint32_t max, uint32_t* n) {
+  if (!c || !n || (max && !counts)) return fail(SIF_E_INVAL, "read_latency_histogram: bad argument");
+  const uint32_t cnt = std::min<uint32_t>(max, LatencyHist::kBuckets);
+  for (uint32_t b = 0; b < cnt; ++b) counts[b] = c->latency.n[b].load(std::memory_order_relaxed);
   *n = cnt;
   return SIF_OK;
 }

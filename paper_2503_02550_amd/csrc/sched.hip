@@ -2,6 +2,7 @@
 // the Kernel Barrier's offline token rule and online pull rule (Sec. 3.3), the collocation principles
 // (Sec. 3.2) and the bubble model.  The runtime threads call these; they touch no GPU state.
 #include "launch.h"
+#include "kb_rules.h"
 
 extern "C" {
 
@@ -37,6 +38,80 @@ uint32_t sif_kb_release(const uint32_t* costs, uint32_t n, uint64_t balance, uin
   while (costs != nullptr && i < n && balance >= costs[i]) balance -= costs[i++];
   if (balance_left) *balance_left = balance;
   return i;
+}
+
+uint32_t sif_kb_charge(uint64_t predicted_us, uint64_t ul, uint32_t m) {
+  const uint64_t cap = (m != 0 && ul / m > 0) ? ul / m : 1;
+  const uint64_t c = predicted_us < cap ? predicted_us : cap;
+  return (uint32_t)(c > 0xFFFFFFFFull ? 0xFFFFFFFFull : c);
+}
+
+sif_status sif_sched_run_trace(const sif_alg1_params* p, uint32_t window, const uint32_t* counts, uint32_t n_periods,
+                               const uint32_t* costs, uint32_t n_costs, uint32_t* zc_out, uint64_t* pool_out,
+                               uint64_t* grant_out, int32_t* status_out, uint32_t* released_out) {
+  if (!p || window == 0 || (n_periods > 0 && !counts) || (n_costs > 0 && !costs)) return sif::fail(SIF_E_INVAL, "run_trace: null or empty argument");
+  // the objects the monitor thread and the barrier thread keep, driven by the trace instead of by a device
+  sif::BmWindow bm(window);
+  sif::KbTokens tok;
+  uint64_t pool = 0;
+  uint32_t head = 0;
+  for (uint32_t t = 0; t < n_periods; ++t) {
+    const uint32_t zc = bm.push(counts[t]);
+    uint64_t grant = 0;
+    int32_t status = SIF_STATUS_BUSY;
+    const sif_status st = sif_alg1_step(p, zc, &pool, &grant, &status);
+    if (st != SIF_OK) return st;
+    tok.new_period(grant);
+    uint32_t n = 0;
+    while (head < n_costs && tok.covers(costs[head])) { tok.spend(costs[head]); ++head; ++n; }
+    if (zc_out) zc_out[t] = zc;
+    if (pool_out) pool_out[t] = pool;
+    if (grant_out) grant_out[t] = grant;
+    if (status_out) status_out[t] = status;
+    if (released_out) released_out[t] = n;
+  }
+  return SIF_OK;
+}
+
+int32_t sif_gate_violation(uint64_t t0, uint64_t bubble_begin, uint64_t bubble_end) {
+  return t0 < bubble_begin || (bubble_end != 0 && t0 > bubble_end);
+}
+
+uint32_t sif_latency_bucket(uint64_t ns) {
+  if (ns < 16) return (uint32_t)ns;
+  const uint32_t top = 63u - (uint32_t)__builtin_clzll(ns);        // position of the leading one, >= 4
+  return (top - 3u) * 16u + (uint32_t)((ns >> (top - 4u)) & 15u);
+}
+
+uint64_t sif_latency_bucket_lower_ns(uint32_t bucket) {
+  if (bucket < 16) return bucket;
+  if (bucket >= sif::LatencyHist::kBuckets) bucket = sif::LatencyHist::kBuckets - 1;
+  const uint32_t top = bucket / 16u + 3u;
+  return (uint64_t)(16u + bucket % 16u) << (top - 4u);
+}
+
+uint32_t sif_latency_buckets(void) { return sif::LatencyHist::kBuckets; }
+
+uint64_t sif_latency_percentile(const uint64_t* counts, uint32_t n_buckets, double p) {
+  if (!counts || n_buckets == 0 || !(p > 0.0)) return 0;
+  if (n_buckets > sif::LatencyHist::kBuckets) n_buckets = sif::LatencyHist::kBuckets;
+  if (p > 1.0) p = 1.0;
+  uint64_t total = 0;
+  for (uint32_t b = 0; b < n_buckets; ++b) total += counts[b];
+  if (total == 0) return 0;
+  uint64_t rank = (uint64_t)(p * (double)total);                    // nearest rank: ceil(p * total), at least 1
+  if ((double)rank < p * (double)total) ++rank;
+  if (rank == 0) rank = 1;
+  uint64_t seen = 0;
+  for (uint32_t b = 0; b < n_buckets; ++b) {
+    seen += counts[b];
+    if (seen >= rank) {
+      const uint64_t lo = sif_latency_bucket_lower_ns(b);
+      const uint64_t hi = b + 1 < sif::LatencyHist::kBuckets ? sif_latency_bucket_lower_ns(b + 1) : lo + 1;
+      return lo + (hi - 1 - lo) / 2;                                  // middle of the values the bucket holds
+    }
+  }
+  return sif_latency_bucket_lower_ns(n_buckets - 1);
 }
 
 int32_t sif_online_pull_ok(int32_t status, uint32_t queue_len, uint64_t predicted_remaining_ns, uint64_t predicted_request_ns) {

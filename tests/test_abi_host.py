@@ -74,13 +74,95 @@ def test_barrier_rules_and_principles_match_oracle():
     assert S.sif_principle_2(5, 6) and not S.sif_principle_2(6, 6)
 
 
+def test_monitor_scheduler_barrier_chain_over_traces_matches_oracle():
+    """The objects the monitor and barrier threads keep (window, Algorithm 1 state, token account), driven over count
+    traces without a GPU, against the oracle's run over the same traces: Z_c, pool, grant, status and the number of
+    kernels forwarded in every period; and from the C side's own outputs, the cost forwarded per period stays within
+    that period's grant."""
+    rng = np.random.default_rng(3)
+    for case in range(300):
+        alpha = int(rng.integers(0, 3)); beta = alpha + int(rng.integers(0, 4))
+        gn, gd = [(2, 1), (3, 2), (5, 4), (1, 1), (3, 1)][int(rng.integers(0, 5))]
+        m = int(rng.integers(1, 4))
+        ll = int(rng.integers(1, 60)); ul = ll + int(rng.integers(0, 200)); t0 = int(rng.integers(1, 30))
+        window = int(rng.integers(1, 12))
+        n = int(rng.integers(1, 120))
+        # training phases (counts > 0) and bubbles (runs of zero counts) of random lengths
+        counts = []
+        while len(counts) < n:
+            counts += [int(v) for v in rng.integers(1, 5, rng.integers(1, 6))]
+            counts += [0] * int(rng.integers(0, 15))
+        counts = counts[:n]
+        costs = [int(v) for v in rng.integers(0, max(2, ul // m + 3), rng.integers(0, 200))]
+        p = S.sif_alg1_params(alpha, beta, gn, gd, m, 0, ll, ul, t0)
+        got = S.sif_sched_run_trace(p, window, counts, costs)
+        want = OK.run_trace(counts, costs, window, alpha, beta, gn, gd, m, ll, ul, t0)
+        assert got == want, (case, alpha, beta, gn, gd, m, ll, ul, t0, window)
+        head = 0
+        for zc, pool, grant, status, nrel in got:
+            assert sum(costs[head:head + nrel]) <= grant
+            assert head + nrel == len(costs) or costs[head + nrel] > grant - sum(costs[head:head + nrel])   # the head blocks only when it must
+            assert (pool == 0) == (zc <= alpha) and grant == pool // m and (status == OK.IDLE) == (zc > beta)
+            head += nrel
+    with pytest.raises(S.SifError):
+        S.sif_sched_run_trace(S.sif_alg1_params(1, 2, 2, 1, 1, 0, 1, 2, 1), 0, [0], [1])                # window = 0
+
+
+def test_kernel_charge_is_its_predicted_time_capped_by_the_largest_grant():
+    for us, ul, m, want in ((7, 800, 1, 7), (800, 800, 1, 800), (801, 800, 1, 800), (500, 800, 2, 400), (3, 2, 4, 1), (0, 10, 1, 0),
+                            (2 ** 40, 2 ** 50, 1, 2 ** 32 - 1)):
+        assert S.sif_kb_charge(us, ul, m) == want, (us, ul, m)
+    # a charged kernel can always be forwarded by a full grant of the stable phase
+    for ul, m in ((800, 1), (800, 3), (5, 7)):
+        grant = ul // m
+        assert S.sif_kb_release([S.sif_kb_charge(10 ** 6, ul, m)], max(grant, 1))[0] == 1
+
+
+def test_gate_violation_checker_on_synthetic_records():
+    """The check behind sif_stats.gate_violations: a kernel start against the bubble's own begin / end stamps."""
+    begin, end = 1_000_000, 1_500_000
+    assert not S.sif_gate_violation(begin, begin, end) and not S.sif_gate_violation(end, begin, end)      # the stamps themselves are inside
+    assert not S.sif_gate_violation(1_200_000, begin, end)
+    assert S.sif_gate_violation(begin - 1, begin, end) and S.sif_gate_violation(end + 1, begin, end)
+    assert not S.sif_gate_violation(2_000_000, begin, 0) and S.sif_gate_violation(999_999, begin, 0)       # bubble not over yet: only its begin binds
+    rng = np.random.default_rng(11)
+    for _ in range(2000):
+        b0 = int(rng.integers(1, 2 ** 60)); b1 = b0 + int(rng.integers(0, 10 ** 7)); t = b0 + int(rng.integers(-10 ** 7, 2 * 10 ** 7))
+        assert S.sif_gate_violation(max(t, 0), b0, b1) == (not (b0 <= max(t, 0) <= b1))
+
+
+def test_latency_histogram_buckets_and_percentiles():
+    nb = S.sif_latency_buckets()
+    lows = [S.sif_latency_bucket_lower_ns(b) for b in range(nb)]
+    assert lows[0] == 0 and all(b > a for a, b in zip(lows, lows[1:]))
+    for b in range(nb):
+        assert S.sif_latency_bucket(lows[b]) == b
+        if b + 1 < nb:
+            assert S.sif_latency_bucket(lows[b + 1] - 1) == b
+            assert lows[b + 1] - lows[b] <= max(1, lows[b] // 16)                  # at most 1/16 wider than its lower edge
+    assert S.sif_latency_bucket(2 ** 64 - 1) == nb - 1
+    rng = np.random.default_rng(12)
+    for trial in range(20):
+        lat = np.exp(rng.normal(15.5, 0.8, int(rng.integers(1, 4000)))).astype(np.int64)      # milliseconds, log-normal
+        counts = [0] * nb
+        for v in lat:
+            counts[S.sif_latency_bucket(int(v))] += 1
+        srt = np.sort(lat)
+        for p in (0.5, 0.95, 0.99, 1.0):
+            exact = int(srt[int(np.ceil(p * len(srt))) - 1])                       # nearest rank
+            got = S.sif_latency_percentile(counts, p)
+            assert S.sif_latency_bucket(got) == S.sif_latency_bucket(exact)
+            assert abs(got - exact) <= exact / 32 + 1
+    assert S.sif_latency_percentile([0] * nb, 0.5) == 0
+
+
 def test_bubble_model_matches_oracle():
     from oracle.decoder import n_params
     n = n_params(Y.DP_DECODER)
     assert S.sif_collective_ns(2 * n, 50_000_000_000) == OB.dp_bubbles(n, 2, 50_000_000_000)[0][1] == 4_977_592
     c = Y.TP_DECODER
     assert S.sif_collective_ns(c["batch"] * c["seq"] * c["d_model"] * 2, c["bw_bytes_per_s"]) == OB.tp_bubbles(1, c["batch"] * c["seq"], c["d_model"], 2, c["bw_bytes_per_s"])[0][1]
-    assert S.sif_collective_ns(2 ** 62, 3) == (2 ** 62 * 10 ** 9) // 3 % 2 ** 64 or True   # 128-bit intermediate, no trap
+    assert S.sif_collective_ns(2 ** 62, 10 ** 12) == (2 ** 62 * 10 ** 9) // 10 ** 12                # the product passes 2^64: 128-bit intermediate
     kinds = {0: "F", 1: "B"}
     for p, m, tf, tb in ((4, 8, 100, 200), (3, 3, 5, 5), (2, 6, 11, 30), (5, 9, 3, 8)):
         for s in range(p):

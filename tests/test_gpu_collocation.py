@@ -34,6 +34,25 @@ def last_launch(s):
     return tr[-1][3] if tr else 0
 
 
+def settled_stats(s, n_gated):
+    """Statistics once the barrier thread has judged the start of every gated kernel that ran (it does so when it sees
+    the kernel complete and its bubble end, a few microseconds after the streams are idle)."""
+    import time
+    t_end = time.time() + 2.0
+    st = s.stats()
+    while st.gate_checked + st.gate_unchecked < n_gated and time.time() < t_end:
+        time.sleep(0.001)
+        st = s.stats()
+    return st
+
+
+def assert_library_checked_every_start(s, ran):
+    """The library's own check of the invariant (sif_stats.gate_violations) covered every kernel that ran."""
+    st = settled_stats(s, len(ran))
+    assert st.gate_checked == len(ran) and st.gate_unchecked == 0 and st.gate_violations == 0 and st.gate_timeouts == 0, \
+        (st.gate_checked, st.gate_unchecked, st.gate_violations, st.gate_timeouts, len(ran))
+
+
 def assert_starts_inside_bubbles(bubbles, ran):
     b0 = np.array([b[0] for b in bubbles]); b1 = np.array([b[1] for b in bubbles])
     for t0, _ in ran:
@@ -108,10 +127,12 @@ DEC = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=1000
 ENC = dict(n_layers=2, d_model=256, n_heads=4, d_head=64, d_ffn=1024, vocab=500, max_pos=64, batch=8, seq=64)
 
 
-def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000, coalesce=0):
+def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000, coalesce=0, tweak=None, extras=None):
     shape, ishape = decoder_shape(DEC), encoder_shape(ENC)
     cfg = S.sif_default_config()
     cfg.collocate = 1 if (collocate and not coalesce) else 0
+    if tweak:
+        tweak(cfg)
     with Session(cfg) as s:
         s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_FIXED, lr=0.01, fixed_bubble_ns=bubble_ns)
         m = s.register_inference(ishape, P.pack(ishape, Y.encoder_params(2, ENC, perturb=True)), coalesce=coalesce)
@@ -137,16 +158,25 @@ def run_transformer(collocate, n_batches, steps=6, bubble_ns=1_500_000, coalesce
                 extra += 1
             for tk in tickets:
                 s.wait(tk, 20.0)
-        return w, l, outs, s.stats(), bubbles_and_kernels(s, n_cal)
+        trace = bubbles_and_kernels(s, n_cal)
+        if extras is not None:
+            extras["release_log"] = S.sif_read_release_log(s.ctx)
+            extras["stats"] = settled_stats(s, len(trace[1]))
+            extras["n_cal"] = n_cal
+        return w, l, outs, s.stats(), trace
 
 
 def test_transformer_collocation_invariants():
     w_solo, l_solo, _, _, _ = run_transformer(False, 0)
-    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_transformer(True, 6)
+    ex = {}
+    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_transformer(True, 6, extras=ex)
     assert np.array_equal(w_solo, w_col) and np.array_equal(l_solo, l_col)
     assert st.offline_batches == 6
     assert_starts_inside_bubbles(bubbles, ran)
     assert len(ran) + skipped == st.kernels_launched
+    # the library's own check of the same invariant judged every kernel that ran, and found nothing
+    sx = ex["stats"]
+    assert sx.gate_checked == len(ran) and sx.gate_unchecked == 0 and sx.gate_violations == 0 and sx.gate_timeouts == 0
     assert st.filled_ns <= st.infer_busy_ns
     ishape = encoder_shape(ENC)
     master = Y.encoder_params(2, ENC, perturb=True)
@@ -160,6 +190,68 @@ def test_transformer_collocation_invariants():
             s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
             assert torch.equal(out, outs[i])                                       # same bits as the solo run
             assert_bf16_close(up(outs[i]), OE.encoder_forward(w, ids, ENC, "bf16"), "collocated encoder", elem_slack=1.5e-2)
+
+
+def solo_encoder_outputs(indices, like):
+    ishape = encoder_shape(ENC)
+    master = Y.encoder_params(2, ENC, perturb=True)
+    got = {}
+    with Session() as s:
+        m = s.register_inference(ishape, P.pack(ishape, master))
+        for i in indices:
+            I, out = i32(Y.token_ids(50 + i, ENC["batch"], ENC["seq"], ENC["vocab"])), torch.zeros_like(like)
+            torch.cuda.synchronize()
+            s.wait(s.submit_offline(m, I, out, ENC["batch"], ENC["seq"]))
+            got[i] = out
+    return got
+
+
+def test_tokens_limit_what_is_forwarded_per_period_when_the_grant_is_small():
+    """The offline token mechanism (Sec. 3.3 "Kernel Barrier") in a regime where it binds: period 100 us, grants of at
+    most 100 tokens = 100 us of predicted kernel time per period.  From the barrier's own log of what it forwarded:
+    the tokens taken within one period never exceed that period's grant, the grants are those Algorithm 1 can hand
+    out, and the limit was reached in some periods (the next kernel had to wait for the next grant)."""
+    def binding(cfg):
+        cfg.period_us = 100
+        cfg.alg1.alpha, cfg.alg1.beta, cfg.alg1.gamma_num, cfg.alg1.gamma_den, cfg.alg1.m = 1, 3, 2, 1, 1
+        cfg.alg1.t0, cfg.alg1.ll, cfg.alg1.ul = 25, 50, 100
+    ex = {}
+    w_solo, l_solo, _, _, _ = run_transformer(False, 0)
+    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_transformer(True, 6, bubble_ns=3_000_000, tweak=binding, extras=ex)
+    assert np.array_equal(w_solo, w_col) and np.array_equal(l_solo, l_col)
+    assert st.offline_batches == 6
+    assert_starts_inside_bubbles(bubbles, ran)
+    log = [r for r in ex["release_log"] if r[4] > ex["n_cal"]]
+    assert len(log) == st.kernels_launched and all(kind == 0 for *_, kind in log)
+    per_period = {}
+    for period, grant, model, charge, launch, kind in log:
+        assert grant in (50, 100) and 1 <= charge <= 100, (grant, charge)          # incremental phase: LL; stable phase: UL
+        tot, g = per_period.get(period, (0, grant))
+        assert g == grant
+        per_period[period] = (tot + charge, grant)
+    assert all(tot <= g for tot, g in per_period.values()), [v for v in per_period.values() if v[0] > v[1]]
+    biggest = max(c for _, _, _, c, _, _ in log)
+    assert sum(1 for tot, g in per_period.values() if tot + biggest > g) >= 3      # the grant did run out
+    assert len(per_period) >= sum(c for _, _, _, c, _, _ in log) / 100             # so the work needed that many periods
+    for i, out in solo_encoder_outputs((0, 5), outs[0]).items():
+        assert torch.equal(out, outs[i])
+
+
+def test_launch_given_back_by_blocks_that_stop_waiting_for_the_gate_is_run_again():
+    """A block of a speculatively launched kernel waits a bounded time for the decision of the launch's first block and
+    then gives the launch back to the host.  Forced from the host here (every fifth launch waits for two polls only);
+    every kernel exits normally, the launches are run again and every output keeps the bits of a run by itself."""
+    def impatient(cfg):
+        cfg.gate_spin_log2, cfg.gate_spin_every = 1, 5
+    ex = {}
+    w_solo, l_solo, _, _, _ = run_transformer(False, 0)
+    w_col, l_col, outs, st, (bubbles, ran, skipped) = run_transformer(True, 6, steps=6, tweak=impatient, extras=ex)
+    assert np.array_equal(w_solo, w_col) and np.array_equal(l_solo, l_col)
+    assert st.offline_batches == 6
+    assert ex["stats"].gate_timeouts != 0 and ex["stats"].gate_violations == 0
+    assert_starts_inside_bubbles(bubbles, ran)
+    for i, out in solo_encoder_outputs(range(6), outs[0]).items():
+        assert torch.equal(out, outs[i]), i
 
 
 def test_coalesced_offline_requests_give_the_same_bits_as_single_ones():
@@ -385,7 +477,7 @@ def dec4_groups():
     return [2 * (layer + (2 * d if l == 0 else 0)) for l in range(DEC4["n_layers"])] + [2 * (DEC4["vocab"] + DEC4["max_pos"]) * d]
 
 
-def run_overlapped(bucket_bytes, bw, device_timed, steps=3, n_batches=0, calibrate=False):
+def run_overlapped(bucket_bytes, bw, device_timed, steps=3, n_batches=0, calibrate=False, all_steps=False):
     from oracle import bubbles as OB
     shape, ishape = decoder_shape(DEC4), encoder_shape(ENC)
     cfg = S.sif_default_config()
@@ -414,6 +506,9 @@ def run_overlapped(bucket_bytes, bw, device_timed, steps=3, n_batches=0, calibra
         tr = S.sif_read_trace(s.ctx, 0)
         marks = [i for i, r in enumerate(tr) if r[0] == 4]
         last = tr[marks[-2] + 1:marks[-1]] if len(marks) >= 2 else tr      # the last step: between its two markers
+        # every step of this run: the records in front of each of its `steps` end markers (a step's begin marker leaves
+        # no record of its own, so a step's records lie between the previous step's end marker and its own)
+        per_step = [tr[(marks[i - 1] + 1 if i > 0 else 0):marks[i]] for i in range(len(marks) - steps, len(marks))] if all_steps else None
         extra = 0                         # a slow host may need more bubbles than the steps that are compared
         while s.stats().offline_batches < n_batches and extra < 60:
             s.step(x, t)
@@ -421,7 +516,8 @@ def run_overlapped(bucket_bytes, bw, device_timed, steps=3, n_batches=0, calibra
             extra += 1
         for tk in tickets:
             s.wait(tk, 20.0)
-        return w, buckets, last, s.stats(), (bubbles_and_kernels(s, n_cal) if n_batches else None), outs
+        res = (w, buckets, last, s.stats(), (bubbles_and_kernels(s, n_cal) if n_batches else None), outs)
+        return res + (per_step,) if all_steps else res
 
 
 def test_overlapped_gradient_exchange_exposes_only_its_tail():
@@ -430,28 +526,34 @@ def test_overlapped_gradient_exchange_exposes_only_its_tail():
     groups = dec4_groups()
     want_buckets = OB.dp_gradient_buckets(groups, cap)
     assert len(want_buckets) == 3
-    w_plain, _, last_plain, _, _, _ = run_overlapped(0, bw, True)
+    _, _, last_plain, _, _, _ = run_overlapped(0, bw, True)
     for device_timed in (True, False):
-        # A bubble that the host times ends late when the monitor thread loses its core for a scheduling quantum
-        # (milliseconds): such a run is repeated; the lower bound and everything else must hold in every run.
-        for attempt in range(4):
-            w, buckets, last, st, _, _ = run_overlapped(cap, bw, device_timed)
-            assert np.array_equal(w, w_plain)                              # finalizing per bucket changes no gradient bit
-            assert [b for b, _ in buckets] == [sum(groups[g] for g in grp) for grp in want_buckets]
+        # Every step of the run is judged (the wait of each step against the oracle's value from that step's own
+        # stamps).  Device-timed, every wait ends within 6 us of that value.  Host-timed, the monitor thread releases
+        # it and may lose its core for a scheduling quantum now and then: the lower bound holds for every step, the
+        # median step ends within 300 us, and none later than the device's own deadline would show (100 ms).
+        steps = 3 if device_timed else 9
+        w, buckets, _, st, _, _, per_step = run_overlapped(cap, bw, device_timed, steps=steps, all_steps=True)
+        assert np.array_equal(w, run_overlapped(0, bw, True, steps=steps)[0])      # finalizing per bucket changes no gradient bit
+        assert [b for b, _ in buckets] == [sum(groups[g] for g in grp) for grp in want_buckets]
+        whole, = [t1 - t0 for kind, _, _, _, t0, t1 in last_plain if kind == 3]
+        late = []
+        for last in per_step:
             end_of = {rid: t1 for kind, rid, _, _, _, t1 in last if kind == 1}
             (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
             ready = [end_of[r] for _, r in buckets]
             assert ready == sorted(ready) and ready[-1] <= b0
             dur = [OB.collective_ns(b, bw) for b, _ in buckets]
             want = OB.dp_overlapped_wait(ready, dur, b0)
-            whole, = [t1 - t0 for kind, _, _, _, t0, t1 in last_plain if kind == 3]
             assert 0 < want < whole                                         # part of the exchange hid behind backward
             got = b1 - b0
             assert want - 500 <= got, (got, want, device_timed)
-            if got <= want + (6_000 if device_timed else 300_000):
-                break
+            late.append(got - want)
+        assert len(late) == steps
+        if device_timed:
+            assert max(late) <= 6_000, late
         else:
-            raise AssertionError((got, want, device_timed))
+            assert float(np.median(late)) <= 300_000 and max(late) <= 100_000_000, late
     # a link so fast that the exchange is over when backward ends: no bubble at all, the stream never goes idle
     _, _, last, st, _, _ = run_overlapped(cap, 10 ** 15, True)
     (b0, b1), = [(t0, t1) for kind, _, _, _, t0, t1 in last if kind == 3]
