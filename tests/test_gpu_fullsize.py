@@ -158,3 +158,54 @@ def test_fill_in_the_benchmark_configuration_keeps_the_bits_of_a_run_alone():
     for i, b in ((0, 3), (35, 31)):
         ref = OE.encoder_forward(w, eids[i][b:b + 1], ecfg, "bf16")
         assert_bf16_close(got[i][b:b + 1].float().numpy(), ref, f"batch {i} sample {b}", elem_slack=2e-2)
+
+
+def test_dp_decoder_full_shape_one_layer_step_matches_oracle_forward_and_backward():
+    """configs[1] at full shape with one of its twelve layers: 8 x 1024 tokens, d 768, 12 heads of 64, vocabulary 50257.
+    Every product of the step runs at the size and in the tile configuration it has in the benchmark (the layer's four
+    forward products, their data and weight gradients with the K split, fused causal attention forward and backward,
+    the 8192 x 50264 x 768 LM head, its weight gradient 50257 x 768 x 8192 and its data gradient cut along K), and is
+    compared with the oracle: activations, loss, the gradient of the logits, every parameter gradient (the embedding
+    scatter included) and the updated parameters."""
+    cfg = dict(Y.DP_DECODER, n_layers=1)
+    shape = decoder_shape(cfg)
+    master = Y.decoder_params(1, cfg, perturb=True)
+    ids, tg = Y.token_ids(3, cfg["batch"], cfg["seq"], cfg["vocab"]), Y.token_ids(4, cfg["batch"], cfg["seq"], cfg["vocab"])
+    ids[0, 5] = ids[0, 1] = ids[1, 7]                                 # repeated tokens meet in one row of the scatter
+    lr = cfg["lr"]
+    m_tok = cfg["batch"] * cfg["seq"]
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_NONE, lr=lr)
+        loss, I, T = torch.zeros(1, device=DEV), i32(ids), i32(tg)
+        torch.cuda.synchronize()
+        s.step(I, T, loss)
+        s.sync()
+        got_loss = loss.item()
+        got_act = {name: up(s.train_tensor(name, 0)) for name in ("ln1", "qkv", "o", "x_mid", "ln2", "z", "a", "x_out")}
+        got_dlogits = s.train_tensor("logits").float().cpu().numpy().reshape(m_tok, -1)[:, :cfg["vocab"]]
+        got_g = P.unpack(shape, up(s.train_tensor("grads")))
+        got_p = P.unpack(shape, up(s.train["master"]))
+    rl, rnew, rg, rc = OD.gpt_train_step(master, ids, tg, cfg, lr, "bf16")
+    c = rc["layers"][0]
+    for name in ("ln1", "qkv", "o", "x_mid", "ln2", "z", "a"):
+        assert_bf16_close(got_act[name].reshape(c[name].shape), c[name], f"full-shape {name}", elem_slack=8e-3)
+    assert_bf16_close(got_act["x_out"].reshape(rc["x_last"].shape), rc["x_last"], "full-shape layer output", elem_slack=8e-3)
+    assert abs(got_loss - rl) <= 2e-2 * abs(rl), (got_loss, rl)
+    # gradient of the logits: (softmax - onehot) / tokens.  The entries at the targets are four orders of magnitude
+    # larger than the rest, so the rest is also compared by itself.
+    ref_d = rc["dlogits"]
+    assert_bf16_close(got_dlogits, ref_d, "full-shape dlogits", elem_slack=2e-2)
+    rows = np.arange(m_tok)
+    g_off, r_off = got_dlogits.astype(np.float64), ref_d.copy()
+    g_off[rows, tg.reshape(-1)] = 0.0
+    r_off[rows, tg.reshape(-1)] = 0.0
+    assert_bf16_close(g_off, r_off, "full-shape dlogits away from the targets", elem_slack=2e-2)
+    del g_off, r_off, got_dlogits, ref_d
+    for path, _ in P.layout(shape):
+        g_ref = rg[path] if isinstance(path, str) else rg["layers"][path[1]][path[2]]
+        g_got = got_g[path] if isinstance(path, str) else got_g["layers"][path[1]][path[2]]
+        assert_bf16_close(g_got, g_ref, f"full-shape gradient of {path}", elem_slack=2e-2)
+        p_ref = rnew[path] if isinstance(path, str) else rnew["layers"][path[1]][path[2]]
+        p_got = got_p[path] if isinstance(path, str) else got_p["layers"][path[1]][path[2]]
+        bound = 1e-4 * np.max(np.abs(p_ref)) + lr * 2e-2 * np.max(np.abs(g_ref))
+        assert np.max(np.abs(p_got - p_ref)) <= bound, path
