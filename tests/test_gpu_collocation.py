@@ -1,5 +1,5 @@
-"""Scheduling invariants on the GPU (Sec. 2.2 "maintain the training throughput while concurrently providing
-additional inference services"): training results are bit-identical with and without collocation, inference
+"""Scheduling invariants on the GPU (Sec. 2.2: training throughput is to be kept while inference is served beside
+it): training results are bit-identical with and without collocation, inference
 outputs are bit-identical to a solo run and match the oracle, and no inference kernel starts outside a bubble."""
 import numpy as np
 import pytest
