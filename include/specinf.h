@@ -286,12 +286,14 @@ sif_status sif_k_attn_bwd(const void* qkv_dev, const void* o_dev, const void* d_
                           void* dqkv_dev, uint32_t batch, uint32_t seq, uint32_t heads, uint32_t d_head, uint32_t ld_qkv,
                           uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal, void* stream);
 
-/* x[t,:] = wte[ids[t],:] + wpe[t % seq,:]   (bf16) */
-sif_status sif_k_embed_fwd(const int32_t* ids_dev, const void* wte_dev, const void* wpe_dev, void* x_dev,
+/* x[t,:] = wte[ids[t],:] + wpe[t % seq,:]   (bf16).  wte has `vocab` rows; an id outside [0, vocab) is taken as the
+ * nearest valid one (here and in every kernel that indexes a table with caller data: embedding backward, the targets
+ * of the cross entropy), so that no input can make a kernel touch memory outside the table. */
+sif_status sif_k_embed_fwd(const int32_t* ids_dev, const void* wte_dev, const void* wpe_dev, void* x_dev, uint32_t vocab,
                            uint32_t tokens, uint32_t seq, uint32_t d, void* stream);
 /* dwte[v,:] += sum over tokens t with ids[t] = v of dx[t,:] in ascending t (bf16, fp32 sum, no atomics);
  * dwpe[s,:] = sum over the batch of dx[b*seq+s,:]. */
-sif_status sif_k_embed_bwd(const int32_t* ids_dev, const void* dx_dev, void* dwte_dev, void* dwpe_dev,
+sif_status sif_k_embed_bwd(const int32_t* ids_dev, const void* dx_dev, void* dwte_dev, void* dwpe_dev, uint32_t vocab,
                            uint32_t tokens, uint32_t seq, uint32_t d, void* stream);
 
 /* Mean token cross entropy over bf16 logits [tokens][ld] (first `vocab` columns valid): per-token loss into

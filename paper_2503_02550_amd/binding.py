@@ -161,8 +161,8 @@ _sig("sif_k_colsum_static", i32, vp, u32, vp, u32, u32, vp)
 _sig("sif_colsum_static_max_floats", u64)
 _sig("sif_k_softmax_fwd", i32, vp, vp, u32, u32, u32, u32, u32, u32, vp)
 _sig("sif_k_softmax_bwd", i32, vp, vp, vp, u32, u32, u32, u32, f32, u32, vp)
-_sig("sif_k_embed_fwd", i32, vp, vp, vp, vp, u32, u32, u32, vp)
-_sig("sif_k_embed_bwd", i32, vp, vp, vp, vp, u32, u32, u32, vp)
+_sig("sif_k_embed_fwd", i32, vp, vp, vp, vp, u32, u32, u32, u32, vp)
+_sig("sif_k_embed_bwd", i32, vp, vp, vp, vp, u32, u32, u32, u32, vp)
 _sig("sif_k_xent_fwd_bwd", i32, vp, vp, vp, u32, u32, u32, vp)
 _sig("sif_k_reduce_sum", i32, vp, vp, u32, f32, vp)
 _sig("sif_k_sgd_bf16", i32, vp, vp, vp, u64, f32, vp)
@@ -326,12 +326,12 @@ def sif_k_softmax_bwd(dp, p, ds, batch, rows, cols, ld, scale, causal, stream=No
     return check(lib.sif_k_softmax_bwd(ptr(dp), ptr(p), ptr(ds), batch, rows, cols, ld, scale, causal, stream_ptr(stream)))
 
 
-def sif_k_embed_fwd(ids, wte, wpe, x, tokens, seq, d, stream=None):
-    return check(lib.sif_k_embed_fwd(ptr(ids), ptr(wte), ptr(wpe), ptr(x), tokens, seq, d, stream_ptr(stream)))
+def sif_k_embed_fwd(ids, wte, wpe, x, vocab, tokens, seq, d, stream=None):
+    return check(lib.sif_k_embed_fwd(ptr(ids), ptr(wte), ptr(wpe), ptr(x), vocab, tokens, seq, d, stream_ptr(stream)))
 
 
-def sif_k_embed_bwd(ids, dx, dwte, dwpe, tokens, seq, d, stream=None):
-    return check(lib.sif_k_embed_bwd(ptr(ids), ptr(dx), ptr(dwte), ptr(dwpe), tokens, seq, d, stream_ptr(stream)))
+def sif_k_embed_bwd(ids, dx, dwte, dwpe, vocab, tokens, seq, d, stream=None):
+    return check(lib.sif_k_embed_bwd(ptr(ids), ptr(dx), ptr(dwte), ptr(dwpe), vocab, tokens, seq, d, stream_ptr(stream)))
 
 
 def sif_k_xent_fwd_bwd(logits, targets, loss, tokens, vocab, ld, stream=None):

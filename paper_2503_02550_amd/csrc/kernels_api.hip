@@ -65,14 +65,14 @@ sif_status sif_k_attn_bwd(const void* qkv, const void* o, const void* d_o, const
   return launch_attn_bwd_dkv(qkv, d_o, lse, delta, dqkv, batch, seq, heads, d_head, ld_qkv, ld_o, ld_dqkv, causal, S(stream), no_ctl());
 }
 
-sif_status sif_k_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens, uint32_t seq,
+sif_status sif_k_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t vocab, uint32_t tokens, uint32_t seq,
                            uint32_t d, void* stream) {
-  return launch_embed_fwd(ids, wte, wpe, x, tokens, seq, d, S(stream), no_ctl());
+  return launch_embed_fwd(ids, wte, wpe, x, vocab, tokens, seq, d, S(stream), no_ctl());
 }
 
-sif_status sif_k_embed_bwd(const int32_t* ids, const void* dx, void* dwte, void* dwpe, uint32_t tokens, uint32_t seq,
+sif_status sif_k_embed_bwd(const int32_t* ids, const void* dx, void* dwte, void* dwpe, uint32_t vocab, uint32_t tokens, uint32_t seq,
                            uint32_t d, void* stream) {
-  sif_status st = launch_embed_bwd_wte(ids, dx, dwte, tokens, d, S(stream), no_ctl());
+  sif_status st = launch_embed_bwd_wte(ids, dx, dwte, vocab, tokens, d, S(stream), no_ctl());
   if (st != SIF_OK) return st;
   return launch_embed_bwd_wpe(dx, dwpe, tokens, seq, d, S(stream), no_ctl());
 }

@@ -60,10 +60,10 @@ sif_status launch_attn_bwd_dkv(const void* qkv, const void* d_o, const float* ls
                                uint32_t heads, uint32_t d_head, uint32_t ld_qkv, uint32_t ld_o, uint32_t ld_dqkv, uint32_t causal, hipStream_t s,
                                const KCtl& c);
 // token ids per segment (segs.ptr), positions restart with every sequence of a segment
-sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const void* wpe, void* x, uint32_t d, hipStream_t s, const KCtl& c);
-sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens,
+sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const void* wpe, void* x, uint32_t vocab, uint32_t d, hipStream_t s, const KCtl& c);
+sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t vocab, uint32_t tokens,
                             uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c);
-sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t tokens, uint32_t d,
+sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t vocab, uint32_t tokens, uint32_t d,
                                 hipStream_t s, const KCtl& c);
 sif_status launch_embed_bwd_wpe(const void* dx, void* dwpe, uint32_t tokens, uint32_t seq, uint32_t d, hipStream_t s,
                                 const KCtl& c);

@@ -624,7 +624,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     bf16_t* xin0 = x0[sl];
     if (s.vocab) {
       const bf16_t *wte = work + pm.at("wte"), *wpe = work + pm.at("wpe");
-      emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_fwd((const int32_t*)t->cur_inputs, wte, wpe, xin0, M, seq, d, s2, c); });
+      emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_fwd((const int32_t*)t->cur_inputs, wte, wpe, xin0, V, M, seq, d, s2, c); });
     } else {
       // layer stack: the caller's activations become the input of the first layer
       emit(p, "stage_x", bytes_cost_us(2.0 * mb_bytes), [=](hipStream_t s2, const KCtl& c) {
@@ -720,7 +720,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     if (s.vocab) {
       bf16_t *gwte = grads + pm.at("wte"), *gwpe = grads + pm.at("wpe");
       const bf16_t* dx0 = sc.dx_a;
-      emit(p, "dwte_scatter", bytes_cost_us(4.0 * M * d) + 10.0, [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wte((const int32_t*)t->cur_inputs, dx0, gwte, M, d, s2, c); });
+      emit(p, "dwte_scatter", bytes_cost_us(4.0 * M * d) + 10.0, [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wte((const int32_t*)t->cur_inputs, dx0, gwte, V, M, d, s2, c); });
       emit(p, "dwpe", bytes_cost_us(2.0 * M * d), [=](hipStream_t s2, const KCtl& c) { return launch_embed_bwd_wpe(dx0, gwpe, M, seq, d, s2, c); });
     }
     if (overlap) {
@@ -916,6 +916,7 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
   bf16_t *prob = (bf16_t*)im.bufs.at("prob"), *o = (bf16_t*)im.bufs.at("o"), *a = (bf16_t*)im.bufs.at("a");
   float* scores = (float*)im.bufs.at("scores");
   const bf16_t *wte = W + pm.at("wte"), *wpe = W + pm.at("wpe"), *eg = W + pm.at("emb_ln_g"), *eb = W + pm.at("emb_ln_b");
+  const uint32_t vocab = s.vocab;
   // the first and the last kernel serve all requests of the sequence at once: a table says which rows are whose
   static_assert(kMaxRowSegs >= kMaxCoalesce, "one row segment per coalesced request");
   RowSegs in_segs, out_segs;
@@ -925,7 +926,7 @@ sif_status build_infer_plan(const InferModel& im, const InferIO* io, uint32_t n_
     in_segs.ptr[r] = const_cast<void*>(io[r].in_dev); out_segs.ptr[r] = io[r].out_dev;
     in_segs.seq[r] = out_segs.seq[r] = rows_of[r] / batch;
   }
-  emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd_segs(in_segs, wte, wpe, t, d, st, c); });
+  emit(p, "embed", bytes_cost_us(6.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_embed_fwd_segs(in_segs, wte, wpe, t, vocab, d, st, c); });
   emit(p, "emb_ln", bytes_cost_us(4.0 * M * d), [=](hipStream_t st, const KCtl& c) { return launch_layernorm_fwd(t, eg, eb, x, nullptr, nullptr, M, d, st, c); });
   for (uint32_t l = 0; l < s.n_layers; ++l) {
     const bf16_t *w_qkv = W + pm.at(L(l, "w_qkv")), *b_qkv = W + pm.at(L(l, "b_qkv")), *w_o = W + pm.at(L(l, "w_o")), *b_o = W + pm.at(L(l, "b_o"));

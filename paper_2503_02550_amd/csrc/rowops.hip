@@ -408,13 +408,17 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const float* __restric
 }
 
 // ---------------------------------------------------------------------------------------------- embedding
+// A token id (or a target) outside [0, vocab) is taken as the nearest valid one, so that no caller's data can make a
+// kernel read or write outside the table.
+__device__ __forceinline__ uint32_t clamp_id(int32_t id, uint32_t vocab) { return id < 0 ? 0u : ((uint32_t)id < vocab ? (uint32_t)id : vocab - 1u); }
+
 __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restrict__ ids, const bf16_t* __restrict__ wte,
                                                         const bf16_t* __restrict__ wpe, bf16_t* __restrict__ x,
-                                                        uint32_t tokens, uint32_t seq, uint32_t d, KCtl ctl) {
+                                                        uint32_t tokens, uint32_t seq, uint32_t d, uint32_t vocab, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63, nv = d >> 3;
   if (t < tokens) {
-    const uint4* a = reinterpret_cast<const uint4*>(wte + (size_t)ids[t] * d);
+    const uint4* a = reinterpret_cast<const uint4*>(wte + (size_t)clamp_id(ids[t], vocab) * d);
     const uint4* b = reinterpret_cast<const uint4*>(wpe + (size_t)(t % seq) * d);
     uint4* o = reinterpret_cast<uint4*>(x + (size_t)t * d);
     for (uint32_t v = lane; v < nv; v += 64) {
@@ -430,14 +434,14 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restric
 // The same for several requests whose rows lie back to back in x: segment r reads its own token ids, positions
 // restart with every sequence of seq[r] tokens.
 __global__ __launch_bounds__(256) void embed_fwd_segs_kernel(RowSegs segs, const bf16_t* __restrict__ wte, const bf16_t* __restrict__ wpe,
-                                                             bf16_t* __restrict__ x, uint32_t tokens, uint32_t d, KCtl ctl) {
+                                                             bf16_t* __restrict__ x, uint32_t tokens, uint32_t d, uint32_t vocab, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6)), lane = threadIdx.x & 63, nv = d >> 3;
   if (t < tokens) {
     uint32_t r = 0;
     while (r + 1 < segs.n && t >= segs.row0[r + 1]) ++r;
     const uint32_t local = t - segs.row0[r];
-    const int32_t id = reinterpret_cast<const int32_t*>(segs.ptr[r])[local];
+    const uint32_t id = clamp_id(reinterpret_cast<const int32_t*>(segs.ptr[r])[local], vocab);
     const uint4* a = reinterpret_cast<const uint4*>(wte + (size_t)id * d);
     const uint4* b = reinterpret_cast<const uint4*>(wpe + (size_t)(local % segs.seq[r]) * d);
     uint4* o = reinterpret_cast<uint4*>(x + (size_t)t * d);
@@ -456,20 +460,20 @@ constexpr int EB_MAXC = 16;   // columns per thread: d <= 4096
 // Block t owns token t.  If an earlier token has the same id the block has nothing to do; otherwise it adds the
 // rows dx[j] of every token j >= t with that id, in ascending j, to dwte[id].
 __global__ __launch_bounds__(256) void embed_bwd_wte_kernel(const int32_t* __restrict__ ids, const bf16_t* __restrict__ dx,
-                                                            bf16_t* __restrict__ dwte, uint32_t tokens, uint32_t d, KCtl ctl) {
+                                                            bf16_t* __restrict__ dwte, uint32_t tokens, uint32_t d, uint32_t vocab, KCtl ctl) {
   __shared__ int sflag[256];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t t = blockIdx.x;
-  const int32_t id = ids[t];
+  const uint32_t id = clamp_id(ids[t], vocab);
   int seen = 0;
-  for (uint32_t j = threadIdx.x; j < t; j += 256) seen |= (ids[j] == id);
+  for (uint32_t j = threadIdx.x; j < t; j += 256) seen |= (clamp_id(ids[j], vocab) == id);
   if (!__syncthreads_or(seen)) {
     float acc[EB_MAXC];
 #pragma unroll
     for (int i = 0; i < EB_MAXC; ++i) acc[i] = 0.f;
     for (uint32_t base = t; base < tokens; base += 256) {
       const uint32_t j = base + threadIdx.x;
-      const int hit = (j < tokens) && (ids[j] == id);
+      const int hit = (j < tokens) && (clamp_id(ids[j], vocab) == id);
       __syncthreads();
       sflag[threadIdx.x] = hit;
       if (__syncthreads_or(hit)) {
@@ -529,7 +533,7 @@ __global__ __launch_bounds__(1024) void xent_kernel(bf16_t* __restrict__ logits,
     for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) sum += __expf(f[i] - mx);
   }
   sum = block_sum(sum, sred);
-  const int32_t tg = targets[t];
+  const int32_t tg = (int32_t)clamp_id(targets[t], vocab);
   const float inv = 1.0f / sum, invn = 1.0f / (float)tokens;
   if (threadIdx.x == 0) loss[t] = (mx + __logf(sum)) - bf2f(row_e[tg]);
   __syncthreads();
@@ -554,7 +558,7 @@ __global__ __launch_bounds__(THREADS) void xent_reg_kernel(bf16_t* __restrict__ 
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   const uint32_t t = blockIdx.x, nv = ld >> 3;
   uint4* gr = reinterpret_cast<uint4*>(logits + (size_t)t * ld);
-  const int32_t tg = targets[t];
+  const int32_t tg = (int32_t)clamp_id(targets[t], vocab);
   const float at_target = bf2f(logits[(size_t)t * ld + tg]);      // read before anything is written back
   uint4 row[MAXV];
 #pragma unroll
@@ -779,28 +783,28 @@ sif_status launch_softmax_bwd(const float* dp, const void* p, void* ds, uint32_t
   return check_launch("softmax_bwd");
 }
 
-sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t tokens,
+sif_status launch_embed_fwd(const int32_t* ids, const void* wte, const void* wpe, void* x, uint32_t vocab, uint32_t tokens,
                             uint32_t seq, uint32_t d, hipStream_t s, const KCtl& c) {
-  REQ(ids && wte && wpe && x && tokens > 0 && seq > 0, "embed_fwd: null or empty");
+  REQ(ids && wte && wpe && x && tokens > 0 && seq > 0 && vocab > 0, "embed_fwd: null or empty");
   REQ((d & 7) == 0 && al16(wte) && al16(wpe) && al16(x), "embed_fwd: d must be a multiple of 8, pointers 16-byte aligned");
-  hipLaunchKernelGGL(embed_fwd_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, ids, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, seq, d, c);
+  hipLaunchKernelGGL(embed_fwd_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, ids, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, seq, d, vocab, c);
   return check_launch("embed_fwd");
 }
 
-sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const void* wpe, void* x, uint32_t d, hipStream_t s, const KCtl& c) {
-  REQ(wte && wpe && x && segs.n > 0 && segs.n <= kMaxRowSegs, "embed_fwd: null or empty");
+sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const void* wpe, void* x, uint32_t vocab, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(wte && wpe && x && segs.n > 0 && segs.n <= kMaxRowSegs && vocab > 0, "embed_fwd: null or empty");
   REQ((d & 7) == 0 && al16(wte) && al16(wpe) && al16(x), "embed_fwd: d must be a multiple of 8, pointers 16-byte aligned");
   const uint32_t tokens = segs.row0[segs.n];
   if (sif_status st = check_segs("embed_fwd", segs, tokens)) return st;
   for (uint32_t r = 0; r < segs.n; ++r) REQ(segs.seq[r] > 0, "embed_fwd: empty sequence");
-  hipLaunchKernelGGL(embed_fwd_segs_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, segs, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, d, c);
+  hipLaunchKernelGGL(embed_fwd_segs_kernel, dim3((tokens + 3) / 4), dim3(256), 0, s, segs, (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x, tokens, d, vocab, c);
   return check_launch("embed_fwd");
 }
 
-sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t tokens, uint32_t d, hipStream_t s, const KCtl& c) {
-  REQ(ids && dx && dwte && tokens > 0, "embed_bwd: null or empty");
+sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t vocab, uint32_t tokens, uint32_t d, hipStream_t s, const KCtl& c) {
+  REQ(ids && dx && dwte && tokens > 0 && vocab > 0, "embed_bwd: null or empty");
   REQ(d <= 256 * EB_MAXC, "embed_bwd: d must be <= 4096");
-  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(tokens), dim3(256), 0, s, ids, (const bf16_t*)dx, (bf16_t*)dwte, tokens, d, c);
+  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(tokens), dim3(256), 0, s, ids, (const bf16_t*)dx, (bf16_t*)dwte, tokens, d, vocab, c);
   return check_launch("embed_bwd_wte");
 }
 

@@ -250,18 +250,32 @@ def test_embedding_fwd_bwd():
     wte, wpe, dx = rnd(29, vocab, d), rnd(30, seq, d), rnd(31, tokens, d)
     I, WTE, WPE, DX = i32(ids), bf(wte), bf(wpe), bf(dx)
     x = torch.zeros((tokens, d), device=DEV, dtype=torch.bfloat16)
-    S.sif_k_embed_fwd(I, WTE, WPE, x, tokens, seq, d)
+    S.sif_k_embed_fwd(I, WTE, WPE, x, vocab, tokens, seq, d)
     assert_bf16_close(up(x), q(wte)[ids] + q(wpe)[np.arange(tokens) % seq], "embed")
     head = rnd(32, vocab, d)
     dwte, dwpe = bf(head), torch.zeros((seq, d), device=DEV, dtype=torch.bfloat16)
-    S.sif_k_embed_bwd(I, DX, dwte, dwpe, tokens, seq, d)
+    S.sif_k_embed_bwd(I, DX, dwte, dwpe, vocab, tokens, seq, d)
     scat = np.zeros((vocab, d))
     np.add.at(scat, ids, q(dx))
     assert_bf16_close(up(dwte), q(head) + scat, "dwte")
     assert_bf16_close(up(dwpe), q(dx).reshape(-1, seq, d).sum(0), "dwpe")
     again = bf(head)
-    S.sif_k_embed_bwd(I, DX, again, dwpe, tokens, seq, d)
+    S.sif_k_embed_bwd(I, DX, again, dwpe, vocab, tokens, seq, d)
     assert torch.equal(again, dwte)                 # fixed summation order
+    # ids outside the vocabulary are taken as the nearest valid id: nothing outside the table is touched
+    wild = ids.copy()
+    wild[3], wild[40], wild[41] = -5, vocab, 2 ** 31 - 1
+    near = np.clip(wild.astype(np.int64), 0, vocab - 1)
+    S.sif_k_embed_fwd(i32(wild), WTE, WPE, x, vocab, tokens, seq, d)
+    assert_bf16_close(up(x), q(wte)[near] + q(wpe)[np.arange(tokens) % seq], "embed, wild ids")
+    guard = torch.full(((vocab + 4) * d,), 3.0, device=DEV, dtype=torch.bfloat16)
+    tab = guard[2 * d:(2 + vocab) * d].view(vocab, d)
+    tab.copy_(bf(head))
+    S.sif_k_embed_bwd(i32(wild), DX, tab, dwpe, vocab, tokens, seq, d)
+    scat = np.zeros((vocab, d))
+    np.add.at(scat, near, q(dx))
+    assert_bf16_close(up(tab), q(head) + scat, "dwte, wild ids")
+    assert bool((guard[:2 * d] == 3.0).all()) and bool((guard[(2 + vocab) * d:] == 3.0).all())
 
 
 @pytest.mark.parametrize("tokens,vocab", [(5, 37), (64, 50257), (3, 8)])
