@@ -256,22 +256,57 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   // Block -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
   // every XCD a contiguous run of tiles, and walk each run in bands of 8 tile rows, so that the tiles an XCD works
   // on at one time share their A and B panels in that XCD's L2.
-  uint32_t tile_m, tile_n;
-  {
-    const uint32_t total = p.tiles_m * p.tiles_n, pid = blockIdx.x;
-    const uint32_t per = (total + 7) / 8, tall = (total % 8) ? (total % 8) : 8, xcd = pid % 8, local = pid / 8;
+  const uint32_t total_tiles = p.tiles_m * p.tiles_n;
+  auto tile_of = [&](uint32_t pid, uint32_t& tm, uint32_t& tn) {
+    const uint32_t per = (total_tiles + 7) / 8, tall = (total_tiles % 8) ? (total_tiles % 8) : 8, xcd = pid % 8, local = pid / 8;
     const uint32_t logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
     const uint32_t width = 8 * p.tiles_n, group = logical / width, first = group * 8;
     const uint32_t gsz = min(p.tiles_m - first, 8u), in = logical % width;
-    tile_m = first + in % gsz;
-    tile_n = in / gsz;
+    tm = first + in % gsz;
+    tn = in / gsz;
+  };
+  const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
+  const bf16_t* A = p.a + bo * p.a_so + bi * p.a_si;
+  const bf16_t* B = p.b + bo * p.b_so + bi * p.b_si;
+  // The configuration without ragged tiles is launched with one block per CU that works through tiles one after the
+  // other: wavefronts, LDS and the prologue are set up once, the first operand tiles of the next output tile are
+  // fetched while the current one's epilogue runs, and the epilogue's stores drain under the next main loop.  The
+  // other configuration is launched with one block per tile and passes through this loop once.
+  // Which tile comes next: a monitored launch hands its tiles out through counters in the stream's record, one per
+  // XCD (a block takes the tiles of its own XCD's run in order and, when that run is exhausted, helps the others), so
+  // that a block that starts late - its CU was held by a kernel of the other stream - simply takes fewer tiles; with a
+  // fixed share per block the whole launch would wait for the late one.  An unmonitored launch has no record: every
+  // block takes each gridDim.x-th tile (a stride that is a multiple of 8 keeps it on its XCD's run).
+  __shared__ uint32_t s_next;
+  const bool dynamic = !EDGE && ctl.rec != nullptr && gridDim.z == 1 && gridDim.x < total_tiles;
+  const uint32_t my_x = blockIdx.x & 7u;
+  auto tiles_of_xcd = [&](uint32_t x) { return x < total_tiles ? (total_tiles - x + 7u) / 8u : 0u; };
+  auto steal = [&]() -> uint32_t {            // one thread: a tile of any XCD's run that still has some, else kNone
+    for (uint32_t r = 0; r < 8; ++r) {
+      const uint32_t x = (my_x + r) & 7u, cnt = tiles_of_xcd(x);
+      uint32_t* ctr = &ctl.rec->tile_next[x * 32u];
+      if (ld_relaxed(ctr) >= cnt) continue;
+      const uint32_t l = atomicAdd(ctr, 1u);
+      if (l < cnt) return l * 8u + x;
+    }
+    return kNone;
+  };
+  uint32_t pid = blockIdx.x;
+  if (dynamic) {
+    if (threadIdx.x == 0) s_next = steal();
+    __syncthreads();
+    pid = s_next;
   }
+  DmaStream<ALAY, BM, THREADS> ta(A, p.lda, 0, p.m, 0);
+  DmaStream<BLAY, BN, THREADS> tb(B, p.ldb, 0, p.n, 0);
+  bool fetched_ahead = false;
+  while (pid < total_tiles) {
+  uint32_t next_pid = kNone;
+  uint32_t tile_m, tile_n;
+  tile_of(pid, tile_m, tile_n);
   const uint32_t m0 = tile_m * BM, n0 = tile_n * BN;
   const bool skip = (p.epi & SIF_EPI_CAUSAL_SKIP) && n0 > m0 + BM - 1;
   if (!skip) {
-    const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
-    const bf16_t* A = p.a + bo * p.a_so + bi * p.a_si;
-    const bf16_t* B = p.b + bo * p.b_so + bi * p.b_si;
     uint32_t k_begin = 0, k_end = p.k;
     if (p.k_limit != 0) k_end = min(p.k, p.k_limit - bi * p.k);      // slices of one long K: the last may be shorter
     if (p.k_causal == 1) k_end = min(p.k, m0 + BM);
@@ -336,16 +371,21 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // The loop takes two K steps per trip (the register sets and LDS buffers alternate by name) and has no exit in
     // its middle, so that the accumulators stay in the same registers throughout; an odd last tile is done after it.
     const uint32_t nt = (k_end - k_begin + BK - 1) / BK;
+    uint32_t l_own = 0;
     // without EDGE the launcher guarantees that every tile is interior
     const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
     if (interior) {
       // tile t+1 is fetched into the other pair of buffers while tile t is multiplied; the other block of the CU
       // covers what the fetch latency exceeds one K step
-      DmaStream<ALAY, BM, THREADS> ta(A, p.lda, m0, p.m, k_begin);
-      DmaStream<BLAY, BN, THREADS> tb(B, p.ldb, n0, p.n, k_begin);
-      ta.next(sA0); tb.next(sB0);
+      if (!fetched_ahead) {
+        ta = DmaStream<ALAY, BM, THREADS>(A, p.lda, m0, p.m, k_begin);
+        tb = DmaStream<BLAY, BN, THREADS>(B, p.ldb, n0, p.n, k_begin);
+        ta.next(sA0); tb.next(sB0);
+      }
       wait_fetches();
       __syncthreads();
+      // the block's next tile is asked for now; the answer is looked at when this tile's main loop is over
+      if (dynamic && threadIdx.x == 0) l_own = atomicAdd(&ctl.rec->tile_next[my_x * 32u], 1u);
       for (uint32_t t = 0; t + 2 <= nt; t += 2) {
         ta.next(sA1); tb.next(sB1);
         compute(sA0, sB0, Int<FETCHES>());
@@ -388,8 +428,26 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // the first.  Accumulator element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
     // Chunk c (four floats) of staging row r lives at c ^ (8*((r/4)%2) | r%2): the two half-wavefronts of a store
     // and the eight rows of a load then fall on different banks.
+    if (!EDGE && threadIdx.x == 0) {
+      uint32_t np = kNone;
+      if (dynamic) np = l_own < tiles_of_xcd(my_x) ? l_own * 8u + my_x : steal();
+      else if (pid + gridDim.x < total_tiles) np = pid + gridDim.x;
+      s_next = np;
+    }
     __syncthreads();
-    float* sW = reinterpret_cast<float*>(wave < WM * WN / 2 ? sA0 : sA1) + (wave % (WM * WN / 2)) * (32 * WCOLS);
+    // the block's next output tile: its first operand tiles travel into sA0 / sB0 while this epilogue runs (the staging
+    // area below is sA1 / sB1, which the next main loop fills only after its first barrier)
+    fetched_ahead = false;
+    if (!EDGE) next_pid = s_next;
+    if (!EDGE && next_pid < total_tiles) {
+      uint32_t nm, nn;
+      tile_of(next_pid, nm, nn);
+      ta = DmaStream<ALAY, BM, THREADS>(A, p.lda, nm * BM, p.m, 0);
+      tb = DmaStream<BLAY, BN, THREADS>(B, p.ldb, nn * BN, p.n, 0);
+      ta.next(sA0); tb.next(sB0);
+      fetched_ahead = true;
+    }
+    float* sW = reinterpret_cast<float*>(wave < WM * WN / 2 ? sA1 : sB1) + (wave % (WM * WN / 2)) * (32 * WCOLS);
     const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
     const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
     const float bias8[8] = {bflo(bias_q.x), bfhi(bias_q.x), bflo(bias_q.y), bfhi(bias_q.y), bflo(bias_q.z), bfhi(bias_q.z), bflo(bias_q.w), bfhi(bias_q.w)};
@@ -480,10 +538,38 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       __builtin_amdgcn_wave_barrier();
     }
   }
+  pid = next_pid;
+  }
   kernel_end(ctl, true);
 }
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// 256x256 tiles (one block of eight wavefronts per CU, 128x64 per wavefront: a quarter fewer LDS reads and half the
+// global fetches per MFMA); they need whole K steps and no causal skipping
+bool gemm_can_use_big_tiles(const sif_gemm_args& a) {
+  const bool causal = a.k_causal != 0 || (a.epilogue & SIF_EPI_CAUSAL_SKIP);
+  return !causal && (a.k % BK) == 0 && a.k_limit == 0;
+}
+
+// Which configuration is faster follows a two-line model fitted to measurements on gfx950 (time of one round of
+// tiles over the chip, us, K in steps of 64): 128x128, two blocks per CU: 1.0 + 1.19 steps, and a CU that holds a
+// single block runs it faster, so a partly filled round costs about its share (never less than 0.85 of a round);
+// 256x256, one persistent block per CU: 4.0 + 1.75 steps for four times the outputs per block, and a partly filled
+// last round costs a whole one.  (65536 x 2304 x 768: 233 against 289 us, 65536 x 768 x 768: 101 against 122,
+// 65536 x 3072 x 768 + GELU: 351 against 424, 65536 x 768 x 3072: 295 against 360, 8192 x 50304 x 768: 690 against
+// 892, 8192^3: 864 against 1044; the other way round 8192 x 2304 x 768: 47 against 43, 8192 x 3072 x 768: 55 against 52.)
+bool gemm_big_tiles(const sif_gemm_args& a) {
+  if (a.tile == 256) return true;
+  if (a.tile == 128 || !gemm_can_use_big_tiles(a)) return false;
+  const uint64_t batches = (uint64_t)a.batch_outer * a.batch_inner;
+  const uint64_t tiles256 = (uint64_t)((a.m + 255) / 256) * ((a.n + 255) / 256) * batches;
+  const uint64_t tiles128 = (uint64_t)((a.m + 127) / 128) * ((a.n + 127) / 128) * batches;
+  const double steps = (double)(a.k / BK);
+  const double t128 = (1.0 + 1.19 * steps) * std::max(0.85, (double)tiles128 / 512.0);
+  const double t256 = (4.0 + 1.75 * steps) * (double)((tiles256 + 255) / 256);
+  return t256 < t128;
+}
 
 sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KCtl& ctl) {
   if (a == nullptr || a->struct_size != sizeof(sif_gemm_args)) return fail(SIF_E_INVAL, "gemm: bad args struct");
@@ -508,26 +594,10 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
     if ((a->ldc & 7) || ((a->c_stride_outer | a->c_stride_inner) & 7)) return fail(SIF_E_INVAL, "gemm: ldc and the output batch strides must be multiples of 8 when n is");
     if ((a->bias_dev && !aligned16(a->bias_dev)) || (a->res_dev && !aligned16(a->res_dev)) || (a->aux_dev && !aligned16(a->aux_dev))) return fail(SIF_E_INVAL, "gemm: bias, residual and aux must be 16-byte aligned");
   }
-  // 256x256 tiles (one block of eight wavefronts per CU, 128x64 per wavefront: a quarter fewer LDS reads and half
-  // the global fetches per MFMA); they need whole K steps and no causal skipping
-  const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
-  const bool causal = a->k_causal != 0 || (a->epilogue & SIF_EPI_CAUSAL_SKIP);
-  const uint64_t tiles256 = (uint64_t)((a->m + 255) / 256) * ((a->n + 255) / 256) * batches;
-  const bool can_big = !causal && (a->k % BK) == 0 && a->k_limit == 0;
   if (a->tile != 0 && a->tile != 128 && a->tile != 256) return fail(SIF_E_INVAL, "gemm: tile must be 0, 128 or 256");
-  if (a->tile == 256 && !can_big) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
-  // Which configuration is faster follows a two-line model fitted to measurements on gfx950 (time of one round of
-  // tiles over the chip, us, K in steps of 64): 128x128, two blocks per CU: 1.0 + 1.19 steps, and a CU that holds a
-  // single block runs it faster, so a partly filled round costs about its share (never less than 0.85 of a round);
-  // 256x256, one block per CU: 8.7 + 1.53 steps for four times the outputs per block, nothing overlaps its prologue
-  // and epilogue, and a partly filled last round costs a whole one.  (16384 x 3072 x 768: 82 against 94 us, 8192 x
-  // 50304 x 768: 753 against 1017, 16384 x 768 x 3072: 80 against 85, 8192^3: 900 against 1150; the other way round
-  // 16384 x 2304 x 768: 78 against 73, 8192 x 768 x 3072: 75 against 51, 8192 x 768 x 50304: 1221 against 830.)
-  const uint64_t tiles128 = (uint64_t)((a->m + 127) / 128) * ((a->n + 127) / 128) * batches;
-  const double steps = (double)(a->k / BK);
-  const double t128 = (1.0 + 1.19 * steps) * std::max(0.85, (double)tiles128 / 512.0);
-  const double t256 = (8.7 + 1.53 * steps) * (double)((tiles256 + 255) / 256);
-  const bool big = a->tile == 256 || (a->tile == 0 && can_big && t256 < t128);
+  if (a->tile == 256 && !gemm_can_use_big_tiles(*a)) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
+  const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
+  const bool big = gemm_big_tiles(*a);
   const uint32_t bm = big ? 256 : 128, bn = bm;
   GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;
@@ -539,7 +609,18 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   p.c_so = a->c_stride_outer; p.c_si = a->c_stride_inner; p.alpha = a->alpha;
   p.tiles_n = (a->n + bn - 1) / bn; p.tiles_m = (a->m + bm - 1) / bm;
   if (batches > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
-  dim3 grid(p.tiles_m * p.tiles_n, 1, (uint32_t)batches);
+  // 256x256 tiles: one block per CU, each working through every (number of CUs)-th tile; a stride that is a multiple of
+  // 8 keeps a block on the tiles of its own XCD
+  uint32_t grid_x = p.tiles_m * p.tiles_n;
+  if (big && batches == 1) {
+    static const uint32_t cus = [] {
+      int dev = 0, n = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+      return (uint32_t)(n / 8 * 8);
+    }();
+    if (grid_x > cus) grid_x = cus;
+  }
+  dim3 grid(grid_x, 1, (uint32_t)batches);
   typedef void (*gemm_kern_fn)(GemmP, KCtl);
   static const gemm_kern_fn table[2][2] = {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>},
                                            {gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>}};

@@ -16,6 +16,9 @@ inline KCtl no_ctl() { KCtl c{}; return c; }
 
 // Internal launchers: same argument checks as the public sif_k_* entry points, plus the monitor control block.
 sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t s, const KCtl& c);
+// whether the product may run, and whether it will run, on 256x256 tiles (else 128x128)
+bool gemm_can_use_big_tiles(const sif_gemm_args& a);
+bool gemm_big_tiles(const sif_gemm_args& a);
 sif_status launch_gemm_f32(const float* a, int64_t a_sm, int64_t a_sk, const float* b, int64_t b_sk, int64_t b_sn,
                            float* c, int64_t ldc, uint32_t m, uint32_t n, uint32_t k, uint32_t epi, const float* bias,
                            float* aux, hipStream_t s, const KCtl& ctl);

@@ -105,6 +105,7 @@ __global__ __launch_bounds__(64) void step_marker_kernel(StreamRec* rec, Mirror*
 // waiting for the gate decision leaves them short of their full count.
 __global__ __launch_bounds__(64) void reset_skip_kernel(StreamRec* rec, Mirror* mir, uint32_t epoch) {
   st_relaxed(&rec->done_sub[threadIdx.x * 32u], 0u);
+  if (threadIdx.x < 8) st_relaxed(&rec->tile_next[threadIdx.x * 32u], 0u);
   __syncthreads();
   if (threadIdx.x != 0) return;
   st_relaxed(&rec->done_top, 0u);

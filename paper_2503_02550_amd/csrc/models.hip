@@ -139,8 +139,8 @@ static sif_gemm_args gemm_row_range(const sif_gemm_args& g, uint32_t r0, uint32_
 }
 
 uint32_t gemm_round_rows(const sif_gemm_args& a) {
-  // wide products run on 256x256 tiles, one per CU; narrow ones on 128x128 tiles, two per CU
-  if (a.n >= 2048) return 256 * std::max(1u, 256u / ((a.n + 255) / 256));
+  // 256x256 tiles run one per CU, 128x128 tiles two per CU
+  if (gemm_big_tiles(a)) return 256 * std::max(1u, 256u / ((a.n + 255) / 256));
   return 128 * std::max(1u, 512u / ((a.n + 127) / 128));
 }
 

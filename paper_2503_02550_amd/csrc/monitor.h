@@ -37,6 +37,9 @@ struct alignas(128) StreamRec {     // one per stream, in HBM
   // completion counters of the kernel currently running on this stream (see kernel_end)
   uint32_t done_top;
   alignas(128) uint32_t done_sub[64 * 32];
+  // work counters of the kernel currently running on this stream (kernels that hand out their tiles dynamically: one
+  // counter per XCD, each on a cache line of its own); zero between kernels, re-armed like the completion counters
+  alignas(128) uint32_t tile_next[8 * 32];
 };
 
 struct alignas(32) Slot {           // one per launch, ring indexed by launch number
@@ -226,6 +229,8 @@ __device__ __forceinline__ void kernel_end(const KCtl& c, bool ran) {
   const uint32_t subs = total < 64u ? total : 64u;
   if (atomicAdd(&c.rec->done_top, 1u) + 1u != subs) return;
   c.rec->done_top = 0;
+#pragma unroll
+  for (int x = 0; x < 8; ++x) st_relaxed(&c.rec->tile_next[x * 32], 0u);
   Mirror* m = c.mir;
   StreamRec* r = c.rec;
   const uint64_t t1 = now_ticks();
