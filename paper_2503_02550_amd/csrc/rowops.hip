@@ -2,12 +2,24 @@
 // cross entropy, column sums, SGD.  They are bound by HBM traffic, so each reads its operands once with 16-byte
 // accesses, keeps fp32 statistics in registers / LDS, and uses fixed-order reductions (no float atomics) so
 // that results are bit-identical from run to run and independent of what else shares the GPU.
+#include <algorithm>
+
 #include "common.h"
 #include "launch.h"
 
 namespace sif {
 
 constexpr float kLnEps = 1e-5f;
+
+// compute units of the current device (256 on MI355X), looked up once
+static uint32_t n_cus() {
+  static const uint32_t n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) v = 256;
+    return (uint32_t)v;
+  }();
+  return n;
+}
 
 __device__ __forceinline__ void unpack8(const uint4& v, float (&f)[8]) {
   f[0] = bflo(v.x); f[1] = bfhi(v.x); f[2] = bflo(v.y); f[3] = bfhi(v.y);
@@ -18,9 +30,11 @@ __device__ __forceinline__ uint4 pack8(const float (&f)[8]) {
 }
 
 // ---------------------------------------------------------------------------------------------- LayerNorm
-// One wavefront per row, 4 rows per block.  MAXV > 0: the row (at most MAXV vectors of 8 columns per lane) is read
-// once and kept in registers for the three passes (mean, variance, output); MAXV = 0: any width, three reads.
-// Both variants add in the same order, so they give the same bits.
+// One wavefront per row at a time, 4 wavefronts per block; a wavefront works through every (number of wavefronts)-th
+// row.  MAXV > 0: the row (at most MAXV vectors of 8 columns per lane) is read once and kept in registers for the
+// three passes (mean, variance, output), the next row's loads are issued before the current row is reduced so that
+// they travel meanwhile, and the gains and offsets are read once per wavefront; MAXV = 0: any width, three reads per
+// row.  Both variants add in the same order, so they give the same bits.
 template <int MAXV>
 __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ g,
                                                             const bf16_t* __restrict__ b, bf16_t* __restrict__ y,
@@ -28,26 +42,37 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __rest
                                                             uint32_t rows, uint32_t d, RowSegs segs, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
   // the row is the same for the whole wavefront: as a scalar it can index the segment table in the kernel arguments
-  const uint32_t row = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6)), lane = threadIdx.x & 63, nv = d >> 3;
-  if (row < rows) {
-    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
-    uint4* yr = reinterpret_cast<uint4*>(y + (size_t)row * d);
+  const uint32_t lane = threadIdx.x & 63, nv = d >> 3, n_waves = gridDim.x * 4;
+  uint32_t row = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+  auto out_row = [&](uint32_t r_) -> uint4* {
     if (segs.n != 0) {
       uint32_t r = 0;
-      while (r + 1 < segs.n && row >= segs.row0[r + 1]) ++r;
-      yr = reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(segs.ptr[r]) + (size_t)(row - segs.row0[r]) * d);
+      while (r + 1 < segs.n && r_ >= segs.row0[r + 1]) ++r;
+      return reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(segs.ptr[r]) + (size_t)(r_ - segs.row0[r]) * d);
     }
-    float s = 0.f, f[8];
-    if constexpr (MAXV > 0) {
-      uint4 cx[MAXV], cg[MAXV], cb[MAXV];
+    return reinterpret_cast<uint4*>(y + (size_t)r_ * d);
+  };
+  if constexpr (MAXV > 0) {
+    uint4 cx[MAXV], nx[MAXV], cg[MAXV], cb[MAXV];
+    auto fetch = [&](uint4 (&dst)[MAXV], uint32_t r_) {
+      const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)r_ * d);
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t) dst[t] = (lane + 64 * t < nv) ? xr[lane + 64 * t] : make_uint4(0, 0, 0, 0);
+    };
+    if (row < rows) {
+      fetch(cx, row);
 #pragma unroll
       for (int t = 0; t < MAXV; ++t) {
         const uint32_t v = lane + 64 * t;
-        const bool in = v < nv;
-        cx[t] = in ? xr[v] : make_uint4(0, 0, 0, 0);
-        cg[t] = in ? reinterpret_cast<const uint4*>(g)[v] : make_uint4(0, 0, 0, 0);
-        cb[t] = in ? reinterpret_cast<const uint4*>(b)[v] : make_uint4(0, 0, 0, 0);
+        cg[t] = v < nv ? reinterpret_cast<const uint4*>(g)[v] : make_uint4(0, 0, 0, 0);
+        cb[t] = v < nv ? reinterpret_cast<const uint4*>(b)[v] : make_uint4(0, 0, 0, 0);
       }
+    }
+    while (row < rows) {
+      const uint32_t next = __builtin_amdgcn_readfirstlane(row + n_waves);
+      if (next < rows) fetch(nx, next);
+      uint4* yr = out_row(row);
+      float s = 0.f, f[8];
 #pragma unroll
       for (int t = 0; t < MAXV; ++t)
         if (lane + 64 * t < nv) { unpack8(cx[t], f); for (int i = 0; i < 8; ++i) s += f[i]; }
@@ -66,7 +91,15 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const bf16_t* __rest
           yr[lane + 64 * t] = pack8(o);
         }
       if (lane == 0 && mean_out != nullptr) { mean_out[row] = mean; rstd_out[row] = rstd; }
-    } else {
+#pragma unroll
+      for (int t = 0; t < MAXV; ++t) cx[t] = nx[t];
+      row = next;
+    }
+  } else {
+    for (; row < rows; row = __builtin_amdgcn_readfirstlane(row + n_waves)) {
+      const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
+      uint4* yr = out_row(row);
+      float s = 0.f, f[8];
       for (uint32_t v = lane; v < nv; v += 64) { unpack8(xr[v], f); for (int i = 0; i < 8; ++i) s += f[i]; }
       const float mean = wave_sum(s) / (float)d;
       float q = 0.f;
@@ -549,54 +582,145 @@ __global__ __launch_bounds__(1024) void xent_kernel(bf16_t* __restrict__ logits,
   kernel_end(ctl, true);
 }
 
-// The same with the row kept in registers (at most MAXV vectors of 8 columns per thread) instead of LDS: several
-// blocks fit on a CU, so one row's reductions overlap the others' loads and stores.
+// The same with the row kept in registers (at most MAXV vectors of 8 columns per thread) instead of LDS, as fp32:
+// the kernel is bound by its arithmetic as much as by memory (two exponentials and two dozen instructions per logit
+// when written naively), so every exponential is taken once and kept, whole vectors inside the vocabulary take a path
+// without per-column checks, and the target's column is corrected afterwards instead of being compared with every
+// column.  Two blocks of 512 threads per CU: one row's reductions overlap the other's loads and stores.  Per row the
+// values and the order of the additions are those of xent_kernel, so the results have the same bits.
 template <int MAXV, int THREADS>
-__global__ __launch_bounds__(THREADS) void xent_reg_kernel(bf16_t* __restrict__ logits, const int32_t* __restrict__ targets,
+__global__ __launch_bounds__(THREADS, (THREADS <= 512 ? 2 : 1)) void xent_reg_kernel(bf16_t* __restrict__ logits, const int32_t* __restrict__ targets,
                                                         float* __restrict__ loss, uint32_t tokens, uint32_t vocab, uint32_t ld, KCtl ctl) {
   __shared__ float sred[16];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
-  const uint32_t t = blockIdx.x, nv = ld >> 3;
+  const uint32_t t = blockIdx.x, nv = ld >> 3, nfull = vocab >> 3;      // nfull: vectors that lie wholly inside the vocabulary
   uint4* gr = reinterpret_cast<uint4*>(logits + (size_t)t * ld);
   const int32_t tg = (int32_t)clamp_id(targets[t], vocab);
   const float at_target = bf2f(logits[(size_t)t * ld + tg]);      // read before anything is written back
-  uint4 row[MAXV];
+  float e[MAXV][8];
+  {
+    uint4 raw[MAXV];
 #pragma unroll
-  for (int k = 0; k < MAXV; ++k) {
-    const uint32_t v = threadIdx.x + k * THREADS;
-    row[k] = v < nv ? gr[v] : make_uint4(0, 0, 0, 0);
+    for (int k = 0; k < MAXV; ++k) {
+      const uint32_t v = threadIdx.x + k * THREADS;
+      raw[k] = v < nv ? gr[v] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+      const uint32_t v = threadIdx.x + k * THREADS;
+      unpack8(raw[k], e[k]);
+      if (v >= nfull) {                  // padding columns (and vectors past the row) count as minus infinity: exp gives 0
+#pragma unroll
+        for (int i = 0; i < 8; ++i) if (v >= nv || v * 8 + i >= vocab) e[k][i] = -INFINITY;
+      }
+    }
   }
   float mx = -INFINITY;
 #pragma unroll
-  for (int k = 0; k < MAXV; ++k) {
-    const uint32_t v = threadIdx.x + k * THREADS;
-    float f[8];
-    unpack8(row[k], f);
-    if (v < nv) for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) mx = fmaxf(mx, f[i]);
-  }
+  for (int k = 0; k < MAXV; ++k)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mx = fmaxf(mx, e[k][i]);
   mx = block_max(mx, sred);
   float sum = 0.f;
 #pragma unroll
-  for (int k = 0; k < MAXV; ++k) {
-    const uint32_t v = threadIdx.x + k * THREADS;
-    float f[8];
-    unpack8(row[k], f);
-    if (v < nv) for (int i = 0; i < 8; ++i) if (v * 8 + i < vocab) sum += __expf(f[i] - mx);
-  }
+  for (int k = 0; k < MAXV; ++k)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { e[k][i] = __expf(e[k][i] - mx); sum += e[k][i]; }
   sum = block_sum(sum, sred);
   const float inv = 1.0f / sum, invn = 1.0f / (float)tokens;
   if (threadIdx.x == 0) loss[t] = (mx + __logf(sum)) - at_target;
+  const uint32_t v_tg = (uint32_t)tg >> 3, i_tg = (uint32_t)tg & 7u;
 #pragma unroll
   for (int k = 0; k < MAXV; ++k) {
     const uint32_t v = threadIdx.x + k * THREADS;
     if (v >= nv) continue;
-    float f[8], o[8];
-    unpack8(row[k], f);
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t c = v * 8 + i;
-      o[i] = c < vocab ? (__expf(f[i] - mx) * inv - (c == (uint32_t)tg ? 1.f : 0.f)) * invn : 0.f;
+    float o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = e[k][i] * inv * invn;
+    if (v == v_tg) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) if ((uint32_t)i == i_tg) o[i] = (e[k][i] * inv - 1.f) * invn;
     }
     gr[v] = pack8(o);
+  }
+  kernel_end(ctl, true);
+}
+
+// The register variant as one block per CU that works through rows one after the other: the next row's loads are
+// issued before the current row is reduced and travel meanwhile, the current row's stores drain during the next row's
+// reductions.  A block's first two rows are fixed (blockIdx.x and blockIdx.x + gridDim.x); a monitored launch hands out
+// the others through a counter in the stream's record, asked for one row ahead so that the answer is there when it
+// is needed: a block that starts late (its CU was held by a kernel of the other stream) then simply takes fewer rows.
+// Same values, same order of additions per row.
+template <int MAXV, int THREADS>
+__global__ __launch_bounds__(THREADS, 1) void xent_stream_kernel(bf16_t* __restrict__ logits, const int32_t* __restrict__ targets,
+                                                                 float* __restrict__ loss, uint32_t tokens, uint32_t vocab, uint32_t ld, KCtl ctl) {
+  __shared__ float sred[16];
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t nv = ld >> 3, nfull = vocab >> 3;
+  const float invn = 1.0f / (float)tokens;
+  uint4 raw[MAXV];
+  auto fetch = [&](uint32_t t_) {
+    const uint4* src = reinterpret_cast<const uint4*>(logits + (size_t)t_ * ld);
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+      const uint32_t v = threadIdx.x + k * THREADS;
+      raw[k] = v < nv ? src[v] : make_uint4(0, 0, 0, 0);
+    }
+  };
+  __shared__ uint32_t s_row;
+  const bool dynamic = ctl.rec != nullptr;
+  uint32_t t = blockIdx.x, next = blockIdx.x + gridDim.x;
+  if (t < tokens) fetch(t);
+  while (t < tokens) {
+    uint4* gr = reinterpret_cast<uint4*>(logits + (size_t)t * ld);
+    const int32_t tg = (int32_t)clamp_id(targets[t], vocab);
+    const float at_target = bf2f(logits[(size_t)t * ld + tg]);      // read before anything of this row is written back
+    uint32_t asked = 0;
+    if (dynamic && threadIdx.x == 0) asked = atomicAdd(&ctl.rec->tile_next[0], 1u);      // the row after the next one
+    float e[MAXV][8];
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+      const uint32_t v = threadIdx.x + k * THREADS;
+      unpack8(raw[k], e[k]);
+      if (v >= nfull) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) if (v >= nv || v * 8 + i >= vocab) e[k][i] = -INFINITY;
+      }
+    }
+    if (next < tokens) fetch(next);                                   // the raw registers are free again: next row's loads go out now
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) mx = fmaxf(mx, e[k][i]);
+    mx = block_max(mx, sred);
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { e[k][i] = __expf(e[k][i] - mx); sum += e[k][i]; }
+    if (threadIdx.x == 0) s_row = dynamic ? 2u * gridDim.x + asked : next + gridDim.x;
+    sum = block_sum(sum, sred);                                       // (its barriers also publish s_row)
+    const uint32_t after = s_row;
+    const float inv = 1.0f / sum;
+    if (threadIdx.x == 0) loss[t] = (mx + __logf(sum)) - at_target;
+    const uint32_t v_tg = (uint32_t)tg >> 3, i_tg = (uint32_t)tg & 7u;
+#pragma unroll
+    for (int k = 0; k < MAXV; ++k) {
+      const uint32_t v = threadIdx.x + k * THREADS;
+      if (v >= nv) continue;
+      float o[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = e[k][i] * inv * invn;
+      if (v == v_tg) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) if ((uint32_t)i == i_tg) o[i] = (e[k][i] * inv - 1.f) * invn;
+      }
+      gr[v] = pack8(o);
+    }
+    t = next;
+    next = after;
   }
   kernel_end(ctl, true);
 }
@@ -708,7 +832,9 @@ sif_status launch_layernorm_fwd(const void* x, const void* g, const void* b, voi
     if (sif_status st = check_segs("layernorm_fwd", *segs, rows)) return st;
     sg = *segs;
   }
-#define LNF(V) hipLaunchKernelGGL((layernorm_fwd_kernel<V>), dim3((rows + 3) / 4), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, \
+  // at most eight blocks of four wavefronts per CU: every wavefront then has a row in flight while it works on another
+  const uint32_t blocks = std::min<uint32_t>((rows + 3) / 4, 8u * n_cus());
+#define LNF(V) hipLaunchKernelGGL((layernorm_fwd_kernel<V>), dim3(blocks), dim3(256), 0, s, (const bf16_t*)x, (const bf16_t*)g, \
                                   (const bf16_t*)b, (bf16_t*)y, mean, rstd, rows, d, sg, c)
   if (d <= 1024) LNF(2); else if (d <= 2048) LNF(4); else LNF(0);
 #undef LNF
@@ -818,7 +944,12 @@ sif_status launch_xent(void* logits, const int32_t* targets, float* loss, uint32
                        hipStream_t s, const KCtl& c) {
   REQ(logits && targets && loss && tokens > 0 && vocab > 0, "xent: null or empty");
   REQ((ld & 7) == 0 && ld >= vocab && al16(logits), "xent: ld must be a multiple of 8 and >= vocab");
-  if (ld <= 8 * 1024 * 8) {          // the row fits in the registers of a block of 1024 threads, two such blocks per CU
+  if (ld <= 8 * 512 * 13) {          // the row fits in the registers of a block of 512 threads
+    // (344 us for 8192 x 50257 with one row per block, two blocks per CU; 328 us as one block per CU with two rows in flight)
+    hipLaunchKernelGGL((xent_stream_kernel<13, 512>), dim3(std::min<uint32_t>(tokens, n_cus())), dim3(512), 0, s, (bf16_t*)logits, targets, loss, tokens, vocab, ld, c);
+    return check_launch("xent");
+  }
+  if (ld <= 8 * 1024 * 8) {          // up to 65536 columns: 1024 threads, one block per CU
     hipLaunchKernelGGL((xent_reg_kernel<8, 1024>), dim3(tokens), dim3(1024), 0, s, (bf16_t*)logits, targets, loss, tokens, vocab, ld, c);
     return check_launch("xent");
   }

@@ -278,7 +278,7 @@ def test_embedding_fwd_bwd():
     assert bool((guard[:2 * d] == 3.0).all()) and bool((guard[(2 + vocab) * d:] == 3.0).all())
 
 
-@pytest.mark.parametrize("tokens,vocab", [(5, 37), (64, 50257), (3, 8)])
+@pytest.mark.parametrize("tokens,vocab", [(5, 37), (64, 50257), (3, 8), (4, 60001), (2, 70003)])
 def test_cross_entropy(tokens, vocab):
     ld = (vocab + 7) // 8 * 8
     lg = np.zeros((tokens, ld), np.float32)
@@ -295,6 +295,13 @@ def test_cross_entropy(tokens, vocab):
     got = up(L)
     assert_bf16_close(got[:, :vocab], rd, "dlogits", elem_slack=1e-3)
     assert np.all(got[:, vocab:] == 0)
+    # a target outside the vocabulary is taken as the nearest valid one
+    wild = tg.copy()
+    wild[0], wild[-1] = -3, vocab + 5
+    L2 = bf(lg)
+    S.sif_k_xent_fwd_bwd(L2, i32(wild), loss, tokens, vocab, ld)
+    _, rd2 = N.cross_entropy_mean(q(lg)[:, :vocab], np.clip(wild, 0, vocab - 1))
+    assert_bf16_close(up(L2)[:, :vocab], rd2, "dlogits, wild targets", elem_slack=1e-3)
 
 
 def test_sgd_and_mse_and_colsum_f32():
