@@ -98,7 +98,7 @@ def cpu_baseline(sample_batch):
 
 def kernel_mode(args):
     """One kernel through the C ABI: GEMM (M N K), fused attention forward (BATCH SEQ HEADS D_HEAD), LayerNorm forward
-    (ROWS D), cross entropy (TOKENS VOCAB).  Prints one JSON line with its time and rate."""
+    (ROWS D), cross entropy (TOKENS VOCAB), SGD update (N).  Prints one JSON line with its time and rate."""
     import torch
     import paper_2503_02550_amd as S
     dev = "cuda:0"
@@ -144,6 +144,17 @@ def kernel_mode(args):
         def run():
             S.sif_k_xent_fwd_bwd(logits, tg, loss, tokens, vocab, ld)
         flops, nbytes = 0.0, 4.0 * tokens * ld
+    elif args.kernel == "sgd":
+        # a streaming kernel of known traffic (6 B read and 6 B written per parameter): the reference that HBM byte
+        # counters are scaled by
+        n, = sh
+        master = torch.randn(n, device=dev)
+        grad = torch.randn(n, device=dev).to(torch.bfloat16)
+        work = torch.zeros(n, device=dev, dtype=torch.bfloat16)
+
+        def run():
+            S.sif_k_sgd_bf16(master, grad, work, n, 1e-6)
+        flops, nbytes = 0.0, 12.0 * n
     else:
         print(f"bench.py: unknown --kernel {args.kernel}", file=sys.stderr)
         sys.exit(2)
@@ -174,6 +185,7 @@ def main():
     ap.add_argument("--kernel-us-max", type=int, default=600, help="longest kernel the planner emits for the headline workload, us (its 4.98 ms bubble takes long kernels; configs[3] always uses 200)")
     ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 5)")
     ap.add_argument("--skip-concurrent", action="store_true", help="leave out the extra phases with concurrent filling and with binding tokens (profiles of the headline phase)")
+    ap.add_argument("--timed-region-last", action="store_true", help="end the headline phase with its timed collocated steps (no further steps with all GEMM variants timed, no second solo phase): in a kernel trace of the process the last dispatches are then those of the timed region")
     ap.add_argument("--feedback", action="store_true", help="headline phase with concurrent filling as well (kernels beside training within the allowance)")
     ap.add_argument("--feedback-eps-ppm", type=int, default=30000, help="concurrent filling: step time allowed above its running minimum, ppm")
     ap.add_argument("--online-feedback-eps-ppm", type=int, default=40000, help="the same allowance for the online run with concurrent filling")
@@ -185,8 +197,8 @@ def main():
                          "the tail of the exchange is a bubble (0 = the configuration's single exposed all-reduce)")
     ap.add_argument("--allow-serial-streams", action="store_true", help="for runs under a counter-collecting profiler, which serialises all kernels")
     ap.add_argument("--small", action="store_true", help="reduced shapes (development only; not a valid measurement)")
-    ap.add_argument("--kernel", default="", help="single-kernel mode: gemm | attn | layernorm | xent")
-    ap.add_argument("--shape", type=int, nargs="+", default=[], help="single-kernel mode: gemm M N K; attn BATCH SEQ HEADS D_HEAD; layernorm ROWS D; xent TOKENS VOCAB")
+    ap.add_argument("--kernel", default="", help="single-kernel mode: gemm | attn | layernorm | xent | sgd")
+    ap.add_argument("--shape", type=int, nargs="+", default=[], help="single-kernel mode: gemm M N K; attn BATCH SEQ HEADS D_HEAD; layernorm ROWS D; xent TOKENS VOCAB; sgd N")
     ap.add_argument("--tile", type=int, default=0)
     ap.add_argument("--a-layout", type=int, default=0, help="gemm: 0 A stored [M][K], 1 [K][M]")
     ap.add_argument("--b-layout", type=int, default=0, help="gemm: 0 B stored [N][K], 1 [K][N]")
@@ -381,19 +393,21 @@ def main():
         S.sif_profile_gemm(s.ctx, 0)
         prof = S.sif_profile_read(s.ctx)
         sched = trace_summary(s, K)
-        # all four GEMM variants, over a few more (untimed) collocated steps
-        S.sif_profile_gemm(s.ctx, 1)
-        run_steps(3)
-        s.sync()
-        S.sif_profile_gemm(s.ctx, 0)
-        prof_all = S.sif_profile_read(s.ctx)
-        # solo once more, after the collocated phase (whatever is still queued stays queued)
-        S.sif_set_collocate(s.ctx, 0)
-        run_steps(W)
-        s.sync()
-        S.sif_profile_gemm(s.ctx, 2)
-        solo_b = timed_steps(s, K, step)
-        S.sif_profile_gemm(s.ctx, 0)
+        prof_all, solo_b = prof, solo_a
+        if not args.timed_region_last:
+            # all four GEMM variants, over a few more (untimed) collocated steps
+            S.sif_profile_gemm(s.ctx, 1)
+            run_steps(3)
+            s.sync()
+            S.sif_profile_gemm(s.ctx, 0)
+            prof_all = S.sif_profile_read(s.ctx)
+            # solo once more, after the collocated phase (whatever is still queued stays queued)
+            S.sif_set_collocate(s.ctx, 0)
+            run_steps(W)
+            s.sync()
+            S.sif_profile_gemm(s.ctx, 2)
+            solo_b = timed_steps(s, K, step)
+            S.sif_profile_gemm(s.ctx, 0)
         fin = s.stats()
     solo_s = min(solo_a, solo_b)
 

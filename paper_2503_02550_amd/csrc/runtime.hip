@@ -513,7 +513,9 @@ static void barrier_main(sif_ctx* c) {
           if (rest_ns > ahead_ns) {
             const double avail_us = (double)(rest_ns - ahead_ns) / 1000.0 - 10.0;
             const uint32_t unit = gemm_round_rows(whole.gemm);
-            const double per_unit = whole.cost_us * unit / (double)whole.gemm.m;
+            // (a part is predicted a tenth longer than its share of the whole plus the fixed part of a launch, see
+            // split_gemm_rows: the part is sized so that this prediction, not the bare share, fits what is left)
+            const double per_unit = 1.1 * whole.cost_us * unit / (double)whole.gemm.m;
             if (whole.cost_us > avail_us && avail_us >= per_unit + 6.0) {
               const uint64_t rows_first = (uint64_t)((avail_us - 6.0) / per_unit) * unit;
               if (rows_first > 0 && rows_first < whole.gemm.m) {
