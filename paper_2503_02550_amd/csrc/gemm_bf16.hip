@@ -31,6 +31,16 @@ namespace sif {
 constexpr int BK = 64;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16 bytes of a result, stored with the non-temporal hint.  A product's output is written once and read by a later
+// kernel, and the chip's CUs write their tiles in bursts that exceed what the L2 takes in at once: stores that do not
+// claim L2 lines are acknowledged sooner (the wavefront waits for them at its next wait for a fetch), and they leave
+// the operand panels, which the tiles of an XCD share, in the L2.
+__device__ __forceinline__ void store_result16(void* p, const uint4& v) {
+  const u32x4 x = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(x, reinterpret_cast<u32x4*>(p));
+}
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct GemmP {
@@ -198,8 +208,7 @@ __device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uin
         const uint4 q = res_q;                // fetched before the staging pass
         v[0] += bflo(q.x); v[1] += bfhi(q.x); v[2] += bflo(q.y); v[3] += bfhi(q.y); v[4] += bflo(q.z); v[5] += bfhi(q.z); v[6] += bflo(q.w); v[7] += bfhi(q.w);
       }
-      *reinterpret_cast<uint4*>(reinterpret_cast<bf16_t*>(p.c) + idx) =
-          make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7]));
+      store_result16(reinterpret_cast<bf16_t*>(p.c) + idx, make_uint4(pack_bf2(v[0], v[1]), pack_bf2(v[2], v[3]), pack_bf2(v[4], v[5]), pack_bf2(v[6], v[7])));
     }
   } else {
     // ragged N (or an output slice that is not 16-byte aligned): one element at a time
@@ -221,6 +230,106 @@ __device__ __forceinline__ void gemm_epilogue8(const GemmP& p, size_t c_off, uin
   }
 }
 
+// Epilogue of one wavefront's (TI*32) x 64 part of an output tile, first row mw, first column nw.  The accumulators
+// pass, 32 rows at a time, through a staging area `sW` of the wavefront's own in LDS (8 KB) so that every global
+// access of the epilogue - bias, residual, auxiliary tensor, result - is a 16-byte vector along a row; no block-wide
+// barrier is needed.  Accumulator element r of lane l is row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32
+// tile.  Chunk c (four floats) of staging row r lives at c ^ (8*((r/4)%2) | r%2): the two half-wavefronts of a
+// store and the eight rows of a load then fall on different banks.  bias_q: the bias of columns nw + 8*(l%8)...
+template <int TI, int TJ>
+__device__ __forceinline__ void gemm_store_tile(const GemmP& p, floatx16 (&acc)[TI][TJ], float* sW, uint32_t mw, uint32_t nw, size_t c_off, const uint4& bias_q) {
+  constexpr int WCOLS = TJ * 32;
+  const uint32_t lane = threadIdx.x & 63;
+  const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
+  const float bias8[8] = {bflo(bias_q.x), bfhi(bias_q.x), bflo(bias_q.y), bfhi(bias_q.y), bflo(bias_q.z), bfhi(bias_q.z), bflo(bias_q.w), bfhi(bias_q.w)};
+  // Epilogues that read nothing but the bias (plain, bias, bias + GELU without the pre-activation output) are
+  // finished in the accumulator layout, where a lane's column is fixed, and staged as bf16: two vertically adjacent
+  // results share a 32-bit word, the staging area is [16 row pairs][64 columns] words, half the LDS traffic of the
+  // fp32 staging below.  A lane then reads eight words = eight columns of two rows, separates the rows with byte
+  // permutes and stores two 16-byte row vectors.  The arithmetic per element is the same as in gemm_epilogue8.
+  const bool packed = vec_ok && (p.epi & (SIF_EPI_RESIDUAL | SIF_EPI_GELU_GRAD | SIF_EPI_OUT_F32)) == 0 &&
+                      !((p.epi & SIF_EPI_GELU) && p.aux != nullptr);
+  if (packed) {
+    uint32_t* sP = reinterpret_cast<uint32_t*>(sW);
+    float bcol[TJ];
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) {
+      const uint32_t n = nw + j * 32 + (lane & 31);
+      bcol[j] = (p.bias != nullptr && n < p.n) ? bf2f(p.bias[n]) : 0.f;
+    }
+    const uint32_t hh = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) {
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          float x0 = acc[i][j][r] * p.alpha + bcol[j], x1 = acc[i][j][r + 1] * p.alpha + bcol[j];
+          if (p.epi & SIF_EPI_GELU) { x0 = gelu_fast(x0); x1 = gelu_fast(x1); }
+          const uint32_t pr = (r >> 2) * 4 + hh * 2 + ((r & 3) >> 1), col = (j * 32 + (lane & 31)) ^ (hh << 5);
+          sP[pr * WCOLS + col] = pack_bf2(x0, x1);
+        }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const uint32_t item = lane + it * 64, pr = item >> 3, c8 = item & 7;     // 16 row pairs x 8 chunks of 8 columns
+        const uint32_t pos = (c8 ^ (((pr >> 1) & 1u) << 2)) * 8;
+        const uint4 w0 = *reinterpret_cast<const uint4*>(sP + pr * WCOLS + pos), w1 = *reinterpret_cast<const uint4*>(sP + pr * WCOLS + pos + 4);
+        const uint4 even = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x05040100), __builtin_amdgcn_perm(w0.w, w0.z, 0x05040100),
+                                      __builtin_amdgcn_perm(w1.y, w1.x, 0x05040100), __builtin_amdgcn_perm(w1.w, w1.z, 0x05040100));
+        const uint4 odd = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x07060302), __builtin_amdgcn_perm(w0.w, w0.z, 0x07060302),
+                                     __builtin_amdgcn_perm(w1.y, w1.x, 0x07060302), __builtin_amdgcn_perm(w1.w, w1.z, 0x07060302));
+        const uint32_t m = mw + i * 32 + 2 * pr, n = nw + c8 * 8;
+        bf16_t* cp = reinterpret_cast<bf16_t*>(p.c) + c_off + (size_t)m * p.ldc + n;
+        if (n < p.n) {
+          if (m < p.m) store_result16(cp, even);
+          if (m + 1 < p.m) store_result16(cp + p.ldc, odd);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    }
+  } else
+#pragma unroll
+  for (int i = 0; i < TI; ++i) {
+    // what the epilogue reads from global memory for this pass is requested before the staging, not inside it
+    uint4 aux_q[WCOLS / 16], res_q[WCOLS / 16];
+#pragma unroll
+    for (int it = 0; it < WCOLS / 16; ++it) {
+      const uint32_t ch = lane + it * 64, row = ch >> 3, c8 = ch & 7;
+      const uint32_t m = mw + i * 32 + row, n = nw + c8 * 8;
+      aux_q[it] = make_uint4(0, 0, 0, 0); res_q[it] = make_uint4(0, 0, 0, 0);
+      if (vec_ok && m < p.m && n < p.n) {
+        const size_t idx = c_off + (size_t)m * p.ldc + n;
+        if (p.epi & SIF_EPI_GELU_GRAD) aux_q[it] = *reinterpret_cast<const uint4*>(p.aux + idx);
+        if ((p.epi & (SIF_EPI_RESIDUAL | SIF_EPI_OUT_F32)) == SIF_EPI_RESIDUAL) res_q[it] = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < TJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), col = j * 32 + (lane & 31);
+        sW[row * WCOLS + ((((col >> 2) ^ ((((row >> 2) & 1) << 3) | (row & 1))) << 2) | (col & 3))] = acc[i][j][r];
+      }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int it = 0; it < WCOLS / 16; ++it) {
+      const uint32_t ch = lane + it * 64, row = ch >> 3, c8 = ch & 7;      // 32 rows x 8 chunks of 8 columns
+      const uint32_t key = (((row >> 2) & 1) << 3) | (row & 1);
+      const float4 q0 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8) ^ key) << 2));
+      const float4 q1 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8 + 1) ^ key) << 2));
+      float v[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
+      const uint32_t m = mw + i * 32 + row, n = nw + c8 * 8;
+      if (m < p.m && n < p.n) gemm_epilogue8(p, c_off, m, n, v, bias8, vec_ok, aux_q[it], res_q[it]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 // Scheduling pipeline of one K step, from MFMA number G on (NS slices of NM MFMAs): after each MFMA its share of the
 // next slice's ND LDS reads and of the step's FETCHES global -> LDS fetches.
 template <int V> struct Int { static constexpr int value = V; };
@@ -239,6 +348,31 @@ __device__ __forceinline__ void sched_pipeline() {
   }
 }
 
+// Block -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Every XCD
+// gets a contiguous run of tiles (tile number pid belongs to XCD pid % 8 and is the (pid / 8)-th of its run), and each
+// run is walked in bands of 8 tile rows, so that the tiles an XCD works on at one time share their A and B panels in
+// that XCD's L2.
+__device__ __forceinline__ void gemm_tile_of(const GemmP& p, uint32_t total_tiles, uint32_t pid, uint32_t& tm, uint32_t& tn) {
+  const uint32_t per = (total_tiles + 7) / 8, tall = (total_tiles % 8) ? (total_tiles % 8) : 8, xcd = pid % 8, local = pid / 8;
+  const uint32_t logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+  const uint32_t width = 8 * p.tiles_n, group = logical / width, first = group * 8;
+  const uint32_t gsz = min(p.tiles_m - first, 8u), in = logical % width;
+  tm = first + in % gsz;
+  tn = in / gsz;
+}
+__device__ __forceinline__ uint32_t gemm_tiles_of_xcd(uint32_t total_tiles, uint32_t x) { return x < total_tiles ? (total_tiles - x + 7u) / 8u : 0u; }
+// One thread: takes a tile from the per-XCD counters of the stream's record, own XCD first: a tile number, else kNone.
+__device__ __forceinline__ uint32_t gemm_steal_tile(StreamRec* rec, uint32_t total_tiles, uint32_t my_x) {
+  for (uint32_t r = 0; r < 8; ++r) {
+    const uint32_t x = (my_x + r) & 7u, cnt = gemm_tiles_of_xcd(total_tiles, x);
+    uint32_t* ctr = &rec->tile_next[x * 32u];
+    if (ld_relaxed(ctr) >= cnt) continue;
+    const uint32_t l = atomicAdd(ctr, 1u);
+    if (l < cnt) return l * 8u + x;
+  }
+  return kNone;
+}
+
 template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE>
 __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
   constexpr int THREADS = 64 * WM * WN, TI = BM / (WM * 32), TJ = BN / (WN * 32), WCOLS = TJ * 32;
@@ -253,18 +387,8 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   __shared__ __align__(1024) bf16_t sB1[BN * BK];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
 
-  // Block -> tile.  Consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.  Give
-  // every XCD a contiguous run of tiles, and walk each run in bands of 8 tile rows, so that the tiles an XCD works
-  // on at one time share their A and B panels in that XCD's L2.
   const uint32_t total_tiles = p.tiles_m * p.tiles_n;
-  auto tile_of = [&](uint32_t pid, uint32_t& tm, uint32_t& tn) {
-    const uint32_t per = (total_tiles + 7) / 8, tall = (total_tiles % 8) ? (total_tiles % 8) : 8, xcd = pid % 8, local = pid / 8;
-    const uint32_t logical = xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-    const uint32_t width = 8 * p.tiles_n, group = logical / width, first = group * 8;
-    const uint32_t gsz = min(p.tiles_m - first, 8u), in = logical % width;
-    tm = first + in % gsz;
-    tn = in / gsz;
-  };
+  auto tile_of = [&](uint32_t pid, uint32_t& tm, uint32_t& tn) { gemm_tile_of(p, total_tiles, pid, tm, tn); };
   const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
   const bf16_t* A = p.a + bo * p.a_so + bi * p.a_si;
   const bf16_t* B = p.b + bo * p.b_so + bi * p.b_si;
@@ -280,17 +404,8 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   __shared__ uint32_t s_next;
   const bool dynamic = !EDGE && ctl.rec != nullptr && gridDim.z == 1 && gridDim.x < total_tiles;
   const uint32_t my_x = blockIdx.x & 7u;
-  auto tiles_of_xcd = [&](uint32_t x) { return x < total_tiles ? (total_tiles - x + 7u) / 8u : 0u; };
-  auto steal = [&]() -> uint32_t {            // one thread: a tile of any XCD's run that still has some, else kNone
-    for (uint32_t r = 0; r < 8; ++r) {
-      const uint32_t x = (my_x + r) & 7u, cnt = tiles_of_xcd(x);
-      uint32_t* ctr = &ctl.rec->tile_next[x * 32u];
-      if (ld_relaxed(ctr) >= cnt) continue;
-      const uint32_t l = atomicAdd(ctr, 1u);
-      if (l < cnt) return l * 8u + x;
-    }
-    return kNone;
-  };
+  auto tiles_of_xcd = [&](uint32_t x) { return gemm_tiles_of_xcd(total_tiles, x); };
+  auto steal = [&]() -> uint32_t { return gemm_steal_tile(ctl.rec, total_tiles, my_x); };
   uint32_t pid = blockIdx.x;
   if (dynamic) {
     if (threadIdx.x == 0) s_next = steal();
@@ -448,95 +563,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
       fetched_ahead = true;
     }
     float* sW = reinterpret_cast<float*>(wave < WM * WN / 2 ? sA1 : sB1) + (wave % (WM * WN / 2)) * (32 * WCOLS);
-    const size_t c_off = (size_t)(bo * p.c_so + bi * p.c_si);
-    const bool vec_ok = (p.n & 7) == 0 && ((c_off & 7) == 0);
-    const float bias8[8] = {bflo(bias_q.x), bfhi(bias_q.x), bflo(bias_q.y), bfhi(bias_q.y), bflo(bias_q.z), bfhi(bias_q.z), bflo(bias_q.w), bfhi(bias_q.w)};
-    // Epilogues that read nothing but the bias (plain, bias, bias + GELU without the pre-activation output) are
-    // finished in the accumulator layout, where a lane's column is fixed, and staged as bf16: two vertically adjacent
-    // results share a 32-bit word, the staging area is [16 row pairs][64 columns] words, half the LDS traffic of the
-    // fp32 staging below.  A lane then reads eight words = eight columns of two rows, separates the rows with byte
-    // permutes and stores two 16-byte row vectors.  The arithmetic per element is the same as in gemm_epilogue8.
-    const bool packed = vec_ok && (p.epi & (SIF_EPI_RESIDUAL | SIF_EPI_GELU_GRAD | SIF_EPI_OUT_F32)) == 0 &&
-                        !((p.epi & SIF_EPI_GELU) && p.aux != nullptr);
-    if (packed) {
-      uint32_t* sP = reinterpret_cast<uint32_t*>(sW);
-      float bcol[TJ];
-#pragma unroll
-      for (int j = 0; j < TJ; ++j) {
-        const uint32_t n = n0 + wn * WCOLS + j * 32 + (lane & 31);
-        bcol[j] = (p.bias != nullptr && n < p.n) ? bf2f(p.bias[n]) : 0.f;
-      }
-      const uint32_t hh = lane >> 5;
-#pragma unroll
-      for (int i = 0; i < TI; ++i) {
-#pragma unroll
-        for (int j = 0; j < TJ; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; r += 2) {
-            float x0 = acc[i][j][r] * p.alpha + bcol[j], x1 = acc[i][j][r + 1] * p.alpha + bcol[j];
-            if (p.epi & SIF_EPI_GELU) { x0 = gelu_fast(x0); x1 = gelu_fast(x1); }
-            const uint32_t pr = (r >> 2) * 4 + hh * 2 + ((r & 3) >> 1), col = (j * 32 + (lane & 31)) ^ (hh << 5);
-            sP[pr * WCOLS + col] = pack_bf2(x0, x1);
-          }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-          const uint32_t item = lane + it * 64, pr = item >> 3, c8 = item & 7;     // 16 row pairs x 8 chunks of 8 columns
-          const uint32_t pos = (c8 ^ (((pr >> 1) & 1u) << 2)) * 8;
-          const uint4 w0 = *reinterpret_cast<const uint4*>(sP + pr * WCOLS + pos), w1 = *reinterpret_cast<const uint4*>(sP + pr * WCOLS + pos + 4);
-          const uint4 even = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x05040100), __builtin_amdgcn_perm(w0.w, w0.z, 0x05040100),
-                                        __builtin_amdgcn_perm(w1.y, w1.x, 0x05040100), __builtin_amdgcn_perm(w1.w, w1.z, 0x05040100));
-          const uint4 odd = make_uint4(__builtin_amdgcn_perm(w0.y, w0.x, 0x07060302), __builtin_amdgcn_perm(w0.w, w0.z, 0x07060302),
-                                       __builtin_amdgcn_perm(w1.y, w1.x, 0x07060302), __builtin_amdgcn_perm(w1.w, w1.z, 0x07060302));
-          const uint32_t m = m0 + wm * (TI * 32) + i * 32 + 2 * pr, n = n0 + wn * WCOLS + c8 * 8;
-          bf16_t* cp = reinterpret_cast<bf16_t*>(p.c) + c_off + (size_t)m * p.ldc + n;
-          if (n < p.n) {
-            if (m < p.m) *reinterpret_cast<uint4*>(cp) = even;
-            if (m + 1 < p.m) *reinterpret_cast<uint4*>(cp + p.ldc) = odd;
-          }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-      }
-    } else
-#pragma unroll
-    for (int i = 0; i < TI; ++i) {
-      // what the epilogue reads from global memory for this pass is requested before the staging, not inside it
-      uint4 aux_q[WCOLS / 16], res_q[WCOLS / 16];
-#pragma unroll
-      for (int it = 0; it < WCOLS / 16; ++it) {
-        const uint32_t ch = lane + it * 64, row = ch >> 3, c8 = ch & 7;
-        const uint32_t m = m0 + wm * (TI * 32) + i * 32 + row, n = n0 + wn * WCOLS + c8 * 8;
-        aux_q[it] = make_uint4(0, 0, 0, 0); res_q[it] = make_uint4(0, 0, 0, 0);
-        if (vec_ok && m < p.m && n < p.n) {
-          const size_t idx = c_off + (size_t)m * p.ldc + n;
-          if (p.epi & SIF_EPI_GELU_GRAD) aux_q[it] = *reinterpret_cast<const uint4*>(p.aux + idx);
-          if ((p.epi & (SIF_EPI_RESIDUAL | SIF_EPI_OUT_F32)) == SIF_EPI_RESIDUAL) res_q[it] = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(p.res) + idx);
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < TJ; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const uint32_t row = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3), col = j * 32 + (lane & 31);
-          sW[row * WCOLS + ((((col >> 2) ^ ((((row >> 2) & 1) << 3) | (row & 1))) << 2) | (col & 3))] = acc[i][j][r];
-        }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int it = 0; it < WCOLS / 16; ++it) {
-        const uint32_t ch = lane + it * 64, row = ch >> 3, c8 = ch & 7;      // 32 rows x 8 chunks of 8 columns
-        const uint32_t key = (((row >> 2) & 1) << 3) | (row & 1);
-        const float4 q0 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8) ^ key) << 2));
-        const float4 q1 = *reinterpret_cast<const float4*>(sW + row * WCOLS + (((2 * c8 + 1) ^ key) << 2));
-        float v[8] = {q0.x, q0.y, q0.z, q0.w, q1.x, q1.y, q1.z, q1.w};
-        const uint32_t m = m0 + wm * (TI * 32) + i * 32 + row, n = n0 + wn * WCOLS + c8 * 8;
-        if (m < p.m && n < p.n) gemm_epilogue8(p, c_off, m, n, v, bias8, vec_ok, aux_q[it], res_q[it]);
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
+    gemm_store_tile<TI, TJ>(p, acc, sW, m0 + wm * (TI * 32), n0 + wn * WCOLS, (size_t)(bo * p.c_so + bi * p.c_si), bias_q);
   }
   pid = next_pid;
   }
