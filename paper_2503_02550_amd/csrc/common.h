@@ -40,9 +40,14 @@ __device__ __forceinline__ float upper_tail_fast(float t) {       // 1 - Phi(t) 
   const float r = fmaf(fmaf(fmaf(fmaf(-0.000502793584f, t, 0.00730014686f), t, -0.0523868538f), t, -0.459369212f), t, -1.15106988f);
   return 0.5f * __builtin_amdgcn_exp2f(t * r);
 }
+// GELU(x) = max(x, 0) - |x| (1 - Phi(|x|)): for x < 0 that is x (1 - Phi(-x)) = x Phi(x), for x >= 0 x - x (1 - Phi(x)).
+// The factor 1/2 goes into the exponent: eleven issue slots per value (five fused multiply-adds, the exponential
+// counting four, one maximum, one more fused multiply-add), no comparison and no select.
 __device__ __forceinline__ float gelu_fast(float x) {
-  const float h = upper_tail_fast(fabsf(x));
-  return x * (x < 0.f ? h : 1.0f - h);
+  const float t = fabsf(x);
+  const float r = fmaf(fmaf(fmaf(fmaf(-0.000502793584f, t, 0.00730014686f), t, -0.0523868538f), t, -0.459369212f), t, -1.15106988f);
+  const float h = __builtin_amdgcn_exp2f(fmaf(t, r, -1.0f));
+  return fmaf(-t, h, fmaxf(x, 0.f));
 }
 __device__ __forceinline__ float gelu_grad_fast(float x) {
   const float h = upper_tail_fast(fabsf(x));
