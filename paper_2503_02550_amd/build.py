@@ -32,7 +32,9 @@ def build(jobs=8):
     os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, sources()))
-    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB, "-lpthread"],
+    # -z defs: a symbol that no object defines (a kernel whose host stub was not emitted, say) fails the link here, not
+    # the first dlopen on the GPU machine
+    r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-Wl,-z,defs", *objs, "-o", LIB, "-lpthread"],
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)
