@@ -17,6 +17,11 @@
 // tiles are fetched from global memory straight into LDS, tile t+1 while tile t is multiplied; tiles on a ragged
 // edge of the 128x128 configuration go through registers (two K steps of prefetch) so that they can be zero-filled.
 //
+// What the main loop waits for is neither the MFMA units nor LDS but the operand fetches: a CU sustains about 28 bytes
+// per cycle of loads that miss its L1 (measured; whatever their destination), a 256x256 tile needs 31 bytes per cycle
+// at full MFMA rate and a 128x128 tile twice that.  Hence the large tile wherever it fills the chip, fetches that hand
+// over 32-bit offsets (buffer loads), and result stores that do not claim L2 lines the operand panels are reused from.
+//
 // Results depend neither on the grid nor on the tile configuration: each output element is reduced over K in one
 // fixed order (ascending, 16 at a time) by one wavefront, so launching a row range of the same problem, or the other
 // configuration, gives bit-identical values.
