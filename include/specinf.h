@@ -197,7 +197,7 @@ typedef struct sif_gemm_args {
   uint32_t m, n, k;            /* logical extents.  The extent along an operand's contiguous dimension may
                                   be ragged only if the row is padded (ld >= extent rounded up to 8) with
                                   zeros; ld must be a multiple of 8 elements.                          */
-  uint32_t lda, ldb, ldc;
+  uint32_t lda, ldb, ldc;      /* leading dimensions in elements; lda, ldb: multiples of 8, at most 4194304 */
   uint32_t batch_outer, batch_inner;             /* grid z = batch_outer * batch_inner (>= 1 each)     */
   int64_t a_stride_outer, a_stride_inner;        /* element offsets per batch index                    */
   int64_t b_stride_outer, b_stride_inner;

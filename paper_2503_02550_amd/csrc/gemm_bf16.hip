@@ -616,6 +616,8 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   if (!a->a_dev || !a->b_dev || !a->c_dev) return fail(SIF_E_INVAL, "gemm: null operand");
   if (!aligned16(a->a_dev) || !aligned16(a->b_dev) || !aligned16(a->c_dev)) return fail(SIF_E_INVAL, "gemm: operands must be 16-byte aligned");
   if ((a->lda & 7) || (a->ldb & 7)) return fail(SIF_E_INVAL, "gemm: lda/ldb must be multiples of 8");
+  // a lane's offset within an operand tile (up to 255 rows of ld elements) is kept in 32 bits
+  if (a->lda > (1u << 22) || a->ldb > (1u << 22)) return fail(SIF_E_INVAL, "gemm: lda/ldb above 4194304 elements are not supported");
   if ((a->a_stride_outer | a->a_stride_inner | a->b_stride_outer | a->b_stride_inner) & 7) return fail(SIF_E_INVAL, "gemm: batch strides must be multiples of 8");
   const uint32_t a_contig = a->a_layout == SIF_A_ROW_K ? a->k : a->m;
   const uint32_t b_contig = a->b_layout == SIF_B_ROW_K ? a->k : a->n;
