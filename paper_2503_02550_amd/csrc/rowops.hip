@@ -526,6 +526,150 @@ __global__ __launch_bounds__(256) void embed_bwd_wte_kernel(const int32_t* __res
   kernel_end(ctl, true);
 }
 
+// The same sums (bit for bit) for up to 16384 tokens and d a multiple of 8, without every block reading every id from
+// global memory twice: a block owns 32 consecutive tokens, keeps all ids in LDS, finds for its tokens in one sweep
+// over them which have an earlier token with the same id (nothing to do) and which later ones (noted in a list),
+// adds the rows of the tokens that have neither - nearly all, with a vocabulary much larger than the batch - as
+// 16-byte vectors, and for the few that own later rows as well takes these from the list in ascending order.  A list
+// that overflows (a tiny vocabulary) sends the block down the old path, on the ids in LDS.
+constexpr uint32_t EB_LDS_TOKENS = 16384, EB_OWN = 32, EB_LIST = 1024;
+__global__ __launch_bounds__(256) void embed_bwd_wte_lds_kernel(const int32_t* __restrict__ ids, const bf16_t* __restrict__ dx,
+                                                                bf16_t* __restrict__ dwte, uint32_t tokens, uint32_t d, uint32_t vocab, KCtl ctl) {
+  __shared__ uint32_t sid[EB_LDS_TOKENS];
+  __shared__ uint32_t smask[8];
+  __shared__ int sflag[256];
+  __shared__ uint32_t s_cnt, s_list[EB_LIST];          // (own token u << 14) | later token j with the same id
+  if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
+  const uint32_t t0 = blockIdx.x * EB_OWN, nloc = min(EB_OWN, tokens - t0), lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (uint32_t j = threadIdx.x; j < tokens; j += 256) sid[j] = clamp_id(ids[j], vocab);
+  if (threadIdx.x == 0) s_cnt = 0;
+  __syncthreads();
+  uint32_t seen = 0, later = 0;                  // bit u: token t0 + u has an earlier / a later token with its id
+  uint32_t own[EB_OWN];                          // the block's ids, the same in every lane: scalar registers
+#pragma unroll
+  for (uint32_t u = 0; u < EB_OWN; ++u) own[u] = __builtin_amdgcn_readfirstlane(sid[min(t0 + u, tokens - 1)]);
+  const uint32_t valid = nloc >= 32 ? 0xFFFFFFFFu : (1u << nloc) - 1u;
+  for (uint32_t j = threadIdx.x; j < tokens; j += 256) {
+    const uint32_t idj = sid[j];
+    uint32_t eq = 0;
+#pragma unroll
+    for (uint32_t u = 0; u < EB_OWN; ++u) eq |= idj == own[u] ? 1u << u : 0u;
+    // own tokens below j: u < j - t0; own tokens above j: u > j - t0
+    const uint32_t below = j <= t0 ? 0u : (j - t0 >= 32 ? 0xFFFFFFFFu : (1u << (j - t0)) - 1u);
+    const uint32_t above = j < t0 ? 0xFFFFFFFFu : (j - t0 >= 31 ? 0u : ~((2u << (j - t0)) - 1u));
+    seen |= eq & above & valid;
+    uint32_t mine = eq & below & valid;          // own tokens that token j comes after with the same id (rare)
+    later |= mine;
+    while (mine) {
+      const uint32_t u = __builtin_ctz(mine);
+      mine &= mine - 1;
+      const uint32_t k = atomicAdd(&s_cnt, 1u);
+      if (k < EB_LIST) s_list[k] = (u << 14) | j;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) { seen |= __shfl_xor(seen, o, 64); later |= __shfl_xor(later, o, 64); }
+  if (lane == 0) { smask[wave] = seen; smask[4 + wave] = later; }
+  __syncthreads();
+  seen = smask[0] | smask[1] | smask[2] | smask[3];
+  later = smask[4] | smask[5] | smask[6] | smask[7];
+  // tokens that are alone with their id: dwte[id] += dx[t], eight columns per item, four items' loads at a time
+  const uint32_t nv = d >> 3, alone = ~(seen | later) & valid, n_items = nloc * nv;
+  for (uint32_t first = threadIdx.x; first < n_items; first += 4 * 256) {
+    uint4 o4[4], x4[4];
+    uint4* out[4];
+    bool on[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const uint32_t item = first + q * 256, u = min(item / nv, nloc - 1), v = item - u * nv;
+      on[q] = item < n_items && ((alone >> u) & 1u);
+      out[q] = reinterpret_cast<uint4*>(dwte + (size_t)sid[t0 + u] * d) + v;
+      if (on[q]) { o4[q] = *out[q]; x4[q] = reinterpret_cast<const uint4*>(dx + (size_t)(t0 + u) * d)[v]; }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (!on[q]) continue;
+      float a[8], b[8];
+      unpack8(o4[q], a); unpack8(x4[q], b);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) a[i] = a[i] + (0.f + b[i]);
+      *out[q] = pack8(a);
+    }
+  }
+  // tokens that are the first of several with their id: their rows in ascending order, as in embed_bwd_wte_kernel
+  const uint32_t n_list = s_cnt;                 // (written before the barrier in front of the masks)
+  const uint32_t first_of_several = later & ~seen & valid;
+  if (n_list <= EB_LIST) {
+    // a wavefront per such token, 8 columns per lane and pass: the token's own row, then again and again the lowest
+    // listed token above the last one taken (nothing here waits for another wavefront)
+    uint32_t todo = first_of_several;
+    for (uint32_t n = 0; todo != 0; ++n) {
+      const uint32_t u = __builtin_ctz(todo);
+      todo &= todo - 1;
+      if ((n & 3u) != wave) continue;
+      const uint32_t t = t0 + u;
+      for (uint32_t v0 = 0; v0 < nv; v0 += 64) {
+        const uint32_t v = v0 + lane;
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+        uint32_t take = t;
+        while (take != kNone) {
+          if (v < nv) {
+            float b[8];
+            unpack8(reinterpret_cast<const uint4*>(dx + (size_t)take * d)[v], b);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] += b[i];
+          }
+          uint32_t best = kNone;
+          for (uint32_t k = lane; k < n_list; k += 64) {
+            const uint32_t e = s_list[k], jj = e & 0x3FFFu;
+            if ((e >> 14) == u && jj > take && jj < best) best = jj;
+          }
+#pragma unroll
+          for (int o = 32; o > 0; o >>= 1) best = min(best, (uint32_t)__shfl_xor(best, o, 64));
+          take = best;
+        }
+        if (v < nv) {
+          uint4* out = reinterpret_cast<uint4*>(dwte + (size_t)sid[t] * d) + v;
+          float a[8];
+          unpack8(*out, a);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) a[i] = a[i] + acc[i];
+          *out = pack8(a);
+        }
+      }
+    }
+  } else {
+    for (uint32_t u = 0; u < nloc; ++u) {
+      if (!((first_of_several >> u) & 1u)) continue;
+      const uint32_t t = t0 + u, id = sid[t];
+      float acc[EB_MAXC];
+#pragma unroll
+      for (int i = 0; i < EB_MAXC; ++i) acc[i] = 0.f;
+      for (uint32_t base = t; base < tokens; base += 256) {
+        const uint32_t j = base + threadIdx.x;
+        const int hit = (j < tokens) && (sid[j] == id);
+        __syncthreads();
+        sflag[threadIdx.x] = hit;
+        if (__syncthreads_or(hit)) {
+          for (uint32_t w = 0; w < 256; ++w) {
+            if (sflag[w]) {
+              const bf16_t* row = dx + (size_t)(base + w) * d;
+#pragma unroll
+              for (int i = 0; i < EB_MAXC; ++i) { const uint32_t c = threadIdx.x + 256 * i; if (c < d) acc[i] += bf2f(row[c]); }
+            }
+          }
+        }
+      }
+      bf16_t* out = dwte + (size_t)id * d;
+#pragma unroll
+      for (int i = 0; i < EB_MAXC; ++i) { const uint32_t c = threadIdx.x + 256 * i; if (c < d) out[c] = f2bf(bf2f(out[c]) + acc[i]); }
+    }
+  }
+  kernel_end(ctl, true);
+}
+
 __global__ __launch_bounds__(256) void embed_bwd_wpe_kernel(const bf16_t* __restrict__ dx, bf16_t* __restrict__ dwpe,
                                                             uint32_t tokens, uint32_t seq, uint32_t d, KCtl ctl) {
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
@@ -930,7 +1074,10 @@ sif_status launch_embed_fwd_segs(const RowSegs& segs, const void* wte, const voi
 sif_status launch_embed_bwd_wte(const int32_t* ids, const void* dx, void* dwte, uint32_t vocab, uint32_t tokens, uint32_t d, hipStream_t s, const KCtl& c) {
   REQ(ids && dx && dwte && tokens > 0 && vocab > 0, "embed_bwd: null or empty");
   REQ(d <= 256 * EB_MAXC, "embed_bwd: d must be <= 4096");
-  hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(tokens), dim3(256), 0, s, ids, (const bf16_t*)dx, (bf16_t*)dwte, tokens, d, vocab, c);
+  if (tokens <= EB_LDS_TOKENS && (d & 7) == 0 && al16(dx) && al16(dwte))
+    hipLaunchKernelGGL(embed_bwd_wte_lds_kernel, dim3((tokens + EB_OWN - 1) / EB_OWN), dim3(256), 0, s, ids, (const bf16_t*)dx, (bf16_t*)dwte, tokens, d, vocab, c);
+  else
+    hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3(tokens), dim3(256), 0, s, ids, (const bf16_t*)dx, (bf16_t*)dwte, tokens, d, vocab, c);
   return check_launch("embed_bwd_wte");
 }
 

@@ -244,6 +244,28 @@ def test_softmax_fwd_bwd(batch, rows, cols, causal):
     assert_bf16_close(np.where(written, up(ds), 0.0), np.where(written, ref_full, 0.0), "softmax bwd")
 
 
+@pytest.mark.parametrize("tokens,seq,d,vocab", [(8192, 1024, 768, 50257), (1000, 8, 64, 40000), (16416, 16, 32, 3000)])
+def test_embedding_gradient_at_training_size_keeps_the_order_of_the_sums(tokens, seq, d, vocab):
+    """Token-embedding gradient where most ids occur once and a few several times (8192 draws from 50257 ids: a few
+    hundred pairs), with a ragged last group of 32 tokens, and with more tokens than the LDS variant takes (the other
+    kernel): rows with the same id are added in ascending token order on top of what the table already holds."""
+    ids = np.random.default_rng(40).integers(0, vocab, tokens).astype(np.int32)
+    dx, head = rnd(41, tokens, d), rnd(42, vocab, d) * 0.1
+    dwte, dwpe = bf(head), torch.zeros((seq, d), device=DEV, dtype=torch.bfloat16)
+    S.sif_k_embed_bwd(i32(ids), bf(dx), dwte, dwpe, vocab, tokens, seq, d)
+    torch.cuda.synchronize()
+    # the kernel's arithmetic written out: fp32 sum of the rows in ascending token order, added to the table's value in fp32
+    order = np.argsort(ids, kind="stable")
+    acc = np.zeros((vocab, d), np.float32)
+    dq = q(dx).astype(np.float32)
+    for t in order: acc[ids[t]] += dq[t]
+    want = N.bf16_round((q(head).astype(np.float32) + acc).astype(np.float64))
+    touched = np.unique(ids)
+    assert np.array_equal(up(dwte)[touched], want[touched])             # same order of additions, same bits
+    untouched = np.setdiff1d(np.arange(vocab), touched)
+    assert np.array_equal(up(dwte)[untouched], q(head)[untouched])
+
+
 def test_embedding_fwd_bwd():
     tokens, seq, d, vocab = 96, 24, 64, 17          # small vocabulary: many repeated ids
     ids = np.random.default_rng(28).integers(0, vocab, tokens).astype(np.int32)
