@@ -151,18 +151,33 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
 #pragma unroll
     for (int t = 0; t < MAXV; ++t) cg[t] = (lane + 64 * t < nv) ? reinterpret_cast<const uint4*>(g)[lane + 64 * t] : make_uint4(0, 0, 0, 0);
   }
+  // (CACHE) the wavefront's next row is requested before the current one is worked on
+  uint4 cdy[CACHE ? MAXV : 1], cx[CACHE ? MAXV : 1], cres[CACHE ? MAXV : 1];
+  uint4 ndy[CACHE ? MAXV : 1], nx[CACHE ? MAXV : 1], nres[CACHE ? MAXV : 1];
+  float mu = 0.f, rs = 0.f, nmu = 0.f, nrs = 0.f;
+  auto fetch_row = [&](uint32_t r_, uint4 (&qdy)[CACHE ? MAXV : 1], uint4 (&qx)[CACHE ? MAXV : 1], uint4 (&qres)[CACHE ? MAXV : 1], float& qmu, float& qrs) {
+    const uint4* dyr = reinterpret_cast<const uint4*>(dy + (size_t)r_ * d);
+    const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)r_ * d);
+#pragma unroll
+    for (int t = 0; t < (CACHE ? MAXV : 1); ++t) {
+      const uint32_t v = lane + 64 * t;
+      qdy[t] = v < nv ? dyr[v] : make_uint4(0, 0, 0, 0);
+      qx[t] = v < nv ? xr[v] : make_uint4(0, 0, 0, 0);
+      qres[t] = (res != nullptr && v < nv) ? reinterpret_cast<const uint4*>(res + (size_t)r_ * d)[v] : make_uint4(0, 0, 0, 0);
+    }
+    qmu = mean[r_]; qrs = rstd[r_];
+  };
+  if (CACHE && r_begin + wave < r_end) fetch_row(r_begin + wave, ndy, nx, nres, nmu, nrs);
   for (uint32_t row = r_begin + wave; row < r_end; row += 4) {
     const uint4* dyr = reinterpret_cast<const uint4*>(dy + (size_t)row * d);
     const uint4* xr = reinterpret_cast<const uint4*>(x + (size_t)row * d);
-    const float mu = mean[row], rs = rstd[row];
-    uint4 cdy[CACHE ? MAXV : 1], cx[CACHE ? MAXV : 1];
     if (CACHE) {
 #pragma unroll
-      for (int t = 0; t < MAXV; ++t) {
-        const uint32_t v = lane + 64 * t;
-        cdy[t] = v < nv ? dyr[v] : make_uint4(0, 0, 0, 0);
-        cx[t] = v < nv ? xr[v] : make_uint4(0, 0, 0, 0);
-      }
+      for (int t = 0; t < MAXV; ++t) { cdy[t] = ndy[t]; cx[t] = nx[t]; cres[t] = nres[t]; }
+      mu = nmu; rs = nrs;
+      if (row + 4 < r_end) fetch_row(row + 4, ndy, nx, nres, nmu, nrs);
+    } else {
+      mu = mean[row]; rs = rstd[row];
     }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -188,7 +203,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const bf16_t* __rest
         float fdy[8], fx[8], fg[8], fr[8], o[8];
         unpack8(CACHE ? cdy[t] : dyr[v], fdy); unpack8(CACHE ? cx[t] : xr[v], fx);
         unpack8(CACHE ? cg[t] : reinterpret_cast<const uint4*>(g)[v], fg);
-        if (res != nullptr) unpack8(reinterpret_cast<const uint4*>(res + (size_t)row * d)[v], fr);
+        if (res != nullptr) unpack8(CACHE ? cres[t] : reinterpret_cast<const uint4*>(res + (size_t)row * d)[v], fr);
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float xh = (fx[i] - mu) * rs;
