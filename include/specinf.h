@@ -216,7 +216,8 @@ typedef struct sif_gemm_args {
   uint32_t k_limit;            /* 0, or the whole K of a product that batch_inner cuts into slices of k along K (the
                                   operands' inner batch strides step along K, the results of the slices go to
                                   separate outputs): slice i then contracts only k_limit - i*k (at most k)
-                                  elements, so the last slice may be shorter than the others.  128-wide tiles only */
+                                  elements, so the last slice may be shorter than the others (256-wide tiles: it
+                                  too must be a multiple of 64) */
 } sif_gemm_args;
 
 /* bf16 matrix product on the MFMA units, fp32 accumulation. */

@@ -584,10 +584,14 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // 256x256 tiles (one block of eight wavefronts per CU, 128x64 per wavefront: a quarter fewer LDS reads and half the
-// global fetches per MFMA); they need whole K steps and no causal skipping
+// global fetches per MFMA); they need whole K steps - also in the last, shorter slice of a K cut into slices - and no
+// causal skipping
 bool gemm_can_use_big_tiles(const sif_gemm_args& a) {
   const bool causal = a.k_causal != 0 || (a.epilogue & SIF_EPI_CAUSAL_SKIP);
-  return !causal && (a.k % BK) == 0 && a.k_limit == 0;
+  if (causal || (a.k % BK) != 0) return false;
+  if (a.k_limit == 0) return true;
+  const uint64_t before_last = (uint64_t)(a.batch_inner - 1) * a.k;
+  return a.k_limit > before_last && ((a.k_limit - before_last) % BK) == 0;
 }
 
 // Which configuration is faster follows a two-line model fitted to measurements on gfx950 (time of one round of
@@ -627,15 +631,15 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   if ((a->epilogue & SIF_EPI_RESIDUAL) && !a->res_dev) return fail(SIF_E_INVAL, "gemm: RESIDUAL needs res");
   if ((a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) == SIF_EPI_BIAS && !a->bias_dev) return fail(SIF_E_INVAL, "gemm: BIAS needs bias");
   if (a->k_causal > 2) return fail(SIF_E_INVAL, "gemm: bad k_causal");
-  if (a->k_limit != 0 && (a->k_causal != 0 || (uint64_t)(a->batch_inner - 1) * a->k >= a->k_limit || a->k_limit > (uint64_t)a->batch_inner * a->k || a->tile == 256))
-    return fail(SIF_E_INVAL, "gemm: k_limit must lie in the last of the batch_inner slices of k (no k_causal, no 256-wide tiles)");
+  if (a->k_limit != 0 && (a->k_causal != 0 || (uint64_t)(a->batch_inner - 1) * a->k >= a->k_limit || a->k_limit > (uint64_t)a->batch_inner * a->k))
+    return fail(SIF_E_INVAL, "gemm: k_limit must lie in the last of the batch_inner slices of k (no k_causal)");
   if ((a->n & 7) == 0) {
     // vector epilogue: rows of C, the residual and the auxiliary tensor are accessed 8 elements at a time
     if ((a->ldc & 7) || ((a->c_stride_outer | a->c_stride_inner) & 7)) return fail(SIF_E_INVAL, "gemm: ldc and the output batch strides must be multiples of 8 when n is");
     if ((a->bias_dev && !aligned16(a->bias_dev)) || (a->res_dev && !aligned16(a->res_dev)) || (a->aux_dev && !aligned16(a->aux_dev))) return fail(SIF_E_INVAL, "gemm: bias, residual and aux must be 16-byte aligned");
   }
   if (a->tile != 0 && a->tile != 128 && a->tile != 256) return fail(SIF_E_INVAL, "gemm: tile must be 0, 128 or 256");
-  if (a->tile == 256 && !gemm_can_use_big_tiles(*a)) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k to be a multiple of 64 and no causal variant");
+  if (a->tile == 256 && !gemm_can_use_big_tiles(*a)) return fail(SIF_E_INVAL, "gemm: 256-wide tiles need k (and the last slice under k_limit) to be a multiple of 64 and no causal variant");
   const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
   const bool big = gemm_big_tiles(*a);
   const uint32_t bm = big ? 256 : 128, bn = bm;

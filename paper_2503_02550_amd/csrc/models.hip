@@ -478,7 +478,9 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   const sif_model_shape& s = tm.desc.shape;
   const ParamMap pm = param_map(s);
   const Dims q = dims_of(s, s.batch, s.seq);
-  const uint32_t M = q.M, d = q.d, Vp = (s.vocab + 7) & ~7u;
+  // Row pitch of the logits: the vocabulary rounded up to 8 columns, for a large vocabulary to whole 64-wide K steps, so
+  // that the LM head's data gradient, which contracts the logits' columns, can be cut into slices of whole K steps.
+  const uint32_t M = q.M, d = q.d, Vp = s.vocab >= 8192 ? (s.vocab + 63) & ~63u : (s.vocab + 7) & ~7u;
   const uint64_t ssz = (uint64_t)q.B * q.H * q.S * q.Sp;
   const bool fused = fused_attention(q.dh);
   const bool pp = tm.desc.par_mode == SIF_PAR_PP;
@@ -532,7 +534,11 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   float *mf = nullptr, *rf = nullptr, *loss_tok = nullptr, *loss = nullptr;
   // The LM head's data gradient [M][d] contracts the whole vocabulary: few output tiles and a very long K.  It is cut
   // along K into slices whose tiles fill whole rounds of block slots, summed by one small launch right behind it.
-  uint32_t head_splits = 1, head_kper = 0;
+  // Where the padded vocabulary can be contracted as a whole (its padding columns are zero in the loss gradient and
+  // the rows of the working copy behind wte stand in for the padding rows, as for the forward product), the slices can
+  // be whole numbers of K steps and the product can take the 256x256 tiles, one block per CU: as many slices as fill
+  // whole rounds of 256 blocks (8192 x 768 over 50304: 96 tiles x 8 slices of 99, ..., 93 steps = three rounds).
+  uint32_t head_splits = 1, head_kper = 0, head_k = s.vocab;
   float* head_part = nullptr;
   RedItem* head_item = nullptr;
   if (s.vocab) {
@@ -545,6 +551,20 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     if (head_splits > 1) {
       head_kper = ((s.vocab + head_splits - 1) / head_splits + 63) / 64 * 64;
       if ((uint64_t)(head_splits - 1) * head_kper >= s.vocab) head_splits = 1;
+    }
+    const uint32_t tiles_big = ((M + 255) / 256) * ((d + 255) / 256), steps = Vp / 64;
+    if (head_splits > 1 && Vp - s.vocab <= s.max_pos && (Vp % 64) == 0 && (d % 8) == 0 && tiles_big < 256) {
+      uint32_t k_big = 1;
+      double best_big = 0.0;
+      for (uint32_t k = 1; k <= 16 && k <= steps; ++k) {
+        const double fill = (double)tiles_big * k / (256.0 * ((tiles_big * k + 255) / 256));
+        if (fill > best_big * 1.02) { best_big = fill; k_big = k; }
+      }
+      const uint32_t kper_big = (steps + k_big - 1) / k_big * 64;
+      // the launcher's timing model for the two configurations, plus what the sum of the slices reads
+      const double t_small = (1.0 + 1.19 * (head_kper / 64.0)) * std::max(0.85, (double)tiles * head_splits / 512.0) + bytes_cost_us(4.0 * M * d * head_splits);
+      const double t_big = (4.0 + 1.75 * (kper_big / 64.0)) * (double)((tiles_big * k_big + 255) / 256) + bytes_cost_us(4.0 * M * d * k_big);
+      if (k_big > 1 && (uint64_t)(k_big - 1) * kper_big < Vp && t_big < t_small) { head_splits = k_big; head_kper = kper_big; head_k = Vp; }
     }
     if (head_splits > 1) {
       head_part = (float*)ar.take((uint64_t)head_splits * M * d * 4);
@@ -701,7 +721,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
       if (head_splits > 1) {
         emit_gemm(p, "dlnf", G(logits, wte, head_part, M, d, head_kper, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
-                                 .batch(1, head_splits, 0, head_kper, 0, (int64_t)head_kper * d, 0, (int64_t)M * d).k_limit(V));
+                                 .batch(1, head_splits, 0, head_kper, 0, (int64_t)head_kper * d, 0, (int64_t)M * d).k_limit(head_k));
         RedItem it;
         it.part = head_part; it.out = sc.dln; it.n = (uint64_t)M * d; it.splits = head_splits; it.pad = 0;
         hipError_t e2 = hipMemcpy(head_item, &it, sizeof(it), hipMemcpyHostToDevice);
