@@ -137,6 +137,30 @@ def test_gemm_bf16_slices_of_one_long_k(bl):
                           a_strides=(0, kper), b_strides=(0, kper), c_strides=(0, m * n), k_limit=2 * kper)
 
 
+@pytest.mark.parametrize("bl", [0, 1])
+def test_gemm_bf16_slices_of_one_long_k_on_large_tiles(bl):
+    """The 256x256 configuration takes a K cut into slices when every slice, the shorter last one too, is a whole number
+    of 64-wide K steps (the LM head's data gradient over the padded vocabulary): same bits as the 128x128 one, ragged M
+    and N included; a last slice that is not a whole number of steps is refused for these tiles."""
+    m, n, kper, slices, k_total = 520, 264, 192, 3, 2 * 192 + 128
+    a = rnd(43, m, k_total)
+    b = rnd(44, n, k_total) if bl == 0 else rnd(44, k_total, n)
+    A, B = bf(a), bf(b)
+    parts = []
+    for tile in (128, 256):
+        part = torch.full((slices, m, n), 9.0, device=DEV)
+        S.sif_k_gemm_bf16(A, B, part, m, n, kper, k_total, B.shape[1], n, b_layout=bl, epilogue=S.SIF_EPI_OUT_F32, batch_inner=slices,
+                          a_strides=(0, kper), b_strides=(0, kper if bl == 0 else kper * n), c_strides=(0, m * n), k_limit=k_total, tile=tile)
+        parts.append(part)
+    torch.cuda.synchronize()
+    assert torch.equal(parts[0], parts[1])
+    bq = q(b) if bl == 0 else q(b).T
+    assert_f32_close(up(parts[1]).sum(0), q(a) @ bq.T, "sum of the slices, large tiles", tol=1e-4)
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16(A, B, parts[1], m, n, kper, k_total, B.shape[1], n, b_layout=bl, epilogue=S.SIF_EPI_OUT_F32, batch_inner=slices,
+                          a_strides=(0, kper), b_strides=(0, kper if bl == 0 else kper * n), c_strides=(0, m * n), k_limit=k_total - 8, tile=256)
+
+
 def test_gemm_bf16_rejects_bad_arguments():
     A = bf(rnd(12, 16, 16))
     c = torch.zeros((16, 16), device=DEV, dtype=torch.bfloat16)
