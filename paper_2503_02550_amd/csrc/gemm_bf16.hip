@@ -53,6 +53,10 @@ struct GemmP {
   uint32_t m, n, k, lda, ldb, ldc, epi, k_causal, batch_inner, tiles_m, tiles_n, k_limit;
   long long a_so, a_si, b_so, b_si, c_so, c_si;
   float alpha;
+  // a launch over several products at once (128x128 tiles, no batch): `group` points to their records in device memory,
+  // each with the number of the launch's first block that works on it (a multiple of 8)
+  const GemmP* group;
+  uint32_t group_n, tile_base;
 };
 
 // LDS tile: rows x 64 k (bf16), 128 bytes per row = eight 16-byte chunks, no padding.  Chunk c of row r
@@ -384,8 +388,12 @@ __device__ __forceinline__ uint32_t gemm_steal_tile(StreamRec* rec, uint32_t tot
   return kNone;
 }
 
-template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE>
-__global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p, KCtl ctl) {
+template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE, bool GROUPED = false>
+__global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p_in, KCtl ctl) {
+  static_assert(!GROUPED || EDGE, "several products in one launch: one block per tile");
+  // (an instantiation of its own for launches over several products: in the others the product's record stays the
+  // kernel argument, in scalar registers)
+  GemmP p = p_in;
   constexpr int THREADS = 64 * WM * WN, TI = BM / (WM * 32), TJ = BN / (WN * 32), WCOLS = TJ * 32;
   static_assert((BM * 8) % THREADS == 0 && (BN * 8) % THREADS == 0, "whole 16-byte vectors per thread and operand tile");
   static_assert(!EDGE || (BM * 8 == 4 * THREADS && BN * 8 == 4 * THREADS), "the register path moves four vectors per thread and operand");
@@ -398,6 +406,17 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   __shared__ __align__(1024) bf16_t sB1[BN * BK];
   if (!kernel_begin(ctl)) { kernel_end(ctl, false); return; }
 
+  if constexpr (GROUPED) {                     // several products in one launch: which one is this block's
+    uint32_t g = 0;
+    while (g + 1 < p_in.group_n && blockIdx.x >= p_in.group[g + 1].tile_base) ++g;
+    // the record is the same for every lane: word by word into scalar registers
+    static_assert(sizeof(GemmP) % 4 == 0, "copied as 32-bit words");
+    uint32_t words[sizeof(GemmP) / 4];
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(p_in.group + g);
+#pragma unroll
+    for (uint32_t w = 0; w < sizeof(GemmP) / 4; ++w) words[w] = __builtin_amdgcn_readfirstlane(src[w]);
+    __builtin_memcpy(&p, words, sizeof(GemmP));
+  }
   const uint32_t total_tiles = p.tiles_m * p.tiles_n;
   auto tile_of = [&](uint32_t pid, uint32_t& tm, uint32_t& tn) { gemm_tile_of(p, total_tiles, pid, tm, tn); };
   const uint32_t bo = blockIdx.z / p.batch_inner, bi = blockIdx.z % p.batch_inner;
@@ -417,7 +436,7 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
   const uint32_t my_x = blockIdx.x & 7u;
   auto tiles_of_xcd = [&](uint32_t x) { return gemm_tiles_of_xcd(total_tiles, x); };
   auto steal = [&]() -> uint32_t { return gemm_steal_tile(ctl.rec, total_tiles, my_x); };
-  uint32_t pid = blockIdx.x;
+  uint32_t pid = blockIdx.x - p.tile_base;
   if (dynamic) {
     if (threadIdx.x == 0) s_next = steal();
     __syncthreads();
@@ -613,7 +632,8 @@ bool gemm_big_tiles(const sif_gemm_args& a) {
   return t256 < t128;
 }
 
-sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KCtl& ctl) {
+// checks one product's arguments and fills its kernel record; *big: the 256x256 configuration was chosen
+static sif_status gemm_fill(const sif_gemm_args* a, GemmP& p, bool* big_out) {
   if (a == nullptr || a->struct_size != sizeof(sif_gemm_args)) return fail(SIF_E_INVAL, "gemm: bad args struct");
   if (a->m == 0 || a->n == 0 || a->k == 0) return fail(SIF_E_INVAL, "gemm: empty extent");
   if (a->a_layout > 1 || a->b_layout > 1) return fail(SIF_E_INVAL, "gemm: bad layout");
@@ -643,7 +663,6 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
   const bool big = gemm_big_tiles(*a);
   const uint32_t bm = big ? 256 : 128, bn = bm;
-  GemmP p;
   p.a = (const bf16_t*)a->a_dev; p.b = (const bf16_t*)a->b_dev; p.c = a->c_dev;
   p.bias = (a->epilogue & (SIF_EPI_BIAS | SIF_EPI_GELU)) ? (const bf16_t*)a->bias_dev : nullptr;
   p.res = a->res_dev; p.aux = (bf16_t*)a->aux_dev;
@@ -652,7 +671,23 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
   p.a_so = a->a_stride_outer; p.a_si = a->a_stride_inner; p.b_so = a->b_stride_outer; p.b_si = a->b_stride_inner;
   p.c_so = a->c_stride_outer; p.c_si = a->c_stride_inner; p.alpha = a->alpha;
   p.tiles_n = (a->n + bn - 1) / bn; p.tiles_m = (a->m + bm - 1) / bm;
+  p.group = nullptr; p.group_n = 0; p.tile_base = 0;
   if (batches > 65535) return fail(SIF_E_INVAL, "gemm: grid too large");
+  *big_out = big;
+  return SIF_OK;
+}
+
+typedef void (*gemm_kern_fn)(GemmP, KCtl);
+static const gemm_kern_fn kGemm128[2][2] = {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>},
+                                            {gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>}};
+static const gemm_kern_fn kGemm256[2][2] = {{gemm_bf16_kernel<0, 0, 256, 256, 2, 4, false>, gemm_bf16_kernel<0, 1, 256, 256, 2, 4, false>},
+                                            {gemm_bf16_kernel<1, 0, 256, 256, 2, 4, false>, gemm_bf16_kernel<1, 1, 256, 256, 2, 4, false>}};
+
+sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KCtl& ctl) {
+  GemmP p;
+  bool big = false;
+  if (sif_status st = gemm_fill(a, p, &big)) return st;
+  const uint64_t batches = (uint64_t)a->batch_outer * a->batch_inner;
   // 256x256 tiles: one block per CU, each working through every (number of CUs)-th tile; a stride that is a multiple of
   // 8 keeps a block on the tiles of its own XCD
   uint32_t grid_x = p.tiles_m * p.tiles_n;
@@ -665,14 +700,44 @@ sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t stream, const KC
     if (grid_x > cus) grid_x = cus;
   }
   dim3 grid(grid_x, 1, (uint32_t)batches);
-  typedef void (*gemm_kern_fn)(GemmP, KCtl);
-  static const gemm_kern_fn table[2][2] = {{gemm_bf16_kernel<0, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<0, 1, 128, 128, 2, 2, true>},
-                                           {gemm_bf16_kernel<1, 0, 128, 128, 2, 2, true>, gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true>}};
-  static const gemm_kern_fn table256[2][2] = {{gemm_bf16_kernel<0, 0, 256, 256, 2, 4, false>, gemm_bf16_kernel<0, 1, 256, 256, 2, 4, false>},
-                                              {gemm_bf16_kernel<1, 0, 256, 256, 2, 4, false>, gemm_bf16_kernel<1, 1, 256, 256, 2, 4, false>}};
-  if (big) hipLaunchKernelGGL(table256[a->a_layout][a->b_layout], grid, dim3(512), 0, stream, p, ctl);
-  else hipLaunchKernelGGL(table[a->a_layout][a->b_layout], grid, dim3(256), 0, stream, p, ctl);
+  if (big) hipLaunchKernelGGL(kGemm256[a->a_layout][a->b_layout], grid, dim3(512), 0, stream, p, ctl);
+  else hipLaunchKernelGGL(kGemm128[a->a_layout][a->b_layout], grid, dim3(256), 0, stream, p, ctl);
   return check_launch("gemm_bf16");
+}
+
+// Several products of the same operand layouts as ONE launch of 128x128 tiles (the weight gradients of a layer: each
+// by itself has too few tiles for the chip and would have to be cut along K, with fp32 partial results written, read
+// again and summed; together they fill it).  gemm_group_fill checks the products and writes their kernel records, to
+// be copied to `gemm_group_bytes(n)` bytes of device memory once; launch_gemm_bf16_group then takes that copy.
+uint64_t gemm_group_bytes(uint32_t n) { return (uint64_t)n * sizeof(GemmP); }
+
+sif_status gemm_group_fill(const sif_gemm_args* list, uint32_t n, void* host_records, uint32_t* grid_out) {
+  if (list == nullptr || n == 0 || n > 16 || host_records == nullptr || grid_out == nullptr) return fail(SIF_E_INVAL, "gemm group: bad arguments");
+  GemmP* rec = static_cast<GemmP*>(host_records);
+  uint32_t base = 0;
+  for (uint32_t i = 0; i < n; ++i) {
+    sif_gemm_args a = list[i];
+    a.tile = 128;
+    if (a.a_layout != list[0].a_layout || a.b_layout != list[0].b_layout) return fail(SIF_E_INVAL, "gemm group: the products must share their operand layouts");
+    if ((uint64_t)a.batch_outer * a.batch_inner != 1) return fail(SIF_E_INVAL, "gemm group: no batched products");
+    bool big = false;
+    if (sif_status st = gemm_fill(&a, rec[i], &big)) return st;
+    rec[i].tile_base = base;
+    base += (rec[i].tiles_m * rec[i].tiles_n + 7u) & ~7u;       // a multiple of 8 keeps the tile order's idea of the XCDs
+  }
+  *grid_out = base;
+  return SIF_OK;
+}
+
+sif_status launch_gemm_bf16_group(const void* dev_records, uint32_t n, uint32_t grid, uint32_t a_layout, uint32_t b_layout, hipStream_t stream, const KCtl& ctl) {
+  if (dev_records == nullptr || n == 0 || grid == 0 || a_layout > 1 || b_layout > 1) return fail(SIF_E_INVAL, "gemm group: bad arguments");
+  GemmP head = {};
+  head.group = static_cast<const GemmP*>(dev_records);
+  head.group_n = n;
+  // (instantiated for the layouts of weight gradients, A [K][M] and B [K][N]; other layouts would need their own)
+  if (a_layout != SIF_A_ROW_M || b_layout != SIF_B_ROW_N) return fail(SIF_E_INVAL, "gemm group: only A stored [K][M] with B stored [K][N]");
+  hipLaunchKernelGGL((gemm_bf16_kernel<1, 1, 128, 128, 2, 2, true, true>), dim3(grid), dim3(256), 0, stream, head, ctl);
+  return check_launch("gemm_bf16_group");
 }
 
 }  // namespace sif

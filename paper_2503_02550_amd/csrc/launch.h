@@ -16,6 +16,11 @@ inline KCtl no_ctl() { KCtl c{}; return c; }
 
 // Internal launchers: same argument checks as the public sif_k_* entry points, plus the monitor control block.
 sif_status launch_gemm_bf16(const sif_gemm_args* a, hipStream_t s, const KCtl& c);
+// several products of the same operand layouts as one launch of 128x128 tiles: fill the kernel records on the host
+// (gemm_group_bytes(n) bytes), copy them to device memory once, launch with that copy
+uint64_t gemm_group_bytes(uint32_t n);
+sif_status gemm_group_fill(const sif_gemm_args* list, uint32_t n, void* host_records, uint32_t* grid_out);
+sif_status launch_gemm_bf16_group(const void* dev_records, uint32_t n, uint32_t grid, uint32_t a_layout, uint32_t b_layout, hipStream_t s, const KCtl& c);
 // whether the product may run, and whether it will run, on 256x256 tiles (else 128x128)
 bool gemm_can_use_big_tiles(const sif_gemm_args& a);
 bool gemm_big_tiles(const sif_gemm_args& a);

@@ -242,6 +242,50 @@ static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t*
                          .batch(1, splits, 0, (int64_t)kper * m_out, 0, (int64_t)kper * n_out, 0, (int64_t)m_out * n_out).k_limit(tokens));
 }
 
+// The four weight gradients of a layer as ONE launch (gemm_group_fill / launch_gemm_bf16_group): each by itself has too
+// few 128x128 tiles for the chip and is cut along K above, with fp32 partial results written, read again and summed
+// (1.25 GB per step of the 12-layer decoder); together they are 432 tiles over the whole K, no partial results.  The
+// products' operands (the incoming gradient, dz, the gradient between the two halves of the layer, dqkv, the saved
+// activations) are all still in place when the last of them, dqkv, has been computed.  GroupPlan hands out device
+// memory for the launches' kernel records, which are written once, when the plan is built.
+struct GroupPlan {
+  unsigned char* pool = nullptr;
+  uint64_t pool_bytes = 0, used = 0;
+  sif_status status = SIF_OK;
+};
+struct WgradItem { const bf16_t* a; const bf16_t* b; bf16_t* dw; uint32_t m_out, n_out; };
+
+static bool emit_wgrad_group(Plan& p, const char* name, const WgradItem* items, uint32_t n, uint32_t tokens, uint32_t acc, GroupPlan& gp) {
+  const uint64_t bytes = gemm_group_bytes(n);
+  if (gp.pool == nullptr || gp.used + bytes > gp.pool_bytes || n > 8) return false;
+  sif_gemm_args list[8];
+  double cost = 0.0, flops = 0.0;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (items[i].n_out & 7) return false;
+    G g(items[i].a, items[i].b, items[i].dw, items[i].m_out, items[i].n_out, tokens, items[i].m_out, items[i].n_out, items[i].n_out);
+    g.lay(SIF_A_ROW_M, SIF_B_ROW_N);
+    if (acc) g.epi(SIF_EPI_RESIDUAL, nullptr, items[i].dw);      // micro-batch accumulation: add to the stored gradient
+    list[i] = g.a;
+    cost += gemm_cost_us(g.a) - 4.0;
+    flops += gemm_flops(g.a);
+  }
+  std::vector<unsigned char> host(bytes);
+  uint32_t grid = 0;
+  if (gemm_group_fill(list, n, host.data(), &grid) != SIF_OK) return false;
+  unsigned char* dev = gp.pool + gp.used;
+  gp.used += (bytes + 255) & ~uint64_t(255);
+  const hipError_t e = hipMemcpy(dev, host.data(), bytes, hipMemcpyHostToDevice);
+  if (e != hipSuccess) { gp.status = fail_hip(e, "training plan: upload of a weight-gradient group"); return false; }
+  Op op;
+  op.name = name;
+  op.fn = [dev, n, grid](hipStream_t s, const KCtl& c) { return launch_gemm_bf16_group(dev, n, grid, SIF_A_ROW_M, SIF_B_ROW_N, s, c); };
+  op.cost_us = cost + 4.0;
+  op.prof_class = (int32_t)(SIF_A_ROW_M * 2 + SIF_B_ROW_N);
+  op.flops = flops;
+  p.push_back(std::move(op));
+  return true;
+}
+
 // Column sums (bias gradients) and the LayerNorm parameter gradients are computed as per-block partial sums by
 // the kernel that reads the rows, and finalized by ONE launch at the end of a backward pass instead of one small
 // launch each (49 per step of the 12-layer decoder).  FinPlan hands every producer its own partial buffer and
@@ -406,17 +450,20 @@ static void emit_decoder_layer_fwd(Plan& p, const Dims& q, const LayerW& w, cons
 // db_proj_below: where this layer's last kernel puts the b_proj gradient of the layer below (null: none).
 static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, const LayerG& g, const bf16_t* x_in, const LayerActs& a,
                                    const Scratch& sc, const bf16_t* dx_out, bf16_t* dx_mid, bf16_t* dx_in, const TpSites& tp, uint32_t acc,
-                                   bool have_db_proj, bf16_t* db_proj_below, FinPlan& fp, RedPlan& rp) {
+                                   bool have_db_proj, bf16_t* db_proj_below, FinPlan& fp, RedPlan& rp, GroupPlan& gp) {
   const uint32_t M = q.M, d = q.d, f = q.f, da = q.da;
+  // the layer's weight gradients as one launch where that can be had (below, once dqkv is there), else one by one
+  const WgradItem wg[4] = {{dx_out, a.a, g.w_proj, d, f}, {sc.dz, a.ln2, g.w_fc, f, d}, {dx_mid, a.o, g.w_o, d, da}, {sc.dqkv, a.ln1, g.w_qkv, 3 * da, d}};
+  const bool grouped = gp.pool != nullptr && gp.used + gemm_group_bytes(4) <= gp.pool_bytes && !((f | d | da) & 7);
   if (!have_db_proj) emit_colsum(p, "db_proj", dx_out, d, g.b_proj, fp, M, d);
-  emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, rp, acc);
+  if (!grouped) emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, rp, acc);
   emit_gemm(p, "dz", G(dx_out, w.w_proj, sc.dz, M, f, d, d, f, f).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_GELU_GRAD, nullptr, nullptr, a.z));
   emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, fp, M, f);
-  emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, rp, acc);
+  if (!grouped) emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, rp, acc);
   emit_gemm(p, "dln2", G(sc.dz, w.w_fc, sc.dln, M, d, f, f, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
   emit_ln_bwd(p, sc.dln, a.x_mid, w.ln2_g, a.m2, a.r2, dx_out, dx_mid, g.ln2_g, g.ln2_b, g.b_o, fp, M, d);
-  emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, rp, acc);
+  if (!grouped) emit_wgrad(p, "dw_o", dx_mid, a.o, g.w_o, d, da, M, rp, acc);
   emit_gemm(p, "do", G(dx_mid, w.w_o, sc.d_o, M, da, d, d, da, da).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (fused_attention(q.dh)) {
     const uint32_t B = q.B, S = q.S, H = q.H, dh = q.dh;
@@ -430,7 +477,12 @@ static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, cons
     emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
   }
   emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, fp, M, 3 * da);
-  emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, rp, acc);
+  if (grouped) {
+    if (!emit_wgrad_group(p, "dw_layer", wg, 4, M, acc, gp) && gp.status == SIF_OK)
+      gp.status = fail(SIF_E_INVAL, "training plan: the weight gradients of a layer could not be set up as one launch");
+  } else {
+    emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, rp, acc);
+  }
   emit_gemm(p, "dln1", G(sc.dqkv, w.w_qkv, sc.dln, M, d, 3 * da, 3 * da, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
   emit_ln_bwd(p, sc.dln, x_in, w.ln1_g, a.m1, a.r1, dx_mid, dx_in, g.ln1_g, g.ln1_b, db_proj_below, fp, M, d);
@@ -520,9 +572,18 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   fp.pool_floats = (uint64_t)colsum_parts(M) * ((uint64_t)s.n_layers * (6 * d + q.f + 3 * q.da) + 3 * d);
   fp.pool = (float*)ar.take(fp.pool_floats * 4);
   fp.dev = (FinItem*)ar.take((uint64_t)fp.max_items * sizeof(FinItem));
+  // the weight gradients: one launch per layer and backward pass where the widths allow it (then there are no K slices
+  // to sum, and no buffer for them), else each product by itself, cut along K
+  GroupPlan gp;
+  const bool group_wgrads = !((q.f | d | q.da) & 7);
+  if (group_wgrads) {
+    // (a pipeline stage emits one backward pass per micro-batch and one more to estimate its duration)
+    gp.pool_bytes = (uint64_t)s.n_layers * (pp ? tm.desc.pp_micro + 1 : 1) * ((gemm_group_bytes(4) + 255) & ~uint64_t(255));
+    gp.pool = (unsigned char*)ar.take(gp.pool_bytes);
+  }
   RedPlan rp;
   rp.max_items = 4 * s.n_layers;
-  {
+  if (!group_wgrads) {
     const uint32_t da = q.da, f = q.f;
     const uint64_t per_layer = (uint64_t)d * f * wgrad_splits(d, f, M) + (uint64_t)f * d * wgrad_splits(f, d, M) +
                                (uint64_t)d * da * wgrad_splits(d, da, M) + (uint64_t)3 * da * d * wgrad_splits(3 * da, d, M);
@@ -682,7 +743,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       const bf16_t* xin_l = (l == 0) ? x0[sl] : acts[sl][l - 1].x_out;
       const bool have_db_proj = s.vocab != 0 || l + 1 < (int32_t)s.n_layers;     // the final LayerNorm or the layer above wrote it
       bf16_t* below = l > 0 ? grads + pm.at(L((uint32_t)l - 1, "b_proj")) : nullptr;
-      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc, have_db_proj, below, fp, rp);
+      emit_decoder_layer_bwd(p, q, w, g, xin_l, acts[sl][l], sc, dx, sc.dx_b, sc.dx_a, tp, acc, have_db_proj, below, fp, rp, gp);
       dx = sc.dx_a;
       const size_t grp = s.n_layers - 1 - (size_t)l;
       if (overlap && closes_bucket(grp)) {       // the bucket is complete: finalize what it holds, its exchange can start
@@ -800,6 +861,7 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
     tm.pp_times_estimated = tm.desc.pp_tf_ns == 0 || tm.desc.pp_tb_ns == 0;
   }
   if (fp.overflow || rp.overflow) return fail(SIF_E_INVAL, "training plan: a partial-result pool does not match the plan");
+  if (gp.status != SIF_OK) return gp.status;
   if (!rp.items.empty()) {
     hipError_t e = hipMemcpy(rp.dev, rp.items.data(), rp.items.size() * sizeof(RedItem), hipMemcpyHostToDevice);
     if (e != hipSuccess) return fail_hip(e, "training plan: upload of the split-product table");
