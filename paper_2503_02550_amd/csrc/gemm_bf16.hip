@@ -517,8 +517,10 @@ __global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_ker
     // its middle, so that the accumulators stay in the same registers throughout; an odd last tile is done after it.
     const uint32_t nt = (k_end - k_begin + BK - 1) / BK;
     uint32_t l_own = 0;
-    // without EDGE the launcher guarantees that every tile is interior
-    const bool interior = !EDGE || (m0 + BM <= p.m && n0 + BN <= p.n && ((k_end - k_begin) % BK) == 0);
+    // Whole K steps take the direct fetches, also in a tile that is ragged in M or N (its missing rows fetch the tile's
+    // first row and are never stored); a ragged K needs the zero fill of the register path.  Without EDGE the launcher
+    // guarantees whole K steps.
+    const bool interior = !EDGE || ((k_end - k_begin) % BK) == 0;
     if (interior) {
       // tile t+1 is fetched into the other pair of buffers while tile t is multiplied; the other block of the CU
       // covers what the fetch latency exceeds one K step

@@ -248,12 +248,16 @@ static void emit_wgrad(Plan& p, const char* name, const bf16_t* a, const bf16_t*
 // products' operands (the incoming gradient, dz, the gradient between the two halves of the layer, dqkv, the saved
 // activations) are all still in place when the last of them, dqkv, has been computed.  GroupPlan hands out device
 // memory for the launches' kernel records, which are written once, when the plan is built.
+// A bias gradient (the column sums of a gradient over the tokens) rides along as one more product of the group: the
+// left operand is `ones`, [tokens][8] with 1 in column 0, the result one row; its few tiles take block slots the weight
+// gradients leave idle, and the launch that would read the gradient once more for the sums is not needed.
 struct GroupPlan {
   unsigned char* pool = nullptr;
   uint64_t pool_bytes = 0, used = 0;
+  const bf16_t* ones = nullptr;
   sif_status status = SIF_OK;
 };
-struct WgradItem { const bf16_t* a; const bf16_t* b; bf16_t* dw; uint32_t m_out, n_out; };
+struct WgradItem { const bf16_t* a; const bf16_t* b; bf16_t* dw; uint32_t m_out, n_out, lda; };
 
 static bool emit_wgrad_group(Plan& p, const char* name, const WgradItem* items, uint32_t n, uint32_t tokens, uint32_t acc, GroupPlan& gp) {
   const uint64_t bytes = gemm_group_bytes(n);
@@ -262,7 +266,7 @@ static bool emit_wgrad_group(Plan& p, const char* name, const WgradItem* items, 
   double cost = 0.0, flops = 0.0;
   for (uint32_t i = 0; i < n; ++i) {
     if (items[i].n_out & 7) return false;
-    G g(items[i].a, items[i].b, items[i].dw, items[i].m_out, items[i].n_out, tokens, items[i].m_out, items[i].n_out, items[i].n_out);
+    G g(items[i].a, items[i].b, items[i].dw, items[i].m_out, items[i].n_out, tokens, items[i].lda, items[i].n_out, items[i].n_out);
     g.lay(SIF_A_ROW_M, SIF_B_ROW_N);
     if (acc) g.epi(SIF_EPI_RESIDUAL, nullptr, items[i].dw);      // micro-batch accumulation: add to the stored gradient
     list[i] = g.a;
@@ -453,12 +457,16 @@ static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, cons
                                    bool have_db_proj, bf16_t* db_proj_below, FinPlan& fp, RedPlan& rp, GroupPlan& gp) {
   const uint32_t M = q.M, d = q.d, f = q.f, da = q.da;
   // the layer's weight gradients as one launch where that can be had (below, once dqkv is there), else one by one
-  const WgradItem wg[4] = {{dx_out, a.a, g.w_proj, d, f}, {sc.dz, a.ln2, g.w_fc, f, d}, {dx_mid, a.o, g.w_o, d, da}, {sc.dqkv, a.ln1, g.w_qkv, 3 * da, d}};
-  const bool grouped = gp.pool != nullptr && gp.used + gemm_group_bytes(4) <= gp.pool_bytes && !((f | d | da) & 7);
+  // (with them the gradients of b_fc and b_qkv, where the plan has the operand for that)
+  const WgradItem wg[6] = {{dx_out, a.a, g.w_proj, d, f, d}, {sc.dz, a.ln2, g.w_fc, f, d, f}, {dx_mid, a.o, g.w_o, d, da, d},
+                           {sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, 3 * da}, {gp.ones, sc.dz, g.b_fc, 1, f, 8}, {gp.ones, sc.dqkv, g.b_qkv, 1, 3 * da, 8}};
+  const uint32_t n_group = gp.ones != nullptr ? 6 : 4;
+  const bool grouped = gp.pool != nullptr && gp.used + gemm_group_bytes(n_group) <= gp.pool_bytes && !((f | d | da) & 7);
+  const bool bias_grouped = grouped && n_group == 6;
   if (!have_db_proj) emit_colsum(p, "db_proj", dx_out, d, g.b_proj, fp, M, d);
   if (!grouped) emit_wgrad(p, "dw_proj", dx_out, a.a, g.w_proj, d, f, M, rp, acc);
   emit_gemm(p, "dz", G(dx_out, w.w_proj, sc.dz, M, f, d, d, f, f).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_GELU_GRAD, nullptr, nullptr, a.z));
-  emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, fp, M, f);
+  if (!bias_grouped) emit_colsum(p, "db_fc", sc.dz, f, g.b_fc, fp, M, f);
   if (!grouped) emit_wgrad(p, "dw_fc", sc.dz, a.ln2, g.w_fc, f, d, M, rp, acc);
   emit_gemm(p, "dln2", G(sc.dz, w.w_fc, sc.dln, M, d, f, f, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N));
   if (tp.on) emit_bubble(p, (*tp.next)++, tp.ns);
@@ -476,9 +484,9 @@ static void emit_decoder_layer_bwd(Plan& p, const Dims& q, const LayerW& w, cons
   } else {
     emit_attention_bwd(p, q, a.qkv, a.prob, sc.d_o, sc.scores, sc.ds, sc.dqkv);
   }
-  emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, fp, M, 3 * da);
+  if (!bias_grouped) emit_colsum(p, "db_qkv", sc.dqkv, 3 * da, g.b_qkv, fp, M, 3 * da);
   if (grouped) {
-    if (!emit_wgrad_group(p, "dw_layer", wg, 4, M, acc, gp) && gp.status == SIF_OK)
+    if (!emit_wgrad_group(p, "dw_layer", wg, n_group, M, acc, gp) && gp.status == SIF_OK)
       gp.status = fail(SIF_E_INVAL, "training plan: the weight gradients of a layer could not be set up as one launch");
   } else {
     emit_wgrad(p, "dw_qkv", sc.dqkv, a.ln1, g.w_qkv, 3 * da, d, M, rp, acc);
@@ -578,8 +586,16 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
   const bool group_wgrads = !((q.f | d | q.da) & 7);
   if (group_wgrads) {
     // (a pipeline stage emits one backward pass per micro-batch and one more to estimate its duration)
-    gp.pool_bytes = (uint64_t)s.n_layers * (pp ? tm.desc.pp_micro + 1 : 1) * ((gemm_group_bytes(4) + 255) & ~uint64_t(255));
+    gp.pool_bytes = (uint64_t)s.n_layers * (pp ? tm.desc.pp_micro + 1 : 1) * ((gemm_group_bytes(6) + 255) & ~uint64_t(255));
     gp.pool = (unsigned char*)ar.take(gp.pool_bytes);
+    bf16_t* ones = (bf16_t*)ar.take((uint64_t)M * 8 * 2);
+    if (ones != nullptr) {
+      std::vector<uint16_t> h((size_t)M * 8, 0);
+      for (uint32_t t = 0; t < M; ++t) h[(size_t)t * 8] = 0x3F80;      // bf16 1.0
+      const hipError_t e = hipMemcpy(ones, h.data(), h.size() * 2, hipMemcpyHostToDevice);
+      if (e != hipSuccess) return fail_hip(e, "training plan: upload of the bias-gradient operand");
+      gp.ones = ones;
+    }
   }
   RedPlan rp;
   rp.max_items = 4 * s.n_layers;
