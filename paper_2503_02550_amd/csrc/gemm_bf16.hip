@@ -388,8 +388,12 @@ __device__ __forceinline__ uint32_t gemm_steal_tile(StreamRec* rec, uint32_t tot
   return kNone;
 }
 
+// Registers: two wavefronts per SIMD may take 256 of its 512 each, and the 256x256 configuration would.  It is held to
+// 248 (the attribute counts in pairs): a one-wavefront kernel that sits on a CU for the length of a bubble (the
+// training stream's wait) then still fits beside a block, which otherwise stays off that CU, and the tiles of 255 CUs
+// end a round later (65536 x 768 x 768: 92 -> 153 us beside such a wavefront, 92 with the limit).
 template <int ALAY, int BLAY, int BM, int BN, int WM, int WN, bool EDGE, bool GROUPED = false>
-__global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) void gemm_bf16_kernel(GemmP p_in, KCtl ctl) {
+__global__ __launch_bounds__(64 * WM * WN, BM == 128 ? 2 : 1) __attribute__((amdgpu_num_vgpr(124))) void gemm_bf16_kernel(GemmP p_in, KCtl ctl) {
   static_assert(!GROUPED || EDGE, "several products in one launch: one block per tile");
   // (an instantiation of its own for launches over several products: in the others the product's record stays the
   // kernel argument, in scalar registers)
