@@ -67,6 +67,7 @@ struct sif_ctx {
 
   // barrier thread state
   std::deque<InFlight> inflight;
+  uint64_t head_since_ns = 0;       // host time at which the kernel at the head of `inflight` got there
   std::deque<Job*> run_online, run_offline;
   std::vector<std::unique_ptr<Job>> groups;      // coalesced jobs in flight (guarded by mu)
   std::vector<KbTokens> tokens;                  // per offline instance: what is left of the period's grant
@@ -299,6 +300,14 @@ static void process_gate_checks(sif_ctx* c, bool last_pass) {
   }
 }
 
+// Of the predicted time of what is in flight, the part the kernel at the head has behind it: it runs since it got to
+// the head, inside a bubble not before the bubble's edge; at most nine tenths of its prediction are taken off.
+static uint64_t head_elapsed_ns(sif_ctx* c) {
+  if (c->inflight.empty()) return 0;
+  const uint64_t begin = std::max(c->head_since_ns, c->edge_host_ns.load(std::memory_order_relaxed)), now = host_now_ns();
+  return now > begin ? std::min<uint64_t>(now - begin, 900ull * c->inflight.front().cost_us) : 0;
+}
+
 static double job_cost_us(const Job* j) {
   double s = 0;
   for (const Op& o : j->plan) s += o.cost_us;
@@ -333,6 +342,7 @@ static void barrier_main(sif_ctx* c) {
         }
       }
       c->inflight.pop_front();
+      c->head_since_ns = host_now_ns();
       c->outstanding_us = c->outstanding_us > f.cost_us ? c->outstanding_us - f.cost_us : 0;      // exactly what its launch added
       if (f.check_gate) c->gate_pending.push_back(sif_ctx::GateCheck{f.kseq, 0, host_now_ns() + 200000000ull, 0, 0, false});
       if (++f.job->done_ops == f.job->plan.size()) {
@@ -509,7 +519,8 @@ static void barrier_main(sif_ctx* c) {
         if (gated && !online && !beside && j->plan[j->next_op].row_split) {
           const Op& whole = j->plan[j->next_op];
           // what is in flight takes its predicted time plus the gap between dependent kernels of a stream, each
-          const uint64_t rest_ns = predicted_remaining_ns(c), ahead_ns = c->outstanding_us * 1000ull + 5000ull * c->inflight.size();
+          // (less what the kernel at the head has already run)
+          const uint64_t rest_ns = predicted_remaining_ns(c), ahead_ns = c->outstanding_us * 1000ull + 5000ull * c->inflight.size() - head_elapsed_ns(c);
           if (rest_ns > ahead_ns) {
             const double avail_us = (double)(rest_ns - ahead_ns) / 1000.0 - 10.0;
             const uint32_t unit = gemm_round_rows(whole.gemm);
@@ -533,7 +544,7 @@ static void barrier_main(sif_ctx* c) {
         // What the device gate is bound to refuse is not launched: behind what is in flight (its predicted time and the
         // gap after each kernel), this kernel would end after the predicted end of the bubble.  The gate still decides;
         // this spares launches whose empty blocks would pass through the CUs beside the training kernels that follow.
-        if (gated && !beside && !kb_fits_bubble(predicted_remaining_ns(c), c->outstanding_us, c->inflight.size(), op.cost_us)) break;
+        if (gated && !beside && !kb_fits_bubble(predicted_remaining_ns(c), c->outstanding_us - head_elapsed_ns(c) / 1000ull, c->inflight.size(), op.cost_us)) break;
         const uint32_t id = (uint32_t)(((j->ticket & 0xFFF) << 16) | (j->next_op & 0xFFFF));
         KCtl k = make_ctl(c, c->I, kKindInfer, id, gated ? c->T.rec : nullptr, (uint32_t)c->ns_to_ticks((uint64_t)(op.cost_us * 1000.0)));
         const bool last_of_job = j->next_op + 1 == j->plan.size();
@@ -565,6 +576,7 @@ static void barrier_main(sif_ctx* c) {
           break;
         }
         c->kernels_launched.fetch_add(1, std::memory_order_relaxed);
+        if (c->inflight.empty()) c->head_since_ns = host_now_ns();
         c->inflight.push_back(InFlight{k.kseq, j, j->next_op, mload(&c->mir->idle_seq), cost, ev, gated && !beside});
         j->next_op++;
         c->outstanding_us += cost;
