@@ -36,7 +36,7 @@ HBM_PEAK_TBPS = 8.0
 # Average bytes per dispatch of gemm_bf16_kernel<0,0> that pass between the L2s and the memory side in the headline
 # workload, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in the file named beside it (counters cannot be
 # read from inside a timed run).
-GEMM00_HBM_BYTES_PER_LAUNCH = 380.2e6
+GEMM00_HBM_BYTES_PER_LAUNCH = 384.7e6
 GEMM00_HBM_BYTES_SOURCE = "constant from profiles/bench_cfg2_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)"
 N_RING = 64          # distinct input / output buffers the queued requests cycle through (a coalesced group is 16)
 
