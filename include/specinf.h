@@ -349,8 +349,9 @@ typedef struct sif_config {
                                 launch back to the host (it is run again).  Tests set 0 < value <= 30 small to force
                                 that path; every kernel still exits normally.                                  */
   uint32_t gate_spin_every;  /* 0 or 1: gate_spin_log2 applies to every launch; n > 1: only to launches whose number on
-                                the inference stream is a multiple of n (the others wait the default time), so that a
-                                launch that was given back gets through when it is run again                    */
+                                the inference stream is a multiple of n, and not to the run that follows a launch
+                                which came back (the others wait the default time), so that such a launch gets
+                                through when it is run again                                                    */
 } sif_config;
 
 /* Fills *cfg with the defaults (P = 5 us, W = 64, alpha 1, beta 3, gamma 2, m 1, t0 = 200, LL = 400, UL = 800

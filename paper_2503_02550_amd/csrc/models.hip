@@ -90,6 +90,7 @@ struct G {
   G& alpha(float v) { a.alpha = v; return *this; }
   G& causal(uint32_t kc) { a.k_causal = kc; return *this; }
   G& k_limit(uint32_t kl) { a.k_limit = kl; return *this; }
+  G& tile(uint32_t t) { a.tile = t; return *this; }
 };
 
 // scratch buffers of the backward pass, shared by all layers
@@ -648,6 +649,30 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       head_item = (RedItem*)ar.take(sizeof(RedItem));
     }
   }
+  // The LM head's weight gradient [V][d] over K = the tokens, on 256x256 tiles with one block per CU: a last round
+  // that few of the CUs take part in costs as much as a full one (50257 x 768: 591 tiles = 2.3 rounds, paid as three).
+  // The tile rows of the whole rounds are then one launch and the rest a second one, cut along K into as many slices
+  // as still fit one round, with fp32 partial results that a small launch sums (510 tiles, then 81 tiles x 3 slices).
+  uint32_t wte_tail_row0 = 0, wte_tail_rows = 0, wte_tail_splits = 1, wte_tail_kper = 0;
+  float* wte_tail_part = nullptr;
+  RedItem* wte_tail_item = nullptr;
+  if (s.vocab && (M % 64) == 0 && (d % 8) == 0) {
+    const uint32_t tm_all = (s.vocab + 255) / 256, tn_all = (d + 255) / 256, tiles_all = tm_all * tn_all, steps = M / 64;
+    const uint32_t main_tm = tiles_all / 256 * 256 / tn_all, tail_tm = tm_all - main_tm;
+    if (tiles_all > 256 && main_tm > 0 && tail_tm > 0 && tail_tm * tn_all <= 128) {
+      uint32_t k = std::min<uint32_t>(std::min<uint32_t>(8u, 256u / (tail_tm * tn_all)), steps);
+      const uint32_t kper = (steps + k - 1) / k * 64;
+      while (k > 1 && (uint64_t)(k - 1) * kper >= M) --k;
+      const uint32_t rows = s.vocab - main_tm * 256;
+      // the launcher's timing model: one more whole round against a round of K / k steps and the sum of the slices
+      const double t_whole = 4.0 + 1.75 * steps, t_cut = 4.0 + 1.75 * (kper / 64.0) + bytes_cost_us(4.0 * rows * d * k) + 8.0;
+      if (k > 1 && t_cut < 0.8 * t_whole) {
+        wte_tail_row0 = main_tm * 256; wte_tail_rows = rows; wte_tail_splits = k; wte_tail_kper = kper;
+        wte_tail_part = (float*)ar.take((uint64_t)k * rows * d * 4);
+        wte_tail_item = (RedItem*)ar.take(sizeof(RedItem));
+      }
+    }
+  }
   if (s.vocab) {
     lnf = (bf16_t*)ar.take((uint64_t)M * d * 2);
     logits = (bf16_t*)ar.take((uint64_t)M * Vp * 2);
@@ -795,7 +820,21 @@ static sif_status build_decoder_train(TrainModel& tm, Arena& ar, hipStream_t str
       emit_gemm(p, "lm_head", G(lnf, wte, logits, M, n_head, d, d, d, Vp));
       emit(p, "xent", bytes_cost_us(4.0 * M * Vp), [=](hipStream_t s2, const KCtl& c) { return launch_xent(logits, (const int32_t*)t->cur_targets, loss_tok, M, V, Vp, s2, c); });
       emit(p, "loss", 4.0, [=](hipStream_t s2, const KCtl& c) { return launch_reduce_sum(loss_tok, t->cur_loss ? t->cur_loss : loss, M, 1.0f / (float)M, s2, c); });
-      emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+      if (wte_tail_splits > 1) {
+        bf16_t* dwte = grads + pm.at("wte");
+        const uint32_t r0 = wte_tail_row0, rows = wte_tail_rows, kper = wte_tail_kper, ks = wte_tail_splits;
+        emit_gemm(p, "dwte_head", G(logits, lnf, dwte, r0, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N).tile(256));
+        emit_gemm(p, "dwte_head_tail", G(logits + r0, lnf, wte_tail_part, rows, d, kper, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32).tile(256)
+                                           .batch(1, ks, 0, (int64_t)kper * Vp, 0, (int64_t)kper * d, 0, (int64_t)rows * d).k_limit(M));
+        RedItem it;
+        it.part = wte_tail_part; it.out = dwte + (size_t)r0 * d; it.n = (uint64_t)rows * d; it.splits = ks; it.pad = 0;
+        hipError_t e2 = hipMemcpy(wte_tail_item, &it, sizeof(it), hipMemcpyHostToDevice);
+        if (e2 != hipSuccess) return fail_hip(e2, "training plan: upload of the LM-head weight gradient's slice table");
+        const RedItem* ti = wte_tail_item;
+        emit(p, "dwte_head_sum", bytes_cost_us(4.0 * rows * d * ks + 2.0 * rows * d), [=](hipStream_t s2, const KCtl& c) { return launch_reduce_splits_batch(ti, 1, 0, s2, c); });
+      } else {
+        emit_gemm(p, "dwte_head", G(logits, lnf, grads + pm.at("wte"), V, d, M, Vp, d, d).lay(SIF_A_ROW_M, SIF_B_ROW_N));
+      }
       if (head_splits > 1) {
         emit_gemm(p, "dlnf", G(logits, wte, head_part, M, d, head_kper, Vp, d, d).lay(SIF_A_ROW_K, SIF_B_ROW_N).epi(SIF_EPI_OUT_F32)
                                  .batch(1, head_splits, 0, head_kper, 0, (int64_t)head_kper * d, 0, (int64_t)M * d).k_limit(head_k));

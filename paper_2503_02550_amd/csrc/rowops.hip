@@ -960,6 +960,7 @@ __global__ __launch_bounds__(256) void reduce_splits_batch_kernel(const RedItem*
   for (uint64_t v = (uint64_t)blockIdx.x * 256 + threadIdx.x; v < nv; v += (uint64_t)gridDim.x * 256) {
     float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (acc) unpack8(reinterpret_cast<const uint4*>(it.out)[v], a);
+#pragma unroll 4
     for (uint32_t s = 0; s < it.splits; ++s) {
       const float4* ps = reinterpret_cast<const float4*>(it.part + (size_t)s * it.n);
       const float4 x0 = ps[2 * v], x1 = ps[2 * v + 1];
@@ -1165,7 +1166,10 @@ sif_status launch_copy(void* dst, const void* src, uint64_t bytes, hipStream_t s
 
 sif_status launch_reduce_splits_batch(const RedItem* items_dev, uint32_t n_items, uint32_t acc, hipStream_t s, const KCtl& c) {
   REQ(items_dev && n_items > 0 && n_items <= 65535, "reduce_splits_batch: bad arguments");
-  hipLaunchKernelGGL(reduce_splits_batch_kernel, dim3(128, n_items), dim3(256), 0, s, items_dev, acc, c);
+  // about 2048 blocks in all (eight per CU), at least 128 per item: a launch with a single item (the LM head's data
+  // gradient) must still cover the chip
+  const uint32_t bx = std::max<uint32_t>(128u, (2048u + n_items - 1) / n_items);
+  hipLaunchKernelGGL(reduce_splits_batch_kernel, dim3(bx, n_items), dim3(256), 0, s, items_dev, acc, c);
   return check_launch("reduce_splits_batch");
 }
 

@@ -68,6 +68,8 @@ struct sif_ctx {
   // barrier thread state
   std::deque<InFlight> inflight;
   uint64_t head_since_ns = 0;       // host time at which the kernel at the head of `inflight` got there
+  const Job* rerun_job = nullptr;   // the launch that found the gate closed or was given back: its job and op
+  uint32_t rerun_op = 0;
   std::deque<Job*> run_online, run_offline;
   std::vector<std::unique_ptr<Job>> groups;      // coalesced jobs in flight (guarded by mu)
   std::vector<KbTokens> tokens;                  // per offline instance: what is left of the period's grant
@@ -360,6 +362,7 @@ static void barrier_main(sif_ctx* c) {
         c->inflight.pop_back();
         if (f.ev >= 0) c->done_ev_free.push_back(f.ev);
         if (f.op < f.job->next_op) f.job->next_op = f.op;
+        if (f.kseq == skip) { c->rerun_job = f.job; c->rerun_op = f.op; }
         c->hold = true;                   // the bubble this launch was aimed at has no room left
         c->hold_seq = f.idle_seq;
       }
@@ -550,7 +553,10 @@ static void barrier_main(sif_ctx* c) {
         const bool last_of_job = j->next_op + 1 == j->plan.size();
         if (last_of_job) k.flags |= 1u;
         if (beside) k.flags |= 2u;        // paid from the time account: starts whatever the training stream does
-        if (c->cfg.gate_spin_log2 && (c->cfg.gate_spin_every < 2 || k.kseq % c->cfg.gate_spin_every == 0))
+        // (with gate_spin_every the run of a launch that came back waits the default time, whatever its number)
+        const bool rerun = c->rerun_job == j && c->rerun_op == j->next_op;
+        if (rerun) c->rerun_job = nullptr;
+        if (c->cfg.gate_spin_log2 && (c->cfg.gate_spin_every < 2 || (k.kseq % c->cfg.gate_spin_every == 0 && !rerun)))
           k.flags |= (std::min<uint32_t>(c->cfg.gate_spin_log2, 30u) + 1u) << 8;
         sif_status st = launch_op(c, op, c->I.stream, k);
         int32_t ev = -1;

@@ -122,6 +122,41 @@ def test_decoder_training_step_matches_oracle_stage_by_stage(cfg):
         print("worst gradient error", worst)
 
 
+# 258 tile rows of 256 for the LM head's weight gradient: 256 of them are one whole round of one block per CU, the last
+# two (464 rows, the second one ragged) are cut along the 768 tokens into six slices of 128
+DEC_WTE_TAIL = dict(n_layers=1, d_model=64, n_heads=1, d_head=64, d_ffn=128, vocab=66000, max_pos=128, batch=6, seq=128, causal=True)
+
+
+def test_lm_head_weight_gradient_with_its_last_tile_rows_cut_along_k_matches_oracle():
+    cfg = DEC_WTE_TAIL
+    shape = decoder_shape(cfg)
+    master = Y.decoder_params(1, cfg, perturb=True)
+    ids, tg = Y.token_ids(2, cfg["batch"], cfg["seq"], cfg["vocab"]), Y.token_ids(3, cfg["batch"], cfg["seq"], cfg["vocab"])
+    tg[0, :8] = np.arange(65990, 65998)            # targets and inputs among the last rows as well
+    ids[1, :8] = np.arange(65700, 65708)
+    rl, rnew, rg, rc = OD.gpt_train_step(master, ids, tg, cfg, 0.01, "bf16")
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, master), par_mode=S.SIF_PAR_NONE, lr=0.01)
+        names, i = [], 0
+        while S.sif_train_op_name(s.ctx, 0, i) is not None:
+            names.append(S.sif_train_op_name(s.ctx, 0, i))
+            i += 1
+        assert "dwte_head_tail" in names and "dwte_head_sum" in names, "the plan did not cut the last tile rows"
+        loss, I, T = torch.zeros(1, device=DEV), i32(ids), i32(tg)
+        torch.cuda.synchronize()
+        s.step(I, T, loss)
+        s.sync()
+        assert abs(loss.item() - rl) <= 2e-2 * abs(rl)
+        got_g = P.unpack(shape, up(s.train_tensor("grads")))
+        for lo, hi in ((0, 65536), (65536, 65792), (65792, 66000)):      # the whole round, the two cut tile rows
+            e = rel_err(got_g["wte"][lo:hi], rg["wte"][lo:hi])
+            assert e <= 2e-2, (lo, hi, e)
+        for path, _ in P.layout(shape):
+            g_ref = rg[path] if isinstance(path, str) else rg["layers"][path[1]][path[2]]
+            g_got = got_g[path] if isinstance(path, str) else got_g["layers"][path[1]][path[2]]
+            assert rel_err(g_got, g_ref) <= 2e-2, path
+
+
 def test_decoder_stack_with_local_heads_matches_oracle():
     # tensor-shard shaped block: n_heads*d_head != d_model, no embedding, upstream gradient from the caller
     cfg = dict(n_layers=2, d_model=128, n_heads=2, d_head=32, d_ffn=192, vocab=0, max_pos=0, batch=2, seq=72, causal=True)
