@@ -530,8 +530,9 @@ sif_status sif_reset_stats(sif_ctx* ctx);
 
 /* Event timing of the bf16 GEMM launches, for roofline reporting.  While on (on = 1: every GEMM launch of both
  * streams; on = 2: only the variant with both operands K-contiguous, a_layout = b_layout = 0, so that a timed region
- * carries fewer event records) a launch is bracketed by two HIP events on its own stream (at most 16384 launches per
- * switch-on).  sif_profile_read (profiling switched off first; synchronises both streams)
+ * carries fewer event records; on = 3: every third launch of that variant on each stream - an event pair takes about
+ * 2 us of its stream's time, and the launches of a layer come in fours, so every shape is sampled alike) a launch is
+ * bracketed by two HIP events on its own stream (at most 16384 launches per switch-on).  sif_profile_read (profiling switched off first; synchronises both streams)
  * returns per layout variant v = a_layout*2 + b_layout the number of timed launches, their algorithmic
  * floating-point operations (2mnk per batch; the lower triangle only for causal products) and the sum of their
  * event-to-event times in seconds.  Inference launches that the device gate skipped are left out. */

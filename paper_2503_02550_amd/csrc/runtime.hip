@@ -103,6 +103,7 @@ struct sif_ctx {
   // optional event timing of the GEMM launches (sif_profile_gemm)
   std::atomic<uint32_t> prof_on{0};        // 0 off, 1 every GEMM launch, 2 only the variant with both operands K-contiguous
   std::vector<hipEvent_t> prof_ev;      // 2 per timed launch
+  uint32_t prof_third[2] = {0, 0};      // eligible launches seen per stream (training, inference) in mode 3
   std::vector<int32_t> prof_class;
   std::vector<double> prof_flops;
   std::vector<uint32_t> prof_kseq;      // launch number on the inference stream, 0 for a training launch
@@ -127,7 +128,10 @@ constexpr uint32_t kReleaseLog = 1u << 16;
 // Launches one op; when GEMM profiling is on, brackets it with two events on its own stream.
 static sif_status launch_op(sif_ctx* c, Op& op, hipStream_t s, const KCtl& k) {
   const uint32_t prof_mode = c->prof_on.load(std::memory_order_relaxed);
-  if (op.prof_class >= 0 && (prof_mode == 1 || (prof_mode == 2 && op.prof_class == 0))) {
+  bool timed = op.prof_class >= 0 && (prof_mode == 1 || (prof_mode >= 2 && op.prof_class == 0));
+  // mode 3: every third eligible launch of a stream (each stream is launched by one thread and counts for itself)
+  if (timed && prof_mode == 3) timed = (s == c->T.stream ? c->prof_third[0] : c->prof_third[1])++ % 3 == 0;
+  if (timed) {
     const uint32_t i = c->prof_n.fetch_add(1, std::memory_order_relaxed);
     if (i < kProfMax) {
       c->prof_class[i] = op.prof_class;
@@ -1116,8 +1120,8 @@ sif_status sif_profile_gemm(sif_ctx* c, uint32_t on) {
     c->prof_flops.assign(kProfMax, 0.0);
     c->prof_kseq.assign(kProfMax, 0);
   }
-  if (on) c->prof_n.store(0);
-  c->prof_on.store(on > 2 ? 1u : on);
+  if (on) { c->prof_n.store(0); c->prof_third[0] = c->prof_third[1] = 0; }
+  c->prof_on.store(on > 3 ? 1u : on);
   return SIF_OK;
 }
 
