@@ -254,6 +254,30 @@ def test_launch_given_back_by_blocks_that_stop_waiting_for_the_gate_is_run_again
         assert torch.equal(out, outs[i]), i
 
 
+def test_event_timing_of_gemm_launches_all_one_variant_or_every_third():
+    """sif_profile_gemm: mode 1 times every GEMM launch, mode 2 the variant with both operands K-contiguous, mode 3 every
+    third launch of that variant per stream; the flops of the timed launches follow, and the timing changes no result."""
+    shape = decoder_shape(DEC)
+    with Session() as s:
+        s.register_training(shape, P.pack(shape, Y.decoder_params(1, DEC)), par_mode=S.SIF_PAR_NONE, lr=0.01)
+        x, t = i32(Y.token_ids(3, DEC["batch"], DEC["seq"], DEC["vocab"])), i32(Y.token_ids(4, DEC["batch"], DEC["seq"], DEC["vocab"]))
+        torch.cuda.synchronize()
+        got = {}
+        for mode in (1, 2, 3):
+            S.sif_profile_gemm(s.ctx, mode)
+            for _ in range(3):
+                s.step(x, t)
+            s.sync()
+            S.sif_profile_gemm(s.ctx, 0)
+            got[mode] = S.sif_profile_read(s.ctx)
+        per_step = 4 * DEC["n_layers"] + 1                       # qkv, attention output, two MLP products per layer, LM head
+        assert got[2][0][0] == 3 * per_step and all(got[2][v][0] == 0 for v in (1, 2, 3))
+        assert got[1][0][0] == 3 * per_step and all(got[1][v][0] > 0 for v in (1, 3))
+        assert got[3][0][0] == (3 * per_step + 2) // 3 and all(got[3][v][0] == 0 for v in (1, 2, 3))
+        assert got[1][0][1] == got[2][0][1] and 0 < got[3][0][1] < got[2][0][1]
+        assert all(g[0][2] > 0 for g in got.values())
+
+
 def test_coalesced_offline_requests_give_the_same_bits_as_single_ones():
     """Queued requests of equal shape run as one kernel sequence over their concatenated rows; every request's
     output must be what a run by itself gives, and the scheduling invariants hold as before."""
