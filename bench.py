@@ -36,10 +36,10 @@ HBM_PEAK_TBPS = 8.0
 # Average bytes per dispatch of gemm_bf16_kernel<0,0> that pass between the L2s and the memory side in the headline
 # workload, from the FETCH_SIZE / WRITE_SIZE counter runs summarised in the file named beside it (counters cannot be
 # read from inside a timed run).
-GEMM00_HBM_BYTES_PER_LAUNCH = 384.2e6
+GEMM00_HBM_BYTES_PER_LAUNCH = 754.7e6
 GEMM00_HBM_BYTES_SOURCE = "constant from profiles/bench_cfg2_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command)"
 PROF_SAMPLED = 3     # sif_profile_gemm: event pairs around every third launch of the a_layout = b_layout = 0 variant per stream
-N_RING = 64          # distinct input / output buffers the queued requests cycle through (a coalesced group is 16)
+N_RING = 64          # distinct input / output buffers the queued requests cycle through (a coalesced group is 32)
 
 
 def oracle_cores():
@@ -179,12 +179,12 @@ def kernel_mode(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--configs", default="0,1,2,3,4", help="which configurations to run besides the headline configs[1] (comma-separated indices into BASELINE.json configs; 1 always runs)")
-    ap.add_argument("--coalesce", type=int, default=16, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
+    ap.add_argument("--coalesce", type=int, default=32, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time, the paper's rule; it is always reported beside this)")
-    ap.add_argument("--kernel-us-max", type=int, default=600, help="longest kernel the planner emits for the headline workload, us (its 4.98 ms bubble takes long kernels; configs[3] always uses 200)")
+    ap.add_argument("--kernel-us-max", type=int, default=1200, help="longest kernel the planner emits for the headline workload, us (its 4.98 ms bubble takes long kernels; configs[3] always uses 200)")
     ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 5)")
     ap.add_argument("--skip-concurrent", action="store_true", help="leave out the extra phases with concurrent filling and with binding tokens (profiles of the headline phase)")
     ap.add_argument("--timed-region-last", action="store_true", help="end the headline phase with its timed collocated steps (no further steps with all GEMM variants timed, no second solo phase): in a kernel trace of the process the last dispatches are then those of the timed region")

@@ -461,7 +461,7 @@ typedef struct sif_infer_desc {
   uint64_t workspace_bytes;
   uint64_t peak_bytes;           /* declared peak memory of this instance (Principle-I)                 */
   uint32_t coalesce;             /* encoder models: up to this many queued requests are released as ONE kernel
-                                    sequence over their concatenated rows (0 or 1 = each request by itself, at most 16).
+                                    sequence over their concatenated rows (0 or 1 = each request by itself, at most 32).
                                     Offline: requests of equal batch and seq.  Online: the requests that wait at the
                                     moment one is pulled, whatever their lengths (fewer if the predicted rest of the
                                     bubble does not hold them all); attention is told where each sequence begins.

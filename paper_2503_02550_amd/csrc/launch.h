@@ -50,7 +50,7 @@ struct AttnSeqs { uint32_t n; uint32_t start[kAttnMaxSeqs + 1]; };
 
 // Rows of several requests laid back to back: segment r is rows row0[r] .. row0[r+1] and has a buffer of its own
 // (the token ids an embedding reads, or the place a LayerNorm writes).  n = 0: no segments, one buffer for all rows.
-constexpr uint32_t kMaxRowSegs = 16;
+constexpr uint32_t kMaxRowSegs = 32;
 struct RowSegs {
   uint32_t n;
   uint32_t row0[kMaxRowSegs + 1];

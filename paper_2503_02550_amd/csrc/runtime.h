@@ -127,7 +127,7 @@ uint32_t infer_coalesce(const sif_infer_desc& d);
 uint32_t gemm_round_rows(const sif_gemm_args& a);
 // Cuts `op` (row_split) into its first `rows_first` rows (a multiple of 128, 0 < rows_first < m) and the rest
 void split_gemm_rows(const Op& op, uint32_t rows_first, Op& first, Op& rest);
-constexpr uint32_t kMaxCoalesce = 16;     // most requests one coalesced kernel sequence serves
+constexpr uint32_t kMaxCoalesce = 32;     // most requests one coalesced kernel sequence serves
 
 // markers.hip
 sif_status launch_bubble(hipStream_t s, StreamRec* rec, Mirror* mir, Slot* slot, uint32_t seq, uint32_t site, uint64_t ticks,
