@@ -223,6 +223,17 @@ typedef struct sif_gemm_args {
 /* bf16 matrix product on the MFMA units, fp32 accumulation. */
 sif_status sif_k_gemm_bf16(const sif_gemm_args* a, void* stream);
 
+/* Several bf16 products as ONE launch of 128 x 128 tiles (Sec. 2.1: the weight gradients of a transformer layer, each
+ * with too few output tiles for the chip by itself).  list[0..n): n <= 16 products, all with A stored [K][M] and B
+ * stored [K][N] (a_layout = SIF_A_ROW_M, b_layout = SIF_B_ROW_N), no batches; `tile` is ignored.  records_dev: device
+ * memory of at least sif_k_gemm_bf16_group_bytes(n) bytes, 16-byte aligned, owned by the caller; the call copies the
+ * products' records there (a synchronous host -> device copy) and launches on `stream`; the memory must stay
+ * untouched until the launch has finished.  Every product's result has the bits of sif_k_gemm_bf16 with tile = 128.
+ * Errors: SIF_E_INVAL for a null or misaligned pointer, n outside 1..16, other layouts, a batched product or anything
+ * sif_k_gemm_bf16 refuses; nothing is launched then. */
+uint64_t sif_k_gemm_bf16_group_bytes(uint32_t n);
+sif_status sif_k_gemm_bf16_group(const sif_gemm_args* list, uint32_t n, void* records_dev, void* stream);
+
 /* fp32 matrix product C[M,N] = sum_k A(m,k) B(k,n) with arbitrary element strides (Tiny configuration):
  * A(m,k) = a[m*a_sm + k*a_sk], B(k,n) = b[k*b_sk + n*b_sn], C row-major ldc.  epilogue: SIF_EPI_BIAS,
  * SIF_EPI_GELU (aux = pre-activation, fp32), SIF_EPI_GELU_GRAD (aux fp32) as above, all fp32. */

@@ -272,9 +272,10 @@ def sif_dp_overlapped_wait(ready_ns, dur_ns, end_ns):
 
 
 # ---- single kernels -------------------------------------------------------------------------------------
-def sif_k_gemm_bf16(a, b, c, m, n, k, lda, ldb, ldc, a_layout=SIF_A_ROW_K, b_layout=SIF_B_ROW_K, epilogue=0,
-                    bias=None, res=None, aux=None, alpha=1.0, batch_outer=1, batch_inner=1,
-                    a_strides=(0, 0), b_strides=(0, 0), c_strides=(0, 0), k_causal=0, tile=0, k_limit=0, stream=None):
+def gemm_args(a, b, c, m, n, k, lda, ldb, ldc, a_layout=SIF_A_ROW_K, b_layout=SIF_B_ROW_K, epilogue=0,
+              bias=None, res=None, aux=None, alpha=1.0, batch_outer=1, batch_inner=1,
+              a_strides=(0, 0), b_strides=(0, 0), c_strides=(0, 0), k_causal=0, tile=0, k_limit=0):
+    """A filled sif_gemm_args (argument marshalling only)."""
     g = sif_gemm_args()
     g.struct_size = C.sizeof(sif_gemm_args)
     g.a_layout, g.b_layout, g.epilogue = a_layout, b_layout, epilogue
@@ -285,7 +286,26 @@ def sif_k_gemm_bf16(a, b, c, m, n, k, lda, ldb, ldc, a_layout=SIF_A_ROW_K, b_lay
     g.c_stride_outer, g.c_stride_inner = c_strides
     g.alpha, g.k_causal, g.tile, g.k_limit = alpha, k_causal, tile, k_limit
     g.a_dev, g.b_dev, g.c_dev, g.bias_dev, g.res_dev, g.aux_dev = ptr(a), ptr(b), ptr(c), ptr(bias), ptr(res), ptr(aux)
+    return g
+
+
+def sif_k_gemm_bf16(*args, stream=None, **kw):
+    g = gemm_args(*args, **kw)
     return check(lib.sif_k_gemm_bf16(C.byref(g), stream_ptr(stream)))
+
+
+_sig("sif_k_gemm_bf16_group_bytes", u64, u32)
+_sig("sif_k_gemm_bf16_group", i32, P(sif_gemm_args), u32, vp, vp)
+
+
+def sif_k_gemm_bf16_group_bytes(n):
+    return lib.sif_k_gemm_bf16_group_bytes(n)
+
+
+def sif_k_gemm_bf16_group(products, records, stream=None):
+    """products: sif_gemm_args from gemm_args(); records: device memory of sif_k_gemm_bf16_group_bytes(len(products)) bytes."""
+    arr = (sif_gemm_args * max(1, len(products)))(*products)
+    return check(lib.sif_k_gemm_bf16_group(arr, len(products), ptr(records), stream_ptr(stream)))
 
 
 def sif_k_gemm_f32(a, a_sm, a_sk, b, b_sk, b_sn, c, ldc, m, n, k, epilogue=0, bias=None, aux=None, stream=None):

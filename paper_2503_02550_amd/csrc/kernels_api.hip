@@ -1,4 +1,6 @@
 // C ABI of the single-kernel launchers (unmonitored launches: no activity record, no gate).
+#include <vector>
+
 #include "launch.h"
 
 using namespace sif;
@@ -7,6 +9,19 @@ static inline hipStream_t S(void* s) { return reinterpret_cast<hipStream_t>(s); 
 extern "C" {
 
 sif_status sif_k_gemm_bf16(const sif_gemm_args* a, void* stream) { return launch_gemm_bf16(a, S(stream), no_ctl()); }
+
+uint64_t sif_k_gemm_bf16_group_bytes(uint32_t n) { return gemm_group_bytes(n); }
+
+sif_status sif_k_gemm_bf16_group(const sif_gemm_args* list, uint32_t n, void* records_dev, void* stream) {
+  if (list == nullptr || n == 0 || n > 16 || records_dev == nullptr || (reinterpret_cast<uintptr_t>(records_dev) & 15))
+    return fail(SIF_E_INVAL, "gemm group: null or misaligned argument, or n outside 1..16");
+  std::vector<unsigned char> host(gemm_group_bytes(n));
+  uint32_t grid = 0;
+  if (sif_status st = gemm_group_fill(list, n, host.data(), &grid)) return st;
+  const hipError_t e = hipMemcpy(records_dev, host.data(), host.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail_hip(e, "gemm group: copy of the records");
+  return launch_gemm_bf16_group(records_dev, n, grid, list[0].a_layout, list[0].b_layout, S(stream), no_ctl());
+}
 
 sif_status sif_k_gemm_f32(const float* a_dev, int64_t a_sm, int64_t a_sk, const float* b_dev, int64_t b_sk, int64_t b_sn,
                           float* c_dev, int64_t ldc, uint32_t m, uint32_t n, uint32_t k, uint32_t epilogue,

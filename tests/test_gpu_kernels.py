@@ -114,6 +114,44 @@ def test_gemm_bf16_large_tiles_give_the_same_bits(al, bl, m, n, k):
         S.sif_k_gemm_bf16(A, B, c256, m, n, k - 8, A.shape[1], B.shape[1], n, a_layout=al, b_layout=bl, tile=256)
 
 
+@pytest.mark.parametrize("k", [520, 1024])
+def test_gemm_bf16_several_products_in_one_launch_give_the_bits_of_launches_of_their_own(k):
+    """Weight-gradient-shaped products (A stored [K][M], B stored [K][N]) as one launch: a large one, a ragged one, one
+    that adds to what its output holds, and a one-row product whose left operand is a column of ones (a bias gradient:
+    the column sums of B); K ragged (the register path) and whole K steps (the direct fetches)."""
+    shapes = [(256, 384, False), (72, 136, False), (200, 128, True), (1, 208, False)]
+    prods, singles, outs, refs = [], [], [], []
+    for i, (m, n, acc) in enumerate(shapes):
+        mp = (m + 7) // 8 * 8
+        a = np.zeros((k, mp), dtype=np.float32)
+        a[:, :m] = 1.0 if m == 1 else rnd(60 + i, k, m)
+        b = rnd(70 + i, k, n)
+        A, B = bf(a), bf(b)
+        c0 = bf(rnd(80 + i, m, n)) if acc else torch.zeros((m, n), device=DEV, dtype=torch.bfloat16)
+        c1 = c0.clone()
+        kw = dict(a_layout=S.SIF_A_ROW_M, b_layout=S.SIF_B_ROW_N, epilogue=S.SIF_EPI_RESIDUAL if acc else 0)
+        prods.append(S.gemm_args(A, B, c0, m, n, k, mp, n, n, res=c0 if acc else None, **kw))
+        singles.append((A, B, c1, m, n, k, mp, n, n, dict(res=c1 if acc else None, tile=128, **kw)))
+        outs.append((c0, c1))
+        refs.append(q(a[:, :m]).T @ q(b) + (q(rnd(80 + i, m, n)) if acc else 0.0))
+    records = torch.zeros(S.sif_k_gemm_bf16_group_bytes(len(prods)) + 16, device=DEV, dtype=torch.uint8)
+    torch.cuda.synchronize()
+    S.sif_k_gemm_bf16_group(prods, records)
+    for A, B, c1, m, n, kk, lda, ldb, ldc, kw in singles:
+        S.sif_k_gemm_bf16(A, B, c1, m, n, kk, lda, ldb, ldc, **kw)
+    torch.cuda.synchronize()
+    for i, (c0, c1) in enumerate(outs):
+        assert torch.equal(c0, c1), shapes[i]
+        assert_bf16_close(up(c0), refs[i], f"grouped product {shapes[i]}", elem_slack=1e-2)
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16_group([], records)
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16_group(prods * 5, records)
+    other = S.gemm_args(prods[0].a_dev, prods[0].b_dev, prods[0].c_dev, 8, 8, 64, 64, 64, 8)      # both operands K-contiguous
+    with pytest.raises(S.SifError):
+        S.sif_k_gemm_bf16_group([other], records)
+
+
 @pytest.mark.parametrize("bl", [0, 1])
 def test_gemm_bf16_slices_of_one_long_k(bl):
     """batch_inner cuts K into slices whose results go to separate fp32 outputs; with k_limit the last slice is
