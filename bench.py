@@ -183,6 +183,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--configs", default="0,1,2,3,4", help="which configurations to run besides the headline configs[1] (comma-separated indices into BASELINE.json configs; 1 always runs)")
     ap.add_argument("--coalesce", type=int, default=32, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
+    ap.add_argument("--pp-coalesce", type=int, default=8, help="configs[2]: queued requests released as one kernel sequence")
+    ap.add_argument("--pp-kernel-us-max", type=int, default=1200, help="configs[2]: longest kernel the planner emits, us")
+    ap.add_argument("--tp-coalesce", type=int, default=16, help="configs[3]: queued requests released as one kernel sequence")
+    ap.add_argument("--tp-kernel-us-max", type=int, default=200, help="configs[3]: longest kernel the planner emits, us")
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time, the paper's rule; it is always reported beside this)")
     ap.add_argument("--kernel-us-max", type=int, default=1200, help="longest kernel the planner emits for the headline workload, us (its 4.98 ms bubble takes long kernels; configs[3] always uses 200)")
     ap.add_argument("--period-us", type=int, default=0, help="monitor period P, us (0 = the library's default, 5)")
@@ -520,12 +524,12 @@ def main():
     if 2 in legs and not args.small:
         per_config["configs[2]"] = stack_leg(
             "configs[2] pipeline stage: 1F1B, stage 1 of 4, 8 micro-batches, 6 decoder layers d2048 h16x128 seq2048 mb2; idle intervals of the "
-            "schedule sized from the measured pass times; fill: 6-layer d512 encoder seq256 batch64", Y.PP_DECODER, Y.PP_FILL_ENCODER, 2, 300, 12, "pp")
+            "schedule sized from the measured pass times; fill: 6-layer d512 encoder seq256 batch64", Y.PP_DECODER, Y.PP_FILL_ENCODER, args.pp_coalesce, args.pp_kernel_us_max, 12, "pp")
     if 3 in legs and not args.small:
         per_config["configs[3]"] = stack_leg(
             "configs[3] tensor shard: 24 decoder layers, d4096 split 1/8 (4 local heads of 128, d_ffn 2048), batch 4 x seq2048; 96 bubbles of 1.34 ms "
             "per step (2 activation all-reduces per layer and pass at 50 GB/s); fill: 12-layer d768 encoder seq128 batch32 in kernels <= 200 us",
-            Y.TP_DECODER, Y.FILL_ENCODER, 4, 200, 8, "tp")
+            Y.TP_DECODER, Y.FILL_ENCODER, args.tp_coalesce, args.tp_kernel_us_max, 8, "tp")
 
     # ================= configs[4] online: same training step, Poisson requests, batch 1 ==============================
     # At the configured 200 req/s, with the requests that wait together run as one kernel sequence (this build's
