@@ -185,7 +185,7 @@ def main():
     ap.add_argument("--coalesce", type=int, default=32, help="queued offline requests of equal shape released as one kernel sequence (1 = off)")
     ap.add_argument("--pp-coalesce", type=int, default=8, help="configs[2]: queued requests released as one kernel sequence")
     ap.add_argument("--pp-kernel-us-max", type=int, default=1200, help="configs[2]: longest kernel the planner emits, us")
-    ap.add_argument("--tp-coalesce", type=int, default=16, help="configs[3]: queued requests released as one kernel sequence")
+    ap.add_argument("--tp-coalesce", type=int, default=21, help="configs[3]: queued requests released as one kernel sequence")
     ap.add_argument("--tp-kernel-us-max", type=int, default=200, help="configs[3]: longest kernel the planner emits, us")
     ap.add_argument("--online-coalesce", type=int, default=8, help="online requests waiting together run as one kernel sequence (1 = one at a time, the paper's rule; it is always reported beside this)")
     ap.add_argument("--kernel-us-max", type=int, default=1200, help="longest kernel the planner emits for the headline workload, us (its 4.98 ms bubble takes long kernels; configs[3] always uses 200)")

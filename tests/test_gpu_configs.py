@@ -25,7 +25,7 @@ if torch.cuda.is_available():
     import paper_2503_02550_amd as S
     from paper_2503_02550_amd import params as P
     from paper_2503_02550_amd.session import Session, decoder_shape, encoder_shape
-    from gpu_util import DEV, bf, i32, up, q, rel_err, assert_bf16_close
+    from gpu_util import assert_deep_bf16_close, DEV, bf, i32, up, q, rel_err, assert_bf16_close
 
 
 @pytest.mark.parametrize("which", ["pipeline-stage-layer", "tensor-shard-layer"])
@@ -136,7 +136,10 @@ def _run_config(dec, enc, n_batches, steps, coalesce, kernel_us_max, register):
             assert torch.equal(out.cpu(), res["outs"][i]), i
         for i, b in ((0, 1), (n_batches - 1, enc["batch"] - 1)):
             ref = OE.encoder_forward(w, eids[i][b:b + 1], enc, "bf16")
-            assert_bf16_close(res["outs"][i][b:b + 1].float().numpy(), ref, f"fill batch {i} sample {b}", elem_slack=2e-2)
+            if enc["n_layers"] >= 12:
+                assert_deep_bf16_close(res["outs"][i][b:b + 1].float().numpy(), ref, OE.encoder_forward(w, eids[i][b:b + 1], enc, "f32"), f"fill batch {i} sample {b}")
+            else:
+                assert_bf16_close(res["outs"][i][b:b + 1].float().numpy(), ref, f"fill batch {i} sample {b}", elem_slack=2e-2)
     return res
 
 
@@ -170,11 +173,11 @@ def test_tensor_shard_configuration_at_full_size_keeps_kernels_within_200_us():
 
     def register(s, dshape, dmaster):
         s.register_training(dshape, dmaster, par_mode=S.SIF_PAR_TP, lr=dec["lr"], bw_bytes_per_s=dec["bw_bytes_per_s"])
-    res = _run_config(dec, enc, n_batches=16, steps=1, coalesce=16, kernel_us_max=limit_us, register=register)      # as bench.py runs it
+    res = _run_config(dec, enc, n_batches=21, steps=1, coalesce=21, kernel_us_max=limit_us, register=register)      # as bench.py runs it
     assert torch.equal(res[0]["master"], res[1]["master"])
     assert bool(torch.isfinite(res[0]["master"].view(torch.float32)).all())
     fin = res["final_stats"]
-    assert fin.offline_batches == 16
+    assert fin.offline_batches == 21
     _assert_inside(res["bubbles"], res["ran"])
     assert fin.gate_violations == 0 and fin.gate_unchecked == 0 and fin.gate_checked == len(res["ran"])
     want_ns = S.sif_collective_ns(dec["batch"] * dec["seq"] * dec["d_model"] * 2, dec["bw_bytes_per_s"])
